@@ -1,0 +1,100 @@
+"""Seeded synthetic inputs for one GSWA layer.
+
+Holds none of the layer's arithmetic: only random draws, shapes and the
+host-side rounding of inputs to the storage type.  Both the HIP path and the
+CPU oracle are fed from here so that they see identical values.
+
+Shapes follow SwinIR-style image-restoration settings: C in {60, 180}, 6 heads,
+8x8 windows, 64x64 training patches.  Two value regimes:
+
+* ``init``   x, dy ~ N(0,1); weights and bias table ~ N(0, 0.02^2); linear biases 0
+             (the initialisation the Swin family trains from);
+* ``stress`` weights ~ N(0, 1/fan_in), bias table ~ N(0,1), linear biases ~ N(0, 0.1^2):
+             scores of order 1-5 and peaked softmax rows, so that mask, bias and
+             exponent mistakes are visible (the ``init`` regime gives almost uniform rows).
+"""
+import numpy as np
+
+
+def param_shapes(C, heads, groups, window):
+    Cg = C // groups
+    return {
+        "w_qkv": (groups, 3 * Cg, Cg),
+        "b_qkv": (groups, 3 * Cg),
+        "w_proj": (C, C),
+        "b_proj": (C,),
+        "table": ((2 * window - 1) ** 2, heads),
+    }
+
+
+def layer_params(C, heads, groups, window, seed, regime="init"):
+    """fp32 parameters of one layer, drawn in the order w_qkv, w_proj, table, b_qkv, b_proj."""
+    rng = np.random.default_rng(seed)
+    shp = param_shapes(C, heads, groups, window)
+    Cg = C // groups
+    if regime == "init":
+        p = {
+            "w_qkv": rng.normal(0.0, 0.02, shp["w_qkv"]),
+            "w_proj": rng.normal(0.0, 0.02, shp["w_proj"]),
+            "table": rng.normal(0.0, 0.02, shp["table"]),
+            "b_qkv": np.zeros(shp["b_qkv"]),
+            "b_proj": np.zeros(shp["b_proj"]),
+        }
+    elif regime == "stress":
+        p = {
+            "w_qkv": rng.normal(0.0, Cg ** -0.5, shp["w_qkv"]),
+            "w_proj": rng.normal(0.0, C ** -0.5, shp["w_proj"]),
+            "table": rng.normal(0.0, 1.0, shp["table"]),
+            "b_qkv": rng.normal(0.0, 0.1, shp["b_qkv"]),
+            "b_proj": rng.normal(0.0, 0.1, shp["b_proj"]),
+        }
+    else:
+        raise ValueError(f"unknown regime {regime!r}")
+    return {k: v.astype(np.float32) for k, v in p.items()}
+
+
+def activations(B, H, W, C, seed):
+    """(x, dy) ~ N(0,1), fp32, drawn in that order."""
+    rng = np.random.default_rng(seed)
+    x = rng.normal(0.0, 1.0, (B, H, W, C)).astype(np.float32)
+    dy = rng.normal(0.0, 1.0, (B, H, W, C)).astype(np.float32)
+    return x, dy
+
+
+def to_bf16_bits(a):
+    """Round fp32 values to bfloat16 (nearest, ties to even); returns the uint16 patterns."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def from_bf16_bits(bits):
+    """Widen bfloat16 bit patterns to fp32 exactly."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def quantize(a, dtype):
+    """Value the storage type ``dtype`` ('f32' or 'bf16') holds for ``a``, as fp32."""
+    if dtype == "f32":
+        return np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        return from_bf16_bits(to_bf16_bits(a)).reshape(np.shape(a))
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+# The benchmark shapes.  "layers" lists the shift of each layer of the case.
+CONFIGS = {
+    "c1": dict(B=1, H=16, W=16, C=60, heads=6, groups=(2,), window=8, layers=(4,), dtype="f32"),
+    "c2": dict(B=32, H=64, W=64, C=60, heads=6, groups=(1, 2, 3, 6), window=8, layers=(0, 4),
+               dtype="bf16"),
+    "c3": dict(B=16, H=64, W=64, C=180, heads=6, groups=(1, 2, 3), window=8, layers=(0, 4),
+               dtype="bf16"),
+    "c4": dict(B=32, H=64, W=64, C=180, heads=6, groups=(2,), window=8,
+               layers=tuple(4 * (i % 2) for i in range(36)), dtype="bf16"),
+    "c5_m8": dict(B=1, H=512, W=512, C=180, heads=6, groups=(2,), window=8, layers=(4,),
+                  dtype="bf16"),
+    "c5_m16": dict(B=1, H=512, W=512, C=180, heads=6, groups=(2,), window=16, layers=(8,),
+                   dtype="bf16"),
+}
+ACT_SEED = 0
+LAYER_SEED0 = 100

@@ -1,0 +1,298 @@
+"""Pins for the CPU oracle: checks against statements of the layer that do not use it.
+
+Each test names the property it fixes.  None of these needs a GPU.
+"""
+import numpy as np
+import pytest
+
+from paper_2409_06206_amd import synth
+from tests import refs
+
+
+def make(B, H, W, C, heads, groups, M, seed=1, regime="stress"):
+    p = refs.as_f64(synth.layer_params(C, heads, groups, M, seed, regime))
+    x, dy = synth.activations(B, H, W, C, seed + 1000)
+    return x.astype(np.float64), dy.astype(np.float64), p
+
+
+def run_fwd(oracle, x, p, **kw):
+    return oracle.forward(x, p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"], **kw)
+
+
+def run_bwd(oracle, x, dy, p, **kw):
+    return oracle.backward(x, dy, p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"], **kw)
+
+
+CASES = [
+    # B, H, W, C, heads, groups, M, s
+    (2, 8, 8, 12, 6, 1, 4, 0),
+    (2, 8, 8, 12, 6, 1, 4, 2),
+    (1, 8, 16, 12, 6, 2, 4, 2),
+    (1, 16, 8, 12, 6, 3, 4, 1),
+    (1, 12, 8, 12, 6, 6, 4, 3),
+    (1, 16, 16, 12, 6, 2, 8, 4),
+    (1, 8, 8, 6, 3, 3, 8, 5),     # a single window per image: all four wrap regions in one window
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,M,s", CASES)
+def test_matches_bruteforce_global_attention(oracle, B, H, W, C, heads, groups, M, s):
+    """Windows, shift, mask, bias, groups and cascade against masked global attention."""
+    x, _, p = make(B, H, W, C, heads, groups, M)
+    for cascade in (True, False):
+        y, ex = run_fwd(oracle, x, p, heads=heads, groups=groups, window=M, shift=s,
+                        cascade=cascade, want_attn=True)
+        y_ref, a_ref = refs.grouped_by_composition(x, p, heads, groups, M, s, cascade,
+                                                   core=refs.global_attention)
+        np.testing.assert_allclose(ex["attn"], a_ref, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,M,s", CASES)
+def test_matches_textbook_window_attention(oracle, B, H, W, C, heads, groups, M, s):
+    """G=1 is shifted-window MSA done with roll/partition copies; G>1 is a chain of those."""
+    x, _, p = make(B, H, W, C, heads, groups, M, seed=3)
+    y = run_fwd(oracle, x, p, heads=heads, groups=groups, window=M, shift=s)
+    y_ref, _ = refs.grouped_by_composition(x, p, heads, groups, M, s, True,
+                                           core=refs.dense_window_msa)
+    np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-12)
+
+
+def test_pins_can_tell_shift_direction_and_cascade(oracle):
+    """The shapes above distinguish the plausible mistakes (guards against vacuous pins)."""
+    B, H, W, C, heads, groups, M, s = 1, 8, 16, 12, 6, 2, 4, 1
+    x, _, p = make(B, H, W, C, heads, groups, M)
+    y = run_fwd(oracle, x, p, heads=heads, groups=groups, window=M, shift=s)
+    other_dir, _ = refs.grouped_by_composition(x, p, heads, groups, M, M - s)
+    no_casc, _ = refs.grouped_by_composition(x, p, heads, groups, M, s, cascade=False)
+    assert np.abs(y - other_dir).max() > 1e-3
+    assert np.abs(y - no_casc).max() > 1e-3
+    # a transposed output projection is visible too (w_qkv blocks are not square, so
+    # transposing them cannot even be expressed)
+    pt = dict(p, w_proj=p["w_proj"].T.copy())
+    yt = run_fwd(oracle, x, pt, heads=heads, groups=groups, window=M, shift=s)
+    assert np.abs(y - yt).max() > 1e-3
+
+
+def test_split_without_cascade_is_block_diagonal_dense_layer(oracle):
+    """Independent groups == one G=1 layer whose QKV weight is block diagonal."""
+    B, H, W, C, heads, G, M, s = 1, 8, 8, 12, 6, 3, 4, 2
+    Cg, hg, d = C // G, heads // G, C // heads
+    x, _, p = make(B, H, W, C, heads, G, M, seed=5)
+    y = run_fwd(oracle, x, p, heads=heads, groups=G, window=M, shift=s, cascade=False)
+    wd = np.zeros((1, 3 * C, C))
+    bd = np.zeros((1, 3 * C))
+    for g in range(G):
+        for t in range(3):
+            rows = slice(t * C + g * Cg, t * C + (g + 1) * Cg)
+            wd[0, rows, g * Cg:(g + 1) * Cg] = p["w_qkv"][g, t * Cg:(t + 1) * Cg]
+            bd[0, rows] = p["b_qkv"][g, t * Cg:(t + 1) * Cg]
+    pd = dict(p, w_qkv=wd, b_qkv=bd)
+    yd = run_fwd(oracle, x, pd, heads=heads, groups=1, window=M, shift=s)
+    np.testing.assert_allclose(y, yd, rtol=0, atol=1e-12)
+    assert hg * d == Cg
+
+
+def test_cascade_flag_is_noop_for_one_group(oracle):
+    x, _, p = make(1, 8, 8, 12, 6, 1, 4)
+    a = run_fwd(oracle, x, p, heads=6, groups=1, window=4, shift=2, cascade=True)
+    b = run_fwd(oracle, x, p, heads=6, groups=1, window=4, shift=2, cascade=False)
+    assert np.array_equal(a, b)
+
+
+def test_zero_query_key_gives_region_means(oracle):
+    """Wq = Wk = 0 and a zero table: every row of P is uniform over its mask region."""
+    B, H, W, C, heads, G, M, s = 1, 8, 8, 12, 6, 1, 4, 2
+    x, _, p = make(B, H, W, C, heads, G, M)
+    p["w_qkv"][:, :2 * C] = 0
+    p["b_qkv"][:, :2 * C] = 0
+    p["table"][:] = 0
+    _, ex = run_fwd(oracle, x, p, heads=heads, groups=G, window=M, shift=s, want_attn=True)
+    v = x @ p["w_qkv"][0, 2 * C:].T + p["b_qkv"][0, 2 * C:]
+    # region of a token = (window in rolled frame, wrap flags); mean of v over it
+    pi, pj = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    key = ((((pi - s) % H) // M) * 100 + ((pj - s) % W) // M) * 4 + 2 * (pi < s) + (pj < s)
+    expect = np.empty_like(v)
+    for kk in np.unique(key):
+        sel = key == kk
+        expect[0][sel] = v[0][sel].mean(axis=0)
+    # -100 is not -inf: other regions of the window keep weight exp(-100) ~ 4e-44
+    np.testing.assert_allclose(ex["attn"], expect, rtol=0, atol=1e-12)
+    # at s = 0 the region is the whole window
+    _, ex0 = run_fwd(oracle, x, p, heads=heads, groups=G, window=M, shift=0, want_attn=True)
+    vw = v.reshape(B, H // M, M, W // M, M, C).mean(axis=(2, 4), keepdims=True)
+    np.testing.assert_allclose(ex0["attn"].reshape(B, H // M, M, W // M, M, C),
+                               np.broadcast_to(vw, (B, H // M, M, W // M, M, C)), atol=1e-12)
+
+
+def test_table_only_probabilities(oracle):
+    """q = k = 0: P[n, m] = softmax_m table[idx(n, m)], whatever x is; rows sum to one."""
+    B, H, W, C, heads, G, M = 1, 8, 8, 12, 6, 2, 4
+    x, _, p = make(B, H, W, C, heads, G, M)
+    Cg = C // G
+    p["w_qkv"][:, :2 * Cg] = 0
+    p["b_qkv"][:, :2 * Cg] = 0
+    _, ex = run_fwd(oracle, x, p, heads=heads, groups=G, window=M, shift=0, want_probs=True)
+    P = ex["probs"]
+    np.testing.assert_allclose(P.sum(-1), 1.0, atol=1e-13)
+    for hd in range(heads):
+        for n in (0, 5, 15):
+            rn, cn = divmod(n, M)
+            row = np.array([p["table"][(rn - m // M + M - 1) * (2 * M - 1) + (cn - m % M + M - 1), hd]
+                            for m in range(M * M)])
+            e = np.exp(row - row.max())
+            np.testing.assert_allclose(P[:, hd, n], np.broadcast_to(e / e.sum(), P[:, hd, n].shape),
+                                       atol=1e-13)
+
+
+def test_probability_rows_sum_to_one_with_mask(oracle):
+    x, _, p = make(1, 8, 8, 12, 6, 3, 4)
+    _, ex = run_fwd(oracle, x, p, heads=6, groups=3, window=4, shift=2, want_probs=True)
+    np.testing.assert_allclose(ex["probs"].sum(-1), 1.0, atol=1e-13)
+    assert ex["probs"].min() >= 0
+
+
+def test_window_grid_translation_equivariance(oracle):
+    """At s = 0, moving x by whole windows moves y the same way; batch permutation commutes."""
+    B, H, W, C, heads, G, M = 2, 8, 16, 12, 6, 2, 4
+    x, _, p = make(B, H, W, C, heads, G, M)
+    kw = dict(heads=heads, groups=G, window=M, shift=0)
+    y = run_fwd(oracle, x, p, **kw)
+    xr = np.roll(x, (M, 2 * M), axis=(1, 2))
+    np.testing.assert_allclose(run_fwd(oracle, xr, p, **kw), np.roll(y, (M, 2 * M), axis=(1, 2)),
+                               atol=1e-13)
+    np.testing.assert_allclose(run_fwd(oracle, x[::-1], p, **kw), y[::-1], atol=0)
+    # with a shift the wrap mask sits at fixed image borders, which breaks this symmetry
+    kw["shift"] = 1
+    ys = run_fwd(oracle, x, p, **kw)
+    assert np.abs(run_fwd(oracle, xr, p, **kw) - np.roll(ys, (M, 2 * M), axis=(1, 2))).max() > 1e-6
+
+
+def test_linear_in_output_projection(oracle):
+    x, _, p = make(1, 8, 8, 12, 6, 2, 4)
+    kw = dict(heads=6, groups=2, window=4, shift=2)
+    y1 = run_fwd(oracle, x, p, **kw)
+    p2 = dict(p, w_proj=2.5 * p["w_proj"], b_proj=2.5 * p["b_proj"])
+    np.testing.assert_allclose(run_fwd(oracle, x, p2, **kw), 2.5 * y1, rtol=1e-13, atol=1e-13)
+
+
+GRAD_CASES = [
+    (1, 8, 8, 12, 6, 1, 4, 2, True),
+    (2, 8, 8, 12, 6, 2, 4, 1, True),
+    (1, 8, 16, 12, 6, 3, 4, 2, True),
+    (1, 8, 8, 12, 6, 6, 4, 0, True),
+    (1, 8, 8, 12, 6, 3, 4, 2, False),
+    (1, 16, 16, 12, 6, 2, 8, 4, True),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,M,s,cascade", GRAD_CASES)
+def test_gradients_against_central_differences(oracle, B, H, W, C, heads, groups, M, s, cascade):
+    """Every gradient, as directional derivatives of L = sum(dy * y) along random directions."""
+    x, dy, p = make(B, H, W, C, heads, groups, M, seed=7)
+    kw = dict(heads=heads, groups=groups, window=M, shift=s, cascade=cascade)
+    grads = run_bwd(oracle, x, dy, p, **kw)
+    names = ("x", "w_qkv", "b_qkv", "w_proj", "b_proj", "table")
+    rng = np.random.default_rng(11)
+
+    def loss(xv, pv):
+        return float((run_fwd(oracle, xv, pv, **kw) * dy).sum())
+
+    for name, g in zip(names, grads):
+        for _ in range(2):
+            direction = rng.normal(size=g.shape)
+            eps = 1e-5
+            if name == "x":
+                lp, lm = loss(x + eps * direction, p), loss(x - eps * direction, p)
+            else:
+                lp = loss(x, dict(p, **{name: p[name] + eps * direction}))
+                lm = loss(x, dict(p, **{name: p[name] - eps * direction}))
+            fd = (lp - lm) / (2 * eps)
+            an = float((g * direction).sum())
+            assert abs(fd - an) <= 2e-7 * max(1.0, abs(an), np.linalg.norm(g)), (name, fd, an)
+
+
+def test_gradient_single_entries(oracle):
+    """Entry-wise finite differences on a few coordinates (catches index permutations that
+    leave directional sums almost unchanged)."""
+    B, H, W, C, heads, G, M, s = 1, 8, 8, 6, 3, 3, 4, 2
+    x, dy, p = make(B, H, W, C, heads, G, M, seed=9)
+    kw = dict(heads=heads, groups=G, window=M, shift=s)
+    grads = dict(zip(("x", "w_qkv", "b_qkv", "w_proj", "b_proj", "table"), run_bwd(oracle, x, dy, p, **kw)))
+    rng = np.random.default_rng(5)
+    eps = 1e-5
+    for name in grads:
+        base = x if name == "x" else p[name]
+        for _ in range(6):
+            idx = tuple(rng.integers(0, n) for n in base.shape)
+            bump = np.zeros_like(base)
+            bump[idx] = eps
+            if name == "x":
+                lp = (run_fwd(oracle, x + bump, p, **kw) * dy).sum()
+                lm = (run_fwd(oracle, x - bump, p, **kw) * dy).sum()
+            else:
+                lp = (run_fwd(oracle, x, dict(p, **{name: base + bump}), **kw) * dy).sum()
+                lm = (run_fwd(oracle, x, dict(p, **{name: base - bump}), **kw) * dy).sum()
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - grads[name][idx]) <= 1e-7 * max(1.0, abs(fd)), (name, idx)
+
+
+def test_bias_table_gradient_sums_to_zero_per_head(oracle):
+    """Each softmax row has sum_m dS = 0, so the table gradient of every head sums to zero."""
+    x, dy, p = make(2, 8, 8, 12, 6, 2, 4, seed=13)
+    g = run_bwd(oracle, x, dy, p, heads=6, groups=2, window=4, shift=2)
+    scale = np.abs(g[5]).sum(axis=0)
+    assert np.all(np.abs(g[5].sum(axis=0)) <= 1e-12 * scale)
+    # bias gradients are plain column sums
+    np.testing.assert_allclose(g[4], dy.reshape(-1, 12).sum(0), rtol=1e-13)
+
+
+def test_thread_count_does_not_change_results(oracle):
+    x, dy, p = make(2, 8, 8, 12, 6, 2, 4, seed=17)
+    kw = dict(heads=6, groups=2, window=4, shift=2)
+    n0 = oracle.threads()
+    try:
+        oracle.set_threads(1)
+        a = run_bwd(oracle, x, dy, p, **kw)
+        oracle.set_threads(3)
+        b = run_bwd(oracle, x, dy, p, **kw)
+    finally:
+        oracle.set_threads(n0)
+    for u, v in zip(a, b):
+        np.testing.assert_allclose(u, v, rtol=1e-12, atol=1e-13)
+
+
+def test_rejects_bad_shapes(oracle):
+    x, _, p = make(1, 8, 8, 12, 6, 2, 4)
+    with pytest.raises(ValueError):
+        run_fwd(oracle, x, p, heads=6, groups=2, window=4, shift=4)
+    with pytest.raises(ValueError):
+        run_fwd(oracle, x[:, :6], p, heads=6, groups=2, window=4, shift=0)
+
+
+def test_bf16_rounding_helper():
+    """Round-to-nearest-even on the host matches the definition of bfloat16."""
+    a = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -0.1, 3.0e38, 0.0],
+                 dtype=np.float32)
+    q = synth.quantize(a, "bf16")
+    assert q[0] == 1.0 and q[1] == 1.0            # tie -> even mantissa
+    assert q[2] == np.float32(1.0 + 2 ** -7)      # just above the tie
+    assert q[3] == np.float32(1.0 + 2 ** -6)      # tie -> even (up)
+    assert abs(q[4] + 0.1) <= 0.1 * 2 ** -8
+    assert np.isfinite(q[5]) and q[6] == 0.0
+    assert np.array_equal(synth.quantize(q, "bf16"), q)
+
+
+def test_oracle_unchanged_on_fp32_parity_case(oracle):
+    """Regression guard: the stored digest was written by tests/golden/make_golden.py."""
+    import json
+    import os
+    from tests.golden import make_golden
+    with open(os.path.join(os.path.dirname(make_golden.__file__), "c1_oracle.json")) as f:
+        stored = json.load(f)
+    now = make_golden.compute()
+    for key, dig in stored.items():
+        if key == "case":
+            continue
+        np.testing.assert_allclose(now[key]["probe"], dig["probe"], rtol=1e-10, atol=1e-14)
+        np.testing.assert_allclose(now[key]["abs_sum"], dig["abs_sum"], rtol=1e-10)
