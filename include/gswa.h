@@ -1,0 +1,125 @@
+/*
+ * gswa.h -- C ABI of the Group Shifted Window Attention (GSWA) layer for AMD MI355X (gfx950).
+ *
+ * One call computes one GW-MSA / GSW-MSA layer of AgileIR (Sec. "Group Shifted Window
+ * Attention"): the feature map is cyclically shifted and cut into M x M windows (Sec. "Patch
+ * Embedding"), its channels are split into G head groups, every group runs multi-head
+ * attention inside each window on its own channel slice with its own Q/K/V projection
+ * (Eq. 6), the input of group g > 0 is its slice plus the output of group g-1 (Eq. 8), and
+ * the concatenated group outputs go through one output projection (Eq. 7) and back to their
+ * places in the map.  Scores carry the learnable relative position bias (Sec. "Learnable
+ * Relative Shifted Bias") and, when shift > 0, the additive -100 mask between tokens that
+ * the cyclic shift brought together from opposite borders.
+ *
+ * In symbols, for image b, window (wi, wj) of the shifted frame and tokens n = r*M + c:
+ *   (i, j) = (wi*M + r, wj*M + c);  src(n) = ((i + shift) mod H, (j + shift) mod W)
+ *   F_g = x[b, src, g*Cg:(g+1)*Cg] (+ O_{g-1} if g > 0);  [q|k|v] = F_g Wqkv_g^T + bqkv_g
+ *   S = q_h k_h^T / sqrt(d) + table[idx(n,m), head] + mask;  O_g = concat_h softmax(S) v_h
+ *   y[b, src, :] = concat_g(O_g) Wproj^T + bproj
+ *   idx(n,m) = (r_n - r_m + M-1)*(2M-1) + (c_n - c_m + M-1)
+ * with Cg = C/groups, d = C/heads, heads/groups heads per group.
+ *
+ * Conventions for every entry point
+ *   - `desc` is a HOST pointer.  Every other pointer is a DEVICE pointer into memory the
+ *     caller owns (hipMalloc or a torch tensor); the library never allocates, frees or
+ *     synchronises.  All work is enqueued on `hip_stream` (a hipStream_t; NULL = default
+ *     stream).  Buffers must stay valid until that work has run.
+ *   - Layouts are C-contiguous with the last index fastest.
+ *       x, y, dy, dx   [B, H, W, C]                         element type desc->dtype
+ *       w_qkv          [groups, 3*Cg, Cg]  (out, in)        desc->dtype
+ *                      out row o = t*Cg + hl*d + e, t in {0:q, 1:k, 2:v}, hl head in group
+ *       b_qkv          [groups, 3*Cg]                       desc->dtype
+ *       w_proj         [C, C] (out, in); in column = (g*hg + hl)*d + e;  b_proj [C]
+ *       bias_table     [(2*window-1)^2, heads]              desc->dtype
+ *       dw_qkv, db_qkv, dw_proj, db_proj, dbias_table: shaped like their parameter, ALWAYS fp32
+ *     With groups == 1 these are the usual window-attention shapes [3C,C], [C,C], [(2M-1)^2,h].
+ *   - Arithmetic accumulates in fp32 for both element types.
+ *   - Return value: GSWA_OK (0) or a negative gswa_status.  Arguments are validated before
+ *     anything is enqueued, so a failed call has not touched any output.  Nothing throws or
+ *     aborts across this boundary.
+ */
+#ifndef GSWA_H
+#define GSWA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GSWA_OK = 0,
+    GSWA_EINVAL = -1,       /* null pointer, non-positive size, divisibility or shift range violated */
+    GSWA_EUNSUPPORTED = -2, /* valid layer, but no kernel of this library covers it (e.g. LDS need)  */
+    GSWA_EHIP = -3          /* a HIP runtime call failed; gswa_last_hip_error() has its text         */
+} gswa_status;
+
+enum { GSWA_F32 = 0, GSWA_BF16 = 1 };
+
+enum {
+    GSWA_NO_CASCADE = 1u << 0, /* drop Eq. 8: every group sees only its own channel slice          */
+    GSWA_ACCUM_WGRAD = 1u << 1 /* backward adds into the five parameter gradients (no zero fill)   */
+};
+
+typedef struct gswa_desc {
+    int32_t B, H, W, C;    /* feature map [B, H, W, C]                                        */
+    int32_t heads, groups; /* C % heads == 0, heads % groups == 0                              */
+    int32_t window, shift; /* H % window == 0, W % window == 0, 0 <= shift < window            */
+    int32_t dtype;         /* GSWA_F32 or GSWA_BF16: x, y, dy, dx, weights, biases, bias table */
+    uint32_t flags;        /* OR of GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD                          */
+} gswa_desc;
+
+/*
+ * Sizes, in bytes, of the caller-provided device buffers (Sec. "Group Shifted Window
+ * Attention": the head-group loop is what bounds them).
+ *   *saved_bytes   state forward leaves for backward: the concatenated group outputs
+ *                  [B*H*W, C] in desc->dtype.  Scores and probabilities are never kept;
+ *                  backward recomputes them.
+ *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given: one group's q|k|v.
+ *                  With saved == NULL the scratch must hold fwd_ws_bytes + saved_bytes.
+ *   *bwd_ws_bytes  scratch of gswa_backward: one group's q|k|v and its gradient.
+ * Any output pointer may be NULL.  All sizes are multiples of 256.
+ */
+int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes,
+                     size_t *bwd_ws_bytes);
+
+/*
+ * y = GSWA(x)  (Eq. 6-8 with shift, partition, bias and mask as above).
+ *   saved  NULL for inference; otherwise receives what gswa_backward needs and must be left
+ *          untouched until that call has run.
+ *   ws     scratch, 256-byte aligned, sized by gswa_query_bytes; contents undefined afterwards.
+ * x and y must not overlap.
+ */
+int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const void *b_qkv,
+                 const void *w_proj, const void *b_proj, const void *bias_table, void *y,
+                 void *saved, void *ws, void *hip_stream);
+
+/*
+ * Gradients of a scalar loss through the layer, given dy = dLoss/dy and the `saved` buffer
+ * written by gswa_forward on the same desc, x and parameters.
+ *   dx                    [B,H,W,C] in desc->dtype, overwritten.
+ *   dw_qkv ... dbias_table fp32, overwritten, or added into with GSWA_ACCUM_WGRAD.
+ *                         They are reduced with fp32 atomics: the summation order, hence the
+ *                         last bits, can differ between runs.
+ * dx may not overlap x, dy or saved.
+ */
+int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const void *w_qkv,
+                  const void *b_qkv, const void *w_proj, const void *b_proj,
+                  const void *bias_table, const void *saved, void *dx, void *dw_qkv,
+                  void *db_qkv, void *dw_proj, void *db_proj, void *dbias_table, void *ws,
+                  void *hip_stream);
+
+/* Static text for a gswa_status value. */
+const char *gswa_strerror(int status);
+
+/* Text of the HIP error behind the calling thread's most recent GSWA_EHIP ("" if none). */
+const char *gswa_last_hip_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int gswa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSWA_H */

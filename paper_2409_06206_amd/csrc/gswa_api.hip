@@ -1,0 +1,252 @@
+// C ABI of the GSWA library: argument validation, buffer carving and the order in which the
+// kernels of one layer are enqueued.  No allocation, no synchronisation.
+#include "../../include/gswa.h"
+#include "common.h"
+#include "staged_kernels.h"
+
+#include <string>
+
+namespace {
+
+using namespace gswa;
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e)
+{
+    g_hip_error = hipGetErrorString(e);
+    return GSWA_EHIP;
+}
+
+#define GSWA_HIP(expr)                                \
+    do {                                              \
+        hipError_t e_ = (expr);                       \
+        if (e_ != hipSuccess) return hip_fail(e_);    \
+    } while (0)
+
+size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+
+// Checks the descriptor (divisibility rules of the window partition and of the head groups)
+// and derives the geometry.
+int make_geom(const gswa_desc *d, Geom *g)
+{
+    if (!d) return GSWA_EINVAL;
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0) return GSWA_EINVAL;
+    if (d->heads <= 0 || d->groups <= 0 || d->window <= 0) return GSWA_EINVAL;
+    if (d->C % d->heads || d->heads % d->groups) return GSWA_EINVAL;
+    if (d->H % d->window || d->W % d->window) return GSWA_EINVAL;
+    if (d->shift < 0 || d->shift >= d->window) return GSWA_EINVAL;
+    if (d->dtype != GSWA_F32 && d->dtype != GSWA_BF16) return GSWA_EINVAL;
+    if (d->flags & ~(uint32_t)(GSWA_NO_CASCADE | GSWA_ACCUM_WGRAD)) return GSWA_EINVAL;
+    const long T = (long)d->B * d->H * d->W;
+    const long nW = T / ((long)d->window * d->window);
+    if (T * 3 * d->C >= (1L << 40) || nW > 0x7fffffffL) return GSWA_EUNSUPPORTED;
+    if (d->window > 64) return GSWA_EUNSUPPORTED;
+    g->B = d->B; g->H = d->H; g->W = d->W; g->C = d->C;
+    g->heads = d->heads; g->groups = d->groups; g->M = d->window; g->shift = d->shift;
+    g->N = d->window * d->window;
+    g->Cg = d->C / d->groups;
+    g->hg = d->heads / d->groups;
+    g->d = d->C / d->heads;
+    g->nwi = d->H / d->window; g->nwj = d->W / d->window;
+    g->nW = (int)nW;
+    g->T = T;
+    g->cascade = (d->flags & GSWA_NO_CASCADE) ? 0 : 1;
+    int rs_f = 0, rs_b = 0;
+    attn_fwd_lds_bytes(*g, &rs_f);
+    attn_bwd_lds_bytes(*g, &rs_b);
+    if (rs_f == 0 || rs_b == 0) return GSWA_EUNSUPPORTED;
+    return GSWA_OK;
+}
+
+size_t elem_size(const gswa_desc *d) { return d->dtype == GSWA_F32 ? 4 : 2; }
+
+struct Sizes {
+    size_t saved, qkv, fwd_ws, bwd_ws;
+};
+
+Sizes make_sizes(const gswa_desc *d, const Geom &g)
+{
+    Sizes s;
+    const size_t e = elem_size(d);
+    s.saved = align256((size_t)g.T * g.C * e);
+    s.qkv = align256((size_t)g.T * 3 * g.Cg * e);
+    s.fwd_ws = s.qkv;
+    s.bwd_ws = 2 * s.qkv;
+    return s;
+}
+
+template <typename T>
+int forward_staged(const Geom &g, const Sizes &sz, const T *x, const T *w_qkv, const T *b_qkv,
+                   const T *w_proj, const T *b_proj, const T *table, T *y, T *saved, char *ws,
+                   hipStream_t st)
+{
+    T *qkv = reinterpret_cast<T *>(ws);
+    T *attn = saved ? saved : reinterpret_cast<T *>(ws + sz.qkv);
+    const int C = g.C, Cg = g.Cg;
+    for (int grp = 0; grp < g.groups; ++grp) {
+        LinearArgs la{};
+        la.a1 = x + grp * Cg; la.lda1 = C;
+        if (grp > 0 && g.cascade) { la.a2 = attn + (grp - 1) * Cg; la.lda2 = C; }
+        la.w = w_qkv + (size_t)grp * 3 * Cg * Cg; la.w_sn = Cg; la.w_sk = 1;
+        la.bias = b_qkv + (size_t)grp * 3 * Cg;
+        la.out = qkv; la.ldout = 3 * Cg;
+        la.rows = g.T; la.N = 3 * Cg; la.K = Cg;
+        GSWA_HIP(launch_linear<T>(la, st));
+        GSWA_HIP(launch_attn_fwd<T>(g, grp, qkv, table, attn, st));
+    }
+    LinearArgs lp{};
+    lp.a1 = attn; lp.lda1 = C;
+    lp.w = w_proj; lp.w_sn = C; lp.w_sk = 1;
+    lp.bias = b_proj;
+    lp.out = y; lp.ldout = C;
+    lp.rows = g.T; lp.N = C; lp.K = C;
+    GSWA_HIP(launch_linear<T>(lp, st));
+    return GSWA_OK;
+}
+
+template <typename T>
+int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, const T *dy,
+                    const T *w_qkv, const T *b_qkv, const T *w_proj, const T *table,
+                    const T *attn, T *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
+                    float *db_proj, float *dtable, char *ws, hipStream_t st)
+{
+    T *qkv = reinterpret_cast<T *>(ws);
+    T *dqkv = reinterpret_cast<T *>(ws + sz.qkv);
+    const int C = g.C, Cg = g.Cg, G = g.groups;
+    if (!(flags & GSWA_ACCUM_WGRAD)) {
+        GSWA_HIP(launch_fill_zero(dw_qkv, (size_t)G * 3 * Cg * Cg, st));
+        GSWA_HIP(launch_fill_zero(db_qkv, (size_t)G * 3 * Cg, st));
+        GSWA_HIP(launch_fill_zero(dw_proj, (size_t)C * C, st));
+        GSWA_HIP(launch_fill_zero(db_proj, (size_t)C, st));
+        GSWA_HIP(launch_fill_zero(dtable, (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads, st));
+    }
+    // adjoint of Eq. 7 with respect to the projection parameters
+    WgradArgs wp{};
+    wp.dout = dy; wp.lddout = C;
+    wp.a1 = attn; wp.lda1 = C;
+    wp.dw = dw_proj; wp.db = db_proj;
+    wp.rows = g.T; wp.N = C; wp.K = C;
+    GSWA_HIP(launch_wgrad<T>(wp, st));
+
+    for (int grp = G - 1; grp >= 0; --grp) {
+        const T *wg = w_qkv + (size_t)grp * 3 * Cg * Cg;
+        const bool has_prev = grp > 0 && g.cascade;
+        // recompute q|k|v of the group (Eq. 6, 8)
+        LinearArgs la{};
+        la.a1 = x + grp * Cg; la.lda1 = C;
+        if (has_prev) { la.a2 = attn + (grp - 1) * Cg; la.lda2 = C; }
+        la.w = wg; la.w_sn = Cg; la.w_sk = 1;
+        la.bias = b_qkv + (size_t)grp * 3 * Cg;
+        la.out = qkv; la.ldout = 3 * Cg;
+        la.rows = g.T; la.N = 3 * Cg; la.K = Cg;
+        GSWA_HIP(launch_linear<T>(la, st));
+        // dO_g = dy Wproj[:, slice g] (+ dF_{g+1}, which is dx[:, slice g+1]) into the v third of dqkv
+        LinearArgs lo{};
+        lo.a1 = dy; lo.lda1 = C;
+        lo.w = w_proj + grp * Cg; lo.w_sn = 1; lo.w_sk = C;
+        if (grp < G - 1 && g.cascade) { lo.add = dx + (grp + 1) * Cg; lo.ldadd = C; }
+        lo.out = dqkv + 2 * Cg; lo.ldout = 3 * Cg;
+        lo.rows = g.T; lo.N = Cg; lo.K = C;
+        GSWA_HIP(launch_linear<T>(lo, st));
+        GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, dtable, st));
+        // dF_g = dqkv Wqkv_g  ->  dx[:, slice g]
+        LinearArgs lx{};
+        lx.a1 = dqkv; lx.lda1 = 3 * Cg;
+        lx.w = wg; lx.w_sn = 1; lx.w_sk = Cg;
+        lx.out = dx + grp * Cg; lx.ldout = C;
+        lx.rows = g.T; lx.N = Cg; lx.K = 3 * Cg;
+        GSWA_HIP(launch_linear<T>(lx, st));
+        WgradArgs wq{};
+        wq.dout = dqkv; wq.lddout = 3 * Cg;
+        wq.a1 = x + grp * Cg; wq.lda1 = C;
+        if (has_prev) { wq.a2 = attn + (grp - 1) * Cg; wq.lda2 = C; }
+        wq.dw = dw_qkv + (size_t)grp * 3 * Cg * Cg;
+        wq.db = db_qkv + (size_t)grp * 3 * Cg;
+        wq.rows = g.T; wq.N = 3 * Cg; wq.K = Cg;
+        GSWA_HIP(launch_wgrad<T>(wq, st));
+    }
+    return GSWA_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes,
+                     size_t *bwd_ws_bytes)
+{
+    Geom g;
+    int rc = make_geom(desc, &g);
+    if (rc != GSWA_OK) return rc;
+    Sizes s = make_sizes(desc, g);
+    if (saved_bytes) *saved_bytes = s.saved;
+    if (fwd_ws_bytes) *fwd_ws_bytes = s.fwd_ws;
+    if (bwd_ws_bytes) *bwd_ws_bytes = s.bwd_ws;
+    return GSWA_OK;
+}
+
+int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const void *b_qkv,
+                 const void *w_proj, const void *b_proj, const void *bias_table, void *y,
+                 void *saved, void *ws, void *hip_stream)
+{
+    Geom g;
+    int rc = make_geom(desc, &g);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !w_qkv || !b_qkv || !w_proj || !b_proj || !bias_table || !y || !ws) return GSWA_EINVAL;
+    if (x == y || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    Sizes s = make_sizes(desc, g);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (desc->dtype == GSWA_F32)
+        return forward_staged<float>(g, s, (const float *)x, (const float *)w_qkv, (const float *)b_qkv,
+                                     (const float *)w_proj, (const float *)b_proj,
+                                     (const float *)bias_table, (float *)y, (float *)saved, (char *)ws, st);
+    return forward_staged<bf16_t>(g, s, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
+                                  (const bf16_t *)w_proj, (const bf16_t *)b_proj,
+                                  (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, (char *)ws, st);
+}
+
+int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const void *w_qkv,
+                  const void *b_qkv, const void *w_proj, const void *b_proj,
+                  const void *bias_table, const void *saved, void *dx, void *dw_qkv,
+                  void *db_qkv, void *dw_proj, void *db_proj, void *dbias_table, void *ws,
+                  void *hip_stream)
+{
+    Geom g;
+    int rc = make_geom(desc, &g);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !dy || !w_qkv || !b_qkv || !w_proj || !b_proj || !bias_table || !saved || !dx ||
+        !dw_qkv || !db_qkv || !dw_proj || !db_proj || !dbias_table || !ws)
+        return GSWA_EINVAL;
+    if (dx == x || dx == dy || dx == saved || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    Sizes s = make_sizes(desc, g);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (desc->dtype == GSWA_F32)
+        return backward_staged<float>(g, s, desc->flags, (const float *)x, (const float *)dy,
+                                      (const float *)w_qkv, (const float *)b_qkv, (const float *)w_proj,
+                                      (const float *)bias_table, (const float *)saved, (float *)dx,
+                                      (float *)dw_qkv, (float *)db_qkv, (float *)dw_proj,
+                                      (float *)db_proj, (float *)dbias_table, (char *)ws, st);
+    return backward_staged<bf16_t>(g, s, desc->flags, (const bf16_t *)x, (const bf16_t *)dy,
+                                   (const bf16_t *)w_qkv, (const bf16_t *)b_qkv, (const bf16_t *)w_proj,
+                                   (const bf16_t *)bias_table, (const bf16_t *)saved, (bf16_t *)dx,
+                                   (float *)dw_qkv, (float *)db_qkv, (float *)dw_proj,
+                                   (float *)db_proj, (float *)dbias_table, (char *)ws, st);
+}
+
+const char *gswa_strerror(int status)
+{
+    switch (status) {
+    case GSWA_OK: return "ok";
+    case GSWA_EINVAL: return "invalid argument (null pointer, size, divisibility or shift range)";
+    case GSWA_EUNSUPPORTED: return "layer shape not covered by any kernel of this library";
+    case GSWA_EHIP: return "HIP runtime call failed";
+    default: return "unknown status";
+    }
+}
+
+const char *gswa_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int gswa_version(void) { return 100; }
+
+} // extern "C"

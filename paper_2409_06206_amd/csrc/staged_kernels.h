@@ -1,0 +1,51 @@
+// Launchers of the staged (one kernel per step) GSWA path.  This path covers every valid
+// layer shape in fp32 arithmetic on plain vector ALUs; the fused MFMA kernels take over the
+// shapes they are built for.
+#pragma once
+#include "common.h"
+
+namespace gswa {
+
+// out[t, n] = sum_k (a1[t,k] + a2[t,k]) * w(n,k) + bias[n] + add[t,n]
+// w(n,k) = w[n*w_sn + k*w_sk]; a2, bias, add may be null.  Strides in elements.
+struct LinearArgs {
+    const void *a1; long lda1;
+    const void *a2; long lda2;
+    const void *w; long w_sn, w_sk;
+    const void *bias;
+    const void *add; long ldadd;
+    void *out; long ldout;
+    long rows; int N, K;
+};
+
+// dw[n,k] += sum_t dout[t,n] * (a1[t,k] + a2[t,k]);  db[n] += sum_t dout[t,n]   (fp32 atomics)
+struct WgradArgs {
+    const void *dout; long lddout;
+    const void *a1; long lda1;
+    const void *a2; long lda2;
+    float *dw; float *db;
+    long rows; int N, K;
+};
+
+template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);
+template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s);
+
+// Attention core of head group `grp` (Eq. 6 right-hand side): reads q|k|v [T, 3Cg] through the
+// shift/partition map, writes O into columns of attn_out [T, C] at the tokens' own positions.
+template <typename T>
+hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table, T *attn_out,
+                           hipStream_t s);
+
+// Adjoint of the attention core for group `grp`.  On entry the v third of dqkv [T, 3Cg] holds
+// dO of the group; on exit dqkv holds dq|dk|dv.  dtable (fp32) is added into.
+template <typename T>
+hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
+                           float *dtable, hipStream_t s);
+
+// LDS bytes the two attention kernels need for this geometry, or 0 if no strip height fits.
+size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows);
+size_t attn_bwd_lds_bytes(const Geom &g, int *strip_rows);
+
+hipError_t launch_fill_zero(float *p, size_t n, hipStream_t s);
+
+} // namespace gswa

@@ -1,0 +1,497 @@
+// Staged GSWA kernels: projection GEMMs, weight-gradient GEMMs and the per-(window, head)
+// attention core, all in fp32 arithmetic on the vector ALUs with LDS tiles.  They read and
+// write token-major buffers in the tokens' own (unshifted) order; the cyclic shift and the
+// window partition exist only as the index map window_token().
+#include "staged_kernels.h"
+
+namespace gswa {
+
+static constexpr int kThreads = 256;
+static constexpr size_t kLdsMax = 160 * 1024;
+
+// ---------------------------------------------------------------------------------------
+// out = (a1 + a2) * w^T-ish + bias + add      64 x 64 output tile, 4 x 4 per thread
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void linear_kernel(LinearArgs p)
+{
+    constexpr int TM = 64, TN = 64, TK = 16;
+    __shared__ float As[TK][TM + 1];
+    __shared__ float Ws[TK][TN + 1];
+    const T *a1 = static_cast<const T *>(p.a1);
+    const T *a2 = static_cast<const T *>(p.a2);
+    const T *w = static_cast<const T *>(p.w);
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const long row0 = (long)blockIdx.x * TM;
+    const int n0 = blockIdx.y * TN;
+    const bool k_contig = (p.w_sk == 1);
+
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < p.K; k0 += TK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + i * kThreads;
+            const int r = e >> 4, kk = e & 15;
+            const long row = row0 + r;
+            float v = 0.f;
+            if (row < p.rows && k0 + kk < p.K) {
+                v = to_f32(a1[row * p.lda1 + k0 + kk]);
+                if (a2) v += to_f32(a2[row * p.lda2 + k0 + kk]);
+            }
+            As[kk][r] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + i * kThreads;
+            const int nn = k_contig ? (e >> 4) : (e & 63);
+            const int kk = k_contig ? (e & 15) : (e >> 6);
+            float v = 0.f;
+            if (n0 + nn < p.N && k0 + kk < p.K) v = to_f32(w[(long)(n0 + nn) * p.w_sn + (long)(k0 + kk) * p.w_sk]);
+            Ws[kk][nn] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < TK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+
+    const T *bias = static_cast<const T *>(p.bias);
+    const T *add = static_cast<const T *>(p.add);
+    T *out = static_cast<T *>(p.out);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const long row = row0 + ty * 4 + i;
+        if (row >= p.rows) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n >= p.N) continue;
+            float v = acc[i][j];
+            if (bias) v += to_f32(bias[n]);
+            if (add) v += to_f32(add[row * p.ldadd + n]);
+            from_f32(out[row * p.ldout + n], v);
+        }
+    }
+}
+
+template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
+{
+    if (a.rows <= 0 || a.N <= 0) return hipSuccess;
+    dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
+    hipLaunchKernelGGL(linear_kernel<T>, grid, dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+template hipError_t launch_linear<float>(const LinearArgs &, hipStream_t);
+template hipError_t launch_linear<bf16_t>(const LinearArgs &, hipStream_t);
+
+// ---------------------------------------------------------------------------------------
+// dw[n,k] += sum_t dout[t,n] (a1+a2)[t,k] ; db[n] += sum_t dout[t,n]
+// 64 x 64 tile of dw per block, the token range split over blockIdx.z, fp32 atomics at the end
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_per_split)
+{
+    constexpr int TT = 16;
+    __shared__ float Ds[TT][64 + 1];
+    __shared__ float As[TT][64 + 1];
+    const T *dout = static_cast<const T *>(p.dout);
+    const T *a1 = static_cast<const T *>(p.a1);
+    const T *a2 = static_cast<const T *>(p.a2);
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    const long t_begin = (long)blockIdx.z * rows_per_split;
+    long t_end = t_begin + rows_per_split;
+    if (t_end > p.rows) t_end = p.rows;
+
+    float acc[4][4] = {};
+    float bacc[4] = {};
+    for (long t0 = t_begin; t0 < t_end; t0 += TT) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + i * kThreads;
+            const int tt = e >> 6, c = e & 63;
+            const long t = t0 + tt;
+            float dv = 0.f, av = 0.f;
+            if (t < t_end) {
+                if (n0 + c < p.N) dv = to_f32(dout[t * p.lddout + n0 + c]);
+                if (k0 + c < p.K) {
+                    av = to_f32(a1[t * p.lda1 + k0 + c]);
+                    if (a2) av += to_f32(a2[t * p.lda2 + k0 + c]);
+                }
+            }
+            Ds[tt][c] = dv;
+            As[tt][c] = av;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = Ds[tt][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = As[tt][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                bacc[i] += a[i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = n0 + ty * 4 + i;
+        if (n >= p.N) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = k0 + tx * 4 + j;
+            if (k < p.K) atomicAdd(&p.dw[(long)n * p.K + k], acc[i][j]);
+        }
+        if (p.db && blockIdx.y == 0 && tx == 0) atomicAdd(&p.db[n], bacc[i]);
+    }
+}
+
+template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
+{
+    if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
+    const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
+    long splits = 2048 / (long)(tn * tk);
+    const long max_splits = (a.rows + 255) / 256;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    long rps = (a.rows + splits - 1) / splits;
+    rps = (rps + 15) / 16 * 16;
+    splits = (a.rows + rps - 1) / rps;
+    dim3 grid(tn, tk, (unsigned)splits);
+    hipLaunchKernelGGL(wgrad_kernel<T>, grid, dim3(kThreads), 0, s, a, rps);
+    return hipGetLastError();
+}
+template hipError_t launch_wgrad<float>(const WgradArgs &, hipStream_t);
+template hipError_t launch_wgrad<bf16_t>(const WgradArgs &, hipStream_t);
+
+// ---------------------------------------------------------------------------------------
+// attention core, one block per (window, head of the group)
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Largest strip height (rows of the score tile held at once) whose LDS need fits `budget`.
+static int pick_strip(int N, size_t fixed_floats, size_t per_row_floats, size_t tail_bytes,
+                      size_t budget, size_t *bytes)
+{
+    int cand[9] = {N, 128, 64, 32, 16, 8, 4, 2, 1};
+    for (int i = 0; i < 9; ++i) {
+        const int rs = cand[i];
+        if (rs > N || (i > 0 && rs >= N)) continue;
+        size_t fl = fixed_floats + per_row_floats * rs;
+        fl = (fl + 1) & ~size_t(1);
+        const size_t b = fl * sizeof(float) + tail_bytes;
+        if (b <= budget) {
+            *bytes = b;
+            return rs;
+        }
+    }
+    *bytes = 0;
+    return 0;
+}
+
+size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows)
+{
+    const size_t dp = g.d | 1;
+    const size_t tail = (size_t)g.N * (sizeof(long) + sizeof(int));
+    size_t bytes = 0;
+    int rs = pick_strip(g.N, 3 * g.N * dp, g.N + 1, tail, 64 * 1024, &bytes);
+    if (rs < 8 && rs < g.N) rs = pick_strip(g.N, 3 * g.N * dp, g.N + 1, tail, kLdsMax, &bytes);
+    if (strip_rows) *strip_rows = rs;
+    return bytes;
+}
+
+size_t attn_bwd_lds_bytes(const Geom &g, int *strip_rows)
+{
+    const size_t dp = g.d | 1;
+    const size_t tbl = (size_t)(2 * g.M - 1) * (2 * g.M - 1);
+    const size_t tail = (size_t)g.N * (sizeof(long) + sizeof(int));
+    const size_t fixed = 4 * g.N * dp + tbl;
+    const size_t per_row = 2 * dp + 2 * (g.N + 1);
+    size_t bytes = 0;
+    int rs = pick_strip(g.N, fixed, per_row, tail, 80 * 1024, &bytes);
+    if (rs < 8 && rs < g.N) rs = pick_strip(g.N, fixed, per_row, tail, kLdsMax, &bytes);
+    if (strip_rows) *strip_rows = rs;
+    return bytes;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attn_fwd_kernel(Geom g, int grp, const T *__restrict__ qkv,
+                                                            const T *__restrict__ table,
+                                                            T *__restrict__ attn_out, int RS)
+{
+    extern __shared__ float smem[];
+    const int N = g.N, d = g.d, dp = d | 1, Cg = g.Cg, M = g.M;
+    const int ldS = N + 1;
+    float *q = smem;
+    float *k = q + N * dp;
+    float *v = k + N * dp;
+    float *S = v + N * dp;
+    size_t fl = (size_t)3 * N * dp + (size_t)RS * ldS;
+    fl = (fl + 1) & ~size_t(1);
+    long *tok = reinterpret_cast<long *>(smem + fl);
+    int *reg = reinterpret_cast<int *>(tok + N);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int w = blockIdx.x, hl = blockIdx.y, hd = grp * g.hg + hl;
+
+    for (int n = tid; n < N; n += kThreads) {
+        int r;
+        tok[n] = window_token(g, w, n, r);
+        reg[n] = r;
+    }
+    __syncthreads();
+    for (int e = tid; e < N * d; e += kThreads) {
+        const int n = e / d, c = e - n * d;
+        const long base = tok[n] * 3 * Cg + hl * d + c;
+        q[n * dp + c] = to_f32(qkv[base]);
+        k[n * dp + c] = to_f32(qkv[base + Cg]);
+        v[n * dp + c] = to_f32(qkv[base + 2 * Cg]);
+    }
+    __syncthreads();
+
+    const float scale = 1.0f / sqrtf((float)d);
+    for (int n0 = 0; n0 < N; n0 += RS) {
+        const int rows = min(RS, N - n0);
+        for (int e = tid; e < rows * N; e += kThreads) {
+            const int r = e / N, m = e - r * N, n = n0 + r;
+            float dot = 0.f;
+            for (int c = 0; c < d; ++c) dot = fmaf(q[n * dp + c], k[m * dp + c], dot);
+            const int rn = n / M, cn = n - rn * M, rm = m / M, cm = m - rm * M;
+            const int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
+            float sc = dot * scale + to_f32(table[(long)idx * g.heads + hd]);
+            if (reg[n] != reg[m]) sc += -100.0f;
+            S[r * ldS + m] = sc;
+        }
+        __syncthreads();
+        for (int r = wave; r < rows; r += kThreads / 64) {
+            float mx = -INFINITY;
+            for (int m = lane; m < N; m += 64) mx = fmaxf(mx, S[r * ldS + m]);
+            mx = wave_max(mx);
+            float sum = 0.f;
+            for (int m = lane; m < N; m += 64) {
+                const float ev = expf(S[r * ldS + m] - mx);
+                S[r * ldS + m] = ev;
+                sum += ev;
+            }
+            sum = wave_sum(sum);
+            const float inv = 1.0f / sum;
+            for (int m = lane; m < N; m += 64) S[r * ldS + m] *= inv;
+        }
+        __syncthreads();
+        for (int e = tid; e < rows * d; e += kThreads) {
+            const int r = e / d, c = e - r * d;
+            float acc = 0.f;
+            for (int m = 0; m < N; ++m) acc = fmaf(S[r * ldS + m], v[m * dp + c], acc);
+            from_f32(attn_out[tok[n0 + r] * g.C + hd * d + c], acc);
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table, T *attn_out,
+                           hipStream_t s)
+{
+    int rs = 0;
+    const size_t lds = attn_fwd_lds_bytes(g, &rs);
+    if (rs == 0) return hipErrorInvalidValue;
+    auto kern = attn_fwd_kernel<T>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, table, attn_out, rs);
+    return hipGetLastError();
+}
+template hipError_t launch_attn_fwd<float>(const Geom &, int, const float *, const float *, float *, hipStream_t);
+template hipError_t launch_attn_fwd<bf16_t>(const Geom &, int, const bf16_t *, const bf16_t *, bf16_t *, hipStream_t);
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, const T *__restrict__ qkv,
+                                                            T *dqkv, const T *__restrict__ table,
+                                                            float *dtable, int RS)
+{
+    extern __shared__ float smem[];
+    const int N = g.N, d = g.d, dp = d | 1, Cg = g.Cg, M = g.M;
+    const int ldS = N + 1, ntbl = (2 * M - 1) * (2 * M - 1);
+    float *k = smem;
+    float *v = k + N * dp;
+    float *dk = v + N * dp;
+    float *dv = dk + N * dp;
+    float *tbl = dv + N * dp;
+    float *q = tbl + ntbl;
+    float *dO = q + RS * dp;
+    float *P = dO + RS * dp;
+    float *dS = P + RS * ldS;
+    size_t fl = (size_t)4 * N * dp + ntbl + (size_t)RS * (2 * dp + 2 * ldS);
+    fl = (fl + 1) & ~size_t(1);
+    long *tok = reinterpret_cast<long *>(smem + fl);
+    int *reg = reinterpret_cast<int *>(tok + N);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int w = blockIdx.x, hl = blockIdx.y, hd = grp * g.hg + hl;
+
+    for (int n = tid; n < N; n += kThreads) {
+        int r;
+        tok[n] = window_token(g, w, n, r);
+        reg[n] = r;
+    }
+    for (int e = tid; e < ntbl; e += kThreads) tbl[e] = 0.f;
+    __syncthreads();
+    for (int e = tid; e < N * d; e += kThreads) {
+        const int n = e / d, c = e - n * d;
+        const long base = tok[n] * 3 * Cg + hl * d + c;
+        k[n * dp + c] = to_f32(qkv[base + Cg]);
+        v[n * dp + c] = to_f32(qkv[base + 2 * Cg]);
+        dk[n * dp + c] = 0.f;
+        dv[n * dp + c] = 0.f;
+    }
+    const float scale = 1.0f / sqrtf((float)d);
+
+    for (int n0 = 0; n0 < N; n0 += RS) {
+        const int rows = min(RS, N - n0);
+        __syncthreads();
+        for (int e = tid; e < rows * d; e += kThreads) {
+            const int r = e / d, c = e - r * d;
+            const long base = tok[n0 + r] * 3 * Cg + hl * d + c;
+            q[r * dp + c] = to_f32(qkv[base]);
+            dO[r * dp + c] = to_f32(dqkv[base + 2 * Cg]);
+        }
+        __syncthreads();
+        // scores and dP = dO v^T
+        for (int e = tid; e < rows * N; e += kThreads) {
+            const int r = e / N, m = e - r * N, n = n0 + r;
+            float dot = 0.f, dp_ = 0.f;
+            for (int c = 0; c < d; ++c) {
+                dot = fmaf(q[r * dp + c], k[m * dp + c], dot);
+                dp_ = fmaf(dO[r * dp + c], v[m * dp + c], dp_);
+            }
+            const int rn = n / M, cn = n - rn * M, rm = m / M, cm = m - rm * M;
+            const int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
+            float sc = dot * scale + to_f32(table[(long)idx * g.heads + hd]);
+            if (reg[n] != reg[m]) sc += -100.0f;
+            P[r * ldS + m] = sc;
+            dS[r * ldS + m] = dp_;
+        }
+        __syncthreads();
+        // softmax and its adjoint, one wave per row; bias-table gradient pre-reduced in LDS
+        for (int r = wave; r < rows; r += kThreads / 64) {
+            const int n = n0 + r, rn = n / M, cn = n - rn * M;
+            float mx = -INFINITY;
+            for (int m = lane; m < N; m += 64) mx = fmaxf(mx, P[r * ldS + m]);
+            mx = wave_max(mx);
+            float sum = 0.f;
+            for (int m = lane; m < N; m += 64) {
+                const float ev = expf(P[r * ldS + m] - mx);
+                P[r * ldS + m] = ev;
+                sum += ev;
+            }
+            sum = wave_sum(sum);
+            const float inv = 1.0f / sum;
+            float dotp = 0.f;
+            for (int m = lane; m < N; m += 64) {
+                const float pv = P[r * ldS + m] * inv;
+                P[r * ldS + m] = pv;
+                dotp = fmaf(pv, dS[r * ldS + m], dotp);
+            }
+            dotp = wave_sum(dotp);
+            for (int m = lane; m < N; m += 64) {
+                const float ds = P[r * ldS + m] * (dS[r * ldS + m] - dotp);
+                dS[r * ldS + m] = ds;
+                const int rm = m / M, cm = m - rm * M;
+                atomicAdd(&tbl[(rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1)], ds);
+            }
+        }
+        __syncthreads();
+        // dq rows of this strip
+        for (int e = tid; e < rows * d; e += kThreads) {
+            const int r = e / d, c = e - r * d;
+            float acc = 0.f;
+            for (int m = 0; m < N; ++m) acc = fmaf(dS[r * ldS + m], k[m * dp + c], acc);
+            from_f32(dqkv[tok[n0 + r] * 3 * Cg + hl * d + c], acc * scale);
+        }
+        // dk, dv accumulate over strips; element (m, c) belongs to one thread
+        for (int e = tid; e < N * d; e += kThreads) {
+            const int m = e / d, c = e - m * d;
+            float ak = 0.f, av = 0.f;
+            for (int r = 0; r < rows; ++r) {
+                ak = fmaf(dS[r * ldS + m], q[r * dp + c], ak);
+                av = fmaf(P[r * ldS + m], dO[r * dp + c], av);
+            }
+            dk[m * dp + c] += ak * scale;
+            dv[m * dp + c] += av;
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < N * d; e += kThreads) {
+        const int n = e / d, c = e - n * d;
+        const long base = tok[n] * 3 * Cg + hl * d + c;
+        from_f32(dqkv[base + Cg], dk[n * dp + c]);
+        from_f32(dqkv[base + 2 * Cg], dv[n * dp + c]);
+    }
+    for (int e = tid; e < ntbl; e += kThreads) atomicAdd(&dtable[(long)e * g.heads + hd], tbl[e]);
+}
+
+template <typename T>
+hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
+                           float *dtable, hipStream_t s)
+{
+    int rs = 0;
+    const size_t lds = attn_bwd_lds_bytes(g, &rs);
+    if (rs == 0) return hipErrorInvalidValue;
+    auto kern = attn_bwd_kernel<T>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, dqkv, table, dtable, rs);
+    return hipGetLastError();
+}
+template hipError_t launch_attn_bwd<float>(const Geom &, int, const float *, float *, const float *, float *, hipStream_t);
+template hipError_t launch_attn_bwd<bf16_t>(const Geom &, int, const bf16_t *, bf16_t *, const bf16_t *, float *, hipStream_t);
+
+__global__ void fill_zero_kernel(float *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0.f;
+}
+
+hipError_t launch_fill_zero(float *p, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
+} // namespace gswa

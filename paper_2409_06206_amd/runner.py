@@ -1,0 +1,64 @@
+"""Device-side plumbing around the binding: uploads numpy inputs as torch tensors, owns the
+output/scratch buffers of one layer and hands raw results back.  No arithmetic of the layer
+happens here."""
+import numpy as np
+import torch
+
+from . import gswa, synth
+
+_PARAMS = ("w_qkv", "b_qkv", "w_proj", "b_proj", "table")
+
+
+def to_device(a, dtype, device="cuda:0"):
+    """numpy fp32 values -> device tensor of storage type 'f32' or 'bf16' (RNE on the host)."""
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    bits = synth.to_bf16_bits(a).reshape(np.shape(a))
+    return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def to_host(t):
+    return t.detach().float().cpu().numpy()
+
+
+class DeviceLayer:
+    """Buffers of one GSWA layer call on the GPU (inputs, outputs, saved state, scratch)."""
+
+    def __init__(self, B, H, W, C, heads, groups, window, shift, dtype, flags=0, device="cuda:0"):
+        self.desc = gswa.make_desc(B, H, W, C, heads, groups, window, shift, dtype, flags)
+        self.dtype, self.device = dtype, device
+        self.shape = (B, H, W, C)
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.saved_bytes, self.fwd_ws_bytes, self.bwd_ws_bytes = gswa.gswa_query_bytes(self.desc)
+        self.y = torch.empty(self.shape, dtype=tdt, device=device)
+        self.dx = torch.empty(self.shape, dtype=tdt, device=device)
+        self.saved = torch.empty(self.saved_bytes, dtype=torch.uint8, device=device)
+        ws_bytes = max(self.fwd_ws_bytes + self.saved_bytes, self.bwd_ws_bytes)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
+        shp = synth.param_shapes(C, heads, groups, window)
+        self.grads = {k: torch.empty(shp[k], dtype=torch.float32, device=device) for k in _PARAMS}
+        self.params = None
+        self.x = self.dy = None
+
+    def set_params(self, p):
+        self.params = {k: to_device(p[k], self.dtype, self.device) for k in _PARAMS}
+
+    def set_inputs(self, x, dy=None):
+        self.x = to_device(x, self.dtype, self.device)
+        self.dy = None if dy is None else to_device(dy, self.dtype, self.device)
+
+    def forward(self, keep=True, stream=None):
+        p = self.params
+        gswa.gswa_forward(self.desc, self.x, p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"],
+                          p["table"], self.y, self.saved if keep else None, self.ws, stream)
+
+    def backward(self, stream=None):
+        p, g = self.params, self.grads
+        gswa.gswa_backward(self.desc, self.x, self.dy, p["w_qkv"], p["b_qkv"], p["w_proj"],
+                           p["b_proj"], p["table"], self.saved, self.dx, g["w_qkv"], g["b_qkv"],
+                           g["w_proj"], g["b_proj"], g["table"], self.ws, stream)
+
+    def results(self):
+        out = {"y": to_host(self.y), "dx": to_host(self.dx)}
+        out.update({"d" + k: to_host(v) for k, v in self.grads.items()})
+        return out

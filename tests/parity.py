@@ -1,0 +1,67 @@
+"""Shared driver of the GPU parity tests: same seeded inputs to the HIP library and to the
+CPU oracle, compared tensor by tensor.
+
+Tolerance (stated by the benchmark definition): per output tensor
+    max|gpu - oracle| / max|oracle|  <=  1e-5 for fp32,  2e-2 for bf16.
+For bf16 the oracle is fed the bf16-rounded inputs, so the comparison measures the kernels'
+arithmetic and the rounding of their outputs only.
+"""
+import numpy as np
+
+from paper_2409_06206_amd import synth
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+GRAD_NAMES = ("dx", "dw_qkv", "db_qkv", "dw_proj", "db_proj", "dtable")
+
+
+def rel_err(got, want):
+    denom = float(np.abs(want).max())
+    num = float(np.abs(np.asarray(got, dtype=np.float64) - want).max())
+    if denom == 0.0:
+        return num
+    return num / denom
+
+
+def make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime):
+    p = synth.layer_params(C, heads, groups, window, seed, regime)
+    x, dy = synth.activations(B, H, W, C, synth.ACT_SEED + seed - synth.LAYER_SEED0)
+    p = {k: synth.quantize(v, dtype) for k, v in p.items()}
+    return synth.quantize(x, dtype), synth.quantize(dy, dtype), p
+
+
+def oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade=True, backward=True):
+    args = (p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"])
+    kw = dict(heads=heads, groups=groups, window=window, shift=shift, cascade=cascade)
+    out = {"y": oracle.forward(x, *args, **kw)}
+    if backward:
+        out.update(zip(GRAD_NAMES, oracle.backward(x, dy, *args, **kw)))
+    return out
+
+
+def gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade=True, backward=True):
+    from paper_2409_06206_amd import gswa, runner
+    B, H, W, C = x.shape
+    flags = 0 if cascade else gswa.GSWA_NO_CASCADE
+    layer = runner.DeviceLayer(B, H, W, C, heads, groups, window, shift, dtype, flags)
+    layer.set_params(p)
+    layer.set_inputs(x, dy)
+    layer.forward(keep=backward)
+    if backward:
+        layer.backward()
+    import torch
+    torch.cuda.synchronize()
+    res = layer.results()
+    if not backward:
+        res = {"y": res["y"]}
+    return res, layer
+
+
+def check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, seed=synth.LAYER_SEED0,
+               regime="init", cascade=True, backward=True, tol_scale=1.0):
+    x, dy, p = make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime)
+    want = oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade, backward)
+    got, layer = gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade, backward)
+    errs = {k: rel_err(got[k], want[k]) for k in want}
+    bad = {k: e for k, e in errs.items() if not e <= TOL[dtype] * tol_scale}
+    assert not bad, f"relative max-norm error above {TOL[dtype] * tol_scale}: {bad} (all: {errs})"
+    return errs, layer

@@ -1,0 +1,76 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the header
+declares, validates arguments before touching the device, and reports buffer sizes."""
+import os
+import re
+
+import pytest
+
+from paper_2409_06206_amd import gswa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gswa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gswa_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = gswa.lib()
+    names = declared_functions()
+    assert set(names) == set(gswa.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+    assert gswa.gswa_version() >= 100
+
+
+def test_strerror_texts():
+    assert gswa.gswa_strerror(0) == "ok"
+    for code in (-1, -2, -3, -99):
+        assert gswa.gswa_strerror(code)
+
+
+GOOD = dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16")
+
+
+@pytest.mark.parametrize("change", [
+    dict(B=0), dict(H=12), dict(W=20), dict(C=62), dict(heads=4, groups=3), dict(groups=4),
+    dict(shift=8), dict(shift=-1), dict(window=0), dict(dtype=7), dict(flags=64),
+])
+def test_invalid_descriptors_are_rejected(change):
+    desc = gswa.make_desc(**{**GOOD, **change})
+    with pytest.raises(gswa.GswaError) as ei:
+        gswa.gswa_query_bytes(desc)
+    assert ei.value.status == gswa.GSWA_EINVAL
+
+
+def test_null_pointers_are_rejected_before_any_launch():
+    desc = gswa.make_desc(**GOOD)
+    fake = 0x1000  # never dereferenced: validation fails first
+    with pytest.raises(gswa.GswaError) as ei:
+        gswa.gswa_forward(desc, fake, fake, fake, fake, fake, fake, None, None, fake, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
+    with pytest.raises(gswa.GswaError) as ei:
+        gswa.gswa_forward(desc, fake, fake, fake, fake, fake, fake, fake, None, fake + 8, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL  # misaligned workspace
+    with pytest.raises(gswa.GswaError) as ei:
+        gswa.gswa_backward(desc, fake, fake, fake, fake, fake, fake, fake, None, fake, fake, fake,
+                           fake, fake, fake, fake, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
+
+
+@pytest.mark.parametrize("dtype,e", [("f32", 4), ("bf16", 2)])
+def test_saved_state_is_one_activation_and_scratch_shrinks_with_groups(dtype, e):
+    """The head-group loop bounds the scratch: one group's q|k|v (and its gradient)."""
+    T, C = 2 * 16 * 16, 60
+    prev = None
+    for G in (1, 2, 3, 6):
+        desc = gswa.make_desc(**{**GOOD, "groups": G, "dtype": dtype})
+        saved, fwd, bwd = gswa.gswa_query_bytes(desc)
+        assert saved == T * C * e
+        assert fwd == 3 * T * (C // G) * e and bwd == 2 * fwd
+        assert all(v % 256 == 0 for v in (saved, fwd, bwd))
+        if prev is not None:
+            assert saved + bwd < prev
+        prev = saved + bwd

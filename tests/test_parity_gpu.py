@@ -1,0 +1,125 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2409_06206_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# B, H, W, C, heads, groups, window, shift, dtype, regime
+SMALL = [
+    (1, 16, 16, 60, 6, 2, 8, 4, "f32", "init"),      # the fp32 parity configuration
+    (1, 16, 16, 60, 6, 2, 8, 4, "f32", "stress"),
+    (2, 16, 24, 60, 6, 1, 8, 0, "f32", "stress"),
+    (2, 24, 16, 60, 6, 3, 8, 3, "f32", "stress"),
+    (1, 16, 16, 60, 6, 6, 8, 7, "f32", "stress"),
+    (3, 8, 16, 12, 6, 2, 4, 1, "f32", "stress"),     # ragged: 12 channels, 16-token windows
+    (1, 8, 8, 6, 3, 3, 8, 5, "f32", "stress"),       # one window per image
+    (1, 7, 14, 6, 2, 1, 7, 3, "f32", "stress"),      # odd window side
+    (1, 16, 16, 180, 6, 1, 8, 4, "f32", "stress"),
+    (1, 16, 16, 180, 6, 3, 8, 4, "f32", "stress"),
+    (1, 32, 32, 180, 6, 2, 16, 8, "f32", "stress"),  # 256-token windows
+    (2, 16, 16, 60, 6, 1, 8, 0, "bf16", "init"),
+    (2, 16, 16, 60, 6, 2, 8, 4, "bf16", "init"),
+    (2, 16, 16, 60, 6, 2, 8, 4, "bf16", "stress"),
+    (2, 24, 16, 60, 6, 3, 8, 4, "bf16", "stress"),
+    (1, 16, 16, 60, 6, 6, 8, 4, "bf16", "stress"),
+    (1, 16, 24, 180, 6, 1, 8, 4, "bf16", "stress"),
+    (1, 16, 16, 180, 6, 2, 8, 0, "bf16", "stress"),
+    (1, 16, 16, 180, 6, 3, 8, 4, "bf16", "init"),
+    (1, 32, 32, 180, 6, 2, 16, 8, "bf16", "stress"),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,window,shift,dtype,regime", SMALL)
+def test_small_shapes_forward_backward(oracle, B, H, W, C, heads, groups, window, shift, dtype, regime):
+    _say("case", B, H, W, C, heads, groups, window, shift, dtype, regime)
+    errs, _ = parity.check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype,
+                                seed=synth.LAYER_SEED0 + 3, regime=regime)
+    _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_no_cascade_flag(oracle, dtype):
+    parity.check_case(oracle, 1, 16, 16, 60, 6, 3, 8, 4, dtype, regime="stress", cascade=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_inference_mode_matches_training_forward(oracle, dtype):
+    x, dy, p = parity.make_inputs(2, 16, 16, 60, 6, 2, 8, 4, dtype, synth.LAYER_SEED0, "stress")
+    a, _ = parity.gpu_results(x, dy, p, 6, 2, 8, 4, dtype, backward=True)
+    b, _ = parity.gpu_results(x, dy, p, 6, 2, 8, 4, dtype, backward=False)
+    assert np.array_equal(a["y"], b["y"])
+
+
+def test_accumulate_flag_adds_into_parameter_gradients(oracle):
+    import torch
+    from paper_2409_06206_amd import gswa, runner
+    x, dy, p = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, 4, "f32", synth.LAYER_SEED0, "stress")
+    layer = runner.DeviceLayer(1, 16, 16, 60, 6, 2, 8, 4, "f32", gswa.GSWA_ACCUM_WGRAD)
+    layer.set_params(p)
+    layer.set_inputs(x, dy)
+    for g in layer.grads.values():
+        g.fill_(1.0)
+    layer.forward()
+    layer.backward()
+    layer.backward()
+    torch.cuda.synchronize()
+    got = layer.results()
+    want = parity.oracle_results(oracle, x, dy, p, 6, 2, 8, 4)
+    for k in parity.GRAD_NAMES[1:]:
+        assert parity.rel_err(got[k], 2.0 * want[k] + 1.0) <= 1e-5, k
+    assert parity.rel_err(got["dx"], want["dx"]) <= 1e-5
+
+
+def test_repeated_calls_reuse_buffers(oracle):
+    """Two different inputs through the same buffers: the second result owes nothing to the first."""
+    import torch
+    from paper_2409_06206_amd import runner
+    x1, dy1, p = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, 4, "bf16", synth.LAYER_SEED0, "stress")
+    x2, dy2, _ = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, 4, "bf16", synth.LAYER_SEED0 + 9, "stress")
+    layer = runner.DeviceLayer(1, 16, 16, 60, 6, 2, 8, 4, "bf16")
+    layer.set_params(p)
+    for x, dy in ((x1, dy1), (x2, dy2)):
+        layer.set_inputs(x, dy)
+        layer.forward()
+        layer.backward()
+        torch.cuda.synchronize()
+        got = layer.results()
+        want = parity.oracle_results(oracle, x, dy, p, 6, 2, 8, 4)
+        for k in want:
+            assert parity.rel_err(got[k], want[k]) <= parity.TOL["bf16"], k
+
+
+FULL = [
+    # name, groups, layer index: full benchmark shapes, every element compared
+    ("c2", 1, 0), ("c2", 2, 1), ("c2", 3, 0), ("c2", 6, 1),
+    ("c3", 1, 1), ("c3", 2, 0), ("c3", 3, 1),
+    ("c4", 2, 1),
+]
+
+
+@pytest.mark.parametrize("name,groups,layer", FULL)
+def test_full_size_layers(oracle, name, groups, layer):
+    cfg = synth.CONFIGS[name]
+    _say("full", name, "G", groups, "layer", layer)
+    errs, _ = parity.check_case(oracle, cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
+                                cfg["window"], cfg["layers"][layer], cfg["dtype"],
+                                seed=synth.LAYER_SEED0 + layer)
+    _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("name", ["c5_m8", "c5_m16"])
+def test_large_image_inference(oracle, name):
+    cfg = synth.CONFIGS[name]
+    _say("full", name)
+    errs, _ = parity.check_case(oracle, cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"],
+                                cfg["groups"][0], cfg["window"], cfg["layers"][0], cfg["dtype"],
+                                backward=False)
+    _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
