@@ -52,7 +52,7 @@ def test_no_cascade_flag(oracle, dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_inference_mode_matches_training_forward(oracle, dtype):
-    x, dy, p = parity.make_inputs(2, 16, 16, 60, 6, 2, 8, 4, dtype, synth.LAYER_SEED0, "stress")
+    x, dy, p = parity.make_inputs(2, 16, 16, 60, 6, 2, 8, dtype, synth.LAYER_SEED0, "stress")
     a, _ = parity.gpu_results(x, dy, p, 6, 2, 8, 4, dtype, backward=True)
     b, _ = parity.gpu_results(x, dy, p, 6, 2, 8, 4, dtype, backward=False)
     assert np.array_equal(a["y"], b["y"])
@@ -61,7 +61,7 @@ def test_inference_mode_matches_training_forward(oracle, dtype):
 def test_accumulate_flag_adds_into_parameter_gradients(oracle):
     import torch
     from paper_2409_06206_amd import gswa, runner
-    x, dy, p = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, 4, "f32", synth.LAYER_SEED0, "stress")
+    x, dy, p = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, "f32", synth.LAYER_SEED0, "stress")
     layer = runner.DeviceLayer(1, 16, 16, 60, 6, 2, 8, 4, "f32", gswa.GSWA_ACCUM_WGRAD)
     layer.set_params(p)
     layer.set_inputs(x, dy)
@@ -82,8 +82,8 @@ def test_repeated_calls_reuse_buffers(oracle):
     """Two different inputs through the same buffers: the second result owes nothing to the first."""
     import torch
     from paper_2409_06206_amd import runner
-    x1, dy1, p = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, 4, "bf16", synth.LAYER_SEED0, "stress")
-    x2, dy2, _ = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, 4, "bf16", synth.LAYER_SEED0 + 9, "stress")
+    x1, dy1, p = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, "bf16", synth.LAYER_SEED0, "stress")
+    x2, dy2, _ = parity.make_inputs(1, 16, 16, 60, 6, 2, 8, "bf16", synth.LAYER_SEED0 + 9, "stress")
     layer = runner.DeviceLayer(1, 16, 16, 60, 6, 2, 8, 4, "bf16")
     layer.set_params(p)
     for x, dy in ((x1, dy1), (x2, dy2)):
