@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the GSWA hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch of the lightweight-SR
+shape: two consecutive GSWA layers (shift 0, then shift 4), forward and backward, bf16
+storage with fp32 accumulation, B=32, 64x64 map, C=60, 6 heads, window 8.  Inputs are
+resident in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--groups G] [--workload c2|c3]
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def build_case(name, groups):
+    import torch
+    from paper_2409_06206_amd import runner, synth
+    cfg = synth.CONFIGS[name]
+    x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
+    layers = []
+    for li, shift in enumerate(cfg["layers"]):
+        L = runner.DeviceLayer(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
+                               cfg["window"], shift, cfg["dtype"])
+        L.set_params(synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"],
+                                        synth.LAYER_SEED0 + li))
+        layers.append(L)
+    layers[0].set_inputs(x)
+    layers[-1].dy = runner.to_device(dy, cfg["dtype"])
+    # chain: layer l+1 reads layer l's y; layer l's dy is layer l+1's dx
+    for a, b in zip(layers[:-1], layers[1:]):
+        b.x = a.y
+        a.dy = b.dx
+    torch.cuda.synchronize()
+    return cfg, layers
+
+
+def step(layers):
+    for L in layers:
+        L.forward()
+    for L in reversed(layers):
+        L.backward()
+
+
+def time_steps(layers, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        step(layers)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(layers)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def profile_steps(layers, steps):
+    """Per-kernel average durations from HIP events recorded on the launch stream."""
+    import torch
+    from paper_2409_06206_amd import gswa
+    gswa.gswa_profile_enable(True)
+    gswa.gswa_profile_collect()
+    t0 = time.perf_counter()
+    per = {}
+    for _ in range(steps):
+        step(layers)
+        res, dropped = gswa.gswa_profile_collect()   # waits for the step's events
+        assert dropped == 0
+        for k, (ms, n) in res.items():
+            a = per.setdefault(k, [0.0, 0])
+            a[0] += ms
+            a[1] += n
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    gswa.gswa_profile_enable(False)
+    return {k: {"total_ms_per_step": v[0] / steps, "launches_per_step": v[1] / steps,
+                "avg_us": 1e3 * v[0] / v[1]} for k, v in per.items()}, wall
+
+
+def algorithmic_bytes_per_launch(kernel, cfg, groups):
+    """Bytes the METHOD has to move for the work one launch of `kernel` covers.
+
+    Per token the layer must read x and write y in forward (2*C*e), write one saved [T,C]
+    tensor, and in backward read x, dy and the saved tensor and write dx (4*C*e); weights are
+    negligible.  A kernel that covers one head group's share of a pass is charged 1/G of the
+    pass; a kernel covering a whole pass is charged all of it.
+    """
+    T = cfg["B"] * cfg["H"] * cfg["W"]
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    fwd = 3 * cfg["C"] * e * T
+    bwd = 4 * cfg["C"] * e * T
+    table = {
+        "qkv_linear": fwd / groups, "attn_fwd": fwd / groups, "proj_linear": fwd,
+        "attn_bwd": bwd / groups, "dO_linear": bwd / groups, "dx_linear": bwd / groups,
+        "qkv_wgrad": bwd / groups, "proj_wgrad": bwd,
+        "fused_fwd": fwd, "fused_bwd": bwd,
+    }
+    return table.get(kernel)
+
+
+def model_flops_per_token(cfg, groups):
+    C, N = cfg["C"], cfg["window"] ** 2
+    return 3 * (6 * C * C / groups + 2 * C * C) + 12 * N * C
+
+
+def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
+    """The CPU oracle, as it stands, on the same layer pair."""
+    from oracle import gswa_oracle
+    from paper_2409_06206_amd import synth
+    cfg = synth.CONFIGS[name]
+    x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
+    x = synth.quantize(x, cfg["dtype"])
+    dy = synth.quantize(dy, cfg["dtype"])
+    kw = dict(heads=cfg["heads"], groups=groups, window=cfg["window"])
+    params = []
+    for li in range(len(cfg["layers"])):
+        p = synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"], synth.LAYER_SEED0 + li)
+        p = {k: synth.quantize(v, cfg["dtype"]) for k, v in p.items()}
+        params.append((p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"]))
+    reps, t0 = 0, time.perf_counter()
+    while reps < max_reps and (reps == 0 or time.perf_counter() - t0 < min_seconds):
+        acts = [x]
+        for a, s in zip(params, cfg["layers"]):
+            acts.append(gswa_oracle.forward(acts[-1], *a, shift=s, **kw))
+        g = dy
+        for a, s, xin in zip(reversed(params), reversed(cfg["layers"]), reversed(acts[:-1])):
+            g = gswa_oracle.backward(xin, g, *a, shift=s, **kw)[0]
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    tokens = cfg["B"] * cfg["H"] * cfg["W"] * len(cfg["layers"])
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": gswa_oracle.threads(), "kind": "oracle",
+            "sample": f"full {name} layer pair (B={cfg['B']}), fwd+bwd, fp64 C oracle with OpenMP, "
+                      f"{reps} repetition(s), {dt:.2f} s each"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--groups", type=int, default=2)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-group-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2409_06206_amd import gswa
+    gswa.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    cfg, layers = build_case(args.workload, args.groups)
+    T = cfg["B"] * cfg["H"] * cfg["W"]
+    tokens_per_step = T * len(layers)
+    sec = time_steps(layers, args.steps, args.warmup)
+
+    prof, prof_wall = profile_steps(layers, min(args.steps, 20))
+    dom = max(prof, key=lambda k: prof[k]["total_ms_per_step"])
+    dom_bytes = algorithmic_bytes_per_launch(dom, cfg, args.groups)
+    dom_s = prof[dom]["avg_us"] * 1e-6
+    achieved = dom_bytes / dom_s / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_us": prof[dom]["avg_us"], "algorithmic_bytes_per_launch": dom_bytes}
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    step_bytes = 7 * cfg["C"] * e * tokens_per_step
+    step_flops = model_flops_per_token(cfg, args.groups) * tokens_per_step
+
+    sweep = {}
+    if not args.no_group_sweep:
+        for G in cfg["groups"]:
+            if G == args.groups:
+                ls, s_ = layers, sec
+            else:
+                _, ls = build_case(args.workload, G)
+                s_ = time_steps(ls, max(5, args.steps // 5), 3)
+            L0 = ls[0]
+            sweep[str(G)] = {"tokens_per_s": tokens_per_step / s_, "ms_per_step": 1e3 * s_,
+                             "saved_bytes_per_layer": L0.saved_bytes,
+                             "workspace_bytes": max(L0.fwd_ws_bytes, L0.bwd_ws_bytes),
+                             "peak_saved_act_bytes": L0.saved_bytes + max(L0.fwd_ws_bytes, L0.bwd_ws_bytes)}
+            if ls is not layers:
+                del ls
+                torch.cuda.empty_cache()
+
+    out = {
+        "metric": "GSWA fwd+bwd tokens/sec (1 GPU); % of HBM/MFMA roofline; peak saved-act bytes",
+        "value": tokens_per_step / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.workload}: GSWA layer pair (shift 0 then {cfg['layers'][-1]}) fwd+bwd, "
+                               f"B={cfg['B']} {cfg['H']}x{cfg['W']} C={cfg['C']} heads={cfg['heads']} "
+                               f"window={cfg['window']} groups={args.groups}",
+                   "groups": args.groups, "tokens_per_step": tokens_per_step},
+        "roofline": roofline,
+        "whole_step": {"algorithmic_GBps": step_bytes / sec / 1e9, "hbm_frac": step_bytes / sec / 1e9 / HBM_PEAK_GBS,
+                       "model_TFLOPs": step_flops / sec / 1e12,
+                       "mfma_frac": step_flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                       "profiled_ms_per_step": 1e3 * prof_wall},
+        "kernels": prof,
+        "peak_saved_act_bytes": layers[0].saved_bytes + max(layers[0].fwd_ws_bytes, layers[0].bwd_ws_bytes),
+        "by_groups": sweep,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload, args.groups)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -119,6 +119,20 @@ const char *gswa_last_hip_error(void);
 /* Library version: major*10000 + minor*100 + patch. */
 int gswa_version(void);
 
+/*
+ * Measurement aid, off by default; not part of the layer's arithmetic.  While enabled, every
+ * kernel the library enqueues is bracketed by two HIP events recorded on that kernel's stream
+ * (the events are created by the first gswa_profile_enable(1); at most 8192 launches are kept
+ * between two collects, later ones are counted in *dropped).  gswa_profile_collect waits for
+ * the recorded events, writes per-kernel totals into the HOST arrays total_ms[] and launches[]
+ * (gswa_profile_kernel_count() entries each, either may be NULL) and clears the record.
+ * Kernel ids are 0 .. count-1; gswa_profile_kernel_name(id) is static text.
+ */
+int gswa_profile_enable(int on);
+int gswa_profile_kernel_count(void);
+const char *gswa_profile_kernel_name(int id);
+int gswa_profile_collect(double *total_ms, long long *launches, long long *dropped);
+
 #ifdef __cplusplus
 }
 #endif

@@ -91,7 +91,7 @@ int forward_staged(const Geom &g, const Sizes &sz, const T *x, const T *w_qkv, c
         la.w = w_qkv + (size_t)grp * 3 * Cg * Cg; la.w_sn = Cg; la.w_sk = 1;
         la.bias = b_qkv + (size_t)grp * 3 * Cg;
         la.out = qkv; la.ldout = 3 * Cg;
-        la.rows = g.T; la.N = 3 * Cg; la.K = Cg;
+        la.rows = g.T; la.N = 3 * Cg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
         GSWA_HIP(launch_linear<T>(la, st));
         GSWA_HIP(launch_attn_fwd<T>(g, grp, qkv, table, attn, st));
     }
@@ -100,7 +100,7 @@ int forward_staged(const Geom &g, const Sizes &sz, const T *x, const T *w_qkv, c
     lp.w = w_proj; lp.w_sn = C; lp.w_sk = 1;
     lp.bias = b_proj;
     lp.out = y; lp.ldout = C;
-    lp.rows = g.T; lp.N = C; lp.K = C;
+    lp.rows = g.T; lp.N = C; lp.K = C; lp.prof_id = K_PROJ_LINEAR;
     GSWA_HIP(launch_linear<T>(lp, st));
     return GSWA_OK;
 }
@@ -126,7 +126,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     wp.dout = dy; wp.lddout = C;
     wp.a1 = attn; wp.lda1 = C;
     wp.dw = dw_proj; wp.db = db_proj;
-    wp.rows = g.T; wp.N = C; wp.K = C;
+    wp.rows = g.T; wp.N = C; wp.K = C; wp.prof_id = K_PROJ_WGRAD;
     GSWA_HIP(launch_wgrad<T>(wp, st));
 
     for (int grp = G - 1; grp >= 0; --grp) {
@@ -139,7 +139,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         la.w = wg; la.w_sn = Cg; la.w_sk = 1;
         la.bias = b_qkv + (size_t)grp * 3 * Cg;
         la.out = qkv; la.ldout = 3 * Cg;
-        la.rows = g.T; la.N = 3 * Cg; la.K = Cg;
+        la.rows = g.T; la.N = 3 * Cg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
         GSWA_HIP(launch_linear<T>(la, st));
         // dO_g = dy Wproj[:, slice g] (+ dF_{g+1}, which is dx[:, slice g+1]) into the v third of dqkv
         LinearArgs lo{};
@@ -147,7 +147,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         lo.w = w_proj + grp * Cg; lo.w_sn = 1; lo.w_sk = C;
         if (grp < G - 1 && g.cascade) { lo.add = dx + (grp + 1) * Cg; lo.ldadd = C; }
         lo.out = dqkv + 2 * Cg; lo.ldout = 3 * Cg;
-        lo.rows = g.T; lo.N = Cg; lo.K = C;
+        lo.rows = g.T; lo.N = Cg; lo.K = C; lo.prof_id = K_DO_LINEAR;
         GSWA_HIP(launch_linear<T>(lo, st));
         GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, dtable, st));
         // dF_g = dqkv Wqkv_g  ->  dx[:, slice g]
@@ -155,7 +155,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         lx.a1 = dqkv; lx.lda1 = 3 * Cg;
         lx.w = wg; lx.w_sn = 1; lx.w_sk = Cg;
         lx.out = dx + grp * Cg; lx.ldout = C;
-        lx.rows = g.T; lx.N = Cg; lx.K = 3 * Cg;
+        lx.rows = g.T; lx.N = Cg; lx.K = 3 * Cg; lx.prof_id = K_DX_LINEAR;
         GSWA_HIP(launch_linear<T>(lx, st));
         WgradArgs wq{};
         wq.dout = dqkv; wq.lddout = 3 * Cg;
@@ -163,7 +163,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         if (has_prev) { wq.a2 = attn + (grp - 1) * Cg; wq.lda2 = C; }
         wq.dw = dw_qkv + (size_t)grp * 3 * Cg * Cg;
         wq.db = db_qkv + (size_t)grp * 3 * Cg;
-        wq.rows = g.T; wq.N = 3 * Cg; wq.K = Cg;
+        wq.rows = g.T; wq.N = 3 * Cg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
         GSWA_HIP(launch_wgrad<T>(wq, st));
     }
     return GSWA_OK;

@@ -1,0 +1,32 @@
+// Optional per-kernel timing with HIP events (off by default).  When enabled, every kernel
+// the library enqueues is bracketed by two events recorded on the kernel's own stream;
+// gswa_profile_collect() turns them into per-kernel totals.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace gswa {
+
+enum KernelId {
+    K_FILL = 0,
+    K_QKV_LINEAR,   // q|k|v projection of one group (Eq. 6), cascade add fused (Eq. 8)
+    K_ATTN_FWD,     // attention core of one group
+    K_PROJ_LINEAR,  // output projection (Eq. 7)
+    K_PROJ_WGRAD,   // d w_proj, d b_proj
+    K_DO_LINEAR,    // dO of one group = dy Wproj slice (+ cascade gradient)
+    K_ATTN_BWD,     // adjoint of the attention core of one group
+    K_DX_LINEAR,    // dF of one group = dqkv Wqkv
+    K_QKV_WGRAD,    // d w_qkv, d b_qkv of one group
+    K_COUNT
+};
+
+const char *kernel_name(int id);
+
+// RAII bracket around one launch.
+struct KernelTimer {
+    KernelTimer(int id, hipStream_t s);
+    ~KernelTimer();
+    int slot;
+    hipStream_t stream;
+};
+
+} // namespace gswa

@@ -3,6 +3,7 @@
 // shapes they are built for.
 #pragma once
 #include "common.h"
+#include "profile.h"
 
 namespace gswa {
 
@@ -16,6 +17,7 @@ struct LinearArgs {
     const void *add; long ldadd;
     void *out; long ldout;
     long rows; int N, K;
+    int prof_id; // KernelId this launch is accounted under
 };
 
 // dw[n,k] += sum_t dout[t,n] * (a1[t,k] + a2[t,k]);  db[n] += sum_t dout[t,n]   (fp32 atomics)
@@ -25,6 +27,7 @@ struct WgradArgs {
     const void *a2; long lda2;
     float *dw; float *db;
     long rows; int N, K;
+    int prof_id;
 };
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);

@@ -88,6 +88,7 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
 {
     if (a.rows <= 0 || a.N <= 0) return hipSuccess;
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
+    KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(linear_kernel<T>, grid, dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
@@ -174,6 +175,7 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
     rps = (rps + 15) / 16 * 16;
     splits = (a.rows + rps - 1) / rps;
     dim3 grid(tn, tk, (unsigned)splits);
+    KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(wgrad_kernel<T>, grid, dim3(kThreads), 0, s, a, rps);
     return hipGetLastError();
 }
@@ -328,6 +330,7 @@ hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
+    KernelTimer kt(K_ATTN_FWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, table, attn_out, rs);
     return hipGetLastError();
 }
@@ -473,6 +476,7 @@ hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const 
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
+    KernelTimer kt(K_ATTN_BWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, dqkv, table, dtable, rs);
     return hipGetLastError();
 }
@@ -490,6 +494,7 @@ hipError_t launch_fill_zero(float *p, size_t n, hipStream_t s)
     if (n == 0) return hipSuccess;
     unsigned blocks = (unsigned)((n + 255) / 256);
     if (blocks > 1024) blocks = 1024;
+    KernelTimer kt(K_FILL, s);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, p, n);
     return hipGetLastError();
 }

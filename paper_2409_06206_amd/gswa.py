@@ -15,7 +15,8 @@ GSWA_F32, GSWA_BF16 = 0, 1
 GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD = 1, 2
 
 EXPORTS = ("gswa_query_bytes", "gswa_forward", "gswa_backward", "gswa_strerror",
-           "gswa_last_hip_error", "gswa_version")
+           "gswa_last_hip_error", "gswa_version", "gswa_profile_enable",
+           "gswa_profile_kernel_count", "gswa_profile_kernel_name", "gswa_profile_collect")
 
 
 class GswaError(RuntimeError):
@@ -58,6 +59,15 @@ def lib():
         L.gswa_strerror.restype = ctypes.c_char_p
         L.gswa_last_hip_error.restype = ctypes.c_char_p
         L.gswa_version.restype = ctypes.c_int
+        L.gswa_profile_enable.argtypes = [ctypes.c_int]
+        L.gswa_profile_enable.restype = ctypes.c_int
+        L.gswa_profile_kernel_count.restype = ctypes.c_int
+        L.gswa_profile_kernel_name.argtypes = [ctypes.c_int]
+        L.gswa_profile_kernel_name.restype = ctypes.c_char_p
+        L.gswa_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_longlong),
+                                           ctypes.POINTER(ctypes.c_longlong)]
+        L.gswa_profile_collect.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -121,3 +131,19 @@ def gswa_backward(desc, x, dy, w_qkv, b_qkv, w_proj, b_proj, bias_table, saved, 
                                _ptr(w_proj), _ptr(b_proj), _ptr(bias_table), _ptr(saved), _ptr(dx),
                                _ptr(dw_qkv), _ptr(db_qkv), _ptr(dw_proj), _ptr(db_proj),
                                _ptr(dbias_table), _ptr(ws), _stream(stream)))
+
+
+def gswa_profile_enable(on):
+    _check(lib().gswa_profile_enable(int(bool(on))))
+
+
+def gswa_profile_collect():
+    """{kernel name: (total_ms, launches)} since the last collect, plus the dropped count."""
+    L = lib()
+    n = L.gswa_profile_kernel_count()
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_longlong * n)()
+    dropped = ctypes.c_longlong()
+    _check(L.gswa_profile_collect(ms, cnt, ctypes.byref(dropped)))
+    out = {L.gswa_profile_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(n) if cnt[i]}
+    return out, dropped.value
