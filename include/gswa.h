@@ -59,7 +59,8 @@ enum { GSWA_F32 = 0, GSWA_BF16 = 1 };
 
 enum {
     GSWA_NO_CASCADE = 1u << 0, /* drop Eq. 8: every group sees only its own channel slice          */
-    GSWA_ACCUM_WGRAD = 1u << 1 /* backward adds into the five parameter gradients (no zero fill)   */
+    GSWA_ACCUM_WGRAD = 1u << 1, /* backward adds into the five parameter gradients (no zero fill)  */
+    GSWA_FORCE_STAGED = 1u << 2 /* use the one-kernel-per-step path even where a fused kernel exists */
 };
 
 typedef struct gswa_desc {
@@ -67,7 +68,7 @@ typedef struct gswa_desc {
     int32_t heads, groups; /* C % heads == 0, heads % groups == 0                              */
     int32_t window, shift; /* H % window == 0, W % window == 0, 0 <= shift < window            */
     int32_t dtype;         /* GSWA_F32 or GSWA_BF16: x, y, dy, dx, weights, biases, bias table */
-    uint32_t flags;        /* OR of GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD                          */
+    uint32_t flags;        /* OR of GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED       */
 } gswa_desc;
 
 /*
@@ -76,9 +77,11 @@ typedef struct gswa_desc {
  *   *saved_bytes   state forward leaves for backward: the concatenated group outputs
  *                  [B*H*W, C] in desc->dtype.  Scores and probabilities are never kept;
  *                  backward recomputes them.
- *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given: one group's q|k|v.
- *                  With saved == NULL the scratch must hold fwd_ws_bytes + saved_bytes.
+ *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given.  Staged path: one group's
+ *                  q|k|v, and with saved == NULL the scratch must hold fwd_ws_bytes + saved_bytes.
+ *                  Fused path: a fragment-ordered copy of the weights (a few tens of KB).
  *   *bwd_ws_bytes  scratch of gswa_backward: one group's q|k|v and its gradient.
+ * Which path serves a layer depends only on desc (shape, dtype, flags).
  * Any output pointer may be NULL.  All sizes are multiples of 256.
  */
 int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes,

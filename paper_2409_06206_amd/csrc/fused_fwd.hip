@@ -1,0 +1,393 @@
+// Fused GSWA forward: shift + partition + per-group QKV projection (Eq. 6) with the cascade add
+// (Eq. 8) + scores with relative bias and shift mask + softmax + PV + output projection (Eq. 7)
+// + window merge + reverse shift, one kernel, one pass over x and y.
+#include "fused.h"
+#include "mfma.h"
+
+namespace gswa {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------------------
+// Weight packing: rewrites w_qkv / w_proj / biases into the lane-major fragment order the
+// fused kernel copies into LDS.  Zero padding of head width (to 16*ET) and of the group
+// width (to 32*KS) happens here, so padded k-slots and rows contribute exact zeros.
+// ---------------------------------------------------------------------------------------
+template <class Cf>
+__global__ __launch_bounds__(256) void pack_fwd_kernel(const bf16_t *__restrict__ w_qkv,
+                                                       const bf16_t *__restrict__ b_qkv,
+                                                       const bf16_t *__restrict__ w_proj,
+                                                       const bf16_t *__restrict__ b_proj,
+                                                       uint8_t *__restrict__ pack)
+{
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET, KS = Cf::KS;
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+    uint16_t *wq = reinterpret_cast<uint16_t *>(pack + Cf::OFF_WQ);
+    uint16_t *wc = reinterpret_cast<uint16_t *>(pack + Cf::OFF_WC);
+    uint16_t *wp = reinterpret_cast<uint16_t *>(pack + Cf::OFF_WP);
+    float *bias = reinterpret_cast<float *>(pack + Cf::OFF_BIAS);
+
+    for (int i = gid; i < Cf::N_WQ * 64; i += stride) {
+        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
+        int f = i >> 6;
+        const int ks = f % KS; f /= KS;
+        const int et = f % ET; f /= ET;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const int e = 16 * et + l16;
+        for (int s = 0; s < 8; ++s) {
+            const int c = 32 * ks + 8 * q + s;
+            uint16_t v = 0;
+            if (e < D && c < CG) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c].bits;
+            wq[(size_t)i * 8 + s] = v;
+        }
+    }
+    for (int i = gid; i < Cf::N_WC * 64; i += stride) {
+        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
+        int f = i >> 6;
+        const int etp = f % ET; f /= ET;
+        const int hlp = f % HG; f /= HG;
+        const int et = f % ET; f /= ET;
+        const int t = f % 3; f /= 3;
+        const int hl = f % HG;
+        const int gi = f / HG + 1;
+        const int e = 16 * et + l16;
+        for (int j = 0; j < 4; ++j) {
+            const int ep = 16 * etp + 4 * q + j;
+            uint16_t v = 0;
+            if (e < D && ep < D) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + ep].bits;
+            wc[(size_t)i * 4 + j] = v;
+        }
+    }
+    for (int i = gid; i < Cf::N_WP * 64; i += stride) {
+        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
+        int f = i >> 6;
+        const int et = f % ET; f /= ET;
+        const int hd = f % HEADS;
+        const int ot = f / HEADS;
+        const int o = 16 * ot + l16;
+        for (int j = 0; j < 4; ++j) {
+            const int e = 16 * et + 4 * q + j;
+            uint16_t v = 0;
+            if (o < C && e < D) v = w_proj[(size_t)o * C + hd * D + e].bits;
+            wp[(size_t)i * 4 + j] = v;
+        }
+    }
+    for (int i = gid; i < 4 * C; i += stride) bias[i] = i < 3 * C ? to_f32(b_qkv[i]) : to_f32(b_proj[i - 3 * C]);
+}
+
+// fragment ids inside the packed arrays
+template <class Cf> __device__ __forceinline__ constexpr int fq(int hd, int t, int et, int ks)
+{
+    return ((hd * 3 + t) * Cf::ET + et) * Cf::KS + ks;
+}
+template <class Cf> __device__ __forceinline__ constexpr int fc(int gi, int hl, int t, int et, int hlp, int etp)
+{
+    return (((((gi - 1) * Cf::HG + hl) * 3 + t) * Cf::ET + et) * Cf::HG + hlp) * Cf::ET + etp;
+}
+
+template <class Cf>
+__global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                        const uint8_t *__restrict__ pack,
+                                                        const bf16_t *__restrict__ table,
+                                                        bf16_t *__restrict__ y, bf16_t *__restrict__ attn)
+{
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
+    constexpr int ET = Cf::ET, KS = Cf::KS, OT = Cf::OT, VT_LD = Cf::VT_LD;
+    constexpr int M = 8, NTBL = (2 * M - 1) * (2 * M - 1);
+    static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0, "dword-granular loads and stores");
+    static_assert((size_t)NTBL * HEADS * 2 <= Cf::K_BYTES, "table staging aliases the K buffers");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint4 *wq = reinterpret_cast<const uint4 *>(lds + Cf::OFF_WQ);
+    const uint2 *wc = reinterpret_cast<const uint2 *>(lds + Cf::OFF_WC);
+    const uint2 *wp = reinterpret_cast<const uint2 *>(lds + Cf::OFF_WP);
+    const float *bqkv = reinterpret_cast<const float *>(lds + Cf::OFF_BIAS);
+    const float *bproj = bqkv + 3 * C;
+    uint2 *kbuf = reinterpret_cast<uint2 *>(lds + Cf::OFF_K);
+    uint16_t *vt = reinterpret_cast<uint16_t *>(lds + Cf::OFF_VT);
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l16 = lane & 15, q = lane >> 4;
+
+    // ---- set-up: weights into LDS, bias table into registers in score-fragment order ----
+    for (int i = tid; i < (int)(Cf::PACK_BYTES / 16); i += 256)
+        reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack)[i];
+    uint16_t *tstage = reinterpret_cast<uint16_t *>(kbuf);
+    for (int i = tid; i < NTBL * HEADS; i += 256) tstage[i] = table[i].bits;
+    __syncthreads();
+
+    // this lane's token inside the window: query column of every score tile it holds
+    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
+    uint32_t bias_frag[HEADS][8];
+#pragma unroll
+    for (int hd = 0; hd < HEADS; ++hd)
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+                uint32_t pr = 0;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int m = 16 * kt + 4 * q + 2 * jp + h;
+                    const int rm = m >> 3, cm = m & 7;
+                    const int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
+                    pr |= (uint32_t)tstage[idx * HEADS + hd] << (16 * h);
+                }
+                bias_frag[hd][kt * 2 + jp] = pr;
+            }
+    // shift mask: a key is masked for this lane's query when their wrap flags differ
+    const int s = g.shift;
+    bool rmask[4], cmask[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) rmask[kt] = (rn >= M - s) != ((2 * kt + (q >> 1)) >= M - s);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
+    __syncthreads();
+
+    const float scale = 1.0f / sqrtf((float)D);
+    const int per_img = g.nwi * g.nwj;
+    int buf = 0;
+
+    for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+        const int b = win / per_img;
+        const int wr = win - b * per_img;
+        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
+        int si = wi * M + rn + s, sj = wj * M + cn + s;
+        if (si >= g.H) si -= g.H;
+        if (sj >= g.W) sj -= g.W;
+        const long tok = ((long)b * g.H + si) * g.W + sj;
+        const bool lastrow = s > 0 && wi == g.nwi - 1, lastcol = s > 0 && wj == g.nwj - 1;
+
+        // x row of this lane's token as B/A operands: k-slot 8q+s of step ks <-> channel 32ks+8q+s
+        const uint32_t *xrow = reinterpret_cast<const uint32_t *>(x + tok * C);
+        uint4 xf[G][KS];
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                uint32_t dwv[4];
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) {
+                    const int c = 32 * ks + 8 * q + 2 * dw;
+                    dwv[dw] = c < CG ? xrow[(gi * CG + c) >> 1] : 0u;
+                }
+                xf[gi][ks] = make_uint4(dwv[0], dwv[1], dwv[2], dwv[3]);
+            }
+
+        uint2 Ob[HEADS][ET];
+#pragma unroll
+        for (int hd = 0; hd < HEADS; ++hd) {
+            const int gi = hd / HG, hl = hd % HG;
+            // ---- Q^T, K^T (rows = head features) and V (rows = tokens) of this wave's tokens ----
+            f32x4 qT[ET], kT[ET], vv[ET];
+#pragma unroll
+            for (int et = 0; et < ET; ++et) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int e = 16 * et + 4 * q + j;
+                    qT[et][j] = e < D ? bqkv[gi * 3 * CG + hl * D + e] : 0.f;
+                    kT[et][j] = e < D ? bqkv[gi * 3 * CG + CG + hl * D + e] : 0.f;
+                }
+                const int ev = 16 * et + l16;
+                const float bv = ev < D ? bqkv[gi * 3 * CG + 2 * CG + hl * D + ev] : 0.f;
+                vv[et] = f32x4{bv, bv, bv, bv};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    qT[et] = mma32(wq[fq<Cf>(hd, 0, et, ks) * 64 + lane], xf[gi][ks], qT[et]);
+                    kT[et] = mma32(wq[fq<Cf>(hd, 1, et, ks) * 64 + lane], xf[gi][ks], kT[et]);
+                    vv[et] = mma32(xf[gi][ks], wq[fq<Cf>(hd, 2, et, ks) * 64 + lane], vv[et]);
+                }
+                if (gi > 0 && g.cascade) {
+#pragma unroll
+                    for (int hlp = 0; hlp < HG; ++hlp)
+#pragma unroll
+                        for (int etp = 0; etp < ET; ++etp) {
+                            const uint2 prev = Ob[(gi > 0 ? gi - 1 : 0) * HG + hlp][etp];
+                            qT[et] = mma16(wc[fc<Cf>(gi > 0 ? gi : 1, hl, 0, et, hlp, etp) * 64 + lane], prev, qT[et]);
+                            kT[et] = mma16(wc[fc<Cf>(gi > 0 ? gi : 1, hl, 1, et, hlp, etp) * 64 + lane], prev, kT[et]);
+                            vv[et] = mma16(prev, wc[fc<Cf>(gi > 0 ? gi : 1, hl, 2, et, hlp, etp) * 64 + lane], vv[et]);
+                        }
+                }
+            }
+            // ---- K and V of all 64 tokens to the other waves ----
+            uint2 Qb[ET];
+#pragma unroll
+            for (int et = 0; et < ET; ++et) {
+                Qb[et] = pack_bf16x4(qT[et]);
+                kbuf[((buf * 4 + wv) * ET + et) * 64 + lane] = pack_bf16x4(kT[et]);
+                *reinterpret_cast<uint2 *>(vt + ((buf * ET + et) * 16 + l16) * VT_LD + 16 * wv + 4 * q) =
+                    pack_bf16x4(vv[et]);
+            }
+            __syncthreads();
+
+            // ---- S^T tiles: rows = keys 16kt+4q+j, column = this lane's query ----
+            f32x4 st[4];
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int et = 0; et < ET; ++et)
+                    st[kt] = mma16(kbuf[((buf * 4 + kt) * ET + et) * 64 + lane], Qb[et], st[kt]);
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t pr = bias_frag[hd][kt * 2 + (j >> 1)];
+                    const float bv = (j & 1) ? bf16_hi(pr) : bf16_lo(pr);
+                    st[kt][j] = fmaf(st[kt][j], scale, bv);
+                }
+            if (lastrow || lastcol) {
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if ((lastrow && rmask[kt]) || (lastcol && cmask[j])) st[kt][j] += -100.0f;
+            }
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) mx = fmaxf(mx, st[kt][j]);
+            mx = qgroup_max(mx);
+            const float mxl = mx * kLog2e;
+            float sum = 0.f;
+            uint2 Pb[4];
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(st[kt][j], kLog2e, -mxl));
+                    st[kt][j] = p;
+                    sum += p;
+                }
+                Pb[kt] = pack_bf16x4(st[kt]);
+            }
+            sum = qgroup_sum(sum);
+            const float inv = 1.0f / sum;
+
+            // ---- O^T = V^T P^T: rows = head features, column = this lane's token ----
+#pragma unroll
+            for (int et = 0; et < ET; ++et) {
+                f32x4 oT = f32x4{0.f, 0.f, 0.f, 0.f};
+                const uint16_t *vrow = vt + ((buf * ET + et) * 16 + l16) * VT_LD + 4 * q;
+#pragma unroll
+                for (int kp = 0; kp < 2; ++kp) {
+                    const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp);
+                    const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp + 16);
+                    oT = mma32(make_uint4(a0.x, a0.y, a1.x, a1.y),
+                               make_uint4(Pb[2 * kp].x, Pb[2 * kp].y, Pb[2 * kp + 1].x, Pb[2 * kp + 1].y), oT);
+                }
+                oT *= inv;
+                Ob[hd][et] = pack_bf16x4(oT);
+                if (attn) {
+                    const int e0 = 16 * et + 4 * q;
+                    uint32_t *dst = reinterpret_cast<uint32_t *>(attn + tok * C + hd * D + e0);
+                    if (e0 < D) dst[0] = Ob[hd][et].x;
+                    if (e0 + 2 < D) dst[1] = Ob[hd][et].y;
+                }
+            }
+            buf ^= 1;
+        }
+
+        // ---- Y^T = Wproj A^T + b: rows = output channels, column = this lane's token ----
+#pragma unroll
+        for (int ot = 0; ot < OT; ++ot) {
+            f32x4 acc;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int o = 16 * ot + 4 * q + j;
+                acc[j] = o < C ? bproj[o] : 0.f;
+            }
+#pragma unroll
+            for (int hd = 0; hd < HEADS; ++hd)
+#pragma unroll
+                for (int et = 0; et < ET; ++et)
+                    acc = mma16(wp[((ot * HEADS + hd) * ET + et) * 64 + lane], Ob[hd][et], acc);
+            const int o0 = 16 * ot + 4 * q;
+            if (o0 < C) *reinterpret_cast<uint2 *>(y + tok * C + o0) = pack_bf16x4(acc);
+        }
+    }
+}
+
+int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+template <class Cf>
+hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
+                   const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table, bf16_t *y,
+                   bf16_t *attn, void *ws, hipStream_t s)
+{
+    uint8_t *pack = static_cast<uint8_t *>(ws);
+    {
+        KernelTimer kt(K_PACK_FWD, s);
+        hipLaunchKernelGGL(pack_fwd_kernel<Cf>, dim3(64), dim3(256), 0, s, w_qkv, b_qkv, w_proj, b_proj, pack);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    auto kern = fused_fwd_kernel<Cf>;
+    static bool attr_done = false;
+    if (!attr_done && Cf::FWD_LDS_BYTES > 64 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::FWD_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    int grid = 2 * device_cu_count();
+    if (grid > g.nW) grid = g.nW;
+    {
+        KernelTimer kt(K_FUSED_FWD, s);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), Cf::FWD_LDS_BYTES, s, g, x, pack, table, y, attn);
+    }
+    return hipGetLastError();
+}
+
+// instantiation table
+#define GSWA_FUSED_SHAPES(X) X(60, 6, 1) X(60, 6, 2) X(60, 6, 3) X(60, 6, 6)
+
+} // namespace
+
+bool fused_fwd_supported(const Geom &g)
+{
+    if (g.M != 8) return false;
+#define X(C_, H_, G_) \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) return true;
+    GSWA_FUSED_SHAPES(X)
+#undef X
+    return false;
+}
+
+size_t fused_fwd_ws_bytes(const Geom &g)
+{
+#define X(C_, H_, G_) \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) return FusedCfg<C_, H_, G_>::PACK_BYTES;
+    GSWA_FUSED_SHAPES(X)
+#undef X
+    return 0;
+}
+
+hipError_t launch_fused_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
+                            const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table,
+                            bf16_t *y, bf16_t *attn_out, void *ws, hipStream_t s)
+{
+#define X(C_, H_, G_)                                                  \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_)                  \
+        return run_fwd<FusedCfg<C_, H_, G_>>(g, x, w_qkv, b_qkv, w_proj, b_proj, table, y, attn_out, ws, s);
+    GSWA_FUSED_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+} // namespace gswa

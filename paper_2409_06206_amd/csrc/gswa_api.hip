@@ -3,6 +3,7 @@
 #include "../../include/gswa.h"
 #include "common.h"
 #include "staged_kernels.h"
+#include "fused.h"
 
 #include <string>
 
@@ -37,7 +38,7 @@ int make_geom(const gswa_desc *d, Geom *g)
     if (d->H % d->window || d->W % d->window) return GSWA_EINVAL;
     if (d->shift < 0 || d->shift >= d->window) return GSWA_EINVAL;
     if (d->dtype != GSWA_F32 && d->dtype != GSWA_BF16) return GSWA_EINVAL;
-    if (d->flags & ~(uint32_t)(GSWA_NO_CASCADE | GSWA_ACCUM_WGRAD)) return GSWA_EINVAL;
+    if (d->flags & ~(uint32_t)(GSWA_NO_CASCADE | GSWA_ACCUM_WGRAD | GSWA_FORCE_STAGED)) return GSWA_EINVAL;
     const long T = (long)d->B * d->H * d->W;
     const long nW = T / ((long)d->window * d->window);
     if (T * 3 * d->C >= (1L << 40) || nW > 0x7fffffffL) return GSWA_EUNSUPPORTED;
@@ -63,7 +64,13 @@ size_t elem_size(const gswa_desc *d) { return d->dtype == GSWA_F32 ? 4 : 2; }
 
 struct Sizes {
     size_t saved, qkv, fwd_ws, bwd_ws;
+    bool fused_fwd;
 };
+
+bool use_fused_fwd(const gswa_desc *d, const Geom &g)
+{
+    return d->dtype == GSWA_BF16 && !(d->flags & GSWA_FORCE_STAGED) && fused_fwd_supported(g);
+}
 
 Sizes make_sizes(const gswa_desc *d, const Geom &g)
 {
@@ -73,6 +80,8 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.qkv = align256((size_t)g.T * 3 * g.Cg * e);
     s.fwd_ws = s.qkv;
     s.bwd_ws = 2 * s.qkv;
+    s.fused_fwd = use_fused_fwd(d, g);
+    if (s.fused_fwd) s.fwd_ws = align256(fused_fwd_ws_bytes(g));
     return s;
 }
 
@@ -201,6 +210,12 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
         return forward_staged<float>(g, s, (const float *)x, (const float *)w_qkv, (const float *)b_qkv,
                                      (const float *)w_proj, (const float *)b_proj,
                                      (const float *)bias_table, (float *)y, (float *)saved, (char *)ws, st);
+    if (s.fused_fwd) {
+        hipError_t e = launch_fused_fwd(g, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
+                                        (const bf16_t *)w_proj, (const bf16_t *)b_proj,
+                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, ws, st);
+        return e == hipSuccess ? GSWA_OK : hip_fail(e);
+    }
     return forward_staged<bf16_t>(g, s, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
                                   (const bf16_t *)w_proj, (const bf16_t *)b_proj,
                                   (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, (char *)ws, st);

@@ -16,6 +16,8 @@ enum KernelId {
     K_ATTN_BWD,     // adjoint of the attention core of one group
     K_DX_LINEAR,    // dF of one group = dqkv Wqkv
     K_QKV_WGRAD,    // d w_qkv, d b_qkv of one group
+    K_PACK_FWD,     // weights into MFMA fragment order for the fused forward
+    K_FUSED_FWD,    // whole forward layer, one launch
     K_COUNT
 };
 

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libgswa.so")
 
 GSWA_OK, GSWA_EINVAL, GSWA_EUNSUPPORTED, GSWA_EHIP = 0, -1, -2, -3
 GSWA_F32, GSWA_BF16 = 0, 1
-GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD = 1, 2
+GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED = 1, 2, 4
 
 EXPORTS = ("gswa_query_bytes", "gswa_forward", "gswa_backward", "gswa_strerror",
            "gswa_last_hip_error", "gswa_version", "gswa_profile_enable",

@@ -38,10 +38,11 @@ def oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade=True,
     return out
 
 
-def gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade=True, backward=True):
+def gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade=True, backward=True,
+                extra_flags=0):
     from paper_2409_06206_amd import gswa, runner
     B, H, W, C = x.shape
-    flags = 0 if cascade else gswa.GSWA_NO_CASCADE
+    flags = (0 if cascade else gswa.GSWA_NO_CASCADE) | extra_flags
     layer = runner.DeviceLayer(B, H, W, C, heads, groups, window, shift, dtype, flags)
     layer.set_params(p)
     layer.set_inputs(x, dy)
@@ -57,10 +58,11 @@ def gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade=True, bac
 
 
 def check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, seed=synth.LAYER_SEED0,
-               regime="init", cascade=True, backward=True, tol_scale=1.0):
+               regime="init", cascade=True, backward=True, tol_scale=1.0, extra_flags=0):
     x, dy, p = make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime)
     want = oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade, backward)
-    got, layer = gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade, backward)
+    got, layer = gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade, backward,
+                             extra_flags)
     errs = {k: rel_err(got[k], want[k]) for k in want}
     bad = {k: e for k, e in errs.items() if not e <= TOL[dtype] * tol_scale}
     assert not bad, f"relative max-norm error above {TOL[dtype] * tol_scale}: {bad} (all: {errs})"

@@ -45,6 +45,14 @@ def test_small_shapes_forward_backward(oracle, B, H, W, C, heads, groups, window
     _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
 
 
+@pytest.mark.parametrize("groups,shift", [(1, 0), (2, 4), (3, 5), (6, 4)])
+def test_forced_staged_path_bf16(oracle, groups, shift):
+    """The one-kernel-per-step path stays correct where a fused kernel would normally run."""
+    from paper_2409_06206_amd import gswa
+    parity.check_case(oracle, 2, 16, 24, 60, 6, groups, 8, shift, "bf16", regime="stress",
+                      extra_flags=gswa.GSWA_FORCE_STAGED)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_no_cascade_flag(oracle, dtype):
     parity.check_case(oracle, 1, 16, 16, 60, 6, 3, 8, 4, dtype, regime="stress", cascade=False)
