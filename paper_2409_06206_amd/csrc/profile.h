@@ -18,6 +18,9 @@ enum KernelId {
     K_QKV_WGRAD,    // d w_qkv, d b_qkv of one group
     K_PACK_FWD,     // weights into MFMA fragment order for the fused forward
     K_FUSED_FWD,    // whole forward layer, one launch
+    K_PACK_BWD,     // weights into MFMA fragment order for the fused backward
+    K_FUSED_BWD,    // dx, d(q|k|v) and bias-table partials, one launch
+    K_REDUCE,       // per-workgroup partial sums -> parameter gradients
     K_COUNT
 };
 

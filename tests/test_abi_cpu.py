@@ -62,11 +62,11 @@ def test_null_pointers_are_rejected_before_any_launch():
 
 @pytest.mark.parametrize("dtype,e", [("f32", 4), ("bf16", 2)])
 def test_saved_state_is_one_activation_and_scratch_shrinks_with_groups(dtype, e):
-    """The head-group loop bounds the scratch: one group's q|k|v (and its gradient)."""
+    """Staged path: the head-group loop bounds the scratch: one group's q|k|v (and its gradient)."""
     T, C = 2 * 16 * 16, 60
     prev = None
     for G in (1, 2, 3, 6):
-        desc = gswa.make_desc(**{**GOOD, "groups": G, "dtype": dtype})
+        desc = gswa.make_desc(**{**GOOD, "groups": G, "dtype": dtype, "flags": gswa.GSWA_FORCE_STAGED})
         saved, fwd, bwd = gswa.gswa_query_bytes(desc)
         assert saved == T * C * e
         assert fwd == 3 * T * (C // G) * e and bwd == 2 * fwd
@@ -74,3 +74,14 @@ def test_saved_state_is_one_activation_and_scratch_shrinks_with_groups(dtype, e)
         if prev is not None:
             assert saved + bwd < prev
         prev = saved + bwd
+
+
+def test_fused_path_sizes():
+    """Fused bf16 path: the saved state is still one [T, C] activation; forward scratch is only
+    the packed weights."""
+    T, C = 2 * 16 * 16, 60
+    for G in (1, 2, 3, 6):
+        saved, fwd, bwd = gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "groups": G}))
+        assert saved == T * C * 2
+        assert 0 < fwd <= 64 * 1024
+        assert bwd > 0 and bwd % 256 == 0
