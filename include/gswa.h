@@ -80,7 +80,9 @@ typedef struct gswa_desc {
  *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given.  Staged path: one group's
  *                  q|k|v, and with saved == NULL the scratch must hold fwd_ws_bytes + saved_bytes.
  *                  Fused path: a fragment-ordered copy of the weights (a few tens of KB).
- *   *bwd_ws_bytes  scratch of gswa_backward: one group's q|k|v and its gradient.
+ *   *bwd_ws_bytes  scratch of gswa_backward.  Staged path: one group's q|k|v and its gradient.
+ *                  Fused path: packed weights plus one partial parameter-gradient vector per
+ *                  workgroup (one workgroup per compute unit).
  * Which path serves a layer depends only on desc (shape, dtype, flags).
  * Any output pointer may be NULL.  All sizes are multiples of 256.
  */
@@ -103,8 +105,9 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
  * written by gswa_forward on the same desc, x and parameters.
  *   dx                    [B,H,W,C] in desc->dtype, overwritten.
  *   dw_qkv ... dbias_table fp32, overwritten, or added into with GSWA_ACCUM_WGRAD.
- *                         They are reduced with fp32 atomics: the summation order, hence the
- *                         last bits, can differ between runs.
+ *                         The fused path sums per-workgroup partials in a fixed order (same
+ *                         bits every run); the staged path reduces with fp32 atomics, so its
+ *                         last bits can differ between runs.
  * dx may not overlap x, dy or saved.
  */
 int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const void *w_qkv,

@@ -47,14 +47,15 @@ hipError_t launch_fused_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv,
                             bf16_t *y, bf16_t *attn_out, void *ws, hipStream_t s);
 
 bool fused_bwd_supported(const Geom &g);
-// Scratch of the fused backward: packed weights + per-workgroup bias-table partials.
+// Scratch of the fused backward: packed weights + per-workgroup partial parameter gradients.
 size_t fused_bwd_ws_bytes(const Geom &g);
 
-// dx, dqkv [T, 3C] (per token: group-major, then q|k|v, then head) and dtable from x, dy and
-// the saved group outputs.  dtable is overwritten unless `accumulate`.
+// dx and the five parameter gradients from x, dy and the saved group outputs.  The parameter
+// gradients are summed over per-workgroup partials in a fixed order (run-to-run identical) and
+// overwrite their outputs unless `accumulate`.
 hipError_t launch_fused_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                             const bf16_t *w_qkv, const bf16_t *b_qkv, const bf16_t *w_proj,
-                            const bf16_t *table, bf16_t *dx, bf16_t *dqkv, float *dtable, int accumulate,
-                            void *ws, hipStream_t s);
+                            const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
+                            float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s);
 
 } // namespace gswa

@@ -1,6 +1,7 @@
 // Fused GSWA backward for 8x8 windows, bf16 storage: one kernel recomputes q, k, v, the scores
-// and the softmax of every head from x and the saved group outputs, and produces dx, the
-// gradients of q|k|v and per-workgroup partial sums of the bias-table gradient.
+// and the softmax of every head from x and the saved group outputs, and produces dx and
+// per-workgroup partial sums of all five parameter gradients (accumulated in registers over the
+// windows a workgroup owns); a second small kernel adds the partials in a fixed order.
 //
 // Per window, wave w owns tokens 16w..16w+15 both as queries and as keys.  Notation for a
 // matrix X[tokens x features] held as an MFMA result tile (see mfma.h):
@@ -23,31 +24,50 @@ template <class Cf> struct BwdCfg {
     static constexpr int ET = Cf::ET, KS = Cf::KS;
     static constexpr int KSC = (C + 31) / 32; // K=32 steps over all C channels of dy
     static constexpr int NTBL = 15 * 15;
+    static constexpr int TBL_N = NTBL * HEADS;
+    // weight-gradient tiling: 16x16 tiles, one spare column (index CG resp. C) carries the bias sums
+    static constexpr int CT = CG / 16 + 1;          // column tiles of d w_qkv of one head
+    static constexpr int NT = 3 * ET * CT;          // tiles of one head's d w_qkv rows
+    static constexpr int KT = (NT + 3) / 4;         // tiles per wave
+    static constexpr int OTP = (C + 15) / 16, CTP = C / 16 + 1;
+    static constexpr int NTP = OTP * CTP, KTP = (NTP + 3) / 4;
     // weight fragments (lane-major)
-    static constexpr int N_WQ = Cf::N_WQ;                     // recompute, K=32: (hd,t,et,ks)
-    static constexpr int N_WC = Cf::N_WC;                     // recompute on cascade input, K=16
-    static constexpr int N_WPT = HEADS * ET * KSC;            // Wproj^T, K=32: (hd,et,ks)
-    static constexpr int N_WQT = HEADS * 3 * ET * HG * ET;    // Wqkv^T, K=16: (hd,t,et,hlp,etp)
+    static constexpr int N_WQ = Cf::N_WQ;                  // Wqkv, K=32: (hd,t,et,ks)
+    static constexpr int N_WPT = HEADS * ET * KSC;         // Wproj^T, K=32: (hd,et,ks)
+    static constexpr int N_WQT = HEADS * 3 * ET * HG * ET; // Wqkv^T, K=16: (hd,t,et,hlp,etp)
     static constexpr size_t OFF_WQ = 0;
-    static constexpr size_t OFF_WC = OFF_WQ + (size_t)N_WQ * 1024;
-    static constexpr size_t OFF_WPT = OFF_WC + (size_t)N_WC * 512;
+    static constexpr size_t OFF_WPT = OFF_WQ + (size_t)N_WQ * 1024;
     static constexpr size_t OFF_WQT = OFF_WPT + (size_t)N_WPT * 1024;
-    static constexpr size_t OFF_BIAS = OFF_WQT + (size_t)N_WQT * 512; // fp32 b_qkv [3C]
-    static constexpr size_t PACK_BYTES = OFF_BIAS + (size_t)16 * C;  // (b_proj slot unused)
-    // exchange buffers
-    static constexpr int LD = 68;                              // row pitch (bf16) of [feature][64 tokens] and [key][64 queries]
-    static constexpr size_t SZ_FRAG = (size_t)4 * ET * 64 * 8; // packed tiles of all 4 waves
+    static constexpr size_t OFF_BIAS = OFF_WQT + (size_t)N_WQT * 512; // fp32 b_qkv [3C] (+C unused)
+    static constexpr size_t PACK_BYTES = OFF_BIAS + (size_t)16 * C;
+    // LDS beyond the packed weights
+    static constexpr int LD = 68; // pitch (bf16) of rows read 4 at a time
+    static constexpr int LW = 72; // pitch (bf16) of rows read 8 at a time
+    static constexpr size_t SZ_FRAG = (size_t)4 * ET * 64 * 8;
     static constexpr size_t SZ_ROWS = (size_t)16 * ET * LD * 2;
-    static constexpr size_t SZ_SQ = (size_t)64 * LD * 2;
-    static constexpr size_t OFF_KB = PACK_BYTES;               // K, T-form packed tiles
-    static constexpr size_t OFF_VB = OFF_KB + SZ_FRAG;         // V, T-form packed tiles
+    static constexpr size_t SZ_SQ = (size_t)64 * LW * 2; // P / dS [key][query]; also dY^T / A^T rows
+    static constexpr size_t OFF_TBLF = PACK_BYTES;             // fp32 bias table [225][HEADS]
+    static constexpr size_t OFF_KB = OFF_TBLF + (((size_t)TBL_N * 4 + 15) & ~size_t(15));
+    static constexpr size_t OFF_VB = OFF_KB + SZ_FRAG;
     static constexpr size_t OFF_KT = OFF_VB + SZ_FRAG;         // K^T rows [e][key]
     static constexpr size_t OFF_QT = OFF_KT + SZ_ROWS;         // Q^T rows [e][query], double buffered
     static constexpr size_t OFF_DOT = OFF_QT + 2 * SZ_ROWS;    // dO^T rows [e][query], double buffered
-    static constexpr size_t OFF_P = OFF_DOT + 2 * SZ_ROWS;     // P  [key][query]
-    static constexpr size_t OFF_DS = OFF_P + SZ_SQ;            // dS [key][query]
-    static constexpr size_t LDS_BYTES = OFF_DS + SZ_SQ;
-    static constexpr int TBL_N = NTBL * HEADS;
+    static constexpr size_t OFF_P = OFF_DOT + 2 * SZ_ROWS;
+    static constexpr size_t OFF_DS = OFF_P + SZ_SQ;
+    static constexpr size_t OFF_DQKV = OFF_DS + SZ_SQ;         // d(q|k|v)^T rows [(t,e)][token]
+    static constexpr size_t SZ_DQKV = (size_t)3 * ET * 16 * LW * 2;
+    static constexpr size_t OFF_F = OFF_DQKV + SZ_DQKV;        // F^T rows [c][token] of the current group
+    static constexpr size_t SZ_F = (size_t)16 * CT * LW * 2;
+    static constexpr size_t LDS_BYTES = OFF_F + SZ_F;
+    // per-workgroup partial sums, in parameter order
+    static constexpr int P_DWQ = 0;
+    static constexpr int P_DBQ = P_DWQ + 3 * C * CG;
+    static constexpr int P_DWP = P_DBQ + 3 * C;
+    static constexpr int P_DBP = P_DWP + C * C;
+    static constexpr int P_TBL = P_DBP + C;
+    static constexpr int P_TOTAL = P_TBL + TBL_N;
+    static_assert(OTP <= 2 * KSC && SZ_SQ >= (size_t)16 * OTP * LW * 2 && SZ_SQ >= (size_t)16 * CTP * LW * 2,
+                  "dY^T / A^T rows alias the P / dS squares");
 };
 
 template <class Cf>
@@ -57,10 +77,9 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const bf16_t *__restrict_
                                                        uint8_t *__restrict__ pack)
 {
     using B = BwdCfg<Cf>;
-    constexpr int C = B::C, D = B::D, CG = B::CG, HG = B::HG, HEADS = B::HEADS, ET = B::ET, KS = B::KS, KSC = B::KSC;
+    constexpr int C = B::C, D = B::D, CG = B::CG, HG = B::HG, ET = B::ET, KS = B::KS, KSC = B::KSC;
     const int gid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
     uint16_t *wq = reinterpret_cast<uint16_t *>(pack + B::OFF_WQ);
-    uint16_t *wc = reinterpret_cast<uint16_t *>(pack + B::OFF_WC);
     uint16_t *wpt = reinterpret_cast<uint16_t *>(pack + B::OFF_WPT);
     uint16_t *wqt = reinterpret_cast<uint16_t *>(pack + B::OFF_WQT);
     float *bias = reinterpret_cast<float *>(pack + B::OFF_BIAS);
@@ -78,23 +97,6 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const bf16_t *__restrict_
             uint16_t v = 0;
             if (e < D && c < CG) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c].bits;
             wq[(size_t)i * 8 + s] = v;
-        }
-    }
-    for (int i = gid; i < B::N_WC * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
-        int f = i >> 6;
-        const int etp = f % ET; f /= ET;
-        const int hlp = f % HG; f /= HG;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3; f /= 3;
-        const int hl = f % HG;
-        const int gi = f / HG + 1;
-        const int e = 16 * et + l16;
-        for (int j = 0; j < 4; ++j) {
-            const int ep = 16 * etp + 4 * q + j;
-            uint16_t v = 0;
-            if (e < D && ep < D) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + ep].bits;
-            wc[(size_t)i * 4 + j] = v;
         }
     }
     // Wproj^T: m-index l16 -> input channel (hd, e), k-slots -> output channel o
@@ -137,10 +139,6 @@ template <class Cf> __device__ __forceinline__ constexpr int fq(int hd, int t, i
 {
     return ((hd * 3 + t) * Cf::ET + et) * Cf::KS + ks;
 }
-template <class Cf> __device__ __forceinline__ constexpr int fc(int gi, int hl, int t, int et, int hlp, int etp)
-{
-    return (((((gi - 1) * Cf::HG + hl) * 3 + t) * Cf::ET + et) * Cf::HG + hlp) * Cf::ET + etp;
-}
 template <class Cf> __device__ __forceinline__ constexpr int fqt(int hd, int t, int et, int hlp, int etp)
 {
     return ((((hd * 3 + t) * Cf::ET + et) * Cf::HG + hlp) * Cf::ET) + etp;
@@ -148,28 +146,40 @@ template <class Cf> __device__ __forceinline__ constexpr int fqt(int hd, int t, 
 
 __device__ __forceinline__ uint4 cat(uint2 a, uint2 b) { return make_uint4(a.x, a.y, b.x, b.y); }
 
+// K=32 operand that is 1.0 in the k-slot holding index `target` and 0 elsewhere, for a lane
+// whose slots 0..7 hold indices first .. first+7.  Multiplying by it moves a matrix held as an
+// operand (k-slots = columns) into result layout exactly: a transposition done by the MFMA unit.
+__device__ __forceinline__ uint4 select_slot(int target, int first)
+{
+    const int sl = target - first;
+    const uint32_t one = (sl & 1) ? 0x3f800000u : 0x00003f80u;
+    const int dw = (sl >= 0 && sl < 8) ? (sl >> 1) : -1;
+    return make_uint4(dw == 0 ? one : 0u, dw == 1 ? one : 0u, dw == 2 ? one : 0u, dw == 3 ? one : 0u);
+}
+
+constexpr bool ranges_overlap(int a0, int a1, int b0, int b1) { return a0 < b1 && b0 < a1; }
+
 template <class Cf>
 __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                                                         const bf16_t *__restrict__ dy,
                                                         const bf16_t *__restrict__ attn,
                                                         const uint8_t *__restrict__ pack,
                                                         const bf16_t *__restrict__ table,
-                                                        bf16_t *__restrict__ dx, bf16_t *__restrict__ dqkv,
-                                                        float *__restrict__ tbl_part)
+                                                        bf16_t *__restrict__ dx, float *__restrict__ part)
 {
     using B = BwdCfg<Cf>;
     constexpr int C = B::C, D = B::D, CG = B::CG, HG = B::HG, HEADS = B::HEADS, G = B::G;
-    constexpr int ET = B::ET, KS = B::KS, KSC = B::KSC, LD = B::LD, NTBL = B::NTBL;
+    constexpr int ET = B::ET, KS = B::KS, KSC = B::KSC, LD = B::LD, LW = B::LW, NTBL = B::NTBL;
+    constexpr int CT = B::CT, NT = B::NT, KT = B::KT, OTP = B::OTP, CTP = B::CTP, NTP = B::NTP, KTP = B::KTP;
     constexpr int M = 8;
     static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0, "dword-granular loads and stores");
-    static_assert((size_t)NTBL * HEADS * 4 <= 2 * B::SZ_SQ, "table staging / flush aliases P and dS");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint4 *wq = reinterpret_cast<const uint4 *>(lds + B::OFF_WQ);
-    const uint2 *wc = reinterpret_cast<const uint2 *>(lds + B::OFF_WC);
     const uint4 *wpt = reinterpret_cast<const uint4 *>(lds + B::OFF_WPT);
     const uint2 *wqt = reinterpret_cast<const uint2 *>(lds + B::OFF_WQT);
     const float *bqkv = reinterpret_cast<const float *>(lds + B::OFF_BIAS);
+    float *tblf = reinterpret_cast<float *>(lds + B::OFF_TBLF);
     uint2 *kb = reinterpret_cast<uint2 *>(lds + B::OFF_KB);
     uint2 *vb = reinterpret_cast<uint2 *>(lds + B::OFF_VB);
     uint16_t *ktr = reinterpret_cast<uint16_t *>(lds + B::OFF_KT);
@@ -177,40 +187,27 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     uint16_t *dotr = reinterpret_cast<uint16_t *>(lds + B::OFF_DOT);
     uint16_t *pbuf = reinterpret_cast<uint16_t *>(lds + B::OFF_P);
     uint16_t *dsbuf = reinterpret_cast<uint16_t *>(lds + B::OFF_DS);
+    uint16_t *dybuf = pbuf, *abuf = dsbuf; // dY^T and A^T rows live where P / dS go later in the window
+    uint16_t *gbuf = reinterpret_cast<uint16_t *>(lds + B::OFF_DQKV);
+    uint16_t *fbuf = reinterpret_cast<uint16_t *>(lds + B::OFF_F);
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l16 = lane & 15, q = lane >> 4;
 
     for (int i = tid; i < (int)(B::PACK_BYTES / 16); i += 256)
         reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack)[i];
-    uint16_t *tstage = pbuf;
-    for (int i = tid; i < NTBL * HEADS; i += 256) tstage[i] = table[i].bits;
-    __syncthreads();
+    for (int i = tid; i < NTBL * HEADS; i += 256) tblf[i] = to_f32(table[i]);
 
+    // this lane's token inside the window, and the bias-table row of its (query, key 4q) pair:
+    // the entry of key 16kt+4q+j is idx0 - 30kt - j
     const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
-    uint32_t bias_frag[HEADS][8];
-#pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd)
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int jp = 0; jp < 2; ++jp) {
-                uint32_t pr = 0;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int m = 16 * kt + 4 * q + 2 * jp + h;
-                    const int idx = (rn - (m >> 3) + M - 1) * (2 * M - 1) + (cn - (m & 7) + M - 1);
-                    pr |= (uint32_t)tstage[idx * HEADS + hd] << (16 * h);
-                }
-                bias_frag[hd][kt * 2 + jp] = pr;
-            }
+    const int idx0 = (rn - (q >> 1) + M - 1) * (2 * M - 1) + (cn - 4 * (q & 1) + M - 1);
     const int s = g.shift;
     bool rmask[4], cmask[4];
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) rmask[kt] = (rn >= M - s) != ((2 * kt + (q >> 1)) >= M - s);
 #pragma unroll
     for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
-    // identity as an A operand: row l16, k-slots 4q+j
-    uint2 ident;
+    uint2 ident; // identity as a K=16 A operand: row l16, k-slots 4q+j
     {
         const uint32_t one = 0x3f80u;
         const int d0 = l16 - 4 * q;
@@ -219,15 +216,21 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     }
     __syncthreads();
 
-    f32x4 tblacc[HEADS][4];
+    f32x4 tblacc[HEADS][4], dwacc[HEADS][KT], wpacc[KTP];
 #pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd)
+    for (int hd = 0; hd < HEADS; ++hd) {
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) tblacc[hd][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < KT; ++k) dwacc[hd][k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int k = 0; k < KTP; ++k) wpacc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const float scale = 1.0f / sqrtf((float)D);
     const int per_img = g.nwi * g.nwj;
-    int par = 0; // parity of the double-buffered exchange rows
+    const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
+    int par = 0;
 
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
         const int b = win / per_img;
@@ -239,22 +242,25 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
         const long tok = ((long)b * g.H + si) * g.W + sj;
         const bool lastrow = s > 0 && wi == g.nwi - 1, lastcol = s > 0 && wj == g.nwj - 1;
 
+        // rows of x, of the saved group outputs and of dy as MFMA operands (k-slots = channels)
         const uint32_t *xrow = reinterpret_cast<const uint32_t *>(x + tok * C);
+        const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + tok * C);
         const uint32_t *dyrow = reinterpret_cast<const uint32_t *>(dy + tok * C);
-        uint4 xf[G][KS];
+        uint4 xf[G][KS], af[G][KS], dyf[KSC];
 #pragma unroll
         for (int gi = 0; gi < G; ++gi)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                uint32_t dwv[4];
+                uint32_t xv[4], av[4];
 #pragma unroll
                 for (int dw = 0; dw < 4; ++dw) {
                     const int c = 32 * ks + 8 * q + 2 * dw;
-                    dwv[dw] = c < CG ? xrow[(gi * CG + c) >> 1] : 0u;
+                    xv[dw] = c < CG ? xrow[(gi * CG + c) >> 1] : 0u;
+                    av[dw] = c < CG ? arow[(gi * CG + c) >> 1] : 0u;
                 }
-                xf[gi][ks] = make_uint4(dwv[0], dwv[1], dwv[2], dwv[3]);
+                xf[gi][ks] = make_uint4(xv[0], xv[1], xv[2], xv[3]);
+                af[gi][ks] = make_uint4(av[0], av[1], av[2], av[3]);
             }
-        uint4 dyf[KSC];
 #pragma unroll
         for (int ks = 0; ks < KSC; ++ks) {
             uint32_t dwv[4];
@@ -265,49 +271,65 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             }
             dyf[ks] = make_uint4(dwv[0], dwv[1], dwv[2], dwv[3]);
         }
-        // saved group outputs of the previous groups, T-form packed (the cascade input, Eq. 8)
-        uint2 Ob[HEADS][ET];
-        if (G > 1 && g.cascade) {
-#pragma unroll
-            for (int hd = 0; hd < HEADS - HG; ++hd)
-#pragma unroll
-                for (int et = 0; et < ET; ++et) {
-                    const int e0 = 16 * et + 4 * q;
-                    const uint32_t *src = reinterpret_cast<const uint32_t *>(attn + tok * C + hd * D + e0);
-                    Ob[hd][et].x = e0 < D ? src[0] : 0u;
-                    Ob[hd][et].y = e0 + 2 < D ? src[1] : 0u;
-                }
-        }
-        // dO of every head from the output projection (adjoint of Eq. 7), both forms
-        f32x4 dOT[HEADS][ET], dON[HEADS][ET];
-#pragma unroll
-        for (int hd = 0; hd < HEADS; ++hd)
-#pragma unroll
-            for (int et = 0; et < ET; ++et) {
-                dOT[hd][et] = f32x4{0.f, 0.f, 0.f, 0.f};
-                dON[hd][et] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KSC; ++ks) {
-                    const uint4 wf = wpt[((hd * ET + et) * KSC + ks) * 64 + lane];
-                    dOT[hd][et] = mma32(wf, dyf[ks], dOT[hd][et]);
-                    dON[hd][et] = mma32(dyf[ks], wf, dON[hd][et]);
-                }
-            }
 
-        f32x4 dFT[HG][ET], dFN[HG][ET];
+        // ---- d w_proj, d b_proj: dY^T and A^T rows [channel][token] through LDS, K = 64 tokens ----
+#pragma unroll
+        for (int ot = 0; ot < OTP; ++ot) {
+            f32x4 tN = mma32(dyf[ot >> 1], select_slot(16 * ot + l16, 32 * (ot >> 1) + 8 * q),
+                             f32x4{0.f, 0.f, 0.f, 0.f});
+            *reinterpret_cast<uint2 *>(dybuf + (16 * ot + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(tN);
+        }
+#pragma unroll
+        for (int ct = 0; ct < CTP; ++ct) {
+            f32x4 tN = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    if (ranges_overlap(gi * CG + 32 * ks, gi * CG + (32 * ks + 32 < CG ? 32 * ks + 32 : CG),
+                                       16 * ct, 16 * ct + 16))
+                        tN = mma32(af[gi][ks], select_slot(16 * ct + l16, gi * CG + 32 * ks + 8 * q), tN);
+            uint2 pk = pack_bf16x4(tN);
+            if (16 * ct + l16 == C) pk = ones2;
+            *reinterpret_cast<uint2 *>(abuf + (16 * ct + l16) * LW + 16 * wv + 4 * q) = pk;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < KTP; ++k) {
+            const int ti = 4 * k + wv;
+            if (ti < NTP) {
+                const int ot = ti / CTP, ct = ti - ot * CTP;
+                const uint16_t *ar = dybuf + (16 * ot + l16) * LW + 8 * q;
+                const uint16_t *br = abuf + (16 * ct + l16) * LW + 8 * q;
+#pragma unroll
+                for (int kp = 0; kp < 2; ++kp)
+                    wpacc[k] = mma32(*reinterpret_cast<const uint4 *>(ar + 32 * kp),
+                                     *reinterpret_cast<const uint4 *>(br + 32 * kp), wpacc[k]);
+            }
+        }
+
+        f32x4 dFT[HG][ET], cascT[HG][ET];
 #pragma unroll
         for (int hdr = 0; hdr < HEADS; ++hdr) {
             const int hd = HEADS - 1 - hdr; // groups in reverse order
             const int gi = hd / HG, hl = hd % HG;
-            const bool casc_in = gi > 0 && g.cascade;
+            const bool casc_in = gi > 0 && g.cascade;      // this group's input has a cascade term
+            const bool casc_out = gi < G - 1 && g.cascade; // this group's output feeds the next group
+            const int gp = gi > 0 ? gi - 1 : 0;
             if (hl == HG - 1) {
 #pragma unroll
                 for (int hlp = 0; hlp < HG; ++hlp)
 #pragma unroll
-                    for (int etp = 0; etp < ET; ++etp) {
-                        dFT[hlp][etp] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        dFN[hlp][etp] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
+                    for (int etp = 0; etp < ET; ++etp) dFT[hlp][etp] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            // ---- dO^T of this head: adjoint of Eq. 7, plus the gradient arriving through Eq. 8 ----
+            f32x4 dOT[ET];
+#pragma unroll
+            for (int et = 0; et < ET; ++et) {
+                dOT[et] = casc_out ? cascT[hl][et] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KSC; ++ks)
+                    dOT[et] = mma32(wpt[((hd * ET + et) * KSC + ks) * 64 + lane], dyf[ks], dOT[et]);
             }
             // ---- recompute q, k (both forms) and v (T-form) of this wave's tokens ----
             f32x4 qT[ET], qN[ET], kT[ET], kN[ET], vT[ET];
@@ -335,22 +357,13 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     kT[et] = mma32(fk_, xf[gi][ks], kT[et]);
                     kN[et] = mma32(xf[gi][ks], fk_, kN[et]);
                     vT[et] = mma32(fv_, xf[gi][ks], vT[et]);
-                }
-                if (casc_in) {
-#pragma unroll
-                    for (int hlp = 0; hlp < HG; ++hlp)
-#pragma unroll
-                        for (int etp = 0; etp < ET; ++etp) {
-                            const uint2 prev = Ob[(gi > 0 ? gi - 1 : 0) * HG + hlp][etp];
-                            const uint2 cq = wc[fc<Cf>(gi > 0 ? gi : 1, hl, 0, et, hlp, etp) * 64 + lane];
-                            const uint2 ck = wc[fc<Cf>(gi > 0 ? gi : 1, hl, 1, et, hlp, etp) * 64 + lane];
-                            const uint2 cv = wc[fc<Cf>(gi > 0 ? gi : 1, hl, 2, et, hlp, etp) * 64 + lane];
-                            qT[et] = mma16(cq, prev, qT[et]);
-                            qN[et] = mma16(prev, cq, qN[et]);
-                            kT[et] = mma16(ck, prev, kT[et]);
-                            kN[et] = mma16(prev, ck, kN[et]);
-                            vT[et] = mma16(cv, prev, vT[et]);
-                        }
+                    if (casc_in) {
+                        qT[et] = mma32(fq_, af[gp][ks], qT[et]);
+                        qN[et] = mma32(af[gp][ks], fq_, qN[et]);
+                        kT[et] = mma32(fk_, af[gp][ks], kT[et]);
+                        kN[et] = mma32(af[gp][ks], fk_, kN[et]);
+                        vT[et] = mma32(fv_, af[gp][ks], vT[et]);
+                    }
                 }
             }
             // ---- exchange: K, V tiles; K^T, Q^T, dO^T rows ----
@@ -358,13 +371,17 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
                 Qb[et] = pack_bf16x4(qT[et]);
-                dOb[et] = pack_bf16x4(dOT[hd][et]);
+                dOb[et] = pack_bf16x4(dOT[et]);
                 kb[(wv * ET + et) * 64 + lane] = pack_bf16x4(kT[et]);
                 vb[(wv * ET + et) * 64 + lane] = pack_bf16x4(vT[et]);
                 const int row = (16 * et + l16) * LD + 16 * wv + 4 * q;
                 *reinterpret_cast<uint2 *>(ktr + row) = pack_bf16x4(kN[et]);
                 *reinterpret_cast<uint2 *>(qtr + par * 16 * ET * LD + row) = pack_bf16x4(qN[et]);
-                *reinterpret_cast<uint2 *>(dotr + par * 16 * ET * LD + row) = pack_bf16x4(dON[hd][et]);
+                uint16_t *dst = dotr + par * 16 * ET * LD + (16 * et + 4 * q) * LD + 16 * wv + l16;
+                dst[0] = (uint16_t)(dOb[et].x & 0xffffu);
+                dst[LD] = (uint16_t)(dOb[et].x >> 16);
+                dst[2 * LD] = (uint16_t)(dOb[et].y & 0xffffu);
+                dst[3 * LD] = (uint16_t)(dOb[et].y >> 16);
             }
             __syncthreads();
 
@@ -383,10 +400,8 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t pr = bias_frag[hd][kt * 2 + (j >> 1)];
-                    st[kt][j] = fmaf(st[kt][j], scale, (j & 1) ? bf16_hi(pr) : bf16_lo(pr));
-                }
+                for (int j = 0; j < 4; ++j)
+                    st[kt][j] = fmaf(st[kt][j], scale, tblf[(idx0 - 30 * kt - j) * HEADS + hd]);
             if (lastrow || lastcol) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
@@ -432,37 +447,42 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             // transposed copies for the key role: [key][query]
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
-                const int base = (16 * kt + 4 * q) * LD + 16 * wv + l16;
+                const int base = (16 * kt + 4 * q) * LW + 16 * wv + l16;
                 pbuf[base] = (uint16_t)(Pb[kt].x & 0xffffu);
-                pbuf[base + LD] = (uint16_t)(Pb[kt].x >> 16);
-                pbuf[base + 2 * LD] = (uint16_t)(Pb[kt].y & 0xffffu);
-                pbuf[base + 3 * LD] = (uint16_t)(Pb[kt].y >> 16);
+                pbuf[base + LW] = (uint16_t)(Pb[kt].x >> 16);
+                pbuf[base + 2 * LW] = (uint16_t)(Pb[kt].y & 0xffffu);
+                pbuf[base + 3 * LW] = (uint16_t)(Pb[kt].y >> 16);
                 dsbuf[base] = (uint16_t)(dSb[kt].x & 0xffffu);
-                dsbuf[base + LD] = (uint16_t)(dSb[kt].x >> 16);
-                dsbuf[base + 2 * LD] = (uint16_t)(dSb[kt].y & 0xffffu);
-                dsbuf[base + 3 * LD] = (uint16_t)(dSb[kt].y >> 16);
+                dsbuf[base + LW] = (uint16_t)(dSb[kt].x >> 16);
+                dsbuf[base + 2 * LW] = (uint16_t)(dSb[kt].y & 0xffffu);
+                dsbuf[base + 3 * LW] = (uint16_t)(dSb[kt].y >> 16);
             }
-            // dQ^T = scale * K^T dS^T  (T-form: rows = features, column = own query)
+            // dQ = scale * dS K in both forms: T-form feeds dF, N-form rows feed d w_qkv
             f32x4 dqT[ET];
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
                 dqT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
+                f32x4 dqN = f32x4{0.f, 0.f, 0.f, 0.f};
                 const uint16_t *krow = ktr + (16 * et + l16) * LD + 4 * q;
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp) {
-                    const uint2 a0 = *reinterpret_cast<const uint2 *>(krow + 32 * kp);
-                    const uint2 a1 = *reinterpret_cast<const uint2 *>(krow + 32 * kp + 16);
-                    dqT[et] = mma32(cat(a0, a1), cat(dSb[2 * kp], dSb[2 * kp + 1]), dqT[et]);
+                    const uint4 kf = cat(*reinterpret_cast<const uint2 *>(krow + 32 * kp),
+                                         *reinterpret_cast<const uint2 *>(krow + 32 * kp + 16));
+                    const uint4 sf = cat(dSb[2 * kp], dSb[2 * kp + 1]);
+                    dqT[et] = mma32(kf, sf, dqT[et]);
+                    dqN = mma32(sf, kf, dqN);
                 }
                 dqT[et] *= scale;
+                dqN *= scale;
+                *reinterpret_cast<uint2 *>(gbuf + ((0 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dqN);
             }
             __syncthreads();
 
-            // ---- key role: dV^T = dO^T P, dK^T = scale * Q^T dS for this wave's 16 keys ----
+            // ---- key role: dV = P^T dO, dK = scale * dS^T Q for this wave's 16 keys, both forms ----
             f32x4 dkT[ET], dvT[ET];
             {
-                const uint16_t *prow = pbuf + (16 * wv + l16) * LD + 4 * q;
-                const uint16_t *srow = dsbuf + (16 * wv + l16) * LD + 4 * q;
+                const uint16_t *prow = pbuf + (16 * wv + l16) * LW + 4 * q;
+                const uint16_t *srow = dsbuf + (16 * wv + l16) * LW + 4 * q;
                 uint4 pf[2], sf[2];
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp) {
@@ -475,6 +495,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                 for (int et = 0; et < ET; ++et) {
                     dkT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
                     dvT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    f32x4 dkN = f32x4{0.f, 0.f, 0.f, 0.f}, dvN = f32x4{0.f, 0.f, 0.f, 0.f};
                     const uint16_t *qrow = qtr + par * 16 * ET * LD + (16 * et + l16) * LD + 4 * q;
                     const uint16_t *orow = dotr + par * 16 * ET * LD + (16 * et + l16) * LD + 4 * q;
 #pragma unroll
@@ -484,47 +505,63 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                         const uint4 oa = cat(*reinterpret_cast<const uint2 *>(orow + 32 * kp),
                                              *reinterpret_cast<const uint2 *>(orow + 32 * kp + 16));
                         dkT[et] = mma32(qa, sf[kp], dkT[et]);
+                        dkN = mma32(sf[kp], qa, dkN);
                         dvT[et] = mma32(oa, pf[kp], dvT[et]);
+                        dvN = mma32(pf[kp], oa, dvN);
                     }
                     dkT[et] *= scale;
+                    dkN *= scale;
+                    *reinterpret_cast<uint2 *>(gbuf + ((1 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dkN);
+                    *reinterpret_cast<uint2 *>(gbuf + ((2 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dvN);
                 }
             }
-            // ---- gradients of q|k|v: to memory, and through Wqkv^T into dF of the group ----
+            // ---- first head of a group: F^T rows [channel][token] of the group input (Eq. 8) ----
+            if (hl == HG - 1) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    f32x4 tN = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (2 * (ct >> 1) < 2 * KS && (ct >> 1) < KS) {
+                        const uint4 sel = select_slot(16 * ct + l16, 32 * (ct >> 1) + 8 * q);
+                        tN = mma32(xf[gi][(ct >> 1) < KS ? (ct >> 1) : 0], sel, tN);
+                        if (casc_in) tN = mma32(af[gp][(ct >> 1) < KS ? (ct >> 1) : 0], sel, tN);
+                    }
+                    uint2 pk = pack_bf16x4(tN);
+                    if (16 * ct + l16 == CG) pk = ones2;
+                    *reinterpret_cast<uint2 *>(fbuf + (16 * ct + l16) * LW + 16 * wv + 4 * q) = pk;
+                }
+            }
+            // ---- d(q|k|v) through Wqkv^T into dF of the group ----
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
                 const uint2 gq = pack_bf16x4(dqT[et]), gk = pack_bf16x4(dkT[et]), gv = pack_bf16x4(dvT[et]);
-                const int e0 = 16 * et + 4 * q;
-                uint32_t *dst = reinterpret_cast<uint32_t *>(dqkv + tok * 3 * C + gi * 3 * CG + hl * D + e0);
-                if (e0 < D) {
-                    dst[0] = gq.x;
-                    dst[CG / 2] = gk.x;
-                    dst[CG] = gv.x;
-                }
-                if (e0 + 2 < D) {
-                    dst[1] = gq.y;
-                    dst[CG / 2 + 1] = gk.y;
-                    dst[CG + 1] = gv.y;
-                }
 #pragma unroll
                 for (int hlp = 0; hlp < HG; ++hlp)
 #pragma unroll
                     for (int etp = 0; etp < ET; ++etp) {
-                        const uint2 w0 = wqt[fqt<Cf>(hd, 0, et, hlp, etp) * 64 + lane];
-                        const uint2 w1 = wqt[fqt<Cf>(hd, 1, et, hlp, etp) * 64 + lane];
-                        const uint2 w2 = wqt[fqt<Cf>(hd, 2, et, hlp, etp) * 64 + lane];
-                        dFT[hlp][etp] = mma16(w0, gq, dFT[hlp][etp]);
-                        dFT[hlp][etp] = mma16(w1, gk, dFT[hlp][etp]);
-                        dFT[hlp][etp] = mma16(w2, gv, dFT[hlp][etp]);
-                        if (casc_in) {
-                            dFN[hlp][etp] = mma16(gq, w0, dFN[hlp][etp]);
-                            dFN[hlp][etp] = mma16(gk, w1, dFN[hlp][etp]);
-                            dFN[hlp][etp] = mma16(gv, w2, dFN[hlp][etp]);
-                        }
+                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hd, 0, et, hlp, etp) * 64 + lane], gq, dFT[hlp][etp]);
+                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hd, 1, et, hlp, etp) * 64 + lane], gk, dFT[hlp][etp]);
+                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hd, 2, et, hlp, etp) * 64 + lane], gv, dFT[hlp][etp]);
                     }
+            }
+            __syncthreads();
+
+            // ---- d w_qkv (and d b_qkv in the spare column) of this head: K = 64 tokens ----
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                const int ti = 4 * k + wv;
+                if (ti < NT) {
+                    const int r = ti / CT, ct = ti - r * CT;
+                    const uint16_t *ar = gbuf + (16 * r + l16) * LW + 8 * q;
+                    const uint16_t *br = fbuf + (16 * ct + l16) * LW + 8 * q;
+#pragma unroll
+                    for (int kp = 0; kp < 2; ++kp)
+                        dwacc[hd][k] = mma32(*reinterpret_cast<const uint4 *>(ar + 32 * kp),
+                                             *reinterpret_cast<const uint4 *>(br + 32 * kp), dwacc[hd][k]);
+                }
             }
             par ^= 1;
 
-            // ---- end of a group: dx slice, and the cascade gradient into the previous group ----
+            // ---- end of a group: dx slice; keep dF as the cascade gradient of the previous group ----
             if (hl == 0) {
 #pragma unroll
                 for (int hlp = 0; hlp < HG; ++hlp)
@@ -535,18 +572,55 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                         uint32_t *dst = reinterpret_cast<uint32_t *>(dx + tok * C + gi * CG + hlp * D + c0);
                         if (c0 < D) dst[0] = v.x;
                         if (c0 + 2 < D) dst[1] = v.y;
-                        if (casc_in) {
-                            dOT[(gi > 0 ? gi - 1 : 0) * HG + hlp][etp] += dFT[hlp][etp];
-                            dON[(gi > 0 ? gi - 1 : 0) * HG + hlp][etp] += dFN[hlp][etp];
-                        }
+                        cascT[hlp][etp] = dFT[hlp][etp];
                     }
             }
         }
     }
 
-    // ---- flush the bias-table gradient: (query, key) accumulators -> table entries -> partials ----
+    // ---- flush: this workgroup's partial sums, in parameter order ----
+    float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
+#pragma unroll
+    for (int k = 0; k < KTP; ++k) {
+        const int ti = 4 * k + wv;
+        if (ti < NTP) {
+            const int ot = ti / CTP, ct = ti - ot * CTP;
+            const int c = 16 * ct + l16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int o = 16 * ot + 4 * q + j;
+                if (o < C) {
+                    if (c < C) mine[B::P_DWP + o * C + c] = wpacc[k][j];
+                    else if (c == C) mine[B::P_DBP + o] = wpacc[k][j];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int hd = 0; hd < HEADS; ++hd) {
+        const int gi = hd / HG, hl = hd % HG;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            const int ti = 4 * k + wv;
+            if (ti < NT) {
+                const int r = ti / CT, ct = ti - r * CT;
+                const int t = r / ET, et = r - t * ET;
+                const int c = 16 * ct + l16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int e = 16 * et + 4 * q + j;
+                    if (e < D) {
+                        const int row = gi * 3 * CG + t * CG + hl * D + e;
+                        if (c < CG) mine[B::P_DWQ + row * CG + c] = dwacc[hd][k][j];
+                        else if (c == CG) mine[B::P_DBQ + row] = dwacc[hd][k][j];
+                    }
+                }
+            }
+        }
+    }
     __syncthreads();
     float *tbl = reinterpret_cast<float *>(lds + B::OFF_P);
+    static_assert((size_t)B::TBL_N * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
     for (int i = tid; i < B::TBL_N; i += 256) tbl[i] = 0.f;
     __syncthreads();
 #pragma unroll
@@ -554,24 +628,35 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int m = 16 * kt + 4 * q + j;
-                const int idx = (rn - (m >> 3) + M - 1) * (2 * M - 1) + (cn - (m & 7) + M - 1);
-                atomicAdd(&tbl[idx * HEADS + hd], tblacc[hd][kt][j]);
-            }
+            for (int j = 0; j < 4; ++j) atomicAdd(&tbl[(idx0 - 30 * kt - j) * HEADS + hd], tblacc[hd][kt][j]);
     __syncthreads();
-    for (int i = tid; i < B::TBL_N; i += 256) tbl_part[(size_t)blockIdx.x * B::TBL_N + i] = tbl[i];
+    for (int i = tid; i < B::TBL_N; i += 256) mine[B::P_TBL + i] = tbl[i];
 }
 
-// out[i] (+)= sum_w part[w][i]
+// Sums the per-workgroup partial vectors and scatters the five segments to their gradients.
+// One block handles 64 entries; its four waves each sum a quarter of the partials.
+struct ReduceOut {
+    float *ptr[5];
+    int begin[6];
+};
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
-                                                              int n, float *__restrict__ out, int accumulate)
+                                                              int n, ReduceOut out, int accumulate)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    __shared__ float red[4][64];
+    const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + col;
     float acc = 0.f;
-    for (int w = 0; w < nparts; ++w) acc += part[(size_t)w * n + i];
-    out[i] = accumulate ? out[i] + acc : acc;
+    if (i < n)
+        for (int w = slice; w < nparts; w += 4) acc += part[(size_t)w * n + i];
+    red[slice][col] = acc;
+    __syncthreads();
+    if (slice == 0 && i < n) {
+        acc = (red[0][col] + red[1][col]) + (red[2][col] + red[3][col]);
+        int seg = 0;
+        while (seg < 4 && i >= out.begin[seg + 1]) ++seg;
+        float *dst = out.ptr[seg] + (i - out.begin[seg]);
+        *dst = accumulate ? *dst + acc : acc;
+    }
 }
 
 int device_cu_count()
@@ -596,7 +681,8 @@ int bwd_grid(const Geom &g)
 template <class Cf>
 hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                    const bf16_t *w_qkv, const bf16_t *b_qkv, const bf16_t *w_proj, const bf16_t *table,
-                   bf16_t *dx, bf16_t *dqkv, float *dtable, int accumulate, void *ws, hipStream_t s)
+                   bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj, float *db_proj, float *dtable,
+                   int accumulate, void *ws, hipStream_t s)
 {
     using B = BwdCfg<Cf>;
     static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -619,14 +705,18 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     const int grid = bwd_grid(g);
     {
         KernelTimer kt(K_FUSED_BWD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, dqkv, part);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, part);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    ReduceOut out;
+    out.ptr[0] = dw_qkv; out.ptr[1] = db_qkv; out.ptr[2] = dw_proj; out.ptr[3] = db_proj; out.ptr[4] = dtable;
+    out.begin[0] = B::P_DWQ; out.begin[1] = B::P_DBQ; out.begin[2] = B::P_DWP; out.begin[3] = B::P_DBP;
+    out.begin[4] = B::P_TBL; out.begin[5] = B::P_TOTAL;
     {
         KernelTimer kt(K_REDUCE, s);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::TBL_N + 255) / 256), dim3(256), 0, s, part, grid,
-                           B::TBL_N, dtable, accumulate);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::P_TOTAL + 63) / 64), dim3(256), 0, s, part, grid,
+                           B::P_TOTAL, out, accumulate);
     }
     return hipGetLastError();
 }
@@ -652,7 +742,7 @@ size_t fused_bwd_ws_bytes(const Geom &g)
 #define X(C_, H_, G_)                                                    \
     if (g.C == C_ && g.heads == H_ && g.groups == G_) {                  \
         pack = BwdCfg<FusedCfg<C_, H_, G_>>::PACK_BYTES;                 \
-        tbl = BwdCfg<FusedCfg<C_, H_, G_>>::TBL_N;                       \
+        tbl = BwdCfg<FusedCfg<C_, H_, G_>>::P_TOTAL;                     \
     }
     GSWA_FUSED_SHAPES(X)
 #undef X
@@ -662,13 +752,13 @@ size_t fused_bwd_ws_bytes(const Geom &g)
 
 hipError_t launch_fused_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                             const bf16_t *w_qkv, const bf16_t *b_qkv, const bf16_t *w_proj,
-                            const bf16_t *table, bf16_t *dx, bf16_t *dqkv, float *dtable, int accumulate,
-                            void *ws, hipStream_t s)
+                            const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
+                            float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s)
 {
 #define X(C_, H_, G_)                                                   \
     if (g.C == C_ && g.heads == H_ && g.groups == G_)                   \
-        return run_bwd<FusedCfg<C_, H_, G_>>(g, x, dy, attn, w_qkv, b_qkv, w_proj, table, dx, dqkv, dtable, \
-                                             accumulate, ws, s);
+        return run_bwd<FusedCfg<C_, H_, G_>>(g, x, dy, attn, w_qkv, b_qkv, w_proj, table, dx, dw_qkv, db_qkv, \
+                                             dw_proj, db_proj, dtable, accumulate, ws, s);
     GSWA_FUSED_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

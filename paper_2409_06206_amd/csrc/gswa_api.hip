@@ -87,7 +87,7 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.fused_bwd_ws = 0;
     if (s.fused_bwd) {
         s.fused_bwd_ws = align256(fused_bwd_ws_bytes(g));
-        s.bwd_ws = s.fused_bwd_ws + align256((size_t)g.T * 3 * g.C * e); // + d(q|k|v) of all groups
+        s.bwd_ws = s.fused_bwd_ws;
     }
     return s;
 }
@@ -185,39 +185,14 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     return GSWA_OK;
 }
 
-// Fused backward kernel for dx, d(q|k|v) and the bias table; weight gradients by the staged
-// split-token GEMMs over d(q|k|v).
-int backward_fused(const Geom &g, const Sizes &sz, uint32_t flags, const bf16_t *x, const bf16_t *dy,
-                   const bf16_t *w_qkv, const bf16_t *b_qkv, const bf16_t *w_proj, const bf16_t *table,
-                   const bf16_t *attn, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
-                   float *db_proj, float *dtable, char *ws, hipStream_t st)
+int backward_fused(const Geom &g, uint32_t flags, const bf16_t *x, const bf16_t *dy, const bf16_t *w_qkv,
+                   const bf16_t *b_qkv, const bf16_t *w_proj, const bf16_t *table, const bf16_t *attn,
+                   bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj, float *db_proj, float *dtable,
+                   char *ws, hipStream_t st)
 {
-    const int C = g.C, Cg = g.Cg, G = g.groups;
     const int accumulate = (flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
-    bf16_t *dqkv = reinterpret_cast<bf16_t *>(ws + sz.fused_bwd_ws);
-    if (!accumulate) {
-        GSWA_HIP(launch_fill_zero(dw_qkv, (size_t)G * 3 * Cg * Cg, st));
-        GSWA_HIP(launch_fill_zero(db_qkv, (size_t)G * 3 * Cg, st));
-        GSWA_HIP(launch_fill_zero(dw_proj, (size_t)C * C, st));
-        GSWA_HIP(launch_fill_zero(db_proj, (size_t)C, st));
-    }
-    WgradArgs wp{};
-    wp.dout = dy; wp.lddout = C;
-    wp.a1 = attn; wp.lda1 = C;
-    wp.dw = dw_proj; wp.db = db_proj;
-    wp.rows = g.T; wp.N = C; wp.K = C; wp.prof_id = K_PROJ_WGRAD;
-    GSWA_HIP(launch_wgrad<bf16_t>(wp, st));
-    GSWA_HIP(launch_fused_bwd(g, x, dy, attn, w_qkv, b_qkv, w_proj, table, dx, dqkv, dtable, accumulate, ws, st));
-    for (int grp = 0; grp < G; ++grp) {
-        WgradArgs wq{};
-        wq.dout = dqkv + (size_t)grp * 3 * Cg; wq.lddout = 3 * C;
-        wq.a1 = x + grp * Cg; wq.lda1 = C;
-        if (grp > 0 && g.cascade) { wq.a2 = attn + (grp - 1) * Cg; wq.lda2 = C; }
-        wq.dw = dw_qkv + (size_t)grp * 3 * Cg * Cg;
-        wq.db = db_qkv + (size_t)grp * 3 * Cg;
-        wq.rows = g.T; wq.N = 3 * Cg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
-        GSWA_HIP(launch_wgrad<bf16_t>(wq, st));
-    }
+    GSWA_HIP(launch_fused_bwd(g, x, dy, attn, w_qkv, b_qkv, w_proj, table, dx, dw_qkv, db_qkv, dw_proj,
+                              db_proj, dtable, accumulate, ws, st));
     return GSWA_OK;
 }
 
@@ -286,7 +261,7 @@ int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const vo
                                       (float *)dw_qkv, (float *)db_qkv, (float *)dw_proj,
                                       (float *)db_proj, (float *)dbias_table, (char *)ws, st);
     if (s.fused_bwd)
-        return backward_fused(g, s, desc->flags, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)w_qkv,
+        return backward_fused(g, desc->flags, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)w_qkv,
                               (const bf16_t *)b_qkv, (const bf16_t *)w_proj, (const bf16_t *)bias_table,
                               (const bf16_t *)saved, (bf16_t *)dx, (float *)dw_qkv, (float *)db_qkv,
                               (float *)dw_proj, (float *)db_proj, (float *)dbias_table, (char *)ws, st);
