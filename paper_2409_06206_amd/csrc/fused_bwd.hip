@@ -618,19 +618,26 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             }
         }
     }
-    __syncthreads();
-    float *tbl = reinterpret_cast<float *>(lds + B::OFF_P);
-    static_assert((size_t)B::TBL_N * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
-    for (int i = tid; i < B::TBL_N; i += 256) tbl[i] = 0.f;
-    __syncthreads();
+    // bias-table gradient: (query, key) accumulators -> table entries, summed in a fixed order
+    float *mat = reinterpret_cast<float *>(lds + B::OFF_P); // [64 queries][64 keys] of one head
+    static_assert((size_t)64 * 64 * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
 #pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd)
+    for (int hd = 0; hd < HEADS; ++hd) {
+        __syncthreads();
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) atomicAdd(&tbl[(idx0 - 30 * kt - j) * HEADS + hd], tblacc[hd][kt][j]);
-    __syncthreads();
-    for (int i = tid; i < B::TBL_N; i += 256) mine[B::P_TBL + i] = tbl[i];
+            for (int j = 0; j < 4; ++j) mat[(16 * wv + l16) * 64 + 16 * kt + 4 * q + j] = tblacc[hd][kt][j];
+        __syncthreads();
+        if (tid < NTBL) {
+            const int dr = tid / (2 * M - 1) - (M - 1), dc = tid % (2 * M - 1) - (M - 1);
+            float acc = 0.f;
+            for (int r = (dr > 0 ? dr : 0); r < (dr < 0 ? M + dr : M); ++r)
+                for (int c = (dc > 0 ? dc : 0); c < (dc < 0 ? M + dc : M); ++c)
+                    acc += mat[(r * M + c) * 64 + (r - dr) * M + (c - dc)];
+            mine[B::P_TBL + tid * HEADS + hd] = acc;
+        }
+    }
 }
 
 // Sums the per-workgroup partial vectors and scatters the five segments to their gradients.
