@@ -75,14 +75,15 @@ typedef struct gswa_desc {
  * Sizes, in bytes, of the caller-provided device buffers (Sec. "Group Shifted Window
  * Attention": the head-group loop is what bounds them).
  *   *saved_bytes   state forward leaves for backward: the concatenated group outputs
- *                  [B*H*W, C] in desc->dtype.  Scores and probabilities are never kept;
- *                  backward recomputes them.
+ *                  [B*H*W, C] in desc->dtype and, on the fused path, the parameters repacked
+ *                  for the matrix cores (tens of KB, independent of B, H, W).  Scores and
+ *                  probabilities are never kept; backward recomputes them.
  *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given.  Staged path: one group's
  *                  q|k|v, and with saved == NULL the scratch must hold fwd_ws_bytes + saved_bytes.
- *                  Fused path: a fragment-ordered copy of the weights (a few tens of KB).
+ *                  Fused path: room for the repacked parameters, used only when saved == NULL.
  *   *bwd_ws_bytes  scratch of gswa_backward.  Staged path: one group's q|k|v and its gradient.
- *                  Fused path: packed weights plus one partial parameter-gradient vector per
- *                  workgroup (one workgroup per compute unit).
+ *                  Fused path: one partial parameter-gradient vector per workgroup (one
+ *                  workgroup per compute unit).
  * Which path serves a layer depends only on desc (shape, dtype, flags).
  * Any output pointer may be NULL.  All sizes are multiples of 256.
  */

@@ -31,22 +31,19 @@ template <class Cf> struct BwdCfg {
     static constexpr int KT = (NT + 3) / 4;         // tiles per wave
     static constexpr int OTP = (C + 15) / 16, CTP = C / 16 + 1;
     static constexpr int NTP = OTP * CTP, KTP = (NTP + 3) / 4;
-    // weight fragments (lane-major)
-    static constexpr int N_WQ = Cf::N_WQ;                  // Wqkv, K=32: (hd,t,et,ks)
-    static constexpr int N_WPT = HEADS * ET * KSC;         // Wproj^T, K=32: (hd,et,ks)
-    static constexpr int N_WQT = HEADS * 3 * ET * HG * ET; // Wqkv^T, K=16: (hd,t,et,hlp,etp)
+    // packed parameters: the backward range [WQ | BIAS | WPT | WQT] of the buffer forward filled
     static constexpr size_t OFF_WQ = 0;
-    static constexpr size_t OFF_WPT = OFF_WQ + (size_t)N_WQ * 1024;
-    static constexpr size_t OFF_WQT = OFF_WPT + (size_t)N_WPT * 1024;
-    static constexpr size_t OFF_BIAS = OFF_WQT + (size_t)N_WQT * 512; // fp32 b_qkv [3C] (+C unused)
-    static constexpr size_t PACK_BYTES = OFF_BIAS + (size_t)16 * C;
+    static constexpr size_t OFF_BIAS = Cf::P_BIAS - Cf::P_WQ;
+    static constexpr size_t OFF_WPT = Cf::P_WPT - Cf::P_WQ;
+    static constexpr size_t OFF_WQT = Cf::P_WQT - Cf::P_WQ;
+    static constexpr size_t PACK_BYTES = Cf::BWD_PACK_BYTES;
     // LDS beyond the packed weights
     static constexpr int LD = 68; // pitch (bf16) of rows read 4 at a time
     static constexpr int LW = 72; // pitch (bf16) of rows read 8 at a time
     static constexpr size_t SZ_FRAG = (size_t)4 * ET * 64 * 8;
     static constexpr size_t SZ_ROWS = (size_t)16 * ET * LD * 2;
     static constexpr size_t SZ_SQ = (size_t)64 * LW * 2; // P / dS [key][query]; also dY^T / A^T rows
-    static constexpr size_t OFF_TBLF = PACK_BYTES;             // fp32 bias table [225][HEADS]
+    static constexpr size_t OFF_TBLF = PACK_BYTES;             // fp32 bias table [HEADS][225]
     static constexpr size_t OFF_KB = OFF_TBLF + (((size_t)TBL_N * 4 + 15) & ~size_t(15));
     static constexpr size_t OFF_VB = OFF_KB + SZ_FRAG;
     static constexpr size_t OFF_KT = OFF_VB + SZ_FRAG;         // K^T rows [e][key]
@@ -69,71 +66,6 @@ template <class Cf> struct BwdCfg {
     static_assert(OTP <= 2 * KSC && SZ_SQ >= (size_t)16 * OTP * LW * 2 && SZ_SQ >= (size_t)16 * CTP * LW * 2,
                   "dY^T / A^T rows alias the P / dS squares");
 };
-
-template <class Cf>
-__global__ __launch_bounds__(256) void pack_bwd_kernel(const bf16_t *__restrict__ w_qkv,
-                                                       const bf16_t *__restrict__ b_qkv,
-                                                       const bf16_t *__restrict__ w_proj,
-                                                       uint8_t *__restrict__ pack)
-{
-    using B = BwdCfg<Cf>;
-    constexpr int C = B::C, D = B::D, CG = B::CG, HG = B::HG, ET = B::ET, KS = B::KS, KSC = B::KSC;
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
-    uint16_t *wq = reinterpret_cast<uint16_t *>(pack + B::OFF_WQ);
-    uint16_t *wpt = reinterpret_cast<uint16_t *>(pack + B::OFF_WPT);
-    uint16_t *wqt = reinterpret_cast<uint16_t *>(pack + B::OFF_WQT);
-    float *bias = reinterpret_cast<float *>(pack + B::OFF_BIAS);
-
-    for (int i = gid; i < B::N_WQ * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
-        int f = i >> 6;
-        const int ks = f % KS; f /= KS;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3;
-        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int e = 16 * et + l16;
-        for (int s = 0; s < 8; ++s) {
-            const int c = 32 * ks + 8 * q + s;
-            uint16_t v = 0;
-            if (e < D && c < CG) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c].bits;
-            wq[(size_t)i * 8 + s] = v;
-        }
-    }
-    // Wproj^T: m-index l16 -> input channel (hd, e), k-slots -> output channel o
-    for (int i = gid; i < B::N_WPT * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
-        int f = i >> 6;
-        const int ks = f % KSC; f /= KSC;
-        const int et = f % ET;
-        const int hd = f / ET;
-        const int e = 16 * et + l16;
-        for (int s = 0; s < 8; ++s) {
-            const int o = 32 * ks + 8 * q + s;
-            uint16_t v = 0;
-            if (e < D && o < C) v = w_proj[(size_t)o * C + hd * D + e].bits;
-            wpt[(size_t)i * 8 + s] = v;
-        }
-    }
-    // Wqkv^T: m-index l16 -> input channel of the group, tiled like the previous group's heads
-    // (c = hlp*D + 16*etp + l16); k-slots -> output feature (t, hl, e = 16*et + 4q + j)
-    for (int i = gid; i < B::N_WQT * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
-        int f = i >> 6;
-        const int etp = f % ET; f /= ET;
-        const int hlp = f % HG; f /= HG;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3;
-        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int cp = 16 * etp + l16;
-        for (int j = 0; j < 4; ++j) {
-            const int e = 16 * et + 4 * q + j;
-            uint16_t v = 0;
-            if (cp < D && e < D) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + cp].bits;
-            wqt[(size_t)i * 4 + j] = v;
-        }
-    }
-    for (int i = gid; i < 4 * C; i += stride) bias[i] = i < 3 * C ? to_f32(b_qkv[i]) : 0.f;
-}
 
 template <class Cf> __device__ __forceinline__ constexpr int fq(int hd, int t, int et, int ks)
 {
@@ -191,11 +123,12 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     uint16_t *gbuf = reinterpret_cast<uint16_t *>(lds + B::OFF_DQKV);
     uint16_t *fbuf = reinterpret_cast<uint16_t *>(lds + B::OFF_F);
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l16 = lane & 15, q = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6); // wave index, held in a scalar register
 
     for (int i = tid; i < (int)(B::PACK_BYTES / 16); i += 256)
-        reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack)[i];
-    for (int i = tid; i < NTBL * HEADS; i += 256) tblf[i] = to_f32(table[i]);
+        reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack + Cf::BWD_PACK_OFF)[i];
+    for (int i = tid; i < NTBL * HEADS; i += 256) tblf[(i % HEADS) * NTBL + i / HEADS] = to_f32(table[i]);
 
     // this lane's token inside the window, and the bias-table row of its (query, key 4q) pair:
     // the entry of key 16kt+4q+j is idx0 - 30kt - j
@@ -227,7 +160,6 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
     for (int k = 0; k < KTP; ++k) wpacc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const float scale = 1.0f / sqrtf((float)D);
     const int per_img = g.nwi * g.nwj;
     const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
     int par = 0;
@@ -401,7 +333,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    st[kt][j] = fmaf(st[kt][j], scale, tblf[(idx0 - 30 * kt - j) * HEADS + hd]);
+                    st[kt][j] += tblf[hd * NTBL + idx0 - 30 * kt - j];
             if (lastrow || lastcol) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
@@ -447,15 +379,15 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             // transposed copies for the key role: [key][query]
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
-                const int base = (16 * kt + 4 * q) * LW + 16 * wv + l16;
+                const int base = (16 * kt + 4 * q) * LD + 16 * wv + l16;
                 pbuf[base] = (uint16_t)(Pb[kt].x & 0xffffu);
-                pbuf[base + LW] = (uint16_t)(Pb[kt].x >> 16);
-                pbuf[base + 2 * LW] = (uint16_t)(Pb[kt].y & 0xffffu);
-                pbuf[base + 3 * LW] = (uint16_t)(Pb[kt].y >> 16);
+                pbuf[base + LD] = (uint16_t)(Pb[kt].x >> 16);
+                pbuf[base + 2 * LD] = (uint16_t)(Pb[kt].y & 0xffffu);
+                pbuf[base + 3 * LD] = (uint16_t)(Pb[kt].y >> 16);
                 dsbuf[base] = (uint16_t)(dSb[kt].x & 0xffffu);
-                dsbuf[base + LW] = (uint16_t)(dSb[kt].x >> 16);
-                dsbuf[base + 2 * LW] = (uint16_t)(dSb[kt].y & 0xffffu);
-                dsbuf[base + 3 * LW] = (uint16_t)(dSb[kt].y >> 16);
+                dsbuf[base + LD] = (uint16_t)(dSb[kt].x >> 16);
+                dsbuf[base + 2 * LD] = (uint16_t)(dSb[kt].y & 0xffffu);
+                dsbuf[base + 3 * LD] = (uint16_t)(dSb[kt].y >> 16);
             }
             // dQ = scale * dS K in both forms: T-form feeds dF, N-form rows feed d w_qkv
             f32x4 dqT[ET];
@@ -472,8 +404,6 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     dqT[et] = mma32(kf, sf, dqT[et]);
                     dqN = mma32(sf, kf, dqN);
                 }
-                dqT[et] *= scale;
-                dqN *= scale;
                 *reinterpret_cast<uint2 *>(gbuf + ((0 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dqN);
             }
             __syncthreads();
@@ -481,8 +411,8 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             // ---- key role: dV = P^T dO, dK = scale * dS^T Q for this wave's 16 keys, both forms ----
             f32x4 dkT[ET], dvT[ET];
             {
-                const uint16_t *prow = pbuf + (16 * wv + l16) * LW + 4 * q;
-                const uint16_t *srow = dsbuf + (16 * wv + l16) * LW + 4 * q;
+                const uint16_t *prow = pbuf + (16 * wv + l16) * LD + 4 * q;
+                const uint16_t *srow = dsbuf + (16 * wv + l16) * LD + 4 * q;
                 uint4 pf[2], sf[2];
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp) {
@@ -509,8 +439,6 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                         dvT[et] = mma32(oa, pf[kp], dvT[et]);
                         dvN = mma32(pf[kp], oa, dvN);
                     }
-                    dkT[et] *= scale;
-                    dkN *= scale;
                     *reinterpret_cast<uint2 *>(gbuf + ((1 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dkN);
                     *reinterpret_cast<uint2 *>(gbuf + ((2 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dvN);
                 }
@@ -578,7 +506,9 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
         }
     }
 
-    // ---- flush: this workgroup's partial sums, in parameter order ----
+    // ---- flush: this workgroup's partial sums, in parameter order.  The packed query weights
+    // carry the 1/sqrt(d) of the scores, so their gradients get it back here. ----
+    const float scale = 1.0f / sqrtf((float)D);
     float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
 #pragma unroll
     for (int k = 0; k < KTP; ++k) {
@@ -611,8 +541,9 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     const int e = 16 * et + 4 * q + j;
                     if (e < D) {
                         const int row = gi * 3 * CG + t * CG + hl * D + e;
-                        if (c < CG) mine[B::P_DWQ + row * CG + c] = dwacc[hd][k][j];
-                        else if (c == CG) mine[B::P_DBQ + row] = dwacc[hd][k][j];
+                        const float v = t == 0 ? dwacc[hd][k][j] * scale : dwacc[hd][k][j];
+                        if (c < CG) mine[B::P_DWQ + row * CG + c] = v;
+                        else if (c == CG) mine[B::P_DBQ + row] = v;
                     }
                 }
             }
@@ -653,8 +584,18 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
     const int i = blockIdx.x * 64 + col;
     float acc = 0.f;
-    if (i < n)
-        for (int w = slice; w < nparts; w += 4) acc += part[(size_t)w * n + i];
+    if (i < n) {
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        int w = slice;
+        for (; w + 12 < nparts; w += 16) {
+            a0 += part[(size_t)w * n + i];
+            a1 += part[(size_t)(w + 4) * n + i];
+            a2 += part[(size_t)(w + 8) * n + i];
+            a3 += part[(size_t)(w + 12) * n + i];
+        }
+        for (; w < nparts; w += 4) a0 += part[(size_t)w * n + i];
+        acc = (a0 + a1) + (a2 + a3);
+    }
     red[slice][col] = acc;
     __syncthreads();
     if (slice == 0 && i < n) {
@@ -687,20 +628,14 @@ int bwd_grid(const Geom &g)
 
 template <class Cf>
 hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
-                   const bf16_t *w_qkv, const bf16_t *b_qkv, const bf16_t *w_proj, const bf16_t *table,
-                   bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj, float *db_proj, float *dtable,
+                   const void *pack_, const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj, float *db_proj, float *dtable,
                    int accumulate, void *ws, hipStream_t s)
 {
     using B = BwdCfg<Cf>;
     static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
-    uint8_t *pack = static_cast<uint8_t *>(ws);
-    float *part = reinterpret_cast<float *>(pack + ((B::PACK_BYTES + 255) & ~size_t(255)));
-    {
-        KernelTimer kt(K_PACK_BWD, s);
-        hipLaunchKernelGGL(pack_bwd_kernel<Cf>, dim3(64), dim3(256), 0, s, w_qkv, b_qkv, w_proj, pack);
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const uint8_t *pack = static_cast<const uint8_t *>(pack_);
+    float *part = static_cast<float *>(ws);
+    hipError_t e = hipSuccess;
     auto kern = fused_bwd_kernel<Cf>;
     static bool attr_done = false;
     if (!attr_done && B::LDS_BYTES > 64 * 1024) {
@@ -744,28 +679,23 @@ bool fused_bwd_supported(const Geom &g)
 
 size_t fused_bwd_ws_bytes(const Geom &g)
 {
-    size_t pack = 0;
-    int tbl = 0;
-#define X(C_, H_, G_)                                                    \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) {                  \
-        pack = BwdCfg<FusedCfg<C_, H_, G_>>::PACK_BYTES;                 \
-        tbl = BwdCfg<FusedCfg<C_, H_, G_>>::P_TOTAL;                     \
-    }
+    int total = 0;
+#define X(C_, H_, G_) \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = BwdCfg<FusedCfg<C_, H_, G_>>::P_TOTAL;
     GSWA_FUSED_SHAPES(X)
 #undef X
-    if (!pack) return 0;
-    return ((pack + 255) & ~size_t(255)) + (((size_t)bwd_grid(g) * tbl * 4 + 255) & ~size_t(255));
+    return ((size_t)bwd_grid(g) * total * 4 + 255) & ~size_t(255);
 }
 
 hipError_t launch_fused_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
-                            const bf16_t *w_qkv, const bf16_t *b_qkv, const bf16_t *w_proj,
-                            const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
-                            float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s)
+                            const void *pack, const bf16_t *table, bf16_t *dx, float *dw_qkv,
+                            float *db_qkv, float *dw_proj, float *db_proj, float *dtable, int accumulate,
+                            void *ws, hipStream_t s)
 {
 #define X(C_, H_, G_)                                                   \
     if (g.C == C_ && g.heads == H_ && g.groups == G_)                   \
-        return run_bwd<FusedCfg<C_, H_, G_>>(g, x, dy, attn, w_qkv, b_qkv, w_proj, table, dx, dw_qkv, db_qkv, \
-                                             dw_proj, db_proj, dtable, accumulate, ws, s);
+        return run_bwd<FusedCfg<C_, H_, G_>>(g, x, dy, attn, pack, table, dx, dw_qkv, db_qkv, dw_proj,      \
+                                             db_proj, dtable, accumulate, ws, s);
     GSWA_FUSED_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

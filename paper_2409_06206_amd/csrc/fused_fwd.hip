@@ -11,41 +11,29 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------
-// Weight packing: rewrites w_qkv / w_proj / biases into the lane-major fragment order the
-// fused kernel copies into LDS.  Zero padding of head width (to 16*ET) and of the group
-// width (to 32*KS) happens here, so padded k-slots and rows contribute exact zeros.
+// Parameter packing (see FusedCfg): every thread assembles the operand of one (fragment, lane).
 // ---------------------------------------------------------------------------------------
-template <class Cf>
-__global__ __launch_bounds__(256) void pack_fwd_kernel(const bf16_t *__restrict__ w_qkv,
-                                                       const bf16_t *__restrict__ b_qkv,
-                                                       const bf16_t *__restrict__ w_proj,
-                                                       const bf16_t *__restrict__ b_proj,
-                                                       uint8_t *__restrict__ pack)
+__device__ __forceinline__ uint32_t bf16_scaled(bf16_t w, float sc)
 {
-    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET, KS = Cf::KS;
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
-    uint16_t *wq = reinterpret_cast<uint16_t *>(pack + Cf::OFF_WQ);
-    uint16_t *wc = reinterpret_cast<uint16_t *>(pack + Cf::OFF_WC);
-    uint16_t *wp = reinterpret_cast<uint16_t *>(pack + Cf::OFF_WP);
-    float *bias = reinterpret_cast<float *>(pack + Cf::OFF_BIAS);
+    return sc == 1.0f ? (uint32_t)w.bits : (uint32_t)f32_to_bf16_bits(to_f32(w) * sc);
+}
 
-    for (int i = gid; i < Cf::N_WQ * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
-        int f = i >> 6;
-        const int ks = f % KS; f /= KS;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3;
-        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int e = 16 * et + l16;
-        for (int s = 0; s < 8; ++s) {
-            const int c = 32 * ks + 8 * q + s;
-            uint16_t v = 0;
-            if (e < D && c < CG) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c].bits;
-            wq[(size_t)i * 8 + s] = v;
-        }
-    }
-    for (int i = gid; i < Cf::N_WC * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
+template <class Cf>
+__global__ __launch_bounds__(256) void pack_params_kernel(const bf16_t *__restrict__ w_qkv,
+                                                          const bf16_t *__restrict__ b_qkv,
+                                                          const bf16_t *__restrict__ w_proj,
+                                                          const bf16_t *__restrict__ b_proj,
+                                                          uint8_t *__restrict__ pack)
+{
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET;
+    constexpr int KS = Cf::KS, KSC = Cf::KSC;
+    constexpr int E_WC = Cf::N_WC * 64, E_WP = Cf::N_WP * 64, E_WQ = Cf::N_WQ * 64, E_WPT = Cf::N_WPT * 64,
+                  E_WQT = Cf::N_WQT * 64, E_BIAS = 4 * C;
+    const float qscale = 1.0f / sqrtf((float)D);
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    int l16 = i & 15, q = (i >> 4) & 3; // lane coordinates inside the current segment
+
+    if (i < E_WC) { // cascade input: m/n-index l16 -> out feature e; k-slots 4q+j -> prev-group channel
         int f = i >> 6;
         const int etp = f % ET; f /= ET;
         const int hlp = f % HG; f /= HG;
@@ -54,28 +42,93 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const bf16_t *__restrict_
         const int hl = f % HG;
         const int gi = f / HG + 1;
         const int e = 16 * et + l16;
+        uint32_t v[4];
         for (int j = 0; j < 4; ++j) {
             const int ep = 16 * etp + 4 * q + j;
-            uint16_t v = 0;
-            if (e < D && ep < D) v = w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + ep].bits;
-            wc[(size_t)i * 4 + j] = v;
+            v[j] = (e < D && ep < D)
+                       ? bf16_scaled(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + ep], t == 0 ? qscale : 1.0f)
+                       : 0u;
         }
+        reinterpret_cast<uint2 *>(pack + Cf::P_WC)[i] = make_uint2(v[0] | v[1] << 16, v[2] | v[3] << 16);
+        return;
     }
-    for (int i = gid; i < Cf::N_WP * 64; i += stride) {
-        const int lane = i & 63, l16 = lane & 15, q = lane >> 4;
+    i -= E_WC;
+    if (i < E_WP) { // Wproj: l16 -> output channel o; k-slots 4q+j -> input channel (hd, e)
         int f = i >> 6;
         const int et = f % ET; f /= ET;
         const int hd = f % HEADS;
         const int ot = f / HEADS;
         const int o = 16 * ot + l16;
+        uint32_t v[4];
         for (int j = 0; j < 4; ++j) {
             const int e = 16 * et + 4 * q + j;
-            uint16_t v = 0;
-            if (o < C && e < D) v = w_proj[(size_t)o * C + hd * D + e].bits;
-            wp[(size_t)i * 4 + j] = v;
+            v[j] = (o < C && e < D) ? (uint32_t)w_proj[(size_t)o * C + hd * D + e].bits : 0u;
         }
+        reinterpret_cast<uint2 *>(pack + Cf::P_WP)[i] = make_uint2(v[0] | v[1] << 16, v[2] | v[3] << 16);
+        return;
     }
-    for (int i = gid; i < 4 * C; i += stride) bias[i] = i < 3 * C ? to_f32(b_qkv[i]) : to_f32(b_proj[i - 3 * C]);
+    i -= E_WP;
+    if (i < E_WQ) { // Wqkv on the x slice: l16 -> out feature e; k-slots 8q+s -> channel 32ks+8q+s
+        int f = i >> 6;
+        const int ks = f % KS; f /= KS;
+        const int et = f % ET; f /= ET;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const int e = 16 * et + l16;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int c = 32 * ks + 8 * q + s;
+            v[s] = (e < D && c < CG)
+                       ? bf16_scaled(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c], t == 0 ? qscale : 1.0f)
+                       : 0u;
+        }
+        reinterpret_cast<uint4 *>(pack + Cf::P_WQ)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        return;
+    }
+    i -= E_WQ;
+    if (i < E_BIAS) { // fp32 biases; the q third of every group scaled like its weights
+        float *bias = reinterpret_cast<float *>(pack + Cf::P_BIAS);
+        if (i < 3 * C) bias[i] = to_f32(b_qkv[i]) * ((i % (3 * CG)) < CG ? qscale : 1.0f);
+        else bias[i] = to_f32(b_proj[i - 3 * C]);
+        return;
+    }
+    i -= E_BIAS; // not a multiple of 64: re-derive the lane coordinates
+    l16 = i & 15;
+    q = (i >> 4) & 3;
+    if (i < E_WPT) { // Wproj^T: l16 -> input channel (hd, e); k-slots 8q+s -> output channel o
+        int f = i >> 6;
+        const int ks = f % KSC; f /= KSC;
+        const int et = f % ET;
+        const int hd = f / ET;
+        const int e = 16 * et + l16;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int o = 32 * ks + 8 * q + s;
+            v[s] = (e < D && o < C) ? (uint32_t)w_proj[(size_t)o * C + hd * D + e].bits : 0u;
+        }
+        reinterpret_cast<uint4 *>(pack + Cf::P_WPT)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        return;
+    }
+    i -= E_WPT;
+    if (i < E_WQT) { // Wqkv^T: l16 -> input channel hlp*D + 16etp + l16; k-slots 4q+j -> out feature (t,hl,e)
+        int f = i >> 6;
+        const int etp = f % ET; f /= ET;
+        const int hlp = f % HG; f /= HG;
+        const int et = f % ET; f /= ET;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const int cp = 16 * etp + l16;
+        uint32_t v[4];
+        for (int j = 0; j < 4; ++j) {
+            const int e = 16 * et + 4 * q + j;
+            v[j] = (cp < D && e < D)
+                       ? bf16_scaled(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + cp], t == 0 ? qscale : 1.0f)
+                       : 0u;
+        }
+        reinterpret_cast<uint2 *>(pack + Cf::P_WQT)[i] = make_uint2(v[0] | v[1] << 16, v[2] | v[3] << 16);
+    }
 }
 
 // fragment ids inside the packed arrays
@@ -112,7 +165,7 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l16 = lane & 15, q = lane >> 4;
 
     // ---- set-up: weights into LDS, bias table into registers in score-fragment order ----
-    for (int i = tid; i < (int)(Cf::PACK_BYTES / 16); i += 256)
+    for (int i = tid; i < (int)(Cf::FWD_PACK_BYTES / 16); i += 256)
         reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack)[i];
     uint16_t *tstage = reinterpret_cast<uint16_t *>(kbuf);
     for (int i = tid; i < NTBL * HEADS; i += 256) tstage[i] = table[i].bits;
@@ -146,7 +199,6 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
     for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
     __syncthreads();
 
-    const float scale = 1.0f / sqrtf((float)D);
     const int per_img = g.nwi * g.nwj;
     int buf = 0;
 
@@ -238,7 +290,7 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t pr = bias_frag[hd][kt * 2 + (j >> 1)];
                     const float bv = (j & 1) ? bf16_hi(pr) : bf16_lo(pr);
-                    st[kt][j] = fmaf(st[kt][j], scale, bv);
+                    st[kt][j] += bv;
                 }
             if (lastrow || lastcol) {
 #pragma unroll
@@ -332,8 +384,10 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
 {
     uint8_t *pack = static_cast<uint8_t *>(ws);
     {
+        constexpr int entries = (Cf::N_WC + Cf::N_WP + Cf::N_WQ + Cf::N_WPT + Cf::N_WQT) * 64 + 4 * Cf::C;
         KernelTimer kt(K_PACK_FWD, s);
-        hipLaunchKernelGGL(pack_fwd_kernel<Cf>, dim3(64), dim3(256), 0, s, w_qkv, b_qkv, w_proj, b_proj, pack);
+        hipLaunchKernelGGL(pack_params_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, b_qkv,
+                           w_proj, b_proj, pack);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -369,10 +423,10 @@ bool fused_fwd_supported(const Geom &g)
     return false;
 }
 
-size_t fused_fwd_ws_bytes(const Geom &g)
+size_t fused_pack_bytes(const Geom &g)
 {
 #define X(C_, H_, G_) \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) return FusedCfg<C_, H_, G_>::PACK_BYTES;
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) return FusedCfg<C_, H_, G_>::P_END;
     GSWA_FUSED_SHAPES(X)
 #undef X
     return 0;
@@ -380,11 +434,11 @@ size_t fused_fwd_ws_bytes(const Geom &g)
 
 hipError_t launch_fused_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
                             const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table,
-                            bf16_t *y, bf16_t *attn_out, void *ws, hipStream_t s)
+                            bf16_t *y, bf16_t *attn_out, void *pack, hipStream_t s)
 {
 #define X(C_, H_, G_)                                                  \
     if (g.C == C_ && g.heads == H_ && g.groups == G_)                  \
-        return run_fwd<FusedCfg<C_, H_, G_>>(g, x, w_qkv, b_qkv, w_proj, b_proj, table, y, attn_out, ws, s);
+        return run_fwd<FusedCfg<C_, H_, G_>>(g, x, w_qkv, b_qkv, w_proj, b_proj, table, y, attn_out, pack, s);
     GSWA_FUSED_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

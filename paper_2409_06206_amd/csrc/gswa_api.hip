@@ -64,7 +64,8 @@ size_t elem_size(const gswa_desc *d) { return d->dtype == GSWA_F32 ? 4 : 2; }
 
 struct Sizes {
     size_t saved, qkv, fwd_ws, bwd_ws;
-    size_t fused_bwd_ws; // packed weights + partial sums of the fused backward
+    size_t act;          // bytes of the saved [T, C] activation at the start of `saved`
+    size_t fused_bwd_ws; // partial sums of the fused backward
     bool fused_fwd, fused_bwd;
 };
 
@@ -82,9 +83,14 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.fwd_ws = s.qkv;
     s.bwd_ws = 2 * s.qkv;
     s.fused_fwd = use_fused_fwd(d, g);
-    if (s.fused_fwd) s.fwd_ws = align256(fused_fwd_ws_bytes(g));
-    s.fused_bwd = d->dtype == GSWA_BF16 && !(d->flags & GSWA_FORCE_STAGED) && fused_bwd_supported(g);
+    s.fused_bwd = s.fused_fwd && fused_bwd_supported(g);
     s.fused_bwd_ws = 0;
+    s.act = s.saved;
+    if (s.fused_fwd) {
+        // the packed parameters ride behind the saved activation (training) or in ws (inference)
+        s.fwd_ws = align256(fused_pack_bytes(g));
+        s.saved = s.act + s.fwd_ws;
+    }
     if (s.fused_bwd) {
         s.fused_bwd_ws = align256(fused_bwd_ws_bytes(g));
         s.bwd_ws = s.fused_bwd_ws;
@@ -185,14 +191,13 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     return GSWA_OK;
 }
 
-int backward_fused(const Geom &g, uint32_t flags, const bf16_t *x, const bf16_t *dy, const bf16_t *w_qkv,
-                   const bf16_t *b_qkv, const bf16_t *w_proj, const bf16_t *table, const bf16_t *attn,
-                   bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj, float *db_proj, float *dtable,
-                   char *ws, hipStream_t st)
+int backward_fused(const Geom &g, const Sizes &sz, uint32_t flags, const bf16_t *x, const bf16_t *dy,
+                   const bf16_t *table, const char *saved, bf16_t *dx, float *dw_qkv, float *db_qkv,
+                   float *dw_proj, float *db_proj, float *dtable, char *ws, hipStream_t st)
 {
     const int accumulate = (flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
-    GSWA_HIP(launch_fused_bwd(g, x, dy, attn, w_qkv, b_qkv, w_proj, table, dx, dw_qkv, db_qkv, dw_proj,
-                              db_proj, dtable, accumulate, ws, st));
+    GSWA_HIP(launch_fused_bwd(g, x, dy, reinterpret_cast<const bf16_t *>(saved), saved + sz.act, table, dx,
+                              dw_qkv, db_qkv, dw_proj, db_proj, dtable, accumulate, ws, st));
     return GSWA_OK;
 }
 
@@ -229,9 +234,10 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
                                      (const float *)w_proj, (const float *)b_proj,
                                      (const float *)bias_table, (float *)y, (float *)saved, (char *)ws, st);
     if (s.fused_fwd) {
+        void *pack = saved ? static_cast<void *>(static_cast<char *>(saved) + s.act) : ws;
         hipError_t e = launch_fused_fwd(g, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
                                         (const bf16_t *)w_proj, (const bf16_t *)b_proj,
-                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, ws, st);
+                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, pack, st);
         return e == hipSuccess ? GSWA_OK : hip_fail(e);
     }
     return forward_staged<bf16_t>(g, s, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
@@ -261,10 +267,10 @@ int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const vo
                                       (float *)dw_qkv, (float *)db_qkv, (float *)dw_proj,
                                       (float *)db_proj, (float *)dbias_table, (char *)ws, st);
     if (s.fused_bwd)
-        return backward_fused(g, desc->flags, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)w_qkv,
-                              (const bf16_t *)b_qkv, (const bf16_t *)w_proj, (const bf16_t *)bias_table,
-                              (const bf16_t *)saved, (bf16_t *)dx, (float *)dw_qkv, (float *)db_qkv,
-                              (float *)dw_proj, (float *)db_proj, (float *)dbias_table, (char *)ws, st);
+        return backward_fused(g, s, desc->flags, (const bf16_t *)x, (const bf16_t *)dy,
+                              (const bf16_t *)bias_table, (const char *)saved, (bf16_t *)dx, (float *)dw_qkv,
+                              (float *)db_qkv, (float *)dw_proj, (float *)db_proj, (float *)dbias_table,
+                              (char *)ws, st);
     return backward_staged<bf16_t>(g, s, desc->flags, (const bf16_t *)x, (const bf16_t *)dy,
                                    (const bf16_t *)w_qkv, (const bf16_t *)b_qkv, (const bf16_t *)w_proj,
                                    (const bf16_t *)bias_table, (const bf16_t *)saved, (bf16_t *)dx,
