@@ -40,13 +40,14 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr size_t FWD_PACK_BYTES = P_WPT;        // [0, P_WPT)
     static constexpr size_t BWD_PACK_OFF = P_WQ;           // [P_WQ, P_END)
     static constexpr size_t BWD_PACK_BYTES = P_END - P_WQ;
-    // forward LDS: the packed range, then per-head K and V exchange buffers (double buffered)
+    // forward LDS: the packed range, then the per-head K and V exchange buffers.  Kept under
+    // 52 KB so that three workgroups share a compute unit.
     static constexpr size_t OFF_WC = P_WC, OFF_WP = P_WP, OFF_WQ = P_WQ, OFF_BIAS = P_BIAS;
     static constexpr int VT_LD = 68;
     static constexpr size_t OFF_K = FWD_PACK_BYTES;
-    static constexpr size_t K_BYTES = (size_t)2 * 4 * ET * 64 * 8;
+    static constexpr size_t K_BYTES = (size_t)4 * ET * 64 * 8;
     static constexpr size_t OFF_VT = OFF_K + K_BYTES;
-    static constexpr size_t VT_BYTES = (size_t)2 * 16 * ET * VT_LD * 2;
+    static constexpr size_t VT_BYTES = (size_t)16 * ET * VT_LD * 2;
     static constexpr size_t FWD_LDS_BYTES = OFF_VT + VT_BYTES;
 };
 

@@ -142,7 +142,7 @@ template <class Cf> __device__ __forceinline__ constexpr int fc(int gi, int hl, 
 }
 
 template <class Cf>
-__global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
+__global__ __launch_bounds__(256, 3) void fused_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
                                                         const uint8_t *__restrict__ pack,
                                                         const bf16_t *__restrict__ table,
                                                         bf16_t *__restrict__ y, bf16_t *__restrict__ attn)
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
     constexpr int ET = Cf::ET, KS = Cf::KS, OT = Cf::OT, VT_LD = Cf::VT_LD;
     constexpr int M = 8, NTBL = (2 * M - 1) * (2 * M - 1);
     static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0, "dword-granular loads and stores");
-    static_assert((size_t)NTBL * HEADS * 2 <= Cf::K_BYTES, "table staging aliases the K buffers");
+    static_assert((size_t)NTBL * HEADS * 2 <= Cf::K_BYTES + Cf::VT_BYTES, "table staging aliases the K buffers");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint4 *wq = reinterpret_cast<const uint4 *>(lds + Cf::OFF_WQ);
@@ -200,7 +200,6 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
     __syncthreads();
 
     const int per_img = g.nwi * g.nwj;
-    int buf = 0;
 
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
         const int b = win / per_img;
@@ -268,8 +267,8 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
                 Qb[et] = pack_bf16x4(qT[et]);
-                kbuf[((buf * 4 + wv) * ET + et) * 64 + lane] = pack_bf16x4(kT[et]);
-                *reinterpret_cast<uint2 *>(vt + ((buf * ET + et) * 16 + l16) * VT_LD + 16 * wv + 4 * q) =
+                kbuf[(wv * ET + et) * 64 + lane] = pack_bf16x4(kT[et]);
+                *reinterpret_cast<uint2 *>(vt + (et * 16 + l16) * VT_LD + 16 * wv + 4 * q) =
                     pack_bf16x4(vv[et]);
             }
             __syncthreads();
@@ -281,7 +280,7 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
                 st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int et = 0; et < ET; ++et)
-                    st[kt] = mma16(kbuf[((buf * 4 + kt) * ET + et) * 64 + lane], Qb[et], st[kt]);
+                    st[kt] = mma16(kbuf[(kt * ET + et) * 64 + lane], Qb[et], st[kt]);
             }
             float mx = -INFINITY;
 #pragma unroll
@@ -324,7 +323,7 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
                 f32x4 oT = f32x4{0.f, 0.f, 0.f, 0.f};
-                const uint16_t *vrow = vt + ((buf * ET + et) * 16 + l16) * VT_LD + 4 * q;
+                const uint16_t *vrow = vt + (et * 16 + l16) * VT_LD + 4 * q;
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp) {
                     const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp);
@@ -341,7 +340,7 @@ __global__ __launch_bounds__(256) void fused_fwd_kernel(Geom g, const bf16_t *__
                     if (e0 + 2 < D) dst[1] = Ob[hd][et].y;
                 }
             }
-            buf ^= 1;
+            __syncthreads(); // K and V of this head are consumed; the next head may overwrite them
         }
 
         // ---- Y^T = Wproj A^T + b: rows = output channels, column = this lane's token ----
@@ -399,7 +398,7 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    int grid = 2 * device_cu_count();
+    int grid = 3 * device_cu_count();
     if (grid > g.nW) grid = g.nW;
     {
         KernelTimer kt(K_FUSED_FWD, s);
