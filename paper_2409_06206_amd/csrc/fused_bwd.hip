@@ -39,7 +39,8 @@ template <class Cf> struct BwdCfg {
     static constexpr size_t PACK_BYTES = Cf::BWD_PACK_BYTES;
     // LDS beyond the packed weights
     static constexpr int LD = 68; // pitch (bf16) of rows read 4 at a time
-    static constexpr int LW = 72; // pitch (bf16) of rows read 8 at a time
+    static constexpr int LW = 68; // pitch (bf16) of rows read 8 at a time (as two 8-byte halves:
+                                  // 34 dwords keeps every 16-lane phase on distinct banks)
     static constexpr size_t SZ_FRAG = (size_t)4 * ET * 64 * 8;
     static constexpr size_t SZ_ROWS = (size_t)16 * ET * LD * 2;
     static constexpr size_t SZ_SQ = (size_t)64 * LW * 2; // P / dS [key][query]; also dY^T / A^T rows
@@ -235,8 +236,10 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                 const uint16_t *br = abuf + (16 * ct + l16) * LW + 8 * q;
 #pragma unroll
                 for (int kp = 0; kp < 2; ++kp)
-                    wpacc[k] = mma32(*reinterpret_cast<const uint4 *>(ar + 32 * kp),
-                                     *reinterpret_cast<const uint4 *>(br + 32 * kp), wpacc[k]);
+                    wpacc[k] = mma32(cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
+                                         *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4)),
+                                     cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
+                                         *reinterpret_cast<const uint2 *>(br + 32 * kp + 4)), wpacc[k]);
             }
         }
 
@@ -483,8 +486,10 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     const uint16_t *br = fbuf + (16 * ct + l16) * LW + 8 * q;
 #pragma unroll
                     for (int kp = 0; kp < 2; ++kp)
-                        dwacc[hd][k] = mma32(*reinterpret_cast<const uint4 *>(ar + 32 * kp),
-                                             *reinterpret_cast<const uint4 *>(br + 32 * kp), dwacc[hd][k]);
+                        dwacc[hd][k] = mma32(cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
+                                                 *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4)),
+                                             cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
+                                                 *reinterpret_cast<const uint2 *>(br + 32 * kp + 4)), dwacc[hd][k]);
                 }
             }
             par ^= 1;

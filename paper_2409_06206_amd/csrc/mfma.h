@@ -53,18 +53,25 @@ __device__ __forceinline__ f32x4 mma32(uint4 a, uint4 b, f32x4 c)
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-// all-reduce over the four lanes that share l16 (q = 0..3)
+// all-reduce over the four lanes that share l16 (q = 0..3), without touching LDS:
+// v_permlane16_swap(v, v) returns {rows 0,0,2,2 of v; rows 1,1,3,3 of v} (rows = 16 lanes), and
+// v_permlane32_swap(w, w) returns {lower half twice; upper half twice}.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float qgroup_max(float v)
 {
-    v = fmaxf(v, __shfl_xor(v, 16));
-    v = fmaxf(v, __shfl_xor(v, 32));
-    return v;
+    const unsigned u = __float_as_uint(v);
+    u32x2 r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned w = __float_as_uint(fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])));
+    r = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float qgroup_sum(float v)
 {
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
+    const unsigned u = __float_as_uint(v);
+    u32x2 r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned w = __float_as_uint(__uint_as_float(r[0]) + __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 } // namespace gswa
