@@ -19,7 +19,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <class Cf> struct BwdCfg {
+template <class Cf, int HB_, int HE_> struct BwdCfg {
     static constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
     static constexpr int ET = Cf::ET, KS = Cf::KS;
     static constexpr int KSC = (C + 31) / 32; // K=32 steps over all C channels of dy
@@ -31,12 +31,22 @@ template <class Cf> struct BwdCfg {
     static constexpr int KT = (NT + 3) / 4;         // tiles per wave
     static constexpr int OTP = (C + 15) / 16, CTP = C / 16 + 1;
     static constexpr int NTP = OTP * CTP, KTP = (NTP + 3) / 4;
-    // packed parameters: the backward range [WQ | BIAS | WPT | WQT] of the buffer forward filled
+    // heads [HB, HE) of this launch (whole groups unless G == 1); the launch that holds the last
+    // head also produces d w_proj / d b_proj
+    static constexpr int HB = HB_, HE = HE_, NH = HE - HB;
+    static constexpr bool FIRST = HE == HEADS;
+    static constexpr int GB = HB / HG, GE = (HE - 1) / HG; // lowest and highest group of the chunk
+    static_assert(NH > 0 && (G == 1 || (HB % HG == 0 && HE % HG == 0)), "chunks are whole groups");
+    // packed parameters of these heads, copied from the buffer forward filled: [WQ | BIAS | WPT | WQT]
+    static constexpr int N_WQ = NH * 3 * ET * KS, N_WPT = NH * ET * KSC, N_WQT = NH * 3 * ET * HG * ET;
+    static constexpr size_t SRC_WQ = Cf::P_WQ + (size_t)HB * 3 * ET * KS * 1024;
+    static constexpr size_t SRC_WPT = Cf::P_WPT + (size_t)HB * ET * KSC * 1024;
+    static constexpr size_t SRC_WQT = Cf::P_WQT + (size_t)HB * 3 * ET * HG * ET * 512;
     static constexpr size_t OFF_WQ = 0;
-    static constexpr size_t OFF_BIAS = Cf::P_BIAS - Cf::P_WQ;
-    static constexpr size_t OFF_WPT = Cf::P_WPT - Cf::P_WQ;
-    static constexpr size_t OFF_WQT = Cf::P_WQT - Cf::P_WQ;
-    static constexpr size_t PACK_BYTES = Cf::BWD_PACK_BYTES;
+    static constexpr size_t OFF_BIAS = OFF_WQ + (size_t)N_WQ * 1024;
+    static constexpr size_t OFF_WPT = OFF_BIAS + (size_t)16 * C;
+    static constexpr size_t OFF_WQT = OFF_WPT + (size_t)N_WPT * 1024;
+    static constexpr size_t PACK_BYTES = OFF_WQT + (size_t)N_WQT * 512;
     // LDS beyond the packed weights
     static constexpr int LD = 68; // pitch (bf16) of rows read 4 at a time
     static constexpr int LW = 68; // pitch (bf16) of rows read 8 at a time (as two 8-byte halves:
@@ -44,13 +54,13 @@ template <class Cf> struct BwdCfg {
     static constexpr size_t SZ_FRAG = (size_t)4 * ET * 64 * 8;
     static constexpr size_t SZ_ROWS = (size_t)16 * ET * LD * 2;
     static constexpr size_t SZ_SQ = (size_t)64 * LW * 2; // P / dS [key][query]; also dY^T / A^T rows
-    static constexpr size_t OFF_TBLF = PACK_BYTES;             // fp32 bias table [HEADS][225]
-    static constexpr size_t OFF_KB = OFF_TBLF + (((size_t)TBL_N * 4 + 15) & ~size_t(15));
+    static constexpr size_t OFF_TBLF = PACK_BYTES;             // fp32 bias table [NH][225]
+    static constexpr size_t OFF_KB = OFF_TBLF + (((size_t)NH * NTBL * 4 + 15) & ~size_t(15));
     static constexpr size_t OFF_VB = OFF_KB + SZ_FRAG;
     static constexpr size_t OFF_KT = OFF_VB + SZ_FRAG;         // K^T rows [e][key]
-    static constexpr size_t OFF_QT = OFF_KT + SZ_ROWS;         // Q^T rows [e][query], double buffered
-    static constexpr size_t OFF_DOT = OFF_QT + 2 * SZ_ROWS;    // dO^T rows [e][query], double buffered
-    static constexpr size_t OFF_P = OFF_DOT + 2 * SZ_ROWS;
+    static constexpr size_t OFF_QT = OFF_KT + SZ_ROWS;         // Q^T rows [e][query]
+    static constexpr size_t OFF_DOT = OFF_QT + SZ_ROWS;        // dO^T rows [e][query]
+    static constexpr size_t OFF_P = OFF_DOT + SZ_ROWS;
     static constexpr size_t OFF_DS = OFF_P + SZ_SQ;
     static constexpr size_t OFF_DQKV = OFF_DS + SZ_SQ;         // d(q|k|v)^T rows [(t,e)][token]
     static constexpr size_t SZ_DQKV = (size_t)3 * ET * 16 * LW * 2;
@@ -92,15 +102,17 @@ __device__ __forceinline__ uint4 select_slot(int target, int first)
 
 constexpr bool ranges_overlap(int a0, int a1, int b0, int b1) { return a0 < b1 && b0 < a1; }
 
-template <class Cf>
-__global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
+template <class Cf, int HB, int HE>
+__global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                                                         const bf16_t *__restrict__ dy,
                                                         const bf16_t *__restrict__ attn,
                                                         const uint8_t *__restrict__ pack,
                                                         const bf16_t *__restrict__ table,
-                                                        bf16_t *__restrict__ dx, float *__restrict__ part)
+                                                        bf16_t *dx, float *__restrict__ part)
 {
-    using B = BwdCfg<Cf>;
+    using B = BwdCfg<Cf, HB, HE>;
+    constexpr int NH = B::NH, GB = B::GB, GE = B::GE;
+    constexpr bool FIRST = B::FIRST;
     constexpr int C = B::C, D = B::D, CG = B::CG, HG = B::HG, HEADS = B::HEADS, G = B::G;
     constexpr int ET = B::ET, KS = B::KS, KSC = B::KSC, LD = B::LD, LW = B::LW, NTBL = B::NTBL;
     constexpr int CT = B::CT, NT = B::NT, KT = B::KT, OTP = B::OTP, CTP = B::CTP, NTP = B::NTP, KTP = B::KTP;
@@ -127,9 +139,15 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6); // wave index, held in a scalar register
 
-    for (int i = tid; i < (int)(B::PACK_BYTES / 16); i += 256)
-        reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack + Cf::BWD_PACK_OFF)[i];
-    for (int i = tid; i < NTBL * HEADS; i += 256) tblf[(i % HEADS) * NTBL + i / HEADS] = to_f32(table[i]);
+    for (int i = tid; i < (int)((B::OFF_BIAS - B::OFF_WQ) / 16); i += 256)
+        reinterpret_cast<uint4 *>(lds + B::OFF_WQ)[i] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQ)[i];
+    for (int i = tid; i < C; i += 256)
+        reinterpret_cast<uint4 *>(lds + B::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
+    for (int i = tid; i < (int)((B::OFF_WQT - B::OFF_WPT) / 16); i += 256)
+        reinterpret_cast<uint4 *>(lds + B::OFF_WPT)[i] = reinterpret_cast<const uint4 *>(pack + B::SRC_WPT)[i];
+    for (int i = tid; i < (int)((B::PACK_BYTES - B::OFF_WQT) / 16); i += 256)
+        reinterpret_cast<uint4 *>(lds + B::OFF_WQT)[i] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQT)[i];
+    for (int i = tid; i < NTBL * NH; i += 256) tblf[i] = to_f32(table[(i % NTBL) * HEADS + HB + i / NTBL]);
 
     // this lane's token inside the window, and the bias-table row of its (query, key 4q) pair:
     // the entry of key 16kt+4q+j is idx0 - 30kt - j
@@ -150,9 +168,9 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     }
     __syncthreads();
 
-    f32x4 tblacc[HEADS][4], dwacc[HEADS][KT], wpacc[KTP];
+    f32x4 tblacc[NH][4], dwacc[NH][KT], wpacc[KTP];
 #pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd) {
+    for (int hd = 0; hd < NH; ++hd) {
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) tblacc[hd][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -163,7 +181,6 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
 
     const int per_img = g.nwi * g.nwj;
     const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
-    int par = 0;
 
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
         const int b = win / per_img;
@@ -185,11 +202,13 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 uint32_t xv[4], av[4];
+                const bool need_x = gi >= GB && gi <= GE;
+                const bool need_a = FIRST || (gi >= GB - 1 && gi < GE);
 #pragma unroll
                 for (int dw = 0; dw < 4; ++dw) {
                     const int c = 32 * ks + 8 * q + 2 * dw;
-                    xv[dw] = c < CG ? xrow[(gi * CG + c) >> 1] : 0u;
-                    av[dw] = c < CG ? arow[(gi * CG + c) >> 1] : 0u;
+                    xv[dw] = (need_x && c < CG) ? xrow[(gi * CG + c) >> 1] : 0u;
+                    av[dw] = (need_a && c < CG) ? arow[(gi * CG + c) >> 1] : 0u;
                 }
                 xf[gi][ks] = make_uint4(xv[0], xv[1], xv[2], xv[3]);
                 af[gi][ks] = make_uint4(av[0], av[1], av[2], av[3]);
@@ -206,6 +225,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
         }
 
         // ---- d w_proj, d b_proj: dY^T and A^T rows [channel][token] through LDS, K = 64 tokens ----
+        if (FIRST) {
 #pragma unroll
         for (int ot = 0; ot < OTP; ++ot) {
             f32x4 tN = mma32(dyf[ot >> 1], select_slot(16 * ot + l16, 32 * (ot >> 1) + 8 * q),
@@ -242,11 +262,13 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                                          *reinterpret_cast<const uint2 *>(br + 32 * kp + 4)), wpacc[k]);
             }
         }
+        }
 
         f32x4 dFT[HG][ET], cascT[HG][ET];
 #pragma unroll
-        for (int hdr = 0; hdr < HEADS; ++hdr) {
-            const int hd = HEADS - 1 - hdr; // groups in reverse order
+        for (int hdr = 0; hdr < NH; ++hdr) {
+            const int hd = HE - 1 - hdr; // groups in reverse order
+            const int hx = hd - HB;      // index into this launch's fragments and accumulators
             const int gi = hd / HG, hl = hd % HG;
             const bool casc_in = gi > 0 && g.cascade;      // this group's input has a cascade term
             const bool casc_out = gi < G - 1 && g.cascade; // this group's output feeds the next group
@@ -261,10 +283,21 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             f32x4 dOT[ET];
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
-                dOT[et] = casc_out ? cascT[hl][et] : f32x4{0.f, 0.f, 0.f, 0.f};
+                dOT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (casc_out) {
+                    if (FIRST || gi < GE) {
+                        dOT[et] = cascT[hl][et];
+                    } else { // the next group was processed by the previous launch: its dF is the dx slice
+                        const int e0 = 16 * et + 4 * q;
+                        const uint32_t *src =
+                            reinterpret_cast<const uint32_t *>(dx + tok * C + (gi + 1) * CG + hl * D + e0);
+                        const uint32_t lo = e0 < D ? src[0] : 0u, hi = e0 + 2 < D ? src[1] : 0u;
+                        dOT[et] = f32x4{bf16_lo(lo), bf16_hi(lo), bf16_lo(hi), bf16_hi(hi)};
+                    }
+                }
 #pragma unroll
                 for (int ks = 0; ks < KSC; ++ks)
-                    dOT[et] = mma32(wpt[((hd * ET + et) * KSC + ks) * 64 + lane], dyf[ks], dOT[et]);
+                    dOT[et] = mma32(wpt[((hx * ET + et) * KSC + ks) * 64 + lane], dyf[ks], dOT[et]);
             }
             // ---- recompute q, k (both forms) and v (T-form) of this wave's tokens ----
             f32x4 qT[ET], qN[ET], kT[ET], kN[ET], vT[ET];
@@ -284,9 +317,9 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                 }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const uint4 fq_ = wq[fq<Cf>(hd, 0, et, ks) * 64 + lane];
-                    const uint4 fk_ = wq[fq<Cf>(hd, 1, et, ks) * 64 + lane];
-                    const uint4 fv_ = wq[fq<Cf>(hd, 2, et, ks) * 64 + lane];
+                    const uint4 fq_ = wq[fq<Cf>(hx, 0, et, ks) * 64 + lane];
+                    const uint4 fk_ = wq[fq<Cf>(hx, 1, et, ks) * 64 + lane];
+                    const uint4 fv_ = wq[fq<Cf>(hx, 2, et, ks) * 64 + lane];
                     qT[et] = mma32(fq_, xf[gi][ks], qT[et]);
                     qN[et] = mma32(xf[gi][ks], fq_, qN[et]);
                     kT[et] = mma32(fk_, xf[gi][ks], kT[et]);
@@ -311,8 +344,8 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                 vb[(wv * ET + et) * 64 + lane] = pack_bf16x4(vT[et]);
                 const int row = (16 * et + l16) * LD + 16 * wv + 4 * q;
                 *reinterpret_cast<uint2 *>(ktr + row) = pack_bf16x4(kN[et]);
-                *reinterpret_cast<uint2 *>(qtr + par * 16 * ET * LD + row) = pack_bf16x4(qN[et]);
-                uint16_t *dst = dotr + par * 16 * ET * LD + (16 * et + 4 * q) * LD + 16 * wv + l16;
+                *reinterpret_cast<uint2 *>(qtr + row) = pack_bf16x4(qN[et]);
+                uint16_t *dst = dotr + (16 * et + 4 * q) * LD + 16 * wv + l16;
                 dst[0] = (uint16_t)(dOb[et].x & 0xffffu);
                 dst[LD] = (uint16_t)(dOb[et].x >> 16);
                 dst[2 * LD] = (uint16_t)(dOb[et].y & 0xffffu);
@@ -336,7 +369,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    st[kt][j] += tblf[hd * NTBL + idx0 - 30 * kt - j];
+                    st[kt][j] += tblf[hx * NTBL + idx0 - 30 * kt - j];
             if (lastrow || lastcol) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
@@ -377,7 +410,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                 for (int j = 0; j < 4; ++j) dp[kt][j] = st[kt][j] * (dp[kt][j] - delta);
                 Pb[kt] = pack_bf16x4(st[kt]);
                 dSb[kt] = pack_bf16x4(dp[kt]);
-                tblacc[hd][kt] = mma16(ident, dSb[kt], tblacc[hd][kt]);
+                tblacc[hx][kt] = mma16(ident, dSb[kt], tblacc[hx][kt]);
             }
             // transposed copies for the key role: [key][query]
 #pragma unroll
@@ -429,8 +462,8 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     dkT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
                     dvT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
                     f32x4 dkN = f32x4{0.f, 0.f, 0.f, 0.f}, dvN = f32x4{0.f, 0.f, 0.f, 0.f};
-                    const uint16_t *qrow = qtr + par * 16 * ET * LD + (16 * et + l16) * LD + 4 * q;
-                    const uint16_t *orow = dotr + par * 16 * ET * LD + (16 * et + l16) * LD + 4 * q;
+                    const uint16_t *qrow = qtr + (16 * et + l16) * LD + 4 * q;
+                    const uint16_t *orow = dotr + (16 * et + l16) * LD + 4 * q;
 #pragma unroll
                     for (int kp = 0; kp < 2; ++kp) {
                         const uint4 qa = cat(*reinterpret_cast<const uint2 *>(qrow + 32 * kp),
@@ -469,9 +502,9 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                 for (int hlp = 0; hlp < HG; ++hlp)
 #pragma unroll
                     for (int etp = 0; etp < ET; ++etp) {
-                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hd, 0, et, hlp, etp) * 64 + lane], gq, dFT[hlp][etp]);
-                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hd, 1, et, hlp, etp) * 64 + lane], gk, dFT[hlp][etp]);
-                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hd, 2, et, hlp, etp) * 64 + lane], gv, dFT[hlp][etp]);
+                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hx, 0, et, hlp, etp) * 64 + lane], gq, dFT[hlp][etp]);
+                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hx, 1, et, hlp, etp) * 64 + lane], gk, dFT[hlp][etp]);
+                        dFT[hlp][etp] = mma16(wqt[fqt<Cf>(hx, 2, et, hlp, etp) * 64 + lane], gv, dFT[hlp][etp]);
                     }
             }
             __syncthreads();
@@ -486,13 +519,12 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     const uint16_t *br = fbuf + (16 * ct + l16) * LW + 8 * q;
 #pragma unroll
                     for (int kp = 0; kp < 2; ++kp)
-                        dwacc[hd][k] = mma32(cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
+                        dwacc[hx][k] = mma32(cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
                                                  *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4)),
                                              cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
-                                                 *reinterpret_cast<const uint2 *>(br + 32 * kp + 4)), dwacc[hd][k]);
+                                                 *reinterpret_cast<const uint2 *>(br + 32 * kp + 4)), dwacc[hx][k]);
                 }
             }
-            par ^= 1;
 
             // ---- end of a group: dx slice; keep dF as the cascade gradient of the previous group ----
             if (hl == 0) {
@@ -515,6 +547,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     // carry the 1/sqrt(d) of the scores, so their gradients get it back here. ----
     const float scale = 1.0f / sqrtf((float)D);
     float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
+    if (FIRST) {
 #pragma unroll
     for (int k = 0; k < KTP; ++k) {
         const int ti = 4 * k + wv;
@@ -531,8 +564,10 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
             }
         }
     }
+    }
 #pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd) {
+    for (int hx = 0; hx < NH; ++hx) {
+        const int hd = HB + hx;
         const int gi = hd / HG, hl = hd % HG;
 #pragma unroll
         for (int k = 0; k < KT; ++k) {
@@ -546,7 +581,7 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
                     const int e = 16 * et + 4 * q + j;
                     if (e < D) {
                         const int row = gi * 3 * CG + t * CG + hl * D + e;
-                        const float v = t == 0 ? dwacc[hd][k][j] * scale : dwacc[hd][k][j];
+                        const float v = t == 0 ? dwacc[hx][k][j] * scale : dwacc[hx][k][j];
                         if (c < CG) mine[B::P_DWQ + row * CG + c] = v;
                         else if (c == CG) mine[B::P_DBQ + row] = v;
                     }
@@ -558,12 +593,13 @@ __global__ __launch_bounds__(256) void fused_bwd_kernel(Geom g, const bf16_t *__
     float *mat = reinterpret_cast<float *>(lds + B::OFF_P); // [64 queries][64 keys] of one head
     static_assert((size_t)64 * 64 * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
 #pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd) {
+    for (int hx = 0; hx < NH; ++hx) {
+        const int hd = HB + hx;
         __syncthreads();
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mat[(16 * wv + l16) * 64 + 16 * kt + 4 * q + j] = tblacc[hd][kt][j];
+            for (int j = 0; j < 4; ++j) mat[(16 * wv + l16) * 64 + 16 * kt + 4 * q + j] = tblacc[hx][kt][j];
         __syncthreads();
         if (tid < NTBL) {
             const int dr = tid / (2 * M - 1) - (M - 1), dc = tid % (2 * M - 1) - (M - 1);
@@ -625,36 +661,65 @@ int device_cu_count()
     return cus;
 }
 
+// Head chunks of the backward, in launch order (last group first).  Chunks are whole groups, so
+// the only thing one launch hands to the next is the cascade gradient, which is the dx slice it
+// wrote.  Three heads per launch keep the accumulators small enough for two workgroups per CU;
+// with one group (no boundary to cut at) a single launch takes all heads at one workgroup per CU.
+template <int G> struct ChunkPlan;
+template <> struct ChunkPlan<1> { static constexpr int N = 1; static constexpr int B[1] = {0}, E[1] = {6}; };
+template <> struct ChunkPlan<2> { static constexpr int N = 2; static constexpr int B[2] = {3, 0}, E[2] = {6, 3}; };
+template <> struct ChunkPlan<3> { static constexpr int N = 3; static constexpr int B[3] = {4, 2, 0}, E[3] = {6, 4, 2}; };
+template <> struct ChunkPlan<6> { static constexpr int N = 2; static constexpr int B[2] = {3, 0}, E[2] = {6, 3}; };
+
 int bwd_grid(const Geom &g)
 {
-    int grid = device_cu_count();
+    int grid = (g.groups > 1 ? 2 : 1) * device_cu_count();
     return grid > g.nW ? g.nW : grid;
+}
+
+template <class Cf, int HB, int HE>
+hipError_t launch_chunk(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
+                        const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, hipStream_t s)
+{
+    using B = BwdCfg<Cf, HB, HE>;
+    static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(B::NH == Cf::HEADS || B::LDS_BYTES <= 80 * 1024, "two workgroups per compute unit");
+    auto kern = fused_bwd_kernel<Cf, HB, HE>;
+    static bool attr_done = false;
+    if (!attr_done && B::LDS_BYTES > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)B::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    KernelTimer kt(K_FUSED_BWD, s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, part);
+    return hipGetLastError();
+}
+
+template <class Cf, int I = 0>
+hipError_t launch_chunks(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
+                         const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, hipStream_t s)
+{
+    using Plan = ChunkPlan<Cf::G>;
+    if constexpr (I < Plan::N) {
+        hipError_t e = launch_chunk<Cf, Plan::B[I], Plan::E[I]>(g, grid, x, dy, attn, pack, table, dx, part, s);
+        if (e != hipSuccess) return e;
+        return launch_chunks<Cf, I + 1>(g, grid, x, dy, attn, pack, table, dx, part, s);
+    }
+    return hipSuccess;
 }
 
 template <class Cf>
 hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
-                   const void *pack_, const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj, float *db_proj, float *dtable,
-                   int accumulate, void *ws, hipStream_t s)
+                   const void *pack_, const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv,
+                   float *dw_proj, float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s)
 {
-    using B = BwdCfg<Cf>;
-    static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
+    using B = BwdCfg<Cf, 0, Cf::HEADS>;
     const uint8_t *pack = static_cast<const uint8_t *>(pack_);
     float *part = static_cast<float *>(ws);
-    hipError_t e = hipSuccess;
-    auto kern = fused_bwd_kernel<Cf>;
-    static bool attr_done = false;
-    if (!attr_done && B::LDS_BYTES > 64 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)B::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     const int grid = bwd_grid(g);
-    {
-        KernelTimer kt(K_FUSED_BWD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, part);
-    }
-    e = hipGetLastError();
+    hipError_t e = launch_chunks<Cf>(g, grid, x, dy, attn, pack, table, dx, part, s);
     if (e != hipSuccess) return e;
     ReduceOut out;
     out.ptr[0] = dw_qkv; out.ptr[1] = db_qkv; out.ptr[2] = dw_proj; out.ptr[3] = db_proj; out.ptr[4] = dtable;
@@ -686,7 +751,7 @@ size_t fused_bwd_ws_bytes(const Geom &g)
 {
     int total = 0;
 #define X(C_, H_, G_) \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = BwdCfg<FusedCfg<C_, H_, G_>>::P_TOTAL;
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = BwdCfg<FusedCfg<C_, H_, G_>, 0, H_>::P_TOTAL;
     GSWA_FUSED_SHAPES(X)
 #undef X
     return ((size_t)bwd_grid(g) * total * 4 + 255) & ~size_t(255);
