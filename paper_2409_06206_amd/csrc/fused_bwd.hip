@@ -613,7 +613,8 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
 }
 
 // Sums the per-workgroup partial vectors and scatters the five segments to their gradients.
-// One block handles 64 entries; its four waves each sum a quarter of the partials.
+// One block handles 32 entries; eight slices of the block each sum an eighth of the partials,
+// eight independent loads in flight per thread; fixed summation order.
 struct ReduceOut {
     float *ptr[5];
     int begin[6];
@@ -621,26 +622,25 @@ struct ReduceOut {
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
                                                               int n, ReduceOut out, int accumulate)
 {
-    __shared__ float red[4][64];
-    const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int i = blockIdx.x * 64 + col;
+    __shared__ float red[8][32];
+    const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + col;
     float acc = 0.f;
     if (i < n) {
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         int w = slice;
-        for (; w + 12 < nparts; w += 16) {
-            a0 += part[(size_t)w * n + i];
-            a1 += part[(size_t)(w + 4) * n + i];
-            a2 += part[(size_t)(w + 8) * n + i];
-            a3 += part[(size_t)(w + 12) * n + i];
+        for (; w + 56 < nparts; w += 64) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(w + 8 * u) * n + i];
         }
-        for (; w < nparts; w += 4) a0 += part[(size_t)w * n + i];
-        acc = (a0 + a1) + (a2 + a3);
+        for (; w < nparts; w += 8) a[0] += part[(size_t)w * n + i];
+        acc = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     }
     red[slice][col] = acc;
     __syncthreads();
     if (slice == 0 && i < n) {
-        acc = (red[0][col] + red[1][col]) + (red[2][col] + red[3][col]);
+        acc = ((red[0][col] + red[1][col]) + (red[2][col] + red[3][col])) +
+              ((red[4][col] + red[5][col]) + (red[6][col] + red[7][col]));
         int seg = 0;
         while (seg < 4 && i >= out.begin[seg + 1]) ++seg;
         float *dst = out.ptr[seg] + (i - out.begin[seg]);
@@ -727,7 +727,7 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     out.begin[4] = B::P_TBL; out.begin[5] = B::P_TOTAL;
     {
         KernelTimer kt(K_REDUCE, s);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::P_TOTAL + 63) / 64), dim3(256), 0, s, part, grid,
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::P_TOTAL + 31) / 32), dim3(256), 0, s, part, grid,
                            B::P_TOTAL, out, accumulate);
     }
     return hipGetLastError();
