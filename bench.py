@@ -62,26 +62,27 @@ def build_case(name, groups):
     return cfg, layers
 
 
-def step(layers):
+def step(layers, backward=True):
     for L in layers:
-        L.forward()
-    for L in reversed(layers):
-        L.backward()
+        L.forward(keep=backward)
+    if backward:
+        for L in reversed(layers):
+            L.backward()
 
 
-def time_steps(layers, steps, warmup):
+def time_steps(layers, steps, warmup, backward=True):
     import torch
     for _ in range(warmup):
-        step(layers)
+        step(layers, backward)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        step(layers)
+        step(layers, backward)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
 
 
-def profile_steps(layers, steps):
+def profile_steps(layers, steps, backward=True):
     """Per-kernel average durations from HIP events recorded on the launch stream."""
     import torch
     from paper_2409_06206_amd import gswa
@@ -90,7 +91,7 @@ def profile_steps(layers, steps):
     t0 = time.perf_counter()
     per = {}
     for _ in range(steps):
-        step(layers)
+        step(layers, backward)
         res, dropped = gswa.gswa_profile_collect()   # waits for the step's events
         assert dropped == 0
         for k, (ms, n) in res.items():
@@ -125,9 +126,14 @@ def algorithmic_bytes_per_launch(kernel, cfg, groups):
     return table.get(kernel)
 
 
-def model_flops_per_token(cfg, groups):
+def synth_groups(name):
+    from paper_2409_06206_amd import synth
+    return synth.CONFIGS[name]["groups"]
+
+
+def model_flops_per_token(cfg, groups, backward=True):
     C, N = cfg["C"], cfg["window"] ** 2
-    return 3 * (6 * C * C / groups + 2 * C * C) + 12 * N * C
+    return (3 if backward else 1) * (6 * C * C / groups + 2 * C * C + 4 * N * C)
 
 
 def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
@@ -166,7 +172,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--groups", type=int, default=2)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16"],
+                    help="c2 is the benchmark line; the others are the remaining benchmark shapes "
+                         "(c5_*: forward only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-sweep", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -181,12 +189,15 @@ def main():
     gswa.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
+    backward = not args.workload.startswith("c5")
+    if args.groups not in synth_groups(args.workload):
+        sys.exit(f"groups={args.groups} is not one of the benchmark's values for {args.workload}")
     cfg, layers = build_case(args.workload, args.groups)
     T = cfg["B"] * cfg["H"] * cfg["W"]
     tokens_per_step = T * len(layers)
-    sec = time_steps(layers, args.steps, args.warmup)
+    sec = time_steps(layers, args.steps, args.warmup, backward)
 
-    prof, prof_wall = profile_steps(layers, min(args.steps, 20))
+    prof, prof_wall = profile_steps(layers, min(args.steps, 20), backward)
     dom = max(prof, key=lambda k: prof[k]["total_ms_per_step"])
     dom_bytes = algorithmic_bytes_per_launch(dom, cfg, args.groups)
     dom_s = prof[dom]["avg_us"] * 1e-6
@@ -196,8 +207,8 @@ def main():
                 "traffic": measured_traffic(args.workload, args.groups, dom),
                 "avg_launch_us": prof[dom]["avg_us"], "algorithmic_bytes_per_launch": dom_bytes}
     e = 2 if cfg["dtype"] == "bf16" else 4
-    step_bytes = 7 * cfg["C"] * e * tokens_per_step
-    step_flops = model_flops_per_token(cfg, args.groups) * tokens_per_step
+    step_bytes = (7 if backward else 2) * cfg["C"] * e * tokens_per_step
+    step_flops = model_flops_per_token(cfg, args.groups, backward) * tokens_per_step
 
     sweep = {}
     if not args.no_group_sweep:
@@ -206,7 +217,7 @@ def main():
                 ls, s_ = layers, sec
             else:
                 _, ls = build_case(args.workload, G)
-                s_ = time_steps(ls, max(5, args.steps // 5), 3)
+                s_ = time_steps(ls, max(5, args.steps // 5), 3, backward)
             L0 = ls[0]
             sweep[str(G)] = {"tokens_per_s": tokens_per_step / s_, "ms_per_step": 1e3 * s_,
                              "saved_bytes_per_layer": L0.saved_bytes,
@@ -221,7 +232,8 @@ def main():
         "value": tokens_per_step / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.workload}: GSWA layer pair (shift 0 then {cfg['layers'][-1]}) fwd+bwd, "
+        "config": {"workload": f"{args.workload}: {len(layers)} GSWA layer(s), shifts {list(cfg['layers'])[:4]}"
+                               f"{'...' if len(layers) > 4 else ''}, {'fwd+bwd' if backward else 'forward only'}, "
                                f"B={cfg['B']} {cfg['H']}x{cfg['W']} C={cfg['C']} heads={cfg['heads']} "
                                f"window={cfg['window']} groups={args.groups}",
                    "groups": args.groups, "tokens_per_step": tokens_per_step},
@@ -241,7 +253,7 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == "c2":
         out["cpu_baseline"] = cpu_baseline(args.workload, args.groups)
     print(json.dumps(out))
 

@@ -17,7 +17,10 @@ namespace gswa {
 // fragment f, lane l at f*64 + l, so one LDS read per lane fetches an operand), zero padded
 // (head width to 16*ET, group width to 32*KS).  The query rows of w_qkv and b_qkv are stored
 // multiplied by 1/sqrt(d), so scores need no separate scaling.  One buffer serves both passes:
-//   [ WC | WP | WQ | BIAS | WPT | WQT ]      forward reads [WC .. BIAS], backward [WQ .. WQT]
+//   [ WC | WP | WQ | BIAS | WPT | WQT | WPK ]   forward reads [WC .. BIAS], backward [WQ .. WQT]
+// Wide layers (C > 64) do not fit their weights in LDS at once: their forward runs per head
+// chunk (SPLIT), takes the cascade input from memory, and projects in a separate GEMM that
+// uses WPK; WC and WP are empty for them.
 template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr int C = C_, HEADS = HEADS_, G = G_;
     static constexpr int D = C / HEADS, CG = C / G, HG = HEADS / G;
@@ -25,8 +28,10 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr int KS = (CG + 31) / 32; // K=32 steps over one group's input channels
     static constexpr int KSC = (C + 31) / 32; // K=32 steps over all channels
     static constexpr int OT = (C + 15) / 16;  // 16-row tiles of the output projection
-    static constexpr int N_WC = (G - 1) * HG * 3 * ET * HG * ET; // Wqkv on the cascade input, K=16: (g,hl,t,et,hlp,etp)
-    static constexpr int N_WP = OT * HEADS * ET;                 // Wproj, K=16: (ot,hd,et)
+    static constexpr bool SPLIT = C > 64;
+    static constexpr int N_WC = SPLIT ? 0 : (G - 1) * HG * 3 * ET * HG * ET; // Wqkv on the cascade input, K=16: (g,hl,t,et,hlp,etp)
+    static constexpr int N_WP = SPLIT ? 0 : OT * HEADS * ET;     // Wproj, K=16: (ot,hd,et)
+    static constexpr int N_WPK = SPLIT ? OT * KSC : 0;           // Wproj, K=32 over all channels: (ot,ks)
     static constexpr int N_WQ = HEADS * 3 * ET * KS;             // Wqkv on the x slice, K=32: (hd,t,et,ks)
     static constexpr int N_WPT = HEADS * ET * KSC;               // Wproj^T, K=32: (hd,et,ks)
     static constexpr int N_WQT = HEADS * 3 * ET * HG * ET;       // Wqkv^T, K=16: (hd,t,et,hlp,etp)
@@ -36,10 +41,11 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr size_t P_BIAS = P_WQ + (size_t)N_WQ * 1024; // fp32 b_qkv [3C], b_proj [C]
     static constexpr size_t P_WPT = P_BIAS + (size_t)16 * C;
     static constexpr size_t P_WQT = P_WPT + (size_t)N_WPT * 1024;
-    static constexpr size_t P_END = P_WQT + (size_t)N_WQT * 512;
+    static constexpr size_t P_WPK = P_WQT + (size_t)N_WQT * 512;
+    static constexpr size_t P_END = P_WPK + (size_t)N_WPK * 1024;
     static constexpr size_t FWD_PACK_BYTES = P_WPT;        // [0, P_WPT)
     static constexpr size_t BWD_PACK_OFF = P_WQ;           // [P_WQ, P_END)
-    static constexpr size_t BWD_PACK_BYTES = P_END - P_WQ;
+    static constexpr size_t BWD_PACK_BYTES = P_WPK - P_WQ;
     // forward LDS: the packed range, then the per-head K and V exchange buffers.  Kept under
     // 52 KB so that three workgroups share a compute unit.
     static constexpr size_t OFF_WC = P_WC, OFF_WP = P_WP, OFF_WQ = P_WQ, OFF_BIAS = P_BIAS;
@@ -56,8 +62,12 @@ bool fused_fwd_supported(const Geom &g);
 // Bytes of the packed parameters (both passes).
 size_t fused_pack_bytes(const Geom &g);
 
-// y = GSWA(x); attn_out (may be null) receives the concatenated group outputs [T, C];
-// `pack` receives the packed parameters (fused_pack_bytes, 256-byte aligned).
+// True when the forward of this geometry runs per head chunk and therefore always needs the
+// attn_out buffer (for inference the caller lends scratch).
+bool fused_fwd_needs_attn(const Geom &g);
+
+// y = GSWA(x); attn_out receives the concatenated group outputs [T, C] (may be null unless
+// fused_fwd_needs_attn); `pack` receives the packed parameters (fused_pack_bytes, 256-byte aligned).
 hipError_t launch_fused_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
                             const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table,
                             bf16_t *y, bf16_t *attn_out, void *pack, hipStream_t s);

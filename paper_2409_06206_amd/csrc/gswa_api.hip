@@ -65,6 +65,7 @@ size_t elem_size(const gswa_desc *d) { return d->dtype == GSWA_F32 ? 4 : 2; }
 struct Sizes {
     size_t saved, qkv, fwd_ws, bwd_ws;
     size_t act;          // bytes of the saved [T, C] activation at the start of `saved`
+    size_t pack;         // bytes of the packed parameters behind it (fused path)
     size_t fused_bwd_ws; // partial sums of the fused backward
     bool fused_fwd, fused_bwd;
 };
@@ -85,11 +86,14 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.fused_fwd = use_fused_fwd(d, g);
     s.fused_bwd = s.fused_fwd && fused_bwd_supported(g);
     s.fused_bwd_ws = 0;
+    s.pack = 0;
     s.act = s.saved;
     if (s.fused_fwd) {
         // the packed parameters ride behind the saved activation (training) or in ws (inference)
-        s.fwd_ws = align256(fused_pack_bytes(g));
-        s.saved = s.act + s.fwd_ws;
+        s.pack = align256(fused_pack_bytes(g));
+        s.saved = s.act + s.pack;
+        // inference: the pack lives in ws, and so do the group outputs when the forward is split
+        s.fwd_ws = s.pack + (fused_fwd_needs_attn(g) ? s.act : 0);
     }
     if (s.fused_bwd) {
         s.fused_bwd_ws = align256(fused_bwd_ws_bytes(g));
@@ -235,9 +239,11 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
                                      (const float *)bias_table, (float *)y, (float *)saved, (char *)ws, st);
     if (s.fused_fwd) {
         void *pack = saved ? static_cast<void *>(static_cast<char *>(saved) + s.act) : ws;
+        void *attn = saved;
+        if (!saved && fused_fwd_needs_attn(g)) attn = static_cast<char *>(ws) + s.pack;
         hipError_t e = launch_fused_fwd(g, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
                                         (const bf16_t *)w_proj, (const bf16_t *)b_proj,
-                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, pack, st);
+                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)attn, pack, st);
         return e == hipSuccess ? GSWA_OK : hip_fail(e);
     }
     return forward_staged<bf16_t>(g, s, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,

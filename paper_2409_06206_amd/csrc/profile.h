@@ -21,6 +21,9 @@ enum KernelId {
     K_PACK_BWD,     // weights into MFMA fragment order for the fused backward
     K_FUSED_BWD,    // dx, d(q|k|v) and bias-table partials, one launch
     K_REDUCE,       // per-workgroup partial sums -> parameter gradients
+    K_ATTN_CHUNK_FWD, // split forward: attention of one head chunk
+    K_PROJ_GEMM,    // split forward: output projection (Eq. 7)
+    K_WPROJ_GRAD,   // split backward: d w_proj, d b_proj
     K_COUNT
 };
 
