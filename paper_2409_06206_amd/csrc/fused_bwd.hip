@@ -19,7 +19,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <class Cf, int HB_, int HE_> struct BwdCfg {
+template <class Cf, int HB_, int HE_, bool WPROJ_ = (HE_ == Cf::HEADS)> struct BwdCfg {
     static constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
     static constexpr int ET = Cf::ET, KS = Cf::KS;
     static constexpr int KSC = (C + 31) / 32; // K=32 steps over all C channels of dy
@@ -31,12 +31,13 @@ template <class Cf, int HB_, int HE_> struct BwdCfg {
     static constexpr int KT = (NT + 3) / 4;         // tiles per wave
     static constexpr int OTP = (C + 15) / 16, CTP = C / 16 + 1;
     static constexpr int NTP = OTP * CTP, KTP = (NTP + 3) / 4;
-    // heads [HB, HE) of this launch (whole groups unless G == 1); the launch that holds the last
-    // head also produces d w_proj / d b_proj
+    // heads [HB, HE) of this launch: whole groups, or part of one group.  WPROJ: this launch also
+    // produces d w_proj / d b_proj (narrow layers; wide ones use a kernel of its own).
     static constexpr int HB = HB_, HE = HE_, NH = HE - HB;
-    static constexpr bool FIRST = HE == HEADS;
+    static constexpr bool WPROJ = WPROJ_;
     static constexpr int GB = HB / HG, GE = (HE - 1) / HG; // lowest and highest group of the chunk
-    static_assert(NH > 0 && (G == 1 || (HB % HG == 0 && HE % HG == 0)), "chunks are whole groups");
+    static_assert(NH > 0 && (GB == GE || (HB % HG == 0 && HE % HG == 0)),
+                  "a chunk is whole groups or lies inside one group");
     // packed parameters of these heads, copied from the buffer forward filled: [WQ | BIAS | WPT | WQT]
     static constexpr int N_WQ = NH * 3 * ET * KS, N_WPT = NH * ET * KSC, N_WQT = NH * 3 * ET * HG * ET;
     static constexpr size_t SRC_WQ = Cf::P_WQ + (size_t)HB * 3 * ET * KS * 1024;
@@ -74,7 +75,8 @@ template <class Cf, int HB_, int HE_> struct BwdCfg {
     static constexpr int P_DBP = P_DWP + C * C;
     static constexpr int P_TBL = P_DBP + C;
     static constexpr int P_TOTAL = P_TBL + TBL_N;
-    static_assert(OTP <= 2 * KSC && SZ_SQ >= (size_t)16 * OTP * LW * 2 && SZ_SQ >= (size_t)16 * CTP * LW * 2,
+    static_assert(!WPROJ || (OTP <= 2 * KSC && SZ_SQ >= (size_t)16 * OTP * LW * 2 &&
+                             SZ_SQ >= (size_t)16 * CTP * LW * 2),
                   "dY^T / A^T rows alias the P / dS squares");
 };
 
@@ -102,17 +104,17 @@ __device__ __forceinline__ uint4 select_slot(int target, int first)
 
 constexpr bool ranges_overlap(int a0, int a1, int b0, int b1) { return a0 < b1 && b0 < a1; }
 
-template <class Cf, int HB, int HE>
-__global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
+template <class Cf, int HB, int HE, bool WPROJ>
+__global__ __launch_bounds__(256, (BwdCfg<Cf, HB, HE, WPROJ>::LDS_BYTES <= 80 * 1024 ? 2 : 1))
+void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                                                         const bf16_t *__restrict__ dy,
                                                         const bf16_t *__restrict__ attn,
                                                         const uint8_t *__restrict__ pack,
                                                         const bf16_t *__restrict__ table,
                                                         bf16_t *dx, float *__restrict__ part)
 {
-    using B = BwdCfg<Cf, HB, HE>;
+    using B = BwdCfg<Cf, HB, HE, WPROJ>;
     constexpr int NH = B::NH, GB = B::GB, GE = B::GE;
-    constexpr bool FIRST = B::FIRST;
     constexpr int C = B::C, D = B::D, CG = B::CG, HG = B::HG, HEADS = B::HEADS, G = B::G;
     constexpr int ET = B::ET, KS = B::KS, KSC = B::KSC, LD = B::LD, LW = B::LW, NTBL = B::NTBL;
     constexpr int CT = B::CT, NT = B::NT, KT = B::KT, OTP = B::OTP, CTP = B::CTP, NTP = B::NTP, KTP = B::KTP;
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
             for (int ks = 0; ks < KS; ++ks) {
                 uint32_t xv[4], av[4];
                 const bool need_x = gi >= GB && gi <= GE;
-                const bool need_a = FIRST || (gi >= GB - 1 && gi < GE);
+                const bool need_a = WPROJ || (gi >= GB - 1 && gi < GE);
 #pragma unroll
                 for (int dw = 0; dw < 4; ++dw) {
                     const int c = 32 * ks + 8 * q + 2 * dw;
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
         }
 
         // ---- d w_proj, d b_proj: dY^T and A^T rows [channel][token] through LDS, K = 64 tokens ----
-        if (FIRST) {
+        if (WPROJ) {
 #pragma unroll
         for (int ot = 0; ot < OTP; ++ot) {
             f32x4 tN = mma32(dyf[ot >> 1], select_slot(16 * ot + l16, 32 * (ot >> 1) + 8 * q),
@@ -273,7 +275,12 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
             const bool casc_in = gi > 0 && g.cascade;      // this group's input has a cascade term
             const bool casc_out = gi < G - 1 && g.cascade; // this group's output feeds the next group
             const int gp = gi > 0 ? gi - 1 : 0;
-            if (hl == HG - 1) {
+            // the heads of group gi this launch processes, top first: [g_lo, g_hi]
+            const int g_hi = (HE < (gi + 1) * HG ? HE : (gi + 1) * HG) - 1;
+            const int g_lo = HB > gi * HG ? HB : gi * HG;
+            const bool starts_group = g_hi == (gi + 1) * HG - 1; // no earlier launch touched this group
+            const bool next_in_regs = HB <= (gi + 1) * HG && HE >= (gi + 2) * HG; // group gi+1 done in this launch
+            if (hd == g_hi) {
 #pragma unroll
                 for (int hlp = 0; hlp < HG; ++hlp)
 #pragma unroll
@@ -285,9 +292,9 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
             for (int et = 0; et < ET; ++et) {
                 dOT[et] = f32x4{0.f, 0.f, 0.f, 0.f};
                 if (casc_out) {
-                    if (FIRST || gi < GE) {
+                    if (next_in_regs) {
                         dOT[et] = cascT[hl][et];
-                    } else { // the next group was processed by the previous launch: its dF is the dx slice
+                    } else { // the next group was finished by earlier launches: its dF is the dx slice
                         const int e0 = 16 * et + 4 * q;
                         const uint32_t *src =
                             reinterpret_cast<const uint32_t *>(dx + tok * C + (gi + 1) * CG + hl * D + e0);
@@ -479,8 +486,8 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
                     *reinterpret_cast<uint2 *>(gbuf + ((2 * ET + et) * 16 + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(dvN);
                 }
             }
-            // ---- first head of a group: F^T rows [channel][token] of the group input (Eq. 8) ----
-            if (hl == HG - 1) {
+            // ---- first head of a group in this launch: F^T rows [channel][token] of the group input (Eq. 8) ----
+            if (hd == g_hi) {
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) {
                     f32x4 tN = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -527,14 +534,18 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
             }
 
             // ---- end of a group: dx slice; keep dF as the cascade gradient of the previous group ----
-            if (hl == 0) {
+            if (hd == g_lo) {
 #pragma unroll
                 for (int hlp = 0; hlp < HG; ++hlp)
 #pragma unroll
                     for (int etp = 0; etp < ET; ++etp) {
-                        const uint2 v = pack_bf16x4(dFT[hlp][etp]);
                         const int c0 = 16 * etp + 4 * q;
                         uint32_t *dst = reinterpret_cast<uint32_t *>(dx + tok * C + gi * CG + hlp * D + c0);
+                        if (!starts_group) { // earlier launches left the other heads' share in the slice
+                            const uint32_t lo = c0 < D ? dst[0] : 0u, hi = c0 + 2 < D ? dst[1] : 0u;
+                            dFT[hlp][etp] += f32x4{bf16_lo(lo), bf16_hi(lo), bf16_lo(hi), bf16_hi(hi)};
+                        }
+                        const uint2 v = pack_bf16x4(dFT[hlp][etp]);
                         if (c0 < D) dst[0] = v.x;
                         if (c0 + 2 < D) dst[1] = v.y;
                         cascT[hlp][etp] = dFT[hlp][etp];
@@ -547,7 +558,7 @@ __global__ __launch_bounds__(256, (HE - HB) < Cf::HEADS ? 2 : 1) void fused_bwd_
     // carry the 1/sqrt(d) of the scores, so their gradients get it back here. ----
     const float scale = 1.0f / sqrtf((float)D);
     float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
-    if (FIRST) {
+    if (WPROJ) {
 #pragma unroll
     for (int k = 0; k < KTP; ++k) {
         const int ti = 4 * k + wv;
@@ -661,30 +672,138 @@ int device_cu_count()
     return cus;
 }
 
+// d w_proj, d b_proj of wide layers: dY^T [A | 1] over plain token rows, 64 tokens per pass.
+// Both operands are moved into [channel][token] LDS rows by selector MFMAs; wave w owns output
+// row tiles w*RW .. w*RW+RW-1 and all column tiles; the spare column C carries the bias sums.
+template <class Cf>
+__global__ __launch_bounds__(256, 2) void wproj_grad_kernel(long T, const bf16_t *__restrict__ dy,
+                                                            const bf16_t *__restrict__ attn,
+                                                            float *__restrict__ part)
+{
+    using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
+    constexpr int C = Cf::C, KSC = Cf::KSC, OTP = B::OTP, CTP = B::CTP, LW = B::LW;
+    constexpr int RW = (OTP + 3) / 4;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint16_t *dybuf = reinterpret_cast<uint16_t *>(lds);
+    uint16_t *abuf = dybuf + 16 * OTP * LW;
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
+
+    f32x4 acc[RW][CTP];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int ct = 0; ct < CTP; ++ct) acc[r][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const long ntile = T / 64;
+    for (long tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        const long tok = tile * 64 + 16 * wv + l16;
+        const uint32_t *dyrow = reinterpret_cast<const uint32_t *>(dy + tok * C);
+        const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + tok * C);
+        uint4 dyf[KSC], af[KSC];
+#pragma unroll
+        for (int ks = 0; ks < KSC; ++ks) {
+            uint32_t dv[4], av[4];
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int c = 32 * ks + 8 * q + 2 * dw;
+                dv[dw] = c < C ? dyrow[c >> 1] : 0u;
+                av[dw] = c < C ? arow[c >> 1] : 0u;
+            }
+            dyf[ks] = make_uint4(dv[0], dv[1], dv[2], dv[3]);
+            af[ks] = make_uint4(av[0], av[1], av[2], av[3]);
+        }
+        __syncthreads(); // the previous tile's rows are consumed
+#pragma unroll
+        for (int ot = 0; ot < OTP; ++ot) {
+            const f32x4 tN = mma32(dyf[ot >> 1], select_slot(16 * ot + l16, 32 * (ot >> 1) + 8 * q),
+                                   f32x4{0.f, 0.f, 0.f, 0.f});
+            *reinterpret_cast<uint2 *>(dybuf + (16 * ot + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(tN);
+        }
+#pragma unroll
+        for (int ct = 0; ct < CTP; ++ct) {
+            f32x4 tN = f32x4{0.f, 0.f, 0.f, 0.f};
+            if ((ct >> 1) < KSC)
+                tN = mma32(af[(ct >> 1) < KSC ? (ct >> 1) : 0], select_slot(16 * ct + l16, 32 * (ct >> 1) + 8 * q), tN);
+            uint2 pk = pack_bf16x4(tN);
+            if (16 * ct + l16 == C) pk = ones2;
+            *reinterpret_cast<uint2 *>(abuf + (16 * ct + l16) * LW + 16 * wv + 4 * q) = pk;
+        }
+        __syncthreads();
+        uint4 afr[RW][2];
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            const int ot = wv * RW + r;
+            const uint16_t *ar = dybuf + (16 * (ot < OTP ? ot : 0) + l16) * LW + 8 * q;
+#pragma unroll
+            for (int kp = 0; kp < 2; ++kp)
+                afr[r][kp] = cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
+                                 *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4));
+        }
+#pragma unroll
+        for (int ct = 0; ct < CTP; ++ct) {
+            const uint16_t *br = abuf + (16 * ct + l16) * LW + 8 * q;
+#pragma unroll
+            for (int kp = 0; kp < 2; ++kp) {
+                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
+                                     *reinterpret_cast<const uint2 *>(br + 32 * kp + 4));
+#pragma unroll
+                for (int r = 0; r < RW; ++r) acc[r][ct] = mma32(afr[r][kp], bf, acc[r][ct]);
+            }
+        }
+    }
+    float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const int ot = wv * RW + r;
+        if (ot < OTP) {
+#pragma unroll
+            for (int ct = 0; ct < CTP; ++ct) {
+                const int c = 16 * ct + l16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int o = 16 * ot + 4 * q + j;
+                    if (o < C) {
+                        if (c < C) mine[B::P_DWP + o * C + c] = acc[r][ct][j];
+                        else if (c == C) mine[B::P_DBP + o] = acc[r][ct][j];
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Head chunks of the backward, in launch order (last group first).  Chunks are whole groups, so
 // the only thing one launch hands to the next is the cascade gradient, which is the dx slice it
 // wrote.  Three heads per launch keep the accumulators small enough for two workgroups per CU;
 // with one group (no boundary to cut at) a single launch takes all heads at one workgroup per CU.
-template <int G> struct ChunkPlan;
-template <> struct ChunkPlan<1> { static constexpr int N = 1; static constexpr int B[1] = {0}, E[1] = {6}; };
-template <> struct ChunkPlan<2> { static constexpr int N = 2; static constexpr int B[2] = {3, 0}, E[2] = {6, 3}; };
-template <> struct ChunkPlan<3> { static constexpr int N = 3; static constexpr int B[3] = {4, 2, 0}, E[3] = {6, 4, 2}; };
-template <> struct ChunkPlan<6> { static constexpr int N = 2; static constexpr int B[2] = {3, 0}, E[2] = {6, 3}; };
+// Wide layers go one head per launch (their per-head weights and row buffers fill LDS); a group
+// split over launches accumulates its dF in the dx slice.
+template <bool SPLIT, int G> struct ChunkPlan;
+template <> struct ChunkPlan<false, 1> { static constexpr int N = 1; static constexpr int B[1] = {0}, E[1] = {6}; };
+template <> struct ChunkPlan<false, 2> { static constexpr int N = 2; static constexpr int B[2] = {3, 0}, E[2] = {6, 3}; };
+template <> struct ChunkPlan<false, 3> { static constexpr int N = 3; static constexpr int B[3] = {4, 2, 0}, E[3] = {6, 4, 2}; };
+template <> struct ChunkPlan<false, 6> { static constexpr int N = 2; static constexpr int B[2] = {3, 0}, E[2] = {6, 3}; };
+template <int G> struct ChunkPlan<true, G> {
+    static constexpr int N = 6;
+    static constexpr int B[6] = {5, 4, 3, 2, 1, 0}, E[6] = {6, 5, 4, 3, 2, 1};
+};
 
 int bwd_grid(const Geom &g)
 {
-    int grid = (g.groups > 1 ? 2 : 1) * device_cu_count();
+    // narrow layers with more than one group run two workgroups per compute unit
+    int grid = ((g.C <= 64 && g.groups > 1) ? 2 : 1) * device_cu_count();
     return grid > g.nW ? g.nW : grid;
 }
 
-template <class Cf, int HB, int HE>
+template <class Cf, int HB, int HE, bool WPROJ>
 hipError_t launch_chunk(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                         const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, hipStream_t s)
 {
-    using B = BwdCfg<Cf, HB, HE>;
+    using B = BwdCfg<Cf, HB, HE, WPROJ>;
     static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
-    static_assert(B::NH == Cf::HEADS || B::LDS_BYTES <= 80 * 1024, "two workgroups per compute unit");
-    auto kern = fused_bwd_kernel<Cf, HB, HE>;
+    auto kern = fused_bwd_kernel<Cf, HB, HE, WPROJ>;
     static bool attr_done = false;
     if (!attr_done && B::LDS_BYTES > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -701,9 +820,10 @@ template <class Cf, int I = 0>
 hipError_t launch_chunks(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                          const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, hipStream_t s)
 {
-    using Plan = ChunkPlan<Cf::G>;
+    using Plan = ChunkPlan<Cf::SPLIT, Cf::G>;
     if constexpr (I < Plan::N) {
-        hipError_t e = launch_chunk<Cf, Plan::B[I], Plan::E[I]>(g, grid, x, dy, attn, pack, table, dx, part, s);
+        hipError_t e = launch_chunk<Cf, Plan::B[I], Plan::E[I], !Cf::SPLIT && Plan::E[I] == Cf::HEADS>(
+            g, grid, x, dy, attn, pack, table, dx, part, s);
         if (e != hipSuccess) return e;
         return launch_chunks<Cf, I + 1>(g, grid, x, dy, attn, pack, table, dx, part, s);
     }
@@ -715,12 +835,29 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
                    const void *pack_, const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv,
                    float *dw_proj, float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s)
 {
-    using B = BwdCfg<Cf, 0, Cf::HEADS>;
+    using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
     const uint8_t *pack = static_cast<const uint8_t *>(pack_);
     float *part = static_cast<float *>(ws);
     const int grid = bwd_grid(g);
     hipError_t e = launch_chunks<Cf>(g, grid, x, dy, attn, pack, table, dx, part, s);
     if (e != hipSuccess) return e;
+    if constexpr (Cf::SPLIT) {
+        constexpr size_t lds = (size_t)16 * (B::OTP + B::CTP) * B::LW * 2;
+        auto kern = wproj_grad_kernel<Cf>;
+        static bool attr_done = false;
+        if (!attr_done && lds > 64 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        {
+            KernelTimer kt(K_WPROJ_GRAD, s);
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.T, dy, attn, part);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     ReduceOut out;
     out.ptr[0] = dw_qkv; out.ptr[1] = db_qkv; out.ptr[2] = dw_proj; out.ptr[3] = db_proj; out.ptr[4] = dtable;
     out.begin[0] = B::P_DWQ; out.begin[1] = B::P_DBQ; out.begin[2] = B::P_DWP; out.begin[3] = B::P_DBP;
@@ -733,7 +870,7 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     return hipGetLastError();
 }
 
-#define GSWA_FUSED_SHAPES(X) X(60, 6, 1) X(60, 6, 2) X(60, 6, 3) X(60, 6, 6)
+#define GSWA_FUSED_SHAPES(X) X(60, 6, 1) X(60, 6, 2) X(60, 6, 3) X(60, 6, 6) X(180, 6, 2) X(180, 6, 3)
 
 } // namespace
 
@@ -751,7 +888,7 @@ size_t fused_bwd_ws_bytes(const Geom &g)
 {
     int total = 0;
 #define X(C_, H_, G_) \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = BwdCfg<FusedCfg<C_, H_, G_>, 0, H_>::P_TOTAL;
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = BwdCfg<FusedCfg<C_, H_, G_>, 0, H_, false>::P_TOTAL;
     GSWA_FUSED_SHAPES(X)
 #undef X
     return ((size_t)bwd_grid(g) * total * 4 + 255) & ~size_t(255);
