@@ -105,25 +105,23 @@ def profile_steps(layers, steps, backward=True):
                 "avg_us": 1e3 * v[0] / v[1]} for k, v in per.items()}, wall
 
 
-def algorithmic_bytes_per_launch(kernel, cfg, groups):
+FORWARD_KERNELS = {"qkv_linear", "attn_fwd", "proj_linear", "fused_fwd", "fused_attn_fwd", "proj_gemm",
+                   "pack_fwd"}
+
+
+def algorithmic_bytes_per_launch(kernel, cfg, launches_per_layer, training=True):
     """Bytes the METHOD has to move for the work one launch of `kernel` covers.
 
     Per token the layer must read x and write y in forward (2*C*e), write one saved [T,C]
-    tensor, and in backward read x, dy and the saved tensor and write dx (4*C*e); weights are
-    negligible.  A kernel that covers one head group's share of a pass is charged 1/G of the
-    pass; a kernel covering a whole pass is charged all of it.
+    tensor when training, and in backward read x, dy and the saved tensor and write dx
+    (4*C*e); weights are negligible.  A kernel that is launched n times per layer and pass
+    (once per head group or head chunk) is charged 1/n of the pass per launch.
     """
     T = cfg["B"] * cfg["H"] * cfg["W"]
     e = 2 if cfg["dtype"] == "bf16" else 4
-    fwd = 3 * cfg["C"] * e * T
+    fwd = (3 if training else 2) * cfg["C"] * e * T
     bwd = 4 * cfg["C"] * e * T
-    table = {
-        "qkv_linear": fwd / groups, "attn_fwd": fwd / groups, "proj_linear": fwd,
-        "attn_bwd": bwd / groups, "dO_linear": bwd / groups, "dx_linear": bwd / groups,
-        "qkv_wgrad": bwd / groups, "proj_wgrad": bwd,
-        "fused_fwd": fwd, "fused_bwd": bwd,
-    }
-    return table.get(kernel)
+    return (fwd if kernel in FORWARD_KERNELS else bwd) / max(launches_per_layer, 1.0)
 
 
 def synth_groups(name):
@@ -199,7 +197,7 @@ def main():
 
     prof, prof_wall = profile_steps(layers, min(args.steps, 20), backward)
     dom = max(prof, key=lambda k: prof[k]["total_ms_per_step"])
-    dom_bytes = algorithmic_bytes_per_launch(dom, cfg, args.groups)
+    dom_bytes = algorithmic_bytes_per_launch(dom, cfg, prof[dom]["launches_per_step"] / len(layers), backward)
     dom_s = prof[dom]["avg_us"] * 1e-6
     achieved = dom_bytes / dom_s / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
