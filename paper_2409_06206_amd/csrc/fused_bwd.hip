@@ -91,6 +91,24 @@ template <class Cf> __device__ __forceinline__ constexpr int fqt(int hd, int t, 
 
 __device__ __forceinline__ uint4 cat(uint2 a, uint2 b) { return make_uint4(a.x, a.y, b.x, b.y); }
 
+// Transposed store of a packed result tile (this lane: rows 4q..4q+3 of column l16) into
+// row-major LDS rows.  Neighbouring lanes l16, l16^1 swap halves through DPP so that every lane
+// writes whole dwords: even lanes rows 4q and 4q+2, odd lanes rows 4q+1 and 4q+3, each holding
+// the columns (l16 & ~1, l16 | 1).  `row0` points at row 4q, column l16 & ~1.
+__device__ __forceinline__ void store_tile_transposed(uint16_t *row0, int pitch, uint2 tile, int lane)
+{
+    const int odd = lane & 1;
+    const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)tile.x, 0xB1, 0xF, 0xF, true); // quad_perm [1,0,3,2]
+    const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)tile.y, 0xB1, 0xF, 0xF, true);
+    const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+    // even: lo16(own) | lo16(partner) << 16 ;  odd: hi16(partner) | hi16(own) << 16
+    const uint32_t vx = __builtin_amdgcn_perm(px, tile.x, sel); // selector bytes 4-7 pick from px, 0-3 from own
+    const uint32_t vy = __builtin_amdgcn_perm(py, tile.y, sel);
+    uint32_t *d = reinterpret_cast<uint32_t *>(row0 + odd * pitch);
+    d[0] = vx;
+    d[pitch] = vy; // two rows further: 2 * pitch halves = pitch dwords
+}
+
 // K=32 operand that is 1.0 in the k-slot holding index `target` and 0 elsewhere, for a lane
 // whose slots 0..7 hold indices first .. first+7.  Multiplying by it moves a matrix held as an
 // operand (k-slots = columns) into result layout exactly: a transposition done by the MFMA unit.
@@ -352,11 +370,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                 const int row = (16 * et + l16) * LD + 16 * wv + 4 * q;
                 *reinterpret_cast<uint2 *>(ktr + row) = pack_bf16x4(kN[et]);
                 *reinterpret_cast<uint2 *>(qtr + row) = pack_bf16x4(qN[et]);
-                uint16_t *dst = dotr + (16 * et + 4 * q) * LD + 16 * wv + l16;
-                dst[0] = (uint16_t)(dOb[et].x & 0xffffu);
-                dst[LD] = (uint16_t)(dOb[et].x >> 16);
-                dst[2 * LD] = (uint16_t)(dOb[et].y & 0xffffu);
-                dst[3 * LD] = (uint16_t)(dOb[et].y >> 16);
+                store_tile_transposed(dotr + (16 * et + 4 * q) * LD + 16 * wv + (l16 & ~1), LD, dOb[et], lane);
             }
             __syncthreads();
 
@@ -422,15 +436,9 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
             // transposed copies for the key role: [key][query]
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
-                const int base = (16 * kt + 4 * q) * LD + 16 * wv + l16;
-                pbuf[base] = (uint16_t)(Pb[kt].x & 0xffffu);
-                pbuf[base + LD] = (uint16_t)(Pb[kt].x >> 16);
-                pbuf[base + 2 * LD] = (uint16_t)(Pb[kt].y & 0xffffu);
-                pbuf[base + 3 * LD] = (uint16_t)(Pb[kt].y >> 16);
-                dsbuf[base] = (uint16_t)(dSb[kt].x & 0xffffu);
-                dsbuf[base + LD] = (uint16_t)(dSb[kt].x >> 16);
-                dsbuf[base + 2 * LD] = (uint16_t)(dSb[kt].y & 0xffffu);
-                dsbuf[base + 3 * LD] = (uint16_t)(dSb[kt].y >> 16);
+                const int base = (16 * kt + 4 * q) * LD + 16 * wv + (l16 & ~1);
+                store_tile_transposed(pbuf + base, LD, Pb[kt], lane);
+                store_tile_transposed(dsbuf + base, LD, dSb[kt], lane);
             }
             // dQ = scale * dS K in both forms: T-form feeds dF, N-form rows feed d w_qkv
             f32x4 dqT[ET];
