@@ -78,12 +78,12 @@ typedef struct gswa_desc {
  *                  [B*H*W, C] in desc->dtype and, on the fused path, the parameters repacked
  *                  for the matrix cores (tens of KB, independent of B, H, W).  Scores and
  *                  probabilities are never kept; backward recomputes them.
- *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given.  Staged path: one group's
- *                  q|k|v, and with saved == NULL the scratch must hold fwd_ws_bytes + saved_bytes.
- *                  Fused path: room for the repacked parameters, used only when saved == NULL.
+ *   *fwd_ws_bytes  scratch of gswa_forward when `saved` is given (staged path: one group's
+ *                  q|k|v; fused path: nothing is used).  For inference (saved == NULL) the
+ *                  scratch must hold *fwd_ws_bytes + *saved_bytes: what would have been saved is
+ *                  then kept there for the duration of the call.
  *   *bwd_ws_bytes  scratch of gswa_backward.  Staged path: one group's q|k|v and its gradient.
- *                  Fused path: one partial parameter-gradient vector per workgroup (one
- *                  workgroup per compute unit).
+ *                  Fused path: one partial parameter-gradient vector per workgroup.
  * Which path serves a layer depends only on desc (shape, dtype, flags).
  * Any output pointer may be NULL.  All sizes are multiples of 256.
  */

@@ -92,8 +92,9 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
         // the packed parameters ride behind the saved activation (training) or in ws (inference)
         s.pack = align256(fused_pack_bytes(g));
         s.saved = s.act + s.pack;
-        // inference: the pack lives in ws, and so do the group outputs when the forward is split
-        s.fwd_ws = s.pack + (fused_fwd_needs_attn(g) ? s.act : 0);
+        // training needs no scratch; inference keeps the pack (and, when the forward is split,
+        // the group outputs) in ws, which the caller sizes as fwd_ws + saved
+        s.fwd_ws = 0;
     }
     if (s.fused_bwd) {
         s.fused_bwd_ws = align256(fused_bwd_ws_bytes(g));

@@ -53,6 +53,41 @@ def test_forced_staged_path_bf16(oracle, groups, shift):
                       extra_flags=gswa.GSWA_FORCE_STAGED)
 
 
+def test_forced_staged_path_wide_layer(oracle):
+    from paper_2409_06206_amd import gswa
+    parity.check_case(oracle, 1, 16, 24, 180, 6, 3, 8, 4, "bf16", regime="stress",
+                      extra_flags=gswa.GSWA_FORCE_STAGED)
+
+
+def test_no_cascade_flag_wide_layer(oracle):
+    """Split fused path (C=180) with Eq. 8 switched off."""
+    parity.check_case(oracle, 1, 16, 16, 180, 6, 2, 8, 4, "bf16", regime="stress", cascade=False)
+
+
+def test_kernel_timing_aid_reports_the_launched_kernels():
+    """gswa_profile_*: per-kernel HIP-event totals for one forward + backward."""
+    import torch
+    from paper_2409_06206_amd import gswa, runner
+    x, dy, p = parity.make_inputs(2, 16, 16, 60, 6, 2, 8, "bf16", synth.LAYER_SEED0, "init")
+    layer = runner.DeviceLayer(2, 16, 16, 60, 6, 2, 8, 4, "bf16")
+    layer.set_params(p)
+    layer.set_inputs(x, dy)
+    gswa.gswa_profile_enable(True)
+    try:
+        gswa.gswa_profile_collect()
+        layer.forward()
+        layer.backward()
+        res, dropped = gswa.gswa_profile_collect()
+    finally:
+        gswa.gswa_profile_enable(False)
+    torch.cuda.synchronize()
+    assert dropped == 0
+    assert res["fused_fwd"][1] == 1 and res["fused_bwd"][1] == 2 and res["reduce_partials"][1] == 1
+    assert all(ms > 0 for ms, _ in res.values())
+    layer.forward()
+    assert gswa.gswa_profile_collect()[0] == {}
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_no_cascade_flag(oracle, dtype):
     parity.check_case(oracle, 1, 16, 16, 60, 6, 3, 8, 4, dtype, regime="stress", cascade=False)
