@@ -296,3 +296,26 @@ def test_oracle_unchanged_on_fp32_parity_case(oracle):
             continue
         np.testing.assert_allclose(now[key]["probe"], dig["probe"], rtol=1e-10, atol=1e-14)
         np.testing.assert_allclose(now[key]["abs_sum"], dig["abs_sum"], rtol=1e-10)
+
+
+def _random_small_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        M = int(rng.choice([2, 3, 4]))
+        heads = int(rng.choice([1, 2, 3, 4, 6]))
+        groups = int(rng.choice([g for g in (1, 2, 3, 4, 6) if heads % g == 0]))
+        d = int(rng.integers(1, 4))
+        out.append((int(rng.integers(1, 3)), int(rng.integers(1, 4)) * M, int(rng.integers(1, 4)) * M,
+                    heads * d, heads, groups, M, int(rng.integers(0, M))))
+    return out
+
+
+@pytest.mark.parametrize("shape", _random_small_shapes(12, 5))
+def test_random_shapes_against_bruteforce(oracle, shape):
+    """Seeded random shapes (odd windows, one window per axis, d = 1, ...) against global attention."""
+    B, H, W, C, heads, groups, M, s = shape
+    x, _, p = make(B, H, W, C, heads, groups, M, seed=21)
+    y = run_fwd(oracle, x, p, heads=heads, groups=groups, window=M, shift=s)
+    y_ref, _ = refs.grouped_by_composition(x, p, heads, groups, M, s, True, core=refs.global_attention)
+    np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-11)

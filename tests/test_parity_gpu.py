@@ -204,3 +204,36 @@ def test_large_image_inference(oracle, name):
                                 cfg["groups"][0], cfg["window"], cfg["layers"][0], cfg["dtype"],
                                 backward=False)
     _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+def _random_shapes(n, seed):
+    """Seeded random layer shapes that satisfy the divisibility rules (staged path territory)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        M = int(rng.choice([2, 3, 4, 5, 6, 8]))
+        heads = int(rng.choice([1, 2, 3, 4, 6]))
+        groups = int(rng.choice([g for g in (1, 2, 3, 4, 6) if heads % g == 0]))
+        d = int(rng.integers(1, 9))
+        B, nh, nw = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        s = int(rng.integers(0, M))
+        out.append((B, nh * M, nw * M, heads * d, heads, groups, M, s))
+    return out
+
+
+@pytest.mark.parametrize("shape", _random_shapes(16, 2024))
+def test_random_shapes_fp32(oracle, shape):
+    B, H, W, C, heads, groups, M, s = shape
+    _say("random", shape)
+    parity.check_case(oracle, B, H, W, C, heads, groups, M, s, "f32", seed=synth.LAYER_SEED0 + 7,
+                      regime="stress")
+
+
+@pytest.mark.parametrize("shape", _random_shapes(6, 77))
+def test_random_shapes_bf16(oracle, shape):
+    # These shapes are tiny (a few windows, head width down to 1): the staged path stores q|k|v and
+    # their gradients in bf16, and with so few terms per sum that rounding noise does not average
+    # out, so the bound is doubled here; index mistakes would show as errors of order one.
+    B, H, W, C, heads, groups, M, s = shape
+    parity.check_case(oracle, B, H, W, C, heads, groups, M, s, "bf16", seed=synth.LAYER_SEED0 + 8,
+                      regime="stress", tol_scale=2.0)
