@@ -379,74 +379,67 @@ __global__ __launch_bounds__(256, 3) void fused_fwd_kernel(Geom g, const bf16_t 
 
 // ---------------------------------------------------------------------------------------
 // Split forward for wide layers: attention of heads [HB, HE) (one group or part of one), the
-// cascade input of Eq. 8 read back from the group outputs in memory, no projection.
+// cascade input of Eq. 8 read back from the group outputs in memory, no projection.  Window side
+// M is 8 or 16: a workgroup has N/16 waves, wave w owns tokens 16w..16w+15 of the window and holds
+// the N keys of each of its queries as N/16 score tiles.
 // ---------------------------------------------------------------------------------------
-template <class Cf, int HB_, int HE_> struct AttnChunkCfg {
-    static constexpr int HB = HB_, HE = HE_, NH = HE - HB;
+template <class Cf, int HB_, int HE_, int M_> struct AttnChunkCfg {
+    static constexpr int HB = HB_, HE = HE_, NH = HE - HB, M = M_, N = M * M, NWV = N / 16, KT = N / 16;
+    static constexpr int NTBL = (2 * M - 1) * (2 * M - 1);
+    static constexpr int VT_LD = N + 4;
     static constexpr int N_WQ = NH * 3 * Cf::ET * Cf::KS;
     static constexpr size_t SRC_WQ = Cf::P_WQ + (size_t)HB * 3 * Cf::ET * Cf::KS * 1024;
     static constexpr size_t OFF_WQ = 0;
     static constexpr size_t OFF_BIAS = (size_t)N_WQ * 1024;
-    static constexpr size_t OFF_K = OFF_BIAS + (size_t)16 * Cf::C;
-    static constexpr size_t OFF_VT = OFF_K + Cf::K_BYTES;
-    static constexpr size_t LDS_BYTES = OFF_VT + Cf::VT_BYTES;
+    static constexpr size_t OFF_TBLF = OFF_BIAS + (size_t)16 * Cf::C;          // fp32 [NH][NTBL]
+    static constexpr size_t OFF_K = OFF_TBLF + (((size_t)NH * NTBL * 4 + 15) & ~size_t(15));
+    static constexpr size_t K_BYTES = (size_t)KT * Cf::ET * 64 * 8;
+    static constexpr size_t OFF_VT = OFF_K + K_BYTES;
+    static constexpr size_t VT_BYTES = (size_t)16 * Cf::ET * VT_LD * 2;
+    static constexpr size_t LDS_BYTES = OFF_VT + VT_BYTES;
     static_assert(HB / Cf::HG == (HE - 1) / Cf::HG, "a chunk stays inside one head group");
+    static_assert(M == 8 || M == 16, "window side");
 };
 
-template <class Cf, int HB, int HE>
-__global__ __launch_bounds__(256, 2) void fused_attn_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
-                                                                const uint8_t *__restrict__ pack,
-                                                                const bf16_t *__restrict__ table,
-                                                                bf16_t *attn)
+template <class Cf, int HB, int HE, int M>
+__global__ __launch_bounds__(4 * M * M, M == 8 ? 2 : 1) void fused_attn_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                                                   const uint8_t *__restrict__ pack,
+                                                                                   const bf16_t *__restrict__ table,
+                                                                                   bf16_t *attn)
 {
-    using A = AttnChunkCfg<Cf, HB, HE>;
+    using A = AttnChunkCfg<Cf, HB, HE, M>;
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS;
-    constexpr int ET = Cf::ET, KS = Cf::KS, VT_LD = Cf::VT_LD, NH = A::NH;
-    constexpr int M = 8, NTBL = (2 * M - 1) * (2 * M - 1);
-    constexpr int GI = HB / HG; // the group of this chunk
+    constexpr int ET = Cf::ET, KS = Cf::KS, VT_LD = A::VT_LD, NH = A::NH, KT = A::KT, NTBL = A::NTBL;
+    constexpr int NTHREADS = 64 * A::NWV;
+    constexpr int GI = HB / HG;              // the group of this chunk
+    constexpr int ROWSTEP = (16 / M) * (2 * M - 1); // table-index step from one key tile to the next
     static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0, "dword-granular loads and stores");
-    static_assert((size_t)NTBL * NH * 2 <= Cf::K_BYTES + Cf::VT_BYTES, "table staging aliases the K/V buffers");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint4 *wq = reinterpret_cast<const uint4 *>(lds + A::OFF_WQ);
     const float *bqkv = reinterpret_cast<const float *>(lds + A::OFF_BIAS);
+    float *tblf = reinterpret_cast<float *>(lds + A::OFF_TBLF);
     uint2 *kbuf = reinterpret_cast<uint2 *>(lds + A::OFF_K);
     uint16_t *vt = reinterpret_cast<uint16_t *>(lds + A::OFF_VT);
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    for (int i = tid; i < A::N_WQ * 64; i += 256)
+    for (int i = tid; i < A::N_WQ * 64; i += NTHREADS)
         reinterpret_cast<uint4 *>(lds + A::OFF_WQ)[i] = reinterpret_cast<const uint4 *>(pack + A::SRC_WQ)[i];
-    for (int i = tid; i < C; i += 256)
+    for (int i = tid; i < C; i += NTHREADS)
         reinterpret_cast<uint4 *>(lds + A::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
-    uint16_t *tstage = reinterpret_cast<uint16_t *>(kbuf);
-    for (int i = tid; i < NTBL * NH; i += 256) tstage[i] = table[(i / NH) * HEADS + HB + i % NH].bits;
-    __syncthreads();
+    for (int i = tid; i < NTBL * NH; i += NTHREADS) tblf[i] = to_f32(table[(i % NTBL) * HEADS + HB + i / NTBL]);
 
-    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
-    uint32_t bias_frag[NH][8];
-#pragma unroll
-    for (int hx = 0; hx < NH; ++hx)
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int jp = 0; jp < 2; ++jp) {
-                uint32_t pr = 0;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int m = 16 * kt + 4 * q + 2 * jp + h;
-                    const int idx = (rn - (m >> 3) + M - 1) * (2 * M - 1) + (cn - (m & 7) + M - 1);
-                    pr |= (uint32_t)tstage[idx * NH + hx] << (16 * h);
-                }
-                bias_frag[hx][kt * 2 + jp] = pr;
-            }
+    // this lane's query inside the window; key 16kt+4q+j sits at (key_r0 + (16/M)kt, key_c0 + j)
+    const int nq = 16 * wv + l16, rn = nq / M, cn = nq % M;
+    const int key_r0 = (4 * q) / M, key_c0 = (4 * q) % M;
+    const int idx0 = (rn - key_r0 + M - 1) * (2 * M - 1) + (cn - key_c0 + M - 1);
     const int s = g.shift;
-    bool rmask[4], cmask[4];
+    bool cmask[4];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) rmask[kt] = (rn >= M - s) != ((2 * kt + (q >> 1)) >= M - s);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
+    for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((key_c0 + j) >= M - s);
+    const bool q_wrapped_row = rn >= M - s;
     __syncthreads();
 
     const int per_img = g.nwi * g.nwj;
@@ -517,39 +510,36 @@ __global__ __launch_bounds__(256, 2) void fused_attn_fwd_kernel(Geom g, const bf
             }
             __syncthreads();
 
-            f32x4 st[4];
+            // scores: tile kt holds keys 16kt+4q+j (rows) for this lane's query (column)
+            f32x4 st[KT];
+            float mx = -INFINITY;
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
-                st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) st[kt][j] = tblf[hx * NTBL + idx0 - ROWSTEP * kt - j];
 #pragma unroll
                 for (int et = 0; et < ET; ++et)
                     st[kt] = mma16(kbuf[(kt * ET + et) * 64 + lane], Qb[et], st[kt]);
             }
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t pr = bias_frag[hx][kt * 2 + (j >> 1)];
-                    st[kt][j] += (j & 1) ? bf16_hi(pr) : bf16_lo(pr);
-                }
             if (lastrow || lastcol) {
 #pragma unroll
-                for (int kt = 0; kt < 4; ++kt)
+                for (int kt = 0; kt < KT; ++kt) {
+                    const bool rmask = q_wrapped_row != ((key_r0 + (16 / M) * kt) >= M - s);
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        if ((lastrow && rmask[kt]) || (lastcol && cmask[j])) st[kt][j] += -100.0f;
+                        if ((lastrow && rmask) || (lastcol && cmask[j])) st[kt][j] += -100.0f;
+                }
             }
-            float mx = -INFINITY;
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+            for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) mx = fmaxf(mx, st[kt][j]);
             mx = qgroup_max(mx);
             const float mxl = mx * kLog2e;
             float sum = 0.f;
-            uint2 Pb[4];
+            uint2 Pb[KT];
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
+            for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float p = __builtin_amdgcn_exp2f(fmaf(st[kt][j], kLog2e, -mxl));
@@ -565,7 +555,7 @@ __global__ __launch_bounds__(256, 2) void fused_attn_fwd_kernel(Geom g, const bf
                 f32x4 oT = f32x4{0.f, 0.f, 0.f, 0.f};
                 const uint16_t *vrow = vt + (et * 16 + l16) * VT_LD + 4 * q;
 #pragma unroll
-                for (int kp = 0; kp < 2; ++kp) {
+                for (int kp = 0; kp < KT / 2; ++kp) {
                     const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp);
                     const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp + 16);
                     oT = mma32(make_uint4(a0.x, a0.y, a1.x, a1.y),
@@ -654,15 +644,15 @@ template <> struct FwdPlan<1> { static constexpr int N = 3; static constexpr int
 template <> struct FwdPlan<2> { static constexpr int N = 2; static constexpr int B[2] = {0, 3}, E[2] = {3, 6}; };
 template <> struct FwdPlan<3> { static constexpr int N = 3; static constexpr int B[3] = {0, 2, 4}, E[3] = {2, 4, 6}; };
 
-template <class Cf, int I = 0>
+template <class Cf, int M, int I = 0>
 hipError_t launch_attn_chunks(const Geom &g, const bf16_t *x, const uint8_t *pack, const bf16_t *table,
                               bf16_t *attn, hipStream_t s)
 {
     using Plan = FwdPlan<Cf::G>;
     if constexpr (I < Plan::N) {
-        using A = AttnChunkCfg<Cf, Plan::B[I], Plan::E[I]>;
+        using A = AttnChunkCfg<Cf, Plan::B[I], Plan::E[I], M>;
         static_assert(A::LDS_BYTES <= 160 * 1024, "LDS budget");
-        auto kern = fused_attn_fwd_kernel<Cf, Plan::B[I], Plan::E[I]>;
+        auto kern = fused_attn_fwd_kernel<Cf, Plan::B[I], Plan::E[I], M>;
         static bool attr_done = false;
         if (!attr_done && A::LDS_BYTES > 64 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -670,15 +660,15 @@ hipError_t launch_attn_chunks(const Geom &g, const bf16_t *x, const uint8_t *pac
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        int grid = (A::LDS_BYTES <= 80 * 1024 ? 2 : 1) * device_cu_count();
+        int grid = ((M == 8 && A::LDS_BYTES <= 80 * 1024) ? 2 : 1) * device_cu_count();
         if (grid > g.nW) grid = g.nW;
         {
             KernelTimer kt(K_ATTN_CHUNK_FWD, s);
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(256), A::LDS_BYTES, s, g, x, pack, table, attn);
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * A::NWV), A::LDS_BYTES, s, g, x, pack, table, attn);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_attn_chunks<Cf, I + 1>(g, x, pack, table, attn, s);
+        return launch_attn_chunks<Cf, M, I + 1>(g, x, pack, table, attn, s);
     }
     return hipSuccess;
 }
@@ -699,7 +689,8 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
     if (e != hipSuccess) return e;
     if constexpr (Cf::SPLIT) {
         if (!attn) return hipErrorInvalidValue;
-        e = launch_attn_chunks<Cf>(g, x, pack, table, attn, s);
+        e = g.M == 16 ? launch_attn_chunks<Cf, 16>(g, x, pack, table, attn, s)
+                      : launch_attn_chunks<Cf, 8>(g, x, pack, table, attn, s);
         if (e != hipSuccess) return e;
         constexpr size_t lds = (size_t)Cf::N_WPK * 1024 + 4 * Cf::C;
         auto kern = proj_gemm_kernel<Cf>;
@@ -740,9 +731,9 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
 
 bool fused_fwd_supported(const Geom &g)
 {
-    if (g.M != 8) return false;
+    if (g.M != 8 && g.M != 16) return false;
 #define X(C_, H_, G_) \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) return true;
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) return g.M == 8 || FusedCfg<C_, H_, G_>::SPLIT;
     GSWA_FUSED_SHAPES(X)
 #undef X
     return false;
