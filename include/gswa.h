@@ -24,6 +24,7 @@
  *     caller owns (hipMalloc or a torch tensor); the library never allocates, frees or
  *     synchronises.  All work is enqueued on `hip_stream` (a hipStream_t; NULL = default
  *     stream).  Buffers must stay valid until that work has run.
+ *     Every tensor pointer must be 16-byte aligned, `ws` 256-byte aligned (GSWA_EINVAL otherwise).
  *   - Layouts are C-contiguous with the last index fastest.
  *       x, y, dy, dx   [B, H, W, C]                         element type desc->dtype
  *       w_qkv          [groups, 3*Cg, Cg]  (out, in)        desc->dtype

@@ -1,8 +1,9 @@
-// Fused per-window GSWA kernels (bf16 storage, MFMA arithmetic, 8x8 windows).
+// Fused per-window GSWA kernels (bf16 storage, MFMA arithmetic).
 //
-// One workgroup of four wavefronts owns one window at a time; wave w owns the 16 tokens of
-// window rows 2w and 2w+1 through the whole layer.  Activations stay in registers in MFMA
-// operand / result layouts (see mfma.h); only K and V of a head cross waves, through LDS.
+// One workgroup owns one window at a time, one wavefront per 16 tokens (four waves for an 8x8
+// window: wave w owns window rows 2w and 2w+1) through the whole layer.  Activations stay in
+// registers in MFMA operand / result layouts (see mfma.h); only K and V of a head (and, in the
+// backward, the transposed score gradients) cross waves, through LDS.
 // The shift, the window partition and their inverses are the address computation of the
 // first load and the last store (Sec. "Patch Embedding", Sec. "Group Shifted Window Attention").
 #pragma once
@@ -44,8 +45,6 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr size_t P_WPK = P_WQT + (size_t)N_WQT * 512;
     static constexpr size_t P_END = P_WPK + (size_t)N_WPK * 1024;
     static constexpr size_t FWD_PACK_BYTES = P_WPT;        // [0, P_WPT)
-    static constexpr size_t BWD_PACK_OFF = P_WQ;           // [P_WQ, P_END)
-    static constexpr size_t BWD_PACK_BYTES = P_WPK - P_WQ;
     // forward LDS: the packed range, then the per-head K and V exchange buffers.  Kept under
     // 52 KB so that three workgroups share a compute unit.
     static constexpr size_t OFF_WC = P_WC, OFF_WP = P_WP, OFF_WQ = P_WQ, OFF_BIAS = P_BIAS;

@@ -1,7 +1,9 @@
-// Fused GSWA backward for 8x8 windows, bf16 storage: one kernel recomputes q, k, v, the scores
-// and the softmax of every head from x and the saved group outputs, and produces dx and
-// per-workgroup partial sums of all five parameter gradients (accumulated in registers over the
-// windows a workgroup owns); a second small kernel adds the partials in a fixed order.
+// Fused GSWA backward for 8x8 windows, bf16 storage.  The backward of a layer is a sequence of
+// launches of fused_bwd_kernel, one per chunk of heads in reverse order; each recomputes q, k, v,
+// the scores and the softmax of its heads from x and the saved group outputs, and produces the dx
+// slices of its groups and per-workgroup partial sums of the parameter gradients (accumulated in
+// registers over the windows a workgroup owns).  reduce_partials_kernel adds the partials in a
+// fixed order.  wproj_grad_kernel is the projection's weight gradient for wide layers.
 //
 // Per window, wave w owns tokens 16w..16w+15 both as queries and as keys.  Notation for a
 // matrix X[tokens x features] held as an MFMA result tile (see mfma.h):

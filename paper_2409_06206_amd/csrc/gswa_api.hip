@@ -27,6 +27,9 @@ int hip_fail(hipError_t e)
 
 size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 
+// true when every pointer is 16-byte aligned (the kernels use vector loads and stores)
+template <typename... P> bool aligned16(P... p) { return (((reinterpret_cast<uintptr_t>(p)) | ...) & 15) == 0; }
+
 // Checks the descriptor (divisibility rules of the window partition and of the head groups)
 // and derives the geometry.
 int make_geom(const gswa_desc *d, Geom *g)
@@ -232,6 +235,7 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
     if (rc != GSWA_OK) return rc;
     if (!x || !w_qkv || !b_qkv || !w_proj || !b_proj || !bias_table || !y || !ws) return GSWA_EINVAL;
     if (x == y || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    if (!aligned16(x, w_qkv, b_qkv, w_proj, b_proj, bias_table, y, saved)) return GSWA_EINVAL;
     Sizes s = make_sizes(desc, g);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->dtype == GSWA_F32)
@@ -265,6 +269,9 @@ int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const vo
         !dw_qkv || !db_qkv || !dw_proj || !db_proj || !dbias_table || !ws)
         return GSWA_EINVAL;
     if (dx == x || dx == dy || dx == saved || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    if (!aligned16(x, dy, w_qkv, b_qkv, w_proj, bias_table, saved, dx, dw_qkv, db_qkv, dw_proj, db_proj,
+                   dbias_table))
+        return GSWA_EINVAL;
     Sizes s = make_sizes(desc, g);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->dtype == GSWA_F32)

@@ -16,10 +16,9 @@ enum KernelId {
     K_ATTN_BWD,     // adjoint of the attention core of one group
     K_DX_LINEAR,    // dF of one group = dqkv Wqkv
     K_QKV_WGRAD,    // d w_qkv, d b_qkv of one group
-    K_PACK_FWD,     // weights into MFMA fragment order for the fused forward
+    K_PACK_FWD,     // parameters into MFMA fragment order (once per forward call, both passes use it)
     K_FUSED_FWD,    // whole forward layer, one launch
-    K_PACK_BWD,     // weights into MFMA fragment order for the fused backward
-    K_FUSED_BWD,    // dx, d(q|k|v) and bias-table partials, one launch
+    K_FUSED_BWD,    // dx and partial parameter gradients of one head chunk
     K_REDUCE,       // per-workgroup partial sums -> parameter gradients
     K_ATTN_CHUNK_FWD, // split forward: attention of one head chunk
     K_PROJ_GEMM,    // split forward: output projection (Eq. 7)

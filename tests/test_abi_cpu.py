@@ -58,6 +58,9 @@ def test_null_pointers_are_rejected_before_any_launch():
         gswa.gswa_backward(desc, fake, fake, fake, fake, fake, fake, fake, None, fake, fake, fake,
                            fake, fake, fake, fake, stream=0)
     assert ei.value.status == gswa.GSWA_EINVAL
+    with pytest.raises(gswa.GswaError) as ei:  # x not 16-byte aligned
+        gswa.gswa_forward(desc, fake + 2, fake, fake, fake, fake, fake, 2 * fake, None, fake, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
 
 
 @pytest.mark.parametrize("dtype,e", [("f32", 4), ("bf16", 2)])
