@@ -18,10 +18,20 @@ namespace gswa {
 // fragment f, lane l at f*64 + l, so one LDS read per lane fetches an operand), zero padded
 // (head width to 16*ET, group width to 32*KS).  The query rows of w_qkv and b_qkv are stored
 // multiplied by 1/sqrt(d), so scores need no separate scaling.  One buffer serves both passes:
-//   [ WC | WP | WQ | BIAS | WPT | WQT | WPK ]   forward reads [WC .. BIAS], backward [WQ .. WQT]
+//   [ WQH | WP2 | BF | WQ | BIAS | WPT | WQT | WPK ]
+// forward of narrow layers: WQH, WP2, BF, BIAS; backward: WQ .. WQT.
+//   WQH  Wqkv with the group's input channels in head-padded order (k-slot 16*hl' + e' <-> channel
+//        hl'*D + e'), the order in which a group's output tiles lie in registers, so that the
+//        cascade input of Eq. 8 is added to the x slice operand in place; K=32 steps over head
+//        pairs.  Query rows carry log2(e)/sqrt(d), so the scores come out in base-2 units.  The
+//        upper half of the last step multiplies four per-token inputs (1, r, c, r*c) and fills rows
+//        D .. D+3 of Q^T and K^T with the terms of the shift mask (see wave_fwd_kernel).
+//   WP2  Wproj, K=32 steps over head pairs
+//   BF   relative-position bias times log2(e) as bf16 score-tile operands, one per head and
+//        key/query tile offset
 // Wide layers (C > 64) do not fit their weights in LDS at once: their forward runs per head
 // chunk (SPLIT), takes the cascade input from memory, and projects in a separate GEMM that
-// uses WPK; WC and WP are empty for them.
+// uses WPK; WQH, WP2 and BF are empty for them.
 template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr int C = C_, HEADS = HEADS_, G = G_;
     static constexpr int D = C / HEADS, CG = C / G, HG = HEADS / G;
@@ -30,30 +40,24 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr int KSC = (C + 31) / 32; // K=32 steps over all channels
     static constexpr int OT = (C + 15) / 16;  // 16-row tiles of the output projection
     static constexpr bool SPLIT = C > 64;
-    static constexpr int N_WC = SPLIT ? 0 : (G - 1) * HG * 3 * ET * HG * ET; // Wqkv on the cascade input, K=16: (g,hl,t,et,hlp,etp)
-    static constexpr int N_WP = SPLIT ? 0 : OT * HEADS * ET;     // Wproj, K=16: (ot,hd,et)
+    static constexpr int NSTEP = HG / 2 + 1;   // K=32 steps over a group's heads: head pairs, then odd head | mask inputs
+    static constexpr int NDLT = 7;             // key/query tile offsets -3 .. 3 of an 8x8 window
+    static constexpr int N_WQH = SPLIT ? 0 : HEADS * 3 * NSTEP;  // (hd,t,step), 1 KB each
+    static constexpr int N_WP2 = SPLIT ? 0 : OT * (HEADS / 2);   // (ot,pair), 1 KB each
+    static constexpr int N_BF = SPLIT ? 0 : HEADS * NDLT;        // (hd,dlt), 512 B each
     static constexpr int N_WPK = SPLIT ? OT * KSC : 0;           // Wproj, K=32 over all channels: (ot,ks)
     static constexpr int N_WQ = HEADS * 3 * ET * KS;             // Wqkv on the x slice, K=32: (hd,t,et,ks)
     static constexpr int N_WPT = HEADS * ET * KSC;               // Wproj^T, K=32: (hd,et,ks)
     static constexpr int N_WQT = HEADS * 3 * ET * HG * ET;       // Wqkv^T, K=16: (hd,t,et,hlp,etp)
-    static constexpr size_t P_WC = 0;
-    static constexpr size_t P_WP = P_WC + (size_t)N_WC * 512;
-    static constexpr size_t P_WQ = P_WP + (size_t)N_WP * 512;
+    static constexpr size_t P_WQH = 0;
+    static constexpr size_t P_WP2 = P_WQH + (size_t)N_WQH * 1024;
+    static constexpr size_t P_BF = P_WP2 + (size_t)N_WP2 * 1024;
+    static constexpr size_t P_WQ = P_BF + (size_t)N_BF * 512;
     static constexpr size_t P_BIAS = P_WQ + (size_t)N_WQ * 1024; // fp32 b_qkv [3C], b_proj [C]
     static constexpr size_t P_WPT = P_BIAS + (size_t)16 * C;
     static constexpr size_t P_WQT = P_WPT + (size_t)N_WPT * 1024;
     static constexpr size_t P_WPK = P_WQT + (size_t)N_WQT * 512;
     static constexpr size_t P_END = P_WPK + (size_t)N_WPK * 1024;
-    static constexpr size_t FWD_PACK_BYTES = P_WPT;        // [0, P_WPT)
-    // forward LDS: the packed range, then the per-head K and V exchange buffers.  Kept under
-    // 52 KB so that three workgroups share a compute unit.
-    static constexpr size_t OFF_WC = P_WC, OFF_WP = P_WP, OFF_WQ = P_WQ, OFF_BIAS = P_BIAS;
-    static constexpr int VT_LD = 68;
-    static constexpr size_t OFF_K = FWD_PACK_BYTES;
-    static constexpr size_t K_BYTES = (size_t)4 * ET * 64 * 8;
-    static constexpr size_t OFF_VT = OFF_K + K_BYTES;
-    static constexpr size_t VT_BYTES = (size_t)16 * ET * VT_LD * 2;
-    static constexpr size_t FWD_LDS_BYTES = OFF_VT + VT_BYTES;
 };
 
 // True when a fused forward instantiation exists for this geometry (bf16 only).

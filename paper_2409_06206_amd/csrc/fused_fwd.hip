@@ -9,6 +9,9 @@ namespace gswa {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
+// Shift mask in the base-2 units of the fused forward: -100 * log2(e) rounded to bf16, so that the
+// terms of the mask product cancel exactly (-144 / log2(e) = -99.8 in natural units).
+constexpr float kMaskLog2 = -144.0f;
 
 // ---------------------------------------------------------------------------------------
 // Parameter packing (see FusedCfg): every thread assembles the operand of one (fragment, lane).
@@ -23,51 +26,74 @@ __global__ __launch_bounds__(256) void pack_params_kernel(const bf16_t *__restri
                                                           const bf16_t *__restrict__ b_qkv,
                                                           const bf16_t *__restrict__ w_proj,
                                                           const bf16_t *__restrict__ b_proj,
+                                                          const bf16_t *__restrict__ table,
                                                           uint8_t *__restrict__ pack)
 {
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET;
     constexpr int KS = Cf::KS, KSC = Cf::KSC;
-    constexpr int E_WC = Cf::N_WC * 64, E_WP = Cf::N_WP * 64, E_WQ = Cf::N_WQ * 64, E_WPT = Cf::N_WPT * 64,
-                  E_WQT = Cf::N_WQT * 64, E_BIAS = 4 * C;
+    constexpr int E_WQH = Cf::N_WQH * 64, E_WP2 = Cf::N_WP2 * 64, E_BF = Cf::N_BF * 64, E_WQ = Cf::N_WQ * 64,
+                  E_WPT = Cf::N_WPT * 64, E_WQT = Cf::N_WQT * 64, E_BIAS = 4 * C;
     const float qscale = 1.0f / sqrtf((float)D);
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     int l16 = i & 15, q = (i >> 4) & 3; // lane coordinates inside the current segment
 
-    if (i < E_WC) { // cascade input: m/n-index l16 -> out feature e; k-slots 4q+j -> prev-group channel
+    if (i < E_WQH) { // Wqkv, head-padded input order: l16 -> out feature e; k-slot s -> head 2*step + s/4, e' = 4q + s%4
         int f = i >> 6;
-        const int etp = f % ET; f /= ET;
-        const int hlp = f % HG; f /= HG;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3; f /= 3;
-        const int hl = f % HG;
-        const int gi = f / HG + 1;
-        const int e = 16 * et + l16;
-        uint32_t v[4];
-        for (int j = 0; j < 4; ++j) {
-            const int ep = 16 * etp + 4 * q + j;
-            v[j] = (e < D && ep < D)
-                       ? bf16_scaled(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + hlp * D + ep], t == 0 ? qscale : 1.0f)
-                       : 0u;
+        const int st = f % Cf::NSTEP; f /= Cf::NSTEP;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const float sc = t == 0 ? qscale * kLog2e : 1.0f;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int hlp = 2 * st + (s >> 2), ep = 4 * q + (s & 3);
+            float w = 0.f;
+            if (st < HG / 2 || s < 4) {
+                if (l16 < D && hlp < HG && ep < D)
+                    w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + l16) * CG + hlp * D + ep]) * sc;
+            } else if (q == 0 && l16 >= D && l16 < D + 4) {
+                // mask inputs (1, r, c, r*c) -> rows D..D+3: the query side carries the coefficients of
+                //   mask(n,m) = kMask * [ (r_n|c_n) + (1-2r_n)(1-c_n) r_m + (1-2c_n)(1-r_n) c_m - (1-2r_n)(1-2c_n) r_m c_m ],
+                // the key side the inputs themselves
+                const int fo = l16 - D, fi = s - 4;
+                const float cq[4][4] = {{0, 1, 1, -1}, {1, -2, -1, 2}, {1, -1, -2, 2}, {-1, 2, 2, -4}};
+                w = t == 0 ? kMaskLog2 * cq[fo][fi] : (t == 1 && fo == fi) ? 1.0f : 0.f;
+            }
+            v[s] = f32_to_bf16_bits(w);
         }
-        reinterpret_cast<uint2 *>(pack + Cf::P_WC)[i] = make_uint2(v[0] | v[1] << 16, v[2] | v[3] << 16);
+        reinterpret_cast<uint4 *>(pack + Cf::P_WQH)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
         return;
     }
-    i -= E_WC;
-    if (i < E_WP) { // Wproj: l16 -> output channel o; k-slots 4q+j -> input channel (hd, e)
-        int f = i >> 6;
-        const int et = f % ET; f /= ET;
-        const int hd = f % HEADS;
-        const int ot = f / HEADS;
+    i -= E_WQH;
+    if (i < E_WP2) { // Wproj: l16 -> output channel o; k-slot s -> head 2*pair + s/4, e = 4q + s%4
+        const int f = i >> 6;
+        const int pr = f % (HEADS / 2), ot = f / (HEADS / 2);
         const int o = 16 * ot + l16;
-        uint32_t v[4];
-        for (int j = 0; j < 4; ++j) {
-            const int e = 16 * et + 4 * q + j;
-            v[j] = (o < C && e < D) ? (uint32_t)w_proj[(size_t)o * C + hd * D + e].bits : 0u;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int hd = 2 * pr + (s >> 2), e = 4 * q + (s & 3);
+            v[s] = (o < C && e < D) ? (uint32_t)w_proj[(size_t)o * C + hd * D + e].bits : 0u;
         }
-        reinterpret_cast<uint2 *>(pack + Cf::P_WP)[i] = make_uint2(v[0] | v[1] << 16, v[2] | v[3] << 16);
+        reinterpret_cast<uint4 *>(pack + Cf::P_WP2)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
         return;
     }
-    i -= E_WP;
+    i -= E_WP2;
+    if (i < E_BF) { // bias (base-2 units) of score tile (key tile kt, query tile nt), nt - kt = dlt - 3, as a
+        // B operand: column l16 = query (2nt + l16/8, l16%8), k-slots 4q+j = key (2kt + q/2, 4(q%2) + j)
+        constexpr int M = 8;
+        const int f = i >> 6;
+        const int dlt = f % Cf::NDLT, hd = f / Cf::NDLT;
+        const int dr = 2 * (dlt - 3) + (l16 >> 3) - (q >> 1);
+        uint32_t v[4];
+        for (int j = 0; j < 4; ++j) {
+            const int dc = (l16 & 7) - 4 * (q & 1) - j;
+            v[j] = f32_to_bf16_bits(to_f32(table[((dr + M - 1) * (2 * M - 1) + (dc + M - 1)) * HEADS + hd]) * kLog2e);
+        }
+        reinterpret_cast<uint2 *>(pack + Cf::P_BF)[i] = make_uint2(v[0] | v[1] << 16, v[2] | v[3] << 16);
+        return;
+    }
+    i -= E_BF;
     if (i < E_WQ) { // Wqkv on the x slice: l16 -> out feature e; k-slots 8q+s -> channel 32ks+8q+s
         int f = i >> 6;
         const int ks = f % KS; f /= KS;
@@ -150,229 +176,265 @@ template <class Cf> __device__ __forceinline__ constexpr int fq(int hd, int t, i
 {
     return ((hd * 3 + t) * Cf::ET + et) * Cf::KS + ks;
 }
-template <class Cf> __device__ __forceinline__ constexpr int fc(int gi, int hl, int t, int et, int hlp, int etp)
+// ---------------------------------------------------------------------------------------
+// Forward with one wavefront per window (8x8 windows, narrow layers).  The wave holds all 64
+// tokens of its window as four 16-token tiles, so K, V and the probabilities never leave its
+// registers and no barrier is needed after the set-up.  The vector ALUs are the scarce unit
+// (the exponentials alone take a third of their time), so everything that can be phrased as a
+// matrix product runs on the MFMA pipe instead:
+//   * a score tile is one K=32 MFMA [K | I] [Q^T ; B]: the upper half adds the relative bias
+//     tile B (it depends on the key/query tile offset only: seven operands per head);
+//   * the shift mask (-100 between tokens of different wrap regions) is a rank-4 function of
+//     the two tokens, carried in the zero-padded rows D..D+3 of Q^T and K^T, which the Q/K
+//     projection itself fills from four per-token inputs (1, r, c, r*c);
+//   * the row maximum is subtracted by a rank-1 MFMA update of the score tiles;
+//   * the softmax denominator is row D of the PV product: column D of V is one;
+//   * scores are in base-2 units (log2(e) folded into the query weights and the bias).
+// The cascade input of Eq. 8 is added to the x operand of the next group in registers (the
+// packed output tiles of a group are the k-slots of the head-padded weight fragments), rounded
+// to bf16 like a stored activation.
+// ---------------------------------------------------------------------------------------
+template <class Cf> struct WaveFwdCfg {
+    static constexpr int NWAVES = 8, NTHREADS = 64 * NWAVES;
+    // LDS: the linear biases first (their many small reads then all have immediate offsets), then
+    // the packed range [0, P_WQ) as it is
+    static constexpr size_t OFF_BIAS = 0;
+    static constexpr size_t OFF_COPY = (size_t)16 * Cf::C;
+    static constexpr size_t OFF_WQH = OFF_COPY + Cf::P_WQH, OFF_WP2 = OFF_COPY + Cf::P_WP2, OFF_BF = OFF_COPY + Cf::P_BF;
+    static constexpr size_t COPY_BYTES = Cf::P_WQ;
+    static constexpr int COPY_IT = (int)((COPY_BYTES / 16 + NTHREADS - 1) / NTHREADS);
+    static constexpr size_t LDS_BYTES = OFF_COPY + COPY_BYTES;
+};
+
+// the value of row-group Q0 (lanes 16*Q0 .. 16*Q0+15) copied to the lanes of all four groups
+template <int Q0> __device__ __forceinline__ float qgroup_broadcast(float v)
 {
-    return (((((gi - 1) * Cf::HG + hl) * 3 + t) * Cf::ET + et) * Cf::HG + hlp) * Cf::ET + etp;
+    const unsigned u = __float_as_uint(v);
+    u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false); // {groups 0,1,0,1; groups 2,3,2,3}
+    const unsigned h = r[Q0 >> 1];
+    r = __builtin_amdgcn_permlane16_swap(h, h, false, false);       // {even group of each pair; odd group}
+    return __uint_as_float(r[Q0 & 1]);
 }
 
-template <class Cf>
-__global__ __launch_bounds__(256, 3) void fused_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
-                                                        const uint8_t *__restrict__ pack,
-                                                        const bf16_t *__restrict__ table,
-                                                        bf16_t *__restrict__ y, bf16_t *__restrict__ attn)
+// elementwise sum of two packed bf16 pairs, rounded to nearest even
+__device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b)
 {
-    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
-    constexpr int ET = Cf::ET, KS = Cf::KS, OT = Cf::OT, VT_LD = Cf::VT_LD;
-    constexpr int M = 8, NTBL = (2 * M - 1) * (2 * M - 1);
-    static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0, "dword-granular loads and stores");
-    static_assert((size_t)NTBL * HEADS * 2 <= Cf::K_BYTES + Cf::VT_BYTES, "table staging aliases the K buffers");
+    return pack_bf16x2(bf16_lo(a) + bf16_lo(b), bf16_hi(a) + bf16_hi(b));
+}
+
+__device__ __forceinline__ uint4 cat(uint2 lo, uint2 hi) { return make_uint4(lo.x, lo.y, hi.x, hi.y); }
+
+template <class Cf>
+__global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                          const uint8_t *__restrict__ pack,
+                                                          bf16_t *__restrict__ y, bf16_t *__restrict__ attn)
+{
+    using W = WaveFwdCfg<Cf>;
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS;
+    constexpr int OT = Cf::OT, NSTEP = Cf::NSTEP, NDLT = Cf::NDLT;
+    constexpr int M = 8, NTHREADS = W::NTHREADS;
+    static_assert(Cf::ET == 1 && D + 4 <= 16, "one 16-row tile per head with four spare rows");
+    static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0 && HEADS % 2 == 0, "dword-granular loads and stores");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const uint4 *wq = reinterpret_cast<const uint4 *>(lds + Cf::OFF_WQ);
-    const uint2 *wc = reinterpret_cast<const uint2 *>(lds + Cf::OFF_WC);
-    const uint2 *wp = reinterpret_cast<const uint2 *>(lds + Cf::OFF_WP);
-    const float *bqkv = reinterpret_cast<const float *>(lds + Cf::OFF_BIAS);
+    const uint4 *wqh = reinterpret_cast<const uint4 *>(lds + W::OFF_WQH);
+    const uint4 *wp2 = reinterpret_cast<const uint4 *>(lds + W::OFF_WP2);
+    const uint2 *bfr = reinterpret_cast<const uint2 *>(lds + W::OFF_BF);
+    const float *bqkv = reinterpret_cast<const float *>(lds + W::OFF_BIAS);
     const float *bproj = bqkv + 3 * C;
-    uint2 *kbuf = reinterpret_cast<uint2 *>(lds + Cf::OFF_K);
-    uint16_t *vt = reinterpret_cast<uint16_t *>(lds + Cf::OFF_VT);
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l16 = lane & 15, q = lane >> 4;
-
-    // ---- set-up: weights into LDS, bias table into registers in score-fragment order ----
-    for (int i = tid; i < (int)(Cf::FWD_PACK_BYTES / 16); i += 256)
-        reinterpret_cast<uint4 *>(lds)[i] = reinterpret_cast<const uint4 *>(pack)[i];
-    uint16_t *tstage = reinterpret_cast<uint16_t *>(kbuf);
-    for (int i = tid; i < NTBL * HEADS; i += 256) tstage[i] = table[i].bits;
-    __syncthreads();
-
-    // this lane's token inside the window: query column of every score tile it holds
-    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
-    uint32_t bias_frag[HEADS][8];
-#pragma unroll
-    for (int hd = 0; hd < HEADS; ++hd)
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int jp = 0; jp < 2; ++jp) {
-                uint32_t pr = 0;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int m = 16 * kt + 4 * q + 2 * jp + h;
-                    const int rm = m >> 3, cm = m & 7;
-                    const int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
-                    pr |= (uint32_t)tstage[idx * HEADS + hd] << (16 * h);
-                }
-                bias_frag[hd][kt * 2 + jp] = pr;
-            }
-    // shift mask: a key is masked for this lane's query when their wrap flags differ
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = g.shift;
-    bool rmask[4], cmask[4];
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt) rmask[kt] = (rn >= M - s) != ((2 * kt + (q >> 1)) >= M - s);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
-    __syncthreads();
-
+    const int cn = l16 & 7, rsub = l16 >> 3;
     const int per_img = g.nwi * g.nwj;
 
-    for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+    // x of a window in head-padded operand order: tile t, head hd: channels hd*D + 4q .. 4q+3 of
+    // token 16t + l16; and the mask inputs (1, r, c, r*c) of the tokens, r / c = "past the wrap in
+    // the last window row / column"
+    uint32_t tok[4]; // byte offset of the token's row (2*T*C fits 32 bits, checked on the host)
+    uint2 xh[HEADS][4], feat[4];
+    auto load_window = [&](int win) {
         const int b = win / per_img;
         const int wr = win - b * per_img;
         const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
-        int si = wi * M + rn + s, sj = wj * M + cn + s;
-        if (si >= g.H) si -= g.H;
-        if (sj >= g.W) sj -= g.W;
-        const long tok = ((long)b * g.H + si) * g.W + sj;
         const bool lastrow = s > 0 && wi == g.nwi - 1, lastcol = s > 0 && wj == g.nwj - 1;
-
-        // x row of this lane's token as B/A operands: k-slot 8q+s of step ks <-> channel 32ks+8q+s
-        const uint32_t *xrow = reinterpret_cast<const uint32_t *>(x + tok * C);
-        uint4 xf[G][KS];
+        int sj = wj * M + cn + s;
+        if (sj >= g.W) sj -= g.W;
+        const float c = (lastcol && cn >= M - s) ? 1.f : 0.f;
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi)
+        for (int t = 0; t < 4; ++t) {
+            int si = wi * M + 2 * t + rsub + s;
+            if (si >= g.H) si -= g.H;
+            tok[t] = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
+            const float r = (lastrow && 2 * t + rsub >= M - s) ? 1.f : 0.f;
+            feat[t] = make_uint2(pack_bf16x2(1.f, r), pack_bf16x2(c, r * c));
+        }
+    };
+    // the x slice of one group: a group is fetched while the previous one is being computed
+    auto load_group = [&](int gi) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                uint32_t dwv[4];
+        for (int t = 0; t < 4; ++t) {
+            const uint8_t *xrow = reinterpret_cast<const uint8_t *>(x) + tok[t];
 #pragma unroll
-                for (int dw = 0; dw < 4; ++dw) {
-                    const int c = 32 * ks + 8 * q + 2 * dw;
-                    dwv[dw] = c < CG ? xrow[(gi * CG + c) >> 1] : 0u;
-                }
-                xf[gi][ks] = make_uint4(dwv[0], dwv[1], dwv[2], dwv[3]);
+            for (int hl = 0; hl < HG; ++hl) {
+                const int hd = gi * HG + hl, e0 = 4 * q;
+                xh[hd][t].x = e0 < D ? *reinterpret_cast<const uint32_t *>(xrow + 2 * (hd * D + e0)) : 0u;
+                xh[hd][t].y = e0 + 2 < D ? *reinterpret_cast<const uint32_t *>(xrow + 2 * (hd * D + e0 + 2)) : 0u;
             }
+        }
+    };
 
-        uint2 Ob[HEADS][ET];
+    int win = wv * gridDim.x + blockIdx.x;
+    if (win < g.nW) { // in flight during the set-up
+        load_window(win);
+        load_group(0);
+    }
+
+    // ---- set-up: packed weights, bias operands and linear biases into LDS (unrolled, so that the
+    // loads of a thread are all in flight together); the workgroups start at different offsets
+    // so that they do not all ask for the same cache lines at once ----
+    {
+        constexpr int N16 = (int)(W::COPY_BYTES / 16);
+        const int rot = (int)((blockIdx.x * 5u) % (unsigned)W::COPY_IT);
+#pragma unroll
+        for (int k = 0; k < W::COPY_IT; ++k) {
+            int kk = k + rot;
+            if (kk >= W::COPY_IT) kk -= W::COPY_IT;
+            const int i = kk * NTHREADS + tid;
+            if (i < N16) reinterpret_cast<uint4 *>(lds + W::OFF_COPY)[i] = reinterpret_cast<const uint4 *>(pack)[i];
+        }
+        if (tid < C)
+            reinterpret_cast<uint4 *>(lds + W::OFF_BIAS)[tid] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[tid];
+    }
+    __syncthreads();
+
+    // constant operands: identity rows (upper half of the score MFMA's A operand) and the column of
+    // ones that spreads -max over a score tile
+    const uint2 ident = make_uint2((4 * q == l16 ? 0x3F80u : 0u) | (4 * q + 1 == l16 ? 0x3F800000u : 0u),
+                                   (4 * q + 2 == l16 ? 0x3F80u : 0u) | (4 * q + 3 == l16 ? 0x3F800000u : 0u));
+    const uint2 ones0 = make_uint2(q == 0 ? 0x3F80u : 0u, 0u);
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (; win < g.nW; win += W::NWAVES * gridDim.x) {
+        uint2 Ob[HEADS][4];
 #pragma unroll
         for (int hd = 0; hd < HEADS; ++hd) {
             const int gi = hd / HG, hl = hd % HG;
-            // ---- Q^T, K^T (rows = head features) and V (rows = tokens) of this wave's tokens ----
-            f32x4 qT[ET], kT[ET], vv[ET];
+            if (hl == 0 && gi > 0 && g.cascade) { // Eq. 8: the previous group's output joins this group's input
 #pragma unroll
-            for (int et = 0; et < ET; ++et) {
+                for (int hlp = 0; hlp < HG; ++hlp)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int e = 16 * et + 4 * q + j;
-                    qT[et][j] = e < D ? bqkv[gi * 3 * CG + hl * D + e] : 0.f;
-                    kT[et][j] = e < D ? bqkv[gi * 3 * CG + CG + hl * D + e] : 0.f;
-                }
-                const int ev = 16 * et + l16;
-                const float bv = ev < D ? bqkv[gi * 3 * CG + 2 * CG + hl * D + ev] : 0.f;
-                vv[et] = f32x4{bv, bv, bv, bv};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    qT[et] = mma32(wq[fq<Cf>(hd, 0, et, ks) * 64 + lane], xf[gi][ks], qT[et]);
-                    kT[et] = mma32(wq[fq<Cf>(hd, 1, et, ks) * 64 + lane], xf[gi][ks], kT[et]);
-                    vv[et] = mma32(xf[gi][ks], wq[fq<Cf>(hd, 2, et, ks) * 64 + lane], vv[et]);
-                }
-                if (gi > 0 && g.cascade) {
-#pragma unroll
-                    for (int hlp = 0; hlp < HG; ++hlp)
-#pragma unroll
-                        for (int etp = 0; etp < ET; ++etp) {
-                            const uint2 prev = Ob[(gi > 0 ? gi - 1 : 0) * HG + hlp][etp];
-                            qT[et] = mma16(wc[fc<Cf>(gi > 0 ? gi : 1, hl, 0, et, hlp, etp) * 64 + lane], prev, qT[et]);
-                            kT[et] = mma16(wc[fc<Cf>(gi > 0 ? gi : 1, hl, 1, et, hlp, etp) * 64 + lane], prev, kT[et]);
-                            vv[et] = mma16(prev, wc[fc<Cf>(gi > 0 ? gi : 1, hl, 2, et, hlp, etp) * 64 + lane], vv[et]);
-                        }
-                }
+                    for (int t = 0; t < 4; ++t) {
+                        const uint2 prev = Ob[(gi > 0 ? gi - 1 : 0) * HG + hlp][t];
+                        uint2 &xv = xh[gi * HG + hlp][t];
+                        xv.x = add_bf16x2(xv.x, prev.x);
+                        xv.y = add_bf16x2(xv.y, prev.y);
+                    }
             }
-            // ---- K and V of all 64 tokens to the other waves ----
-            uint2 Qb[ET];
+            // ---- Q^T, K^T (rows = head features, then the mask terms) and V (rows = tokens) ----
+            uint4 wqf[3][NSTEP];
 #pragma unroll
-            for (int et = 0; et < ET; ++et) {
-                Qb[et] = pack_bf16x4(qT[et]);
-                kbuf[(wv * ET + et) * 64 + lane] = pack_bf16x4(kT[et]);
-                *reinterpret_cast<uint2 *>(vt + (et * 16 + l16) * VT_LD + 16 * wv + 4 * q) =
-                    pack_bf16x4(vv[et]);
+            for (int t3 = 0; t3 < 3; ++t3)
+#pragma unroll
+                for (int st = 0; st < NSTEP; ++st) wqf[t3][st] = wqh[((hd * 3 + t3) * NSTEP + st) * 64 + lane];
+            f32x4 bq, bk;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = 4 * q + j;
+                bq[j] = e < D ? bqkv[gi * 3 * CG + hl * D + e] * kLog2e : 0.f;
+                bk[j] = e < D ? bqkv[gi * 3 * CG + CG + hl * D + e] : 0.f;
             }
-            __syncthreads();
+            // column D of V is one: row D of the PV product is the sum of the probabilities
+            const float bvs = l16 < D ? bqkv[gi * 3 * CG + 2 * CG + hl * D + l16] : (l16 == D ? 1.f : 0.f);
+            uint2 Qb[4], Kb[4], Vb[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                f32x4 qT = bq, kT = bk, vv = f32x4{bvs, bvs, bvs, bvs};
+#pragma unroll
+                for (int st = 0; st < HG / 2; ++st) {
+                    const uint4 xb = cat(xh[gi * HG + 2 * st][t], xh[gi * HG + 2 * st + 1][t]);
+                    qT = mma32(wqf[0][st], xb, qT);
+                    kT = mma32(wqf[1][st], xb, kT);
+                    vv = mma32(xb, wqf[2][st], vv);
+                }
+                {
+                    const uint2 xodd = HG % 2 ? xh[gi * HG + HG - 1][t] : make_uint2(0u, 0u);
+                    const uint4 xb = cat(xodd, feat[t]);
+                    qT = mma32(wqf[0][NSTEP - 1], xb, qT);
+                    kT = mma32(wqf[1][NSTEP - 1], xb, kT);
+                    if (HG % 2) vv = mma32(xb, wqf[2][NSTEP - 1], vv);
+                }
+                Qb[t] = pack_bf16x4(qT);
+                Kb[t] = pack_bf16x4(kT);
+                Vb[t] = pack_bf16x4(vv);
+            }
+            uint2 bfh[NDLT];
+#pragma unroll
+            for (int dlt = 0; dlt < NDLT; ++dlt) bfh[dlt] = bfr[(hd * NDLT + dlt) * 64 + lane];
+            if (hl == HG - 1 && gi + 1 < Cf::G) load_group(gi + 1); // this group's x is consumed
 
-            // ---- S^T tiles: rows = keys 16kt+4q+j, column = this lane's query ----
-            f32x4 st[4];
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
-                st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int nt = 0; nt < 4; ++nt) {
+                // S^T tiles (base-2 units): rows = keys 16kt+4q+j, column = query 16nt+l16
+                f32x4 st[4];
 #pragma unroll
-                for (int et = 0; et < ET; ++et)
-                    st[kt] = mma16(kbuf[(kt * ET + et) * 64 + lane], Qb[et], st[kt]);
-            }
-            float mx = -INFINITY;
+                for (int kt = 0; kt < 4; ++kt) st[kt] = mma16(ident, bfh[nt - kt + 3], zero4);
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+                for (int kt = 0; kt < 4; ++kt) st[kt] = mma16(Kb[kt], Qb[nt], st[kt]);
+                float mx = fmaxf(fmaxf(st[0][0], st[0][1]), fmaxf(st[0][2], st[0][3]));
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t pr = bias_frag[hd][kt * 2 + (j >> 1)];
-                    const float bv = (j & 1) ? bf16_hi(pr) : bf16_lo(pr);
-                    st[kt][j] += bv;
+                for (int kt = 1; kt < 4; ++kt)
+#pragma unroll
+                    for (int j = 0; j < 4; j += 2) mx = fmaxf(fmaxf(mx, st[kt][j]), st[kt][j + 1]);
+                mx = qgroup_max(mx);
+                const uint2 negmx = make_uint2(q == 0 ? pack_bf16x2(-mx, 0.f) : 0u, 0u);
+                uint2 Pb[4];
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) {
+                    st[kt] = mma16(ones0, negmx, st[kt]); // every row of the tile: - max (to bf16)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) st[kt][j] = __builtin_amdgcn_exp2f(st[kt][j]);
+                    Pb[kt] = pack_bf16x4(st[kt]);
                 }
-            if (lastrow || lastcol) {
-#pragma unroll
-                for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if ((lastrow && rmask[kt]) || (lastcol && cmask[j])) st[kt][j] += -100.0f;
-            }
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) mx = fmaxf(mx, st[kt][j]);
-            mx = qgroup_max(mx);
-            const float mxl = mx * kLog2e;
-            float sum = 0.f;
-            uint2 Pb[4];
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(st[kt][j], kLog2e, -mxl));
-                    st[kt][j] = p;
-                    sum += p;
-                }
-                Pb[kt] = pack_bf16x4(st[kt]);
-            }
-            sum = qgroup_sum(sum);
-            const float inv = 1.0f / sum;
-
-            // ---- O^T = V^T P^T: rows = head features, column = this lane's token ----
-#pragma unroll
-            for (int et = 0; et < ET; ++et) {
-                f32x4 oT = f32x4{0.f, 0.f, 0.f, 0.f};
-                const uint16_t *vrow = vt + (et * 16 + l16) * VT_LD + 4 * q;
-#pragma unroll
-                for (int kp = 0; kp < 2; ++kp) {
-                    const uint2 a0 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp);
-                    const uint2 a1 = *reinterpret_cast<const uint2 *>(vrow + 32 * kp + 16);
-                    oT = mma32(make_uint4(a0.x, a0.y, a1.x, a1.y),
-                               make_uint4(Pb[2 * kp].x, Pb[2 * kp].y, Pb[2 * kp + 1].x, Pb[2 * kp + 1].y), oT);
-                }
-                oT *= inv;
-                Ob[hd][et] = pack_bf16x4(oT);
+                // O^T = V^T P^T: rows = head features (row D = sum of the probabilities)
+                f32x4 oT = mma32(cat(Vb[0], Vb[1]), cat(Pb[0], Pb[1]), zero4);
+                oT = mma32(cat(Vb[2], Vb[3]), cat(Pb[2], Pb[3]), oT);
+                oT *= __builtin_amdgcn_rcpf(qgroup_broadcast<D / 4>(oT[D % 4]));
+                Ob[hd][nt] = pack_bf16x4(oT);
                 if (attn) {
-                    const int e0 = 16 * et + 4 * q;
-                    uint32_t *dst = reinterpret_cast<uint32_t *>(attn + tok * C + hd * D + e0);
-                    if (e0 < D) dst[0] = Ob[hd][et].x;
-                    if (e0 + 2 < D) dst[1] = Ob[hd][et].y;
+                    const int e0 = 4 * q;
+                    uint8_t *dst = reinterpret_cast<uint8_t *>(attn) + (tok[nt] + 2 * (hd * D + e0));
+                    if (e0 < D) *reinterpret_cast<uint32_t *>(dst) = Ob[hd][nt].x;
+                    if (e0 + 2 < D) *reinterpret_cast<uint32_t *>(dst + 4) = Ob[hd][nt].y;
                 }
             }
-            __syncthreads(); // K and V of this head are consumed; the next head may overwrite them
         }
 
-        // ---- Y^T = Wproj A^T + b: rows = output channels, column = this lane's token ----
+        // ---- Y^T = Wproj A^T + b: rows = output channels, column = token ----
 #pragma unroll
         for (int ot = 0; ot < OT; ++ot) {
-            f32x4 acc;
+            uint4 wpf[HEADS / 2];
+#pragma unroll
+            for (int pr = 0; pr < HEADS / 2; ++pr) wpf[pr] = wp2[(ot * (HEADS / 2) + pr) * 64 + lane];
+            f32x4 bp;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int o = 16 * ot + 4 * q + j;
-                acc[j] = o < C ? bproj[o] : 0.f;
+                bp[j] = o < C ? bproj[o] : 0.f;
             }
-#pragma unroll
-            for (int hd = 0; hd < HEADS; ++hd)
-#pragma unroll
-                for (int et = 0; et < ET; ++et)
-                    acc = mma16(wp[((ot * HEADS + hd) * ET + et) * 64 + lane], Ob[hd][et], acc);
             const int o0 = 16 * ot + 4 * q;
-            if (o0 < C) *reinterpret_cast<uint2 *>(y + tok * C + o0) = pack_bf16x4(acc);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                f32x4 acc = bp;
+#pragma unroll
+                for (int pr = 0; pr < HEADS / 2; ++pr) acc = mma32(wpf[pr], cat(Ob[2 * pr][t], Ob[2 * pr + 1][t]), acc);
+                if (o0 < C) *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(y) + (tok[t] + 2 * o0)) = pack_bf16x4(acc);
+            }
+        }
+        if (win + W::NWAVES * (int)gridDim.x < g.nW) {
+            load_window(win + W::NWAVES * gridDim.x);
+            load_group(0);
         }
     }
 }
@@ -680,10 +742,11 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
 {
     uint8_t *pack = static_cast<uint8_t *>(ws);
     {
-        constexpr int entries = (Cf::N_WC + Cf::N_WP + Cf::N_WQ + Cf::N_WPT + Cf::N_WQT + Cf::N_WPK) * 64 + 4 * Cf::C;
+        constexpr int entries =
+            (Cf::N_WQH + Cf::N_WP2 + Cf::N_BF + Cf::N_WQ + Cf::N_WPT + Cf::N_WQT + Cf::N_WPK) * 64 + 4 * Cf::C;
         KernelTimer kt(K_PACK_FWD, s);
         hipLaunchKernelGGL(pack_params_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, b_qkv,
-                           w_proj, b_proj, pack);
+                           w_proj, b_proj, table, pack);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -708,18 +771,21 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.T, attn, pack, y);
         return hipGetLastError();
     } else {
-        auto kern = fused_fwd_kernel<Cf>;
+        using W = WaveFwdCfg<Cf>;
+        static_assert(W::LDS_BYTES <= 160 * 1024, "LDS budget");
+        auto kern = wave_fwd_kernel<Cf>;
         static bool attr_done = false;
-        if (!attr_done && Cf::FWD_LDS_BYTES > 64 * 1024) {
+        if (!attr_done && W::LDS_BYTES > 64 * 1024) {
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cf::FWD_LDS_BYTES);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)W::LDS_BYTES);
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        int grid = 3 * device_cu_count();
+        // one window per wave: spread the windows over the compute units before filling a workgroup
+        int grid = device_cu_count();
         if (grid > g.nW) grid = g.nW;
         KernelTimer kt(K_FUSED_FWD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), Cf::FWD_LDS_BYTES, s, g, x, pack, table, y, attn);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * W::NWAVES), W::LDS_BYTES, s, g, x, pack, y, attn);
         return hipGetLastError();
     }
 }
@@ -733,7 +799,8 @@ bool fused_fwd_supported(const Geom &g)
 {
     if (g.M != 8 && g.M != 16) return false;
 #define X(C_, H_, G_) \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) return g.M == 8 || FusedCfg<C_, H_, G_>::SPLIT;
+    if (g.C == C_ && g.heads == H_ && g.groups == G_)                                                  \
+        return FusedCfg<C_, H_, G_>::SPLIT || (g.M == 8 && (long)g.T * g.C < (1L << 31)); /* 32-bit offsets */
     GSWA_FUSED_SHAPES(X)
 #undef X
     return false;

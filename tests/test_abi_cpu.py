@@ -85,7 +85,7 @@ def test_fused_path_sizes():
     T, C = 2 * 16 * 16, 60
     for G in (1, 2, 3, 6):
         saved, fwd, bwd = gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "groups": G}))
-        assert T * C * 2 < saved <= T * C * 2 + 192 * 1024
+        assert T * C * 2 < saved <= T * C * 2 + 256 * 1024
         big = gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "groups": G, "B": 8}))[0]
         assert big - 4 * T * C * 2 == saved - T * C * 2
         assert fwd == 0
