@@ -237,17 +237,20 @@ __global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *
     static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0 && HEADS % 2 == 0, "dword-granular loads and stores");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const uint4 *wqh = reinterpret_cast<const uint4 *>(lds + W::OFF_WQH);
-    const uint4 *wp2 = reinterpret_cast<const uint4 *>(lds + W::OFF_WP2);
-    const uint2 *bfr = reinterpret_cast<const uint2 *>(lds + W::OFF_BF);
-    const float *bqkv = reinterpret_cast<const float *>(lds + W::OFF_BIAS);
-    const float *bproj = bqkv + 3 * C;
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = g.shift;
     const int cn = l16 & 7, rsub = l16 >> 3;
     const int per_img = g.nwi * g.nwj;
+    // Global tensors as buffers (see make_buf).  This lane's four channels 4q .. 4q+3 of a 16-wide
+    // head tile are one 8-byte access; the pairs at or beyond D belong to the next head (or lie
+    // past the tensor): they are masked to zero when read and left out when written.
+    const uint32_t tbytes = (uint32_t)g.T * (2u * C);
+    const buf_t xbuf = make_buf(x, tbytes), ybuf = make_buf(y, tbytes), abuf = make_buf(attn, attn ? tbytes : 0u);
+    const bool lo_ok = 4 * q < D, hi_ok = 4 * q + 2 < D;
+    const uint32_t m_lo = lo_ok ? 0xffffffffu : 0u, m_hi = hi_ok ? 0xffffffffu : 0u;
+    const uint32_t c8 = 8u * q;
 
     // x of a window in head-padded operand order: tile t, head hd: channels hd*D + 4q .. 4q+3 of
     // token 16t + l16; and the mask inputs (1, r, c, r*c) of the tokens, r / c = "past the wrap in
@@ -272,17 +275,16 @@ __global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *
         }
     };
     // the x slice of one group: a group is fetched while the previous one is being computed
-    auto load_group = [&](int gi) {
+    auto load_group = [&, xbuf](int gi) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const uint8_t *xrow = reinterpret_cast<const uint8_t *>(x) + tok[t];
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int hl = 0; hl < HG; ++hl) {
-                const int hd = gi * HG + hl, e0 = 4 * q;
-                xh[hd][t].x = e0 < D ? *reinterpret_cast<const uint32_t *>(xrow + 2 * (hd * D + e0)) : 0u;
-                xh[hd][t].y = e0 + 2 < D ? *reinterpret_cast<const uint32_t *>(xrow + 2 * (hd * D + e0 + 2)) : 0u;
+                const int hd = gi * HG + hl;
+                xh[hd][t] = bload64(xbuf, tok[t] + c8 + 2u * (hd * D), 0u);
+                xh[hd][t].x &= m_lo;
+                xh[hd][t].y &= m_hi;
             }
-        }
     };
 
     int win = wv * gridDim.x + blockIdx.x;
@@ -317,6 +319,16 @@ __global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *
     const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (; win < g.nW; win += W::NWAVES * gridDim.x) {
+        // The LDS contents do not change from window to window, but their reads must stay inside
+        // this loop (hoisted out, the weights of all heads would sit in registers): the offset of
+        // LDS is made opaque once per window.
+        uint32_t lds0 = 0;
+        asm volatile("" : "+v"(lds0));
+        const uint4 *wqh = reinterpret_cast<const uint4 *>(lds + lds0 + W::OFF_WQH);
+        const uint4 *wp2 = reinterpret_cast<const uint4 *>(lds + lds0 + W::OFF_WP2);
+        const uint2 *bfr = reinterpret_cast<const uint2 *>(lds + lds0 + W::OFF_BF);
+        const float *bqkv = reinterpret_cast<const float *>(lds + lds0 + W::OFF_BIAS);
+        const float *bproj = bqkv + 3 * C;
         uint2 Ob[HEADS][4];
 #pragma unroll
         for (int hd = 0; hd < HEADS; ++hd) {
@@ -402,11 +414,14 @@ __global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *
                 oT = mma32(cat(Vb[2], Vb[3]), cat(Pb[2], Pb[3]), oT);
                 oT *= __builtin_amdgcn_rcpf(qgroup_broadcast<D / 4>(oT[D % 4]));
                 Ob[hd][nt] = pack_bf16x4(oT);
-                if (attn) {
-                    const int e0 = 4 * q;
-                    uint8_t *dst = reinterpret_cast<uint8_t *>(attn) + (tok[nt] + 2 * (hd * D + e0));
-                    if (e0 < D) *reinterpret_cast<uint32_t *>(dst) = Ob[hd][nt].x;
-                    if (e0 + 2 < D) *reinterpret_cast<uint32_t *>(dst + 4) = Ob[hd][nt].y;
+            }
+            if (attn) { // the group outputs, kept for the backward
+                if (hi_ok) {
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) bstore64(abuf, tok[nt] + c8 + 2u * (hd * D), 0u, Ob[hd][nt]);
+                } else if (lo_ok) {
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) bstore32(abuf, tok[nt] + c8 + 2u * (hd * D), 0u, Ob[hd][nt].x);
                 }
             }
         }
@@ -429,7 +444,7 @@ __global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *
                 f32x4 acc = bp;
 #pragma unroll
                 for (int pr = 0; pr < HEADS / 2; ++pr) acc = mma32(wpf[pr], cat(Ob[2 * pr][t], Ob[2 * pr + 1][t]), acc);
-                if (o0 < C) *reinterpret_cast<uint2 *>(reinterpret_cast<uint8_t *>(y) + (tok[t] + 2 * o0)) = pack_bf16x4(acc);
+                if (o0 < C) bstore64(ybuf, tok[t] + c8 + 32u * ot, 0u, pack_bf16x4(acc));
             }
         }
         if (win + W::NWAVES * (int)gridDim.x < g.nW) {

@@ -74,4 +74,28 @@ __device__ __forceinline__ float qgroup_sum(float v)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Global memory as a buffer resource: uniform base + 32-bit byte offset per lane (+ a uniform
+// offset and an immediate), so that no access needs a 64-bit address register; reads past
+// `bytes` return zero and writes there are dropped.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t buf_t;
+__device__ __forceinline__ buf_t make_buf(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint2 bload64(buf_t b, uint32_t voff, uint32_t soff)
+{
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(b, (int)voff, (int)soff, 0);
+    return make_uint2(v[0], v[1]);
+}
+__device__ __forceinline__ void bstore32(buf_t b, uint32_t voff, uint32_t soff, uint32_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(v, b, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ void bstore64(buf_t b, uint32_t voff, uint32_t soff, uint2 v)
+{
+    const u32x2 w = {v.x, v.y};
+    __builtin_amdgcn_raw_buffer_store_b64(w, b, (int)voff, (int)soff, 0);
+}
+
 } // namespace gswa
