@@ -415,13 +415,18 @@ __global__ __launch_bounds__(512, 1) void wave_fwd_kernel(Geom g, const bf16_t *
                 oT *= __builtin_amdgcn_rcpf(qgroup_broadcast<D / 4>(oT[D % 4]));
                 Ob[hd][nt] = pack_bf16x4(oT);
             }
-            if (attn) { // the group outputs, kept for the backward
+            if (attn && hl == HG - 1) { // the group's output, kept for the backward: its heads together,
+                                        // so that the pieces of a row reach memory as whole cache lines
                 if (hi_ok) {
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) bstore64(abuf, tok[nt] + c8 + 2u * (hd * D), 0u, Ob[hd][nt]);
+                    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                        for (int h2 = gi * HG; h2 <= hd; ++h2) bstore64(abuf, tok[nt] + c8 + 2u * (h2 * D), 0u, Ob[h2][nt]);
                 } else if (lo_ok) {
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) bstore32(abuf, tok[nt] + c8 + 2u * (hd * D), 0u, Ob[hd][nt].x);
+                    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                        for (int h2 = gi * HG; h2 <= hd; ++h2) bstore32(abuf, tok[nt] + c8 + 2u * (h2 * D), 0u, Ob[h2][nt].x);
                 }
             }
         }
