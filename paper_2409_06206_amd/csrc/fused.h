@@ -1,9 +1,12 @@
 // Fused per-window GSWA kernels (bf16 storage, MFMA arithmetic).
 //
-// One workgroup owns one window at a time, one wavefront per 16 tokens (four waves for an 8x8
-// window: wave w owns window rows 2w and 2w+1) through the whole layer.  Activations stay in
-// registers in MFMA operand / result layouts (see mfma.h); only K and V of a head (and, in the
-// backward, the transposed score gradients) cross waves, through LDS.
+// Activations stay in registers in MFMA operand / result layouts (see mfma.h).  Two ways of
+// giving a window to the hardware are in use:
+//   * one wavefront per window (forward of narrow layers): the wave holds all 64 tokens as four
+//     16-token tiles, so nothing crosses waves and no barrier is needed after the set-up;
+//   * one workgroup per window, one wavefront per 16 tokens (split forward of wide layers, every
+//     fused backward): K and V of a head, and in the backward the transposed score gradients,
+//     cross waves through LDS.
 // The shift, the window partition and their inverses are the address computation of the
 // first load and the last store (Sec. "Patch Embedding", Sec. "Group Shifted Window Attention").
 #pragma once

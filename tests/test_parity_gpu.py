@@ -196,6 +196,16 @@ def test_full_size_layers(oracle, name, groups, layer):
     _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
 
 
+@pytest.mark.parametrize("groups", [2, 3])
+def test_more_windows_than_wavefronts(oracle, groups):
+    """48 x (9 x 5) = 2160 windows: more than the 2048 wavefronts a forward launch has on 256
+    compute units, so some waves take a second window; odd window counts per image, shifted."""
+    _say("many windows", groups)
+    errs, _ = parity.check_case(oracle, 48, 72, 40, 60, 6, groups, 8, 4, "bf16",
+                                seed=synth.LAYER_SEED0 + 3, regime="stress")
+    _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
 @pytest.mark.parametrize("name", ["c5_m8", "c5_m16"])
 def test_large_image_inference(oracle, name):
     cfg = synth.CONFIGS[name]
