@@ -161,64 +161,27 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6); // wave index, held in a scalar register
 
-    for (int i = tid; i < (int)((B::OFF_BIAS - B::OFF_WQ) / 16); i += 256)
-        reinterpret_cast<uint4 *>(lds + B::OFF_WQ)[i] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQ)[i];
-    for (int i = tid; i < C; i += 256)
-        reinterpret_cast<uint4 *>(lds + B::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
-    for (int i = tid; i < (int)((B::OFF_WQT - B::OFF_WPT) / 16); i += 256)
-        reinterpret_cast<uint4 *>(lds + B::OFF_WPT)[i] = reinterpret_cast<const uint4 *>(pack + B::SRC_WPT)[i];
-    for (int i = tid; i < (int)((B::PACK_BYTES - B::OFF_WQT) / 16); i += 256)
-        reinterpret_cast<uint4 *>(lds + B::OFF_WQT)[i] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQT)[i];
-    for (int i = tid; i < NTBL * NH; i += 256) tblf[i] = to_f32(table[(i % NTBL) * HEADS + HB + i / NTBL]);
-
-    // this lane's token inside the window, and the bias-table row of its (query, key 4q) pair:
-    // the entry of key 16kt+4q+j is idx0 - 30kt - j
-    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
-    const int idx0 = (rn - (q >> 1) + M - 1) * (2 * M - 1) + (cn - 4 * (q & 1) + M - 1);
-    const int s = g.shift;
-    bool rmask[4], cmask[4];
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt) rmask[kt] = (rn >= M - s) != ((2 * kt + (q >> 1)) >= M - s);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
-    uint2 ident; // identity as a K=16 A operand: row l16, k-slots 4q+j
-    {
-        const uint32_t one = 0x3f80u;
-        const int d0 = l16 - 4 * q;
-        ident.x = (d0 == 0 ? one : 0u) | (d0 == 1 ? one << 16 : 0u);
-        ident.y = (d0 == 2 ? one : 0u) | (d0 == 3 ? one << 16 : 0u);
-    }
-    __syncthreads();
-
-    f32x4 tblacc[NH][4], dwacc[NH][KT], wpacc[KTP];
-#pragma unroll
-    for (int hd = 0; hd < NH; ++hd) {
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt) tblacc[hd][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int k = 0; k < KT; ++k) dwacc[hd][k] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-#pragma unroll
-    for (int k = 0; k < KTP; ++k) wpacc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-
+    // Rows of x, of the saved group outputs and of dy of this lane's token as MFMA operands (k-slots =
+    // channels).  The rows of a window are fetched while the previous window is finished (the first
+    // window's during the set-up), so that their latency is off the critical path.
     const int per_img = g.nwi * g.nwj;
-    const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
-
-    for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
+    const int s = g.shift;
+    auto token_of = [&](int win) {
         const int b = win / per_img;
         const int wr = win - b * per_img;
         const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
         int si = wi * M + rn + s, sj = wj * M + cn + s;
         if (si >= g.H) si -= g.H;
         if (sj >= g.W) sj -= g.W;
-        const long tok = ((long)b * g.H + si) * g.W + sj;
-        const bool lastrow = s > 0 && wi == g.nwi - 1, lastcol = s > 0 && wj == g.nwj - 1;
-
-        // rows of x, of the saved group outputs and of dy as MFMA operands (k-slots = channels)
+        return ((long)b * g.H + si) * g.W + sj;
+    };
+    uint4 xf[G][KS], af[G][KS], dyf[KSC];
+    auto load_rows = [&](int win) {
+        const long tok = token_of(win);
         const uint32_t *xrow = reinterpret_cast<const uint32_t *>(x + tok * C);
         const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + tok * C);
         const uint32_t *dyrow = reinterpret_cast<const uint32_t *>(dy + tok * C);
-        uint4 xf[G][KS], af[G][KS], dyf[KSC];
 #pragma unroll
         for (int gi = 0; gi < G; ++gi)
 #pragma unroll
@@ -245,6 +208,73 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
             }
             dyf[ks] = make_uint4(dwv[0], dwv[1], dwv[2], dwv[3]);
         }
+    };
+    // (with many groups the row registers are too many to hold two windows' worth at once)
+    constexpr bool PIPE = (2 * G * KS + KSC) * 4 <= 32;
+    if (PIPE && (int)blockIdx.x < g.nW) load_rows(blockIdx.x);
+
+    // set-up copies, unrolled so that a thread's loads are all in flight before its first store
+    {
+        constexpr int N_Q = (int)((B::OFF_BIAS - B::OFF_WQ) / 16), N_PT = (int)((B::OFF_WQT - B::OFF_WPT) / 16);
+        constexpr int N_QT = (int)((B::PACK_BYTES - B::OFF_WQT) / 16), N_T = NTBL * NH;
+        constexpr int I_Q = (N_Q + 255) / 256, I_PT = (N_PT + 255) / 256, I_QT = (N_QT + 255) / 256, I_T = (N_T + 255) / 256;
+        uint4 vq[I_Q], vpt[I_PT], vqt[I_QT], vb = make_uint4(0u, 0u, 0u, 0u);
+        uint16_t vt[I_T];
+#pragma unroll
+        for (int k = 0; k < I_Q; ++k) { const int i = 256 * k + tid; vq[k] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQ)[i < N_Q ? i : 0]; }
+#pragma unroll
+        for (int k = 0; k < I_PT; ++k) { const int i = 256 * k + tid; vpt[k] = reinterpret_cast<const uint4 *>(pack + B::SRC_WPT)[i < N_PT ? i : 0]; }
+#pragma unroll
+        for (int k = 0; k < I_QT; ++k) { const int i = 256 * k + tid; vqt[k] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQT)[i < N_QT ? i : 0]; }
+        if (tid < C) vb = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[tid];
+#pragma unroll
+        for (int k = 0; k < I_T; ++k) { const int i = 256 * k + tid; const int ii = i < N_T ? i : 0; vt[k] = table[(ii % NTBL) * HEADS + HB + ii / NTBL].bits; }
+#pragma unroll
+        for (int k = 0; k < I_Q; ++k) { const int i = 256 * k + tid; if (i < N_Q) reinterpret_cast<uint4 *>(lds + B::OFF_WQ)[i] = vq[k]; }
+#pragma unroll
+        for (int k = 0; k < I_PT; ++k) { const int i = 256 * k + tid; if (i < N_PT) reinterpret_cast<uint4 *>(lds + B::OFF_WPT)[i] = vpt[k]; }
+#pragma unroll
+        for (int k = 0; k < I_QT; ++k) { const int i = 256 * k + tid; if (i < N_QT) reinterpret_cast<uint4 *>(lds + B::OFF_WQT)[i] = vqt[k]; }
+        if (tid < C) reinterpret_cast<uint4 *>(lds + B::OFF_BIAS)[tid] = vb;
+#pragma unroll
+        for (int k = 0; k < I_T; ++k) { const int i = 256 * k + tid; if (i < N_T) tblf[i] = __uint_as_float((uint32_t)vt[k] << 16); }
+    }
+
+    // this lane's token inside the window, and the bias-table row of its (query, key 4q) pair:
+    // the entry of key 16kt+4q+j is idx0 - 30kt - j
+    const int idx0 = (rn - (q >> 1) + M - 1) * (2 * M - 1) + (cn - 4 * (q & 1) + M - 1);
+    bool rmask[4], cmask[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) rmask[kt] = (rn >= M - s) != ((2 * kt + (q >> 1)) >= M - s);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) cmask[j] = (cn >= M - s) != ((4 * (q & 1) + j) >= M - s);
+    uint2 ident; // identity as a K=16 A operand: row l16, k-slots 4q+j
+    {
+        const uint32_t one = 0x3f80u;
+        const int d0 = l16 - 4 * q;
+        ident.x = (d0 == 0 ? one : 0u) | (d0 == 1 ? one << 16 : 0u);
+        ident.y = (d0 == 2 ? one : 0u) | (d0 == 3 ? one << 16 : 0u);
+    }
+    __syncthreads();
+
+    f32x4 tblacc[NH][4], dwacc[NH][KT], wpacc[KTP];
+#pragma unroll
+    for (int hd = 0; hd < NH; ++hd) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) tblacc[hd][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < KT; ++k) dwacc[hd][k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int k = 0; k < KTP; ++k) wpacc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
+
+    for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+        if (!PIPE) load_rows(win);
+        const long tok = token_of(win);
+        const int wr = win % per_img;
+        const bool lastrow = s > 0 && wr / g.nwj == g.nwi - 1, lastcol = s > 0 && wr % g.nwj == g.nwj - 1;
 
         // ---- d w_proj, d b_proj: dY^T and A^T rows [channel][token] through LDS, K = 64 tokens ----
         if (WPROJ) {
@@ -562,6 +592,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                     }
             }
         }
+        if (PIPE && win + (int)gridDim.x < g.nW) load_rows(win + gridDim.x);
     }
 
     // ---- flush: this workgroup's partial sums, in parameter order.  The packed query weights
@@ -611,8 +642,11 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
         }
     }
     // bias-table gradient: (query, key) accumulators -> table entries, summed in a fixed order
-    float *mat = reinterpret_cast<float *>(lds + B::OFF_P); // [64 queries][64 keys] of one head
-    static_assert((size_t)64 * 64 * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
+    float *mat = reinterpret_cast<float *>(lds + B::OFF_P); // [64 queries][64 keys] of one head, rows 65 floats
+                                                            // apart (the 16 query rows a store touches then
+                                                            // fall on different banks)
+    constexpr int MP = 65;
+    static_assert((size_t)64 * MP * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
 #pragma unroll
     for (int hx = 0; hx < NH; ++hx) {
         const int hd = HB + hx;
@@ -620,14 +654,23 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mat[(16 * wv + l16) * 64 + 16 * kt + 4 * q + j] = tblacc[hx][kt][j];
+            for (int j = 0; j < 4; ++j) mat[(16 * wv + l16) * MP + 16 * kt + 4 * q + j] = tblacc[hx][kt][j];
         __syncthreads();
         if (tid < NTBL) {
+            // every (query row r, query column c) in a fixed trip count, so that the 64 reads are all
+            // in flight together; pairs whose key falls outside the window add zero
             const int dr = tid / (2 * M - 1) - (M - 1), dc = tid % (2 * M - 1) - (M - 1);
             float acc = 0.f;
-            for (int r = (dr > 0 ? dr : 0); r < (dr < 0 ? M + dr : M); ++r)
-                for (int c = (dc > 0 ? dc : 0); c < (dc < 0 ? M + dc : M); ++c)
-                    acc += mat[(r * M + c) * 64 + (r - dr) * M + (c - dc)];
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                const bool okr = r - dr >= 0 && r - dr < M;
+#pragma unroll
+                for (int c = 0; c < M; ++c) {
+                    const bool ok = okr && c - dc >= 0 && c - dc < M;
+                    const float v = mat[ok ? (r * M + c) * MP + (r - dr) * M + (c - dc) : 0];
+                    acc += ok ? v : 0.f;
+                }
+            }
             mine[B::P_TBL + tid * HEADS + hd] = acc;
         }
     }
