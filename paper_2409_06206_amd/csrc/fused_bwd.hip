@@ -167,18 +167,43 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     const int per_img = g.nwi * g.nwj;
     const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
     const int s = g.shift;
+    // window -> (image, window row, window column): quotients through a float reciprocal with a fix-up
+    // (exact for operands below 2^24), a fraction of the cost of the integer divisions
+    const float r_img = 1.0f / (float)per_img, r_nwj = 1.0f / (float)g.nwj;
+    auto fdiv = [](int a, int d, float rd) {
+        int qt = (int)((float)a * rd);
+        qt += (qt + 1) * d <= a ? 1 : 0;
+        qt -= qt * d > a ? 1 : 0;
+        return qt;
+    };
     auto token_of = [&](int win) {
-        const int b = win / per_img;
+        const int b = fdiv(win, per_img, r_img);
         const int wr = win - b * per_img;
-        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
+        const int wi = fdiv(wr, g.nwj, r_nwj), wj = wr - wi * g.nwj;
         int si = wi * M + rn + s, sj = wj * M + cn + s;
         if (si >= g.H) si -= g.H;
         if (sj >= g.W) sj -= g.W;
         return ((long)b * g.H + si) * g.W + sj;
     };
     uint4 xf[G][KS], af[G][KS], dyf[KSC];
+    uint2 cgrad[NH][ET]; // dF of the next group (Eq. 8) for the heads whose next group an earlier launch finished
     auto load_rows = [&](int win) {
         const long tok = token_of(win);
+#pragma unroll
+        for (int hx = 0; hx < NH; ++hx) {
+            const int hd = HB + hx, gi = hd / HG, hl = hd % HG;
+            const bool in_regs = HB <= (gi + 1) * HG && HE >= (gi + 2) * HG;
+#pragma unroll
+            for (int et = 0; et < ET; ++et) {
+                cgrad[hx][et] = make_uint2(0u, 0u);
+                if (gi < G - 1 && !in_regs && g.cascade) {
+                    const int e0 = 16 * et + 4 * q;
+                    const uint32_t *src = reinterpret_cast<const uint32_t *>(dx + tok * C + (gi + 1) * CG + hl * D + e0);
+                    if (e0 < D) cgrad[hx][et].x = src[0];
+                    if (e0 + 2 < D) cgrad[hx][et].y = src[1];
+                }
+            }
+        }
         const uint32_t *xrow = reinterpret_cast<const uint32_t *>(x + tok * C);
         const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + tok * C);
         const uint32_t *dyrow = reinterpret_cast<const uint32_t *>(dy + tok * C);
@@ -273,8 +298,8 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
         if (!PIPE) load_rows(win);
         const long tok = token_of(win);
-        const int wr = win % per_img;
-        const bool lastrow = s > 0 && wr / g.nwj == g.nwi - 1, lastcol = s > 0 && wr % g.nwj == g.nwj - 1;
+        const int wr = win - fdiv(win, per_img, r_img) * per_img, wi = fdiv(wr, g.nwj, r_nwj);
+        const bool lastrow = s > 0 && wi == g.nwi - 1, lastcol = s > 0 && wr - wi * g.nwj == g.nwj - 1;
 
         // ---- d w_proj, d b_proj: dY^T and A^T rows [channel][token] through LDS, K = 64 tokens ----
         if (WPROJ) {
@@ -345,10 +370,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                     if (next_in_regs) {
                         dOT[et] = cascT[hl][et];
                     } else { // the next group was finished by earlier launches: its dF is the dx slice
-                        const int e0 = 16 * et + 4 * q;
-                        const uint32_t *src =
-                            reinterpret_cast<const uint32_t *>(dx + tok * C + (gi + 1) * CG + hl * D + e0);
-                        const uint32_t lo = e0 < D ? src[0] : 0u, hi = e0 + 2 < D ? src[1] : 0u;
+                        const uint32_t lo = cgrad[hx][et].x, hi = cgrad[hx][et].y;
                         dOT[et] = f32x4{bf16_lo(lo), bf16_hi(lo), bf16_lo(hi), bf16_hi(hi)};
                     }
                 }
