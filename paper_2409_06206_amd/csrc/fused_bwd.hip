@@ -699,34 +699,38 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 }
 
 // Sums the per-workgroup partial vectors and scatters the five segments to their gradients.
-// One block handles 32 entries; eight slices of the block each sum an eighth of the partials,
-// eight independent loads in flight per thread; fixed summation order.
+// One block handles 32 entries; 32 slices of the block each sum a 32nd of the partials (16 loads per
+// thread at 512 partials, eight in flight at a time); fixed summation order.
 struct ReduceOut {
     float *ptr[5];
     int begin[6];
 };
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
-                                                              int n, ReduceOut out, int accumulate)
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
+                                                               int n, ReduceOut out, int accumulate)
 {
-    __shared__ float red[8][32];
+    constexpr int SL = 32; // slices of the partials, one per wave half: few additions per thread, all loads in flight
+    __shared__ float red[SL][33];
     const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
     const int i = blockIdx.x * 32 + col;
     float acc = 0.f;
     if (i < n) {
         float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         int w = slice;
-        for (; w + 56 < nparts; w += 64) {
+        for (; w + 7 * SL < nparts; w += 8 * SL) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(w + 8 * u) * n + i];
+            for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(w + SL * u) * n + i];
         }
-        for (; w < nparts; w += 8) a[0] += part[(size_t)w * n + i];
+        for (; w < nparts; w += SL) a[0] += part[(size_t)w * n + i];
         acc = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     }
     red[slice][col] = acc;
     __syncthreads();
     if (slice == 0 && i < n) {
-        acc = ((red[0][col] + red[1][col]) + (red[2][col] + red[3][col])) +
-              ((red[4][col] + red[5][col]) + (red[6][col] + red[7][col]));
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            t[u] = (red[4 * u][col] + red[4 * u + 1][col]) + (red[4 * u + 2][col] + red[4 * u + 3][col]);
+        acc = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
         int seg = 0;
         while (seg < 4 && i >= out.begin[seg + 1]) ++seg;
         float *dst = out.ptr[seg] + (i - out.begin[seg]);
@@ -939,7 +943,7 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     out.begin[4] = B::P_TBL; out.begin[5] = B::P_TOTAL;
     {
         KernelTimer kt(K_REDUCE, s);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::P_TOTAL + 31) / 32), dim3(256), 0, s, part, grid,
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::P_TOTAL + 31) / 32), dim3(1024), 0, s, part, grid,
                            B::P_TOTAL, out, accumulate);
     }
     return hipGetLastError();
