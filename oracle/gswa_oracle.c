@@ -19,11 +19,17 @@
  *       F_g  = x[src, g*Cg:(g+1)*Cg]  (+ O_{g-1} when g > 0 and cascade)   Eq. 8
  *       QKV  = F_g Wqkv_g^T + bqkv_g                                        Eq. 6
  *       for each head hl of the group, global head hd = g*hg + hl:
- *           S[n,m] = <q_n, k_m> / sqrt(d) + table[idx(n,m), hd]
+ *           S[n,m] = <q_n, k_m> / sqrt(e) + table[idx(n,m), hd]
  *                    + (s > 0 and reg(n) != reg(m) ? -100 : 0)
  *           idx(n,m) = (r_n - r_m + M-1)*(2M-1) + (c_n - c_m + M-1)
  *           P = softmax over m;   O_g[:, hl*d:(hl+1)*d] = P v
  *   A = concat_g O_g ;  y[src] = A Wproj^T + bproj                          Eq. 7
+ *
+ * Parameter allocation (Sec. "Parameter Allocation"): the query and key of a
+ * head may be narrower (or wider) than its value.  With e = dqk channels per
+ * head for q and k (dqk = 0 means e = d = C/heads, the plain layer), a group
+ * projects to Rg = 2*hg*e + Cg features laid out [q: hg*e | k: hg*e | v: Cg],
+ * head-major inside each block, and the scores are scaled by 1/sqrt(e).
  *
  * The paper leaves the attention core, the mask and the bias indexing to the
  * shifted-window prior art it builds on ("Akin to Swin Transformer"); the
@@ -52,6 +58,7 @@ typedef struct {
     int heads, groups;
     int window, shift;
     int cascade; /* 1: Eq. 8 applied, 0: groups independent */
+    int dqk;     /* channels of q and of k per head; 0: C / heads    */
 } gswa_oracle_shape;
 
 static int shape_ok(const gswa_oracle_shape *p)
@@ -61,8 +68,12 @@ static int shape_ok(const gswa_oracle_shape *p)
     if (p->C % p->heads || p->heads % p->groups) return 0;
     if (p->H % p->window || p->W % p->window) return 0;
     if (p->shift < 0 || p->shift >= p->window) return 0;
+    if (p->dqk < 0) return 0;
     return 1;
 }
+
+/* channels per head of q and k */
+static int qk_width(const gswa_oracle_shape *p) { return p->dqk > 0 ? p->dqk : p->C / p->heads; }
 
 static int band(int pos, int len, int M, int s)
 {
@@ -74,15 +85,16 @@ static int band(int pos, int len, int M, int s)
 /* Per-window scratch: everything one window needs in forward and backward. */
 typedef struct {
     int N, C, Cg, d, hg, heads;
+    int e, Qg, Rg; /* q/k channels per head and per group; projected features per group */
     long *src;    /* [N]   flat token offset (b*H*W + i*W + j) into x / y   */
     int *reg;     /* [N]   mask region id                                    */
     double *F;    /* [G][N][Cg]   group inputs                               */
-    double *QKV;  /* [G][N][3Cg]  projected q|k|v                            */
+    double *QKV;  /* [G][N][Rg]   projected q|k|v                            */
     double *P;    /* [heads][N][N] attention probabilities                   */
     double *A;    /* [N][C]  concatenated group outputs                      */
     /* backward only */
     double *dA;   /* [N][C]                                                  */
-    double *dQKV; /* [N][3Cg]                                                */
+    double *dQKV; /* [N][Rg]                                                 */
     double *dP;   /* [N][N]                                                  */
     double *dS;   /* [N][N]                                                  */
     double *dF;   /* [N][Cg]                                                 */
@@ -95,16 +107,17 @@ static int window_buf_alloc(window_buf *wb, const gswa_oracle_shape *p, int back
     memset(wb, 0, sizeof(*wb));
     wb->N = N; wb->C = C; wb->Cg = Cg; wb->heads = p->heads;
     wb->d = C / p->heads; wb->hg = p->heads / G;
+    wb->e = qk_width(p); wb->Qg = wb->hg * wb->e; wb->Rg = 2 * wb->Qg + Cg;
     wb->src = malloc(sizeof(long) * N);
     wb->reg = malloc(sizeof(int) * N);
     wb->F = malloc(sizeof(double) * G * N * Cg);
-    wb->QKV = malloc(sizeof(double) * G * N * 3 * Cg);
+    wb->QKV = malloc(sizeof(double) * G * N * wb->Rg);
     wb->P = malloc(sizeof(double) * (size_t)p->heads * N * N);
     wb->A = malloc(sizeof(double) * N * C);
     if (!wb->src || !wb->reg || !wb->F || !wb->QKV || !wb->P || !wb->A) return 0;
     if (backward) {
         wb->dA = malloc(sizeof(double) * N * C);
-        wb->dQKV = malloc(sizeof(double) * N * 3 * Cg);
+        wb->dQKV = malloc(sizeof(double) * N * wb->Rg);
         wb->dP = malloc(sizeof(double) * N * N);
         wb->dS = malloc(sizeof(double) * N * N);
         wb->dF = malloc(sizeof(double) * N * Cg);
@@ -139,13 +152,14 @@ static void window_forward(const gswa_oracle_shape *p, window_buf *wb, const dou
 {
     int M = p->window, N = wb->N, C = wb->C, G = p->groups, Cg = wb->Cg;
     int d = wb->d, hg = wb->hg, heads = wb->heads, s = p->shift;
-    double scale = 1.0 / sqrt((double)d);
+    int e_ = wb->e, Qg = wb->Qg, Rg = wb->Rg;
+    double scale = 1.0 / sqrt((double)e_);
 
     for (int g = 0; g < G; ++g) {
         double *F = wb->F + (size_t)g * N * Cg;
-        double *QKV = wb->QKV + (size_t)g * N * 3 * Cg;
-        const double *Wg = wqkv + (size_t)g * 3 * Cg * Cg;
-        const double *bg = bqkv + (size_t)g * 3 * Cg;
+        double *QKV = wb->QKV + (size_t)g * N * Rg;
+        const double *Wg = wqkv + (size_t)g * Rg * Cg;
+        const double *bg = bqkv + (size_t)g * Rg;
 
         for (int n = 0; n < N; ++n)
             for (int c = 0; c < Cg; ++c) {
@@ -155,25 +169,25 @@ static void window_forward(const gswa_oracle_shape *p, window_buf *wb, const dou
             }
 
         for (int n = 0; n < N; ++n)
-            for (int o = 0; o < 3 * Cg; ++o) {
+            for (int o = 0; o < Rg; ++o) {
                 double acc = bg[o];
                 for (int c = 0; c < Cg; ++c) acc += F[n * Cg + c] * Wg[o * Cg + c];
-                QKV[n * 3 * Cg + o] = acc;
+                QKV[n * Rg + o] = acc;
             }
 
         for (int hl = 0; hl < hg; ++hl) {
             int hd = g * hg + hl;
             double *P = wb->P + (size_t)hd * N * N;
-            const double *q = QKV + 0 * Cg + hl * d;
-            const double *k = QKV + 1 * Cg + hl * d;
-            const double *v = QKV + 2 * Cg + hl * d;
+            const double *q = QKV + hl * e_;
+            const double *k = QKV + Qg + hl * e_;
+            const double *v = QKV + 2 * Qg + hl * d;
             for (int n = 0; n < N; ++n) {
                 int rn = n / M, cn = n % M;
                 double mx = -INFINITY;
                 for (int m = 0; m < N; ++m) {
                     int rm = m / M, cm = m % M;
                     double dot = 0.0;
-                    for (int e = 0; e < d; ++e) dot += q[n * 3 * Cg + e] * k[m * 3 * Cg + e];
+                    for (int e = 0; e < e_; ++e) dot += q[n * Rg + e] * k[m * Rg + e];
                     int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
                     double sc = dot * scale + table[(size_t)idx * heads + hd];
                     if (s > 0 && wb->reg[n] != wb->reg[m]) sc += -100.0;
@@ -188,7 +202,7 @@ static void window_forward(const gswa_oracle_shape *p, window_buf *wb, const dou
                 for (int m = 0; m < N; ++m) P[n * N + m] /= sum;
                 for (int e = 0; e < d; ++e) {
                     double acc = 0.0;
-                    for (int m = 0; m < N; ++m) acc += P[n * N + m] * v[m * 3 * Cg + e];
+                    for (int m = 0; m < N; ++m) acc += P[n * N + m] * v[m * Rg + e];
                     wb->A[n * C + g * Cg + hl * d + e] = acc;
                 }
             }
@@ -199,8 +213,9 @@ static void window_forward(const gswa_oracle_shape *p, window_buf *wb, const dou
 /*
  * y = GSWA(x).  All arrays fp64, C-contiguous:
  *   x, y          [B, H, W, C]
- *   wqkv          [G, 3*Cg, Cg]  rows: q block, k block, v block; inside a block head-major
- *   bqkv          [G, 3*Cg]
+ *   wqkv          [G, Rg, Cg]  rows: q block, k block, v block; inside a block head-major
+ *                 (Rg = 3*Cg for the plain layer, 2*hg*dqk + Cg otherwise)
+ *   bqkv          [G, Rg]
  *   wproj         [C, C] (out, in),  bproj [C]
  *   table         [(2M-1)^2, heads]
  *   attn_out      optional [B, H, W, C]: concat of the group outputs A at each token's
@@ -266,13 +281,14 @@ int gswa_oracle_backward(const gswa_oracle_shape *p, const double *x, const doub
     if (!shape_ok(p)) return -1;
     int M = p->window, N = M * M, C = p->C, G = p->groups, Cg = C / G;
     int heads = p->heads, d = C / heads, hg = heads / G;
+    int e_ = qk_width(p), Qg = hg * e_, Rg = 2 * Qg + Cg;
     int nwi = p->H / M, nwj = p->W / M;
     long nW = (long)p->B * nwi * nwj;
-    size_t n_wqkv = (size_t)G * 3 * Cg * Cg, n_bqkv = (size_t)G * 3 * Cg;
+    size_t n_wqkv = (size_t)G * Rg * Cg, n_bqkv = (size_t)G * Rg;
     size_t n_wproj = (size_t)C * C, n_bproj = (size_t)C;
     size_t n_table = (size_t)(2 * M - 1) * (2 * M - 1) * heads;
     size_t n_par = n_wqkv + n_bqkv + n_wproj + n_bproj + n_table;
-    double scale = 1.0 / sqrt((double)d);
+    double scale = 1.0 / sqrt((double)e_);
     int fail = 0;
 
     int nthreads = 1;
@@ -325,19 +341,19 @@ int gswa_oracle_backward(const gswa_oracle_shape *p, const double *x, const doub
 
             for (int g = G - 1; g >= 0; --g) {
                 const double *F = wb.F + (size_t)g * N * Cg;
-                const double *QKV = wb.QKV + (size_t)g * N * 3 * Cg;
-                const double *Wg = wqkv + (size_t)g * 3 * Cg * Cg;
-                memset(wb.dQKV, 0, sizeof(double) * N * 3 * Cg);
+                const double *QKV = wb.QKV + (size_t)g * N * Rg;
+                const double *Wg = wqkv + (size_t)g * Rg * Cg;
+                memset(wb.dQKV, 0, sizeof(double) * N * Rg);
 
                 for (int hl = 0; hl < hg; ++hl) {
                     int hd = g * hg + hl;
                     const double *P = wb.P + (size_t)hd * N * N;
-                    const double *q = QKV + 0 * Cg + hl * d;
-                    const double *k = QKV + 1 * Cg + hl * d;
-                    const double *v = QKV + 2 * Cg + hl * d;
-                    double *dq = wb.dQKV + 0 * Cg + hl * d;
-                    double *dk = wb.dQKV + 1 * Cg + hl * d;
-                    double *dv = wb.dQKV + 2 * Cg + hl * d;
+                    const double *q = QKV + hl * e_;
+                    const double *k = QKV + Qg + hl * e_;
+                    const double *v = QKV + 2 * Qg + hl * d;
+                    double *dq = wb.dQKV + hl * e_;
+                    double *dk = wb.dQKV + Qg + hl * e_;
+                    double *dv = wb.dQKV + 2 * Qg + hl * d;
                     const double *dO = wb.dA + g * Cg + hl * d; /* row stride C */
 
                     /* O = P v  =>  dv = P^T dO,  dP = dO v^T */
@@ -345,8 +361,8 @@ int gswa_oracle_backward(const gswa_oracle_shape *p, const double *x, const doub
                         for (int m = 0; m < N; ++m) {
                             double acc = 0.0;
                             for (int e = 0; e < d; ++e) {
-                                acc += dO[n * C + e] * v[m * 3 * Cg + e];
-                                dv[m * 3 * Cg + e] += P[n * N + m] * dO[n * C + e];
+                                acc += dO[n * C + e] * v[m * Rg + e];
+                                dv[m * Rg + e] += P[n * N + m] * dO[n * C + e];
                             }
                             wb.dP[n * N + m] = acc;
                         }
@@ -365,9 +381,9 @@ int gswa_oracle_backward(const gswa_oracle_shape *p, const double *x, const doub
                             double ds = wb.dS[n * N + m];
                             int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
                             g_table[(size_t)idx * heads + hd] += ds;
-                            for (int e = 0; e < d; ++e) {
-                                dq[n * 3 * Cg + e] += scale * ds * k[m * 3 * Cg + e];
-                                dk[m * 3 * Cg + e] += scale * ds * q[n * 3 * Cg + e];
+                            for (int e = 0; e < e_; ++e) {
+                                dq[n * Rg + e] += scale * ds * k[m * Rg + e];
+                                dk[m * Rg + e] += scale * ds * q[n * Rg + e];
                             }
                         }
                     }
@@ -377,14 +393,14 @@ int gswa_oracle_backward(const gswa_oracle_shape *p, const double *x, const doub
                 for (int n = 0; n < N; ++n) {
                     for (int c = 0; c < Cg; ++c) {
                         double acc = 0.0;
-                        for (int o = 0; o < 3 * Cg; ++o) acc += wb.dQKV[n * 3 * Cg + o] * Wg[o * Cg + c];
+                        for (int o = 0; o < Rg; ++o) acc += wb.dQKV[n * Rg + o] * Wg[o * Cg + c];
                         wb.dF[n * Cg + c] = acc;
                     }
-                    for (int o = 0; o < 3 * Cg; ++o) {
-                        double go = wb.dQKV[n * 3 * Cg + o];
-                        g_bqkv[(size_t)g * 3 * Cg + o] += go;
+                    for (int o = 0; o < Rg; ++o) {
+                        double go = wb.dQKV[n * Rg + o];
+                        g_bqkv[(size_t)g * Rg + o] += go;
                         for (int c = 0; c < Cg; ++c)
-                            g_wqkv[((size_t)g * 3 * Cg + o) * Cg + c] += go * F[n * Cg + c];
+                            g_wqkv[((size_t)g * Rg + o) * Cg + c] += go * F[n * Cg + c];
                     }
                 }
                 /* F_g = x slice (+ O_{g-1}) */

@@ -28,7 +28,7 @@ def build(force=False):
 
 class _Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in
-                ("B", "H", "W", "C", "heads", "groups", "window", "shift", "cascade")]
+                ("B", "H", "W", "C", "heads", "groups", "window", "shift", "cascade", "dqk")]
 
 
 _lib = None
@@ -62,10 +62,12 @@ def _ptr(a):
     return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
 
 
-def param_shapes(C, heads, groups, window):
-    """Shapes of (w_qkv, b_qkv, w_proj, b_proj, bias_table)."""
+def param_shapes(C, heads, groups, window, dqk=0):
+    """Shapes of (w_qkv, b_qkv, w_proj, b_proj, bias_table); dqk = channels of q and of k per
+    head (0: C // heads, the plain layer)."""
     Cg = C // groups
-    return ((groups, 3 * Cg, Cg), (groups, 3 * Cg), (C, C), (C,),
+    Rg = 2 * (heads // groups) * (dqk or C // heads) + Cg
+    return ((groups, Rg, Cg), (groups, Rg), (C, C), (C,),
             ((2 * window - 1) ** 2, heads))
 
 
@@ -78,12 +80,12 @@ def set_threads(n):
 
 
 def forward(x, w_qkv, b_qkv, w_proj, b_proj, table, *, heads, groups, window, shift,
-            cascade=True, want_attn=False, want_probs=False):
+            cascade=True, want_attn=False, want_probs=False, dqk=0):
     """y = GSWA(x); x is [B,H,W,C].  Returns y, or (y, extras dict) if extras are asked for."""
     lib = _load()
     B, H, W, C = x.shape
-    shp = _Shape(B, H, W, C, heads, groups, window, shift, int(bool(cascade)))
-    ps = param_shapes(C, heads, groups, window)
+    shp = _Shape(B, H, W, C, heads, groups, window, shift, int(bool(cascade)), int(dqk))
+    ps = param_shapes(C, heads, groups, window, dqk)
     x = _f64(x, (B, H, W, C))
     args = [_f64(a, s) for a, s in zip((w_qkv, b_qkv, w_proj, b_proj, table), ps)]
     y = np.empty_like(x)
@@ -102,12 +104,12 @@ def forward(x, w_qkv, b_qkv, w_proj, b_proj, table, *, heads, groups, window, sh
 
 
 def backward(x, dy, w_qkv, b_qkv, w_proj, b_proj, table, *, heads, groups, window, shift,
-             cascade=True):
+             cascade=True, dqk=0):
     """Gradients of sum(dy*y): (dx, dw_qkv, db_qkv, dw_proj, db_proj, dtable)."""
     lib = _load()
     B, H, W, C = x.shape
-    shp = _Shape(B, H, W, C, heads, groups, window, shift, int(bool(cascade)))
-    ps = param_shapes(C, heads, groups, window)
+    shp = _Shape(B, H, W, C, heads, groups, window, shift, int(bool(cascade)), int(dqk))
+    ps = param_shapes(C, heads, groups, window, dqk)
     x = _f64(x, (B, H, W, C))
     dy = _f64(dy, (B, H, W, C))
     args = [_f64(a, s) for a, s in zip((w_qkv, b_qkv, w_proj, b_proj, table), ps)]

@@ -5,7 +5,9 @@ host-side rounding of inputs to the storage type.  Both the HIP path and the
 CPU oracle are fed from here so that they see identical values.
 
 Shapes follow SwinIR-style image-restoration settings: C in {60, 180}, 6 heads,
-8x8 windows, 64x64 training patches.  Two value regimes:
+8x8 windows, 64x64 training patches; the "agile" cases take the narrow query/key
+projections and 12x12 windows of Sec. "Parameter Allocation" on 48x48 patches.
+Two value regimes:
 
 * ``init``   x, dy ~ N(0,1); weights and bias table ~ N(0, 0.02^2); linear biases 0
              (the initialisation the Swin family trains from);
@@ -16,21 +18,24 @@ Shapes follow SwinIR-style image-restoration settings: C in {60, 180}, 6 heads,
 import numpy as np
 
 
-def param_shapes(C, heads, groups, window):
+def param_shapes(C, heads, groups, window, dqk=0):
+    """dqk: channels of q and of k per head (0: C // heads); a group projects to
+    2 * heads_per_group * dqk + Cg features [q | k | v]."""
     Cg = C // groups
+    Rg = 2 * (heads // groups) * (dqk or C // heads) + Cg
     return {
-        "w_qkv": (groups, 3 * Cg, Cg),
-        "b_qkv": (groups, 3 * Cg),
+        "w_qkv": (groups, Rg, Cg),
+        "b_qkv": (groups, Rg),
         "w_proj": (C, C),
         "b_proj": (C,),
         "table": ((2 * window - 1) ** 2, heads),
     }
 
 
-def layer_params(C, heads, groups, window, seed, regime="init"):
+def layer_params(C, heads, groups, window, seed, regime="init", dqk=0):
     """fp32 parameters of one layer, drawn in the order w_qkv, w_proj, table, b_qkv, b_proj."""
     rng = np.random.default_rng(seed)
-    shp = param_shapes(C, heads, groups, window)
+    shp = param_shapes(C, heads, groups, window, dqk)
     Cg = C // groups
     if regime == "init":
         p = {
@@ -95,6 +100,16 @@ CONFIGS = {
                   dtype="bf16"),
     "c5_m16": dict(B=1, H=512, W=512, C=180, heads=6, groups=(2,), window=16, layers=(8,),
                    dtype="bf16"),
+}
+# Narrow q/k and 12x12 windows (Sec. "Parameter Allocation", Sec. "Experimental Settings"): C = 60,
+# q and k of 16 resp. 32 channels in total over 4 heads (dqk = 4, 8), and 6 heads with dqk = 4.
+AGILE = {
+    "agile_h4_qk16": dict(B=32, H=48, W=48, C=60, heads=4, groups=2, window=12, dqk=4, layers=(0, 6),
+                          dtype="bf16"),
+    "agile_h4_qk32": dict(B=32, H=48, W=48, C=60, heads=4, groups=2, window=12, dqk=8, layers=(0, 6),
+                          dtype="bf16"),
+    "agile_h6_qk24": dict(B=32, H=48, W=48, C=60, heads=6, groups=2, window=12, dqk=4, layers=(0, 6),
+                          dtype="bf16"),
 }
 ACT_SEED = 0
 LAYER_SEED0 = 100

@@ -42,27 +42,30 @@ def global_additive_matrix(H, W, M, s, table_h):
     return add
 
 
-def global_attention(feat, w_qkv, b_qkv, table, nheads, M, s):
+def global_attention(feat, w_qkv, b_qkv, table, nheads, M, s, dqk=0):
     """Multi-head attention core without output projection, via global attention.
 
-    feat [B,H,W,Cc]; w_qkv [3Cc,Cc]; b_qkv [3Cc]; table [(2M-1)^2, nheads].
+    feat [B,H,W,Cc]; w_qkv [2Q+Cc,Cc]; b_qkv [2Q+Cc], Q = nheads*dqk channels of q and of k
+    (dqk = 0: Q = Cc); table [(2M-1)^2, nheads].
     Returns [B,H,W,Cc] at the tokens' own positions.
     """
     B, H, W, Cc = feat.shape
     d = Cc // nheads
+    e = dqk or d
+    Q = nheads * e
     t = feat.reshape(B, H * W, Cc).astype(np.float64)
     qkv = t @ w_qkv.T.astype(np.float64) + b_qkv
-    q, k, v = qkv[..., :Cc], qkv[..., Cc:2 * Cc], qkv[..., 2 * Cc:]
+    q, k, v = qkv[..., :Q], qkv[..., Q:2 * Q], qkv[..., 2 * Q:]
     out = np.empty_like(t)
     for h in range(nheads):
-        sl = slice(h * d, (h + 1) * d)
+        sl, sle = slice(h * d, (h + 1) * d), slice(h * e, (h + 1) * e)
         add = global_additive_matrix(H, W, M, s, table[:, h].astype(np.float64))
-        sc = np.einsum("bnd,bmd->bnm", q[..., sl], k[..., sl]) / np.sqrt(d) + add[None]
+        sc = np.einsum("bnd,bmd->bnm", q[..., sle], k[..., sle]) / np.sqrt(e) + add[None]
         out[..., sl] = _softmax(sc) @ v[..., sl]
     return out.reshape(B, H, W, Cc)
 
 
-def grouped_by_composition(x, p, heads, groups, M, s, cascade=True, core=global_attention):
+def grouped_by_composition(x, p, heads, groups, M, s, cascade=True, core=global_attention, dqk=0):
     """GSWA as a chain of plain multi-head cores on channel slices + one dense projection."""
     B, H, W, C = x.shape
     Cg, hg = C // groups, heads // groups
@@ -72,16 +75,19 @@ def grouped_by_composition(x, p, heads, groups, M, s, cascade=True, core=global_
         f = x[..., g * Cg:(g + 1) * Cg].astype(np.float64)
         if g > 0 and cascade:
             f = f + prev
-        prev = core(f, p["w_qkv"][g], p["b_qkv"][g], p["table"][:, g * hg:(g + 1) * hg], hg, M, s)
+        prev = core(f, p["w_qkv"][g], p["b_qkv"][g], p["table"][:, g * hg:(g + 1) * hg], hg, M, s,
+                    **({"dqk": dqk} if dqk else {}))
         outs.append(prev)
     a = np.concatenate(outs, axis=-1)
     return a @ p["w_proj"].T.astype(np.float64) + p["b_proj"], a
 
 
-def dense_window_msa(feat, w_qkv, b_qkv, table, nheads, M, s):
-    """Textbook (shifted-)window multi-head attention core with array copies; no projection."""
+def dense_window_msa(feat, w_qkv, b_qkv, table, nheads, M, s, dqk=0):
+    """Textbook (shifted-)window multi-head attention core with array copies; no projection.
+    dqk: channels per head of q and k when they differ from those of v."""
     B, H, W, Cc = feat.shape
     d, N = Cc // nheads, M * M
+    e = dqk or d
     f = np.roll(feat.astype(np.float64), shift=(-s, -s), axis=(1, 2)) if s else feat.astype(np.float64)
 
     def to_windows(a):
@@ -89,9 +95,11 @@ def dense_window_msa(feat, w_qkv, b_qkv, table, nheads, M, s):
         return a.reshape(B, H // M, M, W // M, M, ch).transpose(0, 1, 3, 2, 4, 5).reshape(-1, N, ch)
 
     win = to_windows(f)                                            # [nW*B, N, Cc]
-    qkv = (win @ w_qkv.T + b_qkv).reshape(-1, N, 3, nheads, d).transpose(2, 0, 3, 1, 4)
-    q, k, v = qkv[0], qkv[1], qkv[2]                               # [nWB, h, N, d]
-    att = np.einsum("whnd,whmd->whnm", q, k) * d ** -0.5
+    proj = win @ w_qkv.T + b_qkv
+    qk = proj[..., :2 * nheads * e].reshape(-1, N, 2, nheads, e).transpose(2, 0, 3, 1, 4)
+    q, k = qk[0], qk[1]                                            # [nWB, h, N, e]
+    v = proj[..., 2 * nheads * e:].reshape(-1, N, nheads, d).transpose(0, 2, 1, 3)
+    att = np.einsum("whnd,whmd->whnm", q, k) * e ** -0.5
 
     # relative position index table
     coords = np.stack(np.meshgrid(np.arange(M), np.arange(M), indexing="ij")).reshape(2, -1)

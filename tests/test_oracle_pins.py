@@ -9,8 +9,8 @@ from paper_2409_06206_amd import synth
 from tests import refs
 
 
-def make(B, H, W, C, heads, groups, M, seed=1, regime="stress"):
-    p = refs.as_f64(synth.layer_params(C, heads, groups, M, seed, regime))
+def make(B, H, W, C, heads, groups, M, seed=1, regime="stress", dqk=0):
+    p = refs.as_f64(synth.layer_params(C, heads, groups, M, seed, regime, dqk))
     x, dy = synth.activations(B, H, W, C, seed + 1000)
     return x.astype(np.float64), dy.astype(np.float64), p
 
@@ -46,6 +46,67 @@ def test_matches_bruteforce_global_attention(oracle, B, H, W, C, heads, groups, 
                                                    core=refs.global_attention)
         np.testing.assert_allclose(ex["attn"], a_ref, rtol=0, atol=1e-12)
         np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-12)
+
+
+QK_CASES = [
+    # B, H, W, C, heads, groups, M, s, dqk   (q and k narrower, equal to, or wider than v's d = C/heads)
+    (2, 8, 8, 12, 6, 1, 4, 2, 1),
+    (1, 8, 16, 12, 6, 2, 4, 1, 3),
+    (1, 16, 8, 12, 6, 3, 4, 0, 2),
+    (1, 8, 8, 12, 4, 2, 4, 3, 5),
+    (1, 8, 8, 12, 6, 6, 8, 4, 4),
+    (1, 24, 24, 12, 4, 2, 12, 6, 2),   # 12 x 12 windows, 144 tokens each
+    (1, 12, 24, 12, 6, 2, 12, 5, 4),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,M,s,dqk", QK_CASES)
+def test_narrow_query_key_matches_both_references(oracle, B, H, W, C, heads, groups, M, s, dqk):
+    """Sec. "Parameter Allocation": q and k of dqk channels per head, v of C/heads; 12 x 12 windows.
+    Against masked global attention and against the roll/partition statement."""
+    x, _, p = make(B, H, W, C, heads, groups, M, seed=13, dqk=dqk)
+    assert p["w_qkv"].shape == (groups, 2 * (heads // groups) * dqk + C // groups, C // groups)
+    for cascade in (True, False):
+        y, ex = run_fwd(oracle, x, p, heads=heads, groups=groups, window=M, shift=s,
+                        cascade=cascade, want_attn=True, dqk=dqk)
+        for core in (refs.global_attention, refs.dense_window_msa):
+            y_ref, a_ref = refs.grouped_by_composition(x, p, heads, groups, M, s, cascade, core=core,
+                                                       dqk=dqk)
+            np.testing.assert_allclose(ex["attn"], a_ref, rtol=0, atol=1e-12)
+            np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-12)
+
+
+def test_narrow_query_key_is_the_plain_layer_with_zero_rows(oracle):
+    """A layer with dqk < d equals the plain layer whose extra q/k rows are zero and whose q rows
+    are scaled by sqrt(d/dqk) (the score scale follows the q/k width); gradients map the same way."""
+    B, H, W, C, heads, G, M, s, e = 1, 8, 16, 12, 4, 2, 4, 2, 2
+    d, Cg, hg = C // heads, C // G, heads // G
+    x, dy, p = make(B, H, W, C, heads, G, M, seed=17, dqk=e)
+    kw = dict(heads=heads, groups=G, window=M, shift=s)
+    w_full = np.zeros((G, 3 * Cg, Cg))
+    b_full = np.zeros((G, 3 * Cg))
+    rows_small, rows_full = [], []
+    for t in range(2):                      # q block, k block
+        for hl in range(hg):
+            for c in range(e):
+                rows_small.append(t * hg * e + hl * e + c)
+                rows_full.append(t * Cg + hl * d + c)
+    rows_small += list(range(2 * hg * e, 2 * hg * e + Cg))
+    rows_full += list(range(2 * Cg, 3 * Cg))
+    gain = np.ones(len(rows_small))
+    gain[:hg * e] = np.sqrt(d / e)
+    w_full[:, rows_full] = p["w_qkv"][:, rows_small] * gain[None, :, None]
+    b_full[:, rows_full] = p["b_qkv"][:, rows_small] * gain[None, :]
+    pf = dict(p, w_qkv=w_full, b_qkv=b_full)
+    np.testing.assert_allclose(run_fwd(oracle, x, p, dqk=e, **kw), run_fwd(oracle, x, pf, **kw),
+                               rtol=0, atol=1e-12)
+    gs = run_bwd(oracle, x, dy, p, dqk=e, **kw)
+    gf = run_bwd(oracle, x, dy, pf, **kw)
+    np.testing.assert_allclose(gs[0], gf[0], rtol=0, atol=1e-11)                      # dx
+    np.testing.assert_allclose(gs[1], gf[1][:, rows_full] * gain[None, :, None], rtol=0, atol=1e-10)
+    np.testing.assert_allclose(gs[2], gf[2][:, rows_full] * gain[None, :], rtol=0, atol=1e-10)
+    for a, b in zip(gs[3:], gf[3:]):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-10)
 
 
 @pytest.mark.parametrize("B,H,W,C,heads,groups,M,s", CASES)
@@ -186,11 +247,18 @@ GRAD_CASES = [
 ]
 
 
-@pytest.mark.parametrize("B,H,W,C,heads,groups,M,s,cascade", GRAD_CASES)
-def test_gradients_against_central_differences(oracle, B, H, W, C, heads, groups, M, s, cascade):
+GRAD_CASES = [c + (0,) for c in GRAD_CASES] + [
+    (1, 8, 8, 12, 6, 2, 4, 2, True, 1),
+    (1, 8, 16, 12, 4, 2, 4, 1, True, 5),
+    (1, 12, 12, 12, 6, 3, 12, 6, True, 3),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,M,s,cascade,dqk", GRAD_CASES)
+def test_gradients_against_central_differences(oracle, B, H, W, C, heads, groups, M, s, cascade, dqk):
     """Every gradient, as directional derivatives of L = sum(dy * y) along random directions."""
-    x, dy, p = make(B, H, W, C, heads, groups, M, seed=7)
-    kw = dict(heads=heads, groups=groups, window=M, shift=s, cascade=cascade)
+    x, dy, p = make(B, H, W, C, heads, groups, M, seed=7, dqk=dqk)
+    kw = dict(heads=heads, groups=groups, window=M, shift=s, cascade=cascade, dqk=dqk)
     grads = run_bwd(oracle, x, dy, p, **kw)
     names = ("x", "w_qkv", "b_qkv", "w_proj", "b_proj", "table")
     rng = np.random.default_rng(11)
