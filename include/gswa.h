@@ -19,6 +19,12 @@
  *   idx(n,m) = (r_n - r_m + M-1)*(2M-1) + (c_n - c_m + M-1)
  * with Cg = C/groups, d = C/heads, heads/groups heads per group.
  *
+ * Narrow queries and keys (Sec. "Parameter Allocation": the channels of Q and K need not match
+ * those of V): with desc->dqk = e > 0 every head has e channels of q and of k while v and the
+ * head's output keep d channels; the scores are then scaled by 1/sqrt(e).  dqk = 0 is the plain
+ * layer (e = d).  Any window size up to 64 is accepted, including the 12 x 12 windows of
+ * Sec. "Experimental Settings".
+ *
  * Conventions for every entry point
  *   - `desc` is a HOST pointer.  Every other pointer is a DEVICE pointer into memory the
  *     caller owns (hipMalloc or a torch tensor); the library never allocates, frees or
@@ -27,9 +33,10 @@
  *     Every tensor pointer must be 16-byte aligned, `ws` 256-byte aligned (GSWA_EINVAL otherwise).
  *   - Layouts are C-contiguous with the last index fastest.
  *       x, y, dy, dx   [B, H, W, C]                         element type desc->dtype
- *       w_qkv          [groups, 3*Cg, Cg]  (out, in)        desc->dtype
- *                      out row o = t*Cg + hl*d + e, t in {0:q, 1:k, 2:v}, hl head in group
- *       b_qkv          [groups, 3*Cg]                       desc->dtype
+ *       w_qkv          [groups, Rg, Cg]  (out, in)          desc->dtype
+ *                      Rg = 2*hg*e + Cg out rows: q block (row hl*e + c), k block (hg*e + hl*e + c),
+ *                      v block (2*hg*e + hl*d + c), hl = head in group; 3*Cg rows when dqk == 0
+ *       b_qkv          [groups, Rg]                         desc->dtype
  *       w_proj         [C, C] (out, in); in column = (g*hg + hl)*d + e;  b_proj [C]
  *       bias_table     [(2*window-1)^2, heads]              desc->dtype
  *       dw_qkv, db_qkv, dw_proj, db_proj, dbias_table: shaped like their parameter, ALWAYS fp32
@@ -70,6 +77,7 @@ typedef struct gswa_desc {
     int32_t window, shift; /* H % window == 0, W % window == 0, 0 <= shift < window            */
     int32_t dtype;         /* GSWA_F32 or GSWA_BF16: x, y, dy, dx, weights, biases, bias table */
     uint32_t flags;        /* OR of GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED       */
+    int32_t dqk;           /* channels of q and of k per head; 0 = C / heads (the plain layer) */
 } gswa_desc;
 
 /*

@@ -34,7 +34,10 @@ struct Geom {
     int N;        // tokens per window, M*M
     int Cg;       // channels per group
     int hg;       // heads per group
-    int d;        // head width
+    int d;        // head width (of v and of the head's output)
+    int dq;       // channels of q and of k per head (Sec. "Parameter Allocation"; d for the plain layer)
+    int Qg;       // channels of q (and of k) per group, hg * dq
+    int Rg;       // features a group projects to, [q: Qg | k: Qg | v: Cg]
     int nwi, nwj; // windows along H and W
     int nW;       // windows in the batch
     long T;       // tokens in the batch

@@ -40,18 +40,23 @@ int make_geom(const gswa_desc *d, Geom *g)
     if (d->C % d->heads || d->heads % d->groups) return GSWA_EINVAL;
     if (d->H % d->window || d->W % d->window) return GSWA_EINVAL;
     if (d->shift < 0 || d->shift >= d->window) return GSWA_EINVAL;
+    if (d->dqk < 0) return GSWA_EINVAL;
     if (d->dtype != GSWA_F32 && d->dtype != GSWA_BF16) return GSWA_EINVAL;
     if (d->flags & ~(uint32_t)(GSWA_NO_CASCADE | GSWA_ACCUM_WGRAD | GSWA_FORCE_STAGED)) return GSWA_EINVAL;
     const long T = (long)d->B * d->H * d->W;
     const long nW = T / ((long)d->window * d->window);
-    if (T * 3 * d->C >= (1L << 40) || nW > 0x7fffffffL) return GSWA_EUNSUPPORTED;
-    if (d->window > 64) return GSWA_EUNSUPPORTED;
+    if (d->window > 64 || d->dqk > 4096) return GSWA_EUNSUPPORTED;
+    const int dq = d->dqk > 0 ? d->dqk : d->C / d->heads;
+    if (T * (2L * d->heads * dq + d->C) >= (1L << 40) || nW > 0x7fffffffL) return GSWA_EUNSUPPORTED;
     g->B = d->B; g->H = d->H; g->W = d->W; g->C = d->C;
     g->heads = d->heads; g->groups = d->groups; g->M = d->window; g->shift = d->shift;
     g->N = d->window * d->window;
     g->Cg = d->C / d->groups;
     g->hg = d->heads / d->groups;
     g->d = d->C / d->heads;
+    g->dq = dq;
+    g->Qg = g->hg * dq;
+    g->Rg = 2 * g->Qg + g->Cg;
     g->nwi = d->H / d->window; g->nwj = d->W / d->window;
     g->nW = (int)nW;
     g->T = T;
@@ -75,7 +80,7 @@ struct Sizes {
 
 bool use_fused_fwd(const gswa_desc *d, const Geom &g)
 {
-    return d->dtype == GSWA_BF16 && !(d->flags & GSWA_FORCE_STAGED) && fused_fwd_supported(g);
+    return d->dtype == GSWA_BF16 && !(d->flags & GSWA_FORCE_STAGED) && g.dq == g.d && fused_fwd_supported(g);
 }
 
 Sizes make_sizes(const gswa_desc *d, const Geom &g)
@@ -83,7 +88,7 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     Sizes s;
     const size_t e = elem_size(d);
     s.saved = align256((size_t)g.T * g.C * e);
-    s.qkv = align256((size_t)g.T * 3 * g.Cg * e);
+    s.qkv = align256((size_t)g.T * g.Rg * e);
     s.fwd_ws = s.qkv;
     s.bwd_ws = 2 * s.qkv;
     s.fused_fwd = use_fused_fwd(d, g);
@@ -113,15 +118,15 @@ int forward_staged(const Geom &g, const Sizes &sz, const T *x, const T *w_qkv, c
 {
     T *qkv = reinterpret_cast<T *>(ws);
     T *attn = saved ? saved : reinterpret_cast<T *>(ws + sz.qkv);
-    const int C = g.C, Cg = g.Cg;
+    const int C = g.C, Cg = g.Cg, Rg = g.Rg;
     for (int grp = 0; grp < g.groups; ++grp) {
         LinearArgs la{};
         la.a1 = x + grp * Cg; la.lda1 = C;
         if (grp > 0 && g.cascade) { la.a2 = attn + (grp - 1) * Cg; la.lda2 = C; }
-        la.w = w_qkv + (size_t)grp * 3 * Cg * Cg; la.w_sn = Cg; la.w_sk = 1;
-        la.bias = b_qkv + (size_t)grp * 3 * Cg;
-        la.out = qkv; la.ldout = 3 * Cg;
-        la.rows = g.T; la.N = 3 * Cg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
+        la.w = w_qkv + (size_t)grp * Rg * Cg; la.w_sn = Cg; la.w_sk = 1;
+        la.bias = b_qkv + (size_t)grp * Rg;
+        la.out = qkv; la.ldout = Rg;
+        la.rows = g.T; la.N = Rg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
         GSWA_HIP(launch_linear<T>(la, st));
         GSWA_HIP(launch_attn_fwd<T>(g, grp, qkv, table, attn, st));
     }
@@ -143,10 +148,10 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
 {
     T *qkv = reinterpret_cast<T *>(ws);
     T *dqkv = reinterpret_cast<T *>(ws + sz.qkv);
-    const int C = g.C, Cg = g.Cg, G = g.groups;
+    const int C = g.C, Cg = g.Cg, G = g.groups, Rg = g.Rg;
     if (!(flags & GSWA_ACCUM_WGRAD)) {
-        GSWA_HIP(launch_fill_zero(dw_qkv, (size_t)G * 3 * Cg * Cg, st));
-        GSWA_HIP(launch_fill_zero(db_qkv, (size_t)G * 3 * Cg, st));
+        GSWA_HIP(launch_fill_zero(dw_qkv, (size_t)G * Rg * Cg, st));
+        GSWA_HIP(launch_fill_zero(db_qkv, (size_t)G * Rg, st));
         GSWA_HIP(launch_fill_zero(dw_proj, (size_t)C * C, st));
         GSWA_HIP(launch_fill_zero(db_proj, (size_t)C, st));
         GSWA_HIP(launch_fill_zero(dtable, (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads, st));
@@ -160,40 +165,40 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     GSWA_HIP(launch_wgrad<T>(wp, st));
 
     for (int grp = G - 1; grp >= 0; --grp) {
-        const T *wg = w_qkv + (size_t)grp * 3 * Cg * Cg;
+        const T *wg = w_qkv + (size_t)grp * Rg * Cg;
         const bool has_prev = grp > 0 && g.cascade;
         // recompute q|k|v of the group (Eq. 6, 8)
         LinearArgs la{};
         la.a1 = x + grp * Cg; la.lda1 = C;
         if (has_prev) { la.a2 = attn + (grp - 1) * Cg; la.lda2 = C; }
         la.w = wg; la.w_sn = Cg; la.w_sk = 1;
-        la.bias = b_qkv + (size_t)grp * 3 * Cg;
-        la.out = qkv; la.ldout = 3 * Cg;
-        la.rows = g.T; la.N = 3 * Cg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
+        la.bias = b_qkv + (size_t)grp * Rg;
+        la.out = qkv; la.ldout = Rg;
+        la.rows = g.T; la.N = Rg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
         GSWA_HIP(launch_linear<T>(la, st));
-        // dO_g = dy Wproj[:, slice g] (+ dF_{g+1}, which is dx[:, slice g+1]) into the v third of dqkv
+        // dO_g = dy Wproj[:, slice g] (+ dF_{g+1}, which is dx[:, slice g+1]) into the v part of dqkv
         LinearArgs lo{};
         lo.a1 = dy; lo.lda1 = C;
         lo.w = w_proj + grp * Cg; lo.w_sn = 1; lo.w_sk = C;
         if (grp < G - 1 && g.cascade) { lo.add = dx + (grp + 1) * Cg; lo.ldadd = C; }
-        lo.out = dqkv + 2 * Cg; lo.ldout = 3 * Cg;
+        lo.out = dqkv + 2 * g.Qg; lo.ldout = Rg;
         lo.rows = g.T; lo.N = Cg; lo.K = C; lo.prof_id = K_DO_LINEAR;
         GSWA_HIP(launch_linear<T>(lo, st));
         GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, dtable, st));
         // dF_g = dqkv Wqkv_g  ->  dx[:, slice g]
         LinearArgs lx{};
-        lx.a1 = dqkv; lx.lda1 = 3 * Cg;
+        lx.a1 = dqkv; lx.lda1 = Rg;
         lx.w = wg; lx.w_sn = 1; lx.w_sk = Cg;
         lx.out = dx + grp * Cg; lx.ldout = C;
-        lx.rows = g.T; lx.N = Cg; lx.K = 3 * Cg; lx.prof_id = K_DX_LINEAR;
+        lx.rows = g.T; lx.N = Cg; lx.K = Rg; lx.prof_id = K_DX_LINEAR;
         GSWA_HIP(launch_linear<T>(lx, st));
         WgradArgs wq{};
-        wq.dout = dqkv; wq.lddout = 3 * Cg;
+        wq.dout = dqkv; wq.lddout = Rg;
         wq.a1 = x + grp * Cg; wq.lda1 = C;
         if (has_prev) { wq.a2 = attn + (grp - 1) * Cg; wq.lda2 = C; }
-        wq.dw = dw_qkv + (size_t)grp * 3 * Cg * Cg;
-        wq.db = db_qkv + (size_t)grp * 3 * Cg;
-        wq.rows = g.T; wq.N = 3 * Cg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
+        wq.dw = dw_qkv + (size_t)grp * Rg * Cg;
+        wq.db = db_qkv + (size_t)grp * Rg;
+        wq.rows = g.T; wq.N = Rg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
         GSWA_HIP(launch_wgrad<T>(wq, st));
     }
     return GSWA_OK;

@@ -33,13 +33,13 @@ struct WgradArgs {
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s);
 
-// Attention core of head group `grp` (Eq. 6 right-hand side): reads q|k|v [T, 3Cg] through the
+// Attention core of head group `grp` (Eq. 6 right-hand side): reads q|k|v [T, Rg] through the
 // shift/partition map, writes O into columns of attn_out [T, C] at the tokens' own positions.
 template <typename T>
 hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table, T *attn_out,
                            hipStream_t s);
 
-// Adjoint of the attention core for group `grp`.  On entry the v third of dqkv [T, 3Cg] holds
+// Adjoint of the attention core for group `grp`.  On entry the v part of dqkv [T, Rg] holds
 // dO of the group; on exit dqkv holds dq|dk|dv.  dtable (fp32) is added into.
 template <typename T>
 hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,

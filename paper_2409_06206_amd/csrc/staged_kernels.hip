@@ -220,22 +220,23 @@ static int pick_strip(int N, size_t fixed_floats, size_t per_row_floats, size_t 
 
 size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows)
 {
-    const size_t dp = g.d | 1;
+    const size_t dp = g.d | 1, ep = g.dq | 1;
     const size_t tail = (size_t)g.N * (sizeof(long) + sizeof(int));
+    const size_t fixed = (size_t)g.N * (2 * ep + dp);
     size_t bytes = 0;
-    int rs = pick_strip(g.N, 3 * g.N * dp, g.N + 1, tail, 64 * 1024, &bytes);
-    if (rs < 8 && rs < g.N) rs = pick_strip(g.N, 3 * g.N * dp, g.N + 1, tail, kLdsMax, &bytes);
+    int rs = pick_strip(g.N, fixed, g.N + 1, tail, 64 * 1024, &bytes);
+    if (rs < 8 && rs < g.N) rs = pick_strip(g.N, fixed, g.N + 1, tail, kLdsMax, &bytes);
     if (strip_rows) *strip_rows = rs;
     return bytes;
 }
 
 size_t attn_bwd_lds_bytes(const Geom &g, int *strip_rows)
 {
-    const size_t dp = g.d | 1;
+    const size_t dp = g.d | 1, ep = g.dq | 1;
     const size_t tbl = (size_t)(2 * g.M - 1) * (2 * g.M - 1);
     const size_t tail = (size_t)g.N * (sizeof(long) + sizeof(int));
-    const size_t fixed = 4 * g.N * dp + tbl;
-    const size_t per_row = 2 * dp + 2 * (g.N + 1);
+    const size_t fixed = 2 * g.N * (dp + ep) + tbl;
+    const size_t per_row = dp + ep + 2 * (g.N + 1);
     size_t bytes = 0;
     int rs = pick_strip(g.N, fixed, per_row, tail, 80 * 1024, &bytes);
     if (rs < 8 && rs < g.N) rs = pick_strip(g.N, fixed, per_row, tail, kLdsMax, &bytes);
@@ -249,13 +250,13 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(Geom g, int grp, con
                                                             T *__restrict__ attn_out, int RS)
 {
     extern __shared__ float smem[];
-    const int N = g.N, d = g.d, dp = d | 1, Cg = g.Cg, M = g.M;
+    const int N = g.N, d = g.d, dp = d | 1, dq = g.dq, ep = dq | 1, Qg = g.Qg, Rg = g.Rg, M = g.M;
     const int ldS = N + 1;
     float *q = smem;
-    float *k = q + N * dp;
-    float *v = k + N * dp;
+    float *k = q + N * ep;
+    float *v = k + N * ep;
     float *S = v + N * dp;
-    size_t fl = (size_t)3 * N * dp + (size_t)RS * ldS;
+    size_t fl = (size_t)N * (2 * ep + dp) + (size_t)RS * ldS;
     fl = (fl + 1) & ~size_t(1);
     long *tok = reinterpret_cast<long *>(smem + fl);
     int *reg = reinterpret_cast<int *>(tok + N);
@@ -269,22 +270,25 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(Geom g, int grp, con
         reg[n] = r;
     }
     __syncthreads();
+    for (int e = tid; e < N * dq; e += kThreads) {
+        const int n = e / dq, c = e - n * dq;
+        const long base = tok[n] * Rg + hl * dq + c;
+        q[n * ep + c] = to_f32(qkv[base]);
+        k[n * ep + c] = to_f32(qkv[base + Qg]);
+    }
     for (int e = tid; e < N * d; e += kThreads) {
         const int n = e / d, c = e - n * d;
-        const long base = tok[n] * 3 * Cg + hl * d + c;
-        q[n * dp + c] = to_f32(qkv[base]);
-        k[n * dp + c] = to_f32(qkv[base + Cg]);
-        v[n * dp + c] = to_f32(qkv[base + 2 * Cg]);
+        v[n * dp + c] = to_f32(qkv[tok[n] * Rg + 2 * Qg + hl * d + c]);
     }
     __syncthreads();
 
-    const float scale = 1.0f / sqrtf((float)d);
+    const float scale = 1.0f / sqrtf((float)dq);
     for (int n0 = 0; n0 < N; n0 += RS) {
         const int rows = min(RS, N - n0);
         for (int e = tid; e < rows * N; e += kThreads) {
             const int r = e / N, m = e - r * N, n = n0 + r;
             float dot = 0.f;
-            for (int c = 0; c < d; ++c) dot = fmaf(q[n * dp + c], k[m * dp + c], dot);
+            for (int c = 0; c < dq; ++c) dot = fmaf(q[n * ep + c], k[m * ep + c], dot);
             const int rn = n / M, cn = n - rn * M, rm = m / M, cm = m - rm * M;
             const int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
             float sc = dot * scale + to_f32(table[(long)idx * g.heads + hd]);
@@ -343,18 +347,18 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
                                                             float *dtable, int RS)
 {
     extern __shared__ float smem[];
-    const int N = g.N, d = g.d, dp = d | 1, Cg = g.Cg, M = g.M;
+    const int N = g.N, d = g.d, dp = d | 1, dq = g.dq, ep = dq | 1, Qg = g.Qg, Rg = g.Rg, M = g.M;
     const int ldS = N + 1, ntbl = (2 * M - 1) * (2 * M - 1);
     float *k = smem;
-    float *v = k + N * dp;
+    float *v = k + N * ep;
     float *dk = v + N * dp;
-    float *dv = dk + N * dp;
+    float *dv = dk + N * ep;
     float *tbl = dv + N * dp;
     float *q = tbl + ntbl;
-    float *dO = q + RS * dp;
+    float *dO = q + RS * ep;
     float *P = dO + RS * dp;
     float *dS = P + RS * ldS;
-    size_t fl = (size_t)4 * N * dp + ntbl + (size_t)RS * (2 * dp + 2 * ldS);
+    size_t fl = (size_t)2 * N * (dp + ep) + ntbl + (size_t)RS * (dp + ep + 2 * ldS);
     fl = (fl + 1) & ~size_t(1);
     long *tok = reinterpret_cast<long *>(smem + fl);
     int *reg = reinterpret_cast<int *>(tok + N);
@@ -369,34 +373,36 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
     }
     for (int e = tid; e < ntbl; e += kThreads) tbl[e] = 0.f;
     __syncthreads();
+    for (int e = tid; e < N * dq; e += kThreads) {
+        const int n = e / dq, c = e - n * dq;
+        k[n * ep + c] = to_f32(qkv[tok[n] * Rg + Qg + hl * dq + c]);
+        dk[n * ep + c] = 0.f;
+    }
     for (int e = tid; e < N * d; e += kThreads) {
         const int n = e / d, c = e - n * d;
-        const long base = tok[n] * 3 * Cg + hl * d + c;
-        k[n * dp + c] = to_f32(qkv[base + Cg]);
-        v[n * dp + c] = to_f32(qkv[base + 2 * Cg]);
-        dk[n * dp + c] = 0.f;
+        v[n * dp + c] = to_f32(qkv[tok[n] * Rg + 2 * Qg + hl * d + c]);
         dv[n * dp + c] = 0.f;
     }
-    const float scale = 1.0f / sqrtf((float)d);
+    const float scale = 1.0f / sqrtf((float)dq);
 
     for (int n0 = 0; n0 < N; n0 += RS) {
         const int rows = min(RS, N - n0);
         __syncthreads();
+        for (int e = tid; e < rows * dq; e += kThreads) {
+            const int r = e / dq, c = e - r * dq;
+            q[r * ep + c] = to_f32(qkv[tok[n0 + r] * Rg + hl * dq + c]);
+        }
         for (int e = tid; e < rows * d; e += kThreads) {
             const int r = e / d, c = e - r * d;
-            const long base = tok[n0 + r] * 3 * Cg + hl * d + c;
-            q[r * dp + c] = to_f32(qkv[base]);
-            dO[r * dp + c] = to_f32(dqkv[base + 2 * Cg]);
+            dO[r * dp + c] = to_f32(dqkv[tok[n0 + r] * Rg + 2 * Qg + hl * d + c]);
         }
         __syncthreads();
         // scores and dP = dO v^T
         for (int e = tid; e < rows * N; e += kThreads) {
             const int r = e / N, m = e - r * N, n = n0 + r;
             float dot = 0.f, dp_ = 0.f;
-            for (int c = 0; c < d; ++c) {
-                dot = fmaf(q[r * dp + c], k[m * dp + c], dot);
-                dp_ = fmaf(dO[r * dp + c], v[m * dp + c], dp_);
-            }
+            for (int c = 0; c < dq; ++c) dot = fmaf(q[r * ep + c], k[m * ep + c], dot);
+            for (int c = 0; c < d; ++c) dp_ = fmaf(dO[r * dp + c], v[m * dp + c], dp_);
             const int rn = n / M, cn = n - rn * M, rm = m / M, cm = m - rm * M;
             const int idx = (rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1);
             float sc = dot * scale + to_f32(table[(long)idx * g.heads + hd]);
@@ -435,30 +441,34 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
         }
         __syncthreads();
         // dq rows of this strip
-        for (int e = tid; e < rows * d; e += kThreads) {
-            const int r = e / d, c = e - r * d;
+        for (int e = tid; e < rows * dq; e += kThreads) {
+            const int r = e / dq, c = e - r * dq;
             float acc = 0.f;
-            for (int m = 0; m < N; ++m) acc = fmaf(dS[r * ldS + m], k[m * dp + c], acc);
-            from_f32(dqkv[tok[n0 + r] * 3 * Cg + hl * d + c], acc * scale);
+            for (int m = 0; m < N; ++m) acc = fmaf(dS[r * ldS + m], k[m * ep + c], acc);
+            from_f32(dqkv[tok[n0 + r] * Rg + hl * dq + c], acc * scale);
         }
         // dk, dv accumulate over strips; element (m, c) belongs to one thread
+        for (int e = tid; e < N * dq; e += kThreads) {
+            const int m = e / dq, c = e - m * dq;
+            float ak = 0.f;
+            for (int r = 0; r < rows; ++r) ak = fmaf(dS[r * ldS + m], q[r * ep + c], ak);
+            dk[m * ep + c] += ak * scale;
+        }
         for (int e = tid; e < N * d; e += kThreads) {
             const int m = e / d, c = e - m * d;
-            float ak = 0.f, av = 0.f;
-            for (int r = 0; r < rows; ++r) {
-                ak = fmaf(dS[r * ldS + m], q[r * dp + c], ak);
-                av = fmaf(P[r * ldS + m], dO[r * dp + c], av);
-            }
-            dk[m * dp + c] += ak * scale;
+            float av = 0.f;
+            for (int r = 0; r < rows; ++r) av = fmaf(P[r * ldS + m], dO[r * dp + c], av);
             dv[m * dp + c] += av;
         }
     }
     __syncthreads();
+    for (int e = tid; e < N * dq; e += kThreads) {
+        const int n = e / dq, c = e - n * dq;
+        from_f32(dqkv[tok[n] * Rg + Qg + hl * dq + c], dk[n * ep + c]);
+    }
     for (int e = tid; e < N * d; e += kThreads) {
         const int n = e / d, c = e - n * d;
-        const long base = tok[n] * 3 * Cg + hl * d + c;
-        from_f32(dqkv[base + Cg], dk[n * dp + c]);
-        from_f32(dqkv[base + 2 * Cg], dv[n * dp + c]);
+        from_f32(dqkv[tok[n] * Rg + 2 * Qg + hl * d + c], dv[n * dp + c]);
     }
     for (int e = tid; e < ntbl; e += kThreads) atomicAdd(&dtable[(long)e * g.heads + hd], tbl[e]);
 }

@@ -29,7 +29,7 @@ class gswa_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
                 ("C", ctypes.c_int32), ("heads", ctypes.c_int32), ("groups", ctypes.c_int32),
                 ("window", ctypes.c_int32), ("shift", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("flags", ctypes.c_uint32)]
+                ("flags", ctypes.c_uint32), ("dqk", ctypes.c_int32)]
 
 
 _lib = None
@@ -72,9 +72,9 @@ def lib():
     return _lib
 
 
-def make_desc(B, H, W, C, heads, groups, window, shift, dtype, flags=0):
+def make_desc(B, H, W, C, heads, groups, window, shift, dtype, flags=0, dqk=0):
     code = {"f32": GSWA_F32, "bf16": GSWA_BF16}.get(dtype, dtype)
-    return gswa_desc(B, H, W, C, heads, groups, window, shift, code, flags)
+    return gswa_desc(B, H, W, C, heads, groups, window, shift, code, flags, dqk)
 
 
 def _ptr(t):

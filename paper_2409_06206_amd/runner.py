@@ -24,8 +24,9 @@ def to_host(t):
 class DeviceLayer:
     """Buffers of one GSWA layer call on the GPU (inputs, outputs, saved state, scratch)."""
 
-    def __init__(self, B, H, W, C, heads, groups, window, shift, dtype, flags=0, device="cuda:0"):
-        self.desc = gswa.make_desc(B, H, W, C, heads, groups, window, shift, dtype, flags)
+    def __init__(self, B, H, W, C, heads, groups, window, shift, dtype, flags=0, device="cuda:0",
+                 dqk=0):
+        self.desc = gswa.make_desc(B, H, W, C, heads, groups, window, shift, dtype, flags, dqk)
         self.dtype, self.device = dtype, device
         self.shape = (B, H, W, C)
         tdt = torch.float32 if dtype == "f32" else torch.bfloat16
@@ -35,7 +36,7 @@ class DeviceLayer:
         self.saved = torch.empty(self.saved_bytes, dtype=torch.uint8, device=device)
         ws_bytes = max(self.fwd_ws_bytes + self.saved_bytes, self.bwd_ws_bytes)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
-        shp = synth.param_shapes(C, heads, groups, window)
+        shp = synth.param_shapes(C, heads, groups, window, dqk)
         self.grads = {k: torch.empty(shp[k], dtype=torch.float32, device=device) for k in _PARAMS}
         self.params = None
         self.x = self.dy = None

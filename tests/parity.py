@@ -22,16 +22,16 @@ def rel_err(got, want):
     return num / denom
 
 
-def make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime):
-    p = synth.layer_params(C, heads, groups, window, seed, regime)
+def make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime, dqk=0):
+    p = synth.layer_params(C, heads, groups, window, seed, regime, dqk)
     x, dy = synth.activations(B, H, W, C, synth.ACT_SEED + seed - synth.LAYER_SEED0)
     p = {k: synth.quantize(v, dtype) for k, v in p.items()}
     return synth.quantize(x, dtype), synth.quantize(dy, dtype), p
 
 
-def oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade=True, backward=True):
+def oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade=True, backward=True, dqk=0):
     args = (p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"])
-    kw = dict(heads=heads, groups=groups, window=window, shift=shift, cascade=cascade)
+    kw = dict(heads=heads, groups=groups, window=window, shift=shift, cascade=cascade, dqk=dqk)
     out = {"y": oracle.forward(x, *args, **kw)}
     if backward:
         out.update(zip(GRAD_NAMES, oracle.backward(x, dy, *args, **kw)))
@@ -39,11 +39,11 @@ def oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade=True,
 
 
 def gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade=True, backward=True,
-                extra_flags=0):
+                extra_flags=0, dqk=0):
     from paper_2409_06206_amd import gswa, runner
     B, H, W, C = x.shape
     flags = (0 if cascade else gswa.GSWA_NO_CASCADE) | extra_flags
-    layer = runner.DeviceLayer(B, H, W, C, heads, groups, window, shift, dtype, flags)
+    layer = runner.DeviceLayer(B, H, W, C, heads, groups, window, shift, dtype, flags, dqk=dqk)
     layer.set_params(p)
     layer.set_inputs(x, dy)
     layer.forward(keep=backward)
@@ -58,11 +58,11 @@ def gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade=True, bac
 
 
 def check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, seed=synth.LAYER_SEED0,
-               regime="init", cascade=True, backward=True, tol_scale=1.0, extra_flags=0):
-    x, dy, p = make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime)
-    want = oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade, backward)
+               regime="init", cascade=True, backward=True, tol_scale=1.0, extra_flags=0, dqk=0):
+    x, dy, p = make_inputs(B, H, W, C, heads, groups, window, dtype, seed, regime, dqk)
+    want = oracle_results(oracle, x, dy, p, heads, groups, window, shift, cascade, backward, dqk)
     got, layer = gpu_results(x, dy, p, heads, groups, window, shift, dtype, cascade, backward,
-                             extra_flags)
+                             extra_flags, dqk)
     errs = {k: rel_err(got[k], want[k]) for k in want}
     bad = {k: e for k, e in errs.items() if not e <= TOL[dtype] * tol_scale}
     assert not bad, f"relative max-norm error above {TOL[dtype] * tol_scale}: {bad} (all: {errs})"

@@ -36,7 +36,7 @@ GOOD = dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="
 
 @pytest.mark.parametrize("change", [
     dict(B=0), dict(H=12), dict(W=20), dict(C=62), dict(heads=4, groups=3), dict(groups=4),
-    dict(shift=8), dict(shift=-1), dict(window=0), dict(dtype=7), dict(flags=64),
+    dict(shift=8), dict(shift=-1), dict(window=0), dict(dtype=7), dict(flags=64), dict(dqk=-1),
 ])
 def test_invalid_descriptors_are_rejected(change):
     desc = gswa.make_desc(**{**GOOD, **change})
@@ -77,6 +77,20 @@ def test_saved_state_is_one_activation_and_scratch_shrinks_with_groups(dtype, e)
         if prev is not None:
             assert saved + bwd < prev
         prev = saved + bwd
+
+
+def test_narrow_query_key_sizes_the_group_scratch():
+    """Sec. "Parameter Allocation": a group's q|k|v row has 2*hg*dqk + Cg features; 12 x 12 windows."""
+    T, C, heads = 2 * 24 * 24, 60, 6
+    for G, dqk in ((1, 4), (2, 4), (3, 8), (2, 16)):
+        desc = gswa.make_desc(B=2, H=24, W=24, C=C, heads=heads, groups=G, window=12, shift=6,
+                              dtype="bf16", dqk=dqk)
+        saved, fwd, bwd = gswa.gswa_query_bytes(desc)
+        row = 2 * (heads // G) * dqk + C // G
+        assert saved == T * C * 2
+        assert fwd == T * row * 2 and bwd == 2 * fwd
+    same = [gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "dqk": q})) for q in (0, 10)]
+    assert same[0][0] >= same[1][0]  # dqk = C/heads spelled out is the plain layer
 
 
 def test_fused_path_sizes():

@@ -231,6 +231,36 @@ def _random_shapes(n, seed):
     return out
 
 
+AGILE_SMALL = [
+    # B, H, W, C, heads, groups, window, shift, dqk, dtype, regime   (Sec. "Parameter Allocation")
+    (2, 24, 24, 60, 4, 2, 12, 6, 4, "f32", "stress"),
+    (1, 24, 36, 60, 4, 2, 12, 0, 8, "f32", "init"),
+    (2, 24, 24, 60, 6, 2, 12, 6, 4, "bf16", "stress"),
+    (1, 36, 24, 60, 6, 3, 12, 5, 16, "bf16", "stress"),
+    (3, 16, 24, 60, 6, 2, 8, 4, 4, "bf16", "stress"),     # narrow q/k on 8 x 8 windows
+    (2, 16, 16, 60, 6, 1, 8, 4, 16, "bf16", "init"),      # q/k wider than v
+    (1, 24, 24, 180, 6, 2, 12, 6, 8, "bf16", "stress"),
+    (1, 16, 16, 12, 6, 6, 4, 1, 1, "f32", "stress"),
+]
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,groups,window,shift,dqk,dtype,regime", AGILE_SMALL)
+def test_narrow_query_key_and_window_12(oracle, B, H, W, C, heads, groups, window, shift, dqk, dtype, regime):
+    """q and k of dqk channels per head, 12 x 12 windows: forward and every gradient."""
+    parity.check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, regime=regime, dqk=dqk)
+    parity.check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, regime=regime, dqk=dqk,
+               cascade=False, seed=synth.LAYER_SEED0 + 3)
+
+
+def test_spelled_out_query_key_width_takes_the_same_path(oracle):
+    """dqk = C / heads is the plain layer: same kernels, same bits."""
+    x, dy, p = parity.make_inputs(2, 16, 16, 60, 6, 2, 8, "bf16", synth.LAYER_SEED0, "stress")
+    a, _ = parity.gpu_results(x, dy, p, 6, 2, 8, 4, "bf16")
+    b, _ = parity.gpu_results(x, dy, p, 6, 2, 8, 4, "bf16", dqk=10)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
 @pytest.mark.parametrize("shape", _random_shapes(16, 2024))
 def test_random_shapes_fp32(oracle, shape):
     B, H, W, C, heads, groups, M, s = shape
