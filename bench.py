@@ -6,7 +6,7 @@ shape: two consecutive GSWA layers (shift 0, then shift 4), forward and backward
 storage with fp32 accumulation, B=32, 64x64 map, C=60, 6 heads, window 8.  Inputs are
 resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--groups G] [--workload c2|c3]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--groups G] [--workload c2|c3|c4|c5_m8|c5_m16|agile_h4_qk16|agile_h4_qk32|agile_h6_qk24]
 """
 import argparse
 import json
@@ -48,9 +48,9 @@ def build_case(name, groups):
     layers = []
     for li, shift in enumerate(cfg["layers"]):
         L = runner.DeviceLayer(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
-                               cfg["window"], shift, cfg["dtype"])
+                               cfg["window"], shift, cfg["dtype"], dqk=cfg.get("dqk", 0))
         L.set_params(synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"],
-                                        synth.LAYER_SEED0 + li))
+                                        synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)))
         layers.append(L)
     layers[0].set_inputs(x)
     layers[-1].dy = runner.to_device(dy, cfg["dtype"])
@@ -130,8 +130,10 @@ def synth_groups(name):
 
 
 def model_flops_per_token(cfg, groups, backward=True):
-    C, N = cfg["C"], cfg["window"] ** 2
-    return (3 if backward else 1) * (6 * C * C / groups + 2 * C * C + 4 * N * C)
+    C, N, heads = cfg["C"], cfg["window"] ** 2, cfg["heads"]
+    qk = heads * (cfg.get("dqk", 0) or C // heads)       # channels of q (and of k) over all heads
+    fwd = 2 * (C / groups) * (2 * qk + C) + 2 * N * (qk + C) + 2 * C * C
+    return (3 if backward else 1) * fwd
 
 
 def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
@@ -142,10 +144,12 @@ def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
     x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
     x = synth.quantize(x, cfg["dtype"])
     dy = synth.quantize(dy, cfg["dtype"])
-    kw = dict(heads=cfg["heads"], groups=groups, window=cfg["window"])
+    dqk = cfg.get("dqk", 0)
+    kw = dict(heads=cfg["heads"], groups=groups, window=cfg["window"], dqk=dqk)
     params = []
     for li in range(len(cfg["layers"])):
-        p = synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"], synth.LAYER_SEED0 + li)
+        p = synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"], synth.LAYER_SEED0 + li,
+                               dqk=dqk)
         p = {k: synth.quantize(v, cfg["dtype"]) for k, v in p.items()}
         params.append((p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"]))
     reps, t0 = 0, time.perf_counter()
@@ -170,7 +174,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--groups", type=int, default=2)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -233,7 +237,8 @@ def main():
         "config": {"workload": f"{args.workload}: {len(layers)} GSWA layer(s), shifts {list(cfg['layers'])[:4]}"
                                f"{'...' if len(layers) > 4 else ''}, {'fwd+bwd' if backward else 'forward only'}, "
                                f"B={cfg['B']} {cfg['H']}x{cfg['W']} C={cfg['C']} heads={cfg['heads']} "
-                               f"window={cfg['window']} groups={args.groups}",
+                               f"window={cfg['window']} groups={args.groups}"
+                               f"{' q/k channels per head=%d' % cfg['dqk'] if cfg.get('dqk') else ''}",
                    "groups": args.groups, "tokens_per_step": tokens_per_step},
         "roofline": roofline,
         "whole_step": {"algorithmic_GBps": step_bytes / sec / 1e9, "hbm_frac": step_bytes / sec / 1e9 / HBM_PEAK_GBS,
@@ -251,7 +256,7 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline and args.workload == "c2":
+    if not args.no_cpu_baseline and (args.workload == "c2" or args.workload.startswith("agile")):
         out["cpu_baseline"] = cpu_baseline(args.workload, args.groups)
     print(json.dumps(out))
 

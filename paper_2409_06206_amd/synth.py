@@ -102,14 +102,15 @@ CONFIGS = {
                    dtype="bf16"),
 }
 # Narrow q/k and 12x12 windows (Sec. "Parameter Allocation", Sec. "Experimental Settings"): C = 60,
-# q and k of 16 resp. 32 channels in total over 4 heads (dqk = 4, 8), and 6 heads with dqk = 4.
-AGILE = {
-    "agile_h4_qk16": dict(B=32, H=48, W=48, C=60, heads=4, groups=2, window=12, dqk=4, layers=(0, 6),
-                          dtype="bf16"),
-    "agile_h4_qk32": dict(B=32, H=48, W=48, C=60, heads=4, groups=2, window=12, dqk=8, layers=(0, 6),
-                          dtype="bf16"),
-    "agile_h6_qk24": dict(B=32, H=48, W=48, C=60, heads=6, groups=2, window=12, dqk=4, layers=(0, 6),
-                          dtype="bf16"),
-}
+# q and k of 16 resp. 32 channels in total over 4 heads (dqk = 4, 8), and 6 heads with dqk = 4,
+# on 48x48 patches (the 64x64 patches of the plain cases are not a multiple of 12).
+CONFIGS.update({
+    "agile_h4_qk16": dict(B=32, H=48, W=48, C=60, heads=4, groups=(1, 2, 4), window=12, dqk=4,
+                          layers=(0, 6), dtype="bf16"),
+    "agile_h4_qk32": dict(B=32, H=48, W=48, C=60, heads=4, groups=(1, 2, 4), window=12, dqk=8,
+                          layers=(0, 6), dtype="bf16"),
+    "agile_h6_qk24": dict(B=32, H=48, W=48, C=60, heads=6, groups=(1, 2, 3, 6), window=12, dqk=4,
+                          layers=(0, 6), dtype="bf16"),
+})
 ACT_SEED = 0
 LAYER_SEED0 = 100

@@ -183,6 +183,7 @@ FULL = [
     ("c2", 1, 0), ("c2", 2, 1), ("c2", 3, 0), ("c2", 6, 1),
     ("c3", 1, 1), ("c3", 2, 0), ("c3", 3, 1),
     ("c4", 2, 1),
+    ("agile_h4_qk16", 2, 1), ("agile_h4_qk32", 4, 0), ("agile_h6_qk24", 2, 1), ("agile_h6_qk24", 3, 0),
 ]
 
 
@@ -192,7 +193,7 @@ def test_full_size_layers(oracle, name, groups, layer):
     _say("full", name, "G", groups, "layer", layer)
     errs, _ = parity.check_case(oracle, cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
                                 cfg["window"], cfg["layers"][layer], cfg["dtype"],
-                                seed=synth.LAYER_SEED0 + layer)
+                                seed=synth.LAYER_SEED0 + layer, dqk=cfg.get("dqk", 0))
     _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
 
 
