@@ -6,6 +6,7 @@
 #include "fused.h"
 
 #include <string>
+#include <type_traits>
 
 namespace {
 
@@ -128,6 +129,12 @@ int forward_staged(const Geom &g, const Sizes &sz, const T *x, const T *w_qkv, c
         la.out = qkv; la.ldout = Rg;
         la.rows = g.T; la.N = Rg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
         GSWA_HIP(launch_linear<T>(la, st));
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            if (attn_core_mfma_supported(g)) {
+                GSWA_HIP(launch_attn_core_fwd(g, grp, qkv, table, attn, st));
+                continue;
+            }
+        }
         GSWA_HIP(launch_attn_fwd<T>(g, grp, qkv, table, attn, st));
     }
     LinearArgs lp{};
@@ -184,7 +191,14 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         lo.out = dqkv + 2 * g.Qg; lo.ldout = Rg;
         lo.rows = g.T; lo.N = Cg; lo.K = C; lo.prof_id = K_DO_LINEAR;
         GSWA_HIP(launch_linear<T>(lo, st));
-        GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, dtable, st));
+        bool on_matrix_cores = false;
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            if (attn_core_mfma_supported(g)) {
+                GSWA_HIP(launch_attn_core_bwd(g, grp, qkv, dqkv, table, dtable, st));
+                on_matrix_cores = true;
+            }
+        }
+        if (!on_matrix_cores) GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, dtable, st));
         // dF_g = dqkv Wqkv_g  ->  dx[:, slice g]
         LinearArgs lx{};
         lx.a1 = dqkv; lx.lda1 = Rg;

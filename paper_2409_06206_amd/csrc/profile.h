@@ -23,6 +23,8 @@ enum KernelId {
     K_ATTN_CHUNK_FWD, // split forward: attention of one head chunk
     K_PROJ_GEMM,    // split forward: output projection (Eq. 7)
     K_WPROJ_GRAD,   // split backward: d w_proj, d b_proj
+    K_ATTN_CORE_FWD, // attention core of one group on the matrix cores
+    K_ATTN_CORE_BWD, // its adjoint
     K_COUNT
 };
 

@@ -45,6 +45,14 @@ template <typename T>
 hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
                            float *dtable, hipStream_t s);
 
+// The same two steps on the matrix cores, for bf16 layers whose windows are 64 or 144 tokens and
+// whose heads are at most 32 channels wide (attn_core_mfma_supported); same buffers, same contract.
+bool attn_core_mfma_supported(const Geom &g);
+hipError_t launch_attn_core_fwd(const Geom &g, int grp, const bf16_t *qkv, const bf16_t *table,
+                                bf16_t *attn_out, hipStream_t s);
+hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
+                                float *dtable, hipStream_t s);
+
 // LDS bytes the two attention kernels need for this geometry, or 0 if no strip height fits.
 size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows);
 size_t attn_bwd_lds_bytes(const Geom &g, int *strip_rows);
