@@ -10,7 +10,9 @@
 // they are the B operand of the products that reduce over keys (O^T = V^T P^T, dQ^T = K^T dS^T).
 // The products of the backward that reduce over queries (dV, dK) need the other orientation, so
 // every wave also recomputes S for its own 16 KEYS against all queries, from the row statistics
-// (log-sum-exp, delta = sum_m P dP) the query role left in LDS.
+// (log-sum-exp, delta = sum_m P dP) the query role left in LDS.  LDS float atomics are slow here
+// (a wave's ds_add_f32 takes ~170 clocks), so the bias-table gradient is folded from a bf16 copy
+// of dS in LDS instead.
 #include "staged_kernels.h"
 #include "mfma.h"
 
@@ -38,10 +40,15 @@ template <class Cf> size_t fwd_lds_bytes(int M)
 {
     return (size_t)4 * table_floats(M) + 8 * Cf::N + 2 * ((size_t)Cf::N * Cf::LK + 16 * Cf::ET * Cf::LT);
 }
+template <class Cf> constexpr size_t bwd_operand_bytes()
+{
+    return 2 * ((size_t)2 * Cf::N * Cf::LK + 2 * 16 * Cf::KQ * Cf::LT + 2 * Cf::N * Cf::LV + 16 * Cf::ET * Cf::LT);
+}
 template <class Cf> size_t bwd_lds_bytes(int M)
 {
-    return (size_t)8 * table_floats(M) + 16 * Cf::N +
-           2 * ((size_t)2 * Cf::N * Cf::LK + 2 * 16 * Cf::KQ * Cf::LT + 2 * Cf::N * Cf::LV + 16 * Cf::ET * Cf::LT);
+    // the operand arrays are reused at the end for the N x N matrix of dS (bf16, pitch LT)
+    const size_t ops = bwd_operand_bytes<Cf>(), ds = (size_t)2 * Cf::N * Cf::LT;
+    return (size_t)4 * table_floats(M) + 16 * Cf::N + (ops > ds ? ops : ds);
 }
 
 __device__ __forceinline__ uint2 lds_frag(const uint16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
@@ -89,13 +96,30 @@ __global__ __launch_bounds__(64 * NT) void attn_core_fwd_kernel(Geom g, int grp,
 
     stage_geometry<N, NTH>(g, w, hd, table, tb, koff, tok, tid);
     __syncthreads();
-    for (int e = tid; e < N * 16 * KQ; e += NTH) {
-        const int n = e / (16 * KQ), c = e - n * (16 * KQ);
-        Ks[n * LK + c] = c < dq ? qkv16[(long)tok[n] * Rg + Qg + hl * dq + c] : (uint16_t)0;
-    }
-    for (int e = tid; e < N * 16 * ET; e += NTH) {
-        const int n = e / (16 * ET), c = e - n * (16 * ET);
-        VT[c * LT + n] = c < d ? qkv16[(long)tok[n] * Rg + 2 * Qg + hl * d + c] : (uint16_t)0;
+    // k rows and v of the window (zero beyond the head's channels); a thread's loads are all
+    // issued before its first LDS store (N*16 elements per channel tile = 4 per thread)
+    {
+        uint16_t vk[4 * KQ], vv[4 * ET];
+#pragma unroll
+        for (int i = 0; i < 4 * KQ; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * KQ), c = e - n * (16 * KQ);
+            vk[i] = c < dq ? qkv16[(long)tok[n] * Rg + Qg + hl * dq + c] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * ET; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * ET), c = e - n * (16 * ET);
+            vv[i] = c < d ? qkv16[(long)tok[n] * Rg + 2 * Qg + hl * d + c] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * KQ; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * KQ), c = e - n * (16 * KQ);
+            Ks[n * LK + c] = vk[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * ET; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * ET), c = e - n * (16 * ET);
+            VT[c * LT + n] = vv[i];
+        }
     }
     // this lane's query as a B operand: column l16 = query, k-slots = channels 16ks + 4q + j
     const int nq = 16 * wv + l16;
@@ -179,10 +203,9 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
     using Cf = CoreCfg<NT, ET, KQ>;
     constexpr int N = Cf::N, NTH = Cf::NTHREADS, LK = Cf::LK, LV = Cf::LV, LT = Cf::LT;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int M = g.M, nt1 = 2 * M - 1, ntbl = nt1 * nt1, tf = table_floats(M);
+    const int M = g.M, nt1 = 2 * M - 1, tf = table_floats(M);
     float *tb = reinterpret_cast<float *>(lds);
-    float *tg = tb + tf;                                   // bias-table gradient of this workgroup
-    int *koff = reinterpret_cast<int *>(tg + tf);
+    int *koff = reinterpret_cast<int *>(tb + tf);
     int *tok = koff + N;
     float *lse = reinterpret_cast<float *>(tok + N);       // base-2 log-sum-exp of every query row
     float *dlt = lse + N;                                  // sum_m P dP of every query row
@@ -202,26 +225,40 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
     uint16_t *dqkv16 = reinterpret_cast<uint16_t *>(dqkv);
 
     stage_geometry<N, NTH>(g, w, hd, table, tb, koff, tok, tid);
-    for (int e = tid; e < ntbl; e += NTH) tg[e] = 0.f;
     __syncthreads();
-    for (int e = tid; e < N * 16 * KQ; e += NTH) {
-        const int n = e / (16 * KQ), c = e - n * (16 * KQ);
-        const long base = (long)tok[n] * Rg + hl * dq + c;
-        const uint16_t vq = c < dq ? qkv16[base] : (uint16_t)0;
-        const uint16_t vk = c < dq ? qkv16[base + Qg] : (uint16_t)0;
-        Qs[n * LK + c] = vq;
-        QT[c * LT + n] = vq;
-        Ks[n * LK + c] = vk;
-        KT[c * LT + n] = vk;
-    }
-    for (int e = tid; e < N * 16 * ET; e += NTH) {
-        const int n = e / (16 * ET), c = e - n * (16 * ET);
-        const long base = (long)tok[n] * Rg + 2 * Qg + hl * d + c;
-        const uint16_t vv = c < d ? qkv16[base] : (uint16_t)0;
-        const uint16_t vo = c < d ? dqkv16[base] : (uint16_t)0;
-        Vs[n * LV + c] = vv;
-        Os[n * LV + c] = vo;
-        OT[c * LT + n] = vo;
+    // q, k, v, dO of the window, token-major and channel-major (zero beyond the head's channels);
+    // a thread's loads are all issued before its first LDS store
+    {
+        uint16_t vq[4 * KQ], vk[4 * KQ], vv[4 * ET], vo[4 * ET];
+#pragma unroll
+        for (int i = 0; i < 4 * KQ; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * KQ), c = e - n * (16 * KQ);
+            const long base = (long)tok[n] * Rg + hl * dq + c;
+            vq[i] = c < dq ? qkv16[base] : (uint16_t)0;
+            vk[i] = c < dq ? qkv16[base + Qg] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * ET; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * ET), c = e - n * (16 * ET);
+            const long base = (long)tok[n] * Rg + 2 * Qg + hl * d + c;
+            vv[i] = c < d ? qkv16[base] : (uint16_t)0;
+            vo[i] = c < d ? dqkv16[base] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * KQ; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * KQ), c = e - n * (16 * KQ);
+            Qs[n * LK + c] = vq[i];
+            QT[c * LT + n] = vq[i];
+            Ks[n * LK + c] = vk[i];
+            KT[c * LT + n] = vk[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * ET; ++i) {
+            const int e = tid + i * NTH, n = e / (16 * ET), c = e - n * (16 * ET);
+            Vs[n * LV + c] = vv[i];
+            Os[n * LV + c] = vo[i];
+            OT[c * LT + n] = vo[i];
+        }
     }
     __syncthreads();
 
@@ -232,7 +269,9 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
     const float scale = 1.0f / sqrtf((float)dq);
     const float sc2 = scale * kLog2e, maskv = -100.0f * kLog2e;
 
-    // ---- query role: statistics of the wave's 16 queries, dQ, bias-table gradient ----
+    uint2 dsb[NT]; // dS^T of the wave's queries (bf16), kept for the bias-table gradient at the end
+
+    // ---- query role: statistics of the wave's 16 queries, dQ ----
     {
         uint2 qf[KQ], of[ET];
 #pragma unroll
@@ -241,7 +280,6 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
         for (int es = 0; es < ET; ++es) of[es] = lds_frag(&Os[own * LV + 16 * es + 4 * q]);
         const int qo = off_own + cst;
         f32x4 st[NT], dpt[NT];
-        int tix[NT][4];
         float mx = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < NT; ++kt) {
@@ -254,8 +292,7 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
             const int kk[4] = {ko.x, ko.y, ko.z, ko.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tix[kt][j] = qo - (kk[j] & 0xffff);
-                float s = fmaf(a[j], sc2, tb[tix[kt][j]]);
+                float s = fmaf(a[j], sc2, tb[qo - (kk[j] & 0xffff)]);
                 s += (kk[j] >> 16) != reg_own ? maskv : 0.f;
                 a[j] = s;
                 mx = fmaxf(mx, s);
@@ -295,14 +332,11 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
         for (int kt = 0; kt < NT; ++kt) {
             f32x4 ds;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                ds[j] = st[kt][j] * (dpt[kt][j] - dl);
-                atomicAdd(&tg[tix[kt][j]], ds[j]);
-            }
-            const uint2 dsb = pack_bf16x4(ds);
+            for (int j = 0; j < 4; ++j) ds[j] = st[kt][j] * (dpt[kt][j] - dl);
+            dsb[kt] = pack_bf16x4(ds);
 #pragma unroll
             for (int ks = 0; ks < KQ; ++ks)
-                dqt[ks] = mma16(lds_frag(&KT[(16 * ks + l16) * LT + 16 * kt + 4 * q]), dsb, dqt[ks]);
+                dqt[ks] = mma16(lds_frag(&KT[(16 * ks + l16) * LT + 16 * kt + 4 * q]), dsb[kt], dqt[ks]);
         }
         uint16_t *o16 = dqkv16 + (long)tok[own] * Rg + hl * dq;
 #pragma unroll
@@ -347,13 +381,13 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
                 p[j] = __builtin_amdgcn_exp2f(s - lsv[j]);
                 ds[j] = p[j] * (b[j] - dlv[j]);
             }
-            const uint2 pb = pack_bf16x4(p), dsb = pack_bf16x4(ds);
+            const uint2 pb = pack_bf16x4(p), dsk = pack_bf16x4(ds);
 #pragma unroll
             for (int es = 0; es < ET; ++es)
                 dvt[es] = mma16(lds_frag(&OT[(16 * es + l16) * LT + 16 * nt + 4 * q]), pb, dvt[es]);
 #pragma unroll
             for (int ks = 0; ks < KQ; ++ks)
-                dkt[ks] = mma16(lds_frag(&QT[(16 * ks + l16) * LT + 16 * nt + 4 * q]), dsb, dkt[ks]);
+                dkt[ks] = mma16(lds_frag(&QT[(16 * ks + l16) * LT + 16 * nt + 4 * q]), dsk, dkt[ks]);
         }
         uint16_t *o16 = dqkv16 + (long)tok[own] * Rg;
 #pragma unroll
@@ -371,8 +405,47 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
                 if (c < d) o16[2 * Qg + hl * d + c] = f32_to_bf16_bits(dvt[es][j]);
             }
     }
-    // the table gradient of the workgroup (complete since the barrier above) joins the others
-    for (int e = tid; e < ntbl; e += NTH) atomicAdd(&dtable[(long)e * g.heads + hd], tg[e]);
+    // ---- bias-table gradient: dS of the whole window goes to LDS as an N x N matrix (over the
+    // operand arrays, which nobody reads any more) and is summed per coordinate offset
+    // (dr, dc) = query - key ----
+    __syncthreads();
+    uint16_t *DS = Qs; // [N][LT]: row = query, column = key
+#pragma unroll
+    for (int kt = 0; kt < NT; ++kt) *reinterpret_cast<uint2 *>(&DS[own * LT + 16 * kt + 4 * q]) = dsb[kt];
+    __syncthreads();
+    // Four threads share the offsets (dr0, dc0), (dr0 - M, dc0), (dr0, dc0 - M), (dr0 - M, dc0 - M),
+    // 0 <= dr0, dc0 < M: for every query (rn, cn) exactly one of them has its key inside the window,
+    // key = ((rn - dr0) mod M, (cn - dc0) mod M), so the four entries together take M*M terms, and
+    // each thread sums a quarter of the query rows (the workgroup has 4 * M*M threads).
+    {
+        const int grp4 = tid >> 2, part = tid & 3;
+        const int dr0 = grp4 / M, dc0 = grp4 - dr0 * M;
+        float a00 = 0.f, a01 = 0.f, a10 = 0.f, a11 = 0.f; // [row wrapped][column wrapped]
+        for (int rn = part * (M / 4); rn < (part + 1) * (M / 4); ++rn) {
+            const bool wr = rn < dr0;
+            const int rm = rn - dr0 + (wr ? M : 0);
+            const uint16_t *row = &DS[(rn * M) * LT + rm * M];
+            float s0 = 0.f, s1 = 0.f;
+            for (int cn = 0; cn < M; ++cn) {
+                const bool wc = cn < dc0;
+                const float v = __uint_as_float((uint32_t)row[cn * LT + cn - dc0 + (wc ? M : 0)] << 16);
+                s0 += wc ? 0.f : v;
+                s1 += wc ? v : 0.f;
+            }
+            a00 += wr ? 0.f : s0;
+            a01 += wr ? 0.f : s1;
+            a10 += wr ? s0 : 0.f;
+            a11 += wr ? s1 : 0.f;
+        }
+        a00 += __shfl_xor(a00, 1); a01 += __shfl_xor(a01, 1); a10 += __shfl_xor(a10, 1); a11 += __shfl_xor(a11, 1);
+        a00 += __shfl_xor(a00, 2); a01 += __shfl_xor(a01, 2); a10 += __shfl_xor(a10, 2); a11 += __shfl_xor(a11, 2);
+        // thread `part` of the four adds entry `part`
+        const int e00 = (dr0 + M - 1) * nt1 + dc0 + M - 1;
+        const float val = part == 0 ? a00 : part == 1 ? a01 : part == 2 ? a10 : a11;
+        const int e = e00 - ((part & 1) ? M : 0) - ((part & 2) ? M * nt1 : 0);
+        const bool ok = !((part & 1) && dc0 == 0) && !((part & 2) && dr0 == 0);
+        if (ok) atomicAdd(&dtable[(long)e * g.heads + hd], val);
+    }
 }
 
 template <int NT, int ET, int KQ>

@@ -157,11 +157,14 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     T *dqkv = reinterpret_cast<T *>(ws + sz.qkv);
     const int C = g.C, Cg = g.Cg, G = g.groups, Rg = g.Rg;
     if (!(flags & GSWA_ACCUM_WGRAD)) {
-        GSWA_HIP(launch_fill_zero(dw_qkv, (size_t)G * Rg * Cg, st));
-        GSWA_HIP(launch_fill_zero(db_qkv, (size_t)G * Rg, st));
-        GSWA_HIP(launch_fill_zero(dw_proj, (size_t)C * C, st));
-        GSWA_HIP(launch_fill_zero(db_proj, (size_t)C, st));
-        GSWA_HIP(launch_fill_zero(dtable, (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads, st));
+        ZeroList z{};
+        z.p[0] = dw_qkv; z.n[0] = (size_t)G * Rg * Cg;
+        z.p[1] = db_qkv; z.n[1] = (size_t)G * Rg;
+        z.p[2] = dw_proj; z.n[2] = (size_t)C * C;
+        z.p[3] = db_proj; z.n[3] = (size_t)C;
+        z.p[4] = dtable; z.n[4] = (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
+        z.count = 5;
+        GSWA_HIP(launch_fill_zero(z, st));
     }
     // adjoint of Eq. 7 with respect to the projection parameters
     WgradArgs wp{};

@@ -57,6 +57,12 @@ hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_
 size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows);
 size_t attn_bwd_lds_bytes(const Geom &g, int *strip_rows);
 
-hipError_t launch_fill_zero(float *p, size_t n, hipStream_t s);
+// Zero fill of up to eight fp32 arrays in one launch.
+struct ZeroList {
+    float *p[8];
+    size_t n[8];
+    int count;
+};
+hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s);
 
 } // namespace gswa

@@ -3,6 +3,7 @@
 // write token-major buffers in the tokens' own (unshifted) order; the cyclic shift and the
 // window partition exist only as the index map window_token().
 #include "staged_kernels.h"
+#include "mfma.h"
 
 namespace gswa {
 
@@ -84,9 +85,124 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinearArgs p)
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same linear map on the matrix cores (bf16, even K and row strides, K <= 192): the weights
+// become B-operand fragments in LDS once per workgroup, every wave then walks over 16-row tiles:
+// the rows are its A operand (k-slots = 8 consecutive input channels, read as dwords), one
+// 16x16x32 MFMA per (output tile, K step).
+// ---------------------------------------------------------------------------------------
+template <int KS>
+__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs p, int NT)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
+    uint4 *wl = reinterpret_cast<uint4 *>(lsm); // [NT][KS][64 lanes]
+    const uint16_t *w = static_cast<const uint16_t *>(p.w);
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
+    for (int i = tid; i < NT * KS * 64; i += kThreads) {
+        const int f = i >> 6, ln = i & 63;
+        const int nt = f / KS, ks = f - nt * KS;
+        const int n = 16 * nt + (ln & 15), k0 = 32 * ks + 8 * (ln >> 4);
+        uint32_t v[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8)
+            v[s8] = (n < p.N && k0 + s8 < p.K) ? (uint32_t)w[(long)n * p.w_sn + (long)(k0 + s8) * p.w_sk] : 0u;
+        wl[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+    }
+    __syncthreads();
+
+    const uint32_t *a1 = static_cast<const uint32_t *>(p.a1);
+    const uint32_t *a2 = static_cast<const uint32_t *>(p.a2);
+    const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
+    const uint16_t *add = static_cast<const uint16_t *>(p.add);
+    uint16_t *out = static_cast<uint16_t *>(p.out);
+    const long ntile = (p.rows + 15) / 16;
+    for (long tile = (long)blockIdx.x * (kThreads / 64) + wave; tile < ntile; tile += (long)gridDim.x * (kThreads / 64)) {
+        const long row = 16 * tile + l16;
+        uint4 af[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint32_t v[4];
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int k = 32 * ks + 8 * q + 2 * dw;
+                uint32_t u = 0u;
+                if (row < p.rows && k < p.K) {
+                    u = a1[(row * p.lda1 + k) >> 1];
+                    if (a2) {
+                        const uint32_t u2 = a2[(row * p.lda2 + k) >> 1];
+                        u = pack_bf16x2(bf16_lo(u) + bf16_lo(u2), bf16_hi(u) + bf16_hi(u2));
+                    }
+                }
+                v[dw] = u;
+            }
+            af[ks] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+        for (int nt = 0; nt < NT; ++nt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = mma32(af[ks], wl[(nt * KS + ks) * 64 + lane], acc);
+            // result: column l16 = output feature, rows 4q + j = rows of the tile
+            const int n = 16 * nt + l16;
+            if (n >= p.N) continue;
+            const float b = bias ? __uint_as_float((uint32_t)bias[n] << 16) : 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const long r = 16 * tile + 4 * q + j;
+                if (r >= p.rows) continue;
+                float v = acc[j] + b;
+                if (add) v += __uint_as_float((uint32_t)add[r * p.ldadd + n] << 16);
+                out[r * p.ldout + n] = f32_to_bf16_bits(v);
+            }
+        }
+    }
+}
+
+static int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+    }
+    return cus;
+}
+
+// true when the matrix-core kernel can serve the call (the dword reads need even offsets)
+static bool linear_mfma_ok(const LinearArgs &a)
+{
+    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
+    const bool even = !(a.K & 1) && !(a.lda1 & 1) && !(reinterpret_cast<uintptr_t>(a.a1) & 3) &&
+                      (!a.a2 || (!(a.lda2 & 1) && !(reinterpret_cast<uintptr_t>(a.a2) & 3)));
+    return even && ks <= 6 && (size_t)nt * ks * 1024 <= 64 * 1024;
+}
+
+static hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
+{
+    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
+    const size_t lds = (size_t)nt * ks * 1024;
+    const long ntile = (a.rows + 15) / 16;
+    long blocks = (ntile + 3) / 4;
+    if (blocks > 4L * device_cus()) blocks = 4L * device_cus();
+    KernelTimer kt(a.prof_id, s);
+    switch (ks) {
+    case 1: hipLaunchKernelGGL(linear_mfma_kernel<1>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
+    case 2: hipLaunchKernelGGL(linear_mfma_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
+    case 3: hipLaunchKernelGGL(linear_mfma_kernel<3>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
+    case 4: hipLaunchKernelGGL(linear_mfma_kernel<4>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
+    case 5: hipLaunchKernelGGL(linear_mfma_kernel<5>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
+    default: hipLaunchKernelGGL(linear_mfma_kernel<6>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
+    }
+    return hipGetLastError();
+}
+
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0) return hipSuccess;
+    if constexpr (sizeof(T) == 2) {
+        if (linear_mfma_ok(a)) return launch_linear_mfma(a, s);
+    }
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
     KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(linear_kernel<T>, grid, dim3(kThreads), 0, s, a);
@@ -163,9 +279,94 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same reduction on the matrix cores (bf16): dw = dout^T (a1 + a2) contracts over tokens, so
+// tokens are the k-slots of both operands: a lane reads 8 consecutive tokens of one column.
+// A workgroup owns a 64 x 64 tile of dw and a range of tokens; wave w owns the 16 rows n of the
+// tile (all four 16-column tiles), and the bias sums ride in a fifth product with a column of
+// ones.  One atomic add per output and workgroup.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs p, long rows_per_split)
+{
+    const uint16_t *dout = static_cast<const uint16_t *>(p.dout);
+    const uint16_t *a1 = static_cast<const uint16_t *>(p.a1);
+    const uint16_t *a2 = static_cast<const uint16_t *>(p.a2);
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
+    const int n0 = blockIdx.x * 64 + 16 * wave, k0 = blockIdx.y * 64;
+    if (n0 >= p.N) return; // no barrier in this kernel
+    const long t_begin = (long)blockIdx.z * rows_per_split;
+    long t_end = t_begin + rows_per_split;
+    if (t_end > p.rows) t_end = p.rows;
+    const int n = n0 + l16;
+    const bool n_ok = n < p.N;
+    const uint32_t one = 0x3f80u;
+    const uint4 ones = l16 == 0 ? make_uint4(one | one << 16, one | one << 16, one | one << 16, one | one << 16)
+                                : make_uint4(0u, 0u, 0u, 0u);
+
+    f32x4 acc[4], bacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (long t0 = t_begin; t0 < t_end; t0 += 32) {
+        uint32_t av[8], bv[4][8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+            const long t = t0 + 8 * q + s8;
+            const bool t_ok = t < t_end;
+            av[s8] = (t_ok && n_ok) ? (uint32_t)dout[t * p.lddout + n] : 0u;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                const int k = k0 + 16 * kt + l16;
+                uint32_t u = 0u;
+                if (t_ok && k < p.K) {
+                    u = a1[t * p.lda1 + k];
+                    if (a2) u = f32_to_bf16_bits(__uint_as_float(u << 16) + __uint_as_float((uint32_t)a2[t * p.lda2 + k] << 16));
+                }
+                bv[kt][s8] = u;
+            }
+        }
+        const uint4 af = make_uint4(av[0] | av[1] << 16, av[2] | av[3] << 16, av[4] | av[5] << 16, av[6] | av[7] << 16);
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            const uint4 bf = make_uint4(bv[kt][0] | bv[kt][1] << 16, bv[kt][2] | bv[kt][3] << 16,
+                                        bv[kt][4] | bv[kt][5] << 16, bv[kt][6] | bv[kt][7] << 16);
+            acc[kt] = mma32(af, bf, acc[kt]);
+        }
+        bacc = mma32(af, ones, bacc);
+    }
+    // result tiles: column l16 = k, rows 4q + j = n
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int nn = n0 + 4 * q + j;
+        if (nn >= p.N) continue;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            const int k = k0 + 16 * kt + l16;
+            if (k < p.K) atomicAdd(&p.dw[(long)nn * p.K + k], acc[kt][j]);
+        }
+        if (p.db && blockIdx.y == 0 && l16 == 0) atomicAdd(&p.db[nn], bacc[j]);
+    }
+}
+
+static hipError_t launch_wgrad_mfma(const WgradArgs &a, hipStream_t s)
+{
+    const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
+    long splits = 2L * device_cus() / (long)(tn * tk);
+    const long max_splits = (a.rows + 127) / 128;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    long rps = (a.rows + splits - 1) / splits;
+    rps = (rps + 31) / 32 * 32;
+    splits = (a.rows + rps - 1) / rps;
+    dim3 grid(tn, tk, (unsigned)splits);
+    KernelTimer kt(a.prof_id, s);
+    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kThreads), 0, s, a, rps);
+    return hipGetLastError();
+}
+
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
+    if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, s);
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
     long splits = 2048 / (long)(tn * tk);
     const long max_splits = (a.rows + 255) / 256;
@@ -493,19 +694,23 @@ hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const 
 template hipError_t launch_attn_bwd<float>(const Geom &, int, const float *, float *, const float *, float *, hipStream_t);
 template hipError_t launch_attn_bwd<bf16_t>(const Geom &, int, const bf16_t *, bf16_t *, const bf16_t *, float *, hipStream_t);
 
-__global__ void fill_zero_kernel(float *p, size_t n)
+__global__ void fill_zero_kernel(ZeroList z)
 {
+    float *p = z.p[blockIdx.y];
+    const size_t n = z.n[blockIdx.y];
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         p[i] = 0.f;
 }
 
-hipError_t launch_fill_zero(float *p, size_t n, hipStream_t s)
+hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s)
 {
-    if (n == 0) return hipSuccess;
-    unsigned blocks = (unsigned)((n + 255) / 256);
-    if (blocks > 1024) blocks = 1024;
+    size_t longest = 0;
+    for (int i = 0; i < z.count; ++i) longest = z.n[i] > longest ? z.n[i] : longest;
+    if (z.count <= 0 || longest == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((longest + 255) / 256);
+    if (blocks > 256) blocks = 256;
     KernelTimer kt(K_FILL, s);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, p, n);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks, z.count), dim3(256), 0, s, z);
     return hipGetLastError();
 }
 
