@@ -91,7 +91,9 @@ typedef struct gswa_desc {
  *                  q|k|v; fused path: nothing is used).  For inference (saved == NULL) the
  *                  scratch must hold *fwd_ws_bytes + *saved_bytes: what would have been saved is
  *                  then kept there for the duration of the call.
- *   *bwd_ws_bytes  scratch of gswa_backward.  Staged path: one group's q|k|v and its gradient.
+ *   *bwd_ws_bytes  scratch of gswa_backward.  Staged path: one group's q|k|v and its gradient, plus
+ *                  16 fp32 copies of the five parameter gradients (workgroups spread their atomic
+ *                  adds over the copies; one launch sums them at the end).
  *                  Fused path: one partial parameter-gradient vector per workgroup.
  * Which path serves a layer depends only on desc (shape, dtype, flags).
  * Any output pointer may be NULL.  All sizes are multiples of 256.

@@ -198,7 +198,7 @@ __global__ __launch_bounds__(64 * NT) void attn_core_fwd_kernel(Geom g, int grp,
 template <int NT, int ET, int KQ>
 __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp, const bf16_t *__restrict__ qkv,
                                                                bf16_t *dqkv, const bf16_t *__restrict__ table,
-                                                               float *dtable)
+                                                               float *dtable, long rep_stride, int reps)
 {
     using Cf = CoreCfg<NT, ET, KQ>;
     constexpr int N = Cf::N, NTH = Cf::NTHREADS, LK = Cf::LK, LV = Cf::LV, LT = Cf::LT;
@@ -223,6 +223,7 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
     const int d = g.d, dq = g.dq, Rg = g.Rg, Qg = g.Qg;
     const uint16_t *qkv16 = reinterpret_cast<const uint16_t *>(qkv);
     uint16_t *dqkv16 = reinterpret_cast<uint16_t *>(dqkv);
+    dtable += (long)(w % reps) * rep_stride; // this window's copy of the gradient
 
     stage_geometry<N, NTH>(g, w, hd, table, tb, koff, tok, tid);
     __syncthreads();
@@ -469,7 +470,7 @@ hipError_t launch_fwd(const Geom &g, int grp, const bf16_t *qkv, const bf16_t *t
 
 template <int NT, int ET, int KQ>
 hipError_t launch_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
-                      float *dtable, hipStream_t s)
+                      float *dtable, long rep_stride, int reps, hipStream_t s)
 {
     using Cf = CoreCfg<NT, ET, KQ>;
     const size_t lds = bwd_lds_bytes<Cf>(g.M);
@@ -482,7 +483,8 @@ hipError_t launch_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, c
         attr_done = true;
     }
     KernelTimer kt(K_ATTN_CORE_BWD, s);
-    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(Cf::NTHREADS), lds, s, g, grp, qkv, dqkv, table, dtable);
+    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(Cf::NTHREADS), lds, s, g, grp, qkv, dqkv, table, dtable,
+                       rep_stride, reps);
     return hipGetLastError();
 }
 
@@ -509,12 +511,12 @@ hipError_t launch_attn_core_fwd(const Geom &g, int grp, const bf16_t *qkv, const
 }
 
 hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
-                                float *dtable, hipStream_t s)
+                                float *dtable, long rep_stride, int reps, hipStream_t s)
 {
-    if (!attn_core_mfma_supported(g)) return hipErrorInvalidValue;
+    if (!attn_core_mfma_supported(g) || reps < 1) return hipErrorInvalidValue;
     const int nt = g.N / 16, et = (g.d + 15) / 16, kq = (g.dq + 15) / 16;
 #define X(NT_, ET_, KQ_) \
-    if (nt == NT_ && et == ET_ && kq == KQ_) return launch_bwd<NT_, ET_, KQ_>(g, grp, qkv, dqkv, table, dtable, s);
+    if (nt == NT_ && et == ET_ && kq == KQ_) return launch_bwd<NT_, ET_, KQ_>(g, grp, qkv, dqkv, table, dtable, rep_stride, reps, s);
     GSWA_CORE_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

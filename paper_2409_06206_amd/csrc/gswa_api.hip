@@ -76,6 +76,7 @@ struct Sizes {
     size_t act;          // bytes of the saved [T, C] activation at the start of `saved`
     size_t pack;         // bytes of the packed parameters behind it (fused path)
     size_t fused_bwd_ws; // partial sums of the fused backward
+    size_t params;       // fp32 entries of all five parameter gradients (one copy of the staged backward)
     bool fused_fwd, fused_bwd;
 };
 
@@ -91,7 +92,9 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.saved = align256((size_t)g.T * g.C * e);
     s.qkv = align256((size_t)g.T * g.Rg * e);
     s.fwd_ws = s.qkv;
-    s.bwd_ws = 2 * s.qkv;
+    s.params = (size_t)g.groups * g.Rg * g.Cg + (size_t)g.groups * g.Rg + (size_t)g.C * g.C + g.C +
+               (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
+    s.bwd_ws = 2 * s.qkv + align256(kGradReplicas * s.params * sizeof(float));
     s.fused_fwd = use_fused_fwd(d, g);
     s.fused_bwd = s.fused_fwd && fused_bwd_supported(g);
     s.fused_bwd_ws = 0;
@@ -156,21 +159,23 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     T *qkv = reinterpret_cast<T *>(ws);
     T *dqkv = reinterpret_cast<T *>(ws + sz.qkv);
     const int C = g.C, Cg = g.Cg, G = g.groups, Rg = g.Rg;
-    if (!(flags & GSWA_ACCUM_WGRAD)) {
+    // the parameter gradients are accumulated in kGradReplicas copies behind the two q|k|v buffers
+    // (layout of a copy: dw_qkv | db_qkv | dw_proj | db_proj | dtable) and summed at the end
+    float *rep = reinterpret_cast<float *>(ws + 2 * sz.qkv);
+    const long P = (long)sz.params;
+    const long o_wq = 0, o_bq = o_wq + (long)G * Rg * Cg, o_wp = o_bq + (long)G * Rg, o_bp = o_wp + (long)C * C;
+    const long o_tb = o_bp + C;
+    {
         ZeroList z{};
-        z.p[0] = dw_qkv; z.n[0] = (size_t)G * Rg * Cg;
-        z.p[1] = db_qkv; z.n[1] = (size_t)G * Rg;
-        z.p[2] = dw_proj; z.n[2] = (size_t)C * C;
-        z.p[3] = db_proj; z.n[3] = (size_t)C;
-        z.p[4] = dtable; z.n[4] = (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
-        z.count = 5;
+        z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P;
+        z.count = 1;
         GSWA_HIP(launch_fill_zero(z, st));
     }
     // adjoint of Eq. 7 with respect to the projection parameters
     WgradArgs wp{};
     wp.dout = dy; wp.lddout = C;
     wp.a1 = attn; wp.lda1 = C;
-    wp.dw = dw_proj; wp.db = db_proj;
+    wp.dw = rep + o_wp; wp.db = rep + o_bp; wp.rep_stride = P; wp.reps = kGradReplicas;
     wp.rows = g.T; wp.N = C; wp.K = C; wp.prof_id = K_PROJ_WGRAD;
     GSWA_HIP(launch_wgrad<T>(wp, st));
 
@@ -197,11 +202,12 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         bool on_matrix_cores = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (attn_core_mfma_supported(g)) {
-                GSWA_HIP(launch_attn_core_bwd(g, grp, qkv, dqkv, table, dtable, st));
+                GSWA_HIP(launch_attn_core_bwd(g, grp, qkv, dqkv, table, rep + o_tb, P, kGradReplicas, st));
                 on_matrix_cores = true;
             }
         }
-        if (!on_matrix_cores) GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, dtable, st));
+        if (!on_matrix_cores)
+            GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, rep + o_tb, P, kGradReplicas, st));
         // dF_g = dqkv Wqkv_g  ->  dx[:, slice g]
         LinearArgs lx{};
         lx.a1 = dqkv; lx.lda1 = Rg;
@@ -213,11 +219,22 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         wq.dout = dqkv; wq.lddout = Rg;
         wq.a1 = x + grp * Cg; wq.lda1 = C;
         if (has_prev) { wq.a2 = attn + (grp - 1) * Cg; wq.lda2 = C; }
-        wq.dw = dw_qkv + (size_t)grp * Rg * Cg;
-        wq.db = db_qkv + (size_t)grp * Rg;
+        wq.dw = rep + o_wq + (size_t)grp * Rg * Cg;
+        wq.db = rep + o_bq + (size_t)grp * Rg;
+        wq.rep_stride = P; wq.reps = kGradReplicas;
         wq.rows = g.T; wq.N = Rg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
         GSWA_HIP(launch_wgrad<T>(wq, st));
     }
+    ReplicaSum rs{};
+    rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;
+    rs.out[0] = dw_qkv; rs.off[0] = o_wq; rs.n[0] = (long)G * Rg * Cg;
+    rs.out[1] = db_qkv; rs.off[1] = o_bq; rs.n[1] = (long)G * Rg;
+    rs.out[2] = dw_proj; rs.off[2] = o_wp; rs.n[2] = (long)C * C;
+    rs.out[3] = db_proj; rs.off[3] = o_bp; rs.n[3] = C;
+    rs.out[4] = dtable; rs.off[4] = o_tb; rs.n[4] = (long)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
+    rs.count = 5;
+    rs.accumulate = (flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
+    GSWA_HIP(launch_reduce_replicas(rs, st));
     return GSWA_OK;
 }
 

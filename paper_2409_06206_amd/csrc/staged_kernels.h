@@ -20,12 +20,19 @@ struct LinearArgs {
     int prof_id; // KernelId this launch is accounted under
 };
 
-// dw[n,k] += sum_t dout[t,n] * (a1[t,k] + a2[t,k]);  db[n] += sum_t dout[t,n]   (fp32 atomics)
+// Atomic adds of many workgroups to one address serialise (tens of ns each), so the staged
+// backward accumulates every parameter gradient in kGradReplicas copies (a workgroup adds into
+// copy `its index mod kGradReplicas`), summed at the end by one launch.
+constexpr int kGradReplicas = 16;
+
+// dw[n,k] += sum_t dout[t,n] * (a1[t,k] + a2[t,k]);  db[n] += sum_t dout[t,n]   (fp32 atomics).
+// dw, db point into copy 0; copy r lies rep_stride floats further (reps copies; 1 = a single array).
 struct WgradArgs {
     const void *dout; long lddout;
     const void *a1; long lda1;
     const void *a2; long lda2;
     float *dw; float *db;
+    long rep_stride; int reps;
     long rows; int N, K;
     int prof_id;
 };
@@ -40,10 +47,11 @@ hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table,
                            hipStream_t s);
 
 // Adjoint of the attention core for group `grp`.  On entry the v part of dqkv [T, Rg] holds
-// dO of the group; on exit dqkv holds dq|dk|dv.  dtable (fp32) is added into.
+// dO of the group; on exit dqkv holds dq|dk|dv.  dtable (fp32) is added into: copy
+// `window mod reps` of `reps` copies that lie rep_stride floats apart.
 template <typename T>
 hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
-                           float *dtable, hipStream_t s);
+                           float *dtable, long rep_stride, int reps, hipStream_t s);
 
 // The same two steps on the matrix cores, for bf16 layers whose windows are 64 or 144 tokens and
 // whose heads are at most 32 channels wide (attn_core_mfma_supported); same buffers, same contract.
@@ -51,7 +59,7 @@ bool attn_core_mfma_supported(const Geom &g);
 hipError_t launch_attn_core_fwd(const Geom &g, int grp, const bf16_t *qkv, const bf16_t *table,
                                 bf16_t *attn_out, hipStream_t s);
 hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
-                                float *dtable, hipStream_t s);
+                                float *dtable, long rep_stride, int reps, hipStream_t s);
 
 // LDS bytes the two attention kernels need for this geometry, or 0 if no strip height fits.
 size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows);
@@ -64,5 +72,18 @@ struct ZeroList {
     int count;
 };
 hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s);
+
+// out_k[i] (+)= sum_r rep[r * stride + off_k + i] for up to eight output arrays laid out one after
+// the other (at offsets off_k) inside every copy.
+struct ReplicaSum {
+    const float *rep;
+    long stride;
+    int reps;
+    float *out[8];
+    long off[8], n[8];
+    int count;
+    int accumulate;
+};
+hipError_t launch_reduce_replicas(const ReplicaSum &r, hipStream_t s);
 
 } // namespace gswa

@@ -230,6 +230,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
     long t_end = t_begin + rows_per_split;
     if (t_end > p.rows) t_end = p.rows;
 
+    float *dw = p.dw + (long)(blockIdx.z % p.reps) * p.rep_stride;
+    float *db = p.db ? p.db + (long)(blockIdx.z % p.reps) * p.rep_stride : nullptr;
     float acc[4][4] = {};
     float bacc[4] = {};
     for (long t0 = t_begin; t0 < t_end; t0 += TT) {
@@ -273,9 +275,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int k = k0 + tx * 4 + j;
-            if (k < p.K) atomicAdd(&p.dw[(long)n * p.K + k], acc[i][j]);
+            if (k < p.K) atomicAdd(&dw[(long)n * p.K + k], acc[i][j]);
         }
-        if (p.db && blockIdx.y == 0 && tx == 0) atomicAdd(&p.db[n], bacc[i]);
+        if (db && blockIdx.y == 0 && tx == 0) atomicAdd(&db[n], bacc[i]);
     }
 }
 
@@ -334,6 +336,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs p, long 
         bacc = mma32(af, ones, bacc);
     }
     // result tiles: column l16 = k, rows 4q + j = n
+    float *dw = p.dw + (long)(blockIdx.z % p.reps) * p.rep_stride;
+    float *db = p.db ? p.db + (long)(blockIdx.z % p.reps) * p.rep_stride : nullptr;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int nn = n0 + 4 * q + j;
@@ -341,9 +345,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs p, long 
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) {
             const int k = k0 + 16 * kt + l16;
-            if (k < p.K) atomicAdd(&p.dw[(long)nn * p.K + k], acc[kt][j]);
+            if (k < p.K) atomicAdd(&dw[(long)nn * p.K + k], acc[kt][j]);
         }
-        if (p.db && blockIdx.y == 0 && l16 == 0) atomicAdd(&p.db[nn], bacc[j]);
+        if (db && blockIdx.y == 0 && l16 == 0) atomicAdd(&db[nn], bacc[j]);
     }
 }
 
@@ -366,6 +370,7 @@ static hipError_t launch_wgrad_mfma(const WgradArgs &a, hipStream_t s)
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
+    if (a.reps < 1) return hipErrorInvalidValue;
     if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, s);
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
     long splits = 2048 / (long)(tn * tk);
@@ -545,9 +550,10 @@ template hipError_t launch_attn_fwd<bf16_t>(const Geom &, int, const bf16_t *, c
 template <typename T>
 __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, const T *__restrict__ qkv,
                                                             T *dqkv, const T *__restrict__ table,
-                                                            float *dtable, int RS)
+                                                            float *dtable, long rep_stride, int reps, int RS)
 {
     extern __shared__ float smem[];
+    dtable += (long)(blockIdx.x % reps) * rep_stride;
     const int N = g.N, d = g.d, dp = d | 1, dq = g.dq, ep = dq | 1, Qg = g.Qg, Rg = g.Rg, M = g.M;
     const int ldS = N + 1, ntbl = (2 * M - 1) * (2 * M - 1);
     float *k = smem;
@@ -674,10 +680,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
     for (int e = tid; e < ntbl; e += kThreads) atomicAdd(&dtable[(long)e * g.heads + hd], tbl[e]);
 }
 
+
 template <typename T>
 hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
-                           float *dtable, hipStream_t s)
+                           float *dtable, long rep_stride, int reps, hipStream_t s)
 {
+    if (reps < 1) return hipErrorInvalidValue;
     int rs = 0;
     const size_t lds = attn_bwd_lds_bytes(g, &rs);
     if (rs == 0) return hipErrorInvalidValue;
@@ -688,11 +696,11 @@ hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const 
         if (e != hipSuccess) return e;
     }
     KernelTimer kt(K_ATTN_BWD, s);
-    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, dqkv, table, dtable, rs);
+    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, dqkv, table, dtable, rep_stride, reps, rs);
     return hipGetLastError();
 }
-template hipError_t launch_attn_bwd<float>(const Geom &, int, const float *, float *, const float *, float *, hipStream_t);
-template hipError_t launch_attn_bwd<bf16_t>(const Geom &, int, const bf16_t *, bf16_t *, const bf16_t *, float *, hipStream_t);
+template hipError_t launch_attn_bwd<float>(const Geom &, int, const float *, float *, const float *, float *, long, int, hipStream_t);
+template hipError_t launch_attn_bwd<bf16_t>(const Geom &, int, const bf16_t *, bf16_t *, const bf16_t *, float *, long, int, hipStream_t);
 
 __global__ void fill_zero_kernel(ZeroList z)
 {
@@ -711,6 +719,28 @@ hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s)
     if (blocks > 256) blocks = 256;
     KernelTimer kt(K_FILL, s);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks, z.count), dim3(256), 0, s, z);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void reduce_replicas_kernel(ReplicaSum r)
+{
+    const int k = blockIdx.y;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < r.n[k]; i += (long)gridDim.x * blockDim.x) {
+        float acc = 0.f;
+        for (int c = 0; c < r.reps; ++c) acc += r.rep[(long)c * r.stride + r.off[k] + i];
+        r.out[k][i] = r.accumulate ? r.out[k][i] + acc : acc;
+    }
+}
+
+hipError_t launch_reduce_replicas(const ReplicaSum &r, hipStream_t s)
+{
+    long longest = 0;
+    for (int k = 0; k < r.count; ++k) longest = r.n[k] > longest ? r.n[k] : longest;
+    if (r.count <= 0 || longest == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((longest + 255) / 256);
+    if (blocks > 256) blocks = 256;
+    KernelTimer kt(K_REDUCE, s);
+    hipLaunchKernelGGL(reduce_replicas_kernel, dim3(blocks, r.count), dim3(256), 0, s, r);
     return hipGetLastError();
 }
 
