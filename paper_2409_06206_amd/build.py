@@ -9,7 +9,7 @@ LIB_PATH = os.path.join(_HERE, "libgswa.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-munsafe-fp-atomics",
-    # packed fp32 instructions are kept off on the test machines
+    # packed fp32 instructions are kept off
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
