@@ -242,6 +242,10 @@ AGILE_SMALL = [
     (2, 16, 16, 60, 6, 1, 8, 4, 16, "bf16", "init"),      # q/k wider than v
     (1, 24, 24, 180, 6, 2, 12, 6, 8, "bf16", "stress"),
     (1, 16, 16, 12, 6, 6, 4, 1, 1, "f32", "stress"),
+    (2, 24, 24, 60, 4, 2, 12, 6, 20, "bf16", "stress"),   # q/k of 17..32 channels: two 16-channel tiles
+    (1, 24, 24, 180, 6, 3, 12, 7, 32, "bf16", "stress"),
+    (2, 16, 16, 42, 6, 2, 8, 3, 5, "bf16", "stress"),     # head width 7, 21 channels per group (odd row strides)
+    (1, 24, 24, 18, 6, 2, 12, 6, 3, "bf16", "stress"),    # head width 3
 ]
 
 
