@@ -4,6 +4,7 @@
 // window partition exist only as the index map window_token().
 #include "staged_kernels.h"
 #include "mfma.h"
+#include <cmath>
 
 namespace gswa {
 
@@ -86,27 +87,38 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinearArgs p)
 }
 
 // ---------------------------------------------------------------------------------------
-// The same linear map on the matrix cores (bf16, even K and row strides, K <= 192): the weights
-// become B-operand fragments in LDS once per workgroup, every wave then walks over 16-row tiles:
-// the rows are its A operand (k-slots = 8 consecutive input channels, read as dwords), one
-// 16x16x32 MFMA per (output tile, K step).
+// The same linear map on the matrix cores (bf16, even K and row strides): a workgroup takes up to
+// NTC 16-column tiles of the output (blockIdx.y) and turns their weights into B-operand fragments
+// in LDS once; every wave then walks over 16-row tiles: the rows are its A operand (k-slots = 8
+// consecutive input channels, read as dwords, all K steps in flight together), one 16x16x32 MFMA
+// per (output tile, K step).  KSM bounds the K steps (K <= 32 * KSM).
 // ---------------------------------------------------------------------------------------
-template <int KS>
-__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs p, int NT)
+template <int KSM, int NTC>
+__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs p, int KS)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
-    uint4 *wl = reinterpret_cast<uint4 *>(lsm); // [NT][KS][64 lanes]
+    uint4 *wl = reinterpret_cast<uint4 *>(lsm); // [NTC][KS][64 lanes]
     const uint16_t *w = static_cast<const uint16_t *>(p.w);
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
-    for (int i = tid; i < NT * KS * 64; i += kThreads) {
+    const int ncol0 = blockIdx.y * (16 * NTC);
+    for (int i = tid; i < NTC * KS * 64; i += kThreads) {
         const int f = i >> 6, ln = i & 63;
         const int nt = f / KS, ks = f - nt * KS;
-        const int n = 16 * nt + (ln & 15), k0 = 32 * ks + 8 * (ln >> 4);
-        uint32_t v[8];
+        const int n = ncol0 + 16 * nt + (ln & 15), k0 = 32 * ks + 8 * (ln >> 4);
+        if (p.w_sk == 1 && !(p.w_sn & 1)) {
+            // the lane's 8 input channels are contiguous: dword reads (K is even, so is w_sn)
+            const uint32_t *w32 = reinterpret_cast<const uint32_t *>(w + (long)n * p.w_sn);
+            uint32_t v[4];
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8)
-            v[s8] = (n < p.N && k0 + s8 < p.K) ? (uint32_t)w[(long)n * p.w_sn + (long)(k0 + s8) * p.w_sk] : 0u;
-        wl[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+            for (int dw = 0; dw < 4; ++dw) v[dw] = (n < p.N && k0 + 2 * dw < p.K) ? w32[(k0 >> 1) + dw] : 0u;
+            wl[i] = make_uint4(v[0], v[1], v[2], v[3]);
+        } else {
+            uint32_t v[8];
+#pragma unroll
+            for (int s8 = 0; s8 < 8; ++s8)
+                v[s8] = (n < p.N && k0 + s8 < p.K) ? (uint32_t)w[(long)n * p.w_sn + (long)(k0 + s8) * p.w_sk] : 0u;
+            wl[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        }
     }
     __syncthreads();
 
@@ -118,38 +130,46 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs p, int
     const long ntile = (p.rows + 15) / 16;
     for (long tile = (long)blockIdx.x * (kThreads / 64) + wave; tile < ntile; tile += (long)gridDim.x * (kThreads / 64)) {
         const long row = 16 * tile + l16;
-        uint4 af[KS];
+        uint4 af[KSM];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            uint32_t v[4];
+        for (int ks = 0; ks < KSM; ++ks) {
+            uint32_t v[4] = {0u, 0u, 0u, 0u};
+            if (ks < KS) {
 #pragma unroll
-            for (int dw = 0; dw < 4; ++dw) {
-                const int k = 32 * ks + 8 * q + 2 * dw;
-                uint32_t u = 0u;
-                if (row < p.rows && k < p.K) {
-                    u = a1[(row * p.lda1 + k) >> 1];
-                    if (a2) {
-                        const uint32_t u2 = a2[(row * p.lda2 + k) >> 1];
-                        u = pack_bf16x2(bf16_lo(u) + bf16_lo(u2), bf16_hi(u) + bf16_hi(u2));
+                for (int dw = 0; dw < 4; ++dw) {
+                    const int k = 32 * ks + 8 * q + 2 * dw;
+                    if (row < p.rows && k < p.K) {
+                        uint32_t u = a1[(row * p.lda1 + k) >> 1];
+                        if (a2) {
+                            const uint32_t u2 = a2[(row * p.lda2 + k) >> 1];
+                            u = pack_bf16x2(bf16_lo(u) + bf16_lo(u2), bf16_hi(u) + bf16_hi(u2));
+                        }
+                        v[dw] = u;
                     }
                 }
-                v[dw] = u;
             }
             af[ks] = make_uint4(v[0], v[1], v[2], v[3]);
         }
-        for (int nt = 0; nt < NT; ++nt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4 acc[NTC];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc = mma32(af[ks], wl[(nt * KS + ks) * 64 + lane], acc);
-            // result: column l16 = output feature, rows 4q + j = rows of the tile
-            const int n = 16 * nt + l16;
+        for (int nt = 0; nt < NTC; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks)
+            if (ks < KS) {
+#pragma unroll
+                for (int nt = 0; nt < NTC; ++nt) acc[nt] = mma32(af[ks], wl[(nt * KS + ks) * 64 + lane], acc[nt]);
+            }
+        // result: column l16 = output feature, rows 4q + j = rows of the tile
+#pragma unroll
+        for (int nt = 0; nt < NTC; ++nt) {
+            const int n = ncol0 + 16 * nt + l16;
             if (n >= p.N) continue;
             const float b = bias ? __uint_as_float((uint32_t)bias[n] << 16) : 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const long r = 16 * tile + 4 * q + j;
                 if (r >= p.rows) continue;
-                float v = acc[j] + b;
+                float v = acc[nt][j] + b;
                 if (add) v += __uint_as_float((uint32_t)add[r * p.ldadd + n] << 16);
                 out[r * p.ldout + n] = f32_to_bf16_bits(v);
             }
@@ -172,29 +192,42 @@ static int device_cus()
 // true when the matrix-core kernel can serve the call (the dword reads need even offsets)
 static bool linear_mfma_ok(const LinearArgs &a)
 {
-    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
     const bool even = !(a.K & 1) && !(a.lda1 & 1) && !(reinterpret_cast<uintptr_t>(a.a1) & 3) &&
                       (!a.a2 || (!(a.lda2 & 1) && !(reinterpret_cast<uintptr_t>(a.a2) & 3)));
-    return even && ks <= 6 && (size_t)nt * ks * 1024 <= 64 * 1024;
+    const bool w_ok = a.w_sk != 1 || (a.w_sn & 1) || !(reinterpret_cast<uintptr_t>(a.w) & 3);
+    return even && w_ok && a.K <= 32 * 18;
+}
+
+template <int KSM, int NTC> static hipError_t launch_linear_mfma_t(const LinearArgs &a, hipStream_t s)
+{
+    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
+    const unsigned chunks = (unsigned)((nt + NTC - 1) / NTC);
+    const size_t lds = (size_t)NTC * ks * 1024;
+    auto kern = linear_mfma_kernel<KSM, NTC>;
+    static bool attr_done = false;
+    if (!attr_done && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, NTC * KSM * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const long ntile = (a.rows + 15) / 16;
+    // every workgroup builds its chunk's weight fragments first: with several chunks the rows are
+    // spread over fewer, longer-running workgroups
+    long blocks = (ntile + 3) / 4, cap = (chunks == 1 ? 4L : 2L) * device_cus() / chunks;
+    if (cap < 1) cap = 1;
+    if (blocks > cap) blocks = cap;
+    KernelTimer kt(a.prof_id, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks, chunks), dim3(kThreads), lds, s, a, ks);
+    return hipGetLastError();
 }
 
 static hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
 {
     const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
-    const size_t lds = (size_t)nt * ks * 1024;
-    const long ntile = (a.rows + 15) / 16;
-    long blocks = (ntile + 3) / 4;
-    if (blocks > 4L * device_cus()) blocks = 4L * device_cus();
-    KernelTimer kt(a.prof_id, s);
-    switch (ks) {
-    case 1: hipLaunchKernelGGL(linear_mfma_kernel<1>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
-    case 2: hipLaunchKernelGGL(linear_mfma_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
-    case 3: hipLaunchKernelGGL(linear_mfma_kernel<3>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
-    case 4: hipLaunchKernelGGL(linear_mfma_kernel<4>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
-    case 5: hipLaunchKernelGGL(linear_mfma_kernel<5>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
-    default: hipLaunchKernelGGL(linear_mfma_kernel<6>, dim3((unsigned)blocks), dim3(kThreads), lds, s, a, nt); break;
-    }
-    return hipGetLastError();
+    if (ks <= 2) return nt <= 4 ? launch_linear_mfma_t<2, 4>(a, s) : launch_linear_mfma_t<2, 8>(a, s);
+    if (ks <= 6) return launch_linear_mfma_t<6, 4>(a, s);
+    return launch_linear_mfma_t<18, 4>(a, s);
 }
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
@@ -284,18 +317,21 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
 // ---------------------------------------------------------------------------------------
 // The same reduction on the matrix cores (bf16): dw = dout^T (a1 + a2) contracts over tokens, so
 // tokens are the k-slots of both operands: a lane reads 8 consecutive tokens of one column.
-// A workgroup owns a 64 x 64 tile of dw and a range of tokens; wave w owns the 16 rows n of the
-// tile (all four 16-column tiles), and the bias sums ride in a fifth product with a column of
-// ones.  One atomic add per output and workgroup.
+// A workgroup of 16 waves owns a 64 x 64 tile of dw and a range of tokens: wave (nw, tq) owns
+// the 16 rows n = 16*nw.. of the tile (all four 16-column tiles) and every fourth 32-token step
+// starting at tq; the bias sums ride in a fifth product with a column of ones.  The four token
+// quarters are summed through LDS: one atomic add per output and workgroup.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs p, long rows_per_split)
+constexpr int kWgradThreads = 1024;
+__global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs p, long rows_per_split)
 {
+    __shared__ float red[3][4][20][64]; // [token quarter - 1][nw][accumulator][lane]
     const uint16_t *dout = static_cast<const uint16_t *>(p.dout);
     const uint16_t *a1 = static_cast<const uint16_t *>(p.a1);
     const uint16_t *a2 = static_cast<const uint16_t *>(p.a2);
-    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
-    const int n0 = blockIdx.x * 64 + 16 * wave, k0 = blockIdx.y * 64;
-    if (n0 >= p.N) return; // no barrier in this kernel
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wave = tid >> 6, nw = wave & 3, tq = wave >> 2;
+    const int n0 = blockIdx.x * 64 + 16 * nw, k0 = blockIdx.y * 64;
     const long t_begin = (long)blockIdx.z * rows_per_split;
     long t_end = t_begin + rows_per_split;
     if (t_end > p.rows) t_end = p.rows;
@@ -308,32 +344,53 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs p, long 
     f32x4 acc[4], bacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (long t0 = t_begin; t0 < t_end; t0 += 32) {
-        uint32_t av[8], bv[4][8];
+    if (n0 < p.N)
+        for (long t0 = t_begin + 32 * tq; t0 < t_end; t0 += 128) {
+            uint32_t av[8], bv[4][8];
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) {
-            const long t = t0 + 8 * q + s8;
-            const bool t_ok = t < t_end;
-            av[s8] = (t_ok && n_ok) ? (uint32_t)dout[t * p.lddout + n] : 0u;
+            for (int s8 = 0; s8 < 8; ++s8) {
+                const long t = t0 + 8 * q + s8;
+                const bool t_ok = t < t_end;
+                av[s8] = (t_ok && n_ok) ? (uint32_t)dout[t * p.lddout + n] : 0u;
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) {
+                    const int k = k0 + 16 * kt + l16;
+                    uint32_t u = 0u;
+                    if (t_ok && k < p.K) {
+                        u = a1[t * p.lda1 + k];
+                        if (a2) u = f32_to_bf16_bits(__uint_as_float(u << 16) + __uint_as_float((uint32_t)a2[t * p.lda2 + k] << 16));
+                    }
+                    bv[kt][s8] = u;
+                }
+            }
+            const uint4 af = make_uint4(av[0] | av[1] << 16, av[2] | av[3] << 16, av[4] | av[5] << 16, av[6] | av[7] << 16);
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
-                const int k = k0 + 16 * kt + l16;
-                uint32_t u = 0u;
-                if (t_ok && k < p.K) {
-                    u = a1[t * p.lda1 + k];
-                    if (a2) u = f32_to_bf16_bits(__uint_as_float(u << 16) + __uint_as_float((uint32_t)a2[t * p.lda2 + k] << 16));
-                }
-                bv[kt][s8] = u;
+                if (k0 + 16 * kt >= p.K) continue; // uniform
+                const uint4 bf = make_uint4(bv[kt][0] | bv[kt][1] << 16, bv[kt][2] | bv[kt][3] << 16,
+                                            bv[kt][4] | bv[kt][5] << 16, bv[kt][6] | bv[kt][7] << 16);
+                acc[kt] = mma32(af, bf, acc[kt]);
             }
+            bacc = mma32(af, ones, bacc);
         }
-        const uint4 af = make_uint4(av[0] | av[1] << 16, av[2] | av[3] << 16, av[4] | av[5] << 16, av[6] | av[7] << 16);
+    if (tq > 0) {
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            const uint4 bf = make_uint4(bv[kt][0] | bv[kt][1] << 16, bv[kt][2] | bv[kt][3] << 16,
-                                        bv[kt][4] | bv[kt][5] << 16, bv[kt][6] | bv[kt][7] << 16);
-            acc[kt] = mma32(af, bf, acc[kt]);
-        }
-        bacc = mma32(af, ones, bacc);
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) red[tq - 1][nw][4 * kt + j][lane] = acc[kt][j];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[tq - 1][nw][16 + j][lane] = bacc[j];
+    }
+    __syncthreads();
+    if (tq > 0 || n0 >= p.N) return;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[kt][j] += red[r][nw][4 * kt + j][lane];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bacc[j] += red[r][nw][16 + j][lane];
     }
     // result tiles: column l16 = k, rows 4q + j = n
     float *dw = p.dw + (long)(blockIdx.z % p.reps) * p.rep_stride;
@@ -354,16 +411,21 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(WgradArgs p, long 
 static hipError_t launch_wgrad_mfma(const WgradArgs &a, hipStream_t s)
 {
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
-    long splits = 2L * device_cus() / (long)(tn * tk);
+    // A wave waits for the loads of one 32-token step at a time (about 1.5 us under load) and every
+    // split adds N*K atomic adds (about 60 per ns for the whole chip): the split count balances
+    // rows / (128 * splits) steps per wave against splits * N * K adds.
+    long splits = (long)sqrt(700.0 * (double)a.rows / ((double)a.N * a.K));
     const long max_splits = (a.rows + 127) / 128;
     if (splits > max_splits) splits = max_splits;
+    const long resident = 2L * device_cus() / (long)(tn * tk); // all workgroups on the chip at once
+    if (splits > resident && resident >= 8) splits = resident;
     if (splits < 1) splits = 1;
     long rps = (a.rows + splits - 1) / splits;
-    rps = (rps + 31) / 32 * 32;
+    rps = (rps + 127) / 128 * 128;
     splits = (a.rows + rps - 1) / rps;
     dim3 grid(tn, tk, (unsigned)splits);
     KernelTimer kt(a.prof_id, s);
-    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kThreads), 0, s, a, rps);
+    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kWgradThreads), 0, s, a, rps);
     return hipGetLastError();
 }
 
