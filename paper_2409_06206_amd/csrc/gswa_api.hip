@@ -190,7 +190,6 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         la.bias = b_qkv + (size_t)grp * Rg;
         la.out = qkv; la.ldout = Rg;
         la.rows = g.T; la.N = Rg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
-        GSWA_HIP(launch_linear<T>(la, st));
         // dO_g = dy Wproj[:, slice g] (+ dF_{g+1}, which is dx[:, slice g+1]) into the v part of dqkv
         LinearArgs lo{};
         lo.a1 = dy; lo.lda1 = C;
@@ -198,7 +197,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         if (grp < G - 1 && g.cascade) { lo.add = dx + (grp + 1) * Cg; lo.ldadd = C; }
         lo.out = dqkv + 2 * g.Qg; lo.ldout = Rg;
         lo.rows = g.T; lo.N = Cg; lo.K = C; lo.prof_id = K_DO_LINEAR;
-        GSWA_HIP(launch_linear<T>(lo, st));
+        GSWA_HIP(launch_linear_pair<T>(la, lo, st));
         bool on_matrix_cores = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (attn_core_mfma_supported(g)) {

@@ -25,6 +25,7 @@ enum KernelId {
     K_WPROJ_GRAD,   // split backward: d w_proj, d b_proj
     K_ATTN_CORE_FWD, // attention core of one group on the matrix cores
     K_ATTN_CORE_BWD, // its adjoint
+    K_LINEAR_PAIR,  // backward of one group: q|k|v recomputation and dO in one launch
     K_COUNT
 };
 

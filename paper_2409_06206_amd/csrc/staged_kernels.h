@@ -38,6 +38,8 @@ struct WgradArgs {
 };
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);
+// Two maps that do not depend on each other, in one launch where the kernels allow it.
+template <typename T> hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, hipStream_t s);
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s);
 
 // Attention core of head group `grp` (Eq. 6 right-hand side): reads q|k|v [T, Rg] through the

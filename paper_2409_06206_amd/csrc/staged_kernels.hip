@@ -93,14 +93,20 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinearArgs p)
 // consecutive input channels, read as dwords, all K steps in flight together), one 16x16x32 MFMA
 // per (output tile, K step).  KSM bounds the K steps (K <= 32 * KSM).
 // ---------------------------------------------------------------------------------------
+// One launch can serve two independent maps: the column chunks of the second follow those of the
+// first along blockIdx.y (chunks_a of them; the second map is absent when gridDim.y == chunks_a).
 template <int KSM, int NTC>
-__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs p, int KS)
+__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, LinearArgs pb, int ksa, int ksb,
+                                                              int chunks_a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
     uint4 *wl = reinterpret_cast<uint4 *>(lsm); // [NTC][KS][64 lanes]
+    const bool second = (int)blockIdx.y >= chunks_a;
+    const LinearArgs &p = second ? pb : pa;
+    const int KS = second ? ksb : ksa;
     const uint16_t *w = static_cast<const uint16_t *>(p.w);
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
-    const int ncol0 = blockIdx.y * (16 * NTC);
+    const int ncol0 = ((int)blockIdx.y - (second ? chunks_a : 0)) * (16 * NTC);
     for (int i = tid; i < NTC * KS * 64; i += kThreads) {
         const int f = i >> 6, ln = i & 63;
         const int nt = f / KS, ks = f - nt * KS;
@@ -198,11 +204,14 @@ static bool linear_mfma_ok(const LinearArgs &a)
     return even && w_ok && a.K <= 32 * 18;
 }
 
-template <int KSM, int NTC> static hipError_t launch_linear_mfma_t(const LinearArgs &a, hipStream_t s)
+// `b` may be null: one map only
+template <int KSM, int NTC>
+static hipError_t launch_linear_mfma_t(const LinearArgs &a, const LinearArgs *b, int prof_id, hipStream_t s)
 {
-    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
-    const unsigned chunks = (unsigned)((nt + NTC - 1) / NTC);
-    const size_t lds = (size_t)NTC * ks * 1024;
+    const int nta = (a.N + 15) / 16, ksa = (a.K + 31) / 32;
+    const int ntb = b ? (b->N + 15) / 16 : 0, ksb = b ? (b->K + 31) / 32 : 0;
+    const unsigned chunks_a = (unsigned)((nta + NTC - 1) / NTC), chunks = chunks_a + (unsigned)((ntb + NTC - 1) / NTC);
+    const size_t lds = (size_t)NTC * (ksa > ksb ? ksa : ksb) * 1024;
     auto kern = linear_mfma_kernel<KSM, NTC>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
@@ -211,30 +220,37 @@ template <int KSM, int NTC> static hipError_t launch_linear_mfma_t(const LinearA
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const long ntile = (a.rows + 15) / 16;
+    const long rows = b && b->rows > a.rows ? b->rows : a.rows;
+    const long ntile = (rows + 15) / 16;
     // every workgroup builds its chunk's weight fragments first: with several chunks the rows are
     // spread over fewer, longer-running workgroups
-    long blocks = (ntile + 3) / 4, cap = (chunks == 1 ? 4L : 2L) * device_cus() / chunks;
+    long blocks = (ntile + 3) / 4, cap = (chunks <= 2 ? 4L : 2L) * device_cus() / chunks;
     if (cap < 1) cap = 1;
     if (blocks > cap) blocks = cap;
-    KernelTimer kt(a.prof_id, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks, chunks), dim3(kThreads), lds, s, a, ks);
+    KernelTimer kt(prof_id, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks, chunks), dim3(kThreads), lds, s, a, b ? *b : a, ksa, ksb,
+                       (int)chunks_a);
     return hipGetLastError();
 }
 
-static hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
+static hipError_t launch_linear_mfma(const LinearArgs &a, const LinearArgs *b, int prof_id, hipStream_t s)
 {
-    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
-    if (ks <= 2) return nt <= 4 ? launch_linear_mfma_t<2, 4>(a, s) : launch_linear_mfma_t<2, 8>(a, s);
-    if (ks <= 6) return launch_linear_mfma_t<6, 4>(a, s);
-    return launch_linear_mfma_t<18, 4>(a, s);
+    int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
+    if (b) {
+        const int ntb = (b->N + 15) / 16, ksb = (b->K + 31) / 32;
+        nt = ntb > nt ? ntb : nt;
+        ks = ksb > ks ? ksb : ks;
+    }
+    if (ks <= 2) return nt <= 4 ? launch_linear_mfma_t<2, 4>(a, b, prof_id, s) : launch_linear_mfma_t<2, 8>(a, b, prof_id, s);
+    if (ks <= 6) return launch_linear_mfma_t<6, 4>(a, b, prof_id, s);
+    return launch_linear_mfma_t<18, 4>(a, b, prof_id, s);
 }
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0) return hipSuccess;
     if constexpr (sizeof(T) == 2) {
-        if (linear_mfma_ok(a)) return launch_linear_mfma(a, s);
+        if (linear_mfma_ok(a)) return launch_linear_mfma(a, nullptr, a.prof_id, s);
     }
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
     KernelTimer kt(a.prof_id, s);
@@ -243,6 +259,18 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
 }
 template hipError_t launch_linear<float>(const LinearArgs &, hipStream_t);
 template hipError_t launch_linear<bf16_t>(const LinearArgs &, hipStream_t);
+
+template <typename T> hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, hipStream_t s)
+{
+    if constexpr (sizeof(T) == 2) {
+        if (a.rows > 0 && a.N > 0 && b.rows > 0 && b.N > 0 && linear_mfma_ok(a) && linear_mfma_ok(b))
+            return launch_linear_mfma(a, &b, K_LINEAR_PAIR, s);
+    }
+    hipError_t e = launch_linear<T>(a, s);
+    return e != hipSuccess ? e : launch_linear<T>(b, s);
+}
+template hipError_t launch_linear_pair<float>(const LinearArgs &, const LinearArgs &, hipStream_t);
+template hipError_t launch_linear_pair<bf16_t>(const LinearArgs &, const LinearArgs &, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // dw[n,k] += sum_t dout[t,n] (a1+a2)[t,k] ; db[n] += sum_t dout[t,n]
