@@ -177,7 +177,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     wp.a1 = attn; wp.lda1 = C;
     wp.dw = rep + o_wp; wp.db = rep + o_bp; wp.rep_stride = P; wp.reps = kGradReplicas;
     wp.rows = g.T; wp.N = C; wp.K = C; wp.prof_id = K_PROJ_WGRAD;
-    GSWA_HIP(launch_wgrad<T>(wp, st));
+    // (independent of everything else: enqueued together with the first group's weight gradient)
 
     for (int grp = G - 1; grp >= 0; --grp) {
         const T *wg = w_qkv + (size_t)grp * Rg * Cg;
@@ -222,7 +222,10 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         wq.db = rep + o_bq + (size_t)grp * Rg;
         wq.rep_stride = P; wq.reps = kGradReplicas;
         wq.rows = g.T; wq.N = Rg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
-        GSWA_HIP(launch_wgrad<T>(wq, st));
+        if (grp == G - 1)
+            GSWA_HIP(launch_wgrad_pair<T>(wq, wp, st));
+        else
+            GSWA_HIP(launch_wgrad<T>(wq, st));
     }
     ReplicaSum rs{};
     rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;

@@ -41,6 +41,8 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
 // Two maps that do not depend on each other, in one launch where the kernels allow it.
 template <typename T> hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, hipStream_t s);
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s);
+// Two reductions that do not depend on each other, in one launch where the kernels allow it.
+template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s);
 
 // Attention core of head group `grp` (Eq. 6 right-hand side): reads q|k|v [T, Rg] through the
 // shift/partition map, writes O into columns of attn_out [T, C] at the tokens' own positions.

@@ -351,16 +351,23 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
 // quarters are summed through LDS: one atomic add per output and workgroup.
 // ---------------------------------------------------------------------------------------
 constexpr int kWgradThreads = 1024;
-__global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs p, long rows_per_split)
+// One launch can serve two independent reductions: the splits of the second follow those of the
+// first along blockIdx.z (splits_a of them; no second one when gridDim.z == splits_a).
+__global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs pa, WgradArgs pb, long rps_a,
+                                                                   long rps_b, int splits_a)
 {
     __shared__ float red[3][4][20][64]; // [token quarter - 1][nw][accumulator][lane]
+    const bool second = (int)blockIdx.z >= splits_a;
+    const WgradArgs &p = second ? pb : pa;
+    const long rows_per_split = second ? rps_b : rps_a;
+    const int split = (int)blockIdx.z - (second ? splits_a : 0);
     const uint16_t *dout = static_cast<const uint16_t *>(p.dout);
     const uint16_t *a1 = static_cast<const uint16_t *>(p.a1);
     const uint16_t *a2 = static_cast<const uint16_t *>(p.a2);
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wave = tid >> 6, nw = wave & 3, tq = wave >> 2;
     const int n0 = blockIdx.x * 64 + 16 * nw, k0 = blockIdx.y * 64;
-    const long t_begin = (long)blockIdx.z * rows_per_split;
+    const long t_begin = (long)split * rows_per_split;
     long t_end = t_begin + rows_per_split;
     if (t_end > p.rows) t_end = p.rows;
     const int n = n0 + l16;
@@ -372,7 +379,7 @@ __global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs p, 
     f32x4 acc[4], bacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (n0 < p.N)
+    if (n0 < p.N && k0 < p.K)
         for (long t0 = t_begin + 32 * tq; t0 < t_end; t0 += 128) {
             uint32_t av[8], bv[4][8];
 #pragma unroll
@@ -410,7 +417,7 @@ __global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs p, 
         for (int j = 0; j < 4; ++j) red[tq - 1][nw][16 + j][lane] = bacc[j];
     }
     __syncthreads();
-    if (tq > 0 || n0 >= p.N) return;
+    if (tq > 0 || n0 >= p.N || k0 >= p.K) return;
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
 #pragma unroll
@@ -421,8 +428,8 @@ __global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs p, 
         for (int j = 0; j < 4; ++j) bacc[j] += red[r][nw][16 + j][lane];
     }
     // result tiles: column l16 = k, rows 4q + j = n
-    float *dw = p.dw + (long)(blockIdx.z % p.reps) * p.rep_stride;
-    float *db = p.db ? p.db + (long)(blockIdx.z % p.reps) * p.rep_stride : nullptr;
+    float *dw = p.dw + (long)(split % p.reps) * p.rep_stride;
+    float *db = p.db ? p.db + (long)(split % p.reps) * p.rep_stride : nullptr;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int nn = n0 + 4 * q + j;
@@ -436,24 +443,40 @@ __global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs p, 
     }
 }
 
-static hipError_t launch_wgrad_mfma(const WgradArgs &a, hipStream_t s)
+// token rows per split (a multiple of 128) and the number of splits for one reduction
+static void wgrad_splits(const WgradArgs &a, long *rps, long *splits)
 {
-    const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
+    const long tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
     // A wave waits for the loads of one 32-token step at a time (about 1.5 us under load) and every
     // split adds N*K atomic adds (about 60 per ns for the whole chip): the split count balances
     // rows / (128 * splits) steps per wave against splits * N * K adds.
-    long splits = (long)sqrt(700.0 * (double)a.rows / ((double)a.N * a.K));
+    long s_ = (long)sqrt(700.0 * (double)a.rows / ((double)a.N * a.K));
     const long max_splits = (a.rows + 127) / 128;
-    if (splits > max_splits) splits = max_splits;
-    const long resident = 2L * device_cus() / (long)(tn * tk); // all workgroups on the chip at once
-    if (splits > resident && resident >= 8) splits = resident;
-    if (splits < 1) splits = 1;
-    long rps = (a.rows + splits - 1) / splits;
-    rps = (rps + 127) / 128 * 128;
-    splits = (a.rows + rps - 1) / rps;
-    dim3 grid(tn, tk, (unsigned)splits);
+    if (s_ > max_splits) s_ = max_splits;
+    const long resident = 2L * device_cus() / (tn * tk); // all workgroups on the chip at once
+    if (s_ > resident && resident >= 8) s_ = resident;
+    if (s_ < 1) s_ = 1;
+    long r = (a.rows + s_ - 1) / s_;
+    r = (r + 127) / 128 * 128;
+    *rps = r;
+    *splits = (a.rows + r - 1) / r;
+}
+
+// `b` may be null: one reduction only
+static hipError_t launch_wgrad_mfma(const WgradArgs &a, const WgradArgs *b, hipStream_t s)
+{
+    long rps_a = 0, sp_a = 0, rps_b = 128, sp_b = 0;
+    wgrad_splits(a, &rps_a, &sp_a);
+    unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
+    if (b) {
+        wgrad_splits(*b, &rps_b, &sp_b);
+        const unsigned tnb = (b->N + 63) / 64, tkb = (b->K + 63) / 64;
+        tn = tnb > tn ? tnb : tn;
+        tk = tkb > tk ? tkb : tk;
+    }
+    dim3 grid(tn, tk, (unsigned)(sp_a + sp_b));
     KernelTimer kt(a.prof_id, s);
-    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kWgradThreads), 0, s, a, rps);
+    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kWgradThreads), 0, s, a, b ? *b : a, rps_a, rps_b, (int)sp_a);
     return hipGetLastError();
 }
 
@@ -461,7 +484,7 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
     if (a.reps < 1) return hipErrorInvalidValue;
-    if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, s);
+    if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, nullptr, s);
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
     long splits = 2048 / (long)(tn * tk);
     const long max_splits = (a.rows + 255) / 256;
@@ -477,6 +500,18 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 }
 template hipError_t launch_wgrad<float>(const WgradArgs &, hipStream_t);
 template hipError_t launch_wgrad<bf16_t>(const WgradArgs &, hipStream_t);
+
+template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s)
+{
+    if constexpr (sizeof(T) == 2) {
+        if (a.rows > 0 && a.N > 0 && a.K > 0 && b.rows > 0 && b.N > 0 && b.K > 0 && a.reps >= 1 && b.reps >= 1)
+            return launch_wgrad_mfma(a, &b, s);
+    }
+    hipError_t e = launch_wgrad<T>(a, s);
+    return e != hipSuccess ? e : launch_wgrad<T>(b, s);
+}
+template hipError_t launch_wgrad_pair<float>(const WgradArgs &, const WgradArgs &, hipStream_t);
+template hipError_t launch_wgrad_pair<bf16_t>(const WgradArgs &, const WgradArgs &, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // attention core, one block per (window, head of the group)
