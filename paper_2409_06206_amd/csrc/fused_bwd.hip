@@ -678,22 +678,41 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 #pragma unroll
             for (int j = 0; j < 4; ++j) mat[(16 * wv + l16) * MP + 16 * kt + 4 * q + j] = tblacc[hx][kt][j];
         __syncthreads();
-        if (tid < NTBL) {
-            // every (query row r, query column c) in a fixed trip count, so that the 64 reads are all
-            // in flight together; pairs whose key falls outside the window add zero
-            const int dr = tid / (2 * M - 1) - (M - 1), dc = tid % (2 * M - 1) - (M - 1);
-            float acc = 0.f;
+        {
+            // Four threads share the offsets (dr0, dc0), (dr0 - M, dc0), (dr0, dc0 - M), (dr0 - M, dc0 - M)
+            // with 0 <= dr0, dc0 < M: for every query (rn, cn) exactly one of the four has its key
+            // inside the window, key = ((rn - dr0) mod M, (cn - dc0) mod M), so the four entries take
+            // M*M terms together and each thread sums those of two query rows: 16 reads, all in
+            // flight together, the same for every thread.
+            const int grp4 = tid >> 2, part = tid & 3;
+            const int dr0 = grp4 >> 3, dc0 = grp4 & 7;
+            float a00 = 0.f, a01 = 0.f, a10 = 0.f, a11 = 0.f; // [row wrapped][column wrapped]
 #pragma unroll
-            for (int r = 0; r < M; ++r) {
-                const bool okr = r - dr >= 0 && r - dr < M;
+            for (int i = 0; i < 2; ++i) {
+                const int rn = 2 * part + i;
+                const bool wr = rn < dr0;
+                const int rm = (rn - dr0) & (M - 1);
+                float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-                for (int c = 0; c < M; ++c) {
-                    const bool ok = okr && c - dc >= 0 && c - dc < M;
-                    const float v = mat[ok ? (r * M + c) * MP + (r - dr) * M + (c - dc) : 0];
-                    acc += ok ? v : 0.f;
+                for (int cn = 0; cn < M; ++cn) {
+                    const bool wc = cn < dc0;
+                    const float v = mat[(rn * M + cn) * MP + rm * M + ((cn - dc0) & (M - 1))];
+                    s0 += wc ? 0.f : v;
+                    s1 += wc ? v : 0.f;
                 }
+                a00 += wr ? 0.f : s0;
+                a01 += wr ? 0.f : s1;
+                a10 += wr ? s0 : 0.f;
+                a11 += wr ? s1 : 0.f;
             }
-            mine[B::P_TBL + tid * HEADS + hd] = acc;
+            a00 += __shfl_xor(a00, 1); a01 += __shfl_xor(a01, 1); a10 += __shfl_xor(a10, 1); a11 += __shfl_xor(a11, 1);
+            a00 += __shfl_xor(a00, 2); a01 += __shfl_xor(a01, 2); a10 += __shfl_xor(a10, 2); a11 += __shfl_xor(a11, 2);
+            // thread `part` of the four writes entry `part`
+            const int e00 = (dr0 + M - 1) * (2 * M - 1) + dc0 + M - 1;
+            const float val = part == 0 ? a00 : part == 1 ? a01 : part == 2 ? a10 : a11;
+            const int e = e00 - ((part & 1) ? M : 0) - ((part & 2) ? M * (2 * M - 1) : 0);
+            const bool ok = !((part & 1) && dc0 == 0) && !((part & 2) && dr0 == 0);
+            if (ok) mine[B::P_TBL + e * HEADS + hd] = val;
         }
     }
 }
