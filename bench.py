@@ -22,7 +22,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # (profiles/fused_kernels_c2_groups2_hbm_counters.txt), valid only for the kernel source they
 # were taken on: {(workload, groups, kernel): (sha256 of the kernel source, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c2", 2, "fused_bwd"): ("376d7f12c17c0b32c3d35c70ef0c3552b1979a30cd12ab2781620f119b888a34", 77273088),
+    ("c2", 2, "fused_bwd"): ("a3f5f0820f6cecc9cfbef9ba8ed980ee493e726c011977065fa7f08e7bca7c6c", 77147699),
 }
 
 
