@@ -105,7 +105,7 @@ def profile_steps(layers, steps, backward=True):
                 "avg_us": 1e3 * v[0] / v[1]} for k, v in per.items()}, wall
 
 
-FORWARD_KERNELS = {"qkv_linear", "attn_fwd", "attn_core_fwd", "proj_linear", "fused_fwd", "fused_attn_fwd", "proj_gemm",
+FORWARD_KERNELS = {"qkv_linear", "attn_fwd", "attn_core_fwd", "window_fwd", "proj_linear", "fused_fwd", "fused_attn_fwd", "proj_gemm",
                    "pack_fwd"}
 
 

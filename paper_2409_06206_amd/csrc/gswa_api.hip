@@ -292,6 +292,12 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
                                         (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)attn, pack, st);
         return e == hipSuccess ? GSWA_OK : hip_fail(e);
     }
+    if (!(desc->flags & GSWA_FORCE_STAGED) && window_fwd_supported(g)) {
+        hipError_t e = launch_window_fwd(g, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
+                                         (const bf16_t *)w_proj, (const bf16_t *)b_proj,
+                                         (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, st);
+        return e == hipSuccess ? GSWA_OK : hip_fail(e);
+    }
     return forward_staged<bf16_t>(g, s, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
                                   (const bf16_t *)w_proj, (const bf16_t *)b_proj,
                                   (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)saved, (char *)ws, st);

@@ -26,6 +26,7 @@ enum KernelId {
     K_ATTN_CORE_FWD, // attention core of one group on the matrix cores
     K_ATTN_CORE_BWD, // its adjoint
     K_LINEAR_PAIR,  // backward of one group: q|k|v recomputation and dO in one launch
+    K_WINDOW_FWD,   // whole forward of a narrow layer with 64- or 144-token windows, one launch
     K_COUNT
 };
 

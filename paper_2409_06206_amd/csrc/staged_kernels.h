@@ -65,6 +65,13 @@ hipError_t launch_attn_core_fwd(const Geom &g, int grp, const bf16_t *qkv, const
 hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
                                 float *dtable, long rep_stride, int reps, hipStream_t s);
 
+// The whole forward of a narrow bf16 layer with 64- or 144-token windows in one launch (one
+// workgroup per window, all groups, output projection included); attn_out may be null (inference).
+bool window_fwd_supported(const Geom &g);
+hipError_t launch_window_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
+                             const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table, bf16_t *y,
+                             bf16_t *attn_out, hipStream_t s);
+
 // LDS bytes the two attention kernels need for this geometry, or 0 if no strip height fits.
 size_t attn_fwd_lds_bytes(const Geom &g, int *strip_rows);
 size_t attn_bwd_lds_bytes(const Geom &g, int *strip_rows);
