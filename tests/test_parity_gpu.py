@@ -246,6 +246,11 @@ AGILE_SMALL = [
     (1, 24, 24, 180, 6, 3, 12, 7, 32, "bf16", "stress"),
     (2, 16, 16, 42, 6, 2, 8, 3, 5, "bf16", "stress"),     # head width 7, 21 channels per group (odd row strides)
     (1, 24, 24, 18, 6, 2, 12, 6, 3, "bf16", "stress"),    # head width 3
+    (2, 24, 24, 60, 6, 1, 12, 6, 4, "bf16", "stress"),    # one group: two q/k tiles, four v tiles, two K steps
+    (1, 24, 36, 60, 6, 3, 12, 5, 4, "bf16", "stress"),
+    (1, 24, 24, 60, 6, 6, 12, 6, 8, "bf16", "stress"),    # one head per group
+    (2, 16, 16, 60, 4, 1, 8, 4, 8, "bf16", "stress"),
+    (1, 24, 24, 36, 6, 3, 12, 6, 6, "bf16", "init"),      # q/k as wide as v, spelled out
 ]
 
 
@@ -255,6 +260,20 @@ def test_narrow_query_key_and_window_12(oracle, B, H, W, C, heads, groups, windo
     parity.check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, regime=regime, dqk=dqk)
     parity.check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, regime=regime, dqk=dqk,
                cascade=False, seed=synth.LAYER_SEED0 + 3)
+
+
+def test_window_forward_inference_and_staged_forward_agree(oracle):
+    """12 x 12 windows, narrow q/k: the one-launch forward without a saved buffer gives the bits of the
+    training forward, and the one-kernel-per-step forward the same result within the tolerance."""
+    from paper_2409_06206_amd import gswa
+    shape = (2, 24, 24, 60, 4, 2, 12)
+    x, dy, p = parity.make_inputs(*shape, "bf16", synth.LAYER_SEED0, "stress", dqk=4)
+    a, _ = parity.gpu_results(x, dy, p, 4, 2, 12, 6, "bf16", backward=True, dqk=4)
+    b, _ = parity.gpu_results(x, dy, p, 4, 2, 12, 6, "bf16", backward=False, dqk=4)
+    c, _ = parity.gpu_results(x, dy, p, 4, 2, 12, 6, "bf16", backward=False, dqk=4,
+                              extra_flags=gswa.GSWA_FORCE_STAGED)
+    assert np.array_equal(a["y"], b["y"])
+    assert parity.rel_err(c["y"], a["y"].astype(np.float64)) <= parity.TOL["bf16"]
 
 
 def test_spelled_out_query_key_width_takes_the_same_path(oracle):
