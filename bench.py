@@ -174,7 +174,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--groups", type=int, default=2)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -191,7 +191,8 @@ def main():
     gswa.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    backward = not args.workload.startswith("c5")
+    from paper_2409_06206_amd import synth as _synth
+    backward = not (args.workload.startswith("c5") or _synth.CONFIGS[args.workload].get("forward_only"))
     if args.groups not in synth_groups(args.workload):
         sys.exit(f"groups={args.groups} is not one of the benchmark's values for {args.workload}")
     cfg, layers = build_case(args.workload, args.groups)
@@ -256,7 +257,7 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline and (args.workload == "c2" or args.workload.startswith("agile")):
+    if not args.no_cpu_baseline and backward and (args.workload == "c2" or args.workload.startswith("agile")):
         out["cpu_baseline"] = cpu_baseline(args.workload, args.groups)
     print(json.dumps(out))
 

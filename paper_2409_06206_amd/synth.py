@@ -111,6 +111,9 @@ CONFIGS.update({
                           layers=(0, 6), dtype="bf16"),
     "agile_h6_qk24": dict(B=32, H=48, W=48, C=60, heads=6, groups=(1, 2, 3, 6), window=12, dqk=4,
                           layers=(0, 6), dtype="bf16"),
+    # forward only on a large map, as at deployment (528 = 44 windows of 12)
+    "agile_infer": dict(B=1, H=528, W=528, C=60, heads=4, groups=(1, 2), window=12, dqk=4, layers=(6,),
+                        dtype="bf16", forward_only=True),
 })
 ACT_SEED = 0
 LAYER_SEED0 = 100
