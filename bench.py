@@ -184,7 +184,7 @@ def main():
                          "dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import torch
     from paper_2409_06206_amd import gswa

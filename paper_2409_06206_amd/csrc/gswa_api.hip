@@ -213,7 +213,6 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         lx.w = wg; lx.w_sn = 1; lx.w_sk = Cg;
         lx.out = dx + grp * Cg; lx.ldout = C;
         lx.rows = g.T; lx.N = Cg; lx.K = Rg; lx.prof_id = K_DX_LINEAR;
-        GSWA_HIP(launch_linear<T>(lx, st));
         WgradArgs wq{};
         wq.dout = dqkv; wq.lddout = Rg;
         wq.a1 = x + grp * Cg; wq.lda1 = C;
@@ -222,10 +221,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         wq.db = rep + o_bq + (size_t)grp * Rg;
         wq.rep_stride = P; wq.reps = kGradReplicas;
         wq.rows = g.T; wq.N = Rg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
-        if (grp == G - 1)
-            GSWA_HIP(launch_wgrad_pair<T>(wq, wp, st));
-        else
-            GSWA_HIP(launch_wgrad<T>(wq, st));
+        GSWA_HIP(launch_wgrad_group<T>(wq, grp == G - 1 ? &wp : nullptr, lx, st));
     }
     ReplicaSum rs{};
     rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;

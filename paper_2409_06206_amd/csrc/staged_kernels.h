@@ -41,8 +41,11 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
 // Two maps that do not depend on each other, in one launch where the kernels allow it.
 template <typename T> hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, hipStream_t s);
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s);
-// Two reductions that do not depend on each other, in one launch where the kernels allow it.
-template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s);
+// The tail of a group's backward: the weight-gradient reduction `a`, optionally a second independent
+// one (`b`, may be null) and the linear map `lin` (dF of the group), which all read the same
+// d(q|k|v): one launch where the kernels allow it.
+template <typename T>
+hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const LinearArgs &lin, hipStream_t s);
 
 // Attention core of head group `grp` (Eq. 6 right-hand side): reads q|k|v [T, Rg] through the
 // shift/partition map, writes O into columns of attn_out [T, C] at the tokens' own positions.

@@ -95,19 +95,16 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinearArgs p)
 // ---------------------------------------------------------------------------------------
 // One launch can serve two independent maps: the column chunks of the second follow those of the
 // first along blockIdx.y (chunks_a of them; the second map is absent when gridDim.y == chunks_a).
+// Body: `wl` = LDS for NTC*KS fragments; the workgroup (nthreads threads) is number `blk` of `nblk`
+// that share the rows of the column chunk starting at ncol0.
 template <int KSM, int NTC>
-__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, LinearArgs pb, int ksa, int ksb,
-                                                              int chunks_a)
+__device__ __forceinline__ void linear_mfma_body(const LinearArgs &p, int KS, int ncol0, uint4 *wl, int nthreads,
+                                                 long blk, long nblk)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
-    uint4 *wl = reinterpret_cast<uint4 *>(lsm); // [NTC][KS][64 lanes]
-    const bool second = (int)blockIdx.y >= chunks_a;
-    const LinearArgs &p = second ? pb : pa;
-    const int KS = second ? ksb : ksa;
     const uint16_t *w = static_cast<const uint16_t *>(p.w);
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
-    const int ncol0 = ((int)blockIdx.y - (second ? chunks_a : 0)) * (16 * NTC);
-    for (int i = tid; i < NTC * KS * 64; i += kThreads) {
+    const int nwaves = nthreads >> 6;
+    for (int i = tid; i < NTC * KS * 64; i += nthreads) {
         const int f = i >> 6, ln = i & 63;
         const int nt = f / KS, ks = f - nt * KS;
         const int n = ncol0 + 16 * nt + (ln & 15), k0 = 32 * ks + 8 * (ln >> 4);
@@ -134,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, Li
     const uint16_t *add = static_cast<const uint16_t *>(p.add);
     uint16_t *out = static_cast<uint16_t *>(p.out);
     const long ntile = (p.rows + 15) / 16;
-    for (long tile = (long)blockIdx.x * (kThreads / 64) + wave; tile < ntile; tile += (long)gridDim.x * (kThreads / 64)) {
+    for (long tile = blk * nwaves + wave; tile < ntile; tile += nblk * nwaves) {
         const long row = 16 * tile + l16;
         uint4 af[KSM];
 #pragma unroll
@@ -181,6 +178,17 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, Li
             }
         }
     }
+}
+
+template <int KSM, int NTC>
+__global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, LinearArgs pb, int ksa, int ksb,
+                                                              int chunks_a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
+    const bool second = (int)blockIdx.y >= chunks_a;
+    linear_mfma_body<KSM, NTC>(second ? pb : pa, second ? ksb : ksa,
+                               ((int)blockIdx.y - (second ? chunks_a : 0)) * (16 * NTC),
+                               reinterpret_cast<uint4 *>(lsm), kThreads, blockIdx.x, gridDim.x);
 }
 
 static int device_cus()
@@ -353,10 +361,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
 constexpr int kWgradThreads = 1024;
 // One launch can serve two independent reductions: the splits of the second follow those of the
 // first along blockIdx.z (splits_a of them; no second one when gridDim.z == splits_a).
+// Workgroups beyond the splits (blockIdx.z >= splits_all) serve an independent small linear map
+// (out features <= 64, K <= 64) that reads the same d(q|k|v) rows: dF of the group.
 __global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs pa, WgradArgs pb, long rps_a,
-                                                                   long rps_b, int splits_a)
+                                                                   long rps_b, int splits_a, int splits_all,
+                                                                   LinearArgs lin, int lin_ks)
 {
-    __shared__ float red[3][4][20][64]; // [token quarter - 1][nw][accumulator][lane]
+    __shared__ __attribute__((aligned(16))) float red[3][4][20][64]; // [token quarter - 1][nw][accumulator][lane]
+    if ((int)blockIdx.z >= splits_all) {
+        const long blk = ((long)(blockIdx.z - splits_all) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        const long nblk = (long)(gridDim.z - splits_all) * gridDim.y * gridDim.x;
+        linear_mfma_body<2, 4>(lin, lin_ks, 0, reinterpret_cast<uint4 *>(&red[0][0][0][0]), kWgradThreads, blk, nblk);
+        return;
+    }
     const bool second = (int)blockIdx.z >= splits_a;
     const WgradArgs &p = second ? pb : pa;
     const long rows_per_split = second ? rps_b : rps_a;
@@ -462,8 +479,8 @@ static void wgrad_splits(const WgradArgs &a, long *rps, long *splits)
     *splits = (a.rows + r - 1) / r;
 }
 
-// `b` may be null: one reduction only
-static hipError_t launch_wgrad_mfma(const WgradArgs &a, const WgradArgs *b, hipStream_t s)
+// `b` may be null: one reduction only; `lin` may be null: no linear map riding along
+static hipError_t launch_wgrad_mfma(const WgradArgs &a, const WgradArgs *b, const LinearArgs *lin, hipStream_t s)
 {
     long rps_a = 0, sp_a = 0, rps_b = 128, sp_b = 0;
     wgrad_splits(a, &rps_a, &sp_a);
@@ -474,9 +491,18 @@ static hipError_t launch_wgrad_mfma(const WgradArgs &a, const WgradArgs *b, hipS
         tn = tnb > tn ? tnb : tn;
         tk = tkb > tk ? tkb : tk;
     }
-    dim3 grid(tn, tk, (unsigned)(sp_a + sp_b));
+    // the linear map gets about one workgroup (16 waves, a 16-row tile each) per 64 row tiles
+    long lin_z = 0;
+    if (lin) {
+        const long want = ((lin->rows + 15) / 16 + 63) / 64;
+        lin_z = (want + tn * tk - 1) / (tn * tk);
+        if (lin_z < 1) lin_z = 1;
+    }
+    dim3 grid(tn, tk, (unsigned)(sp_a + sp_b + lin_z));
+    LinearArgs none{};
     KernelTimer kt(a.prof_id, s);
-    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kWgradThreads), 0, s, a, b ? *b : a, rps_a, rps_b, (int)sp_a);
+    hipLaunchKernelGGL(wgrad_mfma_kernel, grid, dim3(kWgradThreads), 0, s, a, b ? *b : a, rps_a, rps_b, (int)sp_a,
+                       (int)(sp_a + sp_b), lin ? *lin : none, lin ? (lin->K + 31) / 32 : 0);
     return hipGetLastError();
 }
 
@@ -484,7 +510,7 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
     if (a.reps < 1) return hipErrorInvalidValue;
-    if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, nullptr, s);
+    if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, nullptr, nullptr, s);
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
     long splits = 2048 / (long)(tn * tk);
     const long max_splits = (a.rows + 255) / 256;
@@ -501,17 +527,27 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 template hipError_t launch_wgrad<float>(const WgradArgs &, hipStream_t);
 template hipError_t launch_wgrad<bf16_t>(const WgradArgs &, hipStream_t);
 
-template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s)
+template <typename T>
+hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const LinearArgs &lin, hipStream_t s)
 {
     if constexpr (sizeof(T) == 2) {
-        if (a.rows > 0 && a.N > 0 && a.K > 0 && b.rows > 0 && b.N > 0 && b.K > 0 && a.reps >= 1 && b.reps >= 1)
-            return launch_wgrad_mfma(a, &b, s);
+        const bool wg_ok = a.rows > 0 && a.N > 0 && a.K > 0 && a.reps >= 1 &&
+                           (!b || (b->rows > 0 && b->N > 0 && b->K > 0 && b->reps >= 1));
+        const bool lin_ok = lin.rows > 0 && lin.N > 0 && lin.N <= 64 && lin.K <= 64 && linear_mfma_ok(lin);
+        if (wg_ok && lin_ok) return launch_wgrad_mfma(a, b, &lin, s);
+        if (wg_ok) {
+            hipError_t e = launch_linear<T>(lin, s);
+            return e != hipSuccess ? e : launch_wgrad_mfma(a, b, nullptr, s);
+        }
     }
-    hipError_t e = launch_wgrad<T>(a, s);
-    return e != hipSuccess ? e : launch_wgrad<T>(b, s);
+    hipError_t e = launch_linear<T>(lin, s);
+    if (e != hipSuccess) return e;
+    e = launch_wgrad<T>(a, s);
+    if (e != hipSuccess || !b) return e;
+    return launch_wgrad<T>(*b, s);
 }
-template hipError_t launch_wgrad_pair<float>(const WgradArgs &, const WgradArgs &, hipStream_t);
-template hipError_t launch_wgrad_pair<bf16_t>(const WgradArgs &, const WgradArgs &, hipStream_t);
+template hipError_t launch_wgrad_group<float>(const WgradArgs &, const WgradArgs *, const LinearArgs &, hipStream_t);
+template hipError_t launch_wgrad_group<bf16_t>(const WgradArgs &, const WgradArgs *, const LinearArgs &, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // attention core, one block per (window, head of the group)
