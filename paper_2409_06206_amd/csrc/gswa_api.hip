@@ -165,12 +165,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     const long P = (long)sz.params;
     const long o_wq = 0, o_bq = o_wq + (long)G * Rg * Cg, o_wp = o_bq + (long)G * Rg, o_bp = o_wp + (long)C * C;
     const long o_tb = o_bp + C;
-    {
-        ZeroList z{};
-        z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P;
-        z.count = 1;
-        GSWA_HIP(launch_fill_zero(z, st));
-    }
+    // (the copies are cleared by the first launch of the loop below)
     // adjoint of Eq. 7 with respect to the projection parameters
     WgradArgs wp{};
     wp.dout = dy; wp.lddout = C;
@@ -197,7 +192,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         if (grp < G - 1 && g.cascade) { lo.add = dx + (grp + 1) * Cg; lo.ldadd = C; }
         lo.out = dqkv + 2 * g.Qg; lo.ldout = Rg;
         lo.rows = g.T; lo.N = Cg; lo.K = C; lo.prof_id = K_DO_LINEAR;
-        GSWA_HIP(launch_linear_pair<T>(la, lo, st));
+        GSWA_HIP(launch_linear_pair<T>(la, lo, grp == G - 1 ? rep : nullptr, (size_t)kGradReplicas * P, st));
         bool on_matrix_cores = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (attn_core_mfma_supported(g)) {

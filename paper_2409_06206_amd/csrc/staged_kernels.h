@@ -38,8 +38,10 @@ struct WgradArgs {
 };
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);
-// Two maps that do not depend on each other, in one launch where the kernels allow it.
-template <typename T> hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, hipStream_t s);
+// Two maps that do not depend on each other, in one launch where the kernels allow it; `zero`
+// (may be null) is an fp32 array of nzero entries to be cleared by the same launch.
+template <typename T>
+hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, float *zero, size_t nzero, hipStream_t s);
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s);
 // The tail of a group's backward: the weight-gradient reduction `a`, optionally a second independent
 // one (`b`, may be null) and the linear map `lin` (dF of the group), which all read the same

@@ -180,11 +180,17 @@ __device__ __forceinline__ void linear_mfma_body(const LinearArgs &p, int KS, in
     }
 }
 
+// blockIdx.y beyond the chunks of both maps: zero fill of `zero` (nothing to do with the maps; it
+// saves the launch a separate fill kernel would take).
 template <int KSM, int NTC>
 __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, LinearArgs pb, int ksa, int ksb,
-                                                              int chunks_a)
+                                                              int chunks_a, int chunks_all, float *zero, long nzero)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
+    if ((int)blockIdx.y >= chunks_all) {
+        for (long i = (long)blockIdx.x * kThreads + threadIdx.x; i < nzero; i += (long)gridDim.x * kThreads) zero[i] = 0.f;
+        return;
+    }
     const bool second = (int)blockIdx.y >= chunks_a;
     linear_mfma_body<KSM, NTC>(second ? pb : pa, second ? ksb : ksa,
                                ((int)blockIdx.y - (second ? chunks_a : 0)) * (16 * NTC),
@@ -214,7 +220,8 @@ static bool linear_mfma_ok(const LinearArgs &a)
 
 // `b` may be null: one map only
 template <int KSM, int NTC>
-static hipError_t launch_linear_mfma_t(const LinearArgs &a, const LinearArgs *b, int prof_id, hipStream_t s)
+static hipError_t launch_linear_mfma_t(const LinearArgs &a, const LinearArgs *b, int prof_id, float *zero,
+                                       long nzero, hipStream_t s)
 {
     const int nta = (a.N + 15) / 16, ksa = (a.K + 31) / 32;
     const int ntb = b ? (b->N + 15) / 16 : 0, ksb = b ? (b->K + 31) / 32 : 0;
@@ -236,12 +243,13 @@ static hipError_t launch_linear_mfma_t(const LinearArgs &a, const LinearArgs *b,
     if (cap < 1) cap = 1;
     if (blocks > cap) blocks = cap;
     KernelTimer kt(prof_id, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks, chunks), dim3(kThreads), lds, s, a, b ? *b : a, ksa, ksb,
-                       (int)chunks_a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks, chunks + (zero && nzero > 0 ? 1 : 0)), dim3(kThreads), lds, s, a,
+                       b ? *b : a, ksa, ksb, (int)chunks_a, (int)chunks, zero, nzero);
     return hipGetLastError();
 }
 
-static hipError_t launch_linear_mfma(const LinearArgs &a, const LinearArgs *b, int prof_id, hipStream_t s)
+static hipError_t launch_linear_mfma(const LinearArgs &a, const LinearArgs *b, int prof_id, float *zero, long nzero,
+                                     hipStream_t s)
 {
     int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
     if (b) {
@@ -249,16 +257,17 @@ static hipError_t launch_linear_mfma(const LinearArgs &a, const LinearArgs *b, i
         nt = ntb > nt ? ntb : nt;
         ks = ksb > ks ? ksb : ks;
     }
-    if (ks <= 2) return nt <= 4 ? launch_linear_mfma_t<2, 4>(a, b, prof_id, s) : launch_linear_mfma_t<2, 8>(a, b, prof_id, s);
-    if (ks <= 6) return launch_linear_mfma_t<6, 4>(a, b, prof_id, s);
-    return launch_linear_mfma_t<18, 4>(a, b, prof_id, s);
+    if (ks <= 2) return nt <= 4 ? launch_linear_mfma_t<2, 4>(a, b, prof_id, zero, nzero, s)
+                                : launch_linear_mfma_t<2, 8>(a, b, prof_id, zero, nzero, s);
+    if (ks <= 6) return launch_linear_mfma_t<6, 4>(a, b, prof_id, zero, nzero, s);
+    return launch_linear_mfma_t<18, 4>(a, b, prof_id, zero, nzero, s);
 }
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0) return hipSuccess;
     if constexpr (sizeof(T) == 2) {
-        if (linear_mfma_ok(a)) return launch_linear_mfma(a, nullptr, a.prof_id, s);
+        if (linear_mfma_ok(a)) return launch_linear_mfma(a, nullptr, a.prof_id, nullptr, 0, s);
     }
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
     KernelTimer kt(a.prof_id, s);
@@ -268,17 +277,25 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
 template hipError_t launch_linear<float>(const LinearArgs &, hipStream_t);
 template hipError_t launch_linear<bf16_t>(const LinearArgs &, hipStream_t);
 
-template <typename T> hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, hipStream_t s)
+template <typename T>
+hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, float *zero, size_t nzero, hipStream_t s)
 {
     if constexpr (sizeof(T) == 2) {
         if (a.rows > 0 && a.N > 0 && b.rows > 0 && b.N > 0 && linear_mfma_ok(a) && linear_mfma_ok(b))
-            return launch_linear_mfma(a, &b, K_LINEAR_PAIR, s);
+            return launch_linear_mfma(a, &b, K_LINEAR_PAIR, zero, (long)nzero, s);
     }
-    hipError_t e = launch_linear<T>(a, s);
+    hipError_t e = hipSuccess;
+    if (zero && nzero > 0) {
+        ZeroList z{};
+        z.p[0] = zero; z.n[0] = nzero; z.count = 1;
+        e = launch_fill_zero(z, s);
+        if (e != hipSuccess) return e;
+    }
+    e = launch_linear<T>(a, s);
     return e != hipSuccess ? e : launch_linear<T>(b, s);
 }
-template hipError_t launch_linear_pair<float>(const LinearArgs &, const LinearArgs &, hipStream_t);
-template hipError_t launch_linear_pair<bf16_t>(const LinearArgs &, const LinearArgs &, hipStream_t);
+template hipError_t launch_linear_pair<float>(const LinearArgs &, const LinearArgs &, float *, size_t, hipStream_t);
+template hipError_t launch_linear_pair<bf16_t>(const LinearArgs &, const LinearArgs &, float *, size_t, hipStream_t);
 
 // ---------------------------------------------------------------------------------------
 // dw[n,k] += sum_t dout[t,n] (a1+a2)[t,k] ; db[n] += sum_t dout[t,n]
