@@ -140,6 +140,28 @@ def test_accumulate_flag_on_fused_path(oracle):
         assert parity.rel_err(got[k] - 0.5, 2.0 * want[k]) <= parity.TOL["bf16"], k
 
 
+def test_accumulate_flag_with_narrow_query_key(oracle):
+    """12 x 12 windows, narrow q/k (gradient copies summed at the end): two backward calls add twice."""
+    import torch
+    from paper_2409_06206_amd import gswa, runner
+    shape = (2, 24, 24, 60, 4, 2, 12)
+    x, dy, p = parity.make_inputs(*shape, "bf16", synth.LAYER_SEED0, "stress", dqk=4)
+    layer = runner.DeviceLayer(*shape, 6, "bf16", gswa.GSWA_ACCUM_WGRAD, dqk=4)
+    layer.set_params(p)
+    layer.set_inputs(x, dy)
+    for g in layer.grads.values():
+        g.fill_(0.25)
+    layer.forward()
+    layer.backward()
+    layer.backward()
+    torch.cuda.synchronize()
+    got = layer.results()
+    want = parity.oracle_results(oracle, x, dy, p, 4, 2, 12, 6, dqk=4)
+    for k in parity.GRAD_NAMES[1:]:
+        assert parity.rel_err(got[k] - 0.25, 2.0 * want[k]) <= parity.TOL["bf16"], k
+    assert parity.rel_err(got["dx"], want["dx"]) <= parity.TOL["bf16"]
+
+
 def test_fused_path_gradients_are_run_to_run_identical():
     """The fused backward sums per-workgroup partials in a fixed order: no atomics on outputs."""
     import torch
