@@ -40,6 +40,9 @@ def measured_traffic(workload, groups, kernel):
     return entry[1] if digest == entry[0] else None
 
 
+FLAGS = 0  # extra descriptor flags for every layer (--force-staged)
+
+
 def build_case(name, groups):
     import torch
     from paper_2409_06206_amd import runner, synth
@@ -48,7 +51,7 @@ def build_case(name, groups):
     layers = []
     for li, shift in enumerate(cfg["layers"]):
         L = runner.DeviceLayer(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
-                               cfg["window"], shift, cfg["dtype"], dqk=cfg.get("dqk", 0))
+                               cfg["window"], shift, cfg["dtype"], FLAGS, dqk=cfg.get("dqk", 0))
         L.set_params(synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"],
                                         synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)))
         layers.append(L)
@@ -177,6 +180,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
+    ap.add_argument("--force-staged", action="store_true",
+                    help="time the one-kernel-per-step path where a fused kernel exists")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-sweep", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -189,6 +194,9 @@ def main():
     import torch
     from paper_2409_06206_amd import gswa
     gswa.lib()
+    if args.force_staged:
+        global FLAGS
+        FLAGS = gswa.GSWA_FORCE_STAGED
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     from paper_2409_06206_amd import synth as _synth
