@@ -41,12 +41,15 @@ def measured_traffic(workload, groups, kernel):
 
 
 FLAGS = 0  # extra descriptor flags for every layer (--force-staged)
+BATCH = 0  # batch size override (--batch); 0 = the workload's own
 
 
 def build_case(name, groups):
     import torch
     from paper_2409_06206_amd import runner, synth
-    cfg = synth.CONFIGS[name]
+    cfg = dict(synth.CONFIGS[name])
+    if BATCH:
+        cfg["B"] = BATCH
     x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
     layers = []
     for li, shift in enumerate(cfg["layers"]):
@@ -143,7 +146,9 @@ def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
     """The CPU oracle, as it stands, on the same layer pair."""
     from oracle import gswa_oracle
     from paper_2409_06206_amd import synth
-    cfg = synth.CONFIGS[name]
+    cfg = dict(synth.CONFIGS[name])
+    if BATCH:
+        cfg["B"] = BATCH
     x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
     x = synth.quantize(x, cfg["dtype"])
     dy = synth.quantize(dy, cfg["dtype"])
@@ -180,6 +185,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="batch size other than the workload's own (a different workload: say so when quoting it)")
     ap.add_argument("--force-staged", action="store_true",
                     help="time the one-kernel-per-step path where a fused kernel exists")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -194,9 +201,10 @@ def main():
     import torch
     from paper_2409_06206_amd import gswa
     gswa.lib()
+    global FLAGS, BATCH
     if args.force_staged:
-        global FLAGS
         FLAGS = gswa.GSWA_FORCE_STAGED
+    BATCH = max(0, args.batch)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     from paper_2409_06206_amd import synth as _synth
