@@ -97,6 +97,11 @@ __global__ __launch_bounds__(kThreads) void linear_kernel(LinearArgs p)
 // first along blockIdx.y (chunks_a of them; the second map is absent when gridDim.y == chunks_a).
 // Body: `wl` = LDS for NTC*KS fragments; the workgroup (nthreads threads) is number `blk` of `nblk`
 // that share the rows of the column chunk starting at ncol0.
+// four consecutive dwords at dword alignment (the hardware reads them in one instruction)
+struct __attribute__((aligned(4))) dwords4 {
+    uint32_t v[4];
+};
+
 template <int KSM, int NTC>
 __device__ __forceinline__ void linear_mfma_body(const LinearArgs &p, int KS, int ncol0, uint4 *wl, int nthreads,
                                                  long blk, long nblk)
@@ -137,17 +142,30 @@ __device__ __forceinline__ void linear_mfma_body(const LinearArgs &p, int KS, in
 #pragma unroll
         for (int ks = 0; ks < KSM; ++ks) {
             uint32_t v[4] = {0u, 0u, 0u, 0u};
-            if (ks < KS) {
+            const int k0 = 32 * ks + 8 * q;
+            if (ks < KS && row < p.rows) {
+                if (k0 + 8 <= p.K) { // the lane's 8 channels as one 16-byte read (dword aligned)
+                    const dwords4 u = *reinterpret_cast<const dwords4 *>(a1 + ((row * p.lda1 + k0) >> 1));
 #pragma unroll
-                for (int dw = 0; dw < 4; ++dw) {
-                    const int k = 32 * ks + 8 * q + 2 * dw;
-                    if (row < p.rows && k < p.K) {
-                        uint32_t u = a1[(row * p.lda1 + k) >> 1];
-                        if (a2) {
-                            const uint32_t u2 = a2[(row * p.lda2 + k) >> 1];
-                            u = pack_bf16x2(bf16_lo(u) + bf16_lo(u2), bf16_hi(u) + bf16_hi(u2));
+                    for (int dw = 0; dw < 4; ++dw) v[dw] = u.v[dw];
+                    if (a2) {
+                        const dwords4 u2 = *reinterpret_cast<const dwords4 *>(a2 + ((row * p.lda2 + k0) >> 1));
+#pragma unroll
+                        for (int dw = 0; dw < 4; ++dw)
+                            v[dw] = pack_bf16x2(bf16_lo(v[dw]) + bf16_lo(u2.v[dw]), bf16_hi(v[dw]) + bf16_hi(u2.v[dw]));
+                    }
+                } else {
+#pragma unroll
+                    for (int dw = 0; dw < 4; ++dw) {
+                        const int k = k0 + 2 * dw;
+                        if (k < p.K) {
+                            uint32_t u = a1[(row * p.lda1 + k) >> 1];
+                            if (a2) {
+                                const uint32_t u2 = a2[(row * p.lda2 + k) >> 1];
+                                u = pack_bf16x2(bf16_lo(u) + bf16_lo(u2), bf16_hi(u) + bf16_hi(u2));
+                            }
+                            v[dw] = u;
                         }
-                        v[dw] = u;
                     }
                 }
             }
