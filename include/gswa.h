@@ -93,7 +93,8 @@ typedef struct gswa_desc {
  *                  then kept there for the duration of the call.
  *   *bwd_ws_bytes  scratch of gswa_backward.  Staged path: one group's q|k|v and its gradient, plus
  *                  16 fp32 copies of the five parameter gradients (workgroups spread their atomic
- *                  adds over the copies; one launch sums them at the end).
+ *                  adds over the copies; one launch sums them at the end) and, for bf16 layers with
+ *                  64- or 144-token windows, one bias-table gradient per window.
  *                  Fused path: one partial parameter-gradient vector per workgroup.
  * Which path serves a layer depends only on desc (shape, dtype, flags).
  * Any output pointer may be NULL.  All sizes are multiples of 256.

@@ -198,7 +198,7 @@ __global__ __launch_bounds__(64 * NT) void attn_core_fwd_kernel(Geom g, int grp,
 template <int NT, int ET, int KQ>
 __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp, const bf16_t *__restrict__ qkv,
                                                                bf16_t *dqkv, const bf16_t *__restrict__ table,
-                                                               float *dtable, long rep_stride, int reps)
+                                                               float *__restrict__ tpart)
 {
     using Cf = CoreCfg<NT, ET, KQ>;
     constexpr int N = Cf::N, NTH = Cf::NTHREADS, LK = Cf::LK, LV = Cf::LV, LT = Cf::LT;
@@ -223,7 +223,6 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
     const int d = g.d, dq = g.dq, Rg = g.Rg, Qg = g.Qg;
     const uint16_t *qkv16 = reinterpret_cast<const uint16_t *>(qkv);
     uint16_t *dqkv16 = reinterpret_cast<uint16_t *>(dqkv);
-    dtable += (long)(w % reps) * rep_stride; // this window's copy of the gradient
 
     stage_geometry<N, NTH>(g, w, hd, table, tb, koff, tok, tid);
     __syncthreads();
@@ -406,9 +405,9 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
                 if (c < d) o16[2 * Qg + hl * d + c] = f32_to_bf16_bits(dvt[es][j]);
             }
     }
-    // ---- bias-table gradient: dS of the whole window goes to LDS as an N x N matrix (over the
-    // operand arrays, which nobody reads any more) and is summed per coordinate offset
-    // (dr, dc) = query - key ----
+    // ---- bias-table gradient of this (window, head): dS of the whole window goes to LDS as an N x N
+    // matrix (over the operand arrays, which nobody reads any more) and is summed per coordinate
+    // offset (dr, dc) = query - key ----
     __syncthreads();
     uint16_t *DS = Qs; // [N][LT]: row = query, column = key
 #pragma unroll
@@ -445,7 +444,8 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
         const float val = part == 0 ? a00 : part == 1 ? a01 : part == 2 ? a10 : a11;
         const int e = e00 - ((part & 1) ? M : 0) - ((part & 2) ? M * nt1 : 0);
         const bool ok = !((part & 1) && dc0 == 0) && !((part & 2) && dr0 == 0);
-        if (ok) atomicAdd(&dtable[(long)e * g.heads + hd], val);
+        // every entry of this (window, head) is written exactly once: no atomics, no zero fill
+        if (ok) tpart[((long)w * ((2 * M - 1) * (2 * M - 1)) + e) * g.heads + hd] = val;
     }
 }
 
@@ -470,7 +470,7 @@ hipError_t launch_fwd(const Geom &g, int grp, const bf16_t *qkv, const bf16_t *t
 
 template <int NT, int ET, int KQ>
 hipError_t launch_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
-                      float *dtable, long rep_stride, int reps, hipStream_t s)
+                      float *tpart, hipStream_t s)
 {
     using Cf = CoreCfg<NT, ET, KQ>;
     const size_t lds = bwd_lds_bytes<Cf>(g.M);
@@ -483,8 +483,7 @@ hipError_t launch_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, c
         attr_done = true;
     }
     KernelTimer kt(K_ATTN_CORE_BWD, s);
-    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(Cf::NTHREADS), lds, s, g, grp, qkv, dqkv, table, dtable,
-                       rep_stride, reps);
+    hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(Cf::NTHREADS), lds, s, g, grp, qkv, dqkv, table, tpart);
     return hipGetLastError();
 }
 
@@ -511,12 +510,12 @@ hipError_t launch_attn_core_fwd(const Geom &g, int grp, const bf16_t *qkv, const
 }
 
 hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
-                                float *dtable, long rep_stride, int reps, hipStream_t s)
+                                float *tpart, hipStream_t s)
 {
-    if (!attn_core_mfma_supported(g) || reps < 1) return hipErrorInvalidValue;
+    if (!attn_core_mfma_supported(g) || !tpart) return hipErrorInvalidValue;
     const int nt = g.N / 16, et = (g.d + 15) / 16, kq = (g.dq + 15) / 16;
 #define X(NT_, ET_, KQ_) \
-    if (nt == NT_ && et == ET_ && kq == KQ_) return launch_bwd<NT_, ET_, KQ_>(g, grp, qkv, dqkv, table, dtable, rep_stride, reps, s);
+    if (nt == NT_ && et == ET_ && kq == KQ_) return launch_bwd<NT_, ET_, KQ_>(g, grp, qkv, dqkv, table, tpart, s);
     GSWA_CORE_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

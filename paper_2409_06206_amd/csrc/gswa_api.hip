@@ -77,6 +77,7 @@ struct Sizes {
     size_t pack;         // bytes of the packed parameters behind it (fused path)
     size_t fused_bwd_ws; // partial sums of the fused backward
     size_t params;       // fp32 entries of all five parameter gradients (one copy of the staged backward)
+    size_t reps, tpart;  // bytes of the gradient copies and of the per-window bias-table gradients
     bool fused_fwd, fused_bwd;
 };
 
@@ -94,7 +95,11 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.fwd_ws = s.qkv;
     s.params = (size_t)g.groups * g.Rg * g.Cg + (size_t)g.groups * g.Rg + (size_t)g.C * g.C + g.C +
                (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
-    s.bwd_ws = 2 * s.qkv + align256(kGradReplicas * s.params * sizeof(float));
+    // (+ one bias-table gradient per window where the attention adjoint runs on the matrix cores)
+    s.tpart = (d->dtype == GSWA_BF16 && attn_core_mfma_supported(g))
+                  ? align256((size_t)g.nW * (2 * g.M - 1) * (2 * g.M - 1) * g.heads * sizeof(float)) : 0;
+    s.reps = align256(kGradReplicas * s.params * sizeof(float));
+    s.bwd_ws = 2 * s.qkv + s.reps + s.tpart;
     s.fused_fwd = use_fused_fwd(d, g);
     s.fused_bwd = s.fused_fwd && fused_bwd_supported(g);
     s.fused_bwd_ws = 0;
@@ -162,6 +167,8 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     // the parameter gradients are accumulated in kGradReplicas copies behind the two q|k|v buffers
     // (layout of a copy: dw_qkv | db_qkv | dw_proj | db_proj | dtable) and summed at the end
     float *rep = reinterpret_cast<float *>(ws + 2 * sz.qkv);
+    float *tpart = reinterpret_cast<float *>(ws + 2 * sz.qkv + sz.reps);
+    bool table_per_window = false;
     const long P = (long)sz.params;
     const long o_wq = 0, o_bq = o_wq + (long)G * Rg * Cg, o_wp = o_bq + (long)G * Rg, o_bp = o_wp + (long)C * C;
     const long o_tb = o_bp + C;
@@ -196,7 +203,8 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         bool on_matrix_cores = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (attn_core_mfma_supported(g)) {
-                GSWA_HIP(launch_attn_core_bwd(g, grp, qkv, dqkv, table, rep + o_tb, P, kGradReplicas, st));
+                GSWA_HIP(launch_attn_core_bwd(g, grp, qkv, dqkv, table, tpart, st));
+                table_per_window = true;
                 on_matrix_cores = true;
             }
         }
@@ -224,8 +232,14 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     rs.out[1] = db_qkv; rs.off[1] = o_bq; rs.n[1] = (long)G * Rg;
     rs.out[2] = dw_proj; rs.off[2] = o_wp; rs.n[2] = (long)C * C;
     rs.out[3] = db_proj; rs.off[3] = o_bp; rs.n[3] = C;
-    rs.out[4] = dtable; rs.off[4] = o_tb; rs.n[4] = (long)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
-    rs.count = 5;
+    const long n_tb = (long)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
+    if (table_per_window) {
+        rs.count = 4;
+        rs.tpart = tpart; rs.t_out = dtable; rs.t_off = o_tb; rs.t_n = n_tb; rs.t_windows = g.nW;
+    } else {
+        rs.out[4] = dtable; rs.off[4] = o_tb; rs.n[4] = n_tb;
+        rs.count = 5;
+    }
     rs.accumulate = (flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
     GSWA_HIP(launch_reduce_replicas(rs, st));
     return GSWA_OK;

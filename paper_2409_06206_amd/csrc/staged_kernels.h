@@ -67,8 +67,11 @@ hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const 
 bool attn_core_mfma_supported(const Geom &g);
 hipError_t launch_attn_core_fwd(const Geom &g, int grp, const bf16_t *qkv, const bf16_t *table,
                                 bf16_t *attn_out, hipStream_t s);
+// Its bias-table gradient is not added anywhere: every (window, head) writes its own copy,
+// tpart[window][entry][head] (fp32, nW * (2M-1)^2 * heads entries, no zero fill needed), which
+// launch_reduce_replicas sums.
 hipError_t launch_attn_core_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, const bf16_t *table,
-                                float *dtable, long rep_stride, int reps, hipStream_t s);
+                                float *tpart, hipStream_t s);
 
 // The whole forward of a narrow bf16 layer with 64- or 144-token windows in one launch (one
 // workgroup per window, all groups, output projection included); attn_out may be null (inference).
@@ -99,6 +102,12 @@ struct ReplicaSum {
     long off[8], n[8];
     int count;
     int accumulate;
+    // optional: per-window copies of one more output (the bias-table gradient), summed on top of
+    // its `reps` copies at offset t_off: t_out[i] (+)= sum_w tpart[w * t_n + i] + copies
+    const float *tpart;
+    float *t_out;
+    long t_off, t_n;
+    int t_windows;
 };
 hipError_t launch_reduce_replicas(const ReplicaSum &r, hipStream_t s);
 

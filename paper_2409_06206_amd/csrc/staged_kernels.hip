@@ -920,6 +920,37 @@ hipError_t launch_fill_zero(const ZeroList &z, hipStream_t s)
 
 __global__ __launch_bounds__(256) void reduce_replicas_kernel(ReplicaSum r)
 {
+    if ((int)blockIdx.y == r.count) {
+        // the output with per-window copies: 32 entries per block, 8 slices of the windows
+        __shared__ float red[8][33];
+        const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
+        for (long i0 = (long)blockIdx.x * 32; i0 < r.t_n; i0 += (long)gridDim.x * 32) {
+            const long i = i0 + col;
+            float acc = 0.f;
+            if (i < r.t_n) {
+                // eight loads in flight per thread
+                float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                int w = slice;
+                for (; w + 56 < r.t_windows; w += 64) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) a8[u] += r.tpart[(long)(w + 8 * u) * r.t_n + i];
+                }
+                for (; w < r.t_windows; w += 8) a8[0] += r.tpart[(long)w * r.t_n + i];
+                acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+                for (int c = slice; c < r.reps; c += 8) acc += r.rep[(long)c * r.stride + r.t_off + i];
+            }
+            red[slice][col] = acc;
+            __syncthreads();
+            if (slice == 0 && i < r.t_n) {
+                float sum = 0.f;
+#pragma unroll
+                for (int k8 = 0; k8 < 8; ++k8) sum += red[k8][col];
+                r.t_out[i] = r.accumulate ? r.t_out[i] + sum : sum;
+            }
+            __syncthreads();
+        }
+        return;
+    }
     const int k = blockIdx.y;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < r.n[k]; i += (long)gridDim.x * blockDim.x) {
         float acc = 0.f;
@@ -934,9 +965,11 @@ hipError_t launch_reduce_replicas(const ReplicaSum &r, hipStream_t s)
     for (int k = 0; k < r.count; ++k) longest = r.n[k] > longest ? r.n[k] : longest;
     if (r.count <= 0 || longest == 0) return hipSuccess;
     unsigned blocks = (unsigned)((longest + 255) / 256);
+    const bool with_t = r.t_out && r.t_n > 0;
+    if (with_t && blocks < (unsigned)((r.t_n + 31) / 32)) blocks = (unsigned)((r.t_n + 31) / 32);
     if (blocks > 256) blocks = 256;
     KernelTimer kt(K_REDUCE, s);
-    hipLaunchKernelGGL(reduce_replicas_kernel, dim3(blocks, r.count), dim3(256), 0, s, r);
+    hipLaunchKernelGGL(reduce_replicas_kernel, dim3(blocks, r.count + (with_t ? 1 : 0)), dim3(256), 0, s, r);
     return hipGetLastError();
 }
 
