@@ -60,7 +60,7 @@ template <int N, int NTHREADS>
 __device__ __forceinline__ void stage_geometry(const Geom &g, int w, int hd, const bf16_t *table, float *tb,
                                                int *koff, int *tok, int tid)
 {
-    const int M = g.M, nt1 = 2 * M - 1, ntbl = nt1 * nt1;
+    constexpr int M = N == 64 ? 8 : 12, nt1 = 2 * M - 1, ntbl = nt1 * nt1; // N = M * M is 64 or 144
     for (int n = tid; n < N; n += NTHREADS) {
         int reg;
         tok[n] = (int)window_token(g, w, n, reg);
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(64 * NT) void attn_core_fwd_kernel(Geom g, int grp,
     using Cf = CoreCfg<NT, ET, KQ>;
     constexpr int N = Cf::N, NTH = Cf::NTHREADS, LK = Cf::LK, LT = Cf::LT;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int M = g.M, nt1 = 2 * M - 1;
+    constexpr int M = NT == 4 ? 8 : 12, nt1 = 2 * M - 1; // N = M * M is 64 or 144
     float *tb = reinterpret_cast<float *>(lds);
     int *koff = reinterpret_cast<int *>(lds + 4 * table_floats(M));
     int *tok = koff + N;
@@ -203,7 +203,8 @@ __global__ __launch_bounds__(64 * NT) void attn_core_bwd_kernel(Geom g, int grp,
     using Cf = CoreCfg<NT, ET, KQ>;
     constexpr int N = Cf::N, NTH = Cf::NTHREADS, LK = Cf::LK, LV = Cf::LV, LT = Cf::LT;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int M = g.M, nt1 = 2 * M - 1, tf = table_floats(M);
+    constexpr int M = NT == 4 ? 8 : 12, nt1 = 2 * M - 1; // N = M * M is 64 or 144
+    const int tf = table_floats(M);
     float *tb = reinterpret_cast<float *>(lds);
     int *koff = reinterpret_cast<int *>(tb + tf);
     int *tok = koff + N;

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(64 * NT) void window_fwd_kernel(Geom g, const bf16_
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int w = blockIdx.x;
-    const int M = g.M, nt1 = 2 * M - 1, ntbl = nt1 * nt1;
+    constexpr int M = NT == 4 ? 8 : 12, nt1 = 2 * M - 1, ntbl = nt1 * nt1; // N = M * M is 64 or 144
     const int C = g.C, Cg = g.Cg, Qg = g.Qg, Rg = g.Rg, d = g.d, dq = g.dq, hg = g.hg, G = g.groups;
     const uint16_t *x16 = reinterpret_cast<const uint16_t *>(x);
     const uint16_t *wq16 = reinterpret_cast<const uint16_t *>(w_qkv);
