@@ -58,6 +58,44 @@ def layer_params(C, heads, groups, window, seed, regime="init", dqk=0):
     return {k: v.astype(np.float32) for k, v in p.items()}
 
 
+def astl_param_shapes(C, heads, groups, window, hidden, dqk=0):
+    """Parameters of a whole layer (Eq. 4-5): two LayerNorms, the attention layer's five tensors and
+    the two fully connected layers of the MLP (``hidden`` features in between)."""
+    shp = {"ln1_w": (C,), "ln1_b": (C,)}
+    shp.update(param_shapes(C, heads, groups, window, dqk))
+    shp.update({"ln2_w": (C,), "ln2_b": (C,), "w_fc1": (hidden, C), "b_fc1": (hidden,),
+                "w_fc2": (C, hidden), "b_fc2": (C,)})
+    return shp
+
+
+def astl_params(C, heads, groups, window, hidden, seed, regime="init", dqk=0):
+    """fp32 parameters of a whole layer: the attention tensors as ``layer_params`` draws them from
+    ``seed``; then, from ``seed + 5000``, in the order w_fc1, w_fc2, b_fc1, b_fc2, ln1_w, ln1_b,
+    ln2_w, ln2_b: ``init`` has fc weights ~ N(0, 0.02^2), zero fc biases and identity LayerNorms
+    (gamma 1, beta 0); ``stress`` has fc weights ~ N(0, 1/fan_in), fc biases ~ N(0, 0.1^2),
+    gamma ~ 1 + N(0, 0.1^2), beta ~ N(0, 0.1^2), so that both branches are of the order of the
+    skip path and every parameter's gradient is visible."""
+    p = dict(layer_params(C, heads, groups, window, seed, regime, dqk))
+    rng = np.random.default_rng(seed + 5000)
+    if regime == "init":
+        q = {
+            "w_fc1": rng.normal(0.0, 0.02, (hidden, C)),
+            "w_fc2": rng.normal(0.0, 0.02, (C, hidden)),
+            "b_fc1": np.zeros(hidden), "b_fc2": np.zeros(C),
+            "ln1_w": np.ones(C), "ln1_b": np.zeros(C), "ln2_w": np.ones(C), "ln2_b": np.zeros(C),
+        }
+    else:
+        q = {
+            "w_fc1": rng.normal(0.0, C ** -0.5, (hidden, C)),
+            "w_fc2": rng.normal(0.0, hidden ** -0.5, (C, hidden)),
+            "b_fc1": rng.normal(0.0, 0.1, hidden), "b_fc2": rng.normal(0.0, 0.1, C),
+            "ln1_w": 1.0 + rng.normal(0.0, 0.1, C), "ln1_b": rng.normal(0.0, 0.1, C),
+            "ln2_w": 1.0 + rng.normal(0.0, 0.1, C), "ln2_b": rng.normal(0.0, 0.1, C),
+        }
+    p.update({k: v.astype(np.float32) for k, v in q.items()})
+    return p
+
+
 def activations(B, H, W, C, seed):
     """(x, dy) ~ N(0,1), fp32, drawn in that order."""
     rng = np.random.default_rng(seed)

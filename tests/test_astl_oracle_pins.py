@@ -1,0 +1,183 @@
+"""Pins of the whole-layer oracle (Eq. 4-5) to things other than itself: torch's CPU routines and
+autograd in fp64 for LayerNorm, GELU and the MLP half, tabulated values of the Gaussian CDF,
+closed forms, and central finite differences of the full layer (attention half included)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import astl_oracle, gswa_oracle
+from paper_2409_06206_amd import synth
+
+EPS = 1e-5
+
+
+def _params(C, heads, groups, window, hidden, seed=7, dqk=0, regime="stress"):
+    p = synth.astl_params(C, heads, groups, window, hidden, seed, regime, dqk)
+    return {k: v.astype(np.float64) for k, v in p.items()}
+
+
+def _acts(B, H, W, C, seed=3):
+    x, dy = synth.activations(B, H, W, C, seed)
+    return x.astype(np.float64), dy.astype(np.float64)
+
+
+def test_gelu_matches_tabulated_gaussian_cdf():
+    # Phi(1) = 0.8413447460685429, Phi(2) = 0.9772498680518208, Phi(-0.5) = 0.3085375387259869
+    t = np.array([0.0, 1.0, 2.0, -0.5])
+    want = t * np.array([0.5, 0.8413447460685429, 0.9772498680518208, 0.3085375387259869])
+    np.testing.assert_allclose(astl_oracle.gelu(t), want, rtol=0, atol=1e-15)
+    # GELU(t) - GELU(-t) = t, and far in the tails it is the identity resp. zero
+    u = np.linspace(-6, 6, 97)
+    np.testing.assert_allclose(astl_oracle.gelu(u) - astl_oracle.gelu(-u), u, atol=1e-14)
+    assert abs(astl_oracle.gelu(np.array([12.0]))[0] - 12.0) < 1e-14
+    assert abs(astl_oracle.gelu(np.array([-12.0]))[0]) < 1e-14
+
+
+def test_gelu_grad_is_the_derivative():
+    t = np.linspace(-4, 4, 41)
+    h = 1e-6
+    fd = (astl_oracle.gelu(t + h) - astl_oracle.gelu(t - h)) / (2 * h)
+    np.testing.assert_allclose(astl_oracle.gelu_grad(t), fd, atol=1e-9)
+    assert astl_oracle.gelu_grad(np.array([0.0]))[0] == 0.5
+
+
+def test_layer_norm_statistics_and_invariance():
+    rng = np.random.default_rng(1)
+    u = rng.normal(2.0, 3.0, (5, 7, 60))
+    one, zero = np.ones(60), np.zeros(60)
+    out, xhat, rstd = astl_oracle.layer_norm(u, one, zero, 0.0)
+    np.testing.assert_allclose(out.mean(-1), 0.0, atol=1e-14)
+    np.testing.assert_allclose((out ** 2).mean(-1), 1.0, atol=1e-13)
+    # shifting and scaling a token does not change its normalised value (eps = 0)
+    out2, _, _ = astl_oracle.layer_norm(4.0 * u - 11.0, one, zero, 0.0)
+    np.testing.assert_allclose(out2, out, atol=1e-12)
+    # a two-channel token normalises to (-1, +1) whatever its values
+    o2, _, _ = astl_oracle.layer_norm(np.array([[3.0, 8.0]]), np.ones(2), np.zeros(2), 0.0)
+    np.testing.assert_allclose(o2, [[-1.0, 1.0]], atol=1e-15)
+    # eps enters under the root: a constant token has variance 0 and maps to beta
+    g, b = rng.normal(size=60), rng.normal(size=60)
+    oc, _, rs = astl_oracle.layer_norm(np.full((1, 60), 5.0), g, b, 0.25)
+    np.testing.assert_allclose(oc[0], b, atol=1e-15)
+    assert rs[0, 0] == 2.0
+
+
+def test_layer_norm_against_torch_cpu():
+    rng = np.random.default_rng(2)
+    u = rng.normal(0.5, 2.0, (3, 4, 4, 60))
+    g, b = 1 + 0.3 * rng.normal(size=60), rng.normal(size=60)
+    dout = rng.normal(size=u.shape)
+    tu = torch.tensor(u, requires_grad=True)
+    tg, tb = torch.tensor(g, requires_grad=True), torch.tensor(b, requires_grad=True)
+    tout = torch.nn.functional.layer_norm(tu, (60,), tg, tb, EPS)
+    tout.backward(torch.tensor(dout))
+    out, xhat, rstd = astl_oracle.layer_norm(u, g, b, EPS)
+    du, dg, db = astl_oracle.layer_norm_backward(dout, xhat, rstd, g)
+    np.testing.assert_allclose(out, tout.detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(du, tu.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(dg, tg.grad.numpy(), atol=1e-11)
+    np.testing.assert_allclose(db, tb.grad.numpy(), atol=1e-11)
+
+
+def _torch_mlp_half(x1, p, dy):
+    """y = MLP(LN_2(x1)) + x1 with torch's own CPU routines, and its autograd gradients."""
+    t = {k: torch.tensor(p[k], requires_grad=True) for k in ("ln2_w", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")}
+    tx = torch.tensor(x1, requires_grad=True)
+    C = x1.shape[-1]
+    u = torch.nn.functional.layer_norm(tx, (C,), t["ln2_w"], t["ln2_b"], EPS)
+    h = torch.nn.functional.gelu(torch.nn.functional.linear(u, t["w_fc1"], t["b_fc1"]))
+    y = torch.nn.functional.linear(h, t["w_fc2"], t["b_fc2"]) + tx
+    y.backward(torch.tensor(dy))
+    return y.detach().numpy(), tx.grad.numpy(), {k: v.grad.numpy() for k, v in t.items()}
+
+
+@pytest.mark.parametrize("C,hidden", [(60, 120), (12, 30), (180, 360)])
+def test_mlp_half_against_torch_cpu(C, hidden):
+    p = _params(C, 6, 2, 4, hidden)
+    x1, dy = _acts(2, 4, 4, C)
+    want_y, want_dx, want_g = _torch_mlp_half(x1, p, dy)
+    x1n, xhat, rstd = astl_oracle.layer_norm(x1, p["ln2_w"], p["ln2_b"], EPS)
+    m, pre, h = astl_oracle.mlp(x1n, p["w_fc1"], p["b_fc1"], p["w_fc2"], p["b_fc2"])
+    np.testing.assert_allclose(m + x1, want_y, atol=1e-12)
+    dx1n, dw1, db1, dw2, db2 = astl_oracle.mlp_backward(dy, x1n, pre, h, p["w_fc1"], p["w_fc2"])
+    dx1, dg, db = astl_oracle.layer_norm_backward(dx1n, xhat, rstd, p["ln2_w"])
+    np.testing.assert_allclose(dx1 + dy, want_dx, atol=1e-11)
+    got = {"ln2_w": dg, "ln2_b": db, "w_fc1": dw1, "b_fc1": db1, "w_fc2": dw2, "b_fc2": db2}
+    for k, v in got.items():
+        np.testing.assert_allclose(v, want_g[k], atol=1e-10, err_msg=k)
+
+
+def test_whole_layer_is_the_composition_with_the_attention_oracle_and_torch():
+    """Eq. 4 then Eq. 5: the attention layer on torch's LayerNorm of x, plus x, then torch's MLP half."""
+    C, heads, groups, window, hidden = 24, 4, 2, 4, 40
+    p = _params(C, heads, groups, window, hidden)
+    x, dy = _acts(2, 8, 8, C)
+    kw = dict(heads=heads, groups=groups, window=window, shift=2)
+    xn = torch.nn.functional.layer_norm(torch.tensor(x), (C,), torch.tensor(p["ln1_w"]),
+                                        torch.tensor(p["ln1_b"]), EPS).numpy()
+    x1 = gswa_oracle.forward(xn, p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"], **kw) + x
+    want_y, _, _ = _torch_mlp_half(x1, p, dy)
+    y, mid = astl_oracle.forward(x, p, eps=EPS, want_mid=True, **kw)
+    np.testing.assert_allclose(mid, x1, atol=1e-12)
+    np.testing.assert_allclose(y, want_y, atol=1e-12)
+
+
+def test_closed_forms():
+    C, heads, groups, window, hidden = 24, 4, 2, 4, 48
+    p = _params(C, heads, groups, window, hidden)
+    x, dy = _acts(1, 8, 8, C)
+    kw = dict(heads=heads, groups=groups, window=window, shift=0, eps=EPS)
+    # zero second fc layer: Eq. 5 adds nothing, y is x1 = GSWA(LN(x)) + x
+    q = dict(p, w_fc2=np.zeros_like(p["w_fc2"]), b_fc2=np.zeros_like(p["b_fc2"]))
+    y, x1 = astl_oracle.forward(x, q, want_mid=True, **kw)
+    np.testing.assert_array_equal(y, x1)
+    dx, g = astl_oracle.backward(x, dy, q, **kw)
+    assert np.all(g["w_fc1"] == 0) and np.all(g["b_fc1"] == 0) and np.all(g["ln2_w"] == 0)
+    np.testing.assert_allclose(g["b_fc2"], dy.reshape(-1, C).sum(0), atol=1e-12)
+    # zero gamma_1 and beta_1: the attention layer sees zeros, so x1 - x is the same row for every
+    # token of the unshifted map (a softmax average of one value vector, projected), and x gets no
+    # gradient through the attention branch
+    q = dict(p, ln1_w=np.zeros(C), ln1_b=np.zeros(C), w_fc2=np.zeros_like(p["w_fc2"]),
+             b_fc2=np.zeros_like(p["b_fc2"]))
+    y = astl_oracle.forward(x, q, **kw)
+    row = (y - x).reshape(-1, C)
+    np.testing.assert_allclose(row, np.broadcast_to(row[0], row.shape), atol=1e-13)
+    dx, g = astl_oracle.backward(x, dy, q, **kw)
+    np.testing.assert_allclose(dx, dy, atol=1e-13)
+
+
+FD_CASES = [
+    dict(B=1, H=8, W=8, C=12, heads=2, groups=2, window=4, shift=2, hidden=20, dqk=0),
+    dict(B=2, H=4, W=8, C=12, heads=4, groups=1, window=4, shift=0, hidden=24, dqk=2),
+]
+
+
+@pytest.mark.parametrize("case", FD_CASES)
+def test_gradients_by_central_differences(case):
+    c = dict(case)
+    B, H, W, C, hidden = c.pop("B"), c.pop("H"), c.pop("W"), c.pop("C"), c.pop("hidden")
+    p = _params(C, c["heads"], c["groups"], c["window"], hidden, dqk=c["dqk"])
+    x, dy = _acts(B, H, W, C)
+    dx, g = astl_oracle.backward(x, dy, p, eps=EPS, **c)
+
+    def loss(xv, pv):
+        return float((astl_oracle.forward(xv, pv, eps=EPS, **c) * dy).sum())
+
+    rng = np.random.default_rng(11)
+    h = 1e-5
+    tensors = {"x": (x, dx)}
+    tensors.update({k: (p[k], g[k]) for k in astl_oracle.PARAM_NAMES})
+    for name, (val, grad) in tensors.items():
+        assert grad.shape == val.shape, name
+        flat = val.reshape(-1)
+        for idx in rng.choice(flat.size, size=min(6, flat.size), replace=False):
+            keep = flat[idx]
+            flat[idx] = keep + h
+            up = loss(x, p)
+            flat[idx] = keep - h
+            dn = loss(x, p)
+            flat[idx] = keep
+            fd = (up - dn) / (2 * h)
+            an = grad.reshape(-1)[idx]
+            assert math.isclose(fd, an, rel_tol=2e-6, abs_tol=2e-7), (name, idx, fd, an)
