@@ -1,0 +1,581 @@
+// One whole Agile Swin Transformer Layer (Sec. "Agile Swin Transformer Block", Eq. 4-5) around
+// the GSWA layer: LayerNorm, skip connections and the two-layer MLP, plus the C ABI of astl.h.
+// This file holds the per-token kernels (LayerNorm and its adjoint, GELU and its derivative) and
+// the order in which the steps are enqueued; the matrix products are the library's linear-map
+// and weight-gradient kernels.
+#include "../../include/astl.h"
+#include "common.h"
+#include "staged_kernels.h"
+#include "astl_mlp.h"
+
+#include <type_traits>
+
+namespace gswa {
+
+namespace {
+
+constexpr int kLnThreads = 256;
+constexpr int kLnMaxBlocks = 1024;
+
+// A token's row of C channels is held by 16 lanes: lane l of the 16 owns channels
+// V * (16 p + l) + i, p < P, i < V (V = 4 where C is a multiple of 4: one 8- or 16-byte access).
+template <typename T, int V> struct Vec;
+template <> struct Vec<float, 4> { float4 v; };
+template <> struct Vec<float, 1> { float v; };
+template <> struct Vec<bf16_t, 4> { uint2 v; };
+template <> struct Vec<bf16_t, 1> { uint16_t v; };
+
+__device__ __forceinline__ void unpack(const Vec<float, 4> &r, float *f) { f[0] = r.v.x; f[1] = r.v.y; f[2] = r.v.z; f[3] = r.v.w; }
+__device__ __forceinline__ void unpack(const Vec<float, 1> &r, float *f) { f[0] = r.v; }
+__device__ __forceinline__ void unpack(const Vec<bf16_t, 4> &r, float *f)
+{
+    f[0] = __uint_as_float(r.v.x << 16); f[1] = __uint_as_float(r.v.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.v.y << 16); f[3] = __uint_as_float(r.v.y & 0xffff0000u);
+}
+__device__ __forceinline__ void unpack(const Vec<bf16_t, 1> &r, float *f) { f[0] = __uint_as_float((uint32_t)r.v << 16); }
+__device__ __forceinline__ void pack(Vec<float, 4> &r, const float *f) { r.v = make_float4(f[0], f[1], f[2], f[3]); }
+__device__ __forceinline__ void pack(Vec<float, 1> &r, const float *f) { r.v = f[0]; }
+__device__ __forceinline__ void pack(Vec<bf16_t, 4> &r, const float *f)
+{
+    r.v.x = (uint32_t)f32_to_bf16_bits(f[0]) | (uint32_t)f32_to_bf16_bits(f[1]) << 16;
+    r.v.y = (uint32_t)f32_to_bf16_bits(f[2]) | (uint32_t)f32_to_bf16_bits(f[3]) << 16;
+}
+__device__ __forceinline__ void pack(Vec<bf16_t, 1> &r, const float *f) { r.v = f32_to_bf16_bits(f[0]); }
+
+// value the storage type keeps for f
+template <typename T> __device__ __forceinline__ float stored(float f)
+{
+    if constexpr (sizeof(T) == 2) return __uint_as_float((uint32_t)f32_to_bf16_bits(f) << 16);
+    return f;
+}
+
+template <typename T, int V, int P>
+__device__ __forceinline__ void load_row(const T *row, int C, int l16, float (&f)[P * V])
+{
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int c = V * (16 * p + l16);
+        if (c < C) {
+            unpack(*reinterpret_cast<const Vec<T, V> *>(row + c), &f[p * V]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) f[p * V + i] = 0.f;
+        }
+    }
+}
+
+template <typename T, int V, int P>
+__device__ __forceinline__ void store_row(T *row, int C, int l16, const float (&f)[P * V])
+{
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int c = V * (16 * p + l16);
+        if (c < C) pack(*reinterpret_cast<Vec<T, V> *>(row + c), &f[p * V]);
+    }
+}
+
+// sum over the 16 lanes that share a token
+__device__ __forceinline__ float sum16(float v)
+{
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8);
+    return v;
+}
+
+// mean and 1/sqrt(var + eps) of a token held by 16 lanes (channels beyond C are zero in f)
+template <int V, int P>
+__device__ __forceinline__ void row_stats(const float (&f)[P * V], int C, int l16, float eps, float &mean, float &rstd)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < P * V; ++k) s += f[k];
+    mean = sum16(s) / (float)C;
+    float q = 0.f;
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float dlt = f[p * V + i] - mean;
+            q += (V * (16 * p + l16) + i < C) ? dlt * dlt : 0.f;
+        }
+    rstd = rsqrtf(sum16(q) / (float)C + eps);
+}
+
+struct LnArgs {
+    const void *u;      // [rows, C] input of the LayerNorm ...
+    const void *add;    // ... plus this (may be null): Eq. 4's skip, u + add is what gets normalised
+    const void *gamma, *beta;
+    void *sum_out;      // u + add in the storage type (may be null)
+    void *out;          // LN(u + add)
+    long rows;
+    int C;
+    float eps;
+};
+
+// LayerNorm of every token (Eq. 4-5).  With `add` the normalised value is the stored (rounded)
+// sum, which is also what the backward pass will read back.
+template <typename T, int V, int P>
+__global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(LnArgs a)
+{
+    const int l16 = threadIdx.x & 15;
+    const long stride = (long)gridDim.x * (kLnThreads / 16);
+    const T *u = static_cast<const T *>(a.u), *add = static_cast<const T *>(a.add);
+    float g[P * V], b[P * V];
+    load_row<T, V, P>(static_cast<const T *>(a.gamma), a.C, l16, g);
+    load_row<T, V, P>(static_cast<const T *>(a.beta), a.C, l16, b);
+    for (long t = (long)blockIdx.x * (kLnThreads / 16) + (threadIdx.x >> 4); t < a.rows; t += stride) {
+        float f[P * V];
+        load_row<T, V, P>(u + t * a.C, a.C, l16, f);
+        if (add) {
+            float f2[P * V];
+            load_row<T, V, P>(add + t * a.C, a.C, l16, f2);
+#pragma unroll
+            for (int k = 0; k < P * V; ++k) f[k] = stored<T>(f[k] + f2[k]);
+            if (a.sum_out) store_row<T, V, P>(static_cast<T *>(a.sum_out) + t * a.C, a.C, l16, f);
+        }
+        float mean, rstd;
+        row_stats<V, P>(f, a.C, l16, a.eps, mean, rstd);
+#pragma unroll
+        for (int k = 0; k < P * V; ++k) f[k] = (f[k] - mean) * rstd * g[k] + b[k];
+        store_row<T, V, P>(static_cast<T *>(a.out) + t * a.C, a.C, l16, f);
+    }
+}
+
+struct LnBwdArgs {
+    const void *u;      // [rows, C] input the LayerNorm saw
+    const void *dout;   // gradient with respect to the LayerNorm's output
+    const void *res;    // gradient arriving over the skip connection, added to du (may be null)
+    const void *gamma;
+    void *du;           // [rows, C]
+    float *dgamma, *dbeta; // copy 0 of `reps` copies rep_stride floats apart, added into
+    long rep_stride;
+    int reps;
+    long rows;
+    int C;
+    float eps;
+};
+
+// Adjoint of LayerNorm: with xh = (u - mean) rstd and g = dout * gamma,
+//   du = rstd (g - mean(g) - xh mean(g xh)) (+ res);  dgamma = sum_t dout xh;  dbeta = sum_t dout.
+template <typename T, int V, int P>
+__global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(LnBwdArgs a)
+{
+    __shared__ float red[kLnThreads / 64][2][16 * P * V];
+    const int l16 = threadIdx.x & 15, wave = threadIdx.x >> 6;
+    const long stride = (long)gridDim.x * (kLnThreads / 16);
+    const T *u = static_cast<const T *>(a.u), *dout = static_cast<const T *>(a.dout);
+    const T *res = static_cast<const T *>(a.res);
+    float g[P * V], ag[P * V], ab[P * V];
+    load_row<T, V, P>(static_cast<const T *>(a.gamma), a.C, l16, g);
+#pragma unroll
+    for (int k = 0; k < P * V; ++k) ag[k] = ab[k] = 0.f;
+    for (long t = (long)blockIdx.x * (kLnThreads / 16) + (threadIdx.x >> 4); t < a.rows; t += stride) {
+        float f[P * V], d[P * V];
+        load_row<T, V, P>(u + t * a.C, a.C, l16, f);
+        load_row<T, V, P>(dout + t * a.C, a.C, l16, d);
+        float mean, rstd;
+        row_stats<V, P>(f, a.C, l16, a.eps, mean, rstd);
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const int k = p * V + i;
+                const bool in = V * (16 * p + l16) + i < a.C;
+                f[k] = in ? (f[k] - mean) * rstd : 0.f; // xh
+                ag[k] += d[k] * f[k];
+                ab[k] += d[k];
+                d[k] *= g[k];
+                s1 += d[k];
+                s2 += d[k] * f[k];
+            }
+        s1 = sum16(s1) / (float)a.C;
+        s2 = sum16(s2) / (float)a.C;
+#pragma unroll
+        for (int k = 0; k < P * V; ++k) d[k] = rstd * (d[k] - s1 - f[k] * s2);
+        if (res) {
+            float r[P * V];
+            load_row<T, V, P>(res + t * a.C, a.C, l16, r);
+#pragma unroll
+            for (int k = 0; k < P * V; ++k) d[k] += r[k];
+        }
+        store_row<T, V, P>(static_cast<T *>(a.du) + t * a.C, a.C, l16, d);
+    }
+    // the four tokens of a wave, then the waves of the workgroup, then one add per channel
+#pragma unroll
+    for (int k = 0; k < P * V; ++k) {
+        ag[k] += __shfl_xor(ag[k], 16); ag[k] += __shfl_xor(ag[k], 32);
+        ab[k] += __shfl_xor(ab[k], 16); ab[k] += __shfl_xor(ab[k], 32);
+    }
+    if ((threadIdx.x & 63) < 16) {
+#pragma unroll
+        for (int k = 0; k < P * V; ++k) {
+            red[wave][0][k * 16 + l16] = ag[k];
+            red[wave][1][k * 16 + l16] = ab[k];
+        }
+    }
+    __syncthreads();
+    const int rep = (int)(blockIdx.x % (unsigned)a.reps);
+    for (int e = threadIdx.x; e < 2 * 16 * P * V; e += kLnThreads) {
+        const int which = e / (16 * P * V), r = e % (16 * P * V);
+        const int k = r / 16, l = r % 16, p = k / V, i = k % V;
+        const int c = V * (16 * p + l) + i;
+        if (c >= a.C) continue;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kLnThreads / 64; ++w) s += red[w][which][r];
+        atomicAdd((which ? a.dbeta : a.dgamma) + (long)rep * a.rep_stride + c, s);
+    }
+}
+
+unsigned ln_blocks(long rows)
+{
+    long b = (rows + kLnThreads / 16 - 1) / (kLnThreads / 16);
+    return (unsigned)(b > kLnMaxBlocks ? kLnMaxBlocks : (b < 1 ? 1 : b));
+}
+
+template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, hipStream_t s)
+{
+    const int P = (a.C + 16 * V - 1) / (16 * V);
+    KernelTimer kt(K_LN_FWD, s);
+    const dim3 grid(ln_blocks(a.rows)), block(kLnThreads);
+    if constexpr (V == 4) {
+        switch (P) {
+        case 1: hipLaunchKernelGGL((ln_fwd_kernel<T, 4, 1>), grid, block, 0, s, a); break;
+        case 2: hipLaunchKernelGGL((ln_fwd_kernel<T, 4, 2>), grid, block, 0, s, a); break;
+        case 3: hipLaunchKernelGGL((ln_fwd_kernel<T, 4, 3>), grid, block, 0, s, a); break;
+        default: hipLaunchKernelGGL((ln_fwd_kernel<T, 4, 4>), grid, block, 0, s, a); break;
+        }
+    } else {
+        if (P <= 4) hipLaunchKernelGGL((ln_fwd_kernel<T, 1, 4>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((ln_fwd_kernel<T, 1, 16>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename T> hipError_t launch_ln_fwd(const LnArgs &a, hipStream_t s)
+{
+    return (a.C % 4 == 0) ? launch_ln_fwd_v<T, 4>(a, s) : launch_ln_fwd_v<T, 1>(a, s);
+}
+
+template <typename T, int V> hipError_t launch_ln_bwd_v(const LnBwdArgs &a, hipStream_t s)
+{
+    const int P = (a.C + 16 * V - 1) / (16 * V);
+    KernelTimer kt(K_LN_BWD, s);
+    const dim3 grid(ln_blocks(a.rows)), block(kLnThreads);
+    if constexpr (V == 4) {
+        switch (P) {
+        case 1: hipLaunchKernelGGL((ln_bwd_kernel<T, 4, 1>), grid, block, 0, s, a); break;
+        case 2: hipLaunchKernelGGL((ln_bwd_kernel<T, 4, 2>), grid, block, 0, s, a); break;
+        case 3: hipLaunchKernelGGL((ln_bwd_kernel<T, 4, 3>), grid, block, 0, s, a); break;
+        default: hipLaunchKernelGGL((ln_bwd_kernel<T, 4, 4>), grid, block, 0, s, a); break;
+        }
+    } else {
+        if (P <= 4) hipLaunchKernelGGL((ln_bwd_kernel<T, 1, 4>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((ln_bwd_kernel<T, 1, 16>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename T> hipError_t launch_ln_bwd(const LnBwdArgs &a, hipStream_t s)
+{
+    return (a.C % 4 == 0) ? launch_ln_bwd_v<T, 4>(a, s) : launch_ln_bwd_v<T, 1>(a, s);
+}
+
+// GELU in its Gaussian-CDF form and its derivative Phi(t) + t phi(t)
+__device__ __forceinline__ float gelu_f(float t) { return 0.5f * t * (1.f + erff(t * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float t)
+{
+    return 0.5f * (1.f + erff(t * 0.70710678118654752f)) + t * 0.39894228040143268f * __expf(-0.5f * t * t);
+}
+
+// h = GELU(pre);  with dh: dh <- dh * GELU'(pre) in place (h not written)
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_kernel(const T *pre, T *h, T *dh, long n)
+{
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+        const float t = to_f32(pre[i]);
+        if (dh) from_f32(dh[i], to_f32(dh[i]) * gelu_df(t));
+        else from_f32(h[i], gelu_f(t));
+    }
+}
+
+template <typename T> hipError_t launch_gelu(const T *pre, T *h, T *dh, long n, hipStream_t s)
+{
+    long blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    KernelTimer kt(dh ? K_GELU_BWD : K_GELU_FWD, s);
+    hipLaunchKernelGGL(gelu_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, pre, h, dh, n);
+    return hipGetLastError();
+}
+
+size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+template <typename... P> bool aligned16(P... p) { return (((reinterpret_cast<uintptr_t>(p)) | ...) & 15) == 0; }
+
+// Byte offsets of everything the two calls carve out of `saved` and `ws`.
+struct Plan {
+    long T;
+    int C, Hd;
+    size_t e;
+    size_t act, hid;              // bytes of a [T, C] and of a [T, hidden] tensor (256-aligned)
+    size_t at_saved, at_fws, at_bws; // the attention layer's own needs
+    size_t saved, fwd_ws, bwd_ws;
+    size_t params;                // fp32 entries of one copy of this file's parameter gradients
+    size_t reps;                  // bytes of the kGradReplicas copies
+    bool fused_mlp;
+};
+
+int make_plan(const astl_desc *d, Plan *p)
+{
+    if (!d) return GSWA_EINVAL;
+    int rc = gswa_query_bytes(&d->attn, &p->at_saved, &p->at_fws, &p->at_bws);
+    if (rc != GSWA_OK) return rc;
+    if (d->hidden <= 0 || !(d->eps >= 0.f)) return GSWA_EINVAL;
+    if (d->attn.C > 256 || d->hidden > (1 << 20)) return GSWA_EUNSUPPORTED;
+    p->T = (long)d->attn.B * d->attn.H * d->attn.W;
+    p->C = d->attn.C; p->Hd = d->hidden;
+    p->e = d->attn.dtype == GSWA_F32 ? 4 : 2;
+    if (p->T * (long)p->Hd >= (1L << 40)) return GSWA_EUNSUPPORTED;
+    p->act = align256((size_t)p->T * p->C * p->e);
+    p->hid = align256((size_t)p->T * p->Hd * p->e);
+    p->fused_mlp = d->attn.dtype == GSWA_BF16 && !(d->attn.flags & GSWA_FORCE_STAGED) &&
+                   astl_mlp_supported(p->C, p->Hd);
+    p->params = 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
+    p->reps = align256(kGradReplicas * p->params * sizeof(float));
+    p->saved = p->act + p->at_saved;
+    // forward: xn | a | max(attention scratch (+ its saved state at inference), pre | h)
+    const size_t hid_f = p->fused_mlp ? 0 : 2 * p->hid;
+    p->fwd_ws = 2 * p->act + (p->at_fws > hid_f ? p->at_fws : hid_f);
+    // backward: xn | dn | dx1 | max(pre | h | dh, attention scratch) | copies of the gradients
+    const size_t hid_b = p->fused_mlp ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd) : 3 * p->hid;
+    p->bwd_ws = 3 * p->act + (p->at_bws > hid_b ? p->at_bws : hid_b) + p->reps;
+    return GSWA_OK;
+}
+
+#define ASTL_HIP(expr)                                         \
+    do {                                                       \
+        hipError_t e_ = (expr);                                \
+        if (e_ != hipSuccess) return report_hip_error(e_);     \
+    } while (0)
+#define ASTL_RC(expr)                  \
+    do {                               \
+        int rc_ = (expr);              \
+        if (rc_ != GSWA_OK) return rc_; \
+    } while (0)
+
+template <typename T>
+int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params *p, T *y, char *saved,
+              char *ws, hipStream_t st)
+{
+    const long rows = pl.T;
+    const int C = pl.C, Hd = pl.Hd;
+    T *xn = reinterpret_cast<T *>(ws);
+    T *a = reinterpret_cast<T *>(ws + pl.act);
+    // at inference x1 takes a third slot of the scratch and the attention layer keeps what it
+    // would have saved behind its own scratch; the caller sized ws as fwd_ws + saved for this
+    T *x1 = reinterpret_cast<T *>(saved ? saved : ws + 2 * pl.act);
+    char *rest = ws + (saved ? 2 : 3) * pl.act;
+    void *at_saved = saved ? static_cast<void *>(saved + pl.act) : nullptr;
+
+    // Eq. 4: x1 = GSWA(LN_1(x)) + x
+    LnArgs l1{};
+    l1.u = x; l1.gamma = p->ln1_w; l1.beta = p->ln1_b; l1.out = xn; l1.rows = rows; l1.C = C; l1.eps = d->eps;
+    ASTL_HIP(launch_ln_fwd<T>(l1, st));
+    ASTL_RC(gswa_forward(&d->attn, xn, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, a, at_saved,
+                         rest, st));
+    if (pl.fused_mlp) {
+        // Eq. 4's skip and the whole of Eq. 5 in one launch
+        ASTL_HIP(launch_astl_mlp_fwd(rows, C, Hd, d->eps, (const bf16_t *)x, (const bf16_t *)a,
+                                     (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
+                                     (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
+                                     (const bf16_t *)p->w_fc2, (const bf16_t *)p->b_fc2,
+                                     (bf16_t *)x1, (bf16_t *)y, st));
+        return GSWA_OK;
+    }
+    // Eq. 5: y = MLP(LN_2(x1)) + x1
+    LnArgs l2{};
+    l2.u = x; l2.add = a; l2.gamma = p->ln2_w; l2.beta = p->ln2_b; l2.sum_out = x1; l2.out = xn;
+    l2.rows = rows; l2.C = C; l2.eps = d->eps;
+    ASTL_HIP(launch_ln_fwd<T>(l2, st));
+    T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
+    LinearArgs f1{};
+    f1.a1 = xn; f1.lda1 = C; f1.w = p->w_fc1; f1.w_sn = C; f1.w_sk = 1; f1.bias = p->b_fc1;
+    f1.out = pre; f1.ldout = Hd; f1.rows = rows; f1.N = Hd; f1.K = C; f1.prof_id = K_FC1_LINEAR;
+    ASTL_HIP(launch_linear<T>(f1, st));
+    ASTL_HIP(launch_gelu<T>(pre, h, nullptr, rows * Hd, st));
+    LinearArgs f2{};
+    f2.a1 = h; f2.lda1 = Hd; f2.w = p->w_fc2; f2.w_sn = Hd; f2.w_sk = 1; f2.bias = p->b_fc2;
+    f2.add = x1; f2.ldadd = C;
+    f2.out = y; f2.ldout = C; f2.rows = rows; f2.N = C; f2.K = Hd; f2.prof_id = K_FC2_LINEAR;
+    ASTL_HIP(launch_linear<T>(f2, st));
+    return GSWA_OK;
+}
+
+template <typename T>
+int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, const astl_params *p,
+               const char *saved, T *dx, const astl_grads *g, char *ws, hipStream_t st)
+{
+    const long rows = pl.T;
+    const int C = pl.C, Hd = pl.Hd;
+    const T *x1 = reinterpret_cast<const T *>(saved);
+    const void *at_saved = saved + pl.act;
+    T *xn = reinterpret_cast<T *>(ws);
+    T *dn = reinterpret_cast<T *>(ws + pl.act);
+    T *dx1 = reinterpret_cast<T *>(ws + 2 * pl.act);
+    char *rest = ws + 3 * pl.act;
+    float *rep = reinterpret_cast<float *>(ws + pl.bwd_ws - pl.reps);
+    // one copy of the gradients: dw_fc1 | db_fc1 | dw_fc2 | db_fc2 | dln1_w | dln1_b | dln2_w | dln2_b
+    const long P = (long)pl.params;
+    const long o_w1 = 0, o_b1 = o_w1 + (long)Hd * C, o_w2 = o_b1 + Hd, o_b2 = o_w2 + (long)C * Hd;
+    const long o_g1 = o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
+
+    ZeroList z{};
+    z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P; z.count = 1;
+    ASTL_HIP(launch_fill_zero(z, st));
+
+    // Eq. 5 backwards
+    if (pl.fused_mlp) {
+        ASTL_HIP(launch_astl_mlp_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
+                                     (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
+                                     (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
+                                     (const bf16_t *)p->w_fc2, (bf16_t *)dx1, rep + o_w1, rep + o_b1,
+                                     rep + o_w2, rep + o_b2, rep + o_g2, rep + o_be2, P, kGradReplicas,
+                                     rest, st));
+    } else {
+        T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
+        T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);
+        // recompute LN_2(x1), the pre-activation and the hidden layer
+        LnArgs l2{};
+        l2.u = x1; l2.gamma = p->ln2_w; l2.beta = p->ln2_b; l2.out = xn; l2.rows = rows; l2.C = C; l2.eps = d->eps;
+        ASTL_HIP(launch_ln_fwd<T>(l2, st));
+        LinearArgs f1{};
+        f1.a1 = xn; f1.lda1 = C; f1.w = p->w_fc1; f1.w_sn = C; f1.w_sk = 1; f1.bias = p->b_fc1;
+        f1.out = pre; f1.ldout = Hd; f1.rows = rows; f1.N = Hd; f1.K = C; f1.prof_id = K_FC1_LINEAR;
+        ASTL_HIP(launch_linear<T>(f1, st));
+        ASTL_HIP(launch_gelu<T>(pre, h, nullptr, rows * Hd, st));
+        // dh = dy Wfc2;  d Wfc2 = dy^T h
+        LinearArgs b2{};
+        b2.a1 = dy; b2.lda1 = C; b2.w = p->w_fc2; b2.w_sn = 1; b2.w_sk = Hd;
+        b2.out = dh; b2.ldout = Hd; b2.rows = rows; b2.N = Hd; b2.K = C; b2.prof_id = K_FC_DLINEAR;
+        ASTL_HIP(launch_linear<T>(b2, st));
+        WgradArgs w2{};
+        w2.dout = dy; w2.lddout = C; w2.a1 = h; w2.lda1 = Hd;
+        w2.dw = rep + o_w2; w2.db = rep + o_b2; w2.rep_stride = P; w2.reps = kGradReplicas;
+        w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
+        ASTL_HIP(launch_wgrad<T>(w2, st));
+        // through the GELU, then d Wfc1 = dpre^T LN_2(x1) and d LN_2(x1) = dpre Wfc1
+        ASTL_HIP(launch_gelu<T>(pre, nullptr, dh, rows * Hd, st));
+        WgradArgs w1{};
+        w1.dout = dh; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
+        w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
+        w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
+        ASTL_HIP(launch_wgrad<T>(w1, st));
+        LinearArgs b1{};
+        b1.a1 = dh; b1.lda1 = Hd; b1.w = p->w_fc1; b1.w_sn = 1; b1.w_sk = C;
+        b1.out = dn; b1.ldout = C; b1.rows = rows; b1.N = C; b1.K = Hd; b1.prof_id = K_FC_DLINEAR;
+        ASTL_HIP(launch_linear<T>(b1, st));
+        // through LN_2, plus the skip of Eq. 5: dx1
+        LnBwdArgs n2{};
+        n2.u = x1; n2.dout = dn; n2.res = dy; n2.gamma = p->ln2_w; n2.du = dx1;
+        n2.dgamma = rep + o_g2; n2.dbeta = rep + o_be2; n2.rep_stride = P; n2.reps = kGradReplicas;
+        n2.rows = rows; n2.C = C; n2.eps = d->eps;
+        ASTL_HIP(launch_ln_bwd<T>(n2, st));
+    }
+
+    // Eq. 4 backwards: the attention layer on LN_1(x) (recomputed), then LN_1 and the skip
+    LnArgs l1{};
+    l1.u = x; l1.gamma = p->ln1_w; l1.beta = p->ln1_b; l1.out = xn; l1.rows = rows; l1.C = C; l1.eps = d->eps;
+    ASTL_HIP(launch_ln_fwd<T>(l1, st));
+    ASTL_RC(gswa_backward(&d->attn, xn, dx1, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, at_saved,
+                          dn, g->w_qkv, g->b_qkv, g->w_proj, g->b_proj, g->bias_table, rest, st));
+    LnBwdArgs n1{};
+    n1.u = x; n1.dout = dn; n1.res = dx1; n1.gamma = p->ln1_w; n1.du = dx;
+    n1.dgamma = rep + o_g1; n1.dbeta = rep + o_be1; n1.rep_stride = P; n1.reps = kGradReplicas;
+    n1.rows = rows; n1.C = C; n1.eps = d->eps;
+    ASTL_HIP(launch_ln_bwd<T>(n1, st));
+
+    ReplicaSum rs{};
+    rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;
+    rs.out[0] = g->w_fc1; rs.off[0] = o_w1; rs.n[0] = (long)Hd * C;
+    rs.out[1] = g->b_fc1; rs.off[1] = o_b1; rs.n[1] = Hd;
+    rs.out[2] = g->w_fc2; rs.off[2] = o_w2; rs.n[2] = (long)C * Hd;
+    rs.out[3] = g->b_fc2; rs.off[3] = o_b2; rs.n[3] = C;
+    rs.out[4] = g->ln1_w; rs.off[4] = o_g1; rs.n[4] = C;
+    rs.out[5] = g->ln1_b; rs.off[5] = o_be1; rs.n[5] = C;
+    rs.out[6] = g->ln2_w; rs.off[6] = o_g2; rs.n[6] = C;
+    rs.out[7] = g->ln2_b; rs.off[7] = o_be2; rs.n[7] = C;
+    rs.count = 8;
+    rs.accumulate = (d->attn.flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
+    ASTL_HIP(launch_reduce_replicas(rs, st));
+    return GSWA_OK;
+}
+
+} // namespace
+
+} // namespace gswa
+
+using namespace gswa;
+
+extern "C" {
+
+int astl_query_bytes(const astl_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes, size_t *bwd_ws_bytes)
+{
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != GSWA_OK) return rc;
+    if (saved_bytes) *saved_bytes = pl.saved;
+    if (fwd_ws_bytes) *fwd_ws_bytes = pl.fwd_ws;
+    if (bwd_ws_bytes) *bwd_ws_bytes = pl.bwd_ws;
+    return GSWA_OK;
+}
+
+int astl_forward(const astl_desc *desc, const void *x, const astl_params *p, void *y, void *saved, void *ws,
+                 void *hip_stream)
+{
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !p || !y || !ws) return GSWA_EINVAL;
+    if (!p->ln1_w || !p->ln1_b || !p->w_qkv || !p->b_qkv || !p->w_proj || !p->b_proj || !p->bias_table ||
+        !p->ln2_w || !p->ln2_b || !p->w_fc1 || !p->b_fc1 || !p->w_fc2 || !p->b_fc2)
+        return GSWA_EINVAL;
+    if (x == y || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    if (!aligned16(x, y, saved, p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table,
+                   p->ln2_w, p->ln2_b, p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2))
+        return GSWA_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (desc->attn.dtype == GSWA_F32)
+        return forward_t<float>(desc, pl, (const float *)x, p, (float *)y, (char *)saved, (char *)ws, st);
+    return forward_t<bf16_t>(desc, pl, (const bf16_t *)x, p, (bf16_t *)y, (char *)saved, (char *)ws, st);
+}
+
+int astl_backward(const astl_desc *desc, const void *x, const void *dy, const astl_params *p, const void *saved,
+                  void *dx, const astl_grads *g, void *ws, void *hip_stream)
+{
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !dy || !p || !saved || !dx || !g || !ws) return GSWA_EINVAL;
+    if (!p->ln1_w || !p->ln1_b || !p->w_qkv || !p->b_qkv || !p->w_proj || !p->b_proj || !p->bias_table ||
+        !p->ln2_w || !p->ln2_b || !p->w_fc1 || !p->b_fc1 || !p->w_fc2 || !p->b_fc2)
+        return GSWA_EINVAL;
+    if (!g->ln1_w || !g->ln1_b || !g->w_qkv || !g->b_qkv || !g->w_proj || !g->b_proj || !g->bias_table ||
+        !g->ln2_w || !g->ln2_b || !g->w_fc1 || !g->b_fc1 || !g->w_fc2 || !g->b_fc2)
+        return GSWA_EINVAL;
+    if (dx == x || dx == dy || dx == saved || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    if (!aligned16(x, dy, saved, dx, p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table,
+                   p->ln2_w, p->ln2_b, p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2, g->ln1_w, g->ln1_b, g->w_qkv,
+                   g->b_qkv, g->w_proj, g->b_proj, g->bias_table, g->ln2_w, g->ln2_b, g->w_fc1, g->b_fc1,
+                   g->w_fc2, g->b_fc2))
+        return GSWA_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (desc->attn.dtype == GSWA_F32)
+        return backward_t<float>(desc, pl, (const float *)x, (const float *)dy, p, (const char *)saved, (float *)dx,
+                                 g, (char *)ws, st);
+    return backward_t<bf16_t>(desc, pl, (const bf16_t *)x, (const bf16_t *)dy, p, (const char *)saved, (bf16_t *)dx,
+                              g, (char *)ws, st);
+}
+
+} // extern "C"

@@ -67,4 +67,7 @@ __device__ __forceinline__ long window_token(const Geom &g, int w, int n, int &r
     return ((long)b * g.H + si) * g.W + sj;
 }
 
+// Records the text of a failed HIP call for gswa_last_hip_error() and returns GSWA_EHIP.
+int report_hip_error(hipError_t e);
+
 } // namespace gswa

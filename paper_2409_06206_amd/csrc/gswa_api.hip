@@ -9,16 +9,20 @@
 #include <type_traits>
 
 namespace {
-
-using namespace gswa;
-
 thread_local std::string g_hip_error;
+}
 
-int hip_fail(hipError_t e)
+int gswa::report_hip_error(hipError_t e)
 {
     g_hip_error = hipGetErrorString(e);
     return GSWA_EHIP;
 }
+
+namespace {
+
+using namespace gswa;
+
+int hip_fail(hipError_t e) { return report_hip_error(e); }
 
 #define GSWA_HIP(expr)                                \
     do {                                              \

@@ -27,6 +27,16 @@ enum KernelId {
     K_ATTN_CORE_BWD, // its adjoint
     K_LINEAR_PAIR,  // backward of one group: q|k|v recomputation and dO in one launch
     K_WINDOW_FWD,   // whole forward of a narrow layer with 64- or 144-token windows, one launch
+    K_LN_FWD,       // LayerNorm of every token (Eq. 4-5), optionally of a sum that is stored as well
+    K_LN_BWD,       // its adjoint, skip gradient added
+    K_GELU_FWD,     // hidden layer of the MLP from its pre-activation
+    K_GELU_BWD,     // gradient through the GELU
+    K_FC1_LINEAR,   // first fully connected layer of the MLP (Eq. 5)
+    K_FC2_LINEAR,   // second one, skip connection added
+    K_FC_DLINEAR,   // gradient with respect to the input of a fully connected layer
+    K_FC_WGRAD,     // gradient of its weight and bias
+    K_MLP_FWD,      // skip of Eq. 4 and all of Eq. 5 in one launch
+    K_MLP_BWD,      // adjoint of Eq. 5 in one launch
     K_COUNT
 };
 

@@ -4,7 +4,7 @@ happens here."""
 import numpy as np
 import torch
 
-from . import gswa, synth
+from . import astl, gswa, synth
 
 _PARAMS = ("w_qkv", "b_qkv", "w_proj", "b_proj", "table")
 
@@ -58,6 +58,52 @@ class DeviceLayer:
         gswa.gswa_backward(self.desc, self.x, self.dy, p["w_qkv"], p["b_qkv"], p["w_proj"],
                            p["b_proj"], p["table"], self.saved, self.dx, g["w_qkv"], g["b_qkv"],
                            g["w_proj"], g["b_proj"], g["table"], self.ws, stream)
+
+    def results(self):
+        out = {"y": to_host(self.y), "dx": to_host(self.dx)}
+        out.update({"d" + k: to_host(v) for k, v in self.grads.items()})
+        return out
+
+
+class DeviceBlock:
+    """Buffers of one whole-layer call (LayerNorms, attention, MLP, skips) on the GPU."""
+
+    def __init__(self, B, H, W, C, heads, groups, window, shift, dtype, hidden, eps=1e-5, flags=0,
+                 device="cuda:0", dqk=0):
+        self.desc = astl.make_desc(B, H, W, C, heads, groups, window, shift, dtype, hidden, eps, flags, dqk)
+        self.dtype, self.device = dtype, device
+        self.shape = (B, H, W, C)
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.saved_bytes, self.fwd_ws_bytes, self.bwd_ws_bytes = astl.astl_query_bytes(self.desc)
+        self.y = torch.empty(self.shape, dtype=tdt, device=device)
+        self.dx = torch.empty(self.shape, dtype=tdt, device=device)
+        self.saved = torch.empty(self.saved_bytes, dtype=torch.uint8, device=device)
+        ws_bytes = max(self.fwd_ws_bytes + self.saved_bytes, self.bwd_ws_bytes)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
+        shp = synth.astl_param_shapes(C, heads, groups, window, hidden, dqk)
+        self.grads = {k: torch.empty(s, dtype=torch.float32, device=device) for k, s in shp.items()}
+        self.params = None
+        self.x = self.dy = None
+
+    @staticmethod
+    def _fields(d):
+        """synth's names -> the field names of the C structs (the bias table is `table` there)."""
+        return {("bias_table" if k == "table" else k): v for k, v in d.items()}
+
+    def set_params(self, p):
+        self.params = {k: to_device(v, self.dtype, self.device) for k, v in p.items()}
+
+    def set_inputs(self, x, dy=None):
+        self.x = to_device(x, self.dtype, self.device)
+        self.dy = None if dy is None else to_device(dy, self.dtype, self.device)
+
+    def forward(self, keep=True, stream=None):
+        astl.astl_forward(self.desc, self.x, self._fields(self.params), self.y,
+                          self.saved if keep else None, self.ws, stream)
+
+    def backward(self, stream=None):
+        astl.astl_backward(self.desc, self.x, self.dy, self._fields(self.params), self.saved, self.dx,
+                           self._fields(self.grads), self.ws, stream)
 
     def results(self):
         out = {"y": to_host(self.y), "dx": to_host(self.dx)}

@@ -67,3 +67,32 @@ def check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, seed=syn
     bad = {k: e for k, e in errs.items() if not e <= TOL[dtype] * tol_scale}
     assert not bad, f"relative max-norm error above {TOL[dtype] * tol_scale}: {bad} (all: {errs})"
     return errs, layer
+
+
+def check_block(oracle, B, H, W, C, heads, groups, window, shift, dtype, hidden, seed=synth.LAYER_SEED0,
+                regime="stress", backward=True, tol_scale=1.0, extra_flags=0, dqk=0, eps=1e-5):
+    """Whole layer (Eq. 4-5): ``oracle`` is the astl_oracle module."""
+    from paper_2409_06206_amd import runner
+    import torch
+    p = synth.astl_params(C, heads, groups, window, hidden, seed, regime, dqk)
+    x, dy = synth.activations(B, H, W, C, synth.ACT_SEED + seed - synth.LAYER_SEED0)
+    p = {k: synth.quantize(v, dtype) for k, v in p.items()}
+    x, dy = synth.quantize(x, dtype), synth.quantize(dy, dtype)
+    kw = dict(heads=heads, groups=groups, window=window, shift=shift, eps=eps, dqk=dqk)
+    want = {"y": oracle.forward(x, p, **kw)}
+    if backward:
+        dx, g = oracle.backward(x, dy, p, **kw)
+        want["dx"] = dx
+        want.update({"d" + k: v for k, v in g.items()})
+    blk = runner.DeviceBlock(B, H, W, C, heads, groups, window, shift, dtype, hidden, eps, extra_flags, dqk=dqk)
+    blk.set_params(p)
+    blk.set_inputs(x, dy)
+    blk.forward(keep=backward)
+    if backward:
+        blk.backward()
+    torch.cuda.synchronize()
+    got = blk.results()
+    errs = {k: rel_err(got[k], want[k]) for k in want}
+    bad = {k: e for k, e in errs.items() if not e <= TOL[dtype] * tol_scale}
+    assert not bad, f"relative max-norm error above {TOL[dtype] * tol_scale}: {bad} (all: {errs})"
+    return errs, blk

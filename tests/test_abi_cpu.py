@@ -10,10 +10,10 @@ from paper_2409_06206_amd import gswa
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "gswa.h")).read()
+def declared_functions(header="gswa.h", prefix="gswa"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gswa_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(%s_[a-z_]+)\s*\(" % prefix, text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -107,3 +107,53 @@ def test_fused_path_sizes():
         assert big - 4 * T * C * 2 == saved - T * C * 2
         assert fwd == 0
         assert bwd > 0 and bwd % 256 == 0
+
+
+def test_whole_layer_entry_points_are_exported():
+    from paper_2409_06206_amd import astl
+    names = declared_functions("astl.h", "astl")
+    assert set(names) == set(astl.EXPORTS)
+    L = astl.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("change", [dict(hidden=0), dict(hidden=-4), dict(eps=-1.0), dict(eps=float("nan")),
+                                    dict(H=12), dict(dtype=5)])
+def test_invalid_whole_layer_descriptors_are_rejected(change):
+    from paper_2409_06206_amd import astl
+    desc = astl.make_desc(**{**GOOD, "hidden": 120, **change})
+    with pytest.raises(gswa.GswaError) as ei:
+        astl.astl_query_bytes(desc)
+    assert ei.value.status == gswa.GSWA_EINVAL
+
+
+def test_whole_layer_rejects_wide_channels_and_null_pointers():
+    from paper_2409_06206_amd import astl
+    desc = astl.make_desc(**{**GOOD, "C": 264, "heads": 6, "hidden": 120})
+    with pytest.raises(gswa.GswaError) as ei:
+        astl.astl_query_bytes(desc)
+    assert ei.value.status == gswa.GSWA_EUNSUPPORTED
+    desc = astl.make_desc(**{**GOOD, "hidden": 120})
+    fake = 0x1000  # never dereferenced: validation fails first
+    full = {n: fake for n in astl.PARAM_FIELDS}
+    with pytest.raises(gswa.GswaError) as ei:
+        astl.astl_forward(desc, fake, {**full, "w_fc1": None}, fake + 0x1000, None, fake, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
+    with pytest.raises(gswa.GswaError) as ei:
+        astl.astl_forward(desc, fake, full, fake + 0x1000, None, fake + 8, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
+    with pytest.raises(gswa.GswaError) as ei:
+        astl.astl_backward(desc, fake, fake, full, fake, fake + 0x2000, {**full, "ln2_b": None}, fake, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
+
+
+def test_whole_layer_sizes_hold_the_attention_layers_state_and_one_activation():
+    from paper_2409_06206_amd import astl
+    desc = astl.make_desc(**{**GOOD, "hidden": 120})
+    saved, fwd, bwd = astl.astl_query_bytes(desc)
+    a_saved, a_fwd, a_bwd = gswa.gswa_query_bytes(desc.attn)
+    act = 2 * 16 * 16 * 60 * 2
+    assert saved == a_saved + act
+    assert fwd >= 2 * act + a_fwd and bwd >= 3 * act + a_bwd
+    assert saved % 256 == 0 and fwd % 256 == 0 and bwd % 256 == 0

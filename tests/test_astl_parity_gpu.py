@@ -1,0 +1,93 @@
+"""GPU parity of the whole layer (Eq. 4-5: LayerNorm, attention, MLP, skips) through the C ABI
+against the fp64 oracle, element by element on the same seeded inputs.  Tolerance as for the
+attention layer: max-norm relative error per tensor, 1e-5 in fp32 and 2e-2 in bf16."""
+import numpy as np
+import pytest
+
+from oracle import astl_oracle
+from paper_2409_06206_amd import gswa, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    # fp32: vector and scalar channel layouts of the per-token kernels, several row passes
+    dict(B=1, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="f32", hidden=120),
+    dict(B=2, H=8, W=8, C=12, heads=2, groups=1, window=4, shift=0, dtype="f32", hidden=20),
+    dict(B=1, H=8, W=12, C=6, heads=2, groups=2, window=4, shift=1, dtype="f32", hidden=9),
+    dict(B=1, H=8, W=8, C=68, heads=4, groups=2, window=4, shift=2, dtype="f32", hidden=100),
+    dict(B=1, H=8, W=8, C=200, heads=4, groups=1, window=4, shift=2, dtype="f32", hidden=64),
+    dict(B=1, H=8, W=8, C=66, heads=6, groups=3, window=4, shift=0, dtype="f32", hidden=40),
+    # bf16: the benchmark's channel counts, every group setting, both window sizes
+    dict(B=2, H=16, W=16, C=60, heads=6, groups=1, window=8, shift=0, dtype="bf16", hidden=120),
+    dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=120),
+    dict(B=3, H=16, W=24, C=60, heads=6, groups=3, window=8, shift=4, dtype="bf16", hidden=120),
+    dict(B=1, H=16, W=16, C=60, heads=6, groups=6, window=8, shift=0, dtype="bf16", hidden=120),
+    dict(B=1, H=24, W=24, C=60, heads=4, groups=2, window=12, shift=6, dtype="bf16", hidden=120, dqk=4),
+    dict(B=1, H=16, W=16, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
+    dict(B=1, H=8, W=8, C=30, heads=3, groups=1, window=4, shift=2, dtype="bf16", hidden=50),
+    dict(B=1, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=60),
+    dict(B=5, H=8, W=8, C=60, heads=6, groups=2, window=8, shift=0, dtype="bf16", hidden=128),
+]
+
+
+def _id(c):
+    return "-".join(f"{k}{v}" for k, v in c.items())
+
+
+@pytest.mark.parametrize("case", SMALL, ids=_id)
+def test_layer_matches_oracle(case):
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, **case)
+
+
+@pytest.mark.parametrize("case", [SMALL[0], SMALL[7], SMALL[10]], ids=_id)
+def test_init_regime(case):
+    """Identity LayerNorms, small weights: the skip path dominates y, the gradients still have to match."""
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, regime="init", **case)
+
+
+@pytest.mark.parametrize("case", [SMALL[7], SMALL[10]], ids=_id)
+def test_every_path_of_the_attention_layer(case):
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, extra_flags=gswa.GSWA_FORCE_STAGED, **case)
+
+
+@pytest.mark.parametrize("case", [SMALL[0], SMALL[7], SMALL[11]], ids=_id)
+def test_inference_call_gives_the_training_output(case):
+    print("case", case, flush=True)
+    import torch
+    _, blk = parity.check_block(astl_oracle, backward=False, **case)
+    y_inf = blk.y.clone()
+    blk.forward(keep=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y_inf, blk.y)
+
+
+@pytest.mark.parametrize("case", [SMALL[0], SMALL[7]], ids=_id)
+def test_accumulate_flag_adds_into_every_parameter_gradient(case):
+    print("case", case, flush=True)
+    import torch
+    _, blk = parity.check_block(astl_oracle, **case)
+    first = {k: v.clone() for k, v in blk.grads.items()}
+    from paper_2409_06206_amd import astl
+    c = dict(case)
+    blk.desc = astl.make_desc(c["B"], c["H"], c["W"], c["C"], c["heads"], c["groups"], c["window"], c["shift"],
+                              c["dtype"], c["hidden"], flags=gswa.GSWA_ACCUM_WGRAD, dqk=c.get("dqk", 0))
+    blk.backward()
+    torch.cuda.synchronize()
+    for k, v in blk.grads.items():
+        want = 2.0 * first[k]
+        err = float((v - want).abs().max()) / max(float(want.abs().max()), 1e-30)
+        assert err <= 1e-3, (k, err)
+
+
+def test_benchmark_shape_pair_against_the_oracle():
+    """Two layers (shifts 0 and 4) at the benchmark's full size, every output element."""
+    cfg = synth.CONFIGS["c2"]
+    for li, shift in enumerate(cfg["layers"]):
+        case = dict(B=cfg["B"], H=cfg["H"], W=cfg["W"], C=cfg["C"], heads=cfg["heads"], groups=2,
+                    window=cfg["window"], shift=shift, dtype=cfg["dtype"], hidden=2 * cfg["C"])
+        print("case", case, flush=True)
+        parity.check_block(astl_oracle, seed=synth.LAYER_SEED0 + li, **case)
