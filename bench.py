@@ -6,7 +6,7 @@ shape: two consecutive GSWA layers (shift 0, then shift 4), forward and backward
 storage with fp32 accumulation, B=32, 64x64 map, C=60, 6 heads, window 8.  Inputs are
 resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--groups G] [--workload c2|c3|c4|c5_m8|c5_m16|agile_h4_qk16|agile_h4_qk32|agile_h6_qk24]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--groups G] [--workload c2|c3|c4|c5_m8|c5_m16|agile_h4_qk16|agile_h4_qk32|agile_h6_qk24|agile_infer|astl_c2|astl_agile|astl_c3]
 """
 import argparse
 import json
@@ -53,10 +53,16 @@ def build_case(name, groups):
     x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
     layers = []
     for li, shift in enumerate(cfg["layers"]):
-        L = runner.DeviceLayer(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
-                               cfg["window"], shift, cfg["dtype"], FLAGS, dqk=cfg.get("dqk", 0))
-        L.set_params(synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"],
-                                        synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)))
+        if cfg.get("block"):
+            L = runner.DeviceBlock(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups, cfg["window"],
+                                   shift, cfg["dtype"], cfg["hidden"], flags=FLAGS, dqk=cfg.get("dqk", 0))
+            L.set_params(synth.astl_params(cfg["C"], cfg["heads"], groups, cfg["window"], cfg["hidden"],
+                                           synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)))
+        else:
+            L = runner.DeviceLayer(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups,
+                                   cfg["window"], shift, cfg["dtype"], FLAGS, dqk=cfg.get("dqk", 0))
+            L.set_params(synth.layer_params(cfg["C"], cfg["heads"], groups, cfg["window"],
+                                            synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)))
         layers.append(L)
     layers[0].set_inputs(x)
     layers[-1].dy = runner.to_device(dy, cfg["dtype"])
@@ -112,7 +118,7 @@ def profile_steps(layers, steps, backward=True):
 
 
 FORWARD_KERNELS = {"qkv_linear", "attn_fwd", "attn_core_fwd", "window_fwd", "proj_linear", "fused_fwd", "fused_attn_fwd", "proj_gemm",
-                   "pack_fwd"}
+                   "pack_fwd", "mlp_fwd", "fc1_linear", "fc2_linear", "gelu_fwd"}
 
 
 def algorithmic_bytes_per_launch(kernel, cfg, launches_per_layer, training=True):
@@ -139,6 +145,8 @@ def model_flops_per_token(cfg, groups, backward=True):
     C, N, heads = cfg["C"], cfg["window"] ** 2, cfg["heads"]
     qk = heads * (cfg.get("dqk", 0) or C // heads)       # channels of q (and of k) over all heads
     fwd = 2 * (C / groups) * (2 * qk + C) + 2 * N * (qk + C) + 2 * C * C
+    if cfg.get("block"):
+        fwd += 4 * C * cfg["hidden"]     # the two fully connected layers of Eq. 5
     return (3 if backward else 1) * fwd
 
 
@@ -160,6 +168,8 @@ def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
                                dqk=dqk)
         p = {k: synth.quantize(v, cfg["dtype"]) for k, v in p.items()}
         params.append((p["w_qkv"], p["b_qkv"], p["w_proj"], p["b_proj"], p["table"]))
+    if cfg.get("block"):
+        return cpu_baseline_block(name, cfg, groups, x, dy, min_seconds, max_reps)
     reps, t0 = 0, time.perf_counter()
     while reps < max_reps and (reps == 0 or time.perf_counter() - t0 < min_seconds):
         acts = [x]
@@ -176,13 +186,41 @@ def cpu_baseline(name, groups, min_seconds=10.0, max_reps=60):
                       f"{reps} repetition(s), {dt:.2f} s each"}
 
 
+def cpu_baseline_block(name, cfg, groups, x, dy, min_seconds, max_reps):
+    """The whole-layer CPU oracle (numpy fp64 around the C attention oracle) on the same layer pair."""
+    from oracle import astl_oracle, gswa_oracle
+    from paper_2409_06206_amd import synth
+    dqk = cfg.get("dqk", 0)
+    kw = dict(heads=cfg["heads"], groups=groups, window=cfg["window"], dqk=dqk)
+    params = []
+    for li in range(len(cfg["layers"])):
+        p = synth.astl_params(cfg["C"], cfg["heads"], groups, cfg["window"], cfg["hidden"],
+                              synth.LAYER_SEED0 + li, dqk=dqk)
+        params.append({k: synth.quantize(v, cfg["dtype"]) for k, v in p.items()})
+    reps, t0 = 0, time.perf_counter()
+    while reps < max_reps and (reps == 0 or time.perf_counter() - t0 < min_seconds):
+        acts = [x]
+        for p, s in zip(params, cfg["layers"]):
+            acts.append(astl_oracle.forward(acts[-1], p, shift=s, **kw))
+        g = dy
+        for p, s, xin in zip(reversed(params), reversed(cfg["layers"]), reversed(acts[:-1])):
+            g = astl_oracle.backward(xin, g, p, shift=s, **kw)[0]
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    tokens = cfg["B"] * cfg["H"] * cfg["W"] * len(cfg["layers"])
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": gswa_oracle.threads(), "kind": "oracle",
+            "sample": f"full {name} layer pair (B={cfg['B']}), fwd+bwd, fp64 oracle (numpy around the C "
+                      f"attention oracle with OpenMP), {reps} repetition(s), {dt:.2f} s each"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--groups", type=int, default=2)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer",
+                                                              "astl_c2", "astl_agile", "astl_c3"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
     ap.add_argument("--batch", type=int, default=0,
@@ -226,7 +264,9 @@ def main():
                 "traffic": measured_traffic(args.workload, args.groups, dom),
                 "avg_launch_us": prof[dom]["avg_us"], "algorithmic_bytes_per_launch": dom_bytes}
     e = 2 if cfg["dtype"] == "bf16" else 4
-    step_bytes = (7 if backward else 2) * cfg["C"] * e * tokens_per_step
+    # whole layers keep two [T, C] tensors for the backward pass instead of one
+    per_token = (9 if backward else 2) if cfg.get("block") else (7 if backward else 2)
+    step_bytes = per_token * cfg["C"] * e * tokens_per_step
     step_flops = model_flops_per_token(cfg, args.groups, backward) * tokens_per_step
 
     sweep = {}
@@ -251,7 +291,7 @@ def main():
         "value": tokens_per_step / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {len(layers)} GSWA layer(s), shifts {list(cfg['layers'])[:4]}"
+        "config": {"workload": f"{args.workload}: {len(layers)} {'whole (LN, GSWA, MLP, skips)' if cfg.get('block') else 'GSWA'} layer(s), shifts {list(cfg['layers'])[:4]}"
                                f"{'...' if len(layers) > 4 else ''}, {'fwd+bwd' if backward else 'forward only'}, "
                                f"B={cfg['B']} {cfg['H']}x{cfg['W']} C={cfg['C']} heads={cfg['heads']} "
                                f"window={cfg['window']} groups={args.groups}"
@@ -273,7 +313,7 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline and backward and (args.workload == "c2" or args.workload.startswith("agile")):
+    if not args.no_cpu_baseline and backward and (args.workload == "c2" or args.workload.startswith("agile") or cfg.get("block")):
         out["cpu_baseline"] = cpu_baseline(args.workload, args.groups)
     print(json.dumps(out))
 

@@ -153,5 +153,12 @@ CONFIGS.update({
     "agile_infer": dict(B=1, H=528, W=528, C=60, heads=4, groups=(1, 2), window=12, dqk=4, layers=(6,),
                         dtype="bf16", forward_only=True),
 })
+# Whole layers (Eq. 4-5: LayerNorm, attention, MLP, skips) at the same shapes; the hidden layer of
+# the MLP is twice as wide as the map, as in the lightweight Swin-family restoration networks.
+CONFIGS.update({
+    "astl_c2": dict(CONFIGS["c2"], block=True, hidden=120, groups=(1, 2, 3, 6)),
+    "astl_agile": dict(CONFIGS["agile_h4_qk16"], block=True, hidden=120),
+    "astl_c3": dict(CONFIGS["c3"], block=True, hidden=360),
+})
 ACT_SEED = 0
 LAYER_SEED0 = 100
