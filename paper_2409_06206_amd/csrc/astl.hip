@@ -324,6 +324,7 @@ struct Plan {
     size_t saved, fwd_ws, bwd_ws;
     size_t params;                // fp32 entries of one copy of this file's parameter gradients
     size_t reps;                  // bytes of the kGradReplicas copies
+    size_t pack;                  // bytes of the MLP's repacked weights at the end of `saved` (fused MLP)
     bool fused_mlp;
 };
 
@@ -344,7 +345,8 @@ int make_plan(const astl_desc *d, Plan *p)
                    astl_mlp_supported(p->C, p->Hd);
     p->params = 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
     p->reps = align256(kGradReplicas * p->params * sizeof(float));
-    p->saved = p->act + p->at_saved;
+    p->pack = p->fused_mlp ? astl_mlp_pack_bytes() : 0;
+    p->saved = p->act + p->at_saved + p->pack;
     // forward: xn | a | max(attention scratch (+ its saved state at inference), pre | h)
     const size_t hid_f = p->fused_mlp ? 0 : 2 * p->hid;
     p->fwd_ws = 2 * p->act + (p->at_fws > hid_f ? p->at_fws : hid_f);
@@ -378,6 +380,8 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
     T *x1 = reinterpret_cast<T *>(saved ? saved : ws + 2 * pl.act);
     char *rest = ws + (saved ? 2 : 3) * pl.act;
     void *at_saved = saved ? static_cast<void *>(saved + pl.act) : nullptr;
+    // (the repacked MLP weights close the saved state, wherever that lives)
+    void *pack = (saved ? saved + pl.saved : ws + pl.fwd_ws + pl.saved) - pl.pack;
 
     // Eq. 4: x1 = GSWA(LN_1(x)) + x
     LnArgs l1{};
@@ -391,7 +395,7 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
                                      (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                      (const bf16_t *)p->w_fc2, (const bf16_t *)p->b_fc2,
-                                     (bf16_t *)x1, (bf16_t *)y, st));
+                                     (bf16_t *)x1, (bf16_t *)y, pack, st));
         return GSWA_OK;
     }
     // Eq. 5: y = MLP(LN_2(x1)) + x1
@@ -442,7 +446,7 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                      (const bf16_t *)p->w_fc2, (bf16_t *)dx1, rep + o_w1, rep + o_b1,
                                      rep + o_w2, rep + o_b2, rep + o_g2, rep + o_be2, P, kGradReplicas,
-                                     rest, st));
+                                     saved + pl.saved - pl.pack, rest, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);

@@ -8,20 +8,26 @@ namespace gswa {
 // C <= 64 (multiple of 4) and hidden <= 128: all weights of the MLP fit in LDS as MFMA fragments.
 bool astl_mlp_supported(int C, int hidden);
 
-// x1 = x + a (stored);  y = MLP(LN_2(x1)) + x1.  rows tokens of C channels.
+// Bytes of the weights repacked for the matrix cores (written by the forward, read by both passes).
+size_t astl_mlp_pack_bytes();
+
+// x1 = x + a (stored);  y = MLP(LN_2(x1)) + x1.  rows tokens of C channels.  `pack` receives the
+// repacked weights (astl_mlp_pack_bytes() bytes, 16-byte aligned).
 hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
-                               const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, hipStream_t s);
+                               const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
+                               hipStream_t s);
 
 // Scratch bytes of the backward (hidden layer and its gradient for the weight-gradient products).
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden);
 
 // dx1 = dy + adjoint of MLP(LN_2(.)) at x1; the six parameter gradients are added into copy
 // `workgroup mod reps` of `reps` copies rep_stride floats apart (each pointer is its place in copy 0).
+// `pack` is what the forward call of the same layer wrote.
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
-                               float *db_fc2, float *dln_w, float *dln_b, long rep_stride, int reps, void *ws,
-                               hipStream_t s);
+                               float *db_fc2, float *dln_w, float *dln_b, long rep_stride, int reps,
+                               const void *pack, void *ws, hipStream_t s);
 
 } // namespace gswa

@@ -1,25 +1,567 @@
-// Fused kernels of the MLP half of a layer (Eq. 5 with the skip of Eq. 4 in the prologue).
+// Fused kernels of the MLP half of a layer (Sec. "Agile Swin Transformer Block", Eq. 5, with the
+// skip connection of Eq. 4 in the prologue) for narrow bf16 layers.
+//
+// A wavefront owns 16 tokens from the first load to the last store.  Lane (tok = lane & 15,
+// q = lane >> 4) holds, of its token, the channels 16 ct + 4 q + i (ct < CT, i < 4): one 8-byte
+// access per ct, and exactly the channels the C layout of a transposed product hands the lane.
+// Both matrix products are taken transposed (features x tokens), weights as the A operand from
+// fragments in LDS, activations as the B operand straight from registers:
+//   pre^T = W1 LN(x1)^T   reduces over channels: the lane's 8 k-slots of step s are the channels
+//                         16 (2s) + 4q + 0..3 and 16 (2s+1) + 4q + 0..3 (the weight fragments use
+//                         the same order), so the normalised row packs into B without any exchange;
+//   y^T   = W2 h^T        reduces over hidden features: h^T comes out of the first product in C
+//                         layout (features 16 ft + 4q + i of token tok) and two such tiles pack
+//                         into one B operand the same way.
+// LayerNorm's gamma is folded into the W1 fragments and beta into the bias (b1 + W1 beta), so the
+// first product takes the plain normalised row.
 #include "astl_mlp.h"
+#include "mfma.h"
 #include "profile.h"
+#include "staged_kernels.h"
 
 namespace gswa {
 
-bool astl_mlp_supported(int, int) { return false; }
+namespace {
 
-size_t astl_mlp_bwd_ws_bytes(long, int, int) { return 0; }
+constexpr int kMlpThreads = 256;
+constexpr int kMlpWaves = kMlpThreads / 64;
+constexpr int kFwdThreads = 512; // the forward needs few registers: eight wavefronts share one copy of the weights
+constexpr int kFwdWaves = kFwdThreads / 64;
 
-hipError_t launch_astl_mlp_fwd(long, int, int, float, const bf16_t *, const bf16_t *, const bf16_t *, const bf16_t *,
-                               const bf16_t *, const bf16_t *, const bf16_t *, const bf16_t *, bf16_t *, bf16_t *,
-                               hipStream_t)
+// Gaussian CDF Phi(t) and density phi(t): erf by the rational-times-exponential approximation
+// 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7); exp(-t^2/2) serves both.
+__device__ __forceinline__ void gauss(float t, float &Phi, float &phi)
 {
-    return hipErrorNotSupported;
+    const float x = fabsf(t) * 0.70710678118654752f;
+    const float k = __frcp_rn(1.f + 0.3275911f * x);
+    const float e = __expf(-x * x);
+    const float poly = ((((1.061405429f * k - 1.453152027f) * k + 1.421413741f) * k - 0.284496736f) * k + 0.254829592f) * k;
+    const float half_erf = 0.5f - 0.5f * poly * e;
+    Phi = t >= 0.f ? 0.5f + half_erf : 0.5f - half_erf;
+    phi = 0.39894228040143268f * e;
 }
 
-hipError_t launch_astl_mlp_bwd(long, int, int, float, const bf16_t *, const bf16_t *, const bf16_t *, const bf16_t *,
-                               const bf16_t *, const bf16_t *, const bf16_t *, bf16_t *, float *, float *, float *,
-                               float *, float *, float *, long, int, void *, hipStream_t)
+__device__ __forceinline__ float bf(const bf16_t *p, long i) { return __uint_as_float((uint32_t)p[i].bits << 16); }
+
+// channel (or hidden feature) a lane's k-slot j of step s stands for
+__device__ __forceinline__ int slot_index(int s, int q, int j) { return 16 * (2 * s + (j >> 2)) + 4 * q + (j & 3); }
+
+// Fragments of a weight matrix as the A operand: tile `mt` of 16 output rows, k-step `s`;
+// get(m, k) returns the entry for output row m and reduction index k (zero outside the matrix).
+template <typename F>
+__device__ __forceinline__ void build_frags(uint4 *dst, int mtiles, int ksteps, F get)
 {
-    return hipErrorNotSupported;
+    uint16_t *d16 = reinterpret_cast<uint16_t *>(dst);
+    const int total = mtiles * ksteps * 512;
+    for (int e = blockIdx.x * kMlpThreads + threadIdx.x; e < total; e += gridDim.x * kMlpThreads) {
+        const int j = e & 7, l = (e >> 3) & 63, fr = e >> 9;
+        const int s = fr % ksteps, mt = fr / ksteps;
+        d16[e] = f32_to_bf16_bits(get(16 * mt + (l & 15), slot_index(s, l >> 4, j)));
+    }
+}
+
+struct MlpArgs {
+    long rows;
+    int C, Hd;
+    float eps;
+    const bf16_t *x, *a;       // forward: x1 = x + a;  backward: x = x1, a = dy
+    const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+    bf16_t *x1, *y;            // forward outputs;  backward: y = dx1
+    bf16_t *h, *dpre, *x1n;    // backward: [rows, Hd], [rows, Hd], [rows, C] for the weight gradients
+    float *dln_w, *dln_b;      // backward: copy 0 of `reps` copies rep_stride floats apart
+    void *pack;                // weights in fragment order, written by the pack kernel
+    long rep_stride;
+    int reps;
+};
+
+// Layout of the packed weights (uint4 units, then floats), shared by the three kernels:
+//   w1f [FT][KSC][64]  W1 diag(gamma)  rows = features, k = channels      (both passes)
+//   w2f [CT][KSF][64]  W2              rows = channels, k = features      (forward)
+//   w2t [FT][KSC][64]  W2^T            rows = features, k = channels      (backward)
+//   w1t [CT][KSF][64]  W1^T            rows = channels, k = features      (backward)
+//   b1s [FT * 16]      b1 + W1 beta;   b2s [CT * 16]
+template <int KSC, int KSF> struct PackLayout {
+    static constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    static constexpr int frag = FT * KSC * 64; // uint4 per weight matrix (CT * KSF * 64 is the same number)
+    static constexpr int w1f = 0, w2f = frag, w2t = 2 * frag, w1t = 3 * frag;
+    static constexpr int floats_at = 4 * frag; // in uint4 units
+    static constexpr int nfloats = (FT + CT) * 16;
+    static constexpr size_t bytes = (size_t)4 * frag * 16 + (size_t)nfloats * 4;
+};
+
+// Once per forward call: the MLP's weights into MFMA fragment order (gamma and beta of LN_2 folded
+// into the first layer); the backward pass reads the same pack.
+template <int KSC, int KSF>
+__global__ __launch_bounds__(kMlpThreads) void astl_mlp_pack_kernel(MlpArgs a)
+{
+    using L = PackLayout<KSC, KSF>;
+    constexpr int CT = L::CT, FT = L::FT;
+    uint4 *pk = static_cast<uint4 *>(a.pack);
+    const int C = a.C, Hd = a.Hd;
+    build_frags(pk + L::w1f, FT, KSC, [&](int f, int c) { return (f < Hd && c < C) ? bf(a.w_fc1, (long)f * C + c) * bf(a.ln_w, c) : 0.f; });
+    build_frags(pk + L::w2f, CT, KSF, [&](int c, int f) { return (f < Hd && c < C) ? bf(a.w_fc2, (long)c * Hd + f) : 0.f; });
+    build_frags(pk + L::w2t, FT, KSC, [&](int f, int c) { return (f < Hd && c < C) ? bf(a.w_fc2, (long)c * Hd + f) : 0.f; });
+    build_frags(pk + L::w1t, CT, KSF, [&](int c, int f) { return (f < Hd && c < C) ? bf(a.w_fc1, (long)f * C + c) : 0.f; });
+    float *fl = reinterpret_cast<float *>(pk + L::floats_at);
+    // b1 + W1 beta: one wavefront per feature
+    const int lane = threadIdx.x & 63;
+    for (int f = blockIdx.x * kMlpWaves + (threadIdx.x >> 6); f < FT * 16; f += gridDim.x * kMlpWaves) {
+        float s = 0.f;
+        if (f < Hd)
+            for (int c = lane; c < C; c += 64) s += bf(a.w_fc1, (long)f * C + c) * bf(a.ln_b, c);
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) s += __shfl_xor(s, m);
+        if (lane == 0) fl[f] = f < Hd ? s + bf(a.b_fc1, f) : 0.f;
+    }
+    for (int c = blockIdx.x * kMlpThreads + threadIdx.x; c < CT * 16; c += gridDim.x * kMlpThreads)
+        fl[FT * 16 + c] = c < C ? bf(a.b_fc2, c) : 0.f;
+}
+
+// copies `n` uint4 from the pack into LDS
+__device__ __forceinline__ void stage(uint4 *dst, const uint4 *src, int n)
+{
+    for (int e = threadIdx.x; e < n; e += blockDim.x) dst[e] = src[e];
+}
+
+template <int CT>
+struct Row {
+    float v[CT][4];
+};
+
+// the same row as loaded: four bf16 per channel tile
+template <int CT>
+struct Raw {
+    uint2 v[CT];
+};
+
+// 8-byte loads of a token's channels in the lane's ownership pattern (zero beyond C or the rows)
+template <int CT>
+__device__ __forceinline__ void load_raw(const bf16_t *base, long t, bool ok, int C, int q, Raw<CT> &r)
+{
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int c = 16 * ct + 4 * q;
+        r.v[ct] = make_uint2(0u, 0u);
+        if (ok && c < C) r.v[ct] = *reinterpret_cast<const uint2 *>(base + t * C + c);
+    }
+}
+
+template <int CT>
+__device__ __forceinline__ void widen(const Raw<CT> &u, Row<CT> &r)
+{
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        r.v[ct][0] = bf16_lo(u.v[ct].x); r.v[ct][1] = bf16_hi(u.v[ct].x);
+        r.v[ct][2] = bf16_lo(u.v[ct].y); r.v[ct][3] = bf16_hi(u.v[ct].y);
+    }
+}
+
+template <int CT>
+__device__ __forceinline__ void load_own(const bf16_t *base, long t, bool ok, int C, int q, Row<CT> &r)
+{
+    Raw<CT> u;
+    load_raw<CT>(base, t, ok, C, q, u);
+    widen<CT>(u, r);
+}
+
+template <int CT>
+__device__ __forceinline__ void store_own(bf16_t *base, long t, bool ok, int C, int q, const Row<CT> &r)
+{
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int c = 16 * ct + 4 * q;
+        if (ok && c < C)
+            *reinterpret_cast<uint2 *>(base + t * C + c) =
+                make_uint2(pack_bf16x2(r.v[ct][0], r.v[ct][1]), pack_bf16x2(r.v[ct][2], r.v[ct][3]));
+    }
+}
+
+// normalised row (zero in the padding channels) and 1/sqrt(var + eps)
+template <int CT>
+__device__ __forceinline__ float normalise(const Row<CT> &u, int C, int q, float eps, Row<CT> &xh)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s += u.v[ct][i];
+    const float mean = qgroup_sum(s) / (float)C;
+    float v = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const bool in = 16 * ct + 4 * q < C;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            xh.v[ct][i] = in ? u.v[ct][i] - mean : 0.f;
+            v += xh.v[ct][i] * xh.v[ct][i];
+        }
+    }
+    const float rstd = rsqrtf(qgroup_sum(v) / (float)C + eps);
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xh.v[ct][i] *= rstd;
+    return rstd;
+}
+
+// B operand of k-step s from a row in the ownership pattern
+template <int CT>
+__device__ __forceinline__ uint4 b_frag(const Row<CT> &r, int s)
+{
+    return make_uint4(pack_bf16x2(r.v[2 * s][0], r.v[2 * s][1]), pack_bf16x2(r.v[2 * s][2], r.v[2 * s][3]),
+                      pack_bf16x2(r.v[2 * s + 1][0], r.v[2 * s + 1][1]), pack_bf16x2(r.v[2 * s + 1][2], r.v[2 * s + 1][3]));
+}
+
+template <int KSC, int KSF>
+__global__ __launch_bounds__(kFwdThreads) void astl_mlp_fwd_kernel(MlpArgs a)
+{
+    constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4 *w1f = reinterpret_cast<uint4 *>(smem);  // [FT][KSC][64]  W1 diag(gamma)
+    uint4 *w2f = w1f + FT * KSC * 64;              // [CT][KSF][64]  W2
+    float *b1s = reinterpret_cast<float *>(w2f + CT * KSF * 64); // [FT * 16]  b1 + W1 beta
+    float *b2s = b1s + FT * 16;                    // [CT * 16]
+    const int C = a.C;
+    {
+        using L = PackLayout<KSC, KSF>;
+        const uint4 *pk = static_cast<const uint4 *>(a.pack);
+        stage(w1f, pk + L::w1f, 2 * L::frag);                        // w1f and w2f lie back to back
+        stage(reinterpret_cast<uint4 *>(b1s), pk + L::floats_at, L::nfloats / 4);
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tok = lane & 15, q = lane >> 4;
+    const long ntiles = (a.rows + 15) / 16;
+    const long tstep = (long)gridDim.x * kFwdWaves;
+    long tile = (long)blockIdx.x * kFwdWaves + wave;
+    Raw<CT> rx, ra;
+    load_raw<CT>(a.x, tile * 16 + tok, tile * 16 + tok < a.rows, C, q, rx);
+    load_raw<CT>(a.a, tile * 16 + tok, tile * 16 + tok < a.rows, C, q, ra);
+    for (; tile < ntiles; tile += tstep) {
+        const long t = tile * 16 + tok;
+        const bool ok = t < a.rows;
+        // (an offset the compiler cannot see through keeps the fragment reads inside the loop
+        // instead of pinning every fragment in registers for the whole kernel)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        Row<CT> x1, av, xh;
+        widen<CT>(rx, x1);
+        widen<CT>(ra, av);
+        {   // the next tile's rows are on their way while this one is computed
+            const long tn = t + tstep * 16;
+            load_raw<CT>(a.x, tn, tn < a.rows, C, q, rx);
+            load_raw<CT>(a.a, tn, tn < a.rows, C, q, ra);
+        }
+        // Eq. 4's skip; the stored (rounded) sum is what LN_2 sees here and in the backward pass
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t u = pack_bf16x2(x1.v[ct][i] + av.v[ct][i], 0.f);
+                x1.v[ct][i] = bf16_lo(u);
+            }
+        store_own<CT>(a.x1, t, ok, C, q, x1);
+        normalise<CT>(x1, C, q, a.eps, xh);
+        uint4 bx[KSC];
+#pragma unroll
+        for (int s = 0; s < KSC; ++s) bx[s] = b_frag<CT>(xh, s);
+        // hidden layer, transposed: features 16 ft + 4q + i of token tok
+        uint2 hp[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSC; ++s) acc = mma32(w1f[(ft * KSC + s) * 64 + ln], bx[s], acc);
+            const float4 b1 = *reinterpret_cast<const float4 *>(b1s + 16 * ft + (ln >> 4) * 4);
+            const float pre[4] = {acc[0] + b1.x, acc[1] + b1.y, acc[2] + b1.z, acc[3] + b1.w};
+            float h[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float Phi, phi;
+                gauss(pre[i], Phi, phi);
+                h[i] = pre[i] * Phi;
+            }
+            hp[ft] = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+        }
+        // second layer and the skip of Eq. 5
+        Row<CT> y;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSF; ++s)
+                acc = mma32(w2f[(ct * KSF + s) * 64 + ln],
+                            make_uint4(hp[2 * s].x, hp[2 * s].y, hp[2 * s + 1].x, hp[2 * s + 1].y), acc);
+            const float4 b2 = *reinterpret_cast<const float4 *>(b2s + 16 * ct + (ln >> 4) * 4);
+            y.v[ct][0] = acc[0] + b2.x + x1.v[ct][0];
+            y.v[ct][1] = acc[1] + b2.y + x1.v[ct][1];
+            y.v[ct][2] = acc[2] + b2.z + x1.v[ct][2];
+            y.v[ct][3] = acc[3] + b2.w + x1.v[ct][3];
+        }
+        store_own<CT>(a.y, t, ok, C, q, y);
+    }
+}
+
+// Adjoint of Eq. 5 for 16 tokens per wavefront: recomputes LN_2(x1), the pre-activation and the
+// hidden layer as the forward does, then dh^T = W2^T dy^T, through the GELU, dLN^T = W1^T dpre^T,
+// LayerNorm's adjoint and the skip.  The hidden layer, its gradient and LN_2(x1) are written out
+// for the two weight-gradient products, which reduce over tokens.
+template <int KSC, int KSF>
+__global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
+{
+    constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4 *w1f = reinterpret_cast<uint4 *>(smem);  // [FT][KSC][64]  W1 diag(gamma): rows = features, k = channels
+    uint4 *w2t = w1f + FT * KSC * 64;              // [FT][KSC][64]  W2^T:            rows = features, k = channels
+    uint4 *w1t = w2t + FT * KSC * 64;              // [CT][KSF][64]  W1^T:            rows = channels, k = features
+    float *b1s = reinterpret_cast<float *>(w1t + CT * KSF * 64); // [FT * 16]
+    float *red = b1s + FT * 16;                    // [kMlpWaves][2][CT * 16]
+    const int C = a.C, Hd = a.Hd;
+    {
+        using L = PackLayout<KSC, KSF>;
+        const uint4 *pk = static_cast<const uint4 *>(a.pack);
+        stage(w1f, pk + L::w1f, L::frag);
+        stage(w2t, pk + L::w2t, 2 * L::frag);                        // w2t and w1t lie back to back
+        stage(reinterpret_cast<uint4 *>(b1s), pk + L::floats_at, FT * 16 / 4);
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tok = lane & 15, q = lane >> 4;
+    Row<CT> gam, bet, acc_g, acc_b;
+    load_own<CT>(a.ln_w, 0, true, C, q, gam);
+    load_own<CT>(a.ln_b, 0, true, C, q, bet);
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc_g.v[ct][i] = acc_b.v[ct][i] = 0.f;
+
+    const long ntiles = (a.rows + 15) / 16;
+    for (long tile = (long)blockIdx.x * kMlpWaves + wave; tile < ntiles; tile += (long)gridDim.x * kMlpWaves) {
+        const long t = tile * 16 + tok;
+        const bool ok = t < a.rows;
+        // (an offset the compiler cannot see through keeps the fragment reads inside the loop
+        // instead of pinning every fragment in registers for the whole kernel)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        Row<CT> x1, dy, xh;
+        load_own<CT>(a.x, t, ok, C, q, x1);
+        load_own<CT>(a.a, t, ok, C, q, dy);
+        const float rstd = normalise<CT>(x1, C, q, a.eps, xh);
+        uint4 bx[KSC], bd[KSC];
+#pragma unroll
+        for (int s = 0; s < KSC; ++s) {
+            bx[s] = b_frag<CT>(xh, s);
+            bd[s] = b_frag<CT>(dy, s);
+        }
+        {   // LN_2(x1) for the weight gradient of the first layer
+            Row<CT> xn;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xn.v[ct][i] = xh.v[ct][i] * gam.v[ct][i] + bet.v[ct][i];
+            store_own<CT>(a.x1n, t, ok, C, q, xn);
+        }
+        uint2 dp[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, dh = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSC; ++s) {
+                acc = mma32(w1f[(ft * KSC + s) * 64 + ln], bx[s], acc);
+                dh = mma32(w2t[(ft * KSC + s) * 64 + ln], bd[s], dh);
+            }
+            const float4 b1 = *reinterpret_cast<const float4 *>(b1s + 16 * ft + (ln >> 4) * 4);
+            const float pre[4] = {acc[0] + b1.x, acc[1] + b1.y, acc[2] + b1.z, acc[3] + b1.w};
+            float h[4], dpre[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float Phi, phi;
+                gauss(pre[i], Phi, phi);
+                h[i] = pre[i] * Phi;
+                dpre[i] = dh[i] * (Phi + pre[i] * phi);
+            }
+            dp[ft] = make_uint2(pack_bf16x2(dpre[0], dpre[1]), pack_bf16x2(dpre[2], dpre[3]));
+            const int f0 = 16 * ft + 4 * q;
+            if (ok && f0 < Hd) {
+                *reinterpret_cast<uint2 *>(a.h + t * Hd + f0) = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+                *reinterpret_cast<uint2 *>(a.dpre + t * Hd + f0) = dp[ft];
+            }
+        }
+        // gradient at LN_2's output, then through the LayerNorm, plus the skip of Eq. 5
+        Row<CT> dxh;
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            f32x4 dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSF; ++s)
+                dn = mma32(w1t[(ct * KSF + s) * 64 + ln],
+                           make_uint4(dp[2 * s].x, dp[2 * s].y, dp[2 * s + 1].x, dp[2 * s + 1].y), dn);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d = ok ? dn[i] : 0.f;
+                acc_g.v[ct][i] += d * xh.v[ct][i];
+                acc_b.v[ct][i] += d;
+                dxh.v[ct][i] = d * gam.v[ct][i];
+                s1 += dxh.v[ct][i];
+                s2 += dxh.v[ct][i] * xh.v[ct][i];
+            }
+        }
+        s1 = qgroup_sum(s1) / (float)C;
+        s2 = qgroup_sum(s2) / (float)C;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                dxh.v[ct][i] = rstd * (dxh.v[ct][i] - s1 - xh.v[ct][i] * s2) + dy.v[ct][i];
+        store_own<CT>(a.y, t, ok, C, q, dxh);
+    }
+
+    // d gamma, d beta: over the 16 tokens of the wave, the waves of the workgroup, then one add
+    // per channel into the workgroup's copy
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float g = acc_g.v[ct][i], b = acc_b.v[ct][i];
+#pragma unroll
+            for (int m = 1; m < 16; m <<= 1) {
+                g += __shfl_xor(g, m);
+                b += __shfl_xor(b, m);
+            }
+            if (tok == 0) {
+                red[(wave * 2 + 0) * CT * 16 + 16 * ct + 4 * q + i] = g;
+                red[(wave * 2 + 1) * CT * 16 + 16 * ct + 4 * q + i] = b;
+            }
+        }
+    __syncthreads();
+    const long rep = (long)(blockIdx.x % (unsigned)a.reps) * a.rep_stride;
+    for (int e = threadIdx.x; e < 2 * CT * 16; e += kMlpThreads) {
+        const int which = e / (CT * 16), c = e % (CT * 16);
+        if (c >= C) continue;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMlpWaves; ++w) s += red[(w * 2 + which) * CT * 16 + c];
+        atomicAdd((which ? a.dln_b : a.dln_w) + rep + c, s);
+    }
+}
+
+unsigned mlp_blocks(long rows, int waves)
+{
+    const long tiles = (rows + 15) / 16;
+    long b = (tiles + waves - 1) / waves;
+    if (b > 512) b = 512;
+    return (unsigned)(b < 1 ? 1 : b);
+}
+
+template <int KSC, int KSF> size_t fwd_lds()
+{
+    return (size_t)(2 * KSF * KSC + 2 * KSC * KSF) * 1024 + (size_t)(2 * KSF + 2 * KSC) * 16 * sizeof(float);
+}
+template <int KSC, int KSF> size_t bwd_lds()
+{
+    return (size_t)(3 * 2 * KSF * KSC) * 1024 + (size_t)(2 * KSF * 16 + kMlpWaves * 2 * 2 * KSC * 16) * sizeof(float);
+}
+
+template <int KSC, int KSF> hipError_t launch_fwd_t(const MlpArgs &a, hipStream_t s)
+{
+    {
+        KernelTimer kt(K_MLP_PACK, s);
+        hipLaunchKernelGGL((astl_mlp_pack_kernel<KSC, KSF>), dim3(32), dim3(kMlpThreads), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    auto kern = astl_mlp_fwd_kernel<KSC, KSF>;
+    const size_t lds = fwd_lds<KSC, KSF>();
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    KernelTimer kt(K_MLP_FWD, s);
+    hipLaunchKernelGGL(kern, dim3(mlp_blocks(a.rows, kFwdWaves)), dim3(kFwdThreads), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int KSC, int KSF> hipError_t launch_bwd_t(const MlpArgs &a, hipStream_t s)
+{
+    auto kern = astl_mlp_bwd_kernel<KSC, KSF>;
+    const size_t lds = bwd_lds<KSC, KSF>();
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    KernelTimer kt(K_MLP_BWD, s);
+    hipLaunchKernelGGL(kern, dim3(mlp_blocks(a.rows, kMlpWaves)), dim3(kMlpThreads), lds, s, a);
+    return hipGetLastError();
+}
+
+size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+
+} // namespace
+
+bool astl_mlp_supported(int C, int hidden)
+{
+    return C >= 4 && C <= 64 && C % 4 == 0 && hidden >= 4 && hidden <= 128 && hidden % 4 == 0;
+}
+
+hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
+                               const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
+                               const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
+                               hipStream_t s)
+{
+    if (!astl_mlp_supported(C, hidden)) return hipErrorInvalidValue;
+    MlpArgs m{};
+    m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
+    m.x = x; m.a = a; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2; m.b_fc2 = b_fc2;
+    m.x1 = x1; m.y = y; m.pack = pack;
+    if (C <= 32) return hidden <= 64 ? launch_fwd_t<1, 2>(m, s) : launch_fwd_t<1, 4>(m, s);
+    return hidden <= 64 ? launch_fwd_t<2, 2>(m, s) : launch_fwd_t<2, 4>(m, s);
+}
+
+size_t astl_mlp_pack_bytes() { return align256(PackLayout<2, 4>::bytes); }
+
+size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden)
+{
+    return 2 * align256((size_t)rows * hidden * 2) + align256((size_t)rows * C * 2);
+}
+
+hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
+                               const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
+                               const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
+                               float *db_fc2, float *dln_w, float *dln_b, long rep_stride, int reps,
+                               const void *pack, void *ws, hipStream_t s)
+{
+    if (!astl_mlp_supported(C, hidden) || reps < 1) return hipErrorInvalidValue;
+    char *w = static_cast<char *>(ws);
+    const size_t hid = align256((size_t)rows * hidden * 2);
+    MlpArgs m{};
+    m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
+    m.x = x1; m.a = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
+    m.y = dx1;
+    m.h = reinterpret_cast<bf16_t *>(w); m.dpre = reinterpret_cast<bf16_t *>(w + hid);
+    m.x1n = reinterpret_cast<bf16_t *>(w + 2 * hid);
+    m.dln_w = dln_w; m.dln_b = dln_b; m.rep_stride = rep_stride; m.reps = reps;
+    m.pack = const_cast<void *>(pack);
+    hipError_t e;
+    if (C <= 32) e = hidden <= 64 ? launch_bwd_t<1, 2>(m, s) : launch_bwd_t<1, 4>(m, s);
+    else e = hidden <= 64 ? launch_bwd_t<2, 2>(m, s) : launch_bwd_t<2, 4>(m, s);
+    if (e != hipSuccess) return e;
+    // the two products that reduce over tokens: d Wfc2 = dy^T h, d Wfc1 = dpre^T LN_2(x1)
+    WgradArgs w2{};
+    w2.dout = dy; w2.lddout = C; w2.a1 = m.h; w2.lda1 = hidden;
+    w2.dw = dw_fc2; w2.db = db_fc2; w2.rep_stride = rep_stride; w2.reps = reps;
+    w2.rows = rows; w2.N = C; w2.K = hidden; w2.prof_id = K_FC_WGRAD;
+    e = launch_wgrad<bf16_t>(w2, s);
+    if (e != hipSuccess) return e;
+    WgradArgs w1{};
+    w1.dout = m.dpre; w1.lddout = hidden; w1.a1 = m.x1n; w1.lda1 = C;
+    w1.dw = dw_fc1; w1.db = db_fc1; w1.rep_stride = rep_stride; w1.reps = reps;
+    w1.rows = rows; w1.N = hidden; w1.K = C; w1.prof_id = K_FC_WGRAD;
+    return launch_wgrad<bf16_t>(w1, s);
 }
 
 } // namespace gswa

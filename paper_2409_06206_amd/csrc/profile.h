@@ -37,6 +37,7 @@ enum KernelId {
     K_FC_WGRAD,     // gradient of its weight and bias
     K_MLP_FWD,      // skip of Eq. 4 and all of Eq. 5 in one launch
     K_MLP_BWD,      // adjoint of Eq. 5 in one launch
+    K_MLP_PACK,     // the MLP's weights into MFMA fragment order (once per forward call)
     K_COUNT
 };
 
