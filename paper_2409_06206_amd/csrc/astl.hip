@@ -325,7 +325,7 @@ struct Plan {
     size_t params;                // fp32 entries of one copy of this file's parameter gradients
     size_t reps;                  // bytes of the kGradReplicas copies
     size_t pack;                  // bytes of the MLP's repacked weights at the end of `saved` (fused MLP)
-    bool fused_mlp;
+    bool fused_mlp, fused_mlp_bwd;
 };
 
 int make_plan(const astl_desc *d, Plan *p)
@@ -343,6 +343,7 @@ int make_plan(const astl_desc *d, Plan *p)
     p->hid = align256((size_t)p->T * p->Hd * p->e);
     p->fused_mlp = d->attn.dtype == GSWA_BF16 && !(d->attn.flags & GSWA_FORCE_STAGED) &&
                    astl_mlp_supported(p->C, p->Hd);
+    p->fused_mlp_bwd = p->fused_mlp && astl_mlp_bwd_supported(p->C, p->Hd);
     p->params = 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
     p->reps = align256(kGradReplicas * p->params * sizeof(float));
     p->pack = p->fused_mlp ? astl_mlp_pack_bytes() : 0;
@@ -351,7 +352,7 @@ int make_plan(const astl_desc *d, Plan *p)
     const size_t hid_f = p->fused_mlp ? 0 : 2 * p->hid;
     p->fwd_ws = 2 * p->act + (p->at_fws > hid_f ? p->at_fws : hid_f);
     // backward: xn | dn | dx1 | max(pre | h | dh, attention scratch) | copies of the gradients
-    const size_t hid_b = p->fused_mlp ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd) : 3 * p->hid;
+    const size_t hid_b = p->fused_mlp_bwd ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd) : 3 * p->hid;
     p->bwd_ws = 3 * p->act + (p->at_bws > hid_b ? p->at_bws : hid_b) + p->reps;
     return GSWA_OK;
 }
@@ -440,7 +441,7 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     ASTL_HIP(launch_fill_zero(z, st));
 
     // Eq. 5 backwards
-    if (pl.fused_mlp) {
+    if (pl.fused_mlp_bwd) {
         ASTL_HIP(launch_astl_mlp_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
                                      (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,

@@ -18,11 +18,16 @@ hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf
                                const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
                                hipStream_t s);
 
-// Scratch bytes of the backward (hidden layer and its gradient for the weight-gradient products).
+// The backward kernel also needs one unused channel and one unused hidden feature in its padded
+// tiles (C not a multiple of 32, hidden not a multiple of 64): the bias sums ride there.
+bool astl_mlp_bwd_supported(int C, int hidden);
+
+// Scratch bytes of the backward (one pair of partial weight-gradient matrices per workgroup).
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden);
 
-// dx1 = dy + adjoint of MLP(LN_2(.)) at x1; the six parameter gradients are added into copy
-// `workgroup mod reps` of `reps` copies rep_stride floats apart (each pointer is its place in copy 0).
+// dx1 = dy + adjoint of MLP(LN_2(.)) at x1.  The gradients of the two fully connected layers are
+// WRITTEN into copy 0 of `reps` gradient copies rep_stride floats apart (each pointer is its place
+// in copy 0), those of the LayerNorm are added into copy `workgroup mod reps`.
 // `pack` is what the forward call of the same layer wrote.
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,

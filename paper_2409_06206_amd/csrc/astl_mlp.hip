@@ -67,9 +67,9 @@ struct MlpArgs {
     const bf16_t *x, *a;       // forward: x1 = x + a;  backward: x = x1, a = dy
     const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
     bf16_t *x1, *y;            // forward outputs;  backward: y = dx1
-    bf16_t *h, *dpre, *x1n;    // backward: [rows, Hd], [rows, Hd], [rows, C] for the weight gradients
     float *dln_w, *dln_b;      // backward: copy 0 of `reps` copies rep_stride floats apart
     void *pack;                // weights in fragment order, written by the pack kernel
+    float *part;               // backward: one pair of partial weight-gradient matrices per workgroup
     long rep_stride;
     int reps;
 };
@@ -302,20 +302,55 @@ __global__ __launch_bounds__(kFwdThreads) void astl_mlp_fwd_kernel(MlpArgs a)
     }
 }
 
-// Adjoint of Eq. 5 for 16 tokens per wavefront: recomputes LN_2(x1), the pre-activation and the
-// hidden layer as the forward does, then dh^T = W2^T dy^T, through the GELU, dLN^T = W1^T dpre^T,
-// LayerNorm's adjoint and the skip.  The hidden layer, its gradient and LN_2(x1) are written out
-// for the two weight-gradient products, which reduce over tokens.
+// Adjoint of Eq. 5.  A workgroup of eight wavefronts takes 128 tokens per round, 16 per wave.
+// Phase 1, per wave: recompute LN_2(x1), the pre-activation and the hidden layer exactly as the
+// forward does, dh^T = W2^T dy^T, through the GELU, dLN^T = W1^T dpre^T, LayerNorm's adjoint and
+// the skip -> dx1.  The four matrices the weight gradients need go to LDS feature-major with the
+// round's tokens contiguous: h^T, dpre^T, LN_2(x1)^T and dy^T.
+// Phase 2, after a barrier: the products that reduce over tokens,
+//   M1[f][c] = sum_t dpre[t][f] LN_2(x1)[t][c] = d Wfc1,      M2[f][c] = sum_t h[t][f] dy[t][c] = d Wfc2^T,
+// wave w owning feature tile w of both (8 accumulator tiles, kept in registers over all rounds).
+// The unused last channel row of LN_2(x1)^T and the unused last feature row of h^T hold ones, so
+// that M1[:, last] = d bfc1 and M2[last, :] = d bfc2 come out of the same products.
+// Every workgroup stores its sums; a second kernel adds them up.
+constexpr int kBwdThreads = 512;
+constexpr int kBwdWaves = kBwdThreads / 64;
+constexpr int kTokPitch = 272;   // bytes per staged row: 128 tokens of bf16 + 16 (conflict-free 16-byte reads)
+
+template <int KSC, int KSF> struct BwdLds {
+    static constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    static constexpr size_t frags = (size_t)3 * FT * KSC * 1024;
+    static constexpr size_t b1 = frags;
+    static constexpr size_t red = b1 + (size_t)FT * 16 * 4;
+    static constexpr size_t hT = red + (size_t)kBwdWaves * 2 * CT * 16 * 4;
+    static constexpr size_t dpT = hT + (size_t)FT * 16 * kTokPitch;
+    static constexpr size_t xnT = dpT + (size_t)FT * 16 * kTokPitch;
+    static constexpr size_t dyT = xnT + (size_t)CT * 16 * kTokPitch;
+    static constexpr size_t bytes = dyT + (size_t)CT * 16 * kTokPitch;
+};
+
+// four values of rows r0 .. r0+3, column `col`, into a staged matrix
+__device__ __forceinline__ void stage4(unsigned char *m, int r0, int col, uint2 packed)
+{
+    uint16_t *p = reinterpret_cast<uint16_t *>(m + (size_t)r0 * kTokPitch) + col;
+    p[0] = (uint16_t)packed.x;
+    p[kTokPitch / 2] = (uint16_t)(packed.x >> 16);
+    p[2 * (kTokPitch / 2)] = (uint16_t)packed.y;
+    p[3 * (kTokPitch / 2)] = (uint16_t)(packed.y >> 16);
+}
+
 template <int KSC, int KSF>
-__global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
+__global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
 {
     constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    using S = BwdLds<KSC, KSF>;
     extern __shared__ __align__(16) unsigned char smem[];
     uint4 *w1f = reinterpret_cast<uint4 *>(smem);  // [FT][KSC][64]  W1 diag(gamma): rows = features, k = channels
     uint4 *w2t = w1f + FT * KSC * 64;              // [FT][KSC][64]  W2^T:            rows = features, k = channels
     uint4 *w1t = w2t + FT * KSC * 64;              // [CT][KSF][64]  W1^T:            rows = channels, k = features
-    float *b1s = reinterpret_cast<float *>(w1t + CT * KSF * 64); // [FT * 16]
-    float *red = b1s + FT * 16;                    // [kMlpWaves][2][CT * 16]
+    float *b1s = reinterpret_cast<float *>(smem + S::b1);   // [FT * 16]
+    float *red = reinterpret_cast<float *>(smem + S::red);  // [kBwdWaves][2][CT * 16]
+    unsigned char *hT = smem + S::hT, *dpT = smem + S::dpT, *xnT = smem + S::xnT, *dyT = smem + S::dyT;
     const int C = a.C, Hd = a.Hd;
     {
         using L = PackLayout<KSC, KSF>;
@@ -334,18 +369,32 @@ __global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc_g.v[ct][i] = acc_b.v[ct][i] = 0.f;
+    f32x4 m1[CT], m2[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) m1[ct] = m2[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const long ntiles = (a.rows + 15) / 16;
-    for (long tile = (long)blockIdx.x * kMlpWaves + wave; tile < ntiles; tile += (long)gridDim.x * kMlpWaves) {
+    const long rounds = (ntiles + (long)gridDim.x * kBwdWaves - 1) / ((long)gridDim.x * kBwdWaves);
+    long tile = (long)blockIdx.x * rounds * kBwdWaves + wave;   // a workgroup's tiles are consecutive
+    Raw<CT> rx, rd;
+    load_raw<CT>(a.x, tile * 16 + tok, tile * 16 + tok < a.rows, C, q, rx);
+    load_raw<CT>(a.a, tile * 16 + tok, tile * 16 + tok < a.rows, C, q, rd);
+    for (long r = 0; r < rounds; ++r, tile += kBwdWaves) {
         const long t = tile * 16 + tok;
         const bool ok = t < a.rows;
-        // (an offset the compiler cannot see through keeps the fragment reads inside the loop
-        // instead of pinning every fragment in registers for the whole kernel)
-        int ln = lane;
+        int ln = lane; // (kept opaque so that the fragment reads stay inside the loop)
         asm volatile("" : "+v"(ln));
+        const int col = 16 * wave + tok;   // this token's column in the staged matrices
         Row<CT> x1, dy, xh;
-        load_own<CT>(a.x, t, ok, C, q, x1);
-        load_own<CT>(a.a, t, ok, C, q, dy);
+        widen<CT>(rx, x1);
+        widen<CT>(rd, dy);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) stage4(dyT, 16 * ct + 4 * (ln >> 4), col, rd.v[ct]);
+        {   // the next round's rows are on their way while this one is computed
+            const long tn = t + kBwdWaves * 16;
+            load_raw<CT>(a.x, tn, tn < a.rows, C, q, rx);
+            load_raw<CT>(a.a, tn, tn < a.rows, C, q, rd);
+        }
         const float rstd = normalise<CT>(x1, C, q, a.eps, xh);
         uint4 bx[KSC], bd[KSC];
 #pragma unroll
@@ -353,13 +402,13 @@ __global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
             bx[s] = b_frag<CT>(xh, s);
             bd[s] = b_frag<CT>(dy, s);
         }
-        {   // LN_2(x1) for the weight gradient of the first layer
-            Row<CT> xn;
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
+        for (int ct = 0; ct < CT; ++ct) {   // LN_2(x1), with a one in the last (unused) channel row
+            float xn[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) xn.v[ct][i] = xh.v[ct][i] * gam.v[ct][i] + bet.v[ct][i];
-            store_own<CT>(a.x1n, t, ok, C, q, xn);
+            for (int i = 0; i < 4; ++i) xn[i] = xh.v[ct][i] * gam.v[ct][i] + bet.v[ct][i];
+            if (ct == CT - 1 && q == 3) xn[3] = 1.f;
+            stage4(xnT, 16 * ct + 4 * (ln >> 4), col, make_uint2(pack_bf16x2(xn[0], xn[1]), pack_bf16x2(xn[2], xn[3])));
         }
         uint2 dp[FT];
 #pragma unroll
@@ -380,12 +429,10 @@ __global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
                 h[i] = pre[i] * Phi;
                 dpre[i] = dh[i] * (Phi + pre[i] * phi);
             }
+            if (ft == FT - 1 && q == 3) h[3] = 1.f;  // the ones row (feature FT*16 - 1 is beyond the hidden width)
             dp[ft] = make_uint2(pack_bf16x2(dpre[0], dpre[1]), pack_bf16x2(dpre[2], dpre[3]));
-            const int f0 = 16 * ft + 4 * q;
-            if (ok && f0 < Hd) {
-                *reinterpret_cast<uint2 *>(a.h + t * Hd + f0) = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-                *reinterpret_cast<uint2 *>(a.dpre + t * Hd + f0) = dp[ft];
-            }
+            stage4(hT, 16 * ft + 4 * (ln >> 4), col, make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3])));
+            stage4(dpT, 16 * ft + 4 * (ln >> 4), col, dp[ft]);
         }
         // gradient at LN_2's output, then through the LayerNorm, plus the skip of Eq. 5
         Row<CT> dxh;
@@ -415,6 +462,39 @@ __global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
             for (int i = 0; i < 4; ++i)
                 dxh.v[ct][i] = rstd * (dxh.v[ct][i] - s1 - xh.v[ct][i] * s2) + dy.v[ct][i];
         store_own<CT>(a.y, t, ok, C, q, dxh);
+
+        __syncthreads();
+        // phase 2: the round's 128 tokens in four k-steps of 32
+        if (wave < FT) {
+            const int m = ln & 15, kq = ln >> 4;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const size_t koff = (size_t)(32 * ks + 8 * kq) * 2;
+                const uint4 a1 = *reinterpret_cast<const uint4 *>(dpT + (size_t)(16 * wave + m) * kTokPitch + koff);
+                const uint4 a2 = *reinterpret_cast<const uint4 *>(hT + (size_t)(16 * wave + m) * kTokPitch + koff);
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const uint4 b1v = *reinterpret_cast<const uint4 *>(xnT + (size_t)(16 * ct + m) * kTokPitch + koff);
+                    const uint4 b2v = *reinterpret_cast<const uint4 *>(dyT + (size_t)(16 * ct + m) * kTokPitch + koff);
+                    m1[ct] = mma32(a1, b1v, m1[ct]);
+                    m2[ct] = mma32(a2, b2v, m2[ct]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // the workgroup's sums: part[workgroup][2][FT*16][CT*16]; lane holds column m, rows 4q + i
+    if (wave < FT) {
+        float *part = a.part + (size_t)blockIdx.x * 2 * FT * 16 * CT * 16;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const size_t at = (size_t)(16 * wave + 4 * q + i) * (CT * 16) + 16 * ct + tok;
+                part[at] = m1[ct][i];
+                part[(size_t)FT * 16 * CT * 16 + at] = m2[ct][i];
+            }
     }
 
     // d gamma, d beta: over the 16 tokens of the wave, the waves of the workgroup, then one add
@@ -436,13 +516,61 @@ __global__ __launch_bounds__(kMlpThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         }
     __syncthreads();
     const long rep = (long)(blockIdx.x % (unsigned)a.reps) * a.rep_stride;
-    for (int e = threadIdx.x; e < 2 * CT * 16; e += kMlpThreads) {
+    for (int e = threadIdx.x; e < 2 * CT * 16; e += kBwdThreads) {
         const int which = e / (CT * 16), c = e % (CT * 16);
         if (c >= C) continue;
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < kMlpWaves; ++w) s += red[(w * 2 + which) * CT * 16 + c];
+        for (int w = 0; w < kBwdWaves; ++w) s += red[(w * 2 + which) * CT * 16 + c];
         atomicAdd((which ? a.dln_b : a.dln_w) + rep + c, s);
+    }
+    (void)Hd;
+}
+
+// Sums the workgroups' partial matrices and writes the MLP's four parameter gradients (into copy 0
+// of the gradient copies, which nothing else touches for these parameters):
+//   d Wfc1[f][c] = M1[f][c], d bfc1[f] = M1[f][last column], d Wfc2[c][f] = M2[f][c], d bfc2[c] = M2[last row][c].
+// 32 entries per block, the workgroups in 8 slices with eight loads in flight per thread.
+struct MlpReduceArgs {
+    const float *part;
+    int nparts, rows, cols; // partial matrices are [2][rows][cols]
+    int C, Hd;
+    float *dw1, *db1, *dw2, *db2;
+};
+
+__global__ __launch_bounds__(256) void astl_mlp_reduce_kernel(MlpReduceArgs a)
+{
+    __shared__ float red[8][33];
+    const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
+    const long per = (long)2 * a.rows * a.cols;
+    const long i = (long)blockIdx.x * 32 + col;
+    float acc = 0.f;
+    if (i < per) {
+        float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int w = slice;
+        for (; w + 56 < a.nparts; w += 64) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a8[u] += a.part[(long)(w + 8 * u) * per + i];
+        }
+        for (; w < a.nparts; w += 8) a8[0] += a.part[(long)w * per + i];
+        acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+    }
+    red[slice][col] = acc;
+    __syncthreads();
+    if (slice == 0 && i < per) {
+        float sum = 0.f;
+#pragma unroll
+        for (int k8 = 0; k8 < 8; ++k8) sum += red[k8][col];
+        const int which = (int)(i / ((long)a.rows * a.cols));
+        const int rem = (int)(i % ((long)a.rows * a.cols));
+        const int f = rem / a.cols, c = rem % a.cols;
+        if (which == 0) {
+            if (f < a.Hd && c < a.C) a.dw1[(long)f * a.C + c] = sum;
+            else if (f < a.Hd && c == a.cols - 1) a.db1[f] = sum;
+        } else {
+            if (f < a.Hd && c < a.C) a.dw2[(long)c * a.Hd + f] = sum;
+            else if (f == a.rows - 1 && c < a.C) a.db2[c] = sum;
+        }
     }
 }
 
@@ -458,9 +586,13 @@ template <int KSC, int KSF> size_t fwd_lds()
 {
     return (size_t)(2 * KSF * KSC + 2 * KSC * KSF) * 1024 + (size_t)(2 * KSF + 2 * KSC) * 16 * sizeof(float);
 }
-template <int KSC, int KSF> size_t bwd_lds()
+constexpr int kBwdMaxBlocks = 256; // one workgroup per compute unit (its LDS need allows no second one)
+unsigned bwd_blocks(long rows)
 {
-    return (size_t)(3 * 2 * KSF * KSC) * 1024 + (size_t)(2 * KSF * 16 + kMlpWaves * 2 * 2 * KSC * 16) * sizeof(float);
+    const long tiles = (rows + 15) / 16;
+    long b = (tiles + kBwdWaves - 1) / kBwdWaves;
+    if (b > kBwdMaxBlocks) b = kBwdMaxBlocks;
+    return (unsigned)(b < 1 ? 1 : b);
 }
 
 template <int KSC, int KSF> hipError_t launch_fwd_t(const MlpArgs &a, hipStream_t s)
@@ -487,7 +619,7 @@ template <int KSC, int KSF> hipError_t launch_fwd_t(const MlpArgs &a, hipStream_
 template <int KSC, int KSF> hipError_t launch_bwd_t(const MlpArgs &a, hipStream_t s)
 {
     auto kern = astl_mlp_bwd_kernel<KSC, KSF>;
-    const size_t lds = bwd_lds<KSC, KSF>();
+    const size_t lds = BwdLds<KSC, KSF>::bytes;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -495,7 +627,7 @@ template <int KSC, int KSF> hipError_t launch_bwd_t(const MlpArgs &a, hipStream_
         attr_done = true;
     }
     KernelTimer kt(K_MLP_BWD, s);
-    hipLaunchKernelGGL(kern, dim3(mlp_blocks(a.rows, kMlpWaves)), dim3(kMlpThreads), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(bwd_blocks(a.rows)), dim3(kBwdThreads), lds, s, a);
     return hipGetLastError();
 }
 
@@ -524,9 +656,17 @@ hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf
 
 size_t astl_mlp_pack_bytes() { return align256(PackLayout<2, 4>::bytes); }
 
+// the backward needs a spare channel row and a spare feature row for the bias sums
+bool astl_mlp_bwd_supported(int C, int hidden)
+{
+    return astl_mlp_supported(C, hidden) && C % 32 != 0 && hidden % 64 != 0;
+}
+
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden)
 {
-    return 2 * align256((size_t)rows * hidden * 2) + align256((size_t)rows * C * 2);
+    (void)rows;
+    const size_t ct16 = C <= 32 ? 32 : 64, ft16 = hidden <= 64 ? 64 : 128;
+    return align256((size_t)kBwdMaxBlocks * 2 * ft16 * ct16 * sizeof(float));
 }
 
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
@@ -535,33 +675,27 @@ hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf
                                float *db_fc2, float *dln_w, float *dln_b, long rep_stride, int reps,
                                const void *pack, void *ws, hipStream_t s)
 {
-    if (!astl_mlp_supported(C, hidden) || reps < 1) return hipErrorInvalidValue;
-    char *w = static_cast<char *>(ws);
-    const size_t hid = align256((size_t)rows * hidden * 2);
+    if (!astl_mlp_bwd_supported(C, hidden) || reps < 1) return hipErrorInvalidValue;
     MlpArgs m{};
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x = x1; m.a = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
     m.y = dx1;
-    m.h = reinterpret_cast<bf16_t *>(w); m.dpre = reinterpret_cast<bf16_t *>(w + hid);
-    m.x1n = reinterpret_cast<bf16_t *>(w + 2 * hid);
     m.dln_w = dln_w; m.dln_b = dln_b; m.rep_stride = rep_stride; m.reps = reps;
     m.pack = const_cast<void *>(pack);
+    m.part = static_cast<float *>(ws);
     hipError_t e;
     if (C <= 32) e = hidden <= 64 ? launch_bwd_t<1, 2>(m, s) : launch_bwd_t<1, 4>(m, s);
     else e = hidden <= 64 ? launch_bwd_t<2, 2>(m, s) : launch_bwd_t<2, 4>(m, s);
     if (e != hipSuccess) return e;
-    // the two products that reduce over tokens: d Wfc2 = dy^T h, d Wfc1 = dpre^T LN_2(x1)
-    WgradArgs w2{};
-    w2.dout = dy; w2.lddout = C; w2.a1 = m.h; w2.lda1 = hidden;
-    w2.dw = dw_fc2; w2.db = db_fc2; w2.rep_stride = rep_stride; w2.reps = reps;
-    w2.rows = rows; w2.N = C; w2.K = hidden; w2.prof_id = K_FC_WGRAD;
-    e = launch_wgrad<bf16_t>(w2, s);
-    if (e != hipSuccess) return e;
-    WgradArgs w1{};
-    w1.dout = m.dpre; w1.lddout = hidden; w1.a1 = m.x1n; w1.lda1 = C;
-    w1.dw = dw_fc1; w1.db = db_fc1; w1.rep_stride = rep_stride; w1.reps = reps;
-    w1.rows = rows; w1.N = hidden; w1.K = C; w1.prof_id = K_FC_WGRAD;
-    return launch_wgrad<bf16_t>(w1, s);
+    MlpReduceArgs r{};
+    r.part = m.part; r.nparts = (int)bwd_blocks(rows);
+    r.rows = hidden <= 64 ? 64 : 128; r.cols = C <= 32 ? 32 : 64;
+    r.C = C; r.Hd = hidden;
+    r.dw1 = dw_fc1; r.db1 = db_fc1; r.dw2 = dw_fc2; r.db2 = db_fc2;
+    const unsigned blocks = (unsigned)((2L * r.rows * r.cols + 31) / 32);
+    KernelTimer kt(K_MLP_REDUCE, s);
+    hipLaunchKernelGGL(astl_mlp_reduce_kernel, dim3(blocks), dim3(256), 0, s, r);
+    return hipGetLastError();
 }
 
 } // namespace gswa

@@ -38,6 +38,7 @@ enum KernelId {
     K_MLP_FWD,      // skip of Eq. 4 and all of Eq. 5 in one launch
     K_MLP_BWD,      // adjoint of Eq. 5 in one launch
     K_MLP_PACK,     // the MLP's weights into MFMA fragment order (once per forward call)
+    K_MLP_REDUCE,   // per-workgroup partial weight gradients of the MLP -> gradients
     K_COUNT
 };
 
