@@ -230,17 +230,17 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(LnBwdArgs a)
     }
 }
 
-unsigned ln_blocks(long rows)
+unsigned ln_blocks(long rows, int max_blocks)
 {
     long b = (rows + kLnThreads / 16 - 1) / (kLnThreads / 16);
-    return (unsigned)(b > kLnMaxBlocks ? kLnMaxBlocks : (b < 1 ? 1 : b));
+    return (unsigned)(b > max_blocks ? max_blocks : (b < 1 ? 1 : b));
 }
 
 template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, hipStream_t s)
 {
     const int P = (a.C + 16 * V - 1) / (16 * V);
     KernelTimer kt(K_LN_FWD, s);
-    const dim3 grid(ln_blocks(a.rows)), block(kLnThreads);
+    const dim3 grid(ln_blocks(a.rows, 4 * kLnMaxBlocks)), block(kLnThreads);
     if constexpr (V == 4) {
         switch (P) {
         case 1: hipLaunchKernelGGL((ln_fwd_kernel<T, 4, 1>), grid, block, 0, s, a); break;
@@ -264,7 +264,7 @@ template <typename T, int V> hipError_t launch_ln_bwd_v(const LnBwdArgs &a, hipS
 {
     const int P = (a.C + 16 * V - 1) / (16 * V);
     KernelTimer kt(K_LN_BWD, s);
-    const dim3 grid(ln_blocks(a.rows)), block(kLnThreads);
+    const dim3 grid(ln_blocks(a.rows, 2 * kLnMaxBlocks)), block(kLnThreads);
     if constexpr (V == 4) {
         switch (P) {
         case 1: hipLaunchKernelGGL((ln_bwd_kernel<T, 4, 1>), grid, block, 0, s, a); break;

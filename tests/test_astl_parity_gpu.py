@@ -91,3 +91,40 @@ def test_benchmark_shape_pair_against_the_oracle():
                     window=cfg["window"], shift=shift, dtype=cfg["dtype"], hidden=2 * cfg["C"])
         print("case", case, flush=True)
         parity.check_block(astl_oracle, seed=synth.LAYER_SEED0 + li, **case)
+
+
+def test_narrow_bf16_layers_take_the_fused_mlp_kernels():
+    """The kernel timing aid names what ran: one fused launch per pass for the MLP half of a narrow
+    bf16 layer, the per-step kernels otherwise (fp32, wide layers, forced)."""
+    import torch
+    case = dict(SMALL[7])
+    print("case", case, flush=True)
+    for flags, fused in ((0, True), (gswa.GSWA_FORCE_STAGED, False)):
+        gswa.gswa_profile_enable(True)
+        gswa.gswa_profile_collect()
+        parity.check_block(astl_oracle, extra_flags=flags, **case)
+        torch.cuda.synchronize()
+        names, dropped = gswa.gswa_profile_collect()
+        gswa.gswa_profile_enable(False)
+        assert dropped == 0
+        assert ("mlp_fwd" in names and "mlp_bwd" in names and "mlp_reduce" in names) == fused, names
+        assert ("fc1_linear" in names and "gelu_fwd" in names and "fc_wgrad" in names) == (not fused), names
+        assert names["ln_fwd"][1] == (2 if fused else 4) and names["ln_bwd"][1] == (1 if fused else 2), names
+
+
+@pytest.mark.parametrize("C,hidden", [(64, 120), (60, 128), (32, 64), (28, 60), (16, 24)])
+def test_padding_edges_of_the_fused_mlp_tiles(C, hidden):
+    """Channel and hidden widths at and next to the tile sizes: full tiles leave no spare row for
+    the bias sums, so the backward of those layers runs on the per-step kernels."""
+    heads = 4 if C % 4 == 0 else 2
+    case = dict(B=2, H=8, W=8, C=C, heads=heads, groups=2, window=4, shift=2, dtype="bf16", hidden=hidden)
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, **case)
+
+
+def test_ragged_token_count_in_the_fused_mlp_kernels():
+    """Token counts that are not a multiple of the 16-token tiles or of the 128-token rounds."""
+    for B, H, W in ((1, 4, 12), (3, 4, 4), (7, 8, 4)):
+        case = dict(B=B, H=H, W=W, C=60, heads=6, groups=2, window=4, shift=1, dtype="bf16", hidden=120)
+        print("case", case, flush=True)
+        parity.check_block(astl_oracle, **case)
