@@ -94,6 +94,29 @@ def time_steps(layers, steps, warmup, backward=True):
     return (time.perf_counter() - t0) / steps
 
 
+def time_graph_replays(layers, steps, warmup, backward=True):
+    """The same step captured once into a HIP graph (every launch of the library goes to the stream
+    it is given, nothing allocates or synchronises) and replayed: launch cost leaves the host."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(layers, backward)          # first calls set kernel attributes: not capturable
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(layers, backward)
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
 def profile_steps(layers, steps, backward=True):
     """Per-kernel average durations from HIP events recorded on the launch stream."""
     import torch
@@ -227,6 +250,9 @@ def main():
                     help="batch size other than the workload's own (a different workload: say so when quoting it)")
     ap.add_argument("--force-staged", action="store_true",
                     help="time the one-kernel-per-step path where a fused kernel exists")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step captured into one HIP graph and replayed (reported as "
+                         "whole_step.graph_ms_per_step; `value` stays the eager figure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-sweep", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -254,6 +280,7 @@ def main():
     tokens_per_step = T * len(layers)
     sec = time_steps(layers, args.steps, args.warmup, backward)
 
+    graph_sec = time_graph_replays(layers, args.steps, args.warmup, backward) if args.graph else None
     prof, prof_wall = profile_steps(layers, min(args.steps, 20), backward)
     dom = max(prof, key=lambda k: prof[k]["total_ms_per_step"])
     dom_bytes = algorithmic_bytes_per_launch(dom, cfg, prof[dom]["launches_per_step"] / len(layers), backward)
@@ -301,7 +328,8 @@ def main():
         "whole_step": {"algorithmic_GBps": step_bytes / sec / 1e9, "hbm_frac": step_bytes / sec / 1e9 / HBM_PEAK_GBS,
                        "model_TFLOPs": step_flops / sec / 1e12,
                        "mfma_frac": step_flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                       "profiled_ms_per_step": 1e3 * prof_wall},
+                       "profiled_ms_per_step": 1e3 * prof_wall,
+                       "graph_ms_per_step": None if graph_sec is None else 1e3 * graph_sec},
         "kernels": prof,
         "peak_saved_act_bytes": layers[0].saved_bytes + max(layers[0].fwd_ws_bytes, layers[0].bwd_ws_bytes),
         "by_groups": sweep,

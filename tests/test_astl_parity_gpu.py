@@ -128,3 +128,63 @@ def test_ragged_token_count_in_the_fused_mlp_kernels():
         case = dict(B=B, H=H, W=W, C=60, heads=6, groups=2, window=4, shift=1, dtype="bf16", hidden=120)
         print("case", case, flush=True)
         parity.check_block(astl_oracle, **case)
+
+
+def test_graph_replays_of_a_layer_pair_match_the_eager_result():
+    """A step of two chained whole layers captured into a HIP graph: every replay, with eager work
+    and synchronisation in between, gives the eager outputs (the attention layer's fused path sums
+    in a fixed order; the LayerNorm gradients go through atomics, hence a tolerance there)."""
+    import torch
+    from paper_2409_06206_amd import runner
+    cfg = dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, dtype="bf16", hidden=120)
+    x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], 1)
+    blocks = []
+    for li, shift in enumerate((0, 4)):
+        blk = runner.DeviceBlock(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], cfg["groups"], cfg["window"],
+                                 shift, cfg["dtype"], cfg["hidden"])
+        blk.set_params(synth.astl_params(cfg["C"], cfg["heads"], cfg["groups"], cfg["window"], cfg["hidden"],
+                                         200 + li, "stress"))
+        blocks.append(blk)
+    blocks[0].set_inputs(x)
+    blocks[1].dy = runner.to_device(dy, cfg["dtype"])
+    blocks[1].x, blocks[0].dy = blocks[0].y, blocks[1].dx
+
+    def step():
+        for b in blocks:
+            b.forward()
+        for b in reversed(blocks):
+            b.backward()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        out = {}
+        for i, b in enumerate(blocks):
+            out.update({f"{i}.{k}": v.copy() for k, v in b.results().items()})
+        return out
+
+    print("eager step", flush=True)
+    step()
+    want = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    print("capture", flush=True)
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(4):
+        # eager work of the program's own between the replays: the outputs are overwritten
+        for b in blocks:
+            b.y.zero_()
+            b.dx.zero_()
+            for g in b.grads.values():
+                g.fill_(7.0)
+        torch.cuda.synchronize()
+        print("replay", rep, flush=True)
+        graph.replay()
+        got = snapshot()
+        for k, w in want.items():
+            exact = k.endswith(".y") or k.endswith(".dx")
+            if exact:
+                assert np.array_equal(got[k], w), (rep, k)
+            else:
+                assert parity.rel_err(got[k], w) <= 1e-4, (rep, k, parity.rel_err(got[k], w))
