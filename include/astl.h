@@ -91,6 +91,40 @@ int astl_forward(const astl_desc *desc, const void *x, const astl_params *params
 int astl_backward(const astl_desc *desc, const void *x, const void *dy, const astl_params *params,
                   const void *saved, void *dx, const astl_grads *grads, void *ws, void *hip_stream);
 
+/*
+ * A stack of n_layers such layers applied one after the other (Sec. "Agile Swin Transformer
+ * Block": the deep feature extractor is a sequence of these layers, window attention and
+ * shifted-window attention alternating): layer l has shift 0 when l is even and `shift` when l
+ * is odd, every layer has its own parameters, and the output of layer l is the input of layer
+ * l + 1.  `params` and `grads` are HOST arrays of n_layers structs.
+ *
+ * checkpoint_every = 0 keeps every layer's input and saved state for the backward pass.
+ * checkpoint_every = k > 0 keeps only the inputs of layers k, 2k, ... (the block boundaries);
+ * astl_stack_backward then runs the forward of one block of k layers again, into its scratch,
+ * before taking that block's gradients: saved memory falls from n_layers to about
+ * n_layers / k + k layer states, for one more forward pass.  The result is the same either way.
+ */
+typedef struct astl_stack_desc {
+    astl_desc layer;          /* shape of every layer; layer.attn.shift is ignored               */
+    int32_t n_layers;         /* > 0                                                             */
+    int32_t shift;            /* shift of the odd layers, 0 <= shift < window                     */
+    int32_t checkpoint_every; /* 0, or the number of layers per recomputed block                  */
+} astl_stack_desc;
+
+/* Sizes as for astl_query_bytes; *saved_bytes covers all layers.  For inference (saved == NULL)
+ * astl_stack_forward needs *fwd_ws_bytes only. */
+int astl_stack_query_bytes(const astl_stack_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes,
+                           size_t *bwd_ws_bytes);
+
+/* y = layer_{n-1}( ... layer_0(x)).  saved = NULL for inference.  x and y must not overlap. */
+int astl_stack_forward(const astl_stack_desc *desc, const void *x, const astl_params *params, void *y,
+                       void *saved, void *ws, void *hip_stream);
+
+/* Gradients through the whole stack: dx, and grads[l] for the parameters of layer l. */
+int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *dy,
+                        const astl_params *params, const void *saved, void *dx, const astl_grads *grads,
+                        void *ws, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,8 @@ Parity pins (tests, CPU only): LayerNorm, GELU and the MLP half against torch's 
 and its autograd in fp64 (a library written independently of this file); printed values of the
 Gaussian CDF; closed forms (zero W2 leaves x1, zero gamma_1 feeds GSWA zeros, LN output
 statistics, invariance of LN under shift and scale of its input); central finite differences
-of the whole layer for every gradient, attention half included.
+of the whole layer for every gradient, attention half included; for a sequence of layers,
+central differences through two layers and the alternation of the shift.
 """
 import numpy as np
 from scipy.special import erf
@@ -123,3 +124,25 @@ def backward(x, dy, p, *, heads, groups, window, shift, eps=1e-5, cascade=True, 
     g.update(zip(_ATTN, dattn))
     dx, g["ln1_w"], g["ln1_b"] = layer_norm_backward(dxn, xhat1, rstd1, p["ln1_w"])
     return dx + dx1, g
+
+
+def stack_forward(x, params, *, heads, groups, window, shift, eps=1e-5, dqk=0, want_inputs=False):
+    """A sequence of layers (Sec. "Agile Swin Transformer Block"): layer l has shift 0 for even l and
+    ``shift`` for odd l, its own parameters ``params[l]``, and takes the output of layer l - 1."""
+    acts = [np.asarray(x, dtype=np.float64)]
+    for l, p in enumerate(params):
+        acts.append(forward(acts[-1], p, heads=heads, groups=groups, window=window,
+                            shift=shift if l % 2 else 0, eps=eps, dqk=dqk))
+    return (acts[-1], acts[:-1]) if want_inputs else acts[-1]
+
+
+def stack_backward(x, dy, params, *, heads, groups, window, shift, eps=1e-5, dqk=0):
+    """Gradients of sum(dy * y) through the sequence: (dx, list of per-layer gradient dicts)."""
+    _, inputs = stack_forward(x, params, heads=heads, groups=groups, window=window, shift=shift, eps=eps,
+                              dqk=dqk, want_inputs=True)
+    g = np.asarray(dy, dtype=np.float64)
+    grads = [None] * len(params)
+    for l in range(len(params) - 1, -1, -1):
+        g, grads[l] = backward(inputs[l], g, params[l], heads=heads, groups=groups, window=window,
+                               shift=shift if l % 2 else 0, eps=eps, dqk=dqk)
+    return g, grads

@@ -584,3 +584,166 @@ int astl_backward(const astl_desc *desc, const void *x, const void *dy, const as
 }
 
 } // extern "C"
+
+namespace {
+
+bool params_ok(const astl_params *p)
+{
+    return p->ln1_w && p->ln1_b && p->w_qkv && p->b_qkv && p->w_proj && p->b_proj && p->bias_table && p->ln2_w &&
+           p->ln2_b && p->w_fc1 && p->b_fc1 && p->w_fc2 && p->b_fc2 &&
+           aligned16(p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, p->ln2_w, p->ln2_b,
+                     p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2);
+}
+
+bool grads_ok(const astl_grads *g)
+{
+    return g->ln1_w && g->ln1_b && g->w_qkv && g->b_qkv && g->w_proj && g->b_proj && g->bias_table && g->ln2_w &&
+           g->ln2_b && g->w_fc1 && g->b_fc1 && g->w_fc2 && g->b_fc2 &&
+           aligned16(g->ln1_w, g->ln1_b, g->w_qkv, g->b_qkv, g->w_proj, g->b_proj, g->bias_table, g->ln2_w, g->ln2_b,
+                     g->w_fc1, g->b_fc1, g->w_fc2, g->b_fc2);
+}
+
+// Sizes of a stack (Sec. "Agile Swin Transformer Block"): S, F, Bw are the largest saved / scratch
+// needs over the two kinds of layer (unshifted, shifted), A one [T, C] activation.
+struct StackPlan {
+    astl_desc even, odd;
+    size_t S, F, Bw, A;
+    int L, k, nblocks;
+    size_t saved, fwd_ws, bwd_ws;
+};
+
+int make_stack_plan(const astl_stack_desc *d, StackPlan *sp)
+{
+    if (!d) return GSWA_EINVAL;
+    if (d->n_layers <= 0 || d->checkpoint_every < 0) return GSWA_EINVAL;
+    if (d->shift < 0 || d->shift >= d->layer.attn.window) return GSWA_EINVAL;
+    sp->even = d->layer; sp->even.attn.shift = 0;
+    sp->odd = d->layer; sp->odd.attn.shift = d->shift;
+    Plan pe, po;
+    int rc = make_plan(&sp->even, &pe);
+    if (rc != GSWA_OK) return rc;
+    rc = make_plan(&sp->odd, &po);
+    if (rc != GSWA_OK) return rc;
+    sp->S = pe.saved > po.saved ? pe.saved : po.saved;
+    sp->F = pe.fwd_ws > po.fwd_ws ? pe.fwd_ws : po.fwd_ws;
+    sp->Bw = pe.bwd_ws > po.bwd_ws ? pe.bwd_ws : po.bwd_ws;
+    sp->A = pe.act;
+    sp->L = d->n_layers;
+    sp->k = d->checkpoint_every > d->n_layers ? d->n_layers : d->checkpoint_every;
+    // forward scratch: two activations (inference and recomputed blocks chain through them) and
+    // one layer's scratch in its inference form
+    sp->fwd_ws = 2 * sp->A + sp->F + sp->S;
+    if (sp->k == 0) {
+        sp->nblocks = 1;
+        sp->saved = (size_t)sp->L * (sp->S + sp->A);
+        sp->bwd_ws = 2 * sp->A + sp->Bw;
+    } else {
+        sp->nblocks = (sp->L + sp->k - 1) / sp->k;
+        sp->saved = (size_t)(sp->nblocks > 1 ? sp->nblocks - 1 : 1) * sp->A;
+        const size_t lw = sp->F > sp->Bw ? sp->F : sp->Bw;
+        sp->bwd_ws = (size_t)sp->k * (sp->S + sp->A) + 2 * sp->A + lw;
+    }
+    return GSWA_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int astl_stack_query_bytes(const astl_stack_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes,
+                           size_t *bwd_ws_bytes)
+{
+    StackPlan sp;
+    int rc = make_stack_plan(desc, &sp);
+    if (rc != GSWA_OK) return rc;
+    if (saved_bytes) *saved_bytes = sp.saved;
+    if (fwd_ws_bytes) *fwd_ws_bytes = sp.fwd_ws;
+    if (bwd_ws_bytes) *bwd_ws_bytes = sp.bwd_ws;
+    return GSWA_OK;
+}
+
+int astl_stack_forward(const astl_stack_desc *desc, const void *x, const astl_params *params, void *y,
+                       void *saved, void *ws, void *hip_stream)
+{
+    StackPlan sp;
+    int rc = make_stack_plan(desc, &sp);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !params || !y || !ws || x == y) return GSWA_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) || !aligned16(x, y, saved)) return GSWA_EINVAL;
+    for (int l = 0; l < sp.L; ++l)
+        if (!params_ok(params + l)) return GSWA_EINVAL;
+    char *w = static_cast<char *>(ws), *sv = static_cast<char *>(saved);
+    char *abuf[2] = {w, w + sp.A};
+    char *layer_ws = w + 2 * sp.A;
+    const void *in = x;
+    for (int l = 0; l < sp.L; ++l) {
+        const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
+        void *out, *lsaved = nullptr;
+        if (l == sp.L - 1) out = y;
+        else if (sv && sp.k == 0) out = sv + (size_t)l * (sp.S + sp.A) + sp.S;       // kept with the layer's state
+        else if (sv && (l + 1) % sp.k == 0) out = sv + (size_t)((l + 1) / sp.k - 1) * sp.A; // input of the next block
+        else out = abuf[l & 1];
+        if (sv && sp.k == 0) lsaved = sv + (size_t)l * (sp.S + sp.A);
+        rc = astl_forward(ld, in, params + l, out, lsaved, layer_ws, hip_stream);
+        if (rc != GSWA_OK) return rc;
+        in = out;
+    }
+    return GSWA_OK;
+}
+
+int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *dy, const astl_params *params,
+                        const void *saved, void *dx, const astl_grads *grads, void *ws, void *hip_stream)
+{
+    StackPlan sp;
+    int rc = make_stack_plan(desc, &sp);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !dy || !params || !saved || !dx || !grads || !ws) return GSWA_EINVAL;
+    if (dx == x || dx == dy || dx == saved) return GSWA_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) || !aligned16(x, dy, saved, dx)) return GSWA_EINVAL;
+    for (int l = 0; l < sp.L; ++l)
+        if (!params_ok(params + l) || !grads_ok(grads + l)) return GSWA_EINVAL;
+    char *w = static_cast<char *>(ws);
+    const char *sv = static_cast<const char *>(saved);
+    const size_t slot = sp.S + sp.A;
+    // gradient of layer l's input goes to gbuf[l & 1] (to dx for layer 0)
+    auto grad_in = [&](int l, char *const *gbuf) -> const void * { return l == sp.L - 1 ? dy : gbuf[(l + 1) & 1]; };
+    auto grad_out = [&](int l, char *const *gbuf) -> void * { return l == 0 ? dx : gbuf[l & 1]; };
+    if (sp.k == 0) {
+        char *gbuf[2] = {w, w + sp.A};
+        char *layer_ws = w + 2 * sp.A;
+        for (int l = sp.L - 1; l >= 0; --l) {
+            const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
+            const void *xin = l == 0 ? x : sv + (size_t)(l - 1) * slot + sp.S;
+            rc = astl_backward(ld, xin, grad_in(l, gbuf), params + l, sv + (size_t)l * slot, grad_out(l, gbuf),
+                               grads + l, layer_ws, hip_stream);
+            if (rc != GSWA_OK) return rc;
+        }
+        return GSWA_OK;
+    }
+    // checkpointed: per block, forward again into the scratch, then backward through the block
+    char *region = w;                                  // k slots of [layer state | layer output]
+    char *gbuf[2] = {w + (size_t)sp.k * slot, w + (size_t)sp.k * slot + sp.A};
+    char *layer_ws = w + (size_t)sp.k * slot + 2 * sp.A;
+    for (int b = sp.nblocks - 1; b >= 0; --b) {
+        const int l0 = b * sp.k, l1 = (l0 + sp.k < sp.L) ? l0 + sp.k : sp.L;
+        const void *block_in = b == 0 ? x : sv + (size_t)(b - 1) * sp.A;
+        const void *in = block_in;
+        for (int l = l0; l < l1; ++l) {
+            const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
+            char *st = region + (size_t)(l - l0) * slot;
+            rc = astl_forward(ld, in, params + l, st + sp.S, st, layer_ws, hip_stream);
+            if (rc != GSWA_OK) return rc;
+            in = st + sp.S;
+        }
+        for (int l = l1 - 1; l >= l0; --l) {
+            const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
+            const void *xin = l == l0 ? block_in : region + (size_t)(l - l0 - 1) * slot + sp.S;
+            rc = astl_backward(ld, xin, grad_in(l, gbuf), params + l, region + (size_t)(l - l0) * slot,
+                               grad_out(l, gbuf), grads + l, layer_ws, hip_stream);
+            if (rc != GSWA_OK) return rc;
+        }
+    }
+    return GSWA_OK;
+}
+
+} // extern "C"

@@ -109,3 +109,46 @@ class DeviceBlock:
         out = {"y": to_host(self.y), "dx": to_host(self.dx)}
         out.update({"d" + k: to_host(v) for k, v in self.grads.items()})
         return out
+
+
+class DeviceStack:
+    """Buffers of a sequence of whole layers (alternating shift) behind the stack entry points."""
+
+    def __init__(self, B, H, W, C, heads, groups, window, shift, dtype, hidden, n_layers, checkpoint_every=0,
+                 eps=1e-5, flags=0, device="cuda:0", dqk=0):
+        self.desc = astl.make_stack_desc(B, H, W, C, heads, groups, window, shift, dtype, hidden, n_layers,
+                                         checkpoint_every, eps, flags, dqk)
+        self.dtype, self.device, self.n_layers = dtype, device, n_layers
+        self.shape = (B, H, W, C)
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.saved_bytes, self.fwd_ws_bytes, self.bwd_ws_bytes = astl.astl_stack_query_bytes(self.desc)
+        self.y = torch.empty(self.shape, dtype=tdt, device=device)
+        self.dx = torch.empty(self.shape, dtype=tdt, device=device)
+        self.saved = torch.empty(self.saved_bytes, dtype=torch.uint8, device=device)
+        self.ws = torch.empty(max(self.fwd_ws_bytes, self.bwd_ws_bytes), dtype=torch.uint8, device=device)
+        shp = synth.astl_param_shapes(C, heads, groups, window, hidden, dqk)
+        self.grads = [{k: torch.empty(s, dtype=torch.float32, device=device) for k, s in shp.items()}
+                      for _ in range(n_layers)]
+        self.params = None
+        self.x = self.dy = None
+
+    def set_params(self, per_layer):
+        self.params = [{k: to_device(v, self.dtype, self.device) for k, v in p.items()} for p in per_layer]
+
+    def set_inputs(self, x, dy=None):
+        self.x = to_device(x, self.dtype, self.device)
+        self.dy = None if dy is None else to_device(dy, self.dtype, self.device)
+
+    def forward(self, keep=True, stream=None):
+        astl.astl_stack_forward(self.desc, self.x, [DeviceBlock._fields(p) for p in self.params], self.y,
+                                self.saved if keep else None, self.ws, stream)
+
+    def backward(self, stream=None):
+        astl.astl_stack_backward(self.desc, self.x, self.dy, [DeviceBlock._fields(p) for p in self.params],
+                                 self.saved, self.dx, [DeviceBlock._fields(g) for g in self.grads], self.ws, stream)
+
+    def results(self):
+        out = {"y": to_host(self.y), "dx": to_host(self.dx)}
+        for l, g in enumerate(self.grads):
+            out.update({f"{l}.d{k}": to_host(v) for k, v in g.items()})
+        return out

@@ -181,3 +181,38 @@ def test_gradients_by_central_differences(case):
             fd = (up - dn) / (2 * h)
             an = grad.reshape(-1)[idx]
             assert math.isclose(fd, an, rel_tol=2e-6, abs_tol=2e-7), (name, idx, fd, an)
+
+
+def test_stack_is_the_composition_with_alternating_shift_and_its_gradients_follow_differences():
+    C, heads, groups, window, hidden, shift = 12, 2, 2, 4, 16, 2
+    ps = [_params(C, heads, groups, window, hidden, seed=20 + l) for l in range(3)]
+    x, dy = _acts(1, 8, 8, C)
+    kw = dict(heads=heads, groups=groups, window=window, eps=EPS)
+    # layer by layer: shifts 0, s, 0
+    a = x
+    for l, p in enumerate(ps):
+        a = astl_oracle.forward(a, p, shift=shift if l == 1 else 0, **kw)
+    y = astl_oracle.stack_forward(x, ps, shift=shift, **kw)
+    np.testing.assert_array_equal(y, a)
+    # the shifted middle layer matters
+    assert np.abs(y - astl_oracle.stack_forward(x, ps, shift=0, **kw)).max() > 1e-6
+    dx, grads = astl_oracle.stack_backward(x, dy, ps, shift=shift, **kw)
+
+    def loss():
+        return float((astl_oracle.stack_forward(x, ps, shift=shift, **kw) * dy).sum())
+
+    rng = np.random.default_rng(5)
+    h = 1e-5
+    probes = [("x", x, dx)] + [(f"{l}.{k}", ps[l][k], grads[l][k]) for l in range(3)
+                               for k in ("ln1_w", "w_qkv", "table", "w_fc1", "b_fc2")]
+    for name, val, grad in probes:
+        flat = val.reshape(-1)
+        for idx in rng.choice(flat.size, size=3, replace=False):
+            keep = flat[idx]
+            flat[idx] = keep + h
+            up = loss()
+            flat[idx] = keep - h
+            dn = loss()
+            flat[idx] = keep
+            fd, an = (up - dn) / (2 * h), grad.reshape(-1)[idx]
+            assert math.isclose(fd, an, rel_tol=5e-6, abs_tol=5e-7), (name, idx, fd, an)

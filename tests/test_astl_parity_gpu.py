@@ -188,3 +188,51 @@ def test_graph_replays_of_a_layer_pair_match_the_eager_result():
                 assert np.array_equal(got[k], w), (rep, k)
             else:
                 assert parity.rel_err(got[k], w) <= 1e-4, (rep, k, parity.rel_err(got[k], w))
+
+
+STACKS = [
+    dict(B=1, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="f32", hidden=120, n_layers=3),
+    dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=120, n_layers=5),
+    dict(B=1, H=24, W=24, C=60, heads=4, groups=2, window=12, shift=6, dtype="bf16", hidden=120, n_layers=4, dqk=4),
+]
+
+
+@pytest.mark.parametrize("every", [0, 1, 2, 3, 9])
+@pytest.mark.parametrize("case", STACKS, ids=_id)
+def test_stack_matches_oracle_with_and_without_checkpointing(case, every):
+    """A sequence of layers with alternating shift; recomputed blocks give the same gradients."""
+    import torch
+    from paper_2409_06206_amd import runner
+    c = dict(case)
+    print("case", c, "checkpoint_every", every, flush=True)
+    dtype, L, dqk = c["dtype"], c["n_layers"], c.get("dqk", 0)
+    ps = [synth.astl_params(c["C"], c["heads"], c["groups"], c["window"], c["hidden"], 300 + l, "stress", dqk)
+          for l in range(L)]
+    ps = [{k: synth.quantize(v, dtype) for k, v in p.items()} for p in ps]
+    x, dy = (synth.quantize(a, dtype) for a in synth.activations(c["B"], c["H"], c["W"], c["C"], 2))
+    kw = dict(heads=c["heads"], groups=c["groups"], window=c["window"], shift=c["shift"], dqk=dqk)
+    want = {"y": astl_oracle.stack_forward(x, ps, **kw)}
+    dx, grads = astl_oracle.stack_backward(x, dy, ps, **kw)
+    want["dx"] = dx
+    for l, g in enumerate(grads):
+        want.update({f"{l}.d{k}": v for k, v in g.items()})
+    st = runner.DeviceStack(c["B"], c["H"], c["W"], c["C"], c["heads"], c["groups"], c["window"], c["shift"], dtype,
+                            c["hidden"], L, every, dqk=dqk)
+    st.set_params(ps)
+    st.set_inputs(x, dy)
+    st.forward()
+    st.backward()
+    torch.cuda.synchronize()
+    got = st.results()
+    # the oracle keeps fp64 activations between layers, the library stores them in the element
+    # type: in bf16 one more rounding per layer boundary
+    tol = parity.TOL[dtype] * (1.0 if dtype == "f32" else 1.5)
+    errs = {k: parity.rel_err(got[k], w) for k, w in want.items()}
+    bad = {k: e for k, e in errs.items() if not e <= tol}
+    assert not bad, (bad, max(errs.values()))
+    # inference call: same output, nothing saved
+    y_train = st.y.clone()
+    st.y.zero_()
+    st.forward(keep=False)
+    torch.cuda.synchronize()
+    assert torch.equal(st.y, y_train)
