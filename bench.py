@@ -42,6 +42,7 @@ def measured_traffic(workload, groups, kernel):
 
 FLAGS = 0  # extra descriptor flags for every layer (--force-staged)
 BATCH = 0  # batch size override (--batch); 0 = the workload's own
+CHECKPOINT_EVERY = 0  # layers per recomputed block of a stack workload (--checkpoint-every)
 
 
 def build_case(name, groups):
@@ -52,6 +53,16 @@ def build_case(name, groups):
         cfg["B"] = BATCH
     x, dy = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED)
     layers = []
+    if cfg.get("stack"):
+        # one call runs the whole sequence of layers (alternating shift) in each direction
+        S = runner.DeviceStack(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups, cfg["window"],
+                               cfg["stack_shift"], cfg["dtype"], cfg["hidden"], cfg["stack"], CHECKPOINT_EVERY,
+                               flags=FLAGS, dqk=cfg.get("dqk", 0))
+        S.set_params([synth.astl_params(cfg["C"], cfg["heads"], groups, cfg["window"], cfg["hidden"],
+                                        synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)) for li in range(cfg["stack"])])
+        S.set_inputs(x, dy)
+        torch.cuda.synchronize()
+        return cfg, [S]
     for li, shift in enumerate(cfg["layers"]):
         if cfg.get("block"):
             L = runner.DeviceBlock(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups, cfg["window"],
@@ -243,7 +254,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--groups", type=int, default=2)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer",
-                                                              "astl_c2", "astl_agile", "astl_c3"],
+                                                              "astl_c2", "astl_agile", "astl_c3", "astl_stack36", "astl_agile_stack36"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
     ap.add_argument("--batch", type=int, default=0,
@@ -253,6 +264,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="also time the step captured into one HIP graph and replayed (reported as "
                          "whole_step.graph_ms_per_step; `value` stays the eager figure)")
+    ap.add_argument("--checkpoint-every", type=int, default=0,
+                    help="stack workloads: keep only every k-th layer input and recompute blocks of k layers "
+                         "in the backward pass (0 = keep everything)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-sweep", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -265,7 +279,8 @@ def main():
     import torch
     from paper_2409_06206_amd import gswa
     gswa.lib()
-    global FLAGS, BATCH
+    global FLAGS, BATCH, CHECKPOINT_EVERY
+    CHECKPOINT_EVERY = max(0, args.checkpoint_every)
     if args.force_staged:
         FLAGS = gswa.GSWA_FORCE_STAGED
     BATCH = max(0, args.batch)
@@ -277,13 +292,14 @@ def main():
         sys.exit(f"groups={args.groups} is not one of the benchmark's values for {args.workload}")
     cfg, layers = build_case(args.workload, args.groups)
     T = cfg["B"] * cfg["H"] * cfg["W"]
-    tokens_per_step = T * len(layers)
+    n_layers = cfg.get("stack") or len(layers)
+    tokens_per_step = T * n_layers
     sec = time_steps(layers, args.steps, args.warmup, backward)
 
     graph_sec = time_graph_replays(layers, args.steps, args.warmup, backward) if args.graph else None
     prof, prof_wall = profile_steps(layers, min(args.steps, 20), backward)
     dom = max(prof, key=lambda k: prof[k]["total_ms_per_step"])
-    dom_bytes = algorithmic_bytes_per_launch(dom, cfg, prof[dom]["launches_per_step"] / len(layers), backward)
+    dom_bytes = algorithmic_bytes_per_launch(dom, cfg, prof[dom]["launches_per_step"] / n_layers, backward)
     dom_s = prof[dom]["avg_us"] * 1e-6
     achieved = dom_bytes / dom_s / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -297,7 +313,7 @@ def main():
     step_flops = model_flops_per_token(cfg, args.groups, backward) * tokens_per_step
 
     sweep = {}
-    if not args.no_group_sweep:
+    if not args.no_group_sweep and not cfg.get("stack"):
         for G in cfg["groups"]:
             if G == args.groups:
                 ls, s_ = layers, sec
@@ -318,8 +334,10 @@ def main():
         "value": tokens_per_step / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {len(layers)} {'whole (LN, GSWA, MLP, skips)' if cfg.get('block') else 'GSWA'} layer(s), shifts {list(cfg['layers'])[:4]}"
-                               f"{'...' if len(layers) > 4 else ''}, {'fwd+bwd' if backward else 'forward only'}, "
+        "config": {"workload": f"{args.workload}: {n_layers} {'whole (LN, GSWA, MLP, skips)' if cfg.get('block') else 'GSWA'} layer(s), shifts {list(cfg['layers'])[:4]}"
+                               f"{'...' if len(layers) > 4 else ''}"
+                               f"{' one stack call per pass, shifts 0/%d alternating, checkpoint_every=%d' % (cfg['stack_shift'], CHECKPOINT_EVERY) if cfg.get('stack') else ''}, "
+                               f"{'fwd+bwd' if backward else 'forward only'}, "
                                f"B={cfg['B']} {cfg['H']}x{cfg['W']} C={cfg['C']} heads={cfg['heads']} "
                                f"window={cfg['window']} groups={args.groups}"
                                f"{' q/k channels per head=%d' % cfg['dqk'] if cfg.get('dqk') else ''}",
@@ -341,7 +359,7 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline and backward and (args.workload == "c2" or args.workload.startswith("agile") or cfg.get("block")):
+    if not args.no_cpu_baseline and backward and (args.workload == "c2" or args.workload.startswith("agile") or cfg.get("block")) and not cfg.get("stack"):
         out["cpu_baseline"] = cpu_baseline(args.workload, args.groups)
     print(json.dumps(out))
 

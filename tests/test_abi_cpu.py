@@ -157,3 +157,33 @@ def test_whole_layer_sizes_hold_the_attention_layers_state_and_one_activation():
     assert a_saved + act <= saved <= a_saved + act + 68 * 1024  # (+ the MLP's repacked weights)
     assert fwd >= 2 * act + a_fwd and bwd >= 3 * act + a_bwd
     assert saved % 256 == 0 and fwd % 256 == 0 and bwd % 256 == 0
+
+
+def test_stack_descriptor_validation_and_sizes():
+    from paper_2409_06206_amd import astl
+    base = dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=120, n_layers=12)
+    for change in (dict(n_layers=0), dict(shift=8), dict(shift=-1), dict(checkpoint_every=-1), dict(hidden=0)):
+        with pytest.raises(gswa.GswaError) as ei:
+            astl.astl_stack_query_bytes(astl.make_stack_desc(**{**base, **change}))
+        assert ei.value.status == gswa.GSWA_EINVAL, change
+    layer = astl.astl_query_bytes(astl.make_desc(**{k: v for k, v in base.items() if k != "n_layers"}))
+    act = 2 * 16 * 16 * 60 * 2
+    keep_all = astl.astl_stack_query_bytes(astl.make_stack_desc(**base))
+    assert keep_all[0] == 12 * (layer[0] + act)          # every layer's state and output
+    blocks = astl.astl_stack_query_bytes(astl.make_stack_desc(**base, checkpoint_every=4))
+    assert blocks[0] == 2 * act                          # the inputs of layers 4 and 8
+    assert blocks[2] >= 4 * (layer[0] + act)             # one block is rebuilt in the scratch
+    # at the benchmark's size recomputed blocks need far less than keeping all 36 layers
+    big = dict(base, B=32, H=64, W=64, n_layers=36)
+    all36 = astl.astl_stack_query_bytes(astl.make_stack_desc(**big))
+    six = astl.astl_stack_query_bytes(astl.make_stack_desc(**big, checkpoint_every=6))
+    assert six[0] + six[2] < 0.3 * (all36[0] + all36[2])
+    # one block that spans the whole stack keeps (next to) nothing
+    whole = astl.astl_stack_query_bytes(astl.make_stack_desc(**base, checkpoint_every=50))
+    assert whole[0] == act
+    fake = 0x1000
+    full = {n: fake for n in astl.PARAM_FIELDS}
+    with pytest.raises(gswa.GswaError) as ei:   # a null parameter in the last layer, found before any launch
+        astl.astl_stack_forward(astl.make_stack_desc(**base), fake, [full] * 11 + [{**full, "ln1_w": None}],
+                                fake + 0x1000, None, fake, stream=0)
+    assert ei.value.status == gswa.GSWA_EINVAL
