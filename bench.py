@@ -254,7 +254,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--groups", type=int, default=2)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer",
-                                                              "astl_c2", "astl_agile", "astl_c3", "astl_stack36", "astl_agile_stack36"],
+                                                              "astl_c2", "astl_agile", "astl_c3", "astl_infer", "astl_stack36",
+                                                              "astl_agile_stack36"],
                     help="c2 is the benchmark line; the others are the remaining benchmark shapes "
                          "(c5_*: forward only)")
     ap.add_argument("--batch", type=int, default=0,

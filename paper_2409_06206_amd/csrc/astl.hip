@@ -8,8 +8,6 @@
 #include "staged_kernels.h"
 #include "astl_mlp.h"
 
-#include <type_traits>
-
 namespace gswa {
 
 namespace {
@@ -344,7 +342,8 @@ int make_plan(const astl_desc *d, Plan *p)
     p->fused_mlp = d->attn.dtype == GSWA_BF16 && !(d->attn.flags & GSWA_FORCE_STAGED) &&
                    astl_mlp_supported(p->C, p->Hd);
     p->fused_mlp_bwd = p->fused_mlp && astl_mlp_bwd_supported(p->C, p->Hd);
-    p->params = 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
+    // (with the fused MLP backward only LN_1's two vectors go through the gradient copies)
+    p->params = p->fused_mlp_bwd ? 2 * (size_t)p->C : 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
     p->reps = align256(kGradReplicas * p->params * sizeof(float));
     p->pack = p->fused_mlp ? astl_mlp_pack_bytes() : 0;
     p->saved = p->act + p->at_saved + p->pack;
@@ -431,22 +430,27 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     T *dx1 = reinterpret_cast<T *>(ws + 2 * pl.act);
     char *rest = ws + 3 * pl.act;
     float *rep = reinterpret_cast<float *>(ws + pl.bwd_ws - pl.reps);
-    // one copy of the gradients: dw_fc1 | db_fc1 | dw_fc2 | db_fc2 | dln1_w | dln1_b | dln2_w | dln2_b
+    // one copy of the gradients: dw_fc1 | db_fc1 | dw_fc2 | db_fc2 | dln1_w | dln1_b | dln2_w | dln2_b;
+    // with the fused MLP backward, which writes its six gradients itself: dln1_w | dln1_b only
     const long P = (long)pl.params;
+    const bool own = pl.fused_mlp_bwd;
     const long o_w1 = 0, o_b1 = o_w1 + (long)Hd * C, o_w2 = o_b1 + Hd, o_b2 = o_w2 + (long)C * Hd;
-    const long o_g1 = o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
+    const long o_g1 = own ? 0 : o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
+    const int accumulate = (d->attn.flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
 
-    ZeroList z{};
-    z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P; z.count = 1;
-    ASTL_HIP(launch_fill_zero(z, st));
+    if (!own) {
+        ZeroList z{};
+        z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P; z.count = 1;
+        ASTL_HIP(launch_fill_zero(z, st));
+    }
 
     // Eq. 5 backwards
     if (pl.fused_mlp_bwd) {
         ASTL_HIP(launch_astl_mlp_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
                                      (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
-                                     (const bf16_t *)p->w_fc2, (bf16_t *)dx1, rep + o_w1, rep + o_b1,
-                                     rep + o_w2, rep + o_b2, rep + o_g2, rep + o_be2, P, kGradReplicas,
+                                     (const bf16_t *)p->w_fc2, (bf16_t *)dx1, g->w_fc1, g->b_fc1, g->w_fc2,
+                                     g->b_fc2, g->ln2_w, g->ln2_b, accumulate, rep, (long)kGradReplicas * P,
                                      saved + pl.saved - pl.pack, rest, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
@@ -503,16 +507,22 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
 
     ReplicaSum rs{};
     rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;
-    rs.out[0] = g->w_fc1; rs.off[0] = o_w1; rs.n[0] = (long)Hd * C;
-    rs.out[1] = g->b_fc1; rs.off[1] = o_b1; rs.n[1] = Hd;
-    rs.out[2] = g->w_fc2; rs.off[2] = o_w2; rs.n[2] = (long)C * Hd;
-    rs.out[3] = g->b_fc2; rs.off[3] = o_b2; rs.n[3] = C;
-    rs.out[4] = g->ln1_w; rs.off[4] = o_g1; rs.n[4] = C;
-    rs.out[5] = g->ln1_b; rs.off[5] = o_be1; rs.n[5] = C;
-    rs.out[6] = g->ln2_w; rs.off[6] = o_g2; rs.n[6] = C;
-    rs.out[7] = g->ln2_b; rs.off[7] = o_be2; rs.n[7] = C;
-    rs.count = 8;
-    rs.accumulate = (d->attn.flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
+    if (own) {
+        rs.out[0] = g->ln1_w; rs.off[0] = o_g1; rs.n[0] = C;
+        rs.out[1] = g->ln1_b; rs.off[1] = o_be1; rs.n[1] = C;
+        rs.count = 2;
+    } else {
+        rs.out[0] = g->w_fc1; rs.off[0] = o_w1; rs.n[0] = (long)Hd * C;
+        rs.out[1] = g->b_fc1; rs.off[1] = o_b1; rs.n[1] = Hd;
+        rs.out[2] = g->w_fc2; rs.off[2] = o_w2; rs.n[2] = (long)C * Hd;
+        rs.out[3] = g->b_fc2; rs.off[3] = o_b2; rs.n[3] = C;
+        rs.out[4] = g->ln1_w; rs.off[4] = o_g1; rs.n[4] = C;
+        rs.out[5] = g->ln1_b; rs.off[5] = o_be1; rs.n[5] = C;
+        rs.out[6] = g->ln2_w; rs.off[6] = o_g2; rs.n[6] = C;
+        rs.out[7] = g->ln2_b; rs.off[7] = o_be2; rs.n[7] = C;
+        rs.count = 8;
+    }
+    rs.accumulate = accumulate;
     ASTL_HIP(launch_reduce_replicas(rs, st));
     return GSWA_OK;
 }

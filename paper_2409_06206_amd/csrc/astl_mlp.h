@@ -25,14 +25,15 @@ bool astl_mlp_bwd_supported(int C, int hidden);
 // Scratch bytes of the backward (one pair of partial weight-gradient matrices per workgroup).
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden);
 
-// dx1 = dy + adjoint of MLP(LN_2(.)) at x1.  The gradients of the two fully connected layers are
-// WRITTEN into copy 0 of `reps` gradient copies rep_stride floats apart (each pointer is its place
-// in copy 0), those of the LayerNorm are added into copy `workgroup mod reps`.
-// `pack` is what the forward call of the same layer wrote.
+// dx1 = dy + adjoint of MLP(LN_2(.)) at x1.  The six parameter gradients (both fully connected
+// layers, gamma and beta of LN_2) are written to their final places, or added there when
+// `accumulate` is set.  `zero` (may be null) is an fp32 array of nzero entries the first kernel
+// clears on the way, for a later launch of the caller's.  `pack` is what the forward call of the
+// same layer wrote; `ws` holds astl_mlp_bwd_ws_bytes().
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
-                               float *db_fc2, float *dln_w, float *dln_b, long rep_stride, int reps,
+                               float *db_fc2, float *dln_w, float *dln_b, int accumulate, float *zero, long nzero,
                                const void *pack, void *ws, hipStream_t s);
 
 } // namespace gswa

@@ -17,7 +17,6 @@
 #include "astl_mlp.h"
 #include "mfma.h"
 #include "profile.h"
-#include "staged_kernels.h"
 
 namespace gswa {
 
@@ -32,12 +31,13 @@ constexpr int kFwdWaves = kFwdThreads / 64;
 // 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7); exp(-t^2/2) serves both.
 __device__ __forceinline__ void gauss(float t, float &Phi, float &phi)
 {
-    const float x = fabsf(t) * 0.70710678118654752f;
-    const float k = __frcp_rn(1.f + 0.3275911f * x);
-    const float e = __expf(-x * x);
-    const float poly = ((((1.061405429f * k - 1.453152027f) * k + 1.421413741f) * k - 0.284496736f) * k + 0.254829592f) * k;
-    const float half_erf = 0.5f - 0.5f * poly * e;
-    Phi = t >= 0.f ? 0.5f + half_erf : 0.5f - half_erf;
+    // exp(-t^2/2) as a power of two; with x = |t|/sqrt(2) the formula's 1/(1 + 0.3275911 x) is
+    // 1/(1 + 0.2316419 |t|), and its five coefficients are halved here: w = (1 - erf x)/2
+    const float e = __builtin_amdgcn_exp2f(t * t * -0.72134752044448170f);
+    const float k = __builtin_amdgcn_rcpf(fmaf(fabsf(t), 0.23164190f, 1.f));
+    const float poly = ((((0.5307027145f * k - 0.7265760135f) * k + 0.7107068705f) * k - 0.142248368f) * k + 0.127414796f) * k;
+    const float w = poly * e;
+    Phi = t >= 0.f ? 1.f - w : w;
     phi = 0.39894228040143268f * e;
 }
 
@@ -67,11 +67,10 @@ struct MlpArgs {
     const bf16_t *x, *a;       // forward: x1 = x + a;  backward: x = x1, a = dy
     const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
     bf16_t *x1, *y;            // forward outputs;  backward: y = dx1
-    float *dln_w, *dln_b;      // backward: copy 0 of `reps` copies rep_stride floats apart
+    float *zero;               // backward: fp32 array the kernel clears for a later launch of the caller's
+    long nzero;
     void *pack;                // weights in fragment order, written by the pack kernel
     float *part;               // backward: one pair of partial weight-gradient matrices per workgroup
-    long rep_stride;
-    int reps;
 };
 
 // Layout of the packed weights (uint4 units, then floats), shared by the three kernels:
@@ -359,6 +358,8 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         stage(w2t, pk + L::w2t, 2 * L::frag);                        // w2t and w1t lie back to back
         stage(reinterpret_cast<uint4 *>(b1s), pk + L::floats_at, FT * 16 / 4);
     }
+    for (long i = (long)blockIdx.x * kBwdThreads + threadIdx.x; i < a.nzero; i += (long)gridDim.x * kBwdThreads)
+        a.zero[i] = 0.f;
     __syncthreads();
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tok = lane & 15, q = lane >> 4;
@@ -484,9 +485,10 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         __syncthreads();
     }
 
-    // the workgroup's sums: part[workgroup][2][FT*16][CT*16]; lane holds column m, rows 4q + i
+    // the workgroup's sums: part[workgroup] = [2][FT*16][CT*16] matrices, then [2][CT*16] LayerNorm
+    // sums; lane holds column m, rows 4q + i
+    float *part = a.part + (size_t)blockIdx.x * (2 * FT * 16 * CT * 16 + 2 * CT * 16);
     if (wave < FT) {
-        float *part = a.part + (size_t)blockIdx.x * 2 * FT * 16 * CT * 16;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -497,8 +499,7 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
             }
     }
 
-    // d gamma, d beta: over the 16 tokens of the wave, the waves of the workgroup, then one add
-    // per channel into the workgroup's copy
+    // d gamma, d beta: over the 16 tokens of the wave, then the waves of the workgroup
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -515,34 +516,33 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
             }
         }
     __syncthreads();
-    const long rep = (long)(blockIdx.x % (unsigned)a.reps) * a.rep_stride;
     for (int e = threadIdx.x; e < 2 * CT * 16; e += kBwdThreads) {
         const int which = e / (CT * 16), c = e % (CT * 16);
-        if (c >= C) continue;
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < kBwdWaves; ++w) s += red[(w * 2 + which) * CT * 16 + c];
-        atomicAdd((which ? a.dln_b : a.dln_w) + rep + c, s);
+        part[2 * FT * 16 * CT * 16 + e] = c < C ? s : 0.f;
     }
     (void)Hd;
 }
 
-// Sums the workgroups' partial matrices and writes the MLP's four parameter gradients (into copy 0
-// of the gradient copies, which nothing else touches for these parameters):
-//   d Wfc1[f][c] = M1[f][c], d bfc1[f] = M1[f][last column], d Wfc2[c][f] = M2[f][c], d bfc2[c] = M2[last row][c].
+// Sums the workgroups' partial results and writes (or adds to) the six parameter gradients:
+//   d Wfc1[f][c] = M1[f][c], d bfc1[f] = M1[f][last column], d Wfc2[c][f] = M2[f][c], d bfc2[c] = M2[last row][c],
+//   d gamma, d beta of LN_2 from the two rows behind the matrices.
 // 32 entries per block, the workgroups in 8 slices with eight loads in flight per thread.
 struct MlpReduceArgs {
     const float *part;
-    int nparts, rows, cols; // partial matrices are [2][rows][cols]
+    int nparts, rows, cols; // a workgroup's partial results are [2][rows][cols] then [2][cols]
     int C, Hd;
-    float *dw1, *db1, *dw2, *db2;
+    int accumulate;
+    float *dw1, *db1, *dw2, *db2, *dln_w, *dln_b;
 };
 
 __global__ __launch_bounds__(256) void astl_mlp_reduce_kernel(MlpReduceArgs a)
 {
     __shared__ float red[8][33];
     const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
-    const long per = (long)2 * a.rows * a.cols;
+    const long mats = (long)2 * a.rows * a.cols, per = mats + 2 * a.cols;
     const long i = (long)blockIdx.x * 32 + col;
     float acc = 0.f;
     if (i < per) {
@@ -561,23 +561,30 @@ __global__ __launch_bounds__(256) void astl_mlp_reduce_kernel(MlpReduceArgs a)
         float sum = 0.f;
 #pragma unroll
         for (int k8 = 0; k8 < 8; ++k8) sum += red[k8][col];
-        const int which = (int)(i / ((long)a.rows * a.cols));
-        const int rem = (int)(i % ((long)a.rows * a.cols));
-        const int f = rem / a.cols, c = rem % a.cols;
-        if (which == 0) {
-            if (f < a.Hd && c < a.C) a.dw1[(long)f * a.C + c] = sum;
-            else if (f < a.Hd && c == a.cols - 1) a.db1[f] = sum;
+        float *dst = nullptr;
+        if (i < mats) {
+            const int which = (int)(i / ((long)a.rows * a.cols));
+            const int rem = (int)(i % ((long)a.rows * a.cols));
+            const int f = rem / a.cols, c = rem % a.cols;
+            if (which == 0) {
+                if (f < a.Hd && c < a.C) dst = a.dw1 + (long)f * a.C + c;
+                else if (f < a.Hd && c == a.cols - 1) dst = a.db1 + f;
+            } else {
+                if (f < a.Hd && c < a.C) dst = a.dw2 + (long)c * a.Hd + f;
+                else if (f == a.rows - 1 && c < a.C) dst = a.db2 + c;
+            }
         } else {
-            if (f < a.Hd && c < a.C) a.dw2[(long)c * a.Hd + f] = sum;
-            else if (f == a.rows - 1 && c < a.C) a.db2[c] = sum;
+            const int j = (int)(i - mats), c = j % a.cols;
+            if (c < a.C) dst = (j < a.cols ? a.dln_w : a.dln_b) + c;
         }
+        if (dst) *dst = a.accumulate ? *dst + sum : sum;
     }
 }
 
-unsigned mlp_blocks(long rows, int waves)
+unsigned fwd_blocks(long rows)
 {
     const long tiles = (rows + 15) / 16;
-    long b = (tiles + waves - 1) / waves;
+    long b = (tiles + kFwdWaves - 1) / kFwdWaves;
     if (b > 512) b = 512;
     return (unsigned)(b < 1 ? 1 : b);
 }
@@ -612,7 +619,7 @@ template <int KSC, int KSF> hipError_t launch_fwd_t(const MlpArgs &a, hipStream_
         attr_done = true;
     }
     KernelTimer kt(K_MLP_FWD, s);
-    hipLaunchKernelGGL(kern, dim3(mlp_blocks(a.rows, kFwdWaves)), dim3(kFwdThreads), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(fwd_blocks(a.rows)), dim3(kFwdThreads), lds, s, a);
     return hipGetLastError();
 }
 
@@ -666,21 +673,21 @@ size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden)
 {
     (void)rows;
     const size_t ct16 = C <= 32 ? 32 : 64, ft16 = hidden <= 64 ? 64 : 128;
-    return align256((size_t)kBwdMaxBlocks * 2 * ft16 * ct16 * sizeof(float));
+    return align256((size_t)kBwdMaxBlocks * (2 * ft16 * ct16 + 2 * ct16) * sizeof(float));
 }
 
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
-                               float *db_fc2, float *dln_w, float *dln_b, long rep_stride, int reps,
+                               float *db_fc2, float *dln_w, float *dln_b, int accumulate, float *zero, long nzero,
                                const void *pack, void *ws, hipStream_t s)
 {
-    if (!astl_mlp_bwd_supported(C, hidden) || reps < 1) return hipErrorInvalidValue;
+    if (!astl_mlp_bwd_supported(C, hidden)) return hipErrorInvalidValue;
     MlpArgs m{};
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x = x1; m.a = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
     m.y = dx1;
-    m.dln_w = dln_w; m.dln_b = dln_b; m.rep_stride = rep_stride; m.reps = reps;
+    m.zero = zero; m.nzero = zero ? nzero : 0;
     m.pack = const_cast<void *>(pack);
     m.part = static_cast<float *>(ws);
     hipError_t e;
@@ -691,8 +698,9 @@ hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf
     r.part = m.part; r.nparts = (int)bwd_blocks(rows);
     r.rows = hidden <= 64 ? 64 : 128; r.cols = C <= 32 ? 32 : 64;
     r.C = C; r.Hd = hidden;
-    r.dw1 = dw_fc1; r.db1 = db_fc1; r.dw2 = dw_fc2; r.db2 = db_fc2;
-    const unsigned blocks = (unsigned)((2L * r.rows * r.cols + 31) / 32);
+    r.accumulate = accumulate;
+    r.dw1 = dw_fc1; r.db1 = db_fc1; r.dw2 = dw_fc2; r.db2 = db_fc2; r.dln_w = dln_w; r.dln_b = dln_b;
+    const unsigned blocks = (unsigned)((2L * r.rows * r.cols + 2L * r.cols + 31) / 32);
     KernelTimer kt(K_MLP_REDUCE, s);
     hipLaunchKernelGGL(astl_mlp_reduce_kernel, dim3(blocks), dim3(256), 0, s, r);
     return hipGetLastError();

@@ -159,6 +159,8 @@ CONFIGS.update({
     "astl_c2": dict(CONFIGS["c2"], block=True, hidden=120, groups=(1, 2, 3, 6)),
     "astl_agile": dict(CONFIGS["agile_h4_qk16"], block=True, hidden=120),
     "astl_c3": dict(CONFIGS["c3"], block=True, hidden=360),
+    # forward only on a large map, as at deployment
+    "astl_infer": dict(CONFIGS["agile_infer"], block=True, hidden=120),
     # the deep feature extractor's depth: 36 layers (6 blocks of 6), shifts 0, 4, 0, 4, ...
     "astl_stack36": dict(CONFIGS["c2"], block=True, hidden=120, stack=36, stack_shift=4, groups=(1, 2, 3, 6)),
     "astl_agile_stack36": dict(CONFIGS["agile_h4_qk16"], block=True, hidden=120, stack=36, stack_shift=6),
