@@ -115,15 +115,15 @@ struct LnArgs {
 // LayerNorm of every token (Eq. 4-5).  With `add` the normalised value is the stored (rounded)
 // sum, which is also what the backward pass will read back.
 template <typename T, int V, int P>
-__global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(LnArgs a)
+__device__ __forceinline__ void ln_fwd_block(const LnArgs &a, unsigned block, unsigned nblocks)
 {
     const int l16 = threadIdx.x & 15;
-    const long stride = (long)gridDim.x * (kLnThreads / 16);
+    const long stride = (long)nblocks * (kLnThreads / 16);
     const T *u = static_cast<const T *>(a.u), *add = static_cast<const T *>(a.add);
     float g[P * V], b[P * V];
     load_row<T, V, P>(static_cast<const T *>(a.gamma), a.C, l16, g);
     load_row<T, V, P>(static_cast<const T *>(a.beta), a.C, l16, b);
-    for (long t = (long)blockIdx.x * (kLnThreads / 16) + (threadIdx.x >> 4); t < a.rows; t += stride) {
+    for (long t = (long)block * (kLnThreads / 16) + (threadIdx.x >> 4); t < a.rows; t += stride) {
         float f[P * V];
         load_row<T, V, P>(u + t * a.C, a.C, l16, f);
         if (add) {
@@ -139,6 +139,24 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(LnArgs a)
         for (int k = 0; k < P * V; ++k) f[k] = (f[k] - mean) * rstd * g[k] + b[k];
         store_row<T, V, P>(static_cast<T *>(a.out) + t * a.C, a.C, l16, f);
     }
+}
+
+template <typename T, int V, int P>
+__global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(LnArgs a)
+{
+    ln_fwd_block<T, V, P>(a, blockIdx.x, gridDim.x);
+}
+
+// The same LayerNorm with, in the first `red_blocks` workgroups of the launch, the final sum of the
+// fused MLP backward's partial results: two short pieces of work that do not depend on each other.
+template <typename T, int V, int P>
+__global__ __launch_bounds__(kLnThreads) void ln_fwd_reduce_kernel(LnArgs a, MlpReduceArgs r, unsigned red_blocks)
+{
+    if (blockIdx.x < red_blocks) {
+        astl_mlp_reduce_block(r, (int)blockIdx.x);
+        return;
+    }
+    ln_fwd_block<T, V, P>(a, blockIdx.x - red_blocks, gridDim.x - red_blocks);
 }
 
 struct LnBwdArgs {
@@ -234,11 +252,29 @@ unsigned ln_blocks(long rows, int max_blocks)
     return (unsigned)(b > max_blocks ? max_blocks : (b < 1 ? 1 : b));
 }
 
-template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, hipStream_t s)
+template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, const MlpReduceArgs *r, hipStream_t s)
 {
     const int P = (a.C + 16 * V - 1) / (16 * V);
+    const dim3 block(kLnThreads);
+    if (r) {   // with the MLP's final sum in front
+        const unsigned rb = astl_mlp_reduce_blocks(*r);
+        const dim3 grid(rb + ln_blocks(a.rows, 4 * kLnMaxBlocks));
+        KernelTimer kt(K_LN_FWD_REDUCE, s);
+        if constexpr (V == 4) {
+            switch (P) {
+            case 1: hipLaunchKernelGGL((ln_fwd_reduce_kernel<T, 4, 1>), grid, block, 0, s, a, *r, rb); break;
+            case 2: hipLaunchKernelGGL((ln_fwd_reduce_kernel<T, 4, 2>), grid, block, 0, s, a, *r, rb); break;
+            case 3: hipLaunchKernelGGL((ln_fwd_reduce_kernel<T, 4, 3>), grid, block, 0, s, a, *r, rb); break;
+            default: hipLaunchKernelGGL((ln_fwd_reduce_kernel<T, 4, 4>), grid, block, 0, s, a, *r, rb); break;
+            }
+        } else {
+            if (P <= 4) hipLaunchKernelGGL((ln_fwd_reduce_kernel<T, 1, 4>), grid, block, 0, s, a, *r, rb);
+            else hipLaunchKernelGGL((ln_fwd_reduce_kernel<T, 1, 16>), grid, block, 0, s, a, *r, rb);
+        }
+        return hipGetLastError();
+    }
     KernelTimer kt(K_LN_FWD, s);
-    const dim3 grid(ln_blocks(a.rows, 4 * kLnMaxBlocks)), block(kLnThreads);
+    const dim3 grid(ln_blocks(a.rows, 4 * kLnMaxBlocks));
     if constexpr (V == 4) {
         switch (P) {
         case 1: hipLaunchKernelGGL((ln_fwd_kernel<T, 4, 1>), grid, block, 0, s, a); break;
@@ -253,9 +289,9 @@ template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, hipStre
     return hipGetLastError();
 }
 
-template <typename T> hipError_t launch_ln_fwd(const LnArgs &a, hipStream_t s)
+template <typename T> hipError_t launch_ln_fwd(const LnArgs &a, hipStream_t s, const MlpReduceArgs *r = nullptr)
 {
-    return (a.C % 4 == 0) ? launch_ln_fwd_v<T, 4>(a, s) : launch_ln_fwd_v<T, 1>(a, s);
+    return (a.C % 4 == 0) ? launch_ln_fwd_v<T, 4>(a, r, s) : launch_ln_fwd_v<T, 1>(a, r, s);
 }
 
 template <typename T, int V> hipError_t launch_ln_bwd_v(const LnBwdArgs &a, hipStream_t s)
@@ -445,13 +481,14 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     }
 
     // Eq. 5 backwards
+    MlpReduceArgs mlp_sum{};
     if (pl.fused_mlp_bwd) {
         ASTL_HIP(launch_astl_mlp_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
                                      (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                      (const bf16_t *)p->w_fc2, (bf16_t *)dx1, g->w_fc1, g->b_fc1, g->w_fc2,
                                      g->b_fc2, g->ln2_w, g->ln2_b, accumulate, rep, (long)kGradReplicas * P,
-                                     saved + pl.saved - pl.pack, rest, st));
+                                     saved + pl.saved - pl.pack, rest, &mlp_sum, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);
@@ -496,7 +533,8 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     // Eq. 4 backwards: the attention layer on LN_1(x) (recomputed), then LN_1 and the skip
     LnArgs l1{};
     l1.u = x; l1.gamma = p->ln1_w; l1.beta = p->ln1_b; l1.out = xn; l1.rows = rows; l1.C = C; l1.eps = d->eps;
-    ASTL_HIP(launch_ln_fwd<T>(l1, st));
+    // (the fused MLP backward's final sum rides in the same launch)
+    ASTL_HIP(launch_ln_fwd<T>(l1, st, pl.fused_mlp_bwd ? &mlp_sum : nullptr));
     ASTL_RC(gswa_backward(&d->attn, xn, dx1, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, at_saved,
                           dn, g->w_qkv, g->b_qkv, g->w_proj, g->b_proj, g->bias_table, rest, st));
     LnBwdArgs n1{};

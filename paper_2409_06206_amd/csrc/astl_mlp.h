@@ -25,15 +25,78 @@ bool astl_mlp_bwd_supported(int C, int hidden);
 // Scratch bytes of the backward (one pair of partial weight-gradient matrices per workgroup).
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden);
 
+// Sums the workgroups' partial results and writes (or adds to) the six parameter gradients:
+//   d Wfc1[f][c] = M1[f][c], d bfc1[f] = M1[f][last column], d Wfc2[c][f] = M2[f][c], d bfc2[c] = M2[last row][c],
+//   d gamma, d beta of LN_2 from the two rows behind the matrices.
+// 32 entries per block, the workgroups in 8 slices with eight loads in flight per thread.
+struct MlpReduceArgs {
+    const float *part;
+    int nparts, rows, cols; // a workgroup's partial results are [2][rows][cols] then [2][cols]
+    int C, Hd;
+    int accumulate;
+    float *dw1, *db1, *dw2, *db2, *dln_w, *dln_b;
+};
+
+inline unsigned astl_mlp_reduce_blocks(const MlpReduceArgs &r)
+{
+    return (unsigned)((2L * r.rows * r.cols + 2L * r.cols + 31) / 32);
+}
+
+// work of block `block` of astl_mlp_reduce_blocks() blocks of 256 threads
+__device__ __forceinline__ void astl_mlp_reduce_block(const MlpReduceArgs &a, int block)
+{
+    __shared__ float red[8][33];
+    const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
+    const long mats = (long)2 * a.rows * a.cols, per = mats + 2 * a.cols;
+    const long i = (long)block * 32 + col;
+    float acc = 0.f;
+    if (i < per) {
+        float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int w = slice;
+        for (; w + 56 < a.nparts; w += 64) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a8[u] += a.part[(long)(w + 8 * u) * per + i];
+        }
+        for (; w < a.nparts; w += 8) a8[0] += a.part[(long)w * per + i];
+        acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+    }
+    red[slice][col] = acc;
+    __syncthreads();
+    if (slice == 0 && i < per) {
+        float sum = 0.f;
+#pragma unroll
+        for (int k8 = 0; k8 < 8; ++k8) sum += red[k8][col];
+        float *dst = nullptr;
+        if (i < mats) {
+            const int which = (int)(i / ((long)a.rows * a.cols));
+            const int rem = (int)(i % ((long)a.rows * a.cols));
+            const int f = rem / a.cols, c = rem % a.cols;
+            if (which == 0) {
+                if (f < a.Hd && c < a.C) dst = a.dw1 + (long)f * a.C + c;
+                else if (f < a.Hd && c == a.cols - 1) dst = a.db1 + f;
+            } else {
+                if (f < a.Hd && c < a.C) dst = a.dw2 + (long)c * a.Hd + f;
+                else if (f == a.rows - 1 && c < a.C) dst = a.db2 + c;
+            }
+        } else {
+            const int j = (int)(i - mats), c = j % a.cols;
+            if (c < a.C) dst = (j < a.cols ? a.dln_w : a.dln_b) + c;
+        }
+        if (dst) *dst = a.accumulate ? *dst + sum : sum;
+    }
+}
+
 // dx1 = dy + adjoint of MLP(LN_2(.)) at x1.  The six parameter gradients (both fully connected
 // layers, gamma and beta of LN_2) are written to their final places, or added there when
 // `accumulate` is set.  `zero` (may be null) is an fp32 array of nzero entries the first kernel
 // clears on the way, for a later launch of the caller's.  `pack` is what the forward call of the
-// same layer wrote; `ws` holds astl_mlp_bwd_ws_bytes().
+// same layer wrote; `ws` holds astl_mlp_bwd_ws_bytes().  With `deferred` non-null the final sum over the
+// workgroups' partial results is not launched: its arguments are returned there and the caller runs
+// astl_mlp_reduce_block for astl_mlp_reduce_blocks() blocks of 256 threads in a launch of its own.
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
                                float *db_fc2, float *dln_w, float *dln_b, int accumulate, float *zero, long nzero,
-                               const void *pack, void *ws, hipStream_t s);
+                               const void *pack, void *ws, MlpReduceArgs *deferred, hipStream_t s);
 
 } // namespace gswa

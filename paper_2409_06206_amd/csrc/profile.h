@@ -39,6 +39,7 @@ enum KernelId {
     K_MLP_BWD,      // adjoint of Eq. 5 in one launch
     K_MLP_PACK,     // the MLP's weights into MFMA fragment order (once per forward call)
     K_MLP_REDUCE,   // per-workgroup partial weight gradients of the MLP -> gradients
+    K_LN_FWD_REDUCE, // LayerNorm of every token and that sum in one launch
     K_COUNT
 };
 

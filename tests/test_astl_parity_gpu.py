@@ -107,9 +107,9 @@ def test_narrow_bf16_layers_take_the_fused_mlp_kernels():
         names, dropped = gswa.gswa_profile_collect()
         gswa.gswa_profile_enable(False)
         assert dropped == 0
-        assert ("mlp_fwd" in names and "mlp_bwd" in names and "mlp_reduce" in names) == fused, names
+        assert ("mlp_fwd" in names and "mlp_bwd" in names and "ln_fwd+mlp_reduce" in names) == fused, names
         assert ("fc1_linear" in names and "gelu_fwd" in names and "fc_wgrad" in names) == (not fused), names
-        assert names["ln_fwd"][1] == (2 if fused else 4) and names["ln_bwd"][1] == (1 if fused else 2), names
+        assert names["ln_fwd"][1] == (1 if fused else 4) and names["ln_bwd"][1] == (1 if fused else 2), names
 
 
 @pytest.mark.parametrize("C,hidden", [(64, 120), (60, 128), (32, 64), (28, 60), (16, 24)])
