@@ -70,7 +70,7 @@ def check_case(oracle, B, H, W, C, heads, groups, window, shift, dtype, seed=syn
 
 
 def check_block(oracle, B, H, W, C, heads, groups, window, shift, dtype, hidden, seed=synth.LAYER_SEED0,
-                regime="stress", backward=True, tol_scale=1.0, extra_flags=0, dqk=0, eps=1e-5):
+                regime="stress", backward=True, tol_scale=1.0, extra_flags=0, dqk=0, eps=1e-5, cascade=True):
     """Whole layer (Eq. 4-5): ``oracle`` is the astl_oracle module."""
     from paper_2409_06206_amd import runner
     import torch
@@ -78,7 +78,10 @@ def check_block(oracle, B, H, W, C, heads, groups, window, shift, dtype, hidden,
     x, dy = synth.activations(B, H, W, C, synth.ACT_SEED + seed - synth.LAYER_SEED0)
     p = {k: synth.quantize(v, dtype) for k, v in p.items()}
     x, dy = synth.quantize(x, dtype), synth.quantize(dy, dtype)
-    kw = dict(heads=heads, groups=groups, window=window, shift=shift, eps=eps, dqk=dqk)
+    kw = dict(heads=heads, groups=groups, window=window, shift=shift, eps=eps, dqk=dqk, cascade=cascade)
+    if not cascade:
+        from paper_2409_06206_amd import gswa
+        extra_flags |= gswa.GSWA_NO_CASCADE
     want = {"y": oracle.forward(x, p, **kw)}
     if backward:
         dx, g = oracle.backward(x, dy, p, **kw)

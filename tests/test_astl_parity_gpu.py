@@ -93,6 +93,20 @@ def test_benchmark_shape_pair_against_the_oracle():
         parity.check_block(astl_oracle, seed=synth.LAYER_SEED0 + li, **case)
 
 
+@pytest.mark.parametrize("case", [SMALL[0], SMALL[8]], ids=_id)
+def test_groups_without_the_cascade(case):
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, cascade=False, **case)
+
+
+@pytest.mark.parametrize("eps", [1e-6, 1e-2, 0.5])
+def test_eps_enters_both_layer_norms(eps):
+    """A large eps changes the result visibly; both sides must take it from the descriptor."""
+    case = dict(SMALL[7])
+    print("case", case, "eps", eps, flush=True)
+    parity.check_block(astl_oracle, eps=eps, **case)
+
+
 def test_narrow_bf16_layers_take_the_fused_mlp_kernels():
     """The kernel timing aid names what ran: one fused launch per pass for the MLP half of a narrow
     bf16 layer, the per-step kernels otherwise (fp32, wide layers, forced)."""
