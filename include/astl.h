@@ -61,9 +61,10 @@ typedef struct astl_grads {
  * Sizes, in bytes, of the caller-provided device buffers (all multiples of 256; any output
  * pointer may be NULL).
  *   *saved_bytes   what astl_forward leaves for astl_backward: x1 [B*H*W, C] in the layer's
- *                  element type and the attention layer's own saved state.  LayerNorm outputs,
- *                  the hidden layer and its pre-activation are never kept: backward recomputes
- *                  them from x and x1.
+ *                  element type, the attention layer's own saved state and, where the MLP runs
+ *                  on the fused kernels (bf16, C <= 64, hidden <= 128), its weights repacked for
+ *                  the matrix cores (65 KB).  LayerNorm outputs, the hidden layer and its
+ *                  pre-activation are never kept: backward recomputes them from x and x1.
  *   *fwd_ws_bytes  scratch of astl_forward (normalised input, attention output, the attention
  *                  layer's scratch, and one [B*H*W, hidden] buffer where the MLP is not fused);
  *                  for inference (saved == NULL) the scratch must hold *fwd_ws_bytes +
