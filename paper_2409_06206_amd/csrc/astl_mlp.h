@@ -18,20 +18,19 @@ hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf
                                const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
                                hipStream_t s);
 
-// The backward kernel also needs one unused channel and one unused hidden feature in its padded
-// tiles (C not a multiple of 32, hidden not a multiple of 64): the bias sums ride there.
+// The backward kernel covers the same shapes.
 bool astl_mlp_bwd_supported(int C, int hidden);
 
 // Scratch bytes of the backward (one pair of partial weight-gradient matrices per workgroup).
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden);
 
 // Sums the workgroups' partial results and writes (or adds to) the six parameter gradients:
-//   d Wfc1[f][c] = M1[f][c], d bfc1[f] = M1[f][last column], d Wfc2[c][f] = M2[f][c], d bfc2[c] = M2[last row][c],
-//   d gamma, d beta of LN_2 from the two rows behind the matrices.
+//   d Wfc1[f][c] = M1[f][c], d Wfc2[c][f] = M2[f][c]; d gamma, d beta of LN_2 and the two bias
+//   gradients from the vectors behind the matrices.
 // 32 entries per block, the workgroups in 8 slices with eight loads in flight per thread.
 struct MlpReduceArgs {
     const float *part;
-    int nparts, rows, cols; // a workgroup's partial results are [2][rows][cols] then [2][cols]
+    int nparts, rows, cols; // a workgroup's partial results: [2][rows][cols], [2][cols] (LN_2), [rows], [cols] (biases)
     int C, Hd;
     int accumulate;
     float *dw1, *db1, *dw2, *db2, *dln_w, *dln_b;
@@ -39,7 +38,7 @@ struct MlpReduceArgs {
 
 inline unsigned astl_mlp_reduce_blocks(const MlpReduceArgs &r)
 {
-    return (unsigned)((2L * r.rows * r.cols + 2L * r.cols + 31) / 32);
+    return (unsigned)((2L * r.rows * r.cols + 3L * r.cols + r.rows + 31) / 32);
 }
 
 // work of block `block` of astl_mlp_reduce_blocks() blocks of 256 threads
@@ -47,7 +46,7 @@ __device__ __forceinline__ void astl_mlp_reduce_block(const MlpReduceArgs &a, in
 {
     __shared__ float red[8][33];
     const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
-    const long mats = (long)2 * a.rows * a.cols, per = mats + 2 * a.cols;
+    const long mats = (long)2 * a.rows * a.cols, per = mats + 3 * a.cols + a.rows;
     const long i = (long)block * 32 + col;
     float acc = 0.f;
     if (i < per) {
@@ -71,16 +70,17 @@ __device__ __forceinline__ void astl_mlp_reduce_block(const MlpReduceArgs &a, in
             const int which = (int)(i / ((long)a.rows * a.cols));
             const int rem = (int)(i % ((long)a.rows * a.cols));
             const int f = rem / a.cols, c = rem % a.cols;
-            if (which == 0) {
-                if (f < a.Hd && c < a.C) dst = a.dw1 + (long)f * a.C + c;
-                else if (f < a.Hd && c == a.cols - 1) dst = a.db1 + f;
-            } else {
-                if (f < a.Hd && c < a.C) dst = a.dw2 + (long)c * a.Hd + f;
-                else if (f == a.rows - 1 && c < a.C) dst = a.db2 + c;
-            }
+            if (f < a.Hd && c < a.C) dst = which == 0 ? a.dw1 + (long)f * a.C + c : a.dw2 + (long)c * a.Hd + f;
         } else {
-            const int j = (int)(i - mats), c = j % a.cols;
-            if (c < a.C) dst = (j < a.cols ? a.dln_w : a.dln_b) + c;
+            const int j = (int)(i - mats);
+            if (j < 2 * a.cols) {
+                const int c = j % a.cols;
+                if (c < a.C) dst = (j < a.cols ? a.dln_w : a.dln_b) + c;
+            } else if (j < 2 * a.cols + a.rows) {
+                if (j - 2 * a.cols < a.Hd) dst = a.db1 + (j - 2 * a.cols);
+            } else if (j - 2 * a.cols - a.rows < a.C) {
+                dst = a.db2 + (j - 2 * a.cols - a.rows);
+            }
         }
         if (dst) *dst = a.accumulate ? *dst + sum : sum;
     }

@@ -308,10 +308,9 @@ __global__ __launch_bounds__(kFwdThreads) void astl_mlp_fwd_kernel(MlpArgs a)
 // round's tokens contiguous: h^T, dpre^T, LN_2(x1)^T and dy^T.
 // Phase 2, after a barrier: the products that reduce over tokens,
 //   M1[f][c] = sum_t dpre[t][f] LN_2(x1)[t][c] = d Wfc1,      M2[f][c] = sum_t h[t][f] dy[t][c] = d Wfc2^T,
-// wave w owning feature tile w of both (8 accumulator tiles, kept in registers over all rounds).
-// The unused last channel row of LN_2(x1)^T and the unused last feature row of h^T hold ones, so
-// that M1[:, last] = d bfc1 and M2[last, :] = d bfc2 come out of the same products.
-// Every workgroup stores its sums; a second kernel adds them up.
+// wave w owning feature tile w of both (8 accumulator tiles, kept in registers over all rounds);
+// the bias gradients are the same staged rows multiplied by a tile of ones (d bfc1 = row sums of
+// dpre^T, d bfc2 = row sums of dy^T).  Every workgroup stores its sums; a second kernel adds them up.
 constexpr int kBwdThreads = 512;
 constexpr int kBwdWaves = kBwdThreads / 64;
 constexpr int kTokPitch = 272;   // bytes per staged row: 128 tokens of bf16 + 16 (conflict-free 16-byte reads)
@@ -370,7 +369,7 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc_g.v[ct][i] = acc_b.v[ct][i] = 0.f;
-    f32x4 m1[CT], m2[CT];
+    f32x4 m1[CT], m2[CT], sb1 = {0.f, 0.f, 0.f, 0.f}, sb2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) m1[ct] = m2[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -404,11 +403,10 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
             bd[s] = b_frag<CT>(dy, s);
         }
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {   // LN_2(x1), with a one in the last (unused) channel row
+        for (int ct = 0; ct < CT; ++ct) {   // LN_2(x1)
             float xn[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) xn[i] = xh.v[ct][i] * gam.v[ct][i] + bet.v[ct][i];
-            if (ct == CT - 1 && q == 3) xn[3] = 1.f;
             stage4(xnT, 16 * ct + 4 * (ln >> 4), col, make_uint2(pack_bf16x2(xn[0], xn[1]), pack_bf16x2(xn[2], xn[3])));
         }
         uint2 dp[FT];
@@ -430,7 +428,6 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
                 h[i] = pre[i] * Phi;
                 dpre[i] = dh[i] * (Phi + pre[i] * phi);
             }
-            if (ft == FT - 1 && q == 3) h[3] = 1.f;  // the ones row (feature FT*16 - 1 is beyond the hidden width)
             dp[ft] = make_uint2(pack_bf16x2(dpre[0], dpre[1]), pack_bf16x2(dpre[2], dpre[3]));
             stage4(hT, 16 * ft + 4 * (ln >> 4), col, make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3])));
             stage4(dpT, 16 * ft + 4 * (ln >> 4), col, dp[ft]);
@@ -468,11 +465,16 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         // phase 2: the round's 128 tokens in four k-steps of 32
         if (wave < FT) {
             const int m = ln & 15, kq = ln >> 4;
+            const uint4 ones = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u); // bf16 1.0
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const size_t koff = (size_t)(32 * ks + 8 * kq) * 2;
                 const uint4 a1 = *reinterpret_cast<const uint4 *>(dpT + (size_t)(16 * wave + m) * kTokPitch + koff);
                 const uint4 a2 = *reinterpret_cast<const uint4 *>(hT + (size_t)(16 * wave + m) * kTokPitch + koff);
+                // bias sums: a product with ones puts the sum over tokens of every row in each column
+                sb1 = mma32(a1, ones, sb1);
+                if (wave < CT)
+                    sb2 = mma32(*reinterpret_cast<const uint4 *>(dyT + (size_t)(16 * wave + m) * kTokPitch + koff), ones, sb2);
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) {
                     const uint4 b1v = *reinterpret_cast<const uint4 *>(xnT + (size_t)(16 * ct + m) * kTokPitch + koff);
@@ -485,9 +487,10 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         __syncthreads();
     }
 
-    // the workgroup's sums: part[workgroup] = [2][FT*16][CT*16] matrices, then [2][CT*16] LayerNorm
-    // sums; lane holds column m, rows 4q + i
-    float *part = a.part + (size_t)blockIdx.x * (2 * FT * 16 * CT * 16 + 2 * CT * 16);
+    // the workgroup's sums: part[workgroup] = [2][FT*16][CT*16] matrices, [2][CT*16] LayerNorm sums,
+    // [FT*16] and [CT*16] bias sums; lane holds column m, rows 4q + i
+    constexpr int kMats = 2 * FT * 16 * CT * 16;
+    float *part = a.part + (size_t)blockIdx.x * (kMats + 2 * CT * 16 + FT * 16 + CT * 16);
     if (wave < FT) {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
@@ -497,6 +500,13 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
                 part[at] = m1[ct][i];
                 part[(size_t)FT * 16 * CT * 16 + at] = m2[ct][i];
             }
+        if (tok == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                part[kMats + 2 * CT * 16 + 16 * wave + 4 * q + i] = sb1[i];
+                if (wave < CT) part[kMats + 2 * CT * 16 + FT * 16 + 16 * wave + 4 * q + i] = sb2[i];
+            }
+        }
     }
 
     // d gamma, d beta: over the 16 tokens of the wave, then the waves of the workgroup
@@ -521,7 +531,7 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < kBwdWaves; ++w) s += red[(w * 2 + which) * CT * 16 + c];
-        part[2 * FT * 16 * CT * 16 + e] = c < C ? s : 0.f;
+        part[kMats + e] = c < C ? s : 0.f;
     }
     (void)Hd;
 }
@@ -610,17 +620,13 @@ hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf
 
 size_t astl_mlp_pack_bytes() { return align256(PackLayout<2, 4>::bytes); }
 
-// the backward needs a spare channel row and a spare feature row for the bias sums
-bool astl_mlp_bwd_supported(int C, int hidden)
-{
-    return astl_mlp_supported(C, hidden) && C % 32 != 0 && hidden % 64 != 0;
-}
+bool astl_mlp_bwd_supported(int C, int hidden) { return astl_mlp_supported(C, hidden); }
 
 size_t astl_mlp_bwd_ws_bytes(long rows, int C, int hidden)
 {
     (void)rows;
     const size_t ct16 = C <= 32 ? 32 : 64, ft16 = hidden <= 64 ? 64 : 128;
-    return align256((size_t)kBwdMaxBlocks * (2 * ft16 * ct16 + 2 * ct16) * sizeof(float));
+    return align256((size_t)kBwdMaxBlocks * (2 * ft16 * ct16 + 3 * ct16 + ft16) * sizeof(float));
 }
 
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,

@@ -128,8 +128,7 @@ def test_narrow_bf16_layers_take_the_fused_mlp_kernels():
 
 @pytest.mark.parametrize("C,hidden", [(64, 120), (60, 128), (32, 64), (28, 60), (16, 24)])
 def test_padding_edges_of_the_fused_mlp_tiles(C, hidden):
-    """Channel and hidden widths at and next to the tile sizes: full tiles leave no spare row for
-    the bias sums, so the backward of those layers runs on the per-step kernels."""
+    """Channel and hidden widths at and next to the tile sizes of the fused MLP kernels."""
     heads = 4 if C % 4 == 0 else 2
     case = dict(B=2, H=8, W=8, C=C, heads=heads, groups=2, window=4, shift=2, dtype="bf16", hidden=hidden)
     print("case", case, flush=True)
