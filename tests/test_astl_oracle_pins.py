@@ -216,3 +216,18 @@ def test_stack_is_the_composition_with_alternating_shift_and_its_gradients_follo
             flat[idx] = keep
             fd, an = (up - dn) / (2 * h), grad.reshape(-1)[idx]
             assert math.isclose(fd, an, rel_tol=5e-6, abs_tol=5e-7), (name, idx, fd, an)
+
+
+def test_oracle_unchanged_on_fp32_parity_case():
+    """Regression guard: the stored digest was written by tests/golden/make_golden.py (oracle only)."""
+    import json
+    import os
+    from tests.golden import make_golden
+    with open(os.path.join(os.path.dirname(make_golden.__file__), "astl_oracle.json")) as f:
+        stored = json.load(f)
+    now = make_golden.compute_astl()
+    for key, dig in stored.items():
+        if key == "case":
+            continue
+        np.testing.assert_allclose(now[key]["probe"], dig["probe"], rtol=1e-9, atol=1e-13)
+        np.testing.assert_allclose(now[key]["abs_sum"], dig["abs_sum"], rtol=1e-9)
