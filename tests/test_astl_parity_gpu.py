@@ -83,12 +83,14 @@ def test_accumulate_flag_adds_into_every_parameter_gradient(case):
         assert err <= 1e-3, (k, err)
 
 
-def test_benchmark_shape_pair_against_the_oracle():
-    """Two layers (shifts 0 and 4) at the benchmark's full size, every output element."""
-    cfg = synth.CONFIGS["c2"]
+@pytest.mark.parametrize("name", ["astl_c2", "astl_agile"])
+def test_benchmark_shape_pair_against_the_oracle(name):
+    """The two layers of a whole-layer workload at its full size, every output element."""
+    cfg = synth.CONFIGS[name]
     for li, shift in enumerate(cfg["layers"]):
         case = dict(B=cfg["B"], H=cfg["H"], W=cfg["W"], C=cfg["C"], heads=cfg["heads"], groups=2,
-                    window=cfg["window"], shift=shift, dtype=cfg["dtype"], hidden=2 * cfg["C"])
+                    window=cfg["window"], shift=shift, dtype=cfg["dtype"], hidden=cfg["hidden"],
+                    dqk=cfg.get("dqk", 0))
         print("case", case, flush=True)
         parity.check_block(astl_oracle, seed=synth.LAYER_SEED0 + li, **case)
 
