@@ -403,9 +403,17 @@ int make_plan(const astl_desc *d, Plan *p)
         if (rc_ != GSWA_OK) return rc_; \
     } while (0)
 
+// What a sequence of layers hands from one forward call to the next: all layers of a sequence
+// use the same scratch, whose first slot holds LN_1(x) of the running layer.
+struct LayerLink {
+    bool have_ln1;             // in: the slot already holds LN_1(x) of this layer
+    const astl_params *next;   // in: the layer that follows (null: none)
+    bool emitted;              // out: the slot now holds LN_1 of the next layer's input
+};
+
 template <typename T>
 int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params *p, T *y, char *saved,
-              char *ws, hipStream_t st)
+              char *ws, hipStream_t st, LayerLink *link)
 {
     const long rows = pl.T;
     const int C = pl.C, Hd = pl.Hd;
@@ -420,18 +428,25 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
     void *pack = (saved ? saved + pl.saved : ws + pl.fwd_ws + pl.saved) - pl.pack;
 
     // Eq. 4: x1 = GSWA(LN_1(x)) + x
-    LnArgs l1{};
-    l1.u = x; l1.gamma = p->ln1_w; l1.beta = p->ln1_b; l1.out = xn; l1.rows = rows; l1.C = C; l1.eps = d->eps;
-    ASTL_HIP(launch_ln_fwd<T>(l1, st));
+    if (!(link && link->have_ln1)) {
+        LnArgs l1{};
+        l1.u = x; l1.gamma = p->ln1_w; l1.beta = p->ln1_b; l1.out = xn; l1.rows = rows; l1.C = C; l1.eps = d->eps;
+        ASTL_HIP(launch_ln_fwd<T>(l1, st));
+    }
+    if (link) link->emitted = false;
     ASTL_RC(gswa_forward(&d->attn, xn, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, a, at_saved,
                          rest, st));
     if (pl.fused_mlp) {
-        // Eq. 4's skip and the whole of Eq. 5 in one launch
+        // Eq. 4's skip and the whole of Eq. 5 in one launch; in a sequence of layers also LN_1 of
+        // the layer that follows (the slot's present content is no longer needed by then)
+        const astl_params *nx = link ? link->next : nullptr;
         ASTL_HIP(launch_astl_mlp_fwd(rows, C, Hd, d->eps, (const bf16_t *)x, (const bf16_t *)a,
                                      (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                      (const bf16_t *)p->w_fc2, (const bf16_t *)p->b_fc2,
-                                     (bf16_t *)x1, (bf16_t *)y, pack, st));
+                                     (bf16_t *)x1, (bf16_t *)y, pack, nx ? (const bf16_t *)nx->ln1_w : nullptr,
+                                     nx ? (const bf16_t *)nx->ln1_b : nullptr, nx ? (bf16_t *)xn : nullptr, st));
+        if (link && nx) link->emitted = true;
         return GSWA_OK;
     }
     // Eq. 5: y = MLP(LN_2(x1)) + x1
@@ -565,6 +580,9 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     return GSWA_OK;
 }
 
+int forward_checked(const astl_desc *desc, const void *x, const astl_params *p, void *y, void *saved, void *ws,
+                    void *hip_stream, LayerLink *link);
+
 } // namespace
 
 } // namespace gswa
@@ -587,6 +605,18 @@ int astl_query_bytes(const astl_desc *desc, size_t *saved_bytes, size_t *fwd_ws_
 int astl_forward(const astl_desc *desc, const void *x, const astl_params *p, void *y, void *saved, void *ws,
                  void *hip_stream)
 {
+    return forward_checked(desc, x, p, y, saved, ws, hip_stream, nullptr);
+}
+
+} // extern "C"
+
+namespace gswa {
+namespace {
+
+// astl_forward with the hand-over between the layers of a sequence (link may be null)
+int forward_checked(const astl_desc *desc, const void *x, const astl_params *p, void *y, void *saved, void *ws,
+                    void *hip_stream, LayerLink *link)
+{
     Plan pl;
     int rc = make_plan(desc, &pl);
     if (rc != GSWA_OK) return rc;
@@ -600,9 +630,14 @@ int astl_forward(const astl_desc *desc, const void *x, const astl_params *p, voi
         return GSWA_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->attn.dtype == GSWA_F32)
-        return forward_t<float>(desc, pl, (const float *)x, p, (float *)y, (char *)saved, (char *)ws, st);
-    return forward_t<bf16_t>(desc, pl, (const bf16_t *)x, p, (bf16_t *)y, (char *)saved, (char *)ws, st);
+        return forward_t<float>(desc, pl, (const float *)x, p, (float *)y, (char *)saved, (char *)ws, st, link);
+    return forward_t<bf16_t>(desc, pl, (const bf16_t *)x, p, (bf16_t *)y, (char *)saved, (char *)ws, st, link);
 }
+
+} // namespace
+} // namespace gswa
+
+extern "C" {
 
 int astl_backward(const astl_desc *desc, const void *x, const void *dy, const astl_params *p, const void *saved,
                   void *dx, const astl_grads *g, void *ws, void *hip_stream)
@@ -724,6 +759,7 @@ int astl_stack_forward(const astl_stack_desc *desc, const void *x, const astl_pa
     char *abuf[2] = {w, w + sp.A};
     char *layer_ws = w + 2 * sp.A;
     const void *in = x;
+    LayerLink link{};
     for (int l = 0; l < sp.L; ++l) {
         const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
         void *out, *lsaved = nullptr;
@@ -732,7 +768,10 @@ int astl_stack_forward(const astl_stack_desc *desc, const void *x, const astl_pa
         else if (sv && (l + 1) % sp.k == 0) out = sv + (size_t)((l + 1) / sp.k - 1) * sp.A; // input of the next block
         else out = abuf[l & 1];
         if (sv && sp.k == 0) lsaved = sv + (size_t)l * (sp.S + sp.A);
-        rc = astl_forward(ld, in, params + l, out, lsaved, layer_ws, hip_stream);
+        // LN_1 of the next layer comes out of this layer's last kernel where that kernel is the fused one
+        link.have_ln1 = link.emitted;
+        link.next = l + 1 < sp.L ? params + l + 1 : nullptr;
+        rc = forward_checked(ld, in, params + l, out, lsaved, layer_ws, hip_stream, &link);
         if (rc != GSWA_OK) return rc;
         in = out;
     }
@@ -776,10 +815,13 @@ int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *
         const int l0 = b * sp.k, l1 = (l0 + sp.k < sp.L) ? l0 + sp.k : sp.L;
         const void *block_in = b == 0 ? x : sv + (size_t)(b - 1) * sp.A;
         const void *in = block_in;
+        LayerLink link{};
         for (int l = l0; l < l1; ++l) {
             const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
             char *st = region + (size_t)(l - l0) * slot;
-            rc = astl_forward(ld, in, params + l, st + sp.S, st, layer_ws, hip_stream);
+            link.have_ln1 = link.emitted;
+            link.next = l + 1 < l1 ? params + l + 1 : nullptr;
+            rc = forward_checked(ld, in, params + l, st + sp.S, st, layer_ws, hip_stream, &link);
             if (rc != GSWA_OK) return rc;
             in = st + sp.S;
         }

@@ -12,11 +12,13 @@ bool astl_mlp_supported(int C, int hidden);
 size_t astl_mlp_pack_bytes();
 
 // x1 = x + a (stored);  y = MLP(LN_2(x1)) + x1.  rows tokens of C channels.  `pack` receives the
-// repacked weights (astl_mlp_pack_bytes() bytes, 16-byte aligned).
+// repacked weights (astl_mlp_pack_bytes() bytes, 16-byte aligned).  With next_ln_out non-null the
+// kernel also writes LN(y) with the given gamma and beta there: the first step of a layer that
+// follows (Eq. 4), of y as stored, at the same eps.
 hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
-                               hipStream_t s);
+                               const bf16_t *next_ln_w, const bf16_t *next_ln_b, bf16_t *next_ln_out, hipStream_t s);
 
 // The backward kernel covers the same shapes.
 bool astl_mlp_bwd_supported(int C, int hidden);

@@ -67,6 +67,8 @@ struct MlpArgs {
     const bf16_t *x, *a;       // forward: x1 = x + a;  backward: x = x1, a = dy
     const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
     bf16_t *x1, *y;            // forward outputs;  backward: y = dx1
+    const bf16_t *nxt_w, *nxt_b; // forward, optional: gamma, beta of the LayerNorm that will read y next ...
+    bf16_t *xn_out;            // ... and where its output goes (null: not wanted)
     float *zero;               // backward: fp32 array the kernel clears for a later launch of the caller's
     long nzero;
     void *pack;                // weights in fragment order, written by the pack kernel
@@ -230,6 +232,11 @@ __global__ __launch_bounds__(kFwdThreads) void astl_mlp_fwd_kernel(MlpArgs a)
     __syncthreads();
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tok = lane & 15, q = lane >> 4;
+    Row<CT> ngam, nbet;
+    if (a.xn_out) {
+        load_own<CT>(a.nxt_w, 0, true, C, q, ngam);
+        load_own<CT>(a.nxt_b, 0, true, C, q, nbet);
+    }
     const long ntiles = (a.rows + 15) / 16;
     const long tstep = (long)gridDim.x * kFwdWaves;
     long tile = (long)blockIdx.x * kFwdWaves + wave;
@@ -298,6 +305,20 @@ __global__ __launch_bounds__(kFwdThreads) void astl_mlp_fwd_kernel(MlpArgs a)
             y.v[ct][3] = acc[3] + b2.w + x1.v[ct][3];
         }
         store_own<CT>(a.y, t, ok, C, q, y);
+        if (a.xn_out) {
+            // the LayerNorm of the layer that follows, taken of y as stored
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) y.v[ct][i] = bf16_lo(pack_bf16x2(y.v[ct][i], 0.f));
+            Row<CT> yh;
+            normalise<CT>(y, C, q, a.eps, yh);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) yh.v[ct][i] = yh.v[ct][i] * ngam.v[ct][i] + nbet.v[ct][i];
+            store_own<CT>(a.xn_out, t, ok, C, q, yh);
+        }
     }
 }
 
@@ -607,13 +628,16 @@ bool astl_mlp_supported(int C, int hidden)
 hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
-                               hipStream_t s)
+                               const bf16_t *next_ln_w, const bf16_t *next_ln_b, bf16_t *next_ln_out, hipStream_t s)
 {
     if (!astl_mlp_supported(C, hidden)) return hipErrorInvalidValue;
     MlpArgs m{};
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x = x; m.a = a; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2; m.b_fc2 = b_fc2;
     m.x1 = x1; m.y = y; m.pack = pack;
+    if (next_ln_out && next_ln_w && next_ln_b) {
+        m.nxt_w = next_ln_w; m.nxt_b = next_ln_b; m.xn_out = next_ln_out;
+    }
     if (C <= 32) return hidden <= 64 ? launch_fwd_t<1, 2>(m, s) : launch_fwd_t<1, 4>(m, s);
     return hidden <= 64 ? launch_fwd_t<2, 2>(m, s) : launch_fwd_t<2, 4>(m, s);
 }
