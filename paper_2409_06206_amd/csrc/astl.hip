@@ -580,6 +580,22 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     return GSWA_OK;
 }
 
+bool params_ok(const astl_params *p)
+{
+    return p->ln1_w && p->ln1_b && p->w_qkv && p->b_qkv && p->w_proj && p->b_proj && p->bias_table && p->ln2_w &&
+           p->ln2_b && p->w_fc1 && p->b_fc1 && p->w_fc2 && p->b_fc2 &&
+           aligned16(p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, p->ln2_w, p->ln2_b,
+                     p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2);
+}
+
+bool grads_ok(const astl_grads *g)
+{
+    return g->ln1_w && g->ln1_b && g->w_qkv && g->b_qkv && g->w_proj && g->b_proj && g->bias_table && g->ln2_w &&
+           g->ln2_b && g->w_fc1 && g->b_fc1 && g->w_fc2 && g->b_fc2 &&
+           aligned16(g->ln1_w, g->ln1_b, g->w_qkv, g->b_qkv, g->w_proj, g->b_proj, g->bias_table, g->ln2_w, g->ln2_b,
+                     g->w_fc1, g->b_fc1, g->w_fc2, g->b_fc2);
+}
+
 int forward_checked(const astl_desc *desc, const void *x, const astl_params *p, void *y, void *saved, void *ws,
                     void *hip_stream, LayerLink *link);
 
@@ -620,14 +636,8 @@ int forward_checked(const astl_desc *desc, const void *x, const astl_params *p, 
     Plan pl;
     int rc = make_plan(desc, &pl);
     if (rc != GSWA_OK) return rc;
-    if (!x || !p || !y || !ws) return GSWA_EINVAL;
-    if (!p->ln1_w || !p->ln1_b || !p->w_qkv || !p->b_qkv || !p->w_proj || !p->b_proj || !p->bias_table ||
-        !p->ln2_w || !p->ln2_b || !p->w_fc1 || !p->b_fc1 || !p->w_fc2 || !p->b_fc2)
-        return GSWA_EINVAL;
-    if (x == y || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
-    if (!aligned16(x, y, saved, p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table,
-                   p->ln2_w, p->ln2_b, p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2))
-        return GSWA_EINVAL;
+    if (!x || !p || !y || !ws || !params_ok(p)) return GSWA_EINVAL;
+    if (x == y || (reinterpret_cast<uintptr_t>(ws) & 255) || !aligned16(x, y, saved)) return GSWA_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->attn.dtype == GSWA_F32)
         return forward_t<float>(desc, pl, (const float *)x, p, (float *)y, (char *)saved, (char *)ws, st, link);
@@ -645,19 +655,9 @@ int astl_backward(const astl_desc *desc, const void *x, const void *dy, const as
     Plan pl;
     int rc = make_plan(desc, &pl);
     if (rc != GSWA_OK) return rc;
-    if (!x || !dy || !p || !saved || !dx || !g || !ws) return GSWA_EINVAL;
-    if (!p->ln1_w || !p->ln1_b || !p->w_qkv || !p->b_qkv || !p->w_proj || !p->b_proj || !p->bias_table ||
-        !p->ln2_w || !p->ln2_b || !p->w_fc1 || !p->b_fc1 || !p->w_fc2 || !p->b_fc2)
-        return GSWA_EINVAL;
-    if (!g->ln1_w || !g->ln1_b || !g->w_qkv || !g->b_qkv || !g->w_proj || !g->b_proj || !g->bias_table ||
-        !g->ln2_w || !g->ln2_b || !g->w_fc1 || !g->b_fc1 || !g->w_fc2 || !g->b_fc2)
-        return GSWA_EINVAL;
+    if (!x || !dy || !p || !saved || !dx || !g || !ws || !params_ok(p) || !grads_ok(g)) return GSWA_EINVAL;
     if (dx == x || dx == dy || dx == saved || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
-    if (!aligned16(x, dy, saved, dx, p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table,
-                   p->ln2_w, p->ln2_b, p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2, g->ln1_w, g->ln1_b, g->w_qkv,
-                   g->b_qkv, g->w_proj, g->b_proj, g->bias_table, g->ln2_w, g->ln2_b, g->w_fc1, g->b_fc1,
-                   g->w_fc2, g->b_fc2))
-        return GSWA_EINVAL;
+    if (!aligned16(x, dy, saved, dx)) return GSWA_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->attn.dtype == GSWA_F32)
         return backward_t<float>(desc, pl, (const float *)x, (const float *)dy, p, (const char *)saved, (float *)dx,
@@ -669,22 +669,6 @@ int astl_backward(const astl_desc *desc, const void *x, const void *dy, const as
 } // extern "C"
 
 namespace {
-
-bool params_ok(const astl_params *p)
-{
-    return p->ln1_w && p->ln1_b && p->w_qkv && p->b_qkv && p->w_proj && p->b_proj && p->bias_table && p->ln2_w &&
-           p->ln2_b && p->w_fc1 && p->b_fc1 && p->w_fc2 && p->b_fc2 &&
-           aligned16(p->ln1_w, p->ln1_b, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, p->ln2_w, p->ln2_b,
-                     p->w_fc1, p->b_fc1, p->w_fc2, p->b_fc2);
-}
-
-bool grads_ok(const astl_grads *g)
-{
-    return g->ln1_w && g->ln1_b && g->w_qkv && g->b_qkv && g->w_proj && g->b_proj && g->bias_table && g->ln2_w &&
-           g->ln2_b && g->w_fc1 && g->b_fc1 && g->w_fc2 && g->b_fc2 &&
-           aligned16(g->ln1_w, g->ln1_b, g->w_qkv, g->b_qkv, g->w_proj, g->b_proj, g->bias_table, g->ln2_w, g->ln2_b,
-                     g->w_fc1, g->b_fc1, g->w_fc2, g->b_fc2);
-}
 
 // Sizes of a stack (Sec. "Agile Swin Transformer Block"): S, F, Bw are the largest saved / scratch
 // needs over the two kinds of layer (unshifted, shifted), A one [T, C] activation.
