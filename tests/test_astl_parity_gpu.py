@@ -137,6 +137,19 @@ def test_padding_edges_of_the_fused_mlp_tiles(C, hidden):
     parity.check_block(astl_oracle, **case)
 
 
+@pytest.mark.parametrize("case", [
+    dict(B=1, H=4, W=4, C=256, heads=4, groups=2, window=4, shift=1, dtype="f32", hidden=16),
+    dict(B=1, H=4, W=8, C=256, heads=8, groups=1, window=4, shift=0, dtype="bf16", hidden=24),
+    dict(B=2, H=4, W=4, C=4, heads=2, groups=2, window=2, shift=1, dtype="bf16", hidden=4),
+    dict(B=2, H=4, W=4, C=8, heads=2, groups=1, window=4, shift=2, dtype="f32", hidden=7),
+    dict(B=1, H=8, W=8, C=20, heads=2, groups=2, window=4, shift=0, dtype="bf16", hidden=36),
+], ids=_id)
+def test_extreme_widths(case):
+    """The widest supported map (256 channels), the narrowest fused one, an odd hidden width."""
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, **case)
+
+
 def test_ragged_token_count_in_the_fused_mlp_kernels():
     """Token counts that are not a multiple of the 16-token tiles or of the 128-token rounds."""
     for B, H, W in ((1, 4, 12), (3, 4, 4), (7, 8, 4)):
