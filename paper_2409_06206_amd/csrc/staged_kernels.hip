@@ -227,6 +227,149 @@ static int device_cus()
     return cus;
 }
 
+// The same map for wide layers whose whole weight matrix fits LDS as fragments (NT * KS <= 152 KB):
+// one workgroup per compute unit (1024 threads; 512 where the rows' own fragments need the
+// registers) builds all of them once, and a wave reads the rows
+// of its 16-row tile ONCE for all output columns (the chunked kernel above reads them once per 64
+// columns and rebuilds fragments per workgroup and chunk).
+template <int KSM, int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p, int KS, int NT)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
+    uint4 *wl = reinterpret_cast<uint4 *>(lsm);
+    const uint16_t *w = static_cast<const uint16_t *>(p.w);
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4, wave = tid >> 6;
+    constexpr int nthreads = NTHREADS, nwaves = NTHREADS / 64;
+    for (int i = tid; i < NT * KS * 64; i += nthreads) {
+        const int f = i >> 6, ln = i & 63;
+        const int nt = f / KS, ks = f - nt * KS;
+        const int n = 16 * nt + (ln & 15), k0 = 32 * ks + 8 * (ln >> 4);
+        if (p.w_sk == 1 && !(p.w_sn & 1) && !(reinterpret_cast<uintptr_t>(w) & 3)) {
+            // the lane's 8 input channels are contiguous: dword reads (K is even, so is w_sn)
+            const uint32_t *w32 = reinterpret_cast<const uint32_t *>(w + (long)n * p.w_sn);
+            uint32_t v[4];
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) v[dw] = (n < p.N && k0 + 2 * dw < p.K) ? w32[(k0 >> 1) + dw] : 0u;
+            wl[i] = make_uint4(v[0], v[1], v[2], v[3]);
+        } else {
+            uint32_t v[8];
+#pragma unroll
+            for (int s8 = 0; s8 < 8; ++s8)
+                v[s8] = (n < p.N && k0 + s8 < p.K) ? (uint32_t)w[(long)n * p.w_sn + (long)(k0 + s8) * p.w_sk] : 0u;
+            wl[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        }
+    }
+    __syncthreads();
+
+    const uint32_t *a1 = static_cast<const uint32_t *>(p.a1);
+    const uint32_t *a2 = static_cast<const uint32_t *>(p.a2);
+    const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
+    const uint16_t *add = static_cast<const uint16_t *>(p.add);
+    uint16_t *out = static_cast<uint16_t *>(p.out);
+    const bool out_even = !(reinterpret_cast<uintptr_t>(p.out) & 3);
+    const long ntile = (p.rows + 15) / 16;
+    for (long tile = (long)blockIdx.x * nwaves + wave; tile < ntile; tile += (long)gridDim.x * nwaves) {
+        const long row = 16 * tile + l16;
+        uint4 af[KSM];
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks) {
+            uint32_t v[4] = {0u, 0u, 0u, 0u};
+            const int k0 = 32 * ks + 8 * q;
+            if (ks < KS && row < p.rows) {
+                if (k0 + 8 <= p.K) { // the lane's 8 channels as one 16-byte read (dword aligned)
+                    const dwords4 u = *reinterpret_cast<const dwords4 *>(a1 + ((row * p.lda1 + k0) >> 1));
+#pragma unroll
+                    for (int dw = 0; dw < 4; ++dw) v[dw] = u.v[dw];
+                    if (a2) {
+                        const dwords4 u2 = *reinterpret_cast<const dwords4 *>(a2 + ((row * p.lda2 + k0) >> 1));
+#pragma unroll
+                        for (int dw = 0; dw < 4; ++dw)
+                            v[dw] = pack_bf16x2(bf16_lo(v[dw]) + bf16_lo(u2.v[dw]), bf16_hi(v[dw]) + bf16_hi(u2.v[dw]));
+                    }
+                } else {
+#pragma unroll
+                    for (int dw = 0; dw < 4; ++dw) {
+                        const int k = k0 + 2 * dw;
+                        if (k < p.K) {
+                            uint32_t u = a1[(row * p.lda1 + k) >> 1];
+                            if (a2) {
+                                const uint32_t u2 = a2[(row * p.lda2 + k) >> 1];
+                                u = pack_bf16x2(bf16_lo(u) + bf16_lo(u2), bf16_hi(u) + bf16_hi(u2));
+                            }
+                            v[dw] = u;
+                        }
+                    }
+                }
+            }
+            af[ks] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+        int opq = lane; // (opaque, so that the fragment reads are not hoisted out of the tile loop)
+        asm volatile("" : "+v"(opq));
+        for (int nt0 = 0; nt0 < NT; nt0 += 4) {
+            f32x4 acc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+                if (ks < KS) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)   // weights as the A operand: the transposed product
+                        if (nt0 + j < NT) acc[j] = mma32(wl[((nt0 + j) * KS + ks) * 64 + opq], af[ks], acc[j]);
+                }
+            // result: column l16 = row of the tile, rows 4q + r4 = four consecutive output features
+            if (row >= p.rows) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n0 = 16 * (nt0 + j) + 4 * q;
+                if (nt0 + j >= NT || n0 >= p.N) continue;
+                float v[4];
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int n = n0 + r4;
+                    v[r4] = acc[j][r4];
+                    if (n < p.N) {
+                        if (bias) v[r4] += __uint_as_float((uint32_t)bias[n] << 16);
+                        if (add) v[r4] += __uint_as_float((uint32_t)add[row * p.ldadd + n] << 16);
+                    }
+                }
+                uint16_t *dst = out + row * p.ldout + n0;
+                if (n0 + 4 <= p.N && out_even && !((row * p.ldout + n0) & 1)) {
+                    uint32_t *d32 = reinterpret_cast<uint32_t *>(dst);
+                    d32[0] = pack_bf16x2(v[0], v[1]);
+                    d32[1] = pack_bf16x2(v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        if (n0 + r4 < p.N) dst[r4] = f32_to_bf16_bits(v[r4]);
+                }
+            }
+        }
+    }
+}
+
+// the wide kernel serves maps with more than 64 output columns whose fragments fit LDS
+static bool linear_wide_ok(const LinearArgs &a)
+{
+    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
+    return a.N > 64 && ks <= 12 && (long)nt * ks <= 152 && a.rows >= 4096;
+}
+
+template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const LinearArgs &a, hipStream_t s)
+{
+    const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
+    const size_t lds = (size_t)nt * ks * 1024;
+    auto kern = linear_mfma_wide_kernel<KSM, NTHREADS>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       152 * 1024);
+    if (e != hipSuccess) return e;
+    const long ntile = (a.rows + 15) / 16;
+    long blocks = (ntile + NTHREADS / 64 - 1) / (NTHREADS / 64);
+    if (blocks > device_cus()) blocks = device_cus();
+    KernelTimer kt(a.prof_id, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), lds, s, a, ks, nt);
+    return hipGetLastError();
+}
+
 // true when the matrix-core kernel can serve the call (the dword reads need even offsets)
 static bool linear_mfma_ok(const LinearArgs &a)
 {
@@ -285,6 +428,8 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
 {
     if (a.rows <= 0 || a.N <= 0) return hipSuccess;
     if constexpr (sizeof(T) == 2) {
+        if (linear_mfma_ok(a) && linear_wide_ok(a))
+            return (a.K + 31) / 32 <= 6 ? launch_linear_wide_t<6, 1024>(a, s) : launch_linear_wide_t<12, 512>(a, s);
         if (linear_mfma_ok(a)) return launch_linear_mfma(a, nullptr, a.prof_id, nullptr, 0, s);
     }
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
