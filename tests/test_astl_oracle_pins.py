@@ -231,3 +231,105 @@ def test_oracle_unchanged_on_fp32_parity_case():
             continue
         np.testing.assert_allclose(now[key]["probe"], dig["probe"], rtol=1e-9, atol=1e-13)
         np.testing.assert_allclose(now[key]["abs_sum"], dig["abs_sum"], rtol=1e-9)
+
+
+# ---- the pins above are not vacuous: each plausible mistake, planted in a copy of the oracle's
+# ---- functions (CPU only), fails at least one of them
+
+
+_REAL_LN_BACKWARD = astl_oracle.layer_norm_backward   # bound before any test patches the module
+
+
+def _mistakes():
+    """name -> dict of replacement functions for astl_oracle (each one a plausible slip)."""
+    o = astl_oracle
+
+    def ln_unbiased(u, gamma, beta, eps):
+        mean = u.mean(axis=-1, keepdims=True)
+        var = ((u - mean) ** 2).sum(axis=-1, keepdims=True) / (u.shape[-1] - 1)
+        rstd = 1.0 / np.sqrt(var + eps)
+        xhat = (u - mean) * rstd
+        return xhat * gamma + beta, xhat, rstd
+
+    def ln_eps_outside(u, gamma, beta, eps):
+        mean = u.mean(axis=-1, keepdims=True)
+        var = ((u - mean) ** 2).mean(axis=-1, keepdims=True)
+        rstd = 1.0 / (np.sqrt(var) + eps)
+        xhat = (u - mean) * rstd
+        return xhat * gamma + beta, xhat, rstd
+
+    def ln_bwd_drops_projection(dout, xhat, rstd, gamma):
+        dxhat = dout * gamma
+        du = rstd * (dxhat - dxhat.mean(axis=-1, keepdims=True))
+        C = dout.shape[-1]
+        return du, (dout * xhat).reshape(-1, C).sum(axis=0), dout.reshape(-1, C).sum(axis=0)
+
+    def ln_bwd_gamma_from_scaled(dout, xhat, rstd, gamma):
+        du, _, db = _REAL_LN_BACKWARD(dout, xhat, rstd, gamma)
+        C = dout.shape[-1]
+        return du, (dout * gamma * xhat).reshape(-1, C).sum(axis=0), db
+
+    def gelu_tanh(t):
+        return 0.5 * t * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (t + 0.044715 * t ** 3)))
+
+    def gelu_grad_cdf_only(t):
+        from scipy.special import erf
+        return 0.5 * (1.0 + erf(t / np.sqrt(2.0)))
+
+    def mlp_transposed_second(u, w1, b1, w2, b2):
+        pre = u @ w1.T + b1
+        h = o.gelu(pre)
+        return h @ w2.reshape(w2.shape[1], w2.shape[0]) + b2, pre, h
+
+    return {
+        "variance with C-1": dict(layer_norm=ln_unbiased),
+        "eps outside the root": dict(layer_norm=ln_eps_outside),
+        "LN adjoint without the xhat projection": dict(layer_norm_backward=ln_bwd_drops_projection),
+        "d gamma from the scaled gradient": dict(layer_norm_backward=ln_bwd_gamma_from_scaled),
+        "tanh form of GELU": dict(gelu=gelu_tanh),
+        "GELU derivative without the density term": dict(gelu_grad=gelu_grad_cdf_only),
+        "second layer's weight reshaped instead of transposed": dict(mlp=mlp_transposed_second),
+    }
+
+
+PIN_TESTS = (test_gelu_matches_tabulated_gaussian_cdf, test_gelu_grad_is_the_derivative,
+             test_layer_norm_statistics_and_invariance, test_layer_norm_against_torch_cpu,
+             lambda: test_mlp_half_against_torch_cpu(12, 30),
+             test_whole_layer_is_the_composition_with_the_attention_oracle_and_torch, test_closed_forms,
+             lambda: test_gradients_by_central_differences(FD_CASES[0]))
+
+
+@pytest.mark.parametrize("name", sorted(_mistakes()))
+def test_pins_catch_a_planted_mistake(name, monkeypatch):
+    for attr, fn in _mistakes()[name].items():
+        monkeypatch.setattr(astl_oracle, attr, fn)
+    caught = 0
+    for t in PIN_TESTS:
+        try:
+            t()
+        except AssertionError:
+            caught += 1
+    assert caught >= 1, f"no pin notices: {name}"
+
+
+def test_pins_catch_a_dropped_skip_connection(monkeypatch):
+    """Eq. 5 without its skip, and the adjoint without the skip's gradient."""
+    real_forward, real_backward = astl_oracle.forward, astl_oracle.backward
+
+    def forward_no_skip(x, p, **kw):
+        want_mid = kw.pop("want_mid", False)
+        y, x1 = real_forward(x, p, want_mid=True, **kw)
+        return (y - x1, x1) if want_mid else y - x1
+
+    monkeypatch.setattr(astl_oracle, "forward", forward_no_skip)
+    with pytest.raises(AssertionError):
+        test_whole_layer_is_the_composition_with_the_attention_oracle_and_torch()
+    monkeypatch.setattr(astl_oracle, "forward", real_forward)
+
+    def backward_no_skip(x, dy, p, **kw):
+        dx, g = real_backward(x, dy, p, **kw)
+        return dx - dy, g          # as if the gradient over the outer skip were forgotten
+
+    monkeypatch.setattr(astl_oracle, "backward", backward_no_skip)
+    with pytest.raises(AssertionError):
+        test_gradients_by_central_differences(FD_CASES[0])
