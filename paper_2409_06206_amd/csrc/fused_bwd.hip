@@ -48,7 +48,10 @@ template <class Cf, int HB_, int HE_, bool WPROJ_ = (HE_ == Cf::HEADS)> struct B
     static constexpr size_t OFF_WQ = 0;
     static constexpr size_t OFF_BIAS = OFF_WQ + (size_t)N_WQ * 1024;
     static constexpr size_t OFF_WPT = OFF_BIAS + (size_t)16 * C;
-    static constexpr size_t OFF_WQT = OFF_WPT + (size_t)N_WPT * 1024;
+    // two heads of a wide three-head group fit LDS only without the Wproj^T fragments: those are
+    // then read from the packed buffer in memory (12 reads per wave, window and head)
+    static constexpr bool WPT_LDS = !(Cf::SPLIT && NH > 1 && Cf::HG == 3);
+    static constexpr size_t OFF_WQT = OFF_WPT + (WPT_LDS ? (size_t)N_WPT * 1024 : 0);
     static constexpr size_t PACK_BYTES = OFF_WQT + (size_t)N_WQT * 512;
     // LDS beyond the packed weights
     static constexpr int LD = 68; // pitch (bf16) of rows read 4 at a time
@@ -143,7 +146,8 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint4 *wq = reinterpret_cast<const uint4 *>(lds + B::OFF_WQ);
-    const uint4 *wpt = reinterpret_cast<const uint4 *>(lds + B::OFF_WPT);
+    const uint4 *wpt = B::WPT_LDS ? reinterpret_cast<const uint4 *>(lds + B::OFF_WPT)
+                                  : reinterpret_cast<const uint4 *>(pack + B::SRC_WPT);
     const uint2 *wqt = reinterpret_cast<const uint2 *>(lds + B::OFF_WQT);
     const float *bqkv = reinterpret_cast<const float *>(lds + B::OFF_BIAS);
     float *tblf = reinterpret_cast<float *>(lds + B::OFF_TBLF);
@@ -243,7 +247,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
         constexpr int N_Q = (int)((B::OFF_BIAS - B::OFF_WQ) / 16), N_PT = (int)((B::OFF_WQT - B::OFF_WPT) / 16);
         constexpr int N_QT = (int)((B::PACK_BYTES - B::OFF_WQT) / 16), N_T = NTBL * NH;
         constexpr int I_Q = (N_Q + 255) / 256, I_PT = (N_PT + 255) / 256, I_QT = (N_QT + 255) / 256, I_T = (N_T + 255) / 256;
-        uint4 vq[I_Q], vpt[I_PT], vqt[I_QT], vb = make_uint4(0u, 0u, 0u, 0u);
+        uint4 vq[I_Q], vpt[I_PT > 0 ? I_PT : 1], vqt[I_QT], vb = make_uint4(0u, 0u, 0u, 0u);
         uint16_t vt[I_T];
 #pragma unroll
         for (int k = 0; k < I_Q; ++k) { const int i = 256 * k + tid; vq[k] = reinterpret_cast<const uint4 *>(pack + B::SRC_WQ)[i < N_Q ? i : 0]; }
@@ -887,6 +891,10 @@ template <int G> struct ChunkPlan<true, G> {
     static constexpr int N = 6;
     static constexpr int B[6] = {5, 4, 3, 2, 1, 0}, E[6] = {6, 5, 4, 3, 2, 1};
 };
+// (with three groups a wide group is two heads, whose weights and buffers fit LDS together; of a
+// three-head group two heads fit)
+template <> struct ChunkPlan<true, 3> { static constexpr int N = 3; static constexpr int B[3] = {4, 2, 0}, E[3] = {6, 4, 2}; };
+template <> struct ChunkPlan<true, 2> { static constexpr int N = 4; static constexpr int B[4] = {4, 3, 1, 0}, E[4] = {6, 4, 3, 1}; };
 
 int bwd_grid(const Geom &g)
 {
