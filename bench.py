@@ -22,7 +22,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # (profiles/fused_kernels_c2_groups2_hbm_counters.txt), valid only for the kernel source they
 # were taken on: {(workload, groups, kernel): (sha256 of the kernel source, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c2", 2, "fused_bwd"): ("a3f5f0820f6cecc9cfbef9ba8ed980ee493e726c011977065fa7f08e7bca7c6c", 77147699),
+    ("c2", 2, "fused_bwd"): ("543025eaca5637d323d8b5d5adeea5f256205d5adcce7374e0e0048c8723f94e", 77146317),
 }
 
 
