@@ -264,3 +264,36 @@ def test_stack_matches_oracle_with_and_without_checkpointing(case, every):
     st.forward(keep=False)
     torch.cuda.synchronize()
     assert torch.equal(st.y, y_train)
+
+
+def _random_layers(n, seed):
+    """Seeded random whole-layer shapes that satisfy the divisibility rules: any window, head count,
+    head width, hidden width, narrow or plain queries and keys."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        M = int(rng.choice([2, 3, 4, 5, 6, 8]))
+        heads = int(rng.choice([1, 2, 3, 4, 6]))
+        groups = int(rng.choice([g for g in (1, 2, 3, 4, 6) if heads % g == 0]))
+        d = int(rng.integers(1, 11))
+        # (a LayerNorm over very few channels is ill-conditioned: 1/sqrt(var + eps) reaches eps^-1/2 when
+        # a token's channels nearly coincide, and fp32 rounding is amplified by that factor)
+        if heads * d > 256 or heads * d < 6:
+            continue
+        B, nh, nw = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        out.append(dict(B=B, H=nh * M, W=nw * M, C=heads * d, heads=heads, groups=groups, window=M,
+                        shift=int(rng.integers(0, M)), hidden=int(rng.integers(1, 140)),
+                        dqk=int(rng.choice([0, 0, 1, 3, 4]))))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_layers(14, 31), ids=_id)
+def test_random_layers_fp32(case):
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, dtype="f32", **case)
+
+
+@pytest.mark.parametrize("case", _random_layers(10, 32), ids=_id)
+def test_random_layers_bf16(case):
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, dtype="bf16", **case)
