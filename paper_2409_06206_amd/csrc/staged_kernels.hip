@@ -532,7 +532,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs p, long rows_
 
 // ---------------------------------------------------------------------------------------
 // The same reduction on the matrix cores (bf16): dw = dout^T (a1 + a2) contracts over tokens, so
-// tokens are the k-slots of both operands: a lane reads 8 consecutive tokens of one column.
+// tokens are the k-slots of both operands.  Rows that allow dword-aligned 16-byte reads are fetched
+// along the features and turned by a product with a 0/1 selector (see below); otherwise a lane
+// gathers 8 consecutive tokens of one column two bytes at a time.
 // A workgroup of 16 waves owns a 64 x 64 tile of dw and a range of tokens: wave (nw, tq) owns
 // the 16 rows n = 16*nw.. of the tile (all four 16-column tiles) and every fourth 32-token step
 // starting at tq; the bias sums ride in a fifth product with a column of ones.  The four token
@@ -576,6 +578,74 @@ __global__ __launch_bounds__(kWgradThreads) void wgrad_mfma_kernel(WgradArgs pa,
     f32x4 acc[4], bacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // Rows whose elements can be fetched as dword-aligned 16-byte pieces take the route below:
+    // a lane reads 8 consecutive FEATURES of one token (the natural, coalesced direction), and the
+    // matrix cores turn the tile: with the loaded tile as the A operand (m = token, k = feature)
+    // and a 0/1 selector as B, the product is the tile in result layout (column = feature, rows =
+    // tokens 4q..4q+3), which packed to bf16 IS the K = 16 operand that reduces over tokens.
+    const bool rows16 = !((p.lddout | p.lda1 | (a2 ? p.lda2 : 0)) & 1) && !(reinterpret_cast<uintptr_t>(dout) & 3) &&
+                        !(reinterpret_cast<uintptr_t>(a1) & 3) && !(a2 && (reinterpret_cast<uintptr_t>(a2) & 3));
+    if (rows16 && n0 < p.N && k0 < p.K) {
+        const int nb = blockIdx.x * 64 + 32 * (nw >> 1);     // the 32-feature block of dout this wave's 16 rows lie in
+        // selector for the 16-feature half `h` of a 32-feature block: 1.0 in the k-slot of feature 16h + l16
+        auto selector = [&](int h) {
+            const int j = 16 * h + l16 - 8 * q;
+            const uint32_t one1 = (j & 1) ? 0x3f800000u : 0x00003f80u;
+            const int dw = (j >= 0 && j < 8) ? (j >> 1) : -1;
+            return make_uint4(dw == 0 ? one1 : 0u, dw == 1 ? one1 : 0u, dw == 2 ? one1 : 0u, dw == 3 ? one1 : 0u);
+        };
+        const uint4 sel0 = selector(0), sel1 = selector(1);
+        const uint2 ones16 = l16 == 0 ? make_uint2(0x3f803f80u, 0x3f803f80u) : make_uint2(0u, 0u);
+        // 8 features of row t starting at feature f (zero beyond `width` and beyond the rows)
+        auto load8 = [&](const uint16_t *base, long ld, long t, int f, int width) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (t < t_end && f < width) {
+                if (f + 8 <= width) {
+                    const dwords4 u = *reinterpret_cast<const dwords4 *>(base + t * ld + f);
+                    v = make_uint4(u.v[0], u.v[1], u.v[2], u.v[3]);
+                } else {
+                    uint32_t e[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) e[j] = f + j < width ? (uint32_t)base[t * ld + f + j] : 0u;
+                    v = make_uint4(e[0] | e[1] << 16, e[2] | e[3] << 16, e[4] | e[5] << 16, e[6] | e[7] << 16);
+                }
+            }
+            return v;
+        };
+        auto add8 = [](uint4 x, uint4 y) {
+            return make_uint4(pack_bf16x2(bf16_lo(x.x) + bf16_lo(y.x), bf16_hi(x.x) + bf16_hi(y.x)),
+                              pack_bf16x2(bf16_lo(x.y) + bf16_lo(y.y), bf16_hi(x.y) + bf16_hi(y.y)),
+                              pack_bf16x2(bf16_lo(x.z) + bf16_lo(y.z), bf16_hi(x.z) + bf16_hi(y.z)),
+                              pack_bf16x2(bf16_lo(x.w) + bf16_lo(y.w), bf16_hi(x.w) + bf16_hi(y.w)));
+        };
+        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+        auto fetch = [&](long t0, uint4 &d, uint4 (&a)[2]) {
+            const long t = t0 + l16;
+            d = load8(dout, p.lddout, t, nb + 8 * q, p.N);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                a[b] = load8(a1, p.lda1, t, k0 + 32 * b + 8 * q, p.K);
+                if (a2) a[b] = add8(a[b], load8(a2, p.lda2, t, k0 + 32 * b + 8 * q, p.K));
+            }
+        };
+        long t0 = t_begin + 16 * tq;
+        uint4 dcur, acur[2];
+        fetch(t0, dcur, acur);
+        for (; t0 < t_end; t0 += 64) {
+            uint4 dnext, anext[2];
+            fetch(t0 + 64, dnext, anext);      // (all zero past the split's rows)
+            // turn the tiles: 16 tokens x this wave's 16 rows of dout, 16 tokens x 64 columns of a
+            const uint2 dT = pack_bf16x4(mma32(dcur, (nw & 1) ? sel1 : sel0, zero4));
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                if (k0 + 16 * kt >= p.K) continue; // uniform
+                const uint2 aT = pack_bf16x4(mma32(acur[kt >> 1], (kt & 1) ? sel1 : sel0, zero4));
+                acc[kt] = mma16(dT, aT, acc[kt]);
+            }
+            bacc = mma16(dT, ones16, bacc);
+            dcur = dnext; acur[0] = anext[0]; acur[1] = anext[1];
+        }
+    } else
     if (n0 < p.N && k0 < p.K)
         for (long t0 = t_begin + 32 * tq; t0 < t_end; t0 += 128) {
             uint32_t av[8], bv[4][8];
