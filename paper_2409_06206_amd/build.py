@@ -1,13 +1,15 @@
 """Compiles the HIP sources under csrc/ into paper_2409_06206_amd/libgswa.so for gfx950."""
+import concurrent.futures
 import glob
 import os
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgswa.so")
+OBJ_DIR = os.path.join(_HERE, "_build")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-munsafe-fp-atomics",
     # packed fp32 instructions are kept off
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -19,11 +21,26 @@ def sources():
     return sorted(glob.glob(os.path.join(_HERE, "csrc", "*.hip")))
 
 
-def build_library(verbose=False):
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB_PATH, *sources()]
+def _compile(hipcc, src, verbose):
+    obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+    cmd = [hipcc, *HIPCC_FLAGS, "-c", "-o", obj, src]
     if verbose:
-        print(" ".join(cmd))
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return obj
+
+
+def build_library(verbose=False, jobs=None):
+    """Every source is compiled (one hipcc per file, a few at a time), then linked."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sources()
+    jobs = jobs or min(len(srcs), max(1, min(8, os.cpu_count() or 1)))
+    with concurrent.futures.ThreadPoolExecutor(jobs) as pool:
+        objs = list(pool.map(lambda s: _compile(hipcc, s, verbose), srcs))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     return LIB_PATH
 
