@@ -60,7 +60,8 @@ typedef enum {
     GSWA_OK = 0,
     GSWA_EINVAL = -1,       /* null pointer, non-positive size, divisibility or shift range violated */
     GSWA_EUNSUPPORTED = -2, /* valid layer, but no kernel of this library covers it (e.g. LDS need)  */
-    GSWA_EHIP = -3          /* a HIP runtime call failed; gswa_last_hip_error() has its text         */
+    GSWA_EHIP = -3,         /* a HIP runtime call failed; gswa_last_hip_error() has its text         */
+    GSWA_ETOOBIG = -4       /* gswa_backward_static: the layer's scratch exceeds the built-in buffer  */
 } gswa_status;
 
 enum { GSWA_F32 = 0, GSWA_BF16 = 1 };
@@ -128,6 +129,26 @@ int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const vo
                   const void *bias_table, const void *saved, void *dx, void *dw_qkv,
                   void *db_qkv, void *dw_proj, void *db_proj, void *dbias_table, void *ws,
                   void *hip_stream);
+
+/*
+ * gswa_backward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and validation as gswa_backward, without `ws`: the scratch is a buffer of
+ * GSWA_STATIC_SCRATCH_BYTES that lives inside the library, one per GPU, held until the process
+ * ends.  The call allocates and frees nothing (its only runtime queries are hipGetDevice and,
+ * on the first call per device, the address lookup of that buffer).
+ *   - A layer whose *bwd_ws_bytes (gswa_query_bytes) exceeds GSWA_STATIC_SCRATCH_BYTES is
+ *     rejected with GSWA_ETOOBIG before anything is enqueued.
+ *   - All calls on one GPU share that GPU's buffer: two calls whose work overlaps in time on the
+ *     same GPU (different streams, or different host threads) race.  Serialise them on one stream.
+ *   - The buffer keeps the previous call's contents; the kernels clear what they accumulate into.
+ */
+#define GSWA_STATIC_SCRATCH_BYTES (96u * 1024u * 1024u)
+int gswa_backward_static(const gswa_desc *desc, const void *x, const void *dy, const void *w_qkv,
+                         const void *b_qkv, const void *w_proj, const void *b_proj,
+                         const void *bias_table, const void *saved, void *dx, void *dw_qkv,
+                         void *db_qkv, void *dw_proj, void *db_proj, void *dbias_table,
+                         void *hip_stream);
 
 /* Static text for a gswa_status value. */
 const char *gswa_strerror(int status);

@@ -5,6 +5,7 @@
 #include "staged_kernels.h"
 #include "fused.h"
 
+#include <mutex>
 #include <string>
 #include <type_traits>
 
@@ -21,6 +22,36 @@ int gswa::report_hip_error(hipError_t e)
 namespace {
 
 using namespace gswa;
+
+// Scratch of gswa_backward_static: device memory owned by the library itself, one copy per GPU
+// (allocated by the runtime when the code object is loaded on that GPU, held until the process
+// ends).  Host code never uses the array's name as an address: static_scratch() asks the runtime
+// for the device address once per device and hands that pointer on.
+constexpr size_t kStaticScratchBytes = (size_t)GSWA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+hipError_t static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 int hip_fail(hipError_t e) { return report_hip_error(e); }
 
@@ -348,6 +379,25 @@ int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const vo
                                    (float *)db_proj, (float *)dbias_table, (char *)ws, st);
 }
 
+int gswa_backward_static(const gswa_desc *desc, const void *x, const void *dy, const void *w_qkv,
+                         const void *b_qkv, const void *w_proj, const void *b_proj,
+                         const void *bias_table, const void *saved, void *dx, void *dw_qkv,
+                         void *db_qkv, void *dw_proj, void *db_proj, void *dbias_table,
+                         void *hip_stream)
+{
+    Geom g;
+    int rc = make_geom(desc, &g);
+    if (rc != GSWA_OK) return rc;
+    const Sizes s = make_sizes(desc, g);
+    if (s.bwd_ws > kStaticScratchBytes) return GSWA_ETOOBIG;
+    void *ws = nullptr;
+    GSWA_HIP(static_scratch(&ws));
+    // every kernel of the backward treats its scratch as undefined on entry and clears what it
+    // accumulates into, so the previous call's contents need no fill here
+    return gswa_backward(desc, x, dy, w_qkv, b_qkv, w_proj, b_proj, bias_table, saved, dx, dw_qkv, db_qkv,
+                         dw_proj, db_proj, dbias_table, ws, hip_stream);
+}
+
 const char *gswa_strerror(int status)
 {
     switch (status) {
@@ -355,6 +405,7 @@ const char *gswa_strerror(int status)
     case GSWA_EINVAL: return "invalid argument (null pointer, size, divisibility or shift range)";
     case GSWA_EUNSUPPORTED: return "layer shape not covered by any kernel of this library";
     case GSWA_EHIP: return "HIP runtime call failed";
+    case GSWA_ETOOBIG: return "layer needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }

@@ -10,11 +10,12 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgswa.so")
 
-GSWA_OK, GSWA_EINVAL, GSWA_EUNSUPPORTED, GSWA_EHIP = 0, -1, -2, -3
+GSWA_OK, GSWA_EINVAL, GSWA_EUNSUPPORTED, GSWA_EHIP, GSWA_ETOOBIG = 0, -1, -2, -3, -4
+GSWA_STATIC_SCRATCH_BYTES = 96 * 1024 * 1024
 GSWA_F32, GSWA_BF16 = 0, 1
 GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED = 1, 2, 4
 
-EXPORTS = ("gswa_query_bytes", "gswa_forward", "gswa_backward", "gswa_strerror",
+EXPORTS = ("gswa_query_bytes", "gswa_forward", "gswa_backward", "gswa_backward_static", "gswa_strerror",
            "gswa_last_hip_error", "gswa_version", "gswa_profile_enable",
            "gswa_profile_kernel_count", "gswa_profile_kernel_name", "gswa_profile_collect")
 
@@ -55,6 +56,8 @@ def lib():
         L.gswa_forward.restype = ctypes.c_int
         L.gswa_backward.argtypes = [dp] + [vp] * 16
         L.gswa_backward.restype = ctypes.c_int
+        L.gswa_backward_static.argtypes = [dp] + [vp] * 15
+        L.gswa_backward_static.restype = ctypes.c_int
         L.gswa_strerror.argtypes = [ctypes.c_int]
         L.gswa_strerror.restype = ctypes.c_char_p
         L.gswa_last_hip_error.restype = ctypes.c_char_p
@@ -131,6 +134,14 @@ def gswa_backward(desc, x, dy, w_qkv, b_qkv, w_proj, b_proj, bias_table, saved, 
                                _ptr(w_proj), _ptr(b_proj), _ptr(bias_table), _ptr(saved), _ptr(dx),
                                _ptr(dw_qkv), _ptr(db_qkv), _ptr(dw_proj), _ptr(db_proj),
                                _ptr(dbias_table), _ptr(ws), _stream(stream)))
+
+
+def gswa_backward_static(desc, x, dy, w_qkv, b_qkv, w_proj, b_proj, bias_table, saved, dx, dw_qkv,
+                         db_qkv, dw_proj, db_proj, dbias_table, stream=None):
+    _check(lib().gswa_backward_static(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(w_qkv), _ptr(b_qkv),
+                                      _ptr(w_proj), _ptr(b_proj), _ptr(bias_table), _ptr(saved), _ptr(dx),
+                                      _ptr(dw_qkv), _ptr(db_qkv), _ptr(dw_proj), _ptr(db_proj),
+                                      _ptr(dbias_table), _stream(stream)))
 
 
 def gswa_profile_enable(on):
