@@ -69,7 +69,13 @@ enum { GSWA_F32 = 0, GSWA_BF16 = 1 };
 enum {
     GSWA_NO_CASCADE = 1u << 0, /* drop Eq. 8: every group sees only its own channel slice          */
     GSWA_ACCUM_WGRAD = 1u << 1, /* backward adds into the five parameter gradients (no zero fill)  */
-    GSWA_FORCE_STAGED = 1u << 2 /* use the one-kernel-per-step path even where a fused kernel exists */
+    GSWA_FORCE_STAGED = 1u << 2, /* use the one-kernel-per-step path even where a fused kernel exists */
+    GSWA_DETERMINISTIC = 1u << 3 /* parameter gradients bit-identical from run to run on every path: the
+                                    one-kernel-per-step path then sums them in a fixed order (every split
+                                    of the token range and every window adds into a copy of its own, one
+                                    launch adds the copies) instead of with fp32 atomics; costs scratch
+                                    (64 copies + one bias-table gradient per window) and some time.  The
+                                    fused path always sums in a fixed order                               */
 };
 
 typedef struct gswa_desc {
@@ -77,7 +83,8 @@ typedef struct gswa_desc {
     int32_t heads, groups; /* C % heads == 0, heads % groups == 0                              */
     int32_t window, shift; /* H % window == 0, W % window == 0, 0 <= shift < window            */
     int32_t dtype;         /* GSWA_F32 or GSWA_BF16: x, y, dy, dx, weights, biases, bias table */
-    uint32_t flags;        /* OR of GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED       */
+    uint32_t flags;        /* OR of GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED,
+                              GSWA_DETERMINISTIC                                               */
     int32_t dqk;           /* channels of q and of k per head; 0 = C / heads (the plain layer) */
 } gswa_desc;
 
@@ -108,7 +115,9 @@ int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_
  *   saved  NULL for inference; otherwise receives what gswa_backward needs and must be left
  *          untouched until that call has run.
  *   ws     scratch, 256-byte aligned, sized by gswa_query_bytes; contents undefined afterwards.
- * x and y must not overlap.
+ *          May be NULL when the size the call needs is 0 (training forward on the fused path).
+ * y, saved and ws must each be disjoint, as byte ranges of the sizes above, from every other
+ * buffer of the call (GSWA_EINVAL otherwise).
  */
 int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const void *b_qkv,
                  const void *w_proj, const void *b_proj, const void *bias_table, void *y,
@@ -121,8 +130,9 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
  *   dw_qkv ... dbias_table fp32, overwritten, or added into with GSWA_ACCUM_WGRAD.
  *                         The fused path sums per-workgroup partials in a fixed order (same
  *                         bits every run); the staged path reduces with fp32 atomics, so its
- *                         last bits can differ between runs.
- * dx may not overlap x, dy or saved.
+ *                         last bits can differ between runs unless GSWA_DETERMINISTIC is set.
+ * dx, the five gradients and ws must each be disjoint, as byte ranges, from every other buffer of
+ * the call (GSWA_EINVAL otherwise); ws may be NULL only if *bwd_ws_bytes is 0.
  */
 int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const void *w_qkv,
                   const void *b_qkv, const void *w_proj, const void *b_proj,

@@ -126,23 +126,35 @@ def backward(x, dy, p, *, heads, groups, window, shift, eps=1e-5, cascade=True, 
     return dx + dx1, g
 
 
-def stack_forward(x, params, *, heads, groups, window, shift, eps=1e-5, dqk=0, want_inputs=False):
+def stack_forward(x, params, *, heads, groups, window, shift, eps=1e-5, dqk=0, want_inputs=False, store=None):
     """A sequence of layers (Sec. "Agile Swin Transformer Block"): layer l has shift 0 for even l and
-    ``shift`` for odd l, its own parameters ``params[l]``, and takes the output of layer l - 1."""
+    ``shift`` for odd l, its own parameters ``params[l]``, and takes the output of layer l - 1.
+
+    ``store`` (optional callable, array -> array) is applied to every activation that crosses a layer
+    boundary: with the rounding of the storage type it states that the tensor handed from one layer
+    to the next IS a tensor of that type ("bf16 activations with fp32 accumulation"); None keeps
+    fp64 throughout.  The arithmetic inside a layer is fp64 either way."""
     acts = [np.asarray(x, dtype=np.float64)]
     for l, p in enumerate(params):
-        acts.append(forward(acts[-1], p, heads=heads, groups=groups, window=window,
-                            shift=shift if l % 2 else 0, eps=eps, dqk=dqk))
+        y = forward(acts[-1], p, heads=heads, groups=groups, window=window,
+                    shift=shift if l % 2 else 0, eps=eps, dqk=dqk)
+        if store is not None and l + 1 < len(params):
+            y = np.asarray(store(y), dtype=np.float64)
+        acts.append(y)
     return (acts[-1], acts[:-1]) if want_inputs else acts[-1]
 
 
-def stack_backward(x, dy, params, *, heads, groups, window, shift, eps=1e-5, dqk=0):
-    """Gradients of sum(dy * y) through the sequence: (dx, list of per-layer gradient dicts)."""
+def stack_backward(x, dy, params, *, heads, groups, window, shift, eps=1e-5, dqk=0, store=None):
+    """Gradients of sum(dy * y) through the sequence: (dx, list of per-layer gradient dicts).
+    ``store`` as in stack_forward; it is also applied to the gradient handed from layer l to layer
+    l - 1 (the same boundary, crossed in the other direction)."""
     _, inputs = stack_forward(x, params, heads=heads, groups=groups, window=window, shift=shift, eps=eps,
-                              dqk=dqk, want_inputs=True)
+                              dqk=dqk, want_inputs=True, store=store)
     g = np.asarray(dy, dtype=np.float64)
     grads = [None] * len(params)
     for l in range(len(params) - 1, -1, -1):
         g, grads[l] = backward(inputs[l], g, params[l], heads=heads, groups=groups, window=window,
                                shift=shift if l % 2 else 0, eps=eps, dqk=dqk)
+        if store is not None and l > 0:
+            g = np.asarray(store(g), dtype=np.float64)
     return g, grads

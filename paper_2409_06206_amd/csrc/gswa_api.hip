@@ -78,7 +78,8 @@ int make_geom(const gswa_desc *d, Geom *g)
     if (d->shift < 0 || d->shift >= d->window) return GSWA_EINVAL;
     if (d->dqk < 0) return GSWA_EINVAL;
     if (d->dtype != GSWA_F32 && d->dtype != GSWA_BF16) return GSWA_EINVAL;
-    if (d->flags & ~(uint32_t)(GSWA_NO_CASCADE | GSWA_ACCUM_WGRAD | GSWA_FORCE_STAGED)) return GSWA_EINVAL;
+    if (d->flags & ~(uint32_t)(GSWA_NO_CASCADE | GSWA_ACCUM_WGRAD | GSWA_FORCE_STAGED | GSWA_DETERMINISTIC))
+        return GSWA_EINVAL;
     const long T = (long)d->B * d->H * d->W;
     const long nW = T / ((long)d->window * d->window);
     if (d->window > 64 || d->dqk > 4096) return GSWA_EUNSUPPORTED;
@@ -106,6 +107,15 @@ int make_geom(const gswa_desc *d, Geom *g)
 
 size_t elem_size(const gswa_desc *d) { return d->dtype == GSWA_F32 ? 4 : 2; }
 
+// A device buffer as a byte range, for the overlap rules of the entry points.
+struct Range {
+    uintptr_t lo, hi;
+    Range(const void *p, size_t bytes) : lo(reinterpret_cast<uintptr_t>(p)), hi(lo + (p ? bytes : 0)) {}
+};
+bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; }
+// true when `out` shares a byte with any of the others
+template <typename... R> bool overlaps_any(const Range &out, const R &...others) { return (overlap(out, others) || ...); }
+
 struct Sizes {
     size_t saved, qkv, fwd_ws, bwd_ws;
     size_t act;          // bytes of the saved [T, C] activation at the start of `saved`
@@ -113,6 +123,7 @@ struct Sizes {
     size_t fused_bwd_ws; // partial sums of the fused backward
     size_t params;       // fp32 entries of all five parameter gradients (one copy of the staged backward)
     size_t reps, tpart;  // bytes of the gradient copies and of the per-window bias-table gradients
+    int nreps;           // gradient copies of the staged backward
     bool fused_fwd, fused_bwd;
 };
 
@@ -130,10 +141,13 @@ Sizes make_sizes(const gswa_desc *d, const Geom &g)
     s.fwd_ws = s.qkv;
     s.params = (size_t)g.groups * g.Rg * g.Cg + (size_t)g.groups * g.Rg + (size_t)g.C * g.C + g.C +
                (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
-    // (+ one bias-table gradient per window where the attention adjoint runs on the matrix cores)
-    s.tpart = (d->dtype == GSWA_BF16 && attn_core_mfma_supported(g))
+    // (+ one bias-table gradient per window where the attention adjoint runs on the matrix cores, and
+    // everywhere in the reproducible mode)
+    const bool det = (d->flags & GSWA_DETERMINISTIC) != 0;
+    s.tpart = (det || (d->dtype == GSWA_BF16 && attn_core_mfma_supported(g)))
                   ? align256((size_t)g.nW * (2 * g.M - 1) * (2 * g.M - 1) * g.heads * sizeof(float)) : 0;
-    s.reps = align256(kGradReplicas * s.params * sizeof(float));
+    s.nreps = det ? kDetReplicas : kGradReplicas;
+    s.reps = align256((size_t)s.nreps * s.params * sizeof(float));
     s.bwd_ws = 2 * s.qkv + s.reps + s.tpart;
     s.fused_fwd = use_fused_fwd(d, g);
     s.fused_bwd = s.fused_fwd && fused_bwd_supported(g);
@@ -207,12 +221,15 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
     const long P = (long)sz.params;
     const long o_wq = 0, o_bq = o_wq + (long)G * Rg * Cg, o_wp = o_bq + (long)G * Rg, o_bp = o_wp + (long)C * C;
     const long o_tb = o_bp + C;
+    const long n_tb = (long)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
     // (the copies are cleared by the first launch of the loop below)
     // adjoint of Eq. 7 with respect to the projection parameters
     WgradArgs wp{};
     wp.dout = dy; wp.lddout = C;
     wp.a1 = attn; wp.lda1 = C;
-    wp.dw = rep + o_wp; wp.db = rep + o_bp; wp.rep_stride = P; wp.reps = kGradReplicas;
+    const bool det = (flags & GSWA_DETERMINISTIC) != 0;
+    const int nreps = sz.nreps;
+    wp.dw = rep + o_wp; wp.db = rep + o_bp; wp.rep_stride = P; wp.reps = nreps; wp.exclusive = det;
     wp.rows = g.T; wp.N = C; wp.K = C; wp.prof_id = K_PROJ_WGRAD;
     // (independent of everything else: enqueued together with the first group's weight gradient)
 
@@ -234,7 +251,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         if (grp < G - 1 && g.cascade) { lo.add = dx + (grp + 1) * Cg; lo.ldadd = C; }
         lo.out = dqkv + 2 * g.Qg; lo.ldout = Rg;
         lo.rows = g.T; lo.N = Cg; lo.K = C; lo.prof_id = K_DO_LINEAR;
-        GSWA_HIP(launch_linear_pair<T>(la, lo, grp == G - 1 ? rep : nullptr, (size_t)kGradReplicas * P, st));
+        GSWA_HIP(launch_linear_pair<T>(la, lo, grp == G - 1 ? rep : nullptr, (size_t)nreps * P, st));
         bool on_matrix_cores = false;
         if constexpr (std::is_same<T, bf16_t>::value) {
             if (attn_core_mfma_supported(g)) {
@@ -243,8 +260,14 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
                 on_matrix_cores = true;
             }
         }
-        if (!on_matrix_cores)
-            GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, rep + o_tb, P, kGradReplicas, st));
+        if (!on_matrix_cores) {
+            if (det) { // one copy per window, plain stores: summed in a fixed order at the end
+                GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, tpart, n_tb, 0, st));
+                table_per_window = true;
+            } else {
+                GSWA_HIP(launch_attn_bwd<T>(g, grp, qkv, dqkv, table, rep + o_tb, P, nreps, st));
+            }
+        }
         // dF_g = dqkv Wqkv_g  ->  dx[:, slice g]
         LinearArgs lx{};
         lx.a1 = dqkv; lx.lda1 = Rg;
@@ -257,17 +280,16 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         if (has_prev) { wq.a2 = attn + (grp - 1) * Cg; wq.lda2 = C; }
         wq.dw = rep + o_wq + (size_t)grp * Rg * Cg;
         wq.db = rep + o_bq + (size_t)grp * Rg;
-        wq.rep_stride = P; wq.reps = kGradReplicas;
+        wq.rep_stride = P; wq.reps = nreps; wq.exclusive = det;
         wq.rows = g.T; wq.N = Rg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
         GSWA_HIP(launch_wgrad_group<T>(wq, grp == G - 1 ? &wp : nullptr, lx, st));
     }
     ReplicaSum rs{};
-    rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;
+    rs.rep = rep; rs.stride = P; rs.reps = nreps;
     rs.out[0] = dw_qkv; rs.off[0] = o_wq; rs.n[0] = (long)G * Rg * Cg;
     rs.out[1] = db_qkv; rs.off[1] = o_bq; rs.n[1] = (long)G * Rg;
     rs.out[2] = dw_proj; rs.off[2] = o_wp; rs.n[2] = (long)C * C;
     rs.out[3] = db_proj; rs.off[3] = o_bp; rs.n[3] = C;
-    const long n_tb = (long)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
     if (table_per_window) {
         rs.count = 4;
         rs.tpart = tpart; rs.t_out = dtable; rs.t_off = o_tb; rs.t_n = n_tb; rs.t_windows = g.nW;
@@ -314,10 +336,22 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
     Geom g;
     int rc = make_geom(desc, &g);
     if (rc != GSWA_OK) return rc;
-    if (!x || !w_qkv || !b_qkv || !w_proj || !b_proj || !bias_table || !y || !ws) return GSWA_EINVAL;
-    if (x == y || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    if (!x || !w_qkv || !b_qkv || !w_proj || !b_proj || !bias_table || !y) return GSWA_EINVAL;
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return GSWA_EINVAL;
     if (!aligned16(x, w_qkv, b_qkv, w_proj, b_proj, bias_table, y, saved)) return GSWA_EINVAL;
     Sizes s = make_sizes(desc, g);
+    {
+        const size_t e = elem_size(desc), act = (size_t)g.T * g.C * e;
+        const size_t ws_bytes = saved ? s.fwd_ws : s.fwd_ws + s.saved;
+        if (!ws && ws_bytes > 0) return GSWA_EINVAL; // no scratch is only acceptable where none is used
+        const Range rx(x, act), ry(y, act), rsv(saved, s.saved), rws(ws, ws_bytes);
+        const Range rwq(w_qkv, (size_t)g.groups * g.Rg * g.Cg * e), rbq(b_qkv, (size_t)g.groups * g.Rg * e);
+        const Range rwp(w_proj, (size_t)g.C * g.C * e), rbp(b_proj, (size_t)g.C * e);
+        const Range rtb(bias_table, (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads * e);
+        if (overlaps_any(ry, rx, rsv, rws, rwq, rbq, rwp, rbp, rtb)) return GSWA_EINVAL;
+        if (overlaps_any(rsv, rx, rws, rwq, rbq, rwp, rbp, rtb)) return GSWA_EINVAL;
+        if (overlaps_any(rws, rx, rwq, rbq, rwp, rbp, rtb)) return GSWA_EINVAL;
+    }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->dtype == GSWA_F32)
         return forward_staged<float>(g, s, (const float *)x, (const float *)w_qkv, (const float *)b_qkv,
@@ -353,13 +387,32 @@ int gswa_backward(const gswa_desc *desc, const void *x, const void *dy, const vo
     int rc = make_geom(desc, &g);
     if (rc != GSWA_OK) return rc;
     if (!x || !dy || !w_qkv || !b_qkv || !w_proj || !b_proj || !bias_table || !saved || !dx ||
-        !dw_qkv || !db_qkv || !dw_proj || !db_proj || !dbias_table || !ws)
+        !dw_qkv || !db_qkv || !dw_proj || !db_proj || !dbias_table)
         return GSWA_EINVAL;
-    if (dx == x || dx == dy || dx == saved || (reinterpret_cast<uintptr_t>(ws) & 255)) return GSWA_EINVAL;
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return GSWA_EINVAL;
     if (!aligned16(x, dy, w_qkv, b_qkv, w_proj, bias_table, saved, dx, dw_qkv, db_qkv, dw_proj, db_proj,
                    dbias_table))
         return GSWA_EINVAL;
     Sizes s = make_sizes(desc, g);
+    {
+        const size_t e = elem_size(desc), act = (size_t)g.T * g.C * e;
+        if (!ws && s.bwd_ws > 0) return GSWA_EINVAL;
+        const size_t n_wq = (size_t)g.groups * g.Rg * g.Cg, n_bq = (size_t)g.groups * g.Rg;
+        const size_t n_wp = (size_t)g.C * g.C, n_tb = (size_t)(2 * g.M - 1) * (2 * g.M - 1) * g.heads;
+        const Range rx(x, act), rdy(dy, act), rsv(saved, s.saved), rdx(dx, act), rws(ws, s.bwd_ws);
+        const Range rwq(w_qkv, n_wq * e), rbq(b_qkv, n_bq * e), rwp(w_proj, n_wp * e), rbp(b_proj, (size_t)g.C * e);
+        const Range rtb(bias_table, n_tb * e);
+        const Range gwq(dw_qkv, n_wq * 4), gbq(db_qkv, n_bq * 4), gwp(dw_proj, n_wp * 4), gbp(db_proj, (size_t)g.C * 4);
+        const Range gtb(dbias_table, n_tb * 4);
+        // every output and the scratch: disjoint from every input and from each other
+        if (overlaps_any(rdx, rx, rdy, rsv, rws, rwq, rbq, rwp, rbp, rtb, gwq, gbq, gwp, gbp, gtb)) return GSWA_EINVAL;
+        if (overlaps_any(rws, rx, rdy, rsv, rwq, rbq, rwp, rbp, rtb, gwq, gbq, gwp, gbp, gtb)) return GSWA_EINVAL;
+        if (overlaps_any(gwq, rx, rdy, rsv, rwq, rbq, rwp, rbp, rtb, gbq, gwp, gbp, gtb)) return GSWA_EINVAL;
+        if (overlaps_any(gbq, rx, rdy, rsv, rwq, rbq, rwp, rbp, rtb, gwp, gbp, gtb)) return GSWA_EINVAL;
+        if (overlaps_any(gwp, rx, rdy, rsv, rwq, rbq, rwp, rbp, rtb, gbp, gtb)) return GSWA_EINVAL;
+        if (overlaps_any(gbp, rx, rdy, rsv, rwq, rbq, rwp, rbp, rtb, gtb)) return GSWA_EINVAL;
+        if (overlaps_any(gtb, rx, rdy, rsv, rwq, rbq, rwp, rbp, rtb)) return GSWA_EINVAL;
+    }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->dtype == GSWA_F32)
         return backward_staged<float>(g, s, desc->flags, (const float *)x, (const float *)dy,

@@ -24,6 +24,9 @@ struct LinearArgs {
 // backward accumulates every parameter gradient in kGradReplicas copies (a workgroup adds into
 // copy `its index mod kGradReplicas`), summed at the end by one launch.
 constexpr int kGradReplicas = 16;
+// Reproducible mode: the token range of a weight gradient is cut into at most this many splits and
+// every split owns a copy, so each entry of a copy is one addition onto zero.
+constexpr int kDetReplicas = 64;
 
 // dw[n,k] += sum_t dout[t,n] * (a1[t,k] + a2[t,k]);  db[n] += sum_t dout[t,n]   (fp32 atomics).
 // dw, db point into copy 0; copy r lies rep_stride floats further (reps copies; 1 = a single array).
@@ -35,6 +38,8 @@ struct WgradArgs {
     long rep_stride; int reps;
     long rows; int N, K;
     int prof_id;
+    int exclusive; // nonzero: at most `reps` splits of the token range, so that every copy receives exactly
+                   // one addition per entry (onto zero) and the sum over the copies has a fixed order
 };
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);
@@ -57,7 +62,8 @@ hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table,
 
 // Adjoint of the attention core for group `grp`.  On entry the v part of dqkv [T, Rg] holds
 // dO of the group; on exit dqkv holds dq|dk|dv.  dtable (fp32) is added into: copy
-// `window mod reps` of `reps` copies that lie rep_stride floats apart.
+// `window mod reps` of `reps` copies that lie rep_stride floats apart.  reps == 0: one copy per
+// window (rep_stride apart), written with plain stores (no zero fill needed, no atomics).
 template <typename T>
 hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
                            float *dtable, long rep_stride, int reps, hipStream_t s);

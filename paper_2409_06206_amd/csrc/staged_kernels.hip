@@ -722,6 +722,7 @@ static void wgrad_splits(const WgradArgs &a, long *rps, long *splits)
     if (s_ > max_splits) s_ = max_splits;
     const long resident = 2L * device_cus() / (tn * tk); // all workgroups on the chip at once
     if (s_ > resident && resident >= 8) s_ = resident;
+    if (a.exclusive && s_ > a.reps) s_ = a.reps; // every split then adds into a copy of its own
     if (s_ < 1) s_ = 1;
     long r = (a.rows + s_ - 1) / s_;
     r = (r + 127) / 128 * 128;
@@ -765,6 +766,7 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
     long splits = 2048 / (long)(tn * tk);
     const long max_splits = (a.rows + 255) / 256;
     if (splits > max_splits) splits = max_splits;
+    if (a.exclusive && splits > a.reps) splits = a.reps; // every split then adds into a copy of its own
     if (splits < 1) splits = 1;
     long rps = (a.rows + splits - 1) / splits;
     rps = (rps + 15) / 16 * 16;
@@ -964,7 +966,9 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
                                                             float *dtable, long rep_stride, int reps, int RS)
 {
     extern __shared__ float smem[];
-    dtable += (long)(blockIdx.x % reps) * rep_stride;
+    // reps == 0: every window owns a copy of its own (rep_stride apart), written with plain stores
+    const bool own_copy = reps == 0;
+    dtable += (long)(own_copy ? blockIdx.x : blockIdx.x % reps) * rep_stride;
     const int N = g.N, d = g.d, dp = d | 1, dq = g.dq, ep = dq | 1, Qg = g.Qg, Rg = g.Rg, M = g.M;
     const int ldS = N + 1, ntbl = (2 * M - 1) * (2 * M - 1);
     float *k = smem;
@@ -1031,7 +1035,6 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
         __syncthreads();
         // softmax and its adjoint, one wave per row; bias-table gradient pre-reduced in LDS
         for (int r = wave; r < rows; r += kThreads / 64) {
-            const int n = n0 + r, rn = n / M, cn = n - rn * M;
             float mx = -INFINITY;
             for (int m = lane; m < N; m += 64) mx = fmaxf(mx, P[r * ldS + m]);
             mx = wave_max(mx);
@@ -1051,13 +1054,22 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
             }
             dotp = wave_sum(dotp);
             for (int m = lane; m < N; m += 64) {
-                const float ds = P[r * ldS + m] * (dS[r * ldS + m] - dotp);
-                dS[r * ldS + m] = ds;
-                const int rm = m / M, cm = m - rm * M;
-                atomicAdd(&tbl[(rn - rm + M - 1) * (2 * M - 1) + (cn - cm + M - 1)], ds);
+                dS[r * ldS + m] = P[r * ldS + m] * (dS[r * ldS + m] - dotp);
             }
         }
         __syncthreads();
+        // bias-table gradient of the strip: entry (dr, dc) takes the pairs (n, m = n - (dr, dc)) whose
+        // key lies inside the window; one thread per entry, rows in ascending order (a fixed order)
+        for (int e = tid; e < ntbl; e += kThreads) {
+            const int dr = e / (2 * M - 1) - (M - 1), dc = e % (2 * M - 1) - (M - 1);
+            float acc = 0.f;
+            for (int r = 0; r < rows; ++r) {
+                const int n = n0 + r, rn = n / M, cn = n - rn * M;
+                const int rm = rn - dr, cm = cn - dc;
+                if ((unsigned)rm < (unsigned)M && (unsigned)cm < (unsigned)M) acc += dS[r * ldS + rm * M + cm];
+            }
+            tbl[e] += acc;
+        }
         // dq rows of this strip
         for (int e = tid; e < rows * dq; e += kThreads) {
             const int r = e / dq, c = e - r * dq;
@@ -1088,7 +1100,10 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(Geom g, int grp, con
         const int n = e / d, c = e - n * d;
         from_f32(dqkv[tok[n] * Rg + 2 * Qg + hl * d + c], dv[n * dp + c]);
     }
-    for (int e = tid; e < ntbl; e += kThreads) atomicAdd(&dtable[(long)e * g.heads + hd], tbl[e]);
+    for (int e = tid; e < ntbl; e += kThreads) {
+        if (own_copy) dtable[(long)e * g.heads + hd] = tbl[e];
+        else atomicAdd(&dtable[(long)e * g.heads + hd], tbl[e]);
+    }
 }
 
 
@@ -1096,7 +1111,7 @@ template <typename T>
 hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const T *table,
                            float *dtable, long rep_stride, int reps, hipStream_t s)
 {
-    if (reps < 1) return hipErrorInvalidValue;
+    if (reps < 0) return hipErrorInvalidValue;
     int rs = 0;
     const size_t lds = attn_bwd_lds_bytes(g, &rs);
     if (rs == 0) return hipErrorInvalidValue;

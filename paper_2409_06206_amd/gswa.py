@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libgswa.so")
 GSWA_OK, GSWA_EINVAL, GSWA_EUNSUPPORTED, GSWA_EHIP, GSWA_ETOOBIG = 0, -1, -2, -3, -4
 GSWA_STATIC_SCRATCH_BYTES = 96 * 1024 * 1024
 GSWA_F32, GSWA_BF16 = 0, 1
-GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED = 1, 2, 4
+GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED, GSWA_DETERMINISTIC = 1, 2, 4, 8
 
 EXPORTS = ("gswa_query_bytes", "gswa_forward", "gswa_backward", "gswa_backward_static", "gswa_strerror",
            "gswa_last_hip_error", "gswa_version", "gswa_profile_enable",

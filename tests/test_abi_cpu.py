@@ -187,3 +187,62 @@ def test_stack_descriptor_validation_and_sizes():
         astl.astl_stack_forward(astl.make_stack_desc(**base), fake, [full] * 11 + [{**full, "ln1_w": None}],
                                 fake + 0x1000, None, fake, stream=0)
     assert ei.value.status == gswa.GSWA_EINVAL
+
+
+def _spread(n, step=1 << 28):
+    """n fake device addresses far apart (never dereferenced: the calls below fail validation)."""
+    return [(i + 1) * step for i in range(n)]
+
+
+def test_partially_overlapping_buffers_are_rejected():
+    """Outputs and scratch are checked against every other buffer as byte ranges, not as pointers."""
+    desc = gswa.make_desc(**{**GOOD, "flags": gswa.GSWA_FORCE_STAGED})
+    act = 2 * 16 * 16 * 60 * 2
+    saved_b, fwd_b, bwd_b = gswa.gswa_query_bytes(desc)
+    x, wq, bq, wp, bp, tb, y, saved, ws = _spread(9)
+
+    def fwd(**kw):
+        a = dict(x=x, w_qkv=wq, b_qkv=bq, w_proj=wp, b_proj=bp, bias_table=tb, y=y, saved=saved, ws=ws)
+        a.update(kw)
+        with pytest.raises(gswa.GswaError) as ei:
+            gswa.gswa_forward(desc, a["x"], a["w_qkv"], a["b_qkv"], a["w_proj"], a["b_proj"], a["bias_table"],
+                              a["y"], a["saved"], a["ws"], stream=0)
+        assert ei.value.status == gswa.GSWA_EINVAL
+
+    fwd(y=x + 64)                       # y starts inside x
+    fwd(y=x - act + 256)                # y ends inside x
+    fwd(saved=ws + fwd_b - 256)         # saved starts inside the scratch
+    fwd(y=wp + 16)                      # y inside a weight
+    fwd(ws=x + act - 256)               # scratch starts inside x
+    fwd(ws=None)                        # this path needs scratch
+
+    dy, dx, gwq, gbq, gwp, gbp, gtb = [a + (1 << 27) for a in _spread(7)]
+
+    def bwd(**kw):
+        a = dict(x=x, dy=dy, saved=saved, dx=dx, dw_qkv=gwq, db_qkv=gbq, dw_proj=gwp, db_proj=gbp,
+                 dbias_table=gtb, ws=ws)
+        a.update(kw)
+        with pytest.raises(gswa.GswaError) as ei:
+            gswa.gswa_backward(desc, a["x"], a["dy"], wq, bq, wp, bp, tb, a["saved"], a["dx"], a["dw_qkv"],
+                               a["db_qkv"], a["dw_proj"], a["db_proj"], a["dbias_table"], a["ws"], stream=0)
+        assert ei.value.status == gswa.GSWA_EINVAL
+
+    bwd(dx=dy + 128)                    # dx starts inside dy
+    bwd(dx=saved + saved_b - 16)        # dx starts in the last bytes of saved
+    bwd(dw_qkv=ws + 1024)               # a gradient inside the scratch
+    bwd(db_proj=gwp + 60 * 60 * 4 - 16)  # two gradients share bytes
+    bwd(ws=x + 256)
+    bwd(ws=None)
+
+
+def test_reproducible_mode_is_a_valid_flag_and_sizes_its_scratch():
+    base = gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "dtype": "f32"}))
+    det = gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "dtype": "f32", "flags": gswa.GSWA_DETERMINISTIC}))
+    assert det[0] == base[0] and det[1] == base[1]
+    params = 3 * 60 * 60 // 2 + 3 * 60 + 60 * 60 + 60 + 15 * 15 * 6
+    per_window = 2 * 16 * 16 // 64 * 15 * 15 * 6 * 4
+    up = lambda b: (b + 255) // 256 * 256
+    assert det[2] - base[2] == up(64 * params * 4) - up(16 * params * 4) + up(per_window)
+    # the fused path sums in a fixed order anyway: the flag changes nothing there
+    assert gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "flags": gswa.GSWA_DETERMINISTIC})) == \
+        gswa.gswa_query_bytes(gswa.make_desc(**GOOD))

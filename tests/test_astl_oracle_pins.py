@@ -218,6 +218,39 @@ def test_stack_is_the_composition_with_alternating_shift_and_its_gradients_follo
             assert math.isclose(fd, an, rel_tol=5e-6, abs_tol=5e-7), (name, idx, fd, an)
 
 
+def test_stack_with_stored_boundaries_is_the_layers_composed_by_hand_with_rounding_in_between():
+    """`store` rounds exactly the tensors that cross a layer boundary, in both directions, and
+    nothing else: equal to single-layer calls with the rounding applied by hand between them."""
+    from paper_2409_06206_amd import synth
+    C, heads, groups, window, hidden, shift = 12, 2, 2, 4, 16, 2
+    ps = [_params(C, heads, groups, window, hidden, seed=40 + l) for l in range(3)]
+    x, dy = _acts(1, 8, 8, C)
+    kw = dict(heads=heads, groups=groups, window=window, eps=EPS)
+    rnd = lambda a: synth.quantize(a, "bf16").astype(np.float64)
+    shifts = [0, shift, 0]
+    acts = [x]
+    for l, p in enumerate(ps):
+        a = astl_oracle.forward(acts[-1], p, shift=shifts[l], **kw)
+        acts.append(rnd(a) if l < 2 else a)
+    y = astl_oracle.stack_forward(x, ps, shift=shift, store=rnd, **kw)
+    np.testing.assert_array_equal(y, acts[-1])
+    assert np.abs(y - astl_oracle.stack_forward(x, ps, shift=shift, **kw)).max() > 0  # it does round
+    g = dy
+    want = [None] * 3
+    for l in (2, 1, 0):
+        g, want[l] = astl_oracle.backward(acts[l], g, ps[l], shift=shifts[l], **kw)
+        if l > 0:
+            g = rnd(g)
+    dx, grads = astl_oracle.stack_backward(x, dy, ps, shift=shift, store=rnd, **kw)
+    np.testing.assert_array_equal(dx, g)
+    for l in range(3):
+        for k in want[l]:
+            np.testing.assert_array_equal(grads[l][k], want[l][k])
+    # one layer has no boundary: nothing is rounded
+    np.testing.assert_array_equal(astl_oracle.stack_forward(x, ps[:1], shift=shift, store=rnd, **kw),
+                                  astl_oracle.stack_forward(x, ps[:1], shift=shift, **kw))
+
+
 def test_oracle_unchanged_on_fp32_parity_case():
     """Regression guard: the stored digest was written by tests/golden/make_golden.py (oracle only)."""
     import json

@@ -238,7 +238,10 @@ def test_stack_matches_oracle_with_and_without_checkpointing(case, every):
           for l in range(L)]
     ps = [{k: synth.quantize(v, dtype) for k, v in p.items()} for p in ps]
     x, dy = (synth.quantize(a, dtype) for a in synth.activations(c["B"], c["H"], c["W"], c["C"], 2))
-    kw = dict(heads=c["heads"], groups=c["groups"], window=c["window"], shift=c["shift"], dqk=dqk)
+    # a tensor handed from one layer to the next is a tensor of the layer's element type on both sides
+    # ("bf16 activations with fp32 accumulation"); inside a layer the oracle stays in fp64
+    kw = dict(heads=c["heads"], groups=c["groups"], window=c["window"], shift=c["shift"], dqk=dqk,
+              store=None if dtype == "f32" else (lambda a: synth.quantize(a, dtype)))
     want = {"y": astl_oracle.stack_forward(x, ps, **kw)}
     dx, grads = astl_oracle.stack_backward(x, dy, ps, **kw)
     want["dx"] = dx
@@ -252,9 +255,7 @@ def test_stack_matches_oracle_with_and_without_checkpointing(case, every):
     st.backward()
     torch.cuda.synchronize()
     got = st.results()
-    # the oracle keeps fp64 activations between layers, the library stores them in the element
-    # type: in bf16 one more rounding per layer boundary
-    tol = parity.TOL[dtype] * (1.0 if dtype == "f32" else 1.5)
+    tol = parity.TOL[dtype]
     errs = {k: parity.rel_err(got[k], w) for k, w in want.items()}
     bad = {k: e for k, e in errs.items() if not e <= tol}
     assert not bad, (bad, max(errs.values()))
@@ -276,14 +277,19 @@ def _random_layers(n, seed):
         heads = int(rng.choice([1, 2, 3, 4, 6]))
         groups = int(rng.choice([g for g in (1, 2, 3, 4, 6) if heads % g == 0]))
         d = int(rng.integers(1, 11))
-        # (a LayerNorm over very few channels is ill-conditioned: 1/sqrt(var + eps) reaches eps^-1/2 when
-        # a token's channels nearly coincide, and fp32 rounding is amplified by that factor)
-        if heads * d > 256 or heads * d < 6:
+        if heads * d > 256:
             continue
         B, nh, nw = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
-        out.append(dict(B=B, H=nh * M, W=nw * M, C=heads * d, heads=heads, groups=groups, window=M,
-                        shift=int(rng.integers(0, M)), hidden=int(rng.integers(1, 140)),
-                        dqk=int(rng.choice([0, 0, 1, 3, 4]))))
+        case = dict(B=B, H=nh * M, W=nw * M, C=heads * d, heads=heads, groups=groups, window=M,
+                    shift=int(rng.integers(0, M)), hidden=int(rng.integers(1, 140)),
+                    dqk=int(rng.choice([0, 0, 1, 3, 4])))
+        # A LayerNorm over very few channels is ill-conditioned with a tiny eps: 1/sqrt(var + eps)
+        # reaches eps^-1/2 = 316 when a token's channels nearly coincide, and every rounding of the
+        # normalised value is amplified by that factor in both arithmetics.  Such layers get an eps
+        # that conditions them (eps is a parameter of the layer): 1/sqrt(var + eps) <= 10.
+        if heads * d < 6:
+            case["eps"] = 1e-2
+        out.append(case)
     return out
 
 
