@@ -60,7 +60,22 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr size_t P_WPT = P_BIAS + (size_t)16 * C;
     static constexpr size_t P_WQT = P_WPT + (size_t)N_WPT * 1024;
     static constexpr size_t P_WPK = P_WQT + (size_t)N_WQT * 512;
-    static constexpr size_t P_END = P_WPK + (size_t)N_WPK * 1024;
+    // Wide layers, forward with one wavefront per window (wide_fwd.hip): a head is 16*ET = 32
+    // k-slots, so one K=32 step carries one head in "head-padded order": lane group q holds the
+    // head's features 4q..4q+3 and 16+4q..16+4q+3 -- the rows of the two result tiles of a head
+    // output, which makes a packed output tile pair the operand of the next product.
+    //   WQW  Wqkv, input channels of the group in head-padded order, one K=32 step per input head:
+    //        (hd, t, et, step); query rows carry log2(e)/sqrt(d)
+    //   WPW  Wproj, one K=32 step per head: (ot, hd)
+    //   TBW  relative-position bias times log2(e), fp32, [head][TBW_PITCH]
+    static constexpr int KSX = CG / D;                            // input heads of a group = K=32 steps
+    static constexpr int N_WQW = SPLIT ? HEADS * 3 * ET * KSX : 0;
+    static constexpr int N_WPW = SPLIT ? OT * HEADS : 0;
+    static constexpr int TBW_PITCH = 228;
+    static constexpr size_t P_WQW = P_WPK + (size_t)N_WPK * 1024;
+    static constexpr size_t P_WPW = P_WQW + (size_t)N_WQW * 1024;
+    static constexpr size_t P_TBW = P_WPW + (size_t)N_WPW * 1024;
+    static constexpr size_t P_END = P_TBW + (SPLIT ? (size_t)HEADS * TBW_PITCH * 4 : 0);
 };
 
 // True when a fused forward instantiation exists for this geometry (bf16 only).
@@ -74,9 +89,20 @@ bool fused_fwd_needs_attn(const Geom &g);
 
 // y = GSWA(x); attn_out receives the concatenated group outputs [T, C] (may be null unless
 // fused_fwd_needs_attn); `pack` receives the packed parameters (fused_pack_bytes, 256-byte aligned).
+// `training`: attn_out is kept by the caller for the backward pass (otherwise it is scratch and a
+// kernel may leave out what only the backward would read).
 hipError_t launch_fused_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
                             const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table,
-                            bf16_t *y, bf16_t *attn_out, void *pack, hipStream_t s);
+                            bf16_t *y, bf16_t *attn_out, void *pack, int training, hipStream_t s);
+
+// Wide layers (C = 180) with 8x8 windows: the whole forward in one launch, one wavefront per
+// window, the weights streamed through LDS (wide_fwd.hip).  `attn` receives the group outputs when
+// `training` (the caller keeps them for the backward pass); otherwise it is not touched.
+bool wide_fwd_supported(const Geom &g);
+hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_proj, const bf16_t *table,
+                            void *pack, hipStream_t s);
+hipError_t launch_wide_fwd(const Geom &g, const bf16_t *x, const void *pack, bf16_t *y, bf16_t *attn,
+                           int training, hipStream_t s);
 
 bool fused_bwd_supported(const Geom &g);
 // Scratch of the fused backward: per-workgroup partial parameter gradients.

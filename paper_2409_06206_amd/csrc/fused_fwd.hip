@@ -758,7 +758,7 @@ hipError_t launch_attn_chunks(const Geom &g, const bf16_t *x, const uint8_t *pac
 template <class Cf>
 hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
                    const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table, bf16_t *y,
-                   bf16_t *attn, void *ws, hipStream_t s)
+                   bf16_t *attn, void *ws, int training, hipStream_t s)
 {
     uint8_t *pack = static_cast<uint8_t *>(ws);
     {
@@ -771,6 +771,11 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if constexpr (Cf::SPLIT) {
+        if (wide_fwd_supported(g)) { // 8x8 windows: the whole layer in one launch
+            e = launch_wide_pack(g, w_qkv, w_proj, table, pack, s);
+            if (e != hipSuccess) return e;
+            return launch_wide_fwd(g, x, pack, y, attn, training, s);
+        }
         if (!attn) return hipErrorInvalidValue;
         e = g.M == 16 ? launch_attn_chunks<Cf, 16>(g, x, pack, table, attn, s)
                       : launch_attn_chunks<Cf, 8>(g, x, pack, table, attn, s);
@@ -846,11 +851,11 @@ size_t fused_pack_bytes(const Geom &g)
 
 hipError_t launch_fused_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf16_t *b_qkv,
                             const bf16_t *w_proj, const bf16_t *b_proj, const bf16_t *table,
-                            bf16_t *y, bf16_t *attn_out, void *pack, hipStream_t s)
+                            bf16_t *y, bf16_t *attn_out, void *pack, int training, hipStream_t s)
 {
 #define X(C_, H_, G_)                                                  \
     if (g.C == C_ && g.heads == H_ && g.groups == G_)                  \
-        return run_fwd<FusedCfg<C_, H_, G_>>(g, x, w_qkv, b_qkv, w_proj, b_proj, table, y, attn_out, pack, s);
+        return run_fwd<FusedCfg<C_, H_, G_>>(g, x, w_qkv, b_qkv, w_proj, b_proj, table, y, attn_out, pack, training, s);
     GSWA_FUSED_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

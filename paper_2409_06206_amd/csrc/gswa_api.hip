@@ -363,7 +363,7 @@ int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const 
         if (!saved && fused_fwd_needs_attn(g)) attn = static_cast<char *>(ws) + s.pack;
         hipError_t e = launch_fused_fwd(g, (const bf16_t *)x, (const bf16_t *)w_qkv, (const bf16_t *)b_qkv,
                                         (const bf16_t *)w_proj, (const bf16_t *)b_proj,
-                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)attn, pack, st);
+                                        (const bf16_t *)bias_table, (bf16_t *)y, (bf16_t *)attn, pack, saved ? 1 : 0, st);
         return e == hipSuccess ? GSWA_OK : hip_fail(e);
     }
     if (!(desc->flags & GSWA_FORCE_STAGED) && window_fwd_supported(g)) {

@@ -1,0 +1,549 @@
+// Forward of wide GSWA layers (C = 180, six heads of 30 channels, 8x8 windows) in one launch:
+// shift + partition + per-group QKV projection (Eq. 6) with the cascade add (Eq. 8) + scores with
+// relative bias and shift mask + softmax + PV + output projection (Eq. 7) + merge + reverse shift.
+//
+// One wavefront owns one window: its 64 tokens are four 16-token tiles, K, V and the
+// probabilities never leave the wave's registers.  A workgroup is eight waves that share the
+// weights in LDS; the weights of a wide layer (108 KB of QKV fragments, 72 KB of projection
+// fragments) do not fit LDS together, so they pass through it in chunks between workgroup
+// barriers: the QKV fragments of three or six heads, then the projection.  Every fragment read
+// from LDS serves the four token tiles of the wave.
+//
+// Everything is kept with rows = features and column = token (T-form, see fused_bwd.hip), and a
+// head of 30 channels is two 16-row tiles, i.e. exactly the 32 k-slots of one K=32 MFMA step in
+// "head-padded order" (lane group q: features 4q..4q+3 and 16+4q..16+4q+3).  A packed pair of
+// output tiles of a head therefore is, as it lies in registers, the operand of the next group's
+// QKV projection (after the cascade add onto the x operand, rounded to bf16 like a stored
+// activation) and of the output projection.
+#include "fused.h"
+#include "mfma.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace gswa {
+
+namespace {
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant
+// expression inside the body (register arrays indexed by it never need memory).
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(static_cast<F &&>(f), std::make_integer_sequence<int, N>{});
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kMaskLog2 = -100.0f * kLog2e; // the additive -100 of the shift mask, in base-2 units
+
+// ---------------------------------------------------------------------------------------
+// Parameter packing for this kernel (layout: FusedCfg, WQW / WPW / TBW)
+// ---------------------------------------------------------------------------------------
+template <class Cf>
+__global__ __launch_bounds__(256) void wide_pack_kernel(const bf16_t *__restrict__ w_qkv,
+                                                        const bf16_t *__restrict__ w_proj,
+                                                        const bf16_t *__restrict__ table,
+                                                        uint8_t *__restrict__ pack)
+{
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET, KSX = Cf::KSX;
+    constexpr int E_WQW = Cf::N_WQW * 64, E_WPW = Cf::N_WPW * 64, E_TBW = HEADS * Cf::TBW_PITCH;
+    const float qscale = kLog2e / sqrtf((float)D);
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int l16 = i & 15, q = (i >> 4) & 3;
+    // feature of a head held in k-slot s of lane group q
+    auto slot_feature = [&](int s) { return s < 4 ? 4 * q + s : 16 + 4 * q + (s - 4); };
+    if (i < E_WQW) {
+        int f = i >> 6;
+        const int ks = f % KSX; f /= KSX;
+        const int et = f % ET; f /= ET;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const int e = 16 * et + l16;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int fe = slot_feature(s);
+            float w = 0.f;
+            if (e < D && fe < D)
+                w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + ks * D + fe]) * (t == 0 ? qscale : 1.0f);
+            v[s] = f32_to_bf16_bits(w);
+        }
+        reinterpret_cast<uint4 *>(pack + Cf::P_WQW)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        return;
+    }
+    i -= E_WQW;
+    if (i < E_WPW) {
+        const int f = i >> 6;
+        const int hd = f % HEADS, ot = f / HEADS;
+        const int o = 16 * ot + l16;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int fe = slot_feature(s);
+            v[s] = (o < C && fe < D) ? (uint32_t)w_proj[(size_t)o * C + hd * D + fe].bits : 0u;
+        }
+        reinterpret_cast<uint4 *>(pack + Cf::P_WPW)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        return;
+    }
+    i -= E_WPW;
+    if (i < E_TBW) {
+        const int hd = i / Cf::TBW_PITCH, e = i % Cf::TBW_PITCH;
+        reinterpret_cast<float *>(pack + Cf::P_TBW)[i] = e < 225 ? to_f32(table[e * HEADS + hd]) * kLog2e : 0.f;
+    }
+}
+
+template <class Cf> struct WideFwdCfg {
+    // one wave per SIMD: a wave then has the whole register file of its SIMD (512 registers), which
+    // holds a window's x, all head outputs and the staging registers of the weight stream
+    static constexpr int NWAVES = 4, NTHREADS = 64 * NWAVES;
+    // The weights pass through LDS as a stream of equal units, double buffered: the QKV fragments of
+    // one head, then the projection fragments in pieces of the same size (whole output tiles).
+    // (one group: a head's fragments are 36 KB, so a unit is one of q, k, v of a head)
+    static constexpr int UPH = Cf::G == 1 ? 3 : 1;                 // units per head
+    static constexpr int FR_UNIT = 3 * Cf::ET * Cf::KSX / UPH;     // fragments (1 KB) of one unit
+    static constexpr size_t UNIT_BYTES = (size_t)FR_UNIT * 1024;
+    static constexpr int OT_UNIT = FR_UNIT / Cf::HEADS;            // output tiles of one projection unit
+    static constexpr int NPU = Cf::OT / OT_UNIT;                   // projection units
+    static constexpr int NHU = Cf::HEADS * UPH;                    // head units
+    static constexpr int NU = NHU + NPU;                           // units per window
+    static constexpr int STG = (int)((UNIT_BYTES / 16 + NTHREADS - 1) / NTHREADS); // 16-byte pieces per thread
+    static constexpr size_t OFF_BIAS = 0;                          // fp32 b_qkv [3C], b_proj [C]
+    static constexpr size_t OFF_TBL = (size_t)16 * Cf::C;          // fp32 [HEADS][TBW_PITCH]
+    static constexpr size_t OFF_W = OFF_TBL + (size_t)Cf::HEADS * Cf::TBW_PITCH * 4;
+    static constexpr size_t LDS_BYTES = OFF_W + 2 * UNIT_BYTES;
+    static_assert(OFF_W % 16 == 0 && LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(FR_UNIT % Cf::HEADS == 0 && Cf::OT % OT_UNIT == 0 && NU % 2 == 0,
+                  "units tile the projection");
+    static_assert(Cf::ET == 2 && Cf::D + 1 <= 32 && Cf::CG % Cf::D == 0, "heads of 17..31 channels: two tiles, a spare row");
+};
+
+template <int Q0> __device__ __forceinline__ float qgroup_bcast(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false); // {groups 0,1,0,1; groups 2,3,2,3}
+    const unsigned h = r[Q0 >> 1];
+    r = __builtin_amdgcn_permlane16_swap(h, h, false, false);       // {even group of each pair; odd group}
+    return __uint_as_float(r[Q0 & 1]);
+}
+
+__device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b)
+{
+    return pack_bf16x2(bf16_lo(a) + bf16_lo(b), bf16_hi(a) + bf16_hi(b));
+}
+__device__ __forceinline__ uint4 cat(uint2 lo, uint2 hi) { return make_uint4(lo.x, lo.y, hi.x, hi.y); }
+
+template <class Cf>
+__global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                          const uint8_t *__restrict__ pack,
+                                                          bf16_t *__restrict__ y, bf16_t *__restrict__ attn)
+{
+    using W = WideFwdCfg<Cf>;
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
+    constexpr int KSX = Cf::KSX, TP = Cf::TBW_PITCH, NU = W::NU, STG = W::STG, OT_UNIT = W::OT_UNIT;
+    constexpr int M = 8, NTHREADS = W::NTHREADS;
+    constexpr int N16 = (int)(W::UNIT_BYTES / 16);
+    constexpr int NTB = 2; // query tiles taken through the softmax together
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = g.shift;
+    const int cn = l16 & 7, rsub = l16 >> 3;
+    const int per_img = g.nwi * g.nwj;
+    const uint32_t tbytes = (uint32_t)g.T * (2u * C);
+    const buf_t xbuf = make_buf(x, tbytes), ybuf = make_buf(y, tbytes), abuf = make_buf(attn, attn ? tbytes : 0u);
+    // second half of a head's k-slots: features 16+4q..16+4q+3, of which only those below D exist
+    const uint32_t m_hx = (16 + 4 * q < D) ? 0xffffffffu : 0u, m_hy = (16 + 4 * q + 2 < D) ? 0xffffffffu : 0u;
+    const uint32_t c8 = 8u * q;
+
+    // ---- weight stream: unit u of a window = QKV fragments of a head (or of its q, k or v alone),
+    // then projection fragments of OT_UNIT output tiles.  A thread stages its 16-byte pieces of the
+    // next unit in registers while the current unit is computed with, and writes them to the other
+    // LDS buffer afterwards; one barrier per unit. ----
+    uint32_t stg[STG][4]; // (scalars: stays in registers across the barriers and the window loop)
+    auto unit_src = [&](int u) {
+        return reinterpret_cast<const uint4 *>(pack + (u < W::NHU ? Cf::P_WQW + (size_t)u * W::UNIT_BYTES
+                                                                  : Cf::P_WPW + (size_t)(u - W::NHU) * W::UNIT_BYTES));
+    };
+    auto stage_load = [&](int u) {
+        const uint4 *src = unit_src(u);
+#pragma unroll
+        for (int k = 0; k < STG; ++k) {
+            const int i = k * NTHREADS + tid;
+            const uint4 v = src[i < N16 ? i : 0];
+            stg[k][0] = v.x; stg[k][1] = v.y; stg[k][2] = v.z; stg[k][3] = v.w;
+        }
+    };
+    auto stage_store = [&](int slot) {
+        uint4 *dst = reinterpret_cast<uint4 *>(lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES);
+#pragma unroll
+        for (int k = 0; k < STG; ++k) {
+            const int i = k * NTHREADS + tid;
+            if (i < N16) dst[i] = make_uint4(stg[k][0], stg[k][1], stg[k][2], stg[k][3]);
+        }
+    };
+
+    // ---- the window of this wave: byte offsets of its tokens (tile t, this lane's column) and its x as
+    // MFMA operands (all groups, head-padded order: step ks of group gi, tile t) ----
+    const int stride = W::NWAVES * (int)gridDim.x;
+    const int rounds = (g.nW + stride - 1) / stride;
+    uint32_t tok[4];
+    bool lastrow = false, lastcol = false;
+    uint4 xh[G][KSX][4];
+    auto window_tokens = [&](int win) {
+        const int b = win / per_img;
+        const int wr = win - b * per_img;
+        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
+        lastrow = s > 0 && wi == g.nwi - 1;
+        lastcol = s > 0 && wj == g.nwj - 1;
+        int sj = wj * M + cn + s;
+        if (sj >= g.W) sj -= g.W;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            int si = wi * M + 2 * t + rsub + s;
+            if (si >= g.H) si -= g.H;
+            tok[t] = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
+        }
+    };
+    auto load_x = [&]() {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+            for (int ks = 0; ks < KSX; ++ks)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t off = tok[t] + c8 + 2u * (gi * CG + ks * D);
+                    const uint2 lo = bload64(xbuf, off, 0u);
+                    uint2 hi = bload64(xbuf, off + 32u, 0u);
+                    hi.x &= m_hx;
+                    hi.y &= m_hy;
+                    xh[gi][ks][t] = cat(lo, hi);
+                }
+    };
+    int win = wv * (int)gridDim.x + (int)blockIdx.x;
+    bool active = win < g.nW;
+    if (active) {
+        window_tokens(win);
+        load_x();
+    }
+
+    // set-up: linear biases, bias table, first unit
+    stage_load(0);
+    for (int i = tid; i < C; i += NTHREADS)
+        reinterpret_cast<uint4 *>(lds + W::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
+    for (int i = tid; i < HEADS * TP / 4; i += NTHREADS)
+        reinterpret_cast<uint4 *>(lds + W::OFF_TBL)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_TBW)[i];
+    stage_store(0);
+    __syncthreads();
+
+    // this lane's query column (rn = 2nt + rsub, cn) against key rows 4q+j of key tile kt:
+    // key (2kt + q/2, 4(q%2) + j); table entry = tb0 + 30(nt - kt) - j
+    const int tb0 = (rsub - (q >> 1) + M - 1) * (2 * M - 1) + (cn - 4 * (q & 1) + M - 1);
+    const bool qc_w = cn >= M - s;
+    bool kc_w[4], qr_w[4], kr_w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kc_w[j] = (4 * (q & 1) + j) >= M - s;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        qr_w[t] = (2 * t + rsub) >= M - s;
+        kr_w[t] = (2 * t + (q >> 1)) >= M - s;
+    }
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int round = 0; round < rounds; ++round) {
+        const bool more = round + 1 < rounds;
+        if (active && round > 0) {
+            window_tokens(win);
+            load_x();
+        }
+        // head outputs, packed tile pairs [head][token tile]: operand of the cascade and of the projection
+        uint4 Ob[HEADS][4];
+        uint2 Qb[2][4], Kb[2][4], Vb[2][4];
+
+        uint32_t lds0 = 0;
+        asm volatile("" : "+v"(lds0)); // keeps the LDS reads of a round inside the round
+        const float *bqkv = reinterpret_cast<const float *>(lds + lds0 + W::OFF_BIAS);
+        const float *bproj = bqkv + 3 * C;
+        const float *tbl = reinterpret_cast<const float *>(lds + lds0 + W::OFF_TBL);
+
+        static_for<NU>([&](auto u_) {
+            constexpr int u = decltype(u_)::value;
+            const uint4 *wu = reinterpret_cast<const uint4 *>(lds + lds0 + W::OFF_W + (size_t)(u & 1) * W::UNIT_BYTES);
+            // next unit on its way (the first of the next window after the last)
+            if (u + 1 < NU) stage_load(u + 1);
+            else if (more) stage_load(0);
+
+            if constexpr (u < W::NHU) {
+                constexpr int hd = u / W::UPH, part = u % W::UPH, gi = hd / HG, hl = hd % HG;
+                constexpr int T3B = part * (3 / W::UPH), T3E = T3B + 3 / W::UPH; // of q, k, v: this unit's
+                if (active) {
+                    if (G > 1 && part == 0 && hl == 0 && gi > 0 && g.cascade) { // Eq. 8
+#pragma unroll
+                        for (int ks = 0; ks < KSX; ++ks)
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const uint4 p = Ob[(gi > 0 ? gi - 1 : 0) * HG + ks][t];
+                                uint4 &xv = xh[gi][ks][t];
+                                xv.x = add_bf16x2(xv.x, p.x);
+                                xv.y = add_bf16x2(xv.y, p.y);
+                                xv.z = add_bf16x2(xv.z, p.z & m_hx);
+                                xv.w = add_bf16x2(xv.w, p.w & m_hy);
+                            }
+                    }
+                    // ---- Q^T, K^T (rows = head features) and V (rows = tokens): eight independent
+                    // accumulator tiles per kind, so that consecutive MFMAs never wait for each other ----
+#pragma unroll
+                    for (int t3 = T3B; t3 < T3E; ++t3) {
+                        f32x4 acc[2][4];
+#pragma unroll
+                        for (int et = 0; et < 2; ++et) {
+                            f32x4 b4;
+                            if (t3 < 2) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const int e = 16 * et + 4 * q + j;
+                                    const float bv = e < D ? bqkv[gi * 3 * CG + t3 * CG + hl * D + e] : 0.f;
+                                    b4[j] = t3 == 0 ? bv * kLog2e : bv;
+                                }
+                            } else {
+                                // column D of V is one: row D of the PV product is the sum of the probabilities
+                                const int e = 16 * et + l16;
+                                const float bv = e < D ? bqkv[gi * 3 * CG + 2 * CG + hl * D + e] : (e == D ? 1.f : 0.f);
+                                b4 = f32x4{bv, bv, bv, bv};
+                            }
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) acc[et][t] = b4;
+                        }
+#pragma unroll
+                        for (int ks = 0; ks < KSX; ++ks) {
+                            const uint4 f0 = wu[(((t3 - T3B) * 2 + 0) * KSX + ks) * 64 + lane];
+                            const uint4 f1 = wu[(((t3 - T3B) * 2 + 1) * KSX + ks) * 64 + lane];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const uint4 xv = xh[gi][ks][t];
+                                acc[0][t] = t3 < 2 ? mma32(f0, xv, acc[0][t]) : mma32(xv, f0, acc[0][t]);
+                                acc[1][t] = t3 < 2 ? mma32(f1, xv, acc[1][t]) : mma32(xv, f1, acc[1][t]);
+                            }
+                        }
+#pragma unroll
+                        for (int et = 0; et < 2; ++et)
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const uint2 pk = pack_bf16x4(acc[et][t]);
+                                if (t3 == 0) Qb[et][t] = pk;
+                                else if (t3 == 1) Kb[et][t] = pk;
+                                else Vb[et][t] = pk;
+                            }
+                        __builtin_amdgcn_sched_barrier(0); // (keeps the scheduler from stretching the next stage's loads over this one)
+                    }
+                }
+                if constexpr (part == W::UPH - 1) {
+                if (active) {
+                    // relative bias of score tile (kt, nt) depends on nt - kt only: seven register tiles
+                    f32x4 bt[7];
+#pragma unroll
+                    for (int dl = 0; dl < 7; ++dl)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) bt[dl][j] = tbl[hd * TP + tb0 + 30 * (dl - 3) - j];
+
+                    // S^T tiles (base-2 units): rows = keys 16kt+4q+j, column = query 16nt+l16; two query
+                    // tiles are taken through every stage together (independent chains)
+#pragma unroll
+                    for (int n0 = 0; n0 < 4; n0 += NTB) {
+                        f32x4 st[NTB][4];
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni) {
+                            const uint4 qop = cat(Qb[0][n0 + ni], Qb[1][n0 + ni]);
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt)
+                                st[ni][kt] = mma32(cat(Kb[0][kt], Kb[1][kt]), qop, bt[n0 + ni - kt + 3]);
+                        }
+                        if (lastrow || lastcol) {
+#pragma unroll
+                            for (int ni = 0; ni < NTB; ++ni)
+#pragma unroll
+                                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                                    for (int j = 0; j < 4; ++j)
+                                        if ((lastrow && qr_w[n0 + ni] != kr_w[kt]) || (lastcol && qc_w != kc_w[j]))
+                                            st[ni][kt][j] += kMaskLog2;
+                        }
+                        float mx[NTB];
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni) {
+                            float m0 = fmaxf(fmaxf(st[ni][0][0], st[ni][0][1]), fmaxf(st[ni][0][2], st[ni][0][3]));
+#pragma unroll
+                            for (int kt = 1; kt < 4; ++kt)
+#pragma unroll
+                                for (int j = 0; j < 4; j += 2) m0 = fmaxf(fmaxf(m0, st[ni][kt][j]), st[ni][kt][j + 1]);
+                            mx[ni] = m0;
+                        }
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni) mx[ni] = qgroup_max(mx[ni]);
+                        uint2 Pb[NTB][4];
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni)
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) st[ni][kt][j] = __builtin_amdgcn_exp2f(st[ni][kt][j] - mx[ni]);
+                                Pb[ni][kt] = pack_bf16x4(st[ni][kt]);
+                            }
+                        // O^T = V^T P^T: rows = head features (row D = sum of the probabilities)
+                        f32x4 o0[NTB], o1[NTB];
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni) {
+                            o0[ni] = mma32(cat(Vb[0][0], Vb[0][1]), cat(Pb[ni][0], Pb[ni][1]), zero4);
+                            o1[ni] = mma32(cat(Vb[1][0], Vb[1][1]), cat(Pb[ni][0], Pb[ni][1]), zero4);
+                        }
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni) {
+                            o0[ni] = mma32(cat(Vb[0][2], Vb[0][3]), cat(Pb[ni][2], Pb[ni][3]), o0[ni]);
+                            o1[ni] = mma32(cat(Vb[1][2], Vb[1][3]), cat(Pb[ni][2], Pb[ni][3]), o1[ni]);
+                        }
+#pragma unroll
+                        for (int ni = 0; ni < NTB; ++ni) {
+                            const float inv = __builtin_amdgcn_rcpf(qgroup_bcast<(D - 16) / 4>(o1[ni][(D - 16) % 4]));
+                            o0[ni] *= inv;
+                            o1[ni] *= inv;
+                            Ob[hd][n0 + ni] = cat(pack_bf16x4(o0[ni]), pack_bf16x4(o1[ni]));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // the outputs of a group leave together when the caller keeps them for the backward
+                    // pass (pieces of a row then fill whole cache lines)
+                    if (attn && hl == HG - 1) {
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                            for (int h2 = gi * HG; h2 <= hd; ++h2) {
+                                const uint32_t off = tok[nt] + c8 + 2u * (h2 * D);
+                                const uint4 o = Ob[h2][nt];
+                                bstore64(abuf, off, 0u, make_uint2(o.x, o.y));
+                                if (m_hy) bstore64(abuf, off + 32u, 0u, make_uint2(o.z, o.w));
+                                else if (m_hx) bstore32(abuf, off + 32u, 0u, o.z);
+                            }
+                    }
+                }
+                }
+            } else {
+                // ---- Y^T = Wproj A^T + b for OT_UNIT output tiles: rows = output channels, column = token ----
+                constexpr int pu = u - W::NHU;
+                if (active) {
+#pragma unroll
+                    for (int oi = 0; oi < OT_UNIT; ++oi) {
+                        const int ot = pu * OT_UNIT + oi;
+                        f32x4 acc[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int o = 16 * ot + 4 * q + j;
+                            const float bv = o < C ? bproj[o] : 0.f;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) acc[t][j] = bv;
+                        }
+#pragma unroll
+                        for (int hd = 0; hd < HEADS; ++hd) {
+                            const uint4 wf = wu[(oi * HEADS + hd) * 64 + lane];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) acc[t] = mma32(wf, Ob[hd][t], acc[t]);
+                        }
+                        const int o0 = 16 * ot + 4 * q;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (o0 < C) bstore64(ybuf, tok[t] + c8 + 32u * ot, 0u, pack_bf16x4(acc[t]));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+            // the staged unit goes to the buffer the previous unit was read from (every wave has
+            // passed the previous barrier, i.e. finished with it)
+            if (u + 1 < NU || more) stage_store((u + 1) & 1);
+            __syncthreads();
+        });
+        win += stride;
+        active = win < g.nW;
+    }
+}
+
+#define GSWA_WIDE_SHAPES(X) X(180, 6, 1) X(180, 6, 2) X(180, 6, 3)
+
+int cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+template <class Cf>
+hipError_t run_wide_fwd(const Geom &g, const bf16_t *x, const uint8_t *pack, bf16_t *y, bf16_t *attn, int training,
+                        hipStream_t s)
+{
+    using W = WideFwdCfg<Cf>;
+    auto kern = wide_fwd_kernel<Cf>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)W::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    // one window per wave: spread the windows over the compute units before filling a workgroup
+    int grid = cu_count();
+    if (grid > g.nW) grid = g.nW;
+    KernelTimer kt(K_FUSED_FWD, s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, pack, y, training ? attn : nullptr);
+    return hipGetLastError();
+}
+
+} // namespace
+
+bool wide_fwd_supported(const Geom &g)
+{
+    if (g.M != 8 || g.dq != g.d || (long)g.T * g.C >= (1L << 31)) return false;
+#define X(C_, H_, G_) \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) return true;
+    GSWA_WIDE_SHAPES(X)
+#undef X
+    return false;
+}
+
+hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_proj, const bf16_t *table,
+                            void *pack, hipStream_t s)
+{
+#define X(C_, H_, G_)                                                                                    \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                                  \
+        using Cf = FusedCfg<C_, H_, G_>;                                                                 \
+        constexpr int entries = (Cf::N_WQW + Cf::N_WPW) * 64 + Cf::HEADS * Cf::TBW_PITCH;                \
+        KernelTimer kt(K_PACK_FWD, s);                                                                   \
+        hipLaunchKernelGGL(wide_pack_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, w_proj, \
+                           table, static_cast<uint8_t *>(pack));                                        \
+        return hipGetLastError();                                                                        \
+    }
+    GSWA_WIDE_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_wide_fwd(const Geom &g, const bf16_t *x, const void *pack, bf16_t *y, bf16_t *attn, int training,
+                           hipStream_t s)
+{
+    if (training && !attn) return hipErrorInvalidValue;
+#define X(C_, H_, G_)                                 \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) \
+        return run_wide_fwd<FusedCfg<C_, H_, G_>>(g, x, static_cast<const uint8_t *>(pack), y, attn, training, s);
+    GSWA_WIDE_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+} // namespace gswa
