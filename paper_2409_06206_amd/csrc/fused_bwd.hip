@@ -143,6 +143,10 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     constexpr int CT = B::CT, NT = B::NT, KT = B::KT, OTP = B::OTP, CTP = B::CTP, NTP = B::NTP, KTP = B::KTP;
     constexpr int M = 8;
     static_assert(CG % 2 == 0 && D % 2 == 0 && C % 4 == 0, "dword-granular loads and stores");
+    // The shift mask, exactly as the forward kernel of the same layer adds it: -100 for wide layers;
+    // narrow layers carry it through bf16 matrix-core operands in base-2 units, where it is
+    // -144 = bf16(-100 log2 e), i.e. -99.81 here.
+    constexpr float kMask = Cf::SPLIT ? -100.0f : -144.0f / kLog2e;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint4 *wq = reinterpret_cast<const uint4 *>(lds + B::OFF_WQ);
@@ -301,6 +305,22 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
         if (!PIPE) load_rows(win);
+        // Eq. 8: the input of a group with a cascade term is F = x slice + previous group's output,
+        // rounded to bf16 exactly as the forward kernels round it (it is the operand of their QKV
+        // product), so that q, k, v and the probabilities are recomputed from the same values
+        if (g.cascade) {
+#pragma unroll
+            for (int gi = (GB > 1 ? GB : 1); gi <= GE; ++gi)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    uint4 &f = xf[gi][ks];
+                    const uint4 a = af[gi - 1][ks];
+                    f.x = pack_bf16x2(bf16_lo(f.x) + bf16_lo(a.x), bf16_hi(f.x) + bf16_hi(a.x));
+                    f.y = pack_bf16x2(bf16_lo(f.y) + bf16_lo(a.y), bf16_hi(f.y) + bf16_hi(a.y));
+                    f.z = pack_bf16x2(bf16_lo(f.z) + bf16_lo(a.z), bf16_hi(f.z) + bf16_hi(a.z));
+                    f.w = pack_bf16x2(bf16_lo(f.w) + bf16_lo(a.w), bf16_hi(f.w) + bf16_hi(a.w));
+                }
+        }
         const long tok = token_of(win);
         const int wr = win - fdiv(win, per_img, r_img) * per_img, wi = fdiv(wr, g.nwj, r_nwj);
         const bool lastrow = s > 0 && wi == g.nwi - 1, lastcol = s > 0 && wr - wi * g.nwj == g.nwj - 1;
@@ -351,9 +371,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
             const int hd = HE - 1 - hdr; // groups in reverse order
             const int hx = hd - HB;      // index into this launch's fragments and accumulators
             const int gi = hd / HG, hl = hd % HG;
-            const bool casc_in = gi > 0 && g.cascade;      // this group's input has a cascade term
             const bool casc_out = gi < G - 1 && g.cascade; // this group's output feeds the next group
-            const int gp = gi > 0 ? gi - 1 : 0;
             // the heads of group gi this launch processes, top first: [g_lo, g_hi]
             const int g_hi = (HE < (gi + 1) * HG ? HE : (gi + 1) * HG) - 1;
             const int g_lo = HB > gi * HG ? HB : gi * HG;
@@ -408,13 +426,6 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                     kT[et] = mma32(fk_, xf[gi][ks], kT[et]);
                     kN[et] = mma32(xf[gi][ks], fk_, kN[et]);
                     vT[et] = mma32(fv_, xf[gi][ks], vT[et]);
-                    if (casc_in) {
-                        qT[et] = mma32(fq_, af[gp][ks], qT[et]);
-                        qN[et] = mma32(af[gp][ks], fq_, qN[et]);
-                        kT[et] = mma32(fk_, af[gp][ks], kT[et]);
-                        kN[et] = mma32(af[gp][ks], fk_, kN[et]);
-                        vT[et] = mma32(fv_, af[gp][ks], vT[et]);
-                    }
                 }
             }
             // ---- exchange: K, V tiles; K^T, Q^T, dO^T rows ----
@@ -454,7 +465,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        if ((lastrow && rmask[kt]) || (lastcol && cmask[j])) st[kt][j] += -100.0f;
+                        if ((lastrow && rmask[kt]) || (lastcol && cmask[j])) st[kt][j] += kMask;
             }
             float mx = -INFINITY;
 #pragma unroll
@@ -560,7 +571,6 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                     if (2 * (ct >> 1) < 2 * KS && (ct >> 1) < KS) {
                         const uint4 sel = select_slot(16 * ct + l16, 32 * (ct >> 1) + 8 * q);
                         tN = mma32(xf[gi][(ct >> 1) < KS ? (ct >> 1) : 0], sel, tN);
-                        if (casc_in) tN = mma32(af[gp][(ct >> 1) < KS ? (ct >> 1) : 0], sel, tN);
                     }
                     uint2 pk = pack_bf16x4(tN);
                     if (16 * ct + l16 == CG) pk = ones2;
