@@ -73,13 +73,21 @@ template <class Cf, int HB_, int HE_, bool WPROJ_ = (HE_ == Cf::HEADS)> struct B
     static constexpr size_t OFF_F = OFF_DQKV + SZ_DQKV;        // F^T rows [c][token] of the current group
     static constexpr size_t SZ_F = (size_t)16 * CT * LW * 2;
     static constexpr size_t LDS_BYTES = OFF_F + SZ_F;
-    // per-workgroup partial sums, in parameter order
-    static constexpr int P_DWQ = 0;
-    static constexpr int P_DBQ = P_DWQ + 3 * C * CG;
-    static constexpr int P_DWP = P_DBQ + 3 * C;
-    static constexpr int P_DBP = P_DWP + C * C;
-    static constexpr int P_TBL = P_DBP + C;
-    static constexpr int P_TOTAL = P_TBL + TBL_N;
+    // Per-workgroup partial sums of THIS launch only (the scratch is reused from launch to launch: the
+    // head-group loop bounds it).  Rows of d w_qkv: for every group of the chunk and each of q, k, v
+    // the RG rows the chunk's heads own, ((gi - GB) * 3 + t) * RG + (hl - HL0) * D + e; then the bias
+    // sums in the same order, d w_proj | d b_proj where this launch produces them, and the bias-table
+    // gradient head by head.
+    static constexpr bool WHOLE = HB_ % HG == 0 && HE_ % HG == 0;   // whole groups (else: part of one group)
+    static constexpr int NG = GE - GB + 1;
+    static constexpr int RG = WHOLE ? CG : NH * D;                  // rows per (group, q|k|v)
+    static constexpr int HL0 = WHOLE ? 0 : HB_ % HG;
+    static constexpr int L_DWQ = 0;
+    static constexpr int L_DBQ = L_DWQ + NG * 3 * RG * CG;
+    static constexpr int L_DWP = L_DBQ + NG * 3 * RG;
+    static constexpr int L_DBP = L_DWP + (WPROJ ? C * C : 0);
+    static constexpr int L_TBL = L_DBP + (WPROJ ? C : 0);
+    static constexpr int L_TOTAL = L_TBL + NH * NTBL;
     static_assert(!WPROJ || (OTP <= 2 * KSC && SZ_SQ >= (size_t)16 * OTP * LW * 2 &&
                              SZ_SQ >= (size_t)16 * CTP * LW * 2),
                   "dY^T / A^T rows alias the P / dS squares");
@@ -634,7 +642,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     // ---- flush: this workgroup's partial sums, in parameter order.  The packed query weights
     // carry the 1/sqrt(d) of the scores, so their gradients get it back here. ----
     const float scale = 1.0f / sqrtf((float)D);
-    float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
+    float *mine = part + (size_t)blockIdx.x * B::L_TOTAL;
     if (WPROJ) {
 #pragma unroll
     for (int k = 0; k < KTP; ++k) {
@@ -646,8 +654,8 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
             for (int j = 0; j < 4; ++j) {
                 const int o = 16 * ot + 4 * q + j;
                 if (o < C) {
-                    if (c < C) mine[B::P_DWP + o * C + c] = wpacc[k][j];
-                    else if (c == C) mine[B::P_DBP + o] = wpacc[k][j];
+                    if (c < C) mine[B::L_DWP + o * C + c] = wpacc[k][j];
+                    else if (c == C) mine[B::L_DBP + o] = wpacc[k][j];
                 }
             }
         }
@@ -668,10 +676,10 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
                 for (int j = 0; j < 4; ++j) {
                     const int e = 16 * et + 4 * q + j;
                     if (e < D) {
-                        const int row = gi * 3 * CG + t * CG + hl * D + e;
+                        const int row = ((gi - GB) * 3 + t) * B::RG + (hl - B::HL0) * D + e;
                         const float v = t == 0 ? dwacc[hx][k][j] * scale : dwacc[hx][k][j];
-                        if (c < CG) mine[B::P_DWQ + row * CG + c] = v;
-                        else if (c == CG) mine[B::P_DBQ + row] = v;
+                        if (c < CG) mine[B::L_DWQ + row * CG + c] = v;
+                        else if (c == CG) mine[B::L_DBQ + row] = v;
                     }
                 }
             }
@@ -685,7 +693,6 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     static_assert((size_t)64 * MP * 4 <= 2 * B::SZ_SQ, "table flush aliases P and dS");
 #pragma unroll
     for (int hx = 0; hx < NH; ++hx) {
-        const int hd = HB + hx;
         __syncthreads();
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
@@ -726,17 +733,23 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
             const float val = part == 0 ? a00 : part == 1 ? a01 : part == 2 ? a10 : a11;
             const int e = e00 - ((part & 1) ? M : 0) - ((part & 2) ? M * (2 * M - 1) : 0);
             const bool ok = !((part & 1) && dc0 == 0) && !((part & 2) && dr0 == 0);
-            if (ok) mine[B::P_TBL + e * HEADS + hd] = val;
+            if (ok) mine[B::L_TBL + hx * NTBL + e] = val;
         }
     }
 }
 
-// Sums the per-workgroup partial vectors and scatters the five segments to their gradients.
+// Sums the per-workgroup partial vectors of one launch and scatters their segments to the gradients.
 // One block handles 32 entries; 32 slices of the block each sum a 32nd of the partials (16 loads per
 // thread at 512 partials, eight in flight at a time); fixed summation order.
+// Segment k covers entries [begin[k], begin[k+1]) of a partial vector and goes to ptr[k] + offset,
+// contiguously; the last segment (if tbl_heads > 0) is the bias-table gradient, stored head by head
+// in the partial vector and scattered to dtable[entry * tbl_stride + tbl_head0 + head].
 struct ReduceOut {
-    float *ptr[5];
-    int begin[6];
+    static constexpr int MAXSEG = 22;
+    float *ptr[MAXSEG];
+    int begin[MAXSEG + 1];
+    int nseg;
+    int tbl_heads, tbl_entries, tbl_stride, tbl_head0;
 };
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
                                                                int n, ReduceOut out, int accumulate)
@@ -765,8 +778,13 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
             t[u] = (red[4 * u][col] + red[4 * u + 1][col]) + (red[4 * u + 2][col] + red[4 * u + 3][col]);
         acc = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
         int seg = 0;
-        while (seg < 4 && i >= out.begin[seg + 1]) ++seg;
-        float *dst = out.ptr[seg] + (i - out.begin[seg]);
+        while (seg < out.nseg - 1 && i >= out.begin[seg + 1]) ++seg;
+        const int k = i - out.begin[seg];
+        float *dst = out.ptr[seg] + k;
+        if (out.tbl_heads > 0 && seg == out.nseg - 1) {
+            const int hd = k / out.tbl_entries, e = k - hd * out.tbl_entries;
+            dst = out.ptr[seg] + e * out.tbl_stride + out.tbl_head0 + hd;
+        }
         *dst = accumulate ? *dst + acc : acc;
     }
 }
@@ -865,7 +883,7 @@ __global__ __launch_bounds__(256, 2) void wproj_grad_kernel(long T, const bf16_t
             }
         }
     }
-    float *mine = part + (size_t)blockIdx.x * B::P_TOTAL;
+    float *mine = part + (size_t)blockIdx.x * (C * C + C); // [d w_proj | d b_proj]
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         const int ot = wv * RW + r;
@@ -877,8 +895,8 @@ __global__ __launch_bounds__(256, 2) void wproj_grad_kernel(long T, const bf16_t
                 for (int j = 0; j < 4; ++j) {
                     const int o = 16 * ot + 4 * q + j;
                     if (o < C) {
-                        if (c < C) mine[B::P_DWP + o * C + c] = acc[r][ct][j];
-                        else if (c == C) mine[B::P_DBP + o] = acc[r][ct][j];
+                        if (c < C) mine[o * C + c] = acc[r][ct][j];
+                        else if (c == C) mine[C * C + o] = acc[r][ct][j];
                     }
                 }
             }
@@ -913,9 +931,25 @@ int bwd_grid(const Geom &g)
     return grid > g.nW ? g.nW : grid;
 }
 
+struct GradOut {
+    float *dw_qkv, *db_qkv, *dw_proj, *db_proj, *dtable;
+    int accumulate;
+};
+
+hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s)
+{
+    KernelTimer kt(K_REDUCE, s);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);
+    return hipGetLastError();
+}
+
+// One chunk of heads: the kernel, then the sum of its partials into the gradients it owns.  The
+// scratch is free again afterwards, so every chunk (and the projection's weight gradient of wide
+// layers) uses the same buffer: its size is the largest chunk's, not the sum.
 template <class Cf, int HB, int HE, bool WPROJ>
 hipError_t launch_chunk(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
-                        const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, hipStream_t s)
+                        const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, const GradOut &go,
+                        hipStream_t s)
 {
     using B = BwdCfg<Cf, HB, HE, WPROJ>;
     static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -927,23 +961,63 @@ hipError_t launch_chunk(const Geom &g, int grid, const bf16_t *x, const bf16_t *
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    KernelTimer kt(K_FUSED_BWD, s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, part);
-    return hipGetLastError();
+    {
+        KernelTimer kt(K_FUSED_BWD, s);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, part);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr int CG = Cf::CG, D = Cf::D;
+    ReduceOut out{};
+    int k = 0;
+    static_assert(2 * B::NG * 3 + 3 <= ReduceOut::MAXSEG, "segment table");
+    for (int gi = 0; gi < B::NG; ++gi)
+        for (int t = 0; t < 3; ++t) { // d w_qkv rows of (group, q|k|v) owned by the chunk's heads
+            out.ptr[k] = go.dw_qkv + (size_t)((B::GB + gi) * 3 * CG + t * CG + B::HL0 * D) * CG;
+            out.begin[k++] = B::L_DWQ + (gi * 3 + t) * B::RG * CG;
+        }
+    for (int gi = 0; gi < B::NG; ++gi)
+        for (int t = 0; t < 3; ++t) {
+            out.ptr[k] = go.db_qkv + (B::GB + gi) * 3 * CG + t * CG + B::HL0 * D;
+            out.begin[k++] = B::L_DBQ + (gi * 3 + t) * B::RG;
+        }
+    if (WPROJ) {
+        out.ptr[k] = go.dw_proj; out.begin[k++] = B::L_DWP;
+        out.ptr[k] = go.db_proj; out.begin[k++] = B::L_DBP;
+    }
+    out.ptr[k] = go.dtable; out.begin[k++] = B::L_TBL;
+    out.begin[k] = B::L_TOTAL;
+    out.nseg = k;
+    out.tbl_heads = B::NH; out.tbl_entries = B::NTBL; out.tbl_stride = Cf::HEADS; out.tbl_head0 = HB;
+    return launch_reduce(part, grid, B::L_TOTAL, out, go.accumulate, s);
 }
 
 template <class Cf, int I = 0>
 hipError_t launch_chunks(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
-                         const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, hipStream_t s)
+                         const uint8_t *pack, const bf16_t *table, bf16_t *dx, float *part, const GradOut &go,
+                         hipStream_t s)
 {
     using Plan = ChunkPlan<Cf::SPLIT, Cf::G>;
     if constexpr (I < Plan::N) {
         hipError_t e = launch_chunk<Cf, Plan::B[I], Plan::E[I], !Cf::SPLIT && Plan::E[I] == Cf::HEADS>(
-            g, grid, x, dy, attn, pack, table, dx, part, s);
+            g, grid, x, dy, attn, pack, table, dx, part, go, s);
         if (e != hipSuccess) return e;
-        return launch_chunks<Cf, I + 1>(g, grid, x, dy, attn, pack, table, dx, part, s);
+        return launch_chunks<Cf, I + 1>(g, grid, x, dy, attn, pack, table, dx, part, go, s);
     }
     return hipSuccess;
+}
+
+// floats of the largest per-workgroup partial vector over the launches of a layer
+template <class Cf, int I = 0> constexpr int max_partial()
+{
+    using Plan = ChunkPlan<Cf::SPLIT, Cf::G>;
+    if constexpr (I < Plan::N) {
+        constexpr int mine = BwdCfg<Cf, Plan::B[I], Plan::E[I], !Cf::SPLIT && Plan::E[I] == Cf::HEADS>::L_TOTAL;
+        constexpr int rest = max_partial<Cf, I + 1>();
+        return mine > rest ? mine : rest;
+    } else {
+        return Cf::SPLIT ? Cf::C * Cf::C + Cf::C : 0;
+    }
 }
 
 template <class Cf>
@@ -955,7 +1029,8 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     const uint8_t *pack = static_cast<const uint8_t *>(pack_);
     float *part = static_cast<float *>(ws);
     const int grid = bwd_grid(g);
-    hipError_t e = launch_chunks<Cf>(g, grid, x, dy, attn, pack, table, dx, part, s);
+    const GradOut go{dw_qkv, db_qkv, dw_proj, db_proj, dtable, accumulate};
+    hipError_t e = launch_chunks<Cf>(g, grid, x, dy, attn, pack, table, dx, part, go, s);
     if (e != hipSuccess) return e;
     if constexpr (Cf::SPLIT) {
         constexpr size_t lds = (size_t)16 * (B::OTP + B::CTP) * B::LW * 2;
@@ -973,17 +1048,14 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
+        ReduceOut out{};
+        out.ptr[0] = dw_proj; out.begin[0] = 0;
+        out.ptr[1] = db_proj; out.begin[1] = Cf::C * Cf::C;
+        out.begin[2] = Cf::C * Cf::C + Cf::C;
+        out.nseg = 2;
+        return launch_reduce(part, grid, Cf::C * Cf::C + Cf::C, out, accumulate, s);
     }
-    ReduceOut out;
-    out.ptr[0] = dw_qkv; out.ptr[1] = db_qkv; out.ptr[2] = dw_proj; out.ptr[3] = db_proj; out.ptr[4] = dtable;
-    out.begin[0] = B::P_DWQ; out.begin[1] = B::P_DBQ; out.begin[2] = B::P_DWP; out.begin[3] = B::P_DBP;
-    out.begin[4] = B::P_TBL; out.begin[5] = B::P_TOTAL;
-    {
-        KernelTimer kt(K_REDUCE, s);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((B::P_TOTAL + 31) / 32), dim3(1024), 0, s, part, grid,
-                           B::P_TOTAL, out, accumulate);
-    }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 #define GSWA_FUSED_SHAPES(X) X(60, 6, 1) X(60, 6, 2) X(60, 6, 3) X(60, 6, 6) X(180, 6, 2) X(180, 6, 3)
@@ -1004,7 +1076,7 @@ size_t fused_bwd_ws_bytes(const Geom &g)
 {
     int total = 0;
 #define X(C_, H_, G_) \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = BwdCfg<FusedCfg<C_, H_, G_>, 0, H_, false>::P_TOTAL;
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) total = max_partial<FusedCfg<C_, H_, G_>>();
     GSWA_FUSED_SHAPES(X)
 #undef X
     return ((size_t)bwd_grid(g) * total * 4 + 255) & ~size_t(255);

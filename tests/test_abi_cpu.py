@@ -246,3 +246,22 @@ def test_reproducible_mode_is_a_valid_flag_and_sizes_its_scratch():
     # the fused path sums in a fixed order anyway: the flag changes nothing there
     assert gswa.gswa_query_bytes(gswa.make_desc(**{**GOOD, "flags": gswa.GSWA_DETERMINISTIC})) == \
         gswa.gswa_query_bytes(gswa.make_desc(**GOOD))
+
+
+def test_fused_path_memory_does_not_grow_with_the_group_count():
+    """Default (fused) path at the benchmark's narrow and wide shapes: saved state plus scratch is
+    non-increasing in the group count -- the scratch holds the partial parameter gradients of one
+    head-group launch at a time, which shrink with the group."""
+    for shape, groups in (((32, 64, 64, 60), (1, 2, 3, 6)), ((16, 64, 64, 180), (2, 3))):
+        B, H, W, C = shape
+        prev = None
+        for G in groups:
+            saved, fwd, bwd = gswa.gswa_query_bytes(gswa.make_desc(B, H, W, C, 6, G, 8, 4, "bf16"))
+            assert fwd == 0 and saved >= B * H * W * C * 2
+            total = saved + bwd
+            if prev is not None:
+                assert total <= prev, (C, G, total, prev)
+            prev = total
+    # narrow layers: strictly falling from one group to two and to three
+    t = [sum(gswa.gswa_query_bytes(gswa.make_desc(32, 64, 64, 60, 6, G, 8, 4, "bf16"))[::2]) for G in (1, 2, 3)]
+    assert t[0] > t[1] > t[2]

@@ -82,7 +82,7 @@ def test_kernel_timing_aid_reports_the_launched_kernels():
         gswa.gswa_profile_enable(False)
     torch.cuda.synchronize()
     assert dropped == 0
-    assert res["fused_fwd"][1] == 1 and res["fused_bwd"][1] == 2 and res["reduce_partials"][1] == 1
+    assert res["fused_fwd"][1] == 1 and res["fused_bwd"][1] == 2 and res["reduce_partials"][1] == 2  # one sum per head-group launch
     assert all(ms > 0 for ms, _ in res.values())
     layer.forward()
     assert gswa.gswa_profile_collect()[0] == {}
