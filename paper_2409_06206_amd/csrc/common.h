@@ -70,4 +70,19 @@ __device__ __forceinline__ long window_token(const Geom &g, int w, int n, int &r
 // Records the text of a failed HIP call for gswa_last_hip_error() and returns GSWA_EHIP.
 int report_hip_error(hipError_t e);
 
+// Compute units of the current device, for sizing launch grids (looked up once per process, in a
+// thread-safe way; 256 if the runtime cannot tell).  Buffer sizes never depend on it.
+inline int device_cu_count()
+{
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        return n > 0 ? n : 256;
+    }();
+    return cus;
+}
+// The compute units every scratch size is computed for: launches use at most this many.
+constexpr int kSizingCus = 256;
+
 } // namespace gswa

@@ -789,19 +789,6 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
     }
 }
 
-int device_cu_count()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 // d w_proj, d b_proj of wide layers: dY^T [A | 1] over plain token rows, 64 tokens per pass.
 // Both operands are moved into [channel][token] LDS rows by selector MFMAs; wave w owns output
 // row tiles w*RW .. w*RW+RW-1 and all column tiles; the spare column C carries the bias sums.
@@ -924,10 +911,13 @@ template <int G> struct ChunkPlan<true, G> {
 template <> struct ChunkPlan<true, 3> { static constexpr int N = 3; static constexpr int B[3] = {4, 2, 0}, E[3] = {6, 4, 2}; };
 template <> struct ChunkPlan<true, 2> { static constexpr int N = 4; static constexpr int B[4] = {4, 3, 1, 0}, E[4] = {6, 4, 3, 1}; };
 
-int bwd_grid(const Geom &g)
+// Workgroups of a backward launch: narrow layers with more than one group run two per compute unit.
+// `cus` = the device's compute units for a launch, kSizingCus for the scratch size (a launch never
+// uses more workgroups than the size was computed for).
+int bwd_grid(const Geom &g, int cus)
 {
-    // narrow layers with more than one group run two workgroups per compute unit
-    int grid = ((g.C <= 64 && g.groups > 1) ? 2 : 1) * device_cu_count();
+    if (cus > kSizingCus) cus = kSizingCus;
+    const int grid = ((g.C <= 64 && g.groups > 1) ? 2 : 1) * cus;
     return grid > g.nW ? g.nW : grid;
 }
 
@@ -1028,7 +1018,7 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
     const uint8_t *pack = static_cast<const uint8_t *>(pack_);
     float *part = static_cast<float *>(ws);
-    const int grid = bwd_grid(g);
+    const int grid = bwd_grid(g, device_cu_count());
     const GradOut go{dw_qkv, db_qkv, dw_proj, db_proj, dtable, accumulate};
     hipError_t e = launch_chunks<Cf>(g, grid, x, dy, attn, pack, table, dx, part, go, s);
     if (e != hipSuccess) return e;
@@ -1079,7 +1069,7 @@ size_t fused_bwd_ws_bytes(const Geom &g)
     if (g.C == C_ && g.heads == H_ && g.groups == G_) total = max_partial<FusedCfg<C_, H_, G_>>();
     GSWA_FUSED_SHAPES(X)
 #undef X
-    return ((size_t)bwd_grid(g) * total * 4 + 255) & ~size_t(255);
+    return ((size_t)bwd_grid(g, kSizingCus) * total * 4 + 255) & ~size_t(255);
 }
 
 hipError_t launch_fused_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,

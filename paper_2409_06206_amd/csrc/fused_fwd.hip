@@ -706,19 +706,6 @@ __global__ __launch_bounds__(256, 2) void proj_gemm_kernel(long T, const bf16_t 
     }
 }
 
-int device_cu_count()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 // Forward head chunks of the split path, in launch order (a group's cascade input must be in
 // memory before its chunk runs).
 template <int G> struct FwdPlan;

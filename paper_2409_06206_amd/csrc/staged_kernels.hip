@@ -215,18 +215,6 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, Li
                                reinterpret_cast<uint4 *>(lsm), kThreads, blockIdx.x, gridDim.x);
 }
 
-static int device_cus()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-    }
-    return cus;
-}
-
 // The same map for wide layers whose whole weight matrix fits LDS as fragments (NT * KS <= 152 KB):
 // one workgroup per compute unit (1024 threads; 512 where the rows' own fragments need the
 // registers) builds all of them once, and a wave reads the rows
@@ -364,7 +352,7 @@ template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const Li
     if (e != hipSuccess) return e;
     const long ntile = (a.rows + 15) / 16;
     long blocks = (ntile + NTHREADS / 64 - 1) / (NTHREADS / 64);
-    if (blocks > device_cus()) blocks = device_cus();
+    if (blocks > device_cu_count()) blocks = device_cu_count();
     KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), lds, s, a, ks, nt);
     return hipGetLastError();
@@ -400,7 +388,7 @@ static hipError_t launch_linear_mfma_t(const LinearArgs &a, const LinearArgs *b,
     const long ntile = (rows + 15) / 16;
     // every workgroup builds its chunk's weight fragments first: with several chunks the rows are
     // spread over fewer, longer-running workgroups
-    long blocks = (ntile + 3) / 4, cap = (chunks <= 2 ? 4L : 2L) * device_cus() / chunks;
+    long blocks = (ntile + 3) / 4, cap = (chunks <= 2 ? 4L : 2L) * device_cu_count() / chunks;
     if (cap < 1) cap = 1;
     if (blocks > cap) blocks = cap;
     KernelTimer kt(prof_id, s);
@@ -720,7 +708,7 @@ static void wgrad_splits(const WgradArgs &a, long *rps, long *splits)
     long s_ = (long)sqrt(700.0 * (double)a.rows / ((double)a.N * a.K));
     const long max_splits = (a.rows + 127) / 128;
     if (s_ > max_splits) s_ = max_splits;
-    const long resident = 2L * device_cus() / (tn * tk); // all workgroups on the chip at once
+    const long resident = 2L * device_cu_count() / (tn * tk); // all workgroups on the chip at once
     if (s_ > resident && resident >= 8) s_ = resident;
     if (a.exclusive && s_ > a.reps) s_ = a.reps; // every split then adds into a copy of its own
     if (s_ < 1) s_ = 1;

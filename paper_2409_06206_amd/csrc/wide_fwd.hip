@@ -471,19 +471,6 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
 
 #define GSWA_WIDE_SHAPES(X) X(180, 6, 1) X(180, 6, 2) X(180, 6, 3)
 
-int cu_count()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 template <class Cf>
 hipError_t run_wide_fwd(const Geom &g, const bf16_t *x, const uint8_t *pack, bf16_t *y, bf16_t *attn, int training,
                         hipStream_t s)
@@ -498,7 +485,7 @@ hipError_t run_wide_fwd(const Geom &g, const bf16_t *x, const uint8_t *pack, bf1
         attr_done = true;
     }
     // one window per wave: spread the windows over the compute units before filling a workgroup
-    int grid = cu_count();
+    int grid = device_cu_count();
     if (grid > g.nW) grid = g.nW;
     KernelTimer kt(K_FUSED_FWD, s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, pack, y, training ? attn : nullptr);
