@@ -22,11 +22,16 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (profiles/fused_kernels_c2_groups2_hbm_counters.txt), valid only for the kernel source they
-# were taken on: {(workload, groups, kernel): (sha256 of the kernel source, bytes per launch)}
+# HBM bytes per launch of a workload's dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (profiles/wide_layers_hbm_counters.txt, profiles/fused_kernels_c2_groups2_hbm_counters.txt; mean over
+# the launch kinds of that kernel), valid only for the kernel source they were taken on:
+# {(workload, groups, kernel): (source file, sha256 of it, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c2", 2, "fused_bwd"): ("543025eaca5637d323d8b5d5adeea5f256205d5adcce7374e0e0048c8723f94e", 77146317),
+    ("c4", 2, "fused_bwd"): ("fused_bwd.hip", "0f5966a802b405a14bc28e2c8ef915c2c013d667d38ef649b5e90da11ad862a5", 187015665),
+    ("c3", 2, "fused_bwd"): ("fused_bwd.hip", "0f5966a802b405a14bc28e2c8ef915c2c013d667d38ef649b5e90da11ad862a5", 103379503),
+    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "0f5966a802b405a14bc28e2c8ef915c2c013d667d38ef649b5e90da11ad862a5", 83589576),
+    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "7feb3b126cf1049bfdf47aa8df6ae3a87c8e3bbc8d61c77ff37fcce7af9c863d", 274594216),
+    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "87766f7201ea41409439c8069d667625587b2b4454e3b3928cb56883acdb02ec", 428977916),
 }
 
 
@@ -34,14 +39,13 @@ def measured_traffic(workload, groups, kernel):
     import hashlib
     import os
     entry = MEASURED_TRAFFIC.get((workload, groups, kernel))
-    if not entry or not entry[0]:
+    if not entry:
         return None
-    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2409_06206_amd", "csrc",
-                       kernel + ".hip")
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2409_06206_amd", "csrc", entry[0])
     if not os.path.exists(src):
         return None
     digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
-    return entry[1] if digest == entry[0] else None
+    return entry[2] if digest == entry[1] else None
 
 
 FLAGS = 0  # extra descriptor flags for every layer (--force-staged)

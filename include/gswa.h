@@ -103,8 +103,11 @@ typedef struct gswa_desc {
  *                  16 fp32 copies of the five parameter gradients (workgroups spread their atomic
  *                  adds over the copies; one launch sums them at the end) and, for bf16 layers with
  *                  64- or 144-token windows, one bias-table gradient per window.
- *                  Fused path: one partial parameter-gradient vector per workgroup.
- * Which path serves a layer depends only on desc (shape, dtype, flags).
+ *                  Fused path: one partial parameter-gradient vector per workgroup of ONE head-group
+ *                  launch (each launch is followed by the fixed-order sum of its partials, and the next
+ *                  reuses the buffer), so this size does not grow with the group count.
+ * Which path serves a layer, and every size, depends only on desc (shape, dtype, flags), not on the
+ * device.
  * Any output pointer may be NULL.  All sizes are multiples of 256.
  */
 int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_bytes,

@@ -3,11 +3,13 @@
 // relative bias and shift mask + softmax + PV + output projection (Eq. 7) + merge + reverse shift.
 //
 // One wavefront owns one window: its 64 tokens are four 16-token tiles, K, V and the
-// probabilities never leave the wave's registers.  A workgroup is eight waves that share the
-// weights in LDS; the weights of a wide layer (108 KB of QKV fragments, 72 KB of projection
-// fragments) do not fit LDS together, so they pass through it in chunks between workgroup
-// barriers: the QKV fragments of three or six heads, then the projection.  Every fragment read
-// from LDS serves the four token tiles of the wave.
+// probabilities never leave the wave's registers.  A workgroup is four waves, one per SIMD (a
+// wave then has the SIMD's whole register file: x of all groups and all head outputs stay in
+// registers).  The weights of a wide layer (108 KB of QKV fragments, 72 KB of projection
+// fragments) do not fit LDS together, so they pass through it as a stream of equal units, double
+// buffered, one workgroup barrier per unit: the QKV fragments of one head (one group: of its q,
+// k or v), then the projection in pieces of the same size.  Every fragment read from LDS serves
+// the four token tiles of the wave.
 //
 // Everything is kept with rows = features and column = token (T-form, see fused_bwd.hip), and a
 // head of 30 channels is two 16-row tiles, i.e. exactly the 32 k-slots of one K=32 MFMA step in
