@@ -75,7 +75,14 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr size_t P_WQW = P_WPK + (size_t)N_WPK * 1024;
     static constexpr size_t P_WPW = P_WQW + (size_t)N_WQW * 1024;
     static constexpr size_t P_TBW = P_WPW + (size_t)N_WPW * 1024;
-    static constexpr size_t P_END = P_TBW + (SPLIT ? (size_t)HEADS * TBW_PITCH * 4 : 0);
+    // Wide layers, backward with one wavefront per window (wide_bwd.hip) additionally reads
+    //   WQX  Wqkv^T for dF = d(q|k|v) Wqkv, K=32: one step = the 32 k-slots of one (head, q|k|v) in
+    //        head-padded order; (hd, t, ct), row l16 -> input channel 16 ct + l16 of the group;
+    //        query rows carry 1/sqrt(d) like WQ
+    static constexpr int CTF = (CG + 15) / 16;                    // 16-row tiles of a group's input channels
+    static constexpr int N_WQX = SPLIT ? HEADS * 3 * CTF : 0;
+    static constexpr size_t P_WQX = P_TBW + (SPLIT ? (size_t)HEADS * TBW_PITCH * 4 : 0);
+    static constexpr size_t P_END = P_WQX + (size_t)N_WQX * 1024;
 };
 
 // True when a fused forward instantiation exists for this geometry (bf16 only).
@@ -103,6 +110,15 @@ hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_
                             void *pack, hipStream_t s);
 hipError_t launch_wide_fwd(const Geom &g, const bf16_t *x, const void *pack, bf16_t *y, bf16_t *attn,
                            int training, hipStream_t s);
+
+// Wide layers (C = 180, two or three groups, 8x8 windows): the backward with one wavefront per
+// window (wide_bwd.hip).  One launch produces dx, the bias-table gradient and d(q|k|v) [T, 3C] in
+// scratch; the weight gradients are token-reducing products of their own over that buffer.
+bool wide_bwd_supported(const Geom &g);
+size_t wide_bwd_ws_bytes(const Geom &g);
+hipError_t launch_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const void *pack,
+                           const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
+                           float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s);
 
 bool fused_bwd_supported(const Geom &g);
 // Scratch of the fused backward: per-workgroup partial parameter gradients.

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void wide_pack_kernel(const bf16_t *__restrict
                                                         uint8_t *__restrict__ pack)
 {
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET, KSX = Cf::KSX;
-    constexpr int E_WQW = Cf::N_WQW * 64, E_WPW = Cf::N_WPW * 64, E_TBW = HEADS * Cf::TBW_PITCH;
+    constexpr int E_WQW = Cf::N_WQW * 64, E_WPW = Cf::N_WPW * 64, E_TBW = HEADS * Cf::TBW_PITCH, E_WQX = Cf::N_WQX * 64;
     const float qscale = kLog2e / sqrtf((float)D);
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int l16 = i & 15, q = (i >> 4) & 3;
@@ -94,6 +94,26 @@ __global__ __launch_bounds__(256) void wide_pack_kernel(const bf16_t *__restrict
     if (i < E_TBW) {
         const int hd = i / Cf::TBW_PITCH, e = i % Cf::TBW_PITCH;
         reinterpret_cast<float *>(pack + Cf::P_TBW)[i] = e < 225 ? to_f32(table[e * HEADS + hd]) * kLog2e : 0.f;
+        return;
+    }
+    i -= E_TBW;
+    if (i < E_WQX) { // Wqkv^T for the backward: row l16 -> input channel of the group, k-slots -> features of (hd, t)
+        int f = i >> 6;
+        const int ct = f % Cf::CTF; f /= Cf::CTF;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const int c = 16 * ct + (i & 15);
+        const int qq = (i >> 4) & 3;
+        const float sc = t == 0 ? 1.0f / sqrtf((float)D) : 1.0f;
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            const int fe = s < 4 ? 4 * qq + s : 16 + 4 * qq + (s - 4);
+            float w = 0.f;
+            if (c < CG && fe < D) w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + fe) * CG + c]) * sc;
+            v[s] = f32_to_bf16_bits(w);
+        }
+        reinterpret_cast<uint4 *>(pack + Cf::P_WQX)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
     }
 }
 
@@ -111,7 +131,6 @@ template <class Cf> struct WideFwdCfg {
     static constexpr int NPU = Cf::OT / OT_UNIT;                   // projection units
     static constexpr int NHU = Cf::HEADS * UPH;                    // head units
     static constexpr int NU = NHU + NPU;                           // units per window
-    static constexpr int STG = (int)((UNIT_BYTES / 16 + NTHREADS - 1) / NTHREADS); // 16-byte pieces per thread
     static constexpr size_t OFF_BIAS = 0;                          // fp32 b_qkv [3C], b_proj [C]
     static constexpr size_t OFF_TBL = (size_t)16 * Cf::C;          // fp32 [HEADS][TBW_PITCH]
     static constexpr size_t OFF_W = OFF_TBL + (size_t)Cf::HEADS * Cf::TBW_PITCH * 4;
@@ -144,9 +163,9 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
 {
     using W = WideFwdCfg<Cf>;
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
-    constexpr int KSX = Cf::KSX, TP = Cf::TBW_PITCH, NU = W::NU, STG = W::STG, OT_UNIT = W::OT_UNIT;
+    constexpr int KSX = Cf::KSX, TP = Cf::TBW_PITCH, NU = W::NU, OT_UNIT = W::OT_UNIT;
     constexpr int M = 8, NTHREADS = W::NTHREADS;
-    constexpr int N16 = (int)(W::UNIT_BYTES / 16);
+    constexpr int FPW = (W::FR_UNIT + W::NWAVES - 1) / W::NWAVES; // fragments a wave moves per unit
     constexpr int NTB = 2; // query tiles taken through the softmax together
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -166,26 +185,21 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
     // then projection fragments of OT_UNIT output tiles.  A thread stages its 16-byte pieces of the
     // next unit in registers while the current unit is computed with, and writes them to the other
     // LDS buffer afterwards; one barrier per unit. ----
-    uint32_t stg[STG][4]; // (scalars: stays in registers across the barriers and the window loop)
     auto unit_src = [&](int u) {
-        return reinterpret_cast<const uint4 *>(pack + (u < W::NHU ? Cf::P_WQW + (size_t)u * W::UNIT_BYTES
-                                                                  : Cf::P_WPW + (size_t)(u - W::NHU) * W::UNIT_BYTES));
+        return pack + (u < W::NHU ? Cf::P_WQW + (size_t)u * W::UNIT_BYTES
+                                  : Cf::P_WPW + (size_t)(u - W::NHU) * W::UNIT_BYTES);
     };
-    auto stage_load = [&](int u) {
-        const uint4 *src = unit_src(u);
+    // Loads that write LDS directly: one instruction moves one fragment (64 lanes x 16 bytes land at
+    // the wave-uniform LDS address + 16 * lane).  Wave w moves fragments w, w + 4, ... of the unit.
+    auto stream_unit = [&](int u, int slot) {
+        const uint8_t *src = unit_src(u) + 16 * lane;
+        uint8_t *dst = lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES;
 #pragma unroll
-        for (int k = 0; k < STG; ++k) {
-            const int i = k * NTHREADS + tid;
-            const uint4 v = src[i < N16 ? i : 0];
-            stg[k][0] = v.x; stg[k][1] = v.y; stg[k][2] = v.z; stg[k][3] = v.w;
-        }
-    };
-    auto stage_store = [&](int slot) {
-        uint4 *dst = reinterpret_cast<uint4 *>(lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES);
-#pragma unroll
-        for (int k = 0; k < STG; ++k) {
-            const int i = k * NTHREADS + tid;
-            if (i < N16) dst[i] = make_uint4(stg[k][0], stg[k][1], stg[k][2], stg[k][3]);
+        for (int k = 0; k < FPW; ++k) {
+            const int f = k * W::NWAVES + wv;
+            if (f < W::FR_UNIT)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (size_t)f * 1024),
+                                                 (__attribute__((address_space(3))) void *)(dst + (size_t)f * 1024), 16, 0, 0);
         }
     };
 
@@ -234,12 +248,12 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
     }
 
     // set-up: linear biases, bias table, first unit
-    stage_load(0);
+    stream_unit(0, 0);
     for (int i = tid; i < C; i += NTHREADS)
         reinterpret_cast<uint4 *>(lds + W::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
     for (int i = tid; i < HEADS * TP / 4; i += NTHREADS)
         reinterpret_cast<uint4 *>(lds + W::OFF_TBL)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_TBW)[i];
-    stage_store(0);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     // this lane's query column (rn = 2nt + rsub, cn) against key rows 4q+j of key tile kt:
@@ -275,9 +289,10 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
         static_for<NU>([&](auto u_) {
             constexpr int u = decltype(u_)::value;
             const uint4 *wu = reinterpret_cast<const uint4 *>(lds + lds0 + W::OFF_W + (size_t)(u & 1) * W::UNIT_BYTES);
-            // next unit on its way (the first of the next window after the last)
-            if (u + 1 < NU) stage_load(u + 1);
-            else if (more) stage_load(0);
+            // next unit on its way into the other buffer (the first of the next window after the last):
+            // every wave has passed the previous barrier, i.e. finished reading that buffer
+            if (u + 1 < NU) stream_unit(u + 1, (u + 1) & 1);
+            else if (more) stream_unit(0, 0);
 
             if constexpr (u < W::NHU) {
                 constexpr int hd = u / W::UPH, part = u % W::UPH, gi = hd / HG, hl = hd % HG;
@@ -461,9 +476,8 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
                     }
                 }
             }
-            // the staged unit goes to the buffer the previous unit was read from (every wave has
-            // passed the previous barrier, i.e. finished with it)
-            if (u + 1 < NU || more) stage_store((u + 1) & 1);
+            // the next unit has landed in LDS before any wave reads it
+            __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
         });
         win += stride;
@@ -512,7 +526,7 @@ hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_
 #define X(C_, H_, G_)                                                                                    \
     if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                                  \
         using Cf = FusedCfg<C_, H_, G_>;                                                                 \
-        constexpr int entries = (Cf::N_WQW + Cf::N_WPW) * 64 + Cf::HEADS * Cf::TBW_PITCH;                \
+        constexpr int entries = (Cf::N_WQW + Cf::N_WPW + Cf::N_WQX) * 64 + Cf::HEADS * Cf::TBW_PITCH;                \
         KernelTimer kt(K_PACK_FWD, s);                                                                   \
         hipLaunchKernelGGL(wide_pack_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, w_proj, \
                            table, static_cast<uint8_t *>(pack));                                        \
