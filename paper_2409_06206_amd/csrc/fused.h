@@ -111,14 +111,31 @@ hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_
 hipError_t launch_wide_fwd(const Geom &g, const bf16_t *x, const void *pack, bf16_t *y, bf16_t *attn,
                            int training, hipStream_t s);
 
-// Wide layers (C = 180, two or three groups, 8x8 windows): the backward with one wavefront per
-// window (wide_bwd.hip).  One launch produces dx, the bias-table gradient and d(q|k|v) [T, 3C] in
-// scratch; the weight gradients are token-reducing products of their own over that buffer.
+// Sums the per-workgroup partial vectors of one launch and scatters their segments to the gradients
+// (fixed summation order).  Segment k covers entries [begin[k], begin[k+1]) of a partial vector and
+// goes to ptr[k] + offset, contiguously; the last segment (if tbl_heads > 0) is the bias-table
+// gradient, stored head by head in the partial vector and scattered to
+// dtable[entry * tbl_stride + tbl_head0 + head].
+struct ReduceOut {
+    static constexpr int MAXSEG = 22;
+    float *ptr[MAXSEG];
+    int begin[MAXSEG + 1];
+    int nseg;
+    int tbl_heads, tbl_entries, tbl_stride, tbl_head0;
+};
+hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s);
+
+// Wide layers (C = 180, two or three groups, 8x8 windows), backward of the attention and of the QKV
+// projection, group by group in reverse order (wide_bwd.hip): one launch with one wavefront per
+// window recomputes the group's q, k, v and probabilities and leaves d(q|k|v) in scratch and the
+// bias-table gradient as per-wavefront partial sums; a second launch turns d(q|k|v) into the
+// group's dx slice (the cascade gradient of the group before, Eq. 8) and its weight gradients.
+// d w_proj / d b_proj are not produced here.
 bool wide_bwd_supported(const Geom &g);
 size_t wide_bwd_ws_bytes(const Geom &g);
 hipError_t launch_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const void *pack,
-                           const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv, float *dw_proj,
-                           float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s);
+                           bf16_t *dx, float *dw_qkv, float *db_qkv, float *dtable, int accumulate, void *ws,
+                           hipStream_t s);
 
 bool fused_bwd_supported(const Geom &g);
 // Scratch of the fused backward: per-workgroup partial parameter gradients.

@@ -102,37 +102,6 @@ template <class Cf> __device__ __forceinline__ constexpr int fqt(int hd, int t, 
     return ((((hd * 3 + t) * Cf::ET + et) * Cf::HG + hlp) * Cf::ET) + etp;
 }
 
-__device__ __forceinline__ uint4 cat(uint2 a, uint2 b) { return make_uint4(a.x, a.y, b.x, b.y); }
-
-// Transposed store of a packed result tile (this lane: rows 4q..4q+3 of column l16) into
-// row-major LDS rows.  Neighbouring lanes l16, l16^1 swap halves through DPP so that every lane
-// writes whole dwords: even lanes rows 4q and 4q+2, odd lanes rows 4q+1 and 4q+3, each holding
-// the columns (l16 & ~1, l16 | 1).  `row0` points at row 4q, column l16 & ~1.
-__device__ __forceinline__ void store_tile_transposed(uint16_t *row0, int pitch, uint2 tile, int lane)
-{
-    const int odd = lane & 1;
-    const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)tile.x, 0xB1, 0xF, 0xF, true); // quad_perm [1,0,3,2]
-    const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)tile.y, 0xB1, 0xF, 0xF, true);
-    const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
-    // even: lo16(own) | lo16(partner) << 16 ;  odd: hi16(partner) | hi16(own) << 16
-    const uint32_t vx = __builtin_amdgcn_perm(px, tile.x, sel); // selector bytes 4-7 pick from px, 0-3 from own
-    const uint32_t vy = __builtin_amdgcn_perm(py, tile.y, sel);
-    uint32_t *d = reinterpret_cast<uint32_t *>(row0 + odd * pitch);
-    d[0] = vx;
-    d[pitch] = vy; // two rows further: 2 * pitch halves = pitch dwords
-}
-
-// K=32 operand that is 1.0 in the k-slot holding index `target` and 0 elsewhere, for a lane
-// whose slots 0..7 hold indices first .. first+7.  Multiplying by it moves a matrix held as an
-// operand (k-slots = columns) into result layout exactly: a transposition done by the MFMA unit.
-__device__ __forceinline__ uint4 select_slot(int target, int first)
-{
-    const int sl = target - first;
-    const uint32_t one = (sl & 1) ? 0x3f800000u : 0x00003f80u;
-    const int dw = (sl >= 0 && sl < 8) ? (sl >> 1) : -1;
-    return make_uint4(dw == 0 ? one : 0u, dw == 1 ? one : 0u, dw == 2 ? one : 0u, dw == 3 ? one : 0u);
-}
-
 constexpr bool ranges_overlap(int a0, int a1, int b0, int b1) { return a0 < b1 && b0 < a1; }
 
 template <class Cf, int HB, int HE, bool WPROJ>
@@ -738,19 +707,7 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     }
 }
 
-// Sums the per-workgroup partial vectors of one launch and scatters their segments to the gradients.
-// One block handles 32 entries; 32 slices of the block each sum a 32nd of the partials (16 loads per
-// thread at 512 partials, eight in flight at a time); fixed summation order.
-// Segment k covers entries [begin[k], begin[k+1]) of a partial vector and goes to ptr[k] + offset,
-// contiguously; the last segment (if tbl_heads > 0) is the bias-table gradient, stored head by head
-// in the partial vector and scattered to dtable[entry * tbl_stride + tbl_head0 + head].
-struct ReduceOut {
-    static constexpr int MAXSEG = 22;
-    float *ptr[MAXSEG];
-    int begin[MAXSEG + 1];
-    int nseg;
-    int tbl_heads, tbl_entries, tbl_stride, tbl_head0;
-};
+// (segment table: ReduceOut, fused.h)
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
                                                                int n, ReduceOut out, int accumulate)
 {
@@ -926,12 +883,16 @@ struct GradOut {
     int accumulate;
 };
 
+} // namespace
+
 hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s)
 {
     KernelTimer kt(K_REDUCE, s);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);
     return hipGetLastError();
 }
+
+namespace {
 
 // One chunk of heads: the kernel, then the sum of its partials into the gradients it owns.  The
 // scratch is free again afterwards, so every chunk (and the projection's weight gradient of wide
@@ -1010,41 +971,54 @@ template <class Cf, int I = 0> constexpr int max_partial()
     }
 }
 
+// d w_proj, d b_proj of a wide layer: the kernel, then the sum of its partials.
+template <class Cf>
+hipError_t run_wproj_grad(const Geom &g, int grid, const bf16_t *dy, const bf16_t *attn, float *part, float *dw_proj,
+                          float *db_proj, int accumulate, hipStream_t s)
+{
+    using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
+    constexpr size_t lds = (size_t)16 * (B::OTP + B::CTP) * B::LW * 2;
+    auto kern = wproj_grad_kernel<Cf>;
+    static bool attr_done = false;
+    if (!attr_done && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    {
+        KernelTimer kt(K_WPROJ_GRAD, s);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.T, dy, attn, part);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    ReduceOut out{};
+    out.ptr[0] = dw_proj; out.begin[0] = 0;
+    out.ptr[1] = db_proj; out.begin[1] = Cf::C * Cf::C;
+    out.begin[2] = Cf::C * Cf::C + Cf::C;
+    out.nseg = 2;
+    return launch_reduce(part, grid, Cf::C * Cf::C + Cf::C, out, accumulate, s);
+}
+
 template <class Cf>
 hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                    const void *pack_, const bf16_t *table, bf16_t *dx, float *dw_qkv, float *db_qkv,
                    float *dw_proj, float *db_proj, float *dtable, int accumulate, void *ws, hipStream_t s)
 {
-    using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
     const uint8_t *pack = static_cast<const uint8_t *>(pack_);
     float *part = static_cast<float *>(ws);
     const int grid = bwd_grid(g, device_cu_count());
+    if constexpr (Cf::SPLIT) {
+        if (wide_bwd_supported(g)) { // (the projection's gradient reuses the scratch afterwards)
+            hipError_t e = launch_wide_bwd(g, x, dy, attn, pack_, dx, dw_qkv, db_qkv, dtable, accumulate, ws, s);
+            if (e != hipSuccess) return e;
+            return run_wproj_grad<Cf>(g, grid, dy, attn, part, dw_proj, db_proj, accumulate, s);
+        }
+    }
     const GradOut go{dw_qkv, db_qkv, dw_proj, db_proj, dtable, accumulate};
     hipError_t e = launch_chunks<Cf>(g, grid, x, dy, attn, pack, table, dx, part, go, s);
     if (e != hipSuccess) return e;
-    if constexpr (Cf::SPLIT) {
-        constexpr size_t lds = (size_t)16 * (B::OTP + B::CTP) * B::LW * 2;
-        auto kern = wproj_grad_kernel<Cf>;
-        static bool attr_done = false;
-        if (!attr_done && lds > 64 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
-        {
-            KernelTimer kt(K_WPROJ_GRAD, s);
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.T, dy, attn, part);
-        }
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        ReduceOut out{};
-        out.ptr[0] = dw_proj; out.begin[0] = 0;
-        out.ptr[1] = db_proj; out.begin[1] = Cf::C * Cf::C;
-        out.begin[2] = Cf::C * Cf::C + Cf::C;
-        out.nseg = 2;
-        return launch_reduce(part, grid, Cf::C * Cf::C + Cf::C, out, accumulate, s);
-    }
+    if constexpr (Cf::SPLIT) return run_wproj_grad<Cf>(g, grid, dy, attn, part, dw_proj, db_proj, accumulate, s);
     return hipSuccess;
 }
 
@@ -1069,7 +1043,9 @@ size_t fused_bwd_ws_bytes(const Geom &g)
     if (g.C == C_ && g.heads == H_ && g.groups == G_) total = max_partial<FusedCfg<C_, H_, G_>>();
     GSWA_FUSED_SHAPES(X)
 #undef X
-    return ((size_t)bwd_grid(g, kSizingCus) * total * 4 + 255) & ~size_t(255);
+    const size_t chunks = ((size_t)bwd_grid(g, kSizingCus) * total * 4 + 255) & ~size_t(255);
+    const size_t wide = wide_bwd_supported(g) ? wide_bwd_ws_bytes(g) : 0;
+    return wide > chunks ? wide : chunks;
 }
 
 hipError_t launch_fused_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,

@@ -16,6 +16,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace gswa {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -88,6 +91,16 @@ __device__ __forceinline__ uint2 bload64(buf_t b, uint32_t voff, uint32_t soff)
     const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(b, (int)voff, (int)soff, 0);
     return make_uint2(v[0], v[1]);
 }
+__device__ __forceinline__ uint4 bload128(buf_t b, uint32_t voff, uint32_t soff)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(b, (int)voff, (int)soff, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void bstore128(buf_t b, uint32_t voff, uint32_t soff, uint4 v)
+{
+    const u32x4 w = {v.x, v.y, v.z, v.w};
+    __builtin_amdgcn_raw_buffer_store_b128(w, b, (int)voff, (int)soff, 0);
+}
 __device__ __forceinline__ void bstore32(buf_t b, uint32_t voff, uint32_t soff, uint32_t v)
 {
     __builtin_amdgcn_raw_buffer_store_b32(v, b, (int)voff, (int)soff, 0);
@@ -96,6 +109,67 @@ __device__ __forceinline__ void bstore64(buf_t b, uint32_t voff, uint32_t soff, 
 {
     const u32x2 w = {v.x, v.y};
     __builtin_amdgcn_raw_buffer_store_b64(w, b, (int)voff, (int)soff, 0);
+}
+
+// One load instruction that writes LDS directly: lane l's 16 bytes at `src` (a per-lane address) land at
+// the wave-uniform LDS address `dst` + 16 l.  Asynchronous: the data is in LDS once the wave's
+// vector-memory counter has drained (s_waitcnt vmcnt(0)), which the caller does before the barrier
+// that hands the data to its readers; the compiler is not told that LDS changes, so it adds no wait
+// of its own to later LDS reads (they must not touch the destination before that barrier).
+__device__ __forceinline__ void lds_dma16(const void *src, void *dst)
+{
+    const uint32_t ldsaddr =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(ldsaddr), "v"(src) : "memory", "m0");
+}
+
+__device__ __forceinline__ uint4 cat(uint2 a, uint2 b) { return make_uint4(a.x, a.y, b.x, b.y); }
+
+// Transposed store of a packed result tile (this lane: rows 4q..4q+3 of column l16) into
+// row-major LDS rows.  Neighbouring lanes l16, l16^1 swap halves through DPP so that every lane
+// writes whole dwords: even lanes rows 4q and 4q+2, odd lanes rows 4q+1 and 4q+3, each holding
+// the columns (l16 & ~1, l16 | 1).  `row0` points at row 4q, column l16 & ~1.
+__device__ __forceinline__ void store_tile_transposed(uint16_t *row0, int pitch, uint2 tile, int lane)
+{
+    const int odd = lane & 1;
+    const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)tile.x, 0xB1, 0xF, 0xF, true); // quad_perm [1,0,3,2]
+    const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)tile.y, 0xB1, 0xF, 0xF, true);
+    const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+    // even: lo16(own) | lo16(partner) << 16 ;  odd: hi16(partner) | hi16(own) << 16
+    const uint32_t vx = __builtin_amdgcn_perm(px, tile.x, sel); // selector bytes 4-7 pick from px, 0-3 from own
+    const uint32_t vy = __builtin_amdgcn_perm(py, tile.y, sel);
+    uint32_t *d = reinterpret_cast<uint32_t *>(row0 + odd * pitch);
+    d[0] = vx;
+    d[pitch] = vy; // two rows further: 2 * pitch halves = pitch dwords
+}
+
+// K=32 operand that is 1.0 in the k-slot holding index `target` and 0 elsewhere, for a lane
+// whose slots 0..7 hold indices first .. first+7.  Multiplying by it moves a matrix held as an
+// operand (k-slots = columns) into result layout exactly: a transposition done by the MFMA unit.
+__device__ __forceinline__ uint4 select_slot(int target, int first)
+{
+    const int sl = target - first;
+    const uint32_t one = (sl & 1) ? 0x3f800000u : 0x00003f80u;
+    const int dw = (sl >= 0 && sl < 8) ? (sl >> 1) : -1;
+    return make_uint4(dw == 0 ? one : 0u, dw == 1 ? one : 0u, dw == 2 ? one : 0u, dw == 3 ? one : 0u);
+}
+
+
+// packed bf16 pairs, added in fp32 and rounded once
+__device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b)
+{
+    return pack_bf16x2(bf16_lo(a) + bf16_lo(b), bf16_hi(a) + bf16_hi(b));
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant
+// expression inside the body (register arrays indexed by it never need memory).
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(static_cast<F &&>(f), std::make_integer_sequence<int, N>{});
 }
 
 } // namespace gswa

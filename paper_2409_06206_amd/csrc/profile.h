@@ -40,6 +40,8 @@ enum KernelId {
     K_MLP_PACK,     // the MLP's weights into MFMA fragment order (once per forward call)
     K_MLP_REDUCE,   // per-workgroup partial weight gradients of the MLP -> gradients
     K_LN_FWD_REDUCE, // LayerNorm of every token and that sum in one launch
+    K_WIDE_ATTN_BWD, // wide layers: adjoint of one group's attention, one wavefront per window
+    K_WIDE_WGRAD,    // wide layers: a group's dx slice and weight gradients from d(q|k|v)
     K_COUNT
 };
 

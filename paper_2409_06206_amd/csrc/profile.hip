@@ -27,7 +27,8 @@ const char *kernel_name(int id)
                                          "qkv_wgrad", "pack_fwd", "fused_fwd", "fused_bwd", "reduce_partials", "fused_attn_fwd", "proj_gemm",
                                          "wproj_grad", "attn_core_fwd", "attn_core_bwd", "qkv+dO_linear", "window_fwd",
                                          "ln_fwd", "ln_bwd", "gelu_fwd", "gelu_bwd", "fc1_linear", "fc2_linear",
-                                         "fc_dlinear", "fc_wgrad", "mlp_fwd", "mlp_bwd", "mlp_pack", "mlp_reduce", "ln_fwd+mlp_reduce"};
+                                         "fc_dlinear", "fc_wgrad", "mlp_fwd", "mlp_bwd", "mlp_pack", "mlp_reduce", "ln_fwd+mlp_reduce",
+                                         "wide_attn_bwd", "wide_qkv_grad"};
     return (id >= 0 && id < K_COUNT) ? names[id] : "?";
 }
 

@@ -1,0 +1,815 @@
+// Backward of wide GSWA layers (C = 180, six heads of 30 channels, 8x8 windows, two or three
+// groups) through the attention and the QKV projection, group by group in reverse order (Eq. 8 hands
+// the gradient of a group's input to the output of the group before it).  Two launches per group:
+//
+// wide_attn_bwd_kernel: one wavefront per window, as in the forward (wide_fwd.hip): four waves per
+//   workgroup, one per SIMD, the weights streamed through LDS as equal units, double buffered, one
+//   workgroup barrier per unit.  Per window: dO of the group's heads = dy Wproj (adjoint of Eq. 7) plus
+//   the cascade gradient (the dx slice of the next group, already final); then per head q, k, v, the
+//   scores and the softmax are recomputed exactly as the forward computes them (same operands, base-2
+//   units, same mask), and dP, dS, dQ, dK, dV follow.  Nothing crosses waves: the products that reduce
+//   over queries take P and dS transposed by the matrix cores (a packed tile times the identity).
+//   d(q|k|v) leaves as MFMA operand fragments, 1 KB per (16 tokens, head, q|k|v), stored with whole
+//   cache lines.  The bias-table gradient of a head is folded from its (query, key) form to the
+//   (2M-1)^2 offsets through a private piece of LDS and kept in registers across the windows of a wave.
+//
+// wide_qkv_grad_kernel: one workgroup per window (one wave per 16 tokens), plain GEMM work: the
+//   group's dx slice = d(q|k|v) Wqkv, and d w_qkv, d b_qkv = d(q|k|v)^T [F | 1] accumulated in
+//   registers over the windows of a workgroup (F = x slice + previous group's output, Eq. 8).
+//
+// Notation (T-form, N-form, head-padded order): fused_bwd.hip, wide_fwd.hip.
+#include "fused.h"
+#include "mfma.h"
+
+namespace gswa {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kMaskLog2 = -100.0f * kLog2e; // the additive -100 of the shift mask, in base-2 units
+
+template <class Cf> struct WideBwdCfg {
+    static constexpr int NWAVES = 4, NTHREADS = 64 * NWAVES;
+    static constexpr int NTBL = 15 * 15;
+    // stream units: the Wproj^T fragments of the group's heads in two halves, then per head its QKV fragments
+    static constexpr int FR_UNIT = 3 * Cf::ET * Cf::KSX;
+    static constexpr size_t UNIT_BYTES = (size_t)FR_UNIT * 1024;
+    static constexpr int NAU = 2;
+    static constexpr int NU = NAU + Cf::HG;
+    static constexpr int TILES_AU = FR_UNIT / Cf::KSC;             // (head, feature tile) pairs of dO per unit
+    static_assert(Cf::HG * Cf::ET * Cf::KSC == NAU * FR_UNIT && FR_UNIT % Cf::KSC == 0, "dO units");
+    static constexpr int FPW = (FR_UNIT + NWAVES - 1) / NWAVES;    // fragments a wave moves per unit
+    static constexpr size_t OFF_BIAS = 0;                          // fp32 b_qkv [3C] (b_proj [C] behind it)
+    static constexpr size_t OFF_TBL = (size_t)16 * Cf::C;          // fp32 [HEADS][TBW_PITCH], base-2 units
+    static constexpr size_t OFF_FOLD = OFF_TBL + (size_t)Cf::HEADS * Cf::TBW_PITCH * 4; // per wave 28 x 64 fp32
+    static constexpr size_t FOLD_BYTES = (size_t)28 * 64 * 4;
+    static constexpr size_t OFF_W = OFF_FOLD + NWAVES * FOLD_BYTES;
+    static constexpr size_t LDS_BYTES = OFF_W + 2 * UNIT_BYTES;
+    static_assert(OFF_W % 1024 == 0 || OFF_W % 16 == 0, "fragment alignment");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(Cf::ET == 2 && Cf::D + 1 <= 32 && Cf::CG % Cf::D == 0, "heads of 17..31 channels");
+    // d(q|k|v) in scratch: fragment ((window * 4 + token tile) * HG + head of the group) * 3 + (q|k|v)
+    static constexpr int FR_TILE = Cf::HG * 3;
+    // second kernel
+    static constexpr int KS = Cf::KS;                  // K=32 steps over the group's channels, natural order
+    static constexpr int CT = Cf::CG / 16 + 1;         // column tiles of d w_qkv, column CG carries the bias sums
+    static constexpr int CTF = Cf::CTF;                // 16-channel tiles of the dx slice
+    static constexpr int FT = Cf::HG * 3 * Cf::ET;     // 16-row tiles of d(q|k|v), head width padded to 32
+    static constexpr int RW = (FT + NWAVES - 1) / NWAVES;
+    static constexpr int LW = 68;                      // pitch (bf16) of the [row][token] buffers
+    static constexpr size_t G_OFF_WQX = 0;
+    static constexpr size_t G_OFF_G = (size_t)Cf::HG * 3 * CTF * 1024;
+    static constexpr size_t G_OFF_F = G_OFF_G + (size_t)FT * 16 * LW * 2;
+    static constexpr size_t G_LDS_BYTES = G_OFF_F + (size_t)CT * 16 * LW * 2;
+    static_assert(G_LDS_BYTES <= 160 * 1024, "LDS budget");
+    static constexpr int L_DW = 0, L_DB = 3 * Cf::CG * Cf::CG, L_TOTAL = L_DB + 3 * Cf::CG;
+};
+
+// transposes a packed 16x16 tile on the matrix cores: the tile as the A operand (row l16, k-slots
+// 4q..4q+3) times the identity is the tile with rows and columns exchanged, exactly
+__device__ __forceinline__ uint2 transpose_tile(uint2 tile, uint2 ident)
+{
+    return pack_bf16x4(mma16(tile, ident, f32x4{0.f, 0.f, 0.f, 0.f}));
+}
+
+template <class Cf, int GI>
+__global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                               const bf16_t *__restrict__ dy,
+                                                               const bf16_t *__restrict__ attn,
+                                                               const uint8_t *__restrict__ pack,
+                                                               const bf16_t *dx, uint8_t *__restrict__ dqkv,
+                                                               float *__restrict__ tpart)
+{
+    using W = WideBwdCfg<Cf>;
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
+    constexpr int KSX = Cf::KSX, KSC = Cf::KSC, TP = Cf::TBW_PITCH, NU = W::NU, NTBL = W::NTBL;
+    constexpr int M = 8;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = g.shift;
+    const int cn = l16 & 7, rsub = l16 >> 3;
+    const int per_img = g.nwi * g.nwj;
+    const uint32_t tbytes = (uint32_t)g.T * (2u * C);
+    const buf_t xbuf = make_buf(x, tbytes), dybuf = make_buf(dy, tbytes), abuf = make_buf(attn, tbytes),
+                dxbuf = make_buf(dx, tbytes);
+    const uint32_t m_hx = (16 + 4 * q < D) ? 0xffffffffu : 0u, m_hy = (16 + 4 * q + 2 < D) ? 0xffffffffu : 0u;
+    const uint32_t c8 = 8u * q;
+    const bool casc_in = GI > 0 && g.cascade, casc_out = GI < G - 1 && g.cascade;
+
+    // ---- weight stream (see wide_fwd.hip): loads that write LDS directly, one fragment per instruction ----
+    auto stream_unit = [&](int u, int slot) {
+        const size_t from = u < W::NAU ? Cf::P_WPT + ((size_t)GI * HG * Cf::ET * KSC + (size_t)u * W::FR_UNIT) * 1024
+                                       : Cf::P_WQW + ((size_t)GI * HG + (u - W::NAU)) * W::UNIT_BYTES;
+        const uint8_t *src = pack + from + 16 * lane;
+        uint8_t *dst = lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES;
+#pragma unroll
+        for (int k = 0; k < W::FPW; ++k) {
+            const int f = k * W::NWAVES + wv;
+            if (f < W::FR_UNIT) lds_dma16(src + (size_t)f * 1024, dst + (size_t)f * 1024);
+        }
+    };
+
+    const int stride = W::NWAVES * (int)gridDim.x;
+    const int rounds = (g.nW + stride - 1) / stride;
+    uint32_t tok[4];
+    bool lastrow = false, lastcol = false;
+    auto window_tokens = [&](int win) {
+        const int b = win / per_img;
+        const int wr = win - b * per_img;
+        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
+        lastrow = s > 0 && wi == g.nwi - 1;
+        lastcol = s > 0 && wj == g.nwj - 1;
+        int sj = wj * M + cn + s;
+        if (sj >= g.W) sj -= g.W;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            int si = wi * M + 2 * t + rsub + s;
+            if (si >= g.H) si -= g.H;
+            tok[t] = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
+        }
+    };
+
+    // rows of a window as operands: dy in channel order (K = 32 steps over all C channels); F = x slice
+    // (+ previous group's output, Eq. 8) in head-padded order
+    uint4 xh[KSX][4], dyf[KSC][4];
+    auto load_dy = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < KSC; ++ks)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                uint4 v = bload128(dybuf, tok[t] + 64u * ks + 16u * q, 0u);
+                const int c0 = 32 * ks + 8 * q; // first channel of this lane's slots
+                if (32 * ks + 32 > C) {
+                    v.x = c0 < C ? v.x : 0u;
+                    v.y = c0 + 2 < C ? v.y : 0u;
+                    v.z = c0 + 4 < C ? v.z : 0u;
+                    v.w = c0 + 6 < C ? v.w : 0u;
+                }
+                dyf[ks][t] = v;
+            }
+    };
+    auto load_x = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < KSX; ++ks)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t off = tok[t] + c8 + 2u * (GI * CG + ks * D);
+                const uint2 lo = bload64(xbuf, off, 0u);
+                uint2 hi = bload64(xbuf, off + 32u, 0u);
+                hi.x &= m_hx;
+                hi.y &= m_hy;
+                xh[ks][t] = cat(lo, hi);
+            }
+        if (casc_in) {
+#pragma unroll
+            for (int ks = 0; ks < KSX; ++ks)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t off = tok[t] + c8 + 2u * ((GI > 0 ? GI - 1 : 0) * CG + ks * D);
+                    const uint2 lo = bload64(abuf, off, 0u);
+                    const uint2 hi = bload64(abuf, off + 32u, 0u);
+                    uint4 &xv = xh[ks][t];
+                    xv.x = add_bf16x2(xv.x, lo.x);
+                    xv.y = add_bf16x2(xv.y, lo.y);
+                    xv.z = add_bf16x2(xv.z, hi.x & m_hx);
+                    xv.w = add_bf16x2(xv.w, hi.y & m_hy);
+                }
+        }
+    };
+
+    int win = wv * (int)gridDim.x + (int)blockIdx.x;
+    bool active = win < g.nW;
+
+    // set-up: linear biases, bias table, first unit
+    stream_unit(0, 0);
+    for (int i = tid; i < C; i += W::NTHREADS)
+        reinterpret_cast<uint4 *>(lds + W::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
+    for (int i = tid; i < HEADS * TP / 4; i += W::NTHREADS)
+        reinterpret_cast<uint4 *>(lds + W::OFF_TBL)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_TBW)[i];
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    // this lane's query column (rn = 2nt + rsub, cn) against key rows 4q+j of key tile kt:
+    // key (2kt + q/2, 4(q%2) + j); table entry = tb0 + 30(nt - kt) - j
+    const int tb0 = (rsub - (q >> 1) + M - 1) * (2 * M - 1) + (cn - 4 * (q & 1) + M - 1);
+    const bool qc_w = cn >= M - s;
+    bool kc_w[4], qr_w[4], kr_w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kc_w[j] = (4 * (q & 1) + j) >= M - s;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        qr_w[t] = (2 * t + rsub) >= M - s;
+        kr_w[t] = (2 * t + (q >> 1)) >= M - s;
+    }
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint2 ident; // identity as a K=16 operand: index l16, k-slots 4q+j
+    {
+        const uint32_t one = 0x3f80u;
+        const int d0 = l16 - 4 * q;
+        ident.x = (d0 == 0 ? one : 0u) | (d0 == 1 ? one << 16 : 0u);
+        ident.y = (d0 == 2 ? one : 0u) | (d0 == 3 ? one << 16 : 0u);
+    }
+    // Table-gradient fold.  A lane's sums of dS over the score tiles with the same offset nt - kt cover
+    // 28 (query, key) offset pairs; they are kept in the wave's piece of LDS, [offset][lane][j], and at
+    // the end of a head lane l collects table entries l, l + 64, ...: entry 15 (dr + 7) + (dc + 7)
+    // receives, from the lanes with 2 (dl - 3) + rsub - q/2 = dr, the slots with cn - 4 (q%2) - j = dc.
+    float *fold = reinterpret_cast<float *>(lds + W::OFF_FOLD + (size_t)wv * W::FOLD_BYTES);
+    f32x4 *fold4 = reinterpret_cast<f32x4 *>(fold);
+    float tgrad[HG][4];
+#pragma unroll
+    for (int hl = 0; hl < HG; ++hl)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tgrad[hl][i] = 0.f;
+
+    int par = 0; // LDS buffer of the first unit of this round
+    for (int round = 0; round < rounds; ++round) {
+        const bool more = round + 1 < rounds;
+        if (active) {
+            window_tokens(win);
+            load_dy();
+        }
+        uint2 dOb[HG][2][4]; // dO^T of the group's heads, packed T-form tiles
+
+        uint32_t lds0 = 0;
+        asm volatile("" : "+v"(lds0)); // keeps the LDS reads of a round inside the round
+        const float *bqkv = reinterpret_cast<const float *>(lds + lds0 + W::OFF_BIAS);
+        const float *tbl = reinterpret_cast<const float *>(lds + lds0 + W::OFF_TBL);
+        uint8_t *dq_win = dqkv + (size_t)win * 4 * W::FR_TILE * 1024 + 16 * lane;
+
+        static_for<NU>([&](auto u_) {
+            constexpr int u = decltype(u_)::value;
+            const uint4 *wu = reinterpret_cast<const uint4 *>(lds + lds0 + W::OFF_W + (size_t)((u + par) & 1) * W::UNIT_BYTES);
+            // next unit on its way into the other buffer: every wave has passed the previous barrier,
+            // i.e. finished reading it
+            if (u + 1 < NU) stream_unit(u + 1, (u + 1 + par) & 1);
+            else if (more) stream_unit(0, (NU + par) & 1);
+
+            if constexpr (u < W::NAU) {
+                // ---- dO^T = Wproj^T dY^T + cascade gradient (the dx slice of the next group): rows = head
+                // features, column = token ----
+                if (active) {
+                    uint2 cg[W::TILES_AU][4];
+#pragma unroll
+                    for (int i = 0; i < W::TILES_AU; ++i) {
+                        const int ti = u * W::TILES_AU + i, hl = ti / 2, et = ti % 2;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            uint2 v = make_uint2(0u, 0u);
+                            if (casc_out) {
+                                v = bload64(dxbuf, tok[t] + c8 + 2u * ((GI < G - 1 ? GI + 1 : 0) * CG + hl * D) + 32u * et, 0u);
+                                if (et == 1) {
+                                    v.x &= m_hx;
+                                    v.y &= m_hy;
+                                }
+                            }
+                            cg[i][t] = v;
+                        }
+                    }
+                    if (u == W::NAU - 1) load_x(); // in flight under this unit's products
+#pragma unroll
+                    for (int i = 0; i < W::TILES_AU; ++i) {
+                        const int ti = u * W::TILES_AU + i, hl = ti / 2, et = ti % 2;
+                        f32x4 acc[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) acc[t] = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < KSC; ++ks) {
+                            const uint4 wf = wu[(i * KSC + ks) * 64 + lane];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) acc[t] = mma32(wf, dyf[ks][t], acc[t]);
+                        }
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const uint2 c = cg[i][t];
+                            acc[t] += f32x4{bf16_lo(c.x), bf16_hi(c.x), bf16_lo(c.y), bf16_hi(c.y)};
+                            dOb[hl][et][t] = pack_bf16x4(acc[t]);
+                        }
+                    }
+                }
+            } else {
+                constexpr int hl = u - W::NAU, hd = GI * HG + hl;
+                if (active) {
+                    // ---- Q^T, K^T, V^T exactly as the forward computes them (rows = head features) ----
+                    uint2 Qb[2][4], Kb[2][4], Vb[2][4];
+#pragma unroll
+                    for (int t3 = 0; t3 < 3; ++t3) {
+                        f32x4 acc[2][4];
+#pragma unroll
+                        for (int et = 0; et < 2; ++et) {
+                            f32x4 b4;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int e = 16 * et + 4 * q + j;
+                                const float bv = e < D ? bqkv[GI * 3 * CG + t3 * CG + hl * D + e] : 0.f;
+                                b4[j] = t3 == 0 ? bv * kLog2e : bv;
+                            }
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) acc[et][t] = b4;
+                        }
+#pragma unroll
+                        for (int ks = 0; ks < KSX; ++ks) {
+                            const uint4 f0 = wu[((t3 * 2 + 0) * KSX + ks) * 64 + lane];
+                            const uint4 f1 = wu[((t3 * 2 + 1) * KSX + ks) * 64 + lane];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                acc[0][t] = mma32(f0, xh[ks][t], acc[0][t]);
+                                acc[1][t] = mma32(f1, xh[ks][t], acc[1][t]);
+                            }
+                        }
+#pragma unroll
+                        for (int et = 0; et < 2; ++et)
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const uint2 pk = pack_bf16x4(acc[et][t]);
+                                if (t3 == 0) Qb[et][t] = pk;
+                                else if (t3 == 1) Kb[et][t] = pk;
+                                else Vb[et][t] = pk;
+                            }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // N-form (rows = tokens, column = feature) of K for dQ
+                    uint2 KN[2][4];
+#pragma unroll
+                    for (int et = 0; et < 2; ++et)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) KN[et][t] = transpose_tile(Kb[et][t], ident);
+                    f32x4 dkT[2][4], dvT[2][4];
+#pragma unroll
+                    for (int et = 0; et < 2; ++et)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) dkT[et][t] = dvT[et][t] = zero4;
+                    // sums of dS over the score tiles with the same offset nt - kt, in this wave's piece of LDS:
+                    // [offset][lane] x 4 key rows
+#pragma unroll
+                    for (int dl = 0; dl < 7; ++dl) fold4[dl * 64 + lane] = zero4;
+
+#pragma unroll
+                    for (int p2 = 0; p2 < 2; ++p2) {
+                        // N-forms of Q and dO of this pair of query tiles, for dK and dV
+                        uint4 qn[2], on[2];
+#pragma unroll
+                        for (int et = 0; et < 2; ++et) {
+                            qn[et] = cat(transpose_tile(Qb[et][2 * p2], ident), transpose_tile(Qb[et][2 * p2 + 1], ident));
+                            on[et] = cat(transpose_tile(dOb[hl][et][2 * p2], ident),
+                                         transpose_tile(dOb[hl][et][2 * p2 + 1], ident));
+                        }
+                        uint2 Pq[4][2], dSq[4][2]; // P and dS with rows = queries, column = key
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            const int nt = 2 * p2 + ni;
+                            // ---- S^T, P^T, dP^T, dS^T of one query tile: rows = keys 16kt+4q+j, column = query ----
+                            f32x4 st[4], dp[4];
+                            const uint4 qop = cat(Qb[0][nt], Qb[1][nt]);
+                            const uint4 oop = cat(dOb[hl][0][nt], dOb[hl][1][nt]);
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt) {
+                                f32x4 bt;
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) bt[j] = tbl[hd * TP + tb0 + 30 * (nt - kt) - j];
+                                st[kt] = mma32(cat(Kb[0][kt], Kb[1][kt]), qop, bt);
+                                dp[kt] = mma32(cat(Vb[0][kt], Vb[1][kt]), oop, zero4);
+                            }
+                            if (lastrow || lastcol) {
+#pragma unroll
+                                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                                    for (int j = 0; j < 4; ++j)
+                                        if ((lastrow && qr_w[nt] != kr_w[kt]) || (lastcol && qc_w != kc_w[j]))
+                                            st[kt][j] += kMaskLog2;
+                            }
+                            float mx = fmaxf(fmaxf(st[0][0], st[0][1]), fmaxf(st[0][2], st[0][3]));
+#pragma unroll
+                            for (int kt = 1; kt < 4; ++kt)
+#pragma unroll
+                                for (int j = 0; j < 4; j += 2) mx = fmaxf(fmaxf(mx, st[kt][j]), st[kt][j + 1]);
+                            mx = qgroup_max(mx);
+                            float sum = 0.f, dlt = 0.f;
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const float p = __builtin_amdgcn_exp2f(st[kt][j] - mx);
+                                    st[kt][j] = p;
+                                    sum += p;
+                                    dlt = fmaf(p, dp[kt][j], dlt);
+                                }
+                            sum = qgroup_sum(sum);
+                            dlt = qgroup_sum(dlt);
+                            const float inv = __builtin_amdgcn_rcpf(sum);
+                            const float delta = dlt * inv; // sum over keys of P dP
+                            uint2 Pb[4], dSb[4];
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const float p = st[kt][j] * inv;
+                                    st[kt][j] = p;
+                                    dp[kt][j] = p * (dp[kt][j] - delta);
+                                }
+                                Pb[kt] = pack_bf16x4(st[kt]);
+                                dSb[kt] = pack_bf16x4(dp[kt]);
+                                fold4[(nt - kt + 3) * 64 + lane] += dp[kt];
+                            }
+                            // dQ^T = K^T dS^T (gradient of q / sqrt(d)): rows = head features, column = query
+                            f32x4 d0 = zero4, d1 = zero4;
+#pragma unroll
+                            for (int kp = 0; kp < 2; ++kp) {
+                                const uint4 sop = cat(dSb[2 * kp], dSb[2 * kp + 1]);
+                                d0 = mma32(cat(KN[0][2 * kp], KN[0][2 * kp + 1]), sop, d0);
+                                d1 = mma32(cat(KN[1][2 * kp], KN[1][2 * kp + 1]), sop, d1);
+                            }
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt) {
+                                Pq[kt][ni] = transpose_tile(Pb[kt], ident);
+                                dSq[kt][ni] = transpose_tile(dSb[kt], ident);
+                            }
+                            *reinterpret_cast<uint4 *>(dq_win + (size_t)((nt * HG + hl) * 3 + 0) * 1024) =
+                                cat(pack_bf16x4(d0), pack_bf16x4(d1));
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        // dK^T += Q^T dS, dV^T += dO^T P over the 32 queries of the pair
+#pragma unroll
+                        for (int et = 0; et < 2; ++et)
+#pragma unroll
+                            for (int kt = 0; kt < 4; ++kt) {
+                                dkT[et][kt] = mma32(qn[et], cat(dSq[kt][0], dSq[kt][1]), dkT[et][kt]);
+                                dvT[et][kt] = mma32(on[et], cat(Pq[kt][0], Pq[kt][1]), dvT[et][kt]);
+                            }
+                    }
+                    // dK = dS^T (q / sqrt(d)): the recomputed Q carries log2(e) / sqrt(d)
+#pragma unroll
+                    for (int kt = 0; kt < 4; ++kt) {
+                        *reinterpret_cast<uint4 *>(dq_win + (size_t)((kt * HG + hl) * 3 + 1) * 1024) =
+                            cat(pack_bf16x4(dkT[0][kt] * (1.0f / kLog2e)), pack_bf16x4(dkT[1][kt] * (1.0f / kLog2e)));
+                        *reinterpret_cast<uint4 *>(dq_win + (size_t)((kt * HG + hl) * 3 + 2) * 1024) =
+                            cat(pack_bf16x4(dvT[0][kt]), pack_bf16x4(dvT[1][kt]));
+                    }
+                    // ---- bias-table gradient of this head and window: fold to the offsets ----
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    int lane_here = lane; // (opaque: the 64 addresses below are recomputed here, not kept in registers)
+                    asm volatile("" : "+v"(lane_here));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int e = lane_here + 64 * i;
+                        const int R = e / 15, dc = e - 15 * R - 7, dr = R - 7;
+                        // the 16 reads of an entry are issued together, then summed
+                        float v[16];
+                        bool ok[16];
+#pragma unroll
+                        for (int c = 0; c < 2; ++c) {
+                            // lanes (rsub, q/2) = (c, c) for even dr, (c, 1 - c) for odd dr
+                            const int odd = dr & 1;
+                            const int rs = c, qh = odd ? 1 - c : c;
+                            const int num = dr - rs + qh; // = 2 (dl - 3)
+                            const int dl = (num >> 1) + 3;
+                            const bool rok = e < NTBL && dl >= 0 && dl <= 6;
+                            const int base = dl * 256 + 128 * qh + 32 * rs + 4 * dc;
+#pragma unroll
+                            for (int ql = 0; ql < 2; ++ql)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const int kc = dc + 4 * ql + j; // the contributing lane's query column
+                                    const int k = (c * 2 + ql) * 4 + j;
+                                    ok[k] = rok && kc >= 0 && kc < M;
+                                    v[k] = fold[ok[k] ? base + 80 * ql + 5 * j : 0];
+                                }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        float acc = 0.f;
+#pragma unroll
+                        for (int k = 0; k < 16; ++k) acc += ok[k] ? v[k] : 0.f;
+                        tgrad[hl][i] += acc;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+            // the next unit has landed in LDS before any wave reads it
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+        });
+        par = (par + NU) & 1;
+        win += stride;
+        active = win < g.nW;
+    }
+
+    // this wave's partial sums of the bias-table gradient (heads of this group; every wave writes)
+    float *mine = tpart + ((size_t)blockIdx.x * W::NWAVES + wv) * (HEADS * NTBL);
+#pragma unroll
+    for (int hl = 0; hl < HG; ++hl)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = lane + 64 * i;
+            if (e < NTBL) mine[(GI * HG + hl) * NTBL + e] = tgrad[hl][i];
+        }
+}
+
+// The group's dx slice and weight gradients from d(q|k|v).  One workgroup per window, wave w =
+// token tile w (the tokens whose fragments the first kernel stored as tile w of the window).
+template <class Cf, int GI>
+__global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf16_t *__restrict__ x,
+                                                               const bf16_t *__restrict__ attn,
+                                                               const uint8_t *__restrict__ pack,
+                                                               const uint8_t *__restrict__ dqkv,
+                                                               bf16_t *__restrict__ dx, float *__restrict__ part)
+{
+    using W = WideBwdCfg<Cf>;
+    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG;
+    constexpr int KS = W::KS, CT = W::CT, CTF = W::CTF, FT = W::FT, RW = W::RW, LW = W::LW;
+    constexpr int M = 8;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint4 *wqx = reinterpret_cast<const uint4 *>(lds + W::G_OFF_WQX);
+    uint16_t *gbuf = reinterpret_cast<uint16_t *>(lds + W::G_OFF_G); // d(q|k|v)^T rows [feature][token]
+    uint16_t *fbuf = reinterpret_cast<uint16_t *>(lds + W::G_OFF_F); // F^T rows [channel][token], row CG = 1
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = g.shift;
+    const int per_img = g.nwi * g.nwj;
+    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
+    const uint32_t tbytes = (uint32_t)g.T * (2u * C);
+    const buf_t xbuf = make_buf(x, tbytes), abuf = make_buf(attn, tbytes), dxbuf = make_buf(dx, tbytes);
+    const bool casc_in = GI > 0 && g.cascade;
+    const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
+
+    // the group's Wqkv^T fragments: (head of the group, q|k|v, channel tile)
+    {
+        constexpr int N16 = HG * 3 * CTF * 64;
+        const uint4 *src = reinterpret_cast<const uint4 *>(pack + Cf::P_WQX + (size_t)GI * HG * 3 * CTF * 1024);
+        for (int i = tid; i < N16; i += 256) reinterpret_cast<uint4 *>(lds + W::G_OFF_WQX)[i] = src[i];
+    }
+
+    f32x4 acc[RW][CT];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[r][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+        const int b = win / per_img;
+        const int wr = win - b * per_img;
+        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
+        int si = wi * M + rn + s, sj = wj * M + cn + s;
+        if (si >= g.H) si -= g.H;
+        if (sj >= g.W) sj -= g.W;
+        const uint32_t tok = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
+
+        uint4 dq[HG * 3];
+        const uint4 *dsrc = reinterpret_cast<const uint4 *>(dqkv + ((size_t)win * 4 + wv) * W::FR_TILE * 1024) + lane;
+#pragma unroll
+        for (int i = 0; i < HG * 3; ++i) dq[i] = dsrc[i * 64];
+        uint4 xf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint32_t off = tok + 2u * (GI * CG) + 64u * ks + 16u * q;
+            uint4 v = bload128(xbuf, off, 0u);
+            if (casc_in) {
+                const uint4 a = bload128(abuf, tok + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
+                v.x = add_bf16x2(v.x, a.x);
+                v.y = add_bf16x2(v.y, a.y);
+                v.z = add_bf16x2(v.z, a.z);
+                v.w = add_bf16x2(v.w, a.w);
+            }
+            const int c0 = 32 * ks + 8 * q;
+            if (32 * ks + 32 > CG) {
+                v.x = c0 < CG ? v.x : 0u;
+                v.y = c0 + 2 < CG ? v.y : 0u;
+                v.z = c0 + 4 < CG ? v.z : 0u;
+                v.w = c0 + 6 < CG ? v.w : 0u;
+            }
+            xf[ks] = v;
+        }
+        __syncthreads(); // the previous window's rows are consumed (first pass: the weights are in place)
+        // F^T rows through a selector product; d(q|k|v)^T rows by a transposed store of the packed tiles
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            f32x4 tN = f32x4{0.f, 0.f, 0.f, 0.f};
+            if ((ct >> 1) < KS)
+                tN = mma32(xf[(ct >> 1) < KS ? (ct >> 1) : 0], select_slot(16 * ct + l16, 32 * (ct >> 1) + 8 * q), tN);
+            uint2 pk = pack_bf16x4(tN);
+            if (16 * ct + l16 == CG) pk = ones2;
+            *reinterpret_cast<uint2 *>(fbuf + (16 * ct + l16) * LW + 16 * wv + 4 * q) = pk;
+        }
+#pragma unroll
+        for (int i = 0; i < HG * 3; ++i) {
+            store_tile_transposed(gbuf + ((2 * i + 0) * 16 + 4 * q) * LW + 16 * wv + (l16 & ~1), LW,
+                                  make_uint2(dq[i].x, dq[i].y), lane);
+            store_tile_transposed(gbuf + ((2 * i + 1) * 16 + 4 * q) * LW + 16 * wv + (l16 & ~1), LW,
+                                  make_uint2(dq[i].z, dq[i].w), lane);
+        }
+        // ---- dx slice of this wave's 16 tokens: dF^T = Wqkv^T d(q|k|v)^T, rows = channels ----
+        {
+            f32x4 df[CTF];
+#pragma unroll
+            for (int ct = 0; ct < CTF; ++ct) df[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < HG * 3; ++i)
+#pragma unroll
+                for (int ct = 0; ct < CTF; ++ct) df[ct] = mma32(wqx[(i * CTF + ct) * 64 + lane], dq[i], df[ct]);
+#pragma unroll
+            for (int ct = 0; ct < CTF; ++ct) {
+                const int c0 = 16 * ct + 4 * q;
+                const uint2 v = pack_bf16x4(df[ct]);
+                const uint32_t off = tok + 2u * (GI * CG + c0);
+                if (c0 + 2 < CG) bstore64(dxbuf, off, 0u, v);
+                else if (c0 < CG) bstore32(dxbuf, off, 0u, v.x);
+            }
+        }
+        __syncthreads();
+        // ---- d w_qkv, d b_qkv: wave w owns row tiles w*RW .., K = the window's 64 tokens ----
+        uint4 afr[RW][2];
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            const int rt = wv * RW + r;
+            const uint16_t *ar = gbuf + (16 * (rt < FT ? rt : 0) + l16) * LW + 8 * q;
+#pragma unroll
+            for (int kp = 0; kp < 2; ++kp)
+                afr[r][kp] = cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
+                                 *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4));
+        }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const uint16_t *br = fbuf + (16 * ct + l16) * LW + 8 * q;
+#pragma unroll
+            for (int kp = 0; kp < 2; ++kp) {
+                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
+                                     *reinterpret_cast<const uint2 *>(br + 32 * kp + 4));
+#pragma unroll
+                for (int r = 0; r < RW; ++r) acc[r][ct] = mma32(afr[r][kp], bf, acc[r][ct]);
+            }
+        }
+    }
+
+    // flush: rows in the order of w_qkv's rows of this group, (q|k|v, head, feature); the gradient of
+    // q / sqrt(d) becomes that of q
+    const float scale = 1.0f / sqrtf((float)D);
+    float *mine = part + (size_t)blockIdx.x * W::L_TOTAL;
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const int rt = wv * RW + r; // (head, q|k|v, half of the head's features)
+        if (rt < FT) {
+            const int i = rt >> 1, et = rt & 1, hl = i / 3, t3 = i - 3 * hl;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const int c = 16 * ct + l16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int e = 16 * et + 4 * q + j;
+                    if (e < D) {
+                        const int row = t3 * CG + hl * D + e;
+                        const float v = t3 == 0 ? acc[r][ct][j] * scale : acc[r][ct][j];
+                        if (c < CG) mine[W::L_DW + row * CG + c] = v;
+                        else if (c == CG) mine[W::L_DB + row] = v;
+                    }
+                }
+            }
+        }
+    }
+}
+
+int attn_grid(const Geom &g, int cus)
+{
+    if (cus > kSizingCus) cus = kSizingCus;
+    return cus > g.nW ? g.nW : cus;
+}
+
+// scratch: [ d(q|k|v) of one group | d w_qkv partials of one group | table partials ]; the projection's weight
+// gradient, which runs after this pass, puts its partial vectors over the same memory
+template <class Cf> struct WideBwdWs {
+    using W = WideBwdCfg<Cf>;
+    static size_t up(size_t v) { return (v + 255) & ~size_t(255); }
+    static size_t dqkv_bytes(const Geom &g) { return up((size_t)g.nW * 4 * W::FR_TILE * 1024); }
+    static size_t part_bytes(const Geom &g) { return up((size_t)attn_grid(g, kSizingCus) * W::L_TOTAL * 4); }
+    static size_t tbl_bytes(const Geom &g)
+    {
+        return up((size_t)attn_grid(g, kSizingCus) * W::NWAVES * Cf::HEADS * W::NTBL * 4);
+    }
+    static size_t wproj_bytes(const Geom &g) { return up((size_t)attn_grid(g, kSizingCus) * (Cf::C * Cf::C + Cf::C) * 4); }
+};
+
+template <class Cf, int GI>
+hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const uint8_t *pack,
+                     bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv, float *part, float *tpart,
+                     hipStream_t s)
+{
+    using W = WideBwdCfg<Cf>;
+    {
+        auto kern = wide_attn_bwd_kernel<Cf, GI>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)W::LDS_BYTES);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        KernelTimer kt(K_WIDE_ATTN_BWD, s);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, dy, attn, pack, dx, dqkv, tpart);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    {
+        auto kern = wide_qkv_grad_kernel<Cf, GI>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)W::G_LDS_BYTES);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        KernelTimer kt(K_WIDE_WGRAD, s);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), W::G_LDS_BYTES, s, g, x, attn, pack, dqkv, dx, part);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    ReduceOut out{};
+    out.ptr[0] = dw_qkv + (size_t)GI * 3 * Cf::CG * Cf::CG; out.begin[0] = W::L_DW;
+    out.ptr[1] = db_qkv + GI * 3 * Cf::CG; out.begin[1] = W::L_DB;
+    out.begin[2] = W::L_TOTAL;
+    out.nseg = 2;
+    return launch_reduce(part, grid, W::L_TOTAL, out, accumulate, s);
+}
+
+template <class Cf, int GI>
+hipError_t run_groups(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
+                      const uint8_t *pack, bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv,
+                      float *part, float *tpart, hipStream_t s)
+{
+    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, s);
+    if (e != hipSuccess) return e;
+    if constexpr (GI > 0)
+        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, s);
+    return hipSuccess;
+}
+
+template <class Cf>
+hipError_t run_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const uint8_t *pack,
+                        bf16_t *dx, float *dw_qkv, float *db_qkv, float *dtable, int accumulate, void *ws, hipStream_t s)
+{
+    using W = WideBwdCfg<Cf>;
+    using Ws = WideBwdWs<Cf>;
+    uint8_t *base = static_cast<uint8_t *>(ws);
+    uint8_t *dqkv = base;
+    float *part = reinterpret_cast<float *>(base + Ws::dqkv_bytes(g));
+    float *tpart = reinterpret_cast<float *>(base + Ws::dqkv_bytes(g) + Ws::part_bytes(g));
+    const int grid = attn_grid(g, device_cu_count());
+    hipError_t e = run_groups<Cf, Cf::G - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part,
+                                             tpart, s);
+    if (e != hipSuccess) return e;
+    ReduceOut out{};
+    out.ptr[0] = dtable; out.begin[0] = 0;
+    out.begin[1] = Cf::HEADS * W::NTBL;
+    out.nseg = 1;
+    out.tbl_heads = Cf::HEADS; out.tbl_entries = W::NTBL; out.tbl_stride = Cf::HEADS; out.tbl_head0 = 0;
+    return launch_reduce(tpart, grid * W::NWAVES, Cf::HEADS * W::NTBL, out, accumulate, s);
+}
+
+#define GSWA_WIDE_BWD_SHAPES(X) X(180, 6, 2) X(180, 6, 3)
+
+} // namespace
+
+bool wide_bwd_supported(const Geom &g)
+{
+    if (!wide_fwd_supported(g)) return false; // (8x8 windows, q and k of the head's width; the forward fills the fragments)
+    // 32-bit byte offsets into d(q|k|v)
+    if ((size_t)g.nW * 4 * 9 * 1024 >= (size_t(1) << 32)) return false;
+#define X(C_, H_, G_) \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) return true;
+    GSWA_WIDE_BWD_SHAPES(X)
+#undef X
+    return false;
+}
+
+size_t wide_bwd_ws_bytes(const Geom &g)
+{
+#define X(C_, H_, G_)                                                                       \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                     \
+        using Ws = WideBwdWs<FusedCfg<C_, H_, G_>>;                                         \
+        const size_t own = Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g);          \
+        return own > Ws::wproj_bytes(g) ? own : Ws::wproj_bytes(g);                         \
+    }
+    GSWA_WIDE_BWD_SHAPES(X)
+#undef X
+    return 0;
+}
+
+hipError_t launch_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const void *pack,
+                           bf16_t *dx, float *dw_qkv, float *db_qkv, float *dtable, int accumulate, void *ws,
+                           hipStream_t s)
+{
+#define X(C_, H_, G_)                                                                                            \
+    if (g.C == C_ && g.heads == H_ && g.groups == G_)                                                            \
+        return run_wide_bwd<FusedCfg<C_, H_, G_>>(g, x, dy, attn, static_cast<const uint8_t *>(pack), dx, dw_qkv, \
+                                                  db_qkv, dtable, accumulate, ws, s);
+    GSWA_WIDE_BWD_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+} // namespace gswa

@@ -20,23 +20,9 @@
 #include "fused.h"
 #include "mfma.h"
 
-#include <type_traits>
-#include <utility>
-
 namespace gswa {
 
 namespace {
-
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant
-// expression inside the body (register arrays indexed by it never need memory).
-template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(static_cast<F &&>(f), std::make_integer_sequence<int, N>{});
-}
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMaskLog2 = -100.0f * kLog2e; // the additive -100 of the shift mask, in base-2 units
@@ -150,12 +136,6 @@ template <int Q0> __device__ __forceinline__ float qgroup_bcast(float v)
     return __uint_as_float(r[Q0 & 1]);
 }
 
-__device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b)
-{
-    return pack_bf16x2(bf16_lo(a) + bf16_lo(b), bf16_hi(a) + bf16_hi(b));
-}
-__device__ __forceinline__ uint4 cat(uint2 lo, uint2 hi) { return make_uint4(lo.x, lo.y, hi.x, hi.y); }
-
 template <class Cf>
 __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *__restrict__ x,
                                                           const uint8_t *__restrict__ pack,
@@ -197,9 +177,7 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
 #pragma unroll
         for (int k = 0; k < FPW; ++k) {
             const int f = k * W::NWAVES + wv;
-            if (f < W::FR_UNIT)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (size_t)f * 1024),
-                                                 (__attribute__((address_space(3))) void *)(dst + (size_t)f * 1024), 16, 0, 0);
+            if (f < W::FR_UNIT) lds_dma16(src + (size_t)f * 1024, dst + (size_t)f * 1024);
         }
     };
 
