@@ -77,12 +77,17 @@ template <int C_, int HEADS_, int G_> struct FusedCfg {
     static constexpr size_t P_TBW = P_WPW + (size_t)N_WPW * 1024;
     // Wide layers, backward with one wavefront per window (wide_bwd.hip) additionally reads
     //   WQX  Wqkv^T for dF = d(q|k|v) Wqkv, K=32: one step = the 32 k-slots of one (head, q|k|v) in
-    //        head-padded order; (hd, t, ct), row l16 -> input channel 16 ct + l16 of the group;
+    //        head-padded order; (hd, t, ct), ct = (input head hl', half et') of the group: row l16 ->
+    //        input channel hl' D + 16 et' + l16 (so that dF comes out in the tiles dO is held in);
     //        query rows carry 1/sqrt(d) like WQ
-    static constexpr int CTF = (CG + 15) / 16;                    // 16-row tiles of a group's input channels
+    static constexpr int CTF = HG * ET;                           // 16-row tiles of a group's input channels, per head
     static constexpr int N_WQX = SPLIT ? HEADS * 3 * CTF : 0;
     static constexpr size_t P_WQX = P_TBW + (SPLIT ? (size_t)HEADS * TBW_PITCH * 4 : 0);
-    static constexpr size_t P_END = P_WQX + (size_t)N_WQX * 1024;
+    //   WQN  Wqkv on the group's channels in their own order, K=32 (the layout of WQ), query rows times
+    //        log2(e)/sqrt(d) as in WQW: the backward recomputes q, k, v from 16-byte row pieces
+    static constexpr int N_WQN = SPLIT ? N_WQ : 0;
+    static constexpr size_t P_WQN = P_WQX + (size_t)N_WQX * 1024;
+    static constexpr size_t P_END = P_WQN + (size_t)N_WQN * 1024;
 };
 
 // True when a fused forward instantiation exists for this geometry (bf16 only).

@@ -32,7 +32,7 @@ template <class Cf> struct WideBwdCfg {
     static constexpr int NWAVES = 4, NTHREADS = 64 * NWAVES;
     static constexpr int NTBL = 15 * 15;
     // stream units: the Wproj^T fragments of the group's heads in two halves, then per head its QKV fragments
-    static constexpr int FR_UNIT = 3 * Cf::ET * Cf::KSX;
+    static constexpr int FR_UNIT = 3 * Cf::ET * Cf::KS;
     static constexpr size_t UNIT_BYTES = (size_t)FR_UNIT * 1024;
     static constexpr int NAU = 2;
     static constexpr int NU = NAU + Cf::HG;
@@ -40,12 +40,21 @@ template <class Cf> struct WideBwdCfg {
     static_assert(Cf::HG * Cf::ET * Cf::KSC == NAU * FR_UNIT && FR_UNIT % Cf::KSC == 0, "dO units");
     static constexpr int FPW = (FR_UNIT + NWAVES - 1) / NWAVES;    // fragments a wave moves per unit
     static constexpr size_t OFF_BIAS = 0;                          // fp32 b_qkv [3C] (b_proj [C] behind it)
-    static constexpr size_t OFF_TBL = (size_t)16 * Cf::C;          // fp32 [HEADS][TBW_PITCH], base-2 units
-    static constexpr size_t OFF_FOLD = OFF_TBL + (size_t)Cf::HEADS * Cf::TBW_PITCH * 4; // per wave 28 x 64 fp32
+    static constexpr size_t OFF_TBL = (size_t)16 * Cf::C;          // fp32 [HG][TBW_PITCH], base-2 units: the group's heads
+    static constexpr size_t OFF_FOLD = OFF_TBL + (size_t)Cf::HG * Cf::TBW_PITCH * 4; // per wave 28 x 64 fp32
     static constexpr size_t FOLD_BYTES = (size_t)28 * 64 * 4;
     static constexpr size_t OFF_W = OFF_FOLD + NWAVES * FOLD_BYTES;
-    static constexpr size_t LDS_BYTES = OFF_W + 2 * UNIT_BYTES;
-    static_assert(OFF_W % 1024 == 0 || OFF_W % 16 == 0, "fragment alignment");
+    // per wave: the dy rows of its window as they lie in memory (64 tokens x C channels, image row after
+    // image row), fetched ahead by direct-to-LDS loads; a few bytes of slack behind the last row, where the
+    // operand reads of the zero-padded last K step reach
+    static constexpr int DY_CHUNKS = 64 * 2 * Cf::C / 16;          // 16-byte pieces of a window
+    static constexpr int DY_ROW_CHUNKS = 8 * 2 * Cf::C / 16;       // of one image row of the window (8 tokens)
+    static constexpr int DY_INSTR = (DY_CHUNKS + 63) / 64;
+    static constexpr size_t STAGE_BYTES = (size_t)DY_CHUNKS * 16 + 64;
+    static constexpr size_t OFF_STAGE = OFF_W + 2 * UNIT_BYTES;
+    static constexpr size_t LDS_BYTES = OFF_STAGE + NWAVES * STAGE_BYTES;
+    static_assert(OFF_W % 16 == 0 && OFF_STAGE % 16 == 0 && STAGE_BYTES % 16 == 0, "16-byte pieces");
+    static_assert((8 * 2 * Cf::C) % 16 == 0, "an image row of a window is whole 16-byte pieces");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(Cf::ET == 2 && Cf::D + 1 <= 32 && Cf::CG % Cf::D == 0, "heads of 17..31 channels");
     // d(q|k|v) in scratch: fragment ((window * 4 + token tile) * HG + head of the group) * 3 + (q|k|v)
@@ -77,12 +86,12 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                                                                const bf16_t *__restrict__ dy,
                                                                const bf16_t *__restrict__ attn,
                                                                const uint8_t *__restrict__ pack,
-                                                               const bf16_t *dx, uint8_t *__restrict__ dqkv,
-                                                               float *__restrict__ tpart)
+                                                               const uint8_t *__restrict__ cgf,
+                                                               uint8_t *__restrict__ dqkv, float *__restrict__ tpart)
 {
     using W = WideBwdCfg<Cf>;
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
-    constexpr int KSX = Cf::KSX, KSC = Cf::KSC, TP = Cf::TBW_PITCH, NU = W::NU, NTBL = W::NTBL;
+    constexpr int KS = Cf::KS, KSC = Cf::KSC, TP = Cf::TBW_PITCH, NU = W::NU, NTBL = W::NTBL;
     constexpr int M = 8;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -93,16 +102,13 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     const int cn = l16 & 7, rsub = l16 >> 3;
     const int per_img = g.nwi * g.nwj;
     const uint32_t tbytes = (uint32_t)g.T * (2u * C);
-    const buf_t xbuf = make_buf(x, tbytes), dybuf = make_buf(dy, tbytes), abuf = make_buf(attn, tbytes),
-                dxbuf = make_buf(dx, tbytes);
-    const uint32_t m_hx = (16 + 4 * q < D) ? 0xffffffffu : 0u, m_hy = (16 + 4 * q + 2 < D) ? 0xffffffffu : 0u;
-    const uint32_t c8 = 8u * q;
+    const buf_t xbuf = make_buf(x, tbytes), abuf = make_buf(attn, tbytes);
     const bool casc_in = GI > 0 && g.cascade, casc_out = GI < G - 1 && g.cascade;
 
     // ---- weight stream (see wide_fwd.hip): loads that write LDS directly, one fragment per instruction ----
     auto stream_unit = [&](int u, int slot) {
         const size_t from = u < W::NAU ? Cf::P_WPT + ((size_t)GI * HG * Cf::ET * KSC + (size_t)u * W::FR_UNIT) * 1024
-                                       : Cf::P_WQW + ((size_t)GI * HG + (u - W::NAU)) * W::UNIT_BYTES;
+                                       : Cf::P_WQN + ((size_t)GI * HG + (u - W::NAU)) * W::UNIT_BYTES;
         const uint8_t *src = pack + from + 16 * lane;
         uint8_t *dst = lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES;
 #pragma unroll
@@ -132,63 +138,83 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         }
     };
 
-    // rows of a window as operands: dy in channel order (K = 32 steps over all C channels); F = x slice
-    // (+ previous group's output, Eq. 8) in head-padded order
-    uint4 xh[KSX][4], dyf[KSC][4];
-    auto load_dy = [&]() {
+    // dy rows of a window -> this wave's staging buffer, in memory order: 8 image rows of 8 tokens, each one
+    // contiguous run of 16 C bytes (two runs in the last window column of a shifted layer, split at token
+    // M - s: a whole number of 16-byte pieces because s is even).  Piece 64 k + lane is moved by instruction k.
+    uint8_t *stage = lds + W::OFF_STAGE + (size_t)wv * W::STAGE_BYTES;
+    auto fetch_dy = [&](int win_) {
+        const int b = win_ / per_img;
+        const int wr = win_ - b * per_img;
+        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
+        const bool wrap = s > 0 && wj == g.nwj - 1;
+        const uint32_t col_a = (uint32_t)(wj * M + s) * (2u * C);              // first run: from this column
+        const uint32_t split = wrap ? (uint32_t)(M - s) * (2u * C) : 0xffffffffu; // second run (from column 0) starts here
+        const int si0 = wi * M + s;
+        int cc = lane, r = 0; // piece within the image row, image row
 #pragma unroll
-        for (int ks = 0; ks < KSC; ++ks)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                uint4 v = bload128(dybuf, tok[t] + 64u * ks + 16u * q, 0u);
-                const int c0 = 32 * ks + 8 * q; // first channel of this lane's slots
-                if (32 * ks + 32 > C) {
-                    v.x = c0 < C ? v.x : 0u;
-                    v.y = c0 + 2 < C ? v.y : 0u;
-                    v.z = c0 + 4 < C ? v.z : 0u;
-                    v.w = c0 + 6 < C ? v.w : 0u;
-                }
-                dyf[ks][t] = v;
+        for (int k = 0; k < W::DY_INSTR; ++k) {
+            if (cc >= W::DY_ROW_CHUNKS) {
+                cc -= W::DY_ROW_CHUNKS;
+                ++r;
             }
+            if (64 * k + lane < W::DY_CHUNKS) {
+                int si = si0 + r;
+                if (si >= g.H) si -= g.H;
+                const uint32_t br = 16u * cc;
+                const uint32_t off = (uint32_t)((b * g.H + si) * g.W) * (2u * C) + (br < split ? col_a + br : br - split);
+                lds_dma16(reinterpret_cast<const uint8_t *>(dy) + off, stage + k * 1024);
+            }
+            cc += 64;
+        }
     };
+    // F = x slice (+ previous group's output, Eq. 8) as operands, channels in their own order: K = 32 steps,
+    // lane group q holds channels 32 ks + 8 q .. + 7 (one 16-byte piece of the row)
+    uint4 xh[KS][4];
+    uint4 ah[KS][4]; // the previous group's output, added when the loads have landed
     auto load_x = [&]() {
 #pragma unroll
-        for (int ks = 0; ks < KSX; ++ks)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const uint32_t off = tok[t] + c8 + 2u * (GI * CG + ks * D);
-                const uint2 lo = bload64(xbuf, off, 0u);
-                uint2 hi = bload64(xbuf, off + 32u, 0u);
-                hi.x &= m_hx;
-                hi.y &= m_hy;
-                xh[ks][t] = cat(lo, hi);
+                xh[ks][t] = bload128(xbuf, tok[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
+                if (casc_in) ah[ks][t] = bload128(abuf, tok[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
             }
-        if (casc_in) {
+    };
+    auto add_cascade = [&]() { // and the channels past the group's width, which belong to the next slice, cleared
 #pragma unroll
-            for (int ks = 0; ks < KSX; ++ks)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const uint32_t off = tok[t] + c8 + 2u * ((GI > 0 ? GI - 1 : 0) * CG + ks * D);
-                    const uint2 lo = bload64(abuf, off, 0u);
-                    const uint2 hi = bload64(abuf, off + 32u, 0u);
-                    uint4 &xv = xh[ks][t];
-                    xv.x = add_bf16x2(xv.x, lo.x);
-                    xv.y = add_bf16x2(xv.y, lo.y);
-                    xv.z = add_bf16x2(xv.z, hi.x & m_hx);
-                    xv.w = add_bf16x2(xv.w, hi.y & m_hy);
+            for (int t = 0; t < 4; ++t) {
+                uint4 v = xh[ks][t];
+                if (casc_in) {
+                    const uint4 a = ah[ks][t];
+                    v.x = add_bf16x2(v.x, a.x);
+                    v.y = add_bf16x2(v.y, a.y);
+                    v.z = add_bf16x2(v.z, a.z);
+                    v.w = add_bf16x2(v.w, a.w);
                 }
-        }
+                const int c0 = 32 * ks + 8 * q;
+                if (32 * ks + 32 > CG) {
+                    v.x = c0 < CG ? v.x : 0u;
+                    v.y = c0 + 2 < CG ? v.y : 0u;
+                    v.z = c0 + 4 < CG ? v.z : 0u;
+                    v.w = c0 + 6 < CG ? v.w : 0u;
+                }
+                xh[ks][t] = v;
+            }
     };
 
     int win = wv * (int)gridDim.x + (int)blockIdx.x;
     bool active = win < g.nW;
 
-    // set-up: linear biases, bias table, first unit
+    // set-up: dy of the first window, first unit, linear biases, the bias table of the group's heads
+    if (active) fetch_dy(win);
     stream_unit(0, 0);
     for (int i = tid; i < C; i += W::NTHREADS)
         reinterpret_cast<uint4 *>(lds + W::OFF_BIAS)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_BIAS)[i];
-    for (int i = tid; i < HEADS * TP / 4; i += W::NTHREADS)
-        reinterpret_cast<uint4 *>(lds + W::OFF_TBL)[i] = reinterpret_cast<const uint4 *>(pack + Cf::P_TBW)[i];
+    for (int i = tid; i < HG * TP / 4; i += W::NTHREADS)
+        reinterpret_cast<uint4 *>(lds + W::OFF_TBL)[i] =
+            reinterpret_cast<const uint4 *>(pack + Cf::P_TBW + (size_t)GI * HG * TP * 4)[i];
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -229,7 +255,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         const bool more = round + 1 < rounds;
         if (active) {
             window_tokens(win);
-            load_dy();
+            load_x(); // lands under the dO products
         }
         uint2 dOb[HG][2][4]; // dO^T of the group's heads, packed T-form tiles
 
@@ -238,6 +264,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         const float *bqkv = reinterpret_cast<const float *>(lds + lds0 + W::OFF_BIAS);
         const float *tbl = reinterpret_cast<const float *>(lds + lds0 + W::OFF_TBL);
         uint8_t *dq_win = dqkv + (size_t)win * 4 * W::FR_TILE * 1024 + 16 * lane;
+        const uint8_t *cg_win = cgf + (size_t)win * 4 * HG * 1024 + 16 * lane;
 
         static_for<NU>([&](auto u_) {
             constexpr int u = decltype(u_)::value;
@@ -258,39 +285,62 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             uint2 v = make_uint2(0u, 0u);
-                            if (casc_out) {
-                                v = bload64(dxbuf, tok[t] + c8 + 2u * ((GI < G - 1 ? GI + 1 : 0) * CG + hl * D) + 32u * et, 0u);
-                                if (et == 1) {
-                                    v.x &= m_hx;
-                                    v.y &= m_hy;
-                                }
-                            }
+                            if (casc_out) // the next group's dF in the layout of this accumulator (its second kernel left it)
+                                v = *reinterpret_cast<const uint2 *>(cg_win + (size_t)(t * HG + hl) * 1024 + 8 * et);
                             cg[i][t] = v;
                         }
                     }
-                    if (u == W::NAU - 1) load_x(); // in flight under this unit's products
+                    // one K step of dy (read from the staging buffer as operands, channels 32 ks + 8 q ..) serves
+                    // every tile of the unit
+                    f32x4 acc[W::TILES_AU][4];
+#pragma unroll
+                    for (int i = 0; i < W::TILES_AU; ++i)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) acc[i][t] = zero4;
+                    const uint8_t *dyrow = stage + lds0 + (size_t)(rsub * M + cn) * (2 * C) + 16 * q;
+#pragma unroll
+                    for (int ks = 0; ks < KSC; ++ks) {
+                        uint4 dyf[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const uint8_t *p = dyrow + (size_t)t * (2 * M * 2 * C) + 64 * ks;
+                            const uint2 lo = *reinterpret_cast<const uint2 *>(p);
+                            const uint2 hi = *reinterpret_cast<const uint2 *>(p + 8);
+                            uint4 v = cat(lo, hi);
+                            const int c0 = 32 * ks + 8 * q; // first channel of this lane's slots
+                            if (32 * ks + 32 > C) {
+                                v.x = c0 < C ? v.x : 0u;
+                                v.y = c0 + 2 < C ? v.y : 0u;
+                                v.z = c0 + 4 < C ? v.z : 0u;
+                                v.w = c0 + 6 < C ? v.w : 0u;
+                            }
+                            dyf[t] = v;
+                        }
+#pragma unroll
+                        for (int i = 0; i < W::TILES_AU; ++i) {
+                            const uint4 wf = wu[(i * KSC + ks) * 64 + lane];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) acc[i][t] = mma32(wf, dyf[t], acc[i][t]);
+                        }
+                    }
 #pragma unroll
                     for (int i = 0; i < W::TILES_AU; ++i) {
                         const int ti = u * W::TILES_AU + i, hl = ti / 2, et = ti % 2;
-                        f32x4 acc[4];
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) acc[t] = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < KSC; ++ks) {
-                            const uint4 wf = wu[(i * KSC + ks) * 64 + lane];
-#pragma unroll
-                            for (int t = 0; t < 4; ++t) acc[t] = mma32(wf, dyf[ks][t], acc[t]);
-                        }
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const uint2 c = cg[i][t];
-                            acc[t] += f32x4{bf16_lo(c.x), bf16_hi(c.x), bf16_lo(c.y), bf16_hi(c.y)};
-                            dOb[hl][et][t] = pack_bf16x4(acc[t]);
+                            acc[i][t] += f32x4{bf16_lo(c.x), bf16_hi(c.x), bf16_lo(c.y), bf16_hi(c.y)};
+                            dOb[hl][et][t] = pack_bf16x4(acc[i][t]);
                         }
                     }
                 }
             } else {
-                constexpr int hl = u - W::NAU, hd = GI * HG + hl;
+                constexpr int hl = u - W::NAU;
+                if (hl == 0) {
+                    // the staging buffer is free (the dO units are done): dy of this wave's next window
+                    if (more && win + stride < g.nW) fetch_dy(win + stride);
+                    if (active) add_cascade();
+                }
                 if (active) {
                     // ---- Q^T, K^T, V^T exactly as the forward computes them (rows = head features) ----
                     uint2 Qb[2][4], Kb[2][4], Vb[2][4];
@@ -310,9 +360,9 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                             for (int t = 0; t < 4; ++t) acc[et][t] = b4;
                         }
 #pragma unroll
-                        for (int ks = 0; ks < KSX; ++ks) {
-                            const uint4 f0 = wu[((t3 * 2 + 0) * KSX + ks) * 64 + lane];
-                            const uint4 f1 = wu[((t3 * 2 + 1) * KSX + ks) * 64 + lane];
+                        for (int ks = 0; ks < KS; ++ks) {
+                            const uint4 f0 = wu[((t3 * 2 + 0) * KS + ks) * 64 + lane];
+                            const uint4 f1 = wu[((t3 * 2 + 1) * KS + ks) * 64 + lane];
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
                                 acc[0][t] = mma32(f0, xh[ks][t], acc[0][t]);
@@ -368,7 +418,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                             for (int kt = 0; kt < 4; ++kt) {
                                 f32x4 bt;
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) bt[j] = tbl[hd * TP + tb0 + 30 * (nt - kt) - j];
+                                for (int j = 0; j < 4; ++j) bt[j] = tbl[hl * TP + tb0 + 30 * (nt - kt) - j];
                                 st[kt] = mma32(cat(Kb[0][kt], Kb[1][kt]), qop, bt);
                                 dp[kt] = mma32(cat(Vb[0][kt], Vb[1][kt]), oop, zero4);
                             }
@@ -517,10 +567,12 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
                                                                const bf16_t *__restrict__ attn,
                                                                const uint8_t *__restrict__ pack,
                                                                const uint8_t *__restrict__ dqkv,
-                                                               bf16_t *__restrict__ dx, float *__restrict__ part)
+                                                               bf16_t *__restrict__ dx, uint8_t *__restrict__ cgf,
+                                                               float *__restrict__ part)
 {
     using W = WideBwdCfg<Cf>;
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG;
+    static_assert(Cf::ET == 2, "two tiles per head");
     constexpr int KS = W::KS, CT = W::CT, CTF = W::CTF, FT = W::FT, RW = W::RW, LW = W::LW;
     constexpr int M = 8;
 
@@ -613,13 +665,20 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
             for (int i = 0; i < HG * 3; ++i)
 #pragma unroll
                 for (int ct = 0; ct < CTF; ++ct) df[ct] = mma32(wqx[(i * CTF + ct) * 64 + lane], dq[i], df[ct]);
+            // tile ct = (input head hl', half et'): rows = channels hl' D + 16 et' + 4q ..
 #pragma unroll
             for (int ct = 0; ct < CTF; ++ct) {
-                const int c0 = 16 * ct + 4 * q;
+                const int cl = 16 * (ct % 2) + 4 * q;
                 const uint2 v = pack_bf16x4(df[ct]);
-                const uint32_t off = tok + 2u * (GI * CG + c0);
-                if (c0 + 2 < CG) bstore64(dxbuf, off, 0u, v);
-                else if (c0 < CG) bstore32(dxbuf, off, 0u, v.x);
+                const uint32_t off = tok + 2u * (GI * CG + (ct / 2) * D + cl);
+                if (cl + 2 < D) bstore64(dxbuf, off, 0u, v);
+                else if (cl < D) bstore32(dxbuf, off, 0u, v.x);
+            }
+            // the same tiles as the previous group's first kernel adds them to its dO (Eq. 8)
+            if (casc_in) {
+                uint4 *cdst = reinterpret_cast<uint4 *>(cgf + ((size_t)win * 4 + wv) * HG * 1024) + lane;
+#pragma unroll
+                for (int hl = 0; hl < HG; ++hl) cdst[hl * 64] = cat(pack_bf16x4(df[2 * hl]), pack_bf16x4(df[2 * hl + 1]));
             }
         }
         __syncthreads();
@@ -680,7 +739,8 @@ int attn_grid(const Geom &g, int cus)
     return cus > g.nW ? g.nW : cus;
 }
 
-// scratch: [ d(q|k|v) of one group | d w_qkv partials of one group | table partials ]; the projection's weight
+// scratch: [ d(q|k|v) of one group | d w_qkv partials of one group | table partials | a group's dF as the
+// previous group's dO tiles ]; the projection's weight
 // gradient, which runs after this pass, puts its partial vectors over the same memory
 template <class Cf> struct WideBwdWs {
     using W = WideBwdCfg<Cf>;
@@ -691,13 +751,14 @@ template <class Cf> struct WideBwdWs {
     {
         return up((size_t)attn_grid(g, kSizingCus) * W::NWAVES * Cf::HEADS * W::NTBL * 4);
     }
+    static size_t cg_bytes(const Geom &g) { return up((size_t)g.nW * 4 * Cf::HG * 1024); }
     static size_t wproj_bytes(const Geom &g) { return up((size_t)attn_grid(g, kSizingCus) * (Cf::C * Cf::C + Cf::C) * 4); }
 };
 
 template <class Cf, int GI>
 hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const uint8_t *pack,
                      bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv, float *part, float *tpart,
-                     hipStream_t s)
+                     uint8_t *cgf, hipStream_t s)
 {
     using W = WideBwdCfg<Cf>;
     {
@@ -710,7 +771,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
             attr_done = true;
         }
         KernelTimer kt(K_WIDE_ATTN_BWD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, dy, attn, pack, dx, dqkv, tpart);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, dy, attn, pack, cgf, dqkv, tpart);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -724,7 +785,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
             attr_done = true;
         }
         KernelTimer kt(K_WIDE_WGRAD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), W::G_LDS_BYTES, s, g, x, attn, pack, dqkv, dx, part);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), W::G_LDS_BYTES, s, g, x, attn, pack, dqkv, dx, cgf, part);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -739,12 +800,12 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
 template <class Cf, int GI>
 hipError_t run_groups(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                       const uint8_t *pack, bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv,
-                      float *part, float *tpart, hipStream_t s)
+                      float *part, float *tpart, uint8_t *cgf, hipStream_t s)
 {
-    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, s);
+    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, s);
     if (e != hipSuccess) return e;
     if constexpr (GI > 0)
-        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, s);
+        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, s);
     return hipSuccess;
 }
 
@@ -758,9 +819,10 @@ hipError_t run_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const 
     uint8_t *dqkv = base;
     float *part = reinterpret_cast<float *>(base + Ws::dqkv_bytes(g));
     float *tpart = reinterpret_cast<float *>(base + Ws::dqkv_bytes(g) + Ws::part_bytes(g));
+    uint8_t *cgf = base + Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g);
     const int grid = attn_grid(g, device_cu_count());
     hipError_t e = run_groups<Cf, Cf::G - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part,
-                                             tpart, s);
+                                             tpart, cgf, s);
     if (e != hipSuccess) return e;
     ReduceOut out{};
     out.ptr[0] = dtable; out.begin[0] = 0;
@@ -777,6 +839,7 @@ hipError_t run_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const 
 bool wide_bwd_supported(const Geom &g)
 {
     if (!wide_fwd_supported(g)) return false; // (8x8 windows, q and k of the head's width; the forward fills the fragments)
+    if (g.shift % 2 != 0) return false;        // (the runs of a window's rows are fetched in 16-byte pieces)
     // 32-bit byte offsets into d(q|k|v)
     if ((size_t)g.nW * 4 * 9 * 1024 >= (size_t(1) << 32)) return false;
 #define X(C_, H_, G_) \
@@ -791,7 +854,7 @@ size_t wide_bwd_ws_bytes(const Geom &g)
 #define X(C_, H_, G_)                                                                       \
     if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                     \
         using Ws = WideBwdWs<FusedCfg<C_, H_, G_>>;                                         \
-        const size_t own = Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g);          \
+        const size_t own = Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g) + Ws::cg_bytes(g); \
         return own > Ws::wproj_bytes(g) ? own : Ws::wproj_bytes(g);                         \
     }
     GSWA_WIDE_BWD_SHAPES(X)

@@ -83,22 +83,42 @@ __global__ __launch_bounds__(256) void wide_pack_kernel(const bf16_t *__restrict
         return;
     }
     i -= E_TBW;
-    if (i < E_WQX) { // Wqkv^T for the backward: row l16 -> input channel of the group, k-slots -> features of (hd, t)
+    if (i < E_WQX) { // Wqkv^T for the backward: row l16 -> input channel (per head of the group), k-slots -> features of (hd, t)
         int f = i >> 6;
         const int ct = f % Cf::CTF; f /= Cf::CTF;
         const int t = f % 3;
         const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int c = 16 * ct + (i & 15);
+        const int cl = 16 * (ct % ET) + (i & 15), c = (ct / ET) * D + cl; // channel inside its head, inside the group
         const int qq = (i >> 4) & 3;
         const float sc = t == 0 ? 1.0f / sqrtf((float)D) : 1.0f;
         uint32_t v[8];
         for (int s = 0; s < 8; ++s) {
             const int fe = s < 4 ? 4 * qq + s : 16 + 4 * qq + (s - 4);
             float w = 0.f;
-            if (c < CG && fe < D) w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + fe) * CG + c]) * sc;
+            if (cl < D && fe < D) w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + fe) * CG + c]) * sc;
             v[s] = f32_to_bf16_bits(w);
         }
         reinterpret_cast<uint4 *>(pack + Cf::P_WQX)[i] =
+            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+        return;
+    }
+    i -= E_WQX;
+    if (i < Cf::N_WQN * 64) { // (hd, t, et, ks): row l16 -> feature 16 et + l16, k-slots -> channels 32 ks + 8 q ..
+        int f = i >> 6;
+        const int ks = f % Cf::KS; f /= Cf::KS;
+        const int et = f % ET; f /= ET;
+        const int t = f % 3;
+        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
+        const int e = 16 * et + (i & 15);
+        const int c0 = 32 * ks + 8 * ((i >> 4) & 3);
+        uint32_t v[8];
+        for (int s = 0; s < 8; ++s) {
+            float w = 0.f;
+            if (e < D && c0 + s < CG)
+                w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c0 + s]) * (t == 0 ? qscale : 1.0f);
+            v[s] = f32_to_bf16_bits(w);
+        }
+        reinterpret_cast<uint4 *>(pack + Cf::P_WQN)[i] =
             make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
     }
 }
@@ -504,7 +524,7 @@ hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_
 #define X(C_, H_, G_)                                                                                    \
     if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                                  \
         using Cf = FusedCfg<C_, H_, G_>;                                                                 \
-        constexpr int entries = (Cf::N_WQW + Cf::N_WPW + Cf::N_WQX) * 64 + Cf::HEADS * Cf::TBW_PITCH;                \
+        constexpr int entries = (Cf::N_WQW + Cf::N_WPW + Cf::N_WQX + Cf::N_WQN) * 64 + Cf::HEADS * Cf::TBW_PITCH;                \
         KernelTimer kt(K_PACK_FWD, s);                                                                   \
         hipLaunchKernelGGL(wide_pack_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, w_proj, \
                            table, static_cast<uint8_t *>(pack));                                        \
