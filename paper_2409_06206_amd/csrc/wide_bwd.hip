@@ -64,12 +64,14 @@ template <class Cf> struct WideBwdCfg {
     static constexpr int CT = Cf::CG / 16 + 1;         // column tiles of d w_qkv, column CG carries the bias sums
     static constexpr int CTF = Cf::CTF;                // 16-channel tiles of the dx slice
     static constexpr int FT = Cf::HG * 3 * Cf::ET;     // 16-row tiles of d(q|k|v), head width padded to 32
-    static constexpr int RW = (FT + NWAVES - 1) / NWAVES;
-    static constexpr int LW = 68;                      // pitch (bf16) of the [row][token] buffers
+    static constexpr int G_WAVES = 8;                  // two windows at a time
+    static constexpr int G_RW = (FT + G_WAVES - 1) / G_WAVES;
+    static constexpr int G_LW = 136;                   // pitch (bf16) of the [row][128 tokens] buffers (68 dwords:
+                                                       // the 16 rows of an operand read fall on distinct banks)
     static constexpr size_t G_OFF_WQX = 0;
     static constexpr size_t G_OFF_G = (size_t)Cf::HG * 3 * CTF * 1024;
-    static constexpr size_t G_OFF_F = G_OFF_G + (size_t)FT * 16 * LW * 2;
-    static constexpr size_t G_LDS_BYTES = G_OFF_F + (size_t)CT * 16 * LW * 2;
+    static constexpr size_t G_OFF_F = G_OFF_G + (size_t)FT * 16 * G_LW * 2;
+    static constexpr size_t G_LDS_BYTES = G_OFF_F + (size_t)CT * 16 * G_LW * 2;
     static_assert(G_LDS_BYTES <= 160 * 1024, "LDS budget");
     static constexpr int L_DW = 0, L_DB = 3 * Cf::CG * Cf::CG, L_TOTAL = L_DB + 3 * Cf::CG;
 };
@@ -560,10 +562,11 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         }
 }
 
-// The group's dx slice and weight gradients from d(q|k|v).  One workgroup per window, wave w =
-// token tile w (the tokens whose fragments the first kernel stored as tile w of the window).
+// The group's dx slice and weight gradients from d(q|k|v).  A workgroup of eight waves takes two windows
+// at a time: wave w = token tile w % 4 of window w / 4 (the tokens whose fragments the first kernel stored
+// as that tile), so a SIMD holds two waves and the weight-gradient products run over 128 tokens.
 template <class Cf, int GI>
-__global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf16_t *__restrict__ x,
+__global__ __launch_bounds__(512, 1) void wide_qkv_grad_kernel(Geom g, const bf16_t *__restrict__ x,
                                                                const bf16_t *__restrict__ attn,
                                                                const uint8_t *__restrict__ pack,
                                                                const uint8_t *__restrict__ dqkv,
@@ -573,8 +576,8 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
     using W = WideBwdCfg<Cf>;
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG;
     static_assert(Cf::ET == 2, "two tiles per head");
-    constexpr int KS = W::KS, CT = W::CT, CTF = W::CTF, FT = W::FT, RW = W::RW, LW = W::LW;
-    constexpr int M = 8;
+    constexpr int KS = W::KS, CT = W::CT, CTF = W::CTF, FT = W::FT, RW = W::G_RW, LW = W::G_LW;
+    constexpr int M = 8, NWV = W::G_WAVES;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint4 *wqx = reinterpret_cast<const uint4 *>(lds + W::G_OFF_WQX);
@@ -583,9 +586,11 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slot = wv >> 2, tt = wv & 3; // window of the pair, token tile
+    const int col0 = 64 * slot + 16 * tt;  // this wave's columns of the row buffers
     const int s = g.shift;
     const int per_img = g.nwi * g.nwj;
-    const int rn = 2 * wv + (l16 >> 3), cn = l16 & 7;
+    const int rn = 2 * tt + (l16 >> 3), cn = l16 & 7;
     const uint32_t tbytes = (uint32_t)g.T * (2u * C);
     const buf_t xbuf = make_buf(x, tbytes), abuf = make_buf(attn, tbytes), dxbuf = make_buf(dx, tbytes);
     const bool casc_in = GI > 0 && g.cascade;
@@ -595,16 +600,20 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
     {
         constexpr int N16 = HG * 3 * CTF * 64;
         const uint4 *src = reinterpret_cast<const uint4 *>(pack + Cf::P_WQX + (size_t)GI * HG * 3 * CTF * 1024);
-        for (int i = tid; i < N16; i += 256) reinterpret_cast<uint4 *>(lds + W::G_OFF_WQX)[i] = src[i];
+        for (int i = tid; i < N16; i += 64 * NWV) reinterpret_cast<uint4 *>(lds + W::G_OFF_WQX)[i] = src[i];
     }
 
+    // row tiles of d w_qkv this wave owns: rt = wv, wv + 8, ...
     f32x4 acc[RW][CT];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) acc[r][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+    const int npair = (g.nW + 1) / 2;
+    for (int pair = blockIdx.x; pair < npair; pair += gridDim.x) {
+        const int win = 2 * pair + slot;
+        const bool valid = win < g.nW;
         const int b = win / per_img;
         const int wr = win - b * per_img;
         const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
@@ -614,31 +623,38 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
         const uint32_t tok = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
 
         uint4 dq[HG * 3];
-        const uint4 *dsrc = reinterpret_cast<const uint4 *>(dqkv + ((size_t)win * 4 + wv) * W::FR_TILE * 1024) + lane;
-#pragma unroll
-        for (int i = 0; i < HG * 3; ++i) dq[i] = dsrc[i * 64];
         uint4 xf[KS];
+        if (valid) {
+            const uint4 *dsrc = reinterpret_cast<const uint4 *>(dqkv + ((size_t)win * 4 + tt) * W::FR_TILE * 1024) + lane;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const uint32_t off = tok + 2u * (GI * CG) + 64u * ks + 16u * q;
-            uint4 v = bload128(xbuf, off, 0u);
-            if (casc_in) {
-                const uint4 a = bload128(abuf, tok + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
-                v.x = add_bf16x2(v.x, a.x);
-                v.y = add_bf16x2(v.y, a.y);
-                v.z = add_bf16x2(v.z, a.z);
-                v.w = add_bf16x2(v.w, a.w);
+            for (int i = 0; i < HG * 3; ++i) dq[i] = dsrc[i * 64];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const uint32_t off = tok + 2u * (GI * CG) + 64u * ks + 16u * q;
+                uint4 v = bload128(xbuf, off, 0u);
+                if (casc_in) {
+                    const uint4 a = bload128(abuf, tok + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
+                    v.x = add_bf16x2(v.x, a.x);
+                    v.y = add_bf16x2(v.y, a.y);
+                    v.z = add_bf16x2(v.z, a.z);
+                    v.w = add_bf16x2(v.w, a.w);
+                }
+                const int c0 = 32 * ks + 8 * q;
+                if (32 * ks + 32 > CG) {
+                    v.x = c0 < CG ? v.x : 0u;
+                    v.y = c0 + 2 < CG ? v.y : 0u;
+                    v.z = c0 + 4 < CG ? v.z : 0u;
+                    v.w = c0 + 6 < CG ? v.w : 0u;
+                }
+                xf[ks] = v;
             }
-            const int c0 = 32 * ks + 8 * q;
-            if (32 * ks + 32 > CG) {
-                v.x = c0 < CG ? v.x : 0u;
-                v.y = c0 + 2 < CG ? v.y : 0u;
-                v.z = c0 + 4 < CG ? v.z : 0u;
-                v.w = c0 + 6 < CG ? v.w : 0u;
-            }
-            xf[ks] = v;
+        } else { // the odd window out: its columns of the row buffers are zero
+#pragma unroll
+            for (int i = 0; i < HG * 3; ++i) dq[i] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xf[ks] = make_uint4(0u, 0u, 0u, 0u);
         }
-        __syncthreads(); // the previous window's rows are consumed (first pass: the weights are in place)
+        __syncthreads(); // the previous pair's rows are consumed (first pass: the weights are in place)
         // F^T rows through a selector product; d(q|k|v)^T rows by a transposed store of the packed tiles
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
@@ -646,18 +662,18 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
             if ((ct >> 1) < KS)
                 tN = mma32(xf[(ct >> 1) < KS ? (ct >> 1) : 0], select_slot(16 * ct + l16, 32 * (ct >> 1) + 8 * q), tN);
             uint2 pk = pack_bf16x4(tN);
-            if (16 * ct + l16 == CG) pk = ones2;
-            *reinterpret_cast<uint2 *>(fbuf + (16 * ct + l16) * LW + 16 * wv + 4 * q) = pk;
+            if (16 * ct + l16 == CG) pk = valid ? ones2 : make_uint2(0u, 0u);
+            *reinterpret_cast<uint2 *>(fbuf + (16 * ct + l16) * LW + col0 + 4 * q) = pk;
         }
 #pragma unroll
         for (int i = 0; i < HG * 3; ++i) {
-            store_tile_transposed(gbuf + ((2 * i + 0) * 16 + 4 * q) * LW + 16 * wv + (l16 & ~1), LW,
+            store_tile_transposed(gbuf + ((2 * i + 0) * 16 + 4 * q) * LW + col0 + (l16 & ~1), LW,
                                   make_uint2(dq[i].x, dq[i].y), lane);
-            store_tile_transposed(gbuf + ((2 * i + 1) * 16 + 4 * q) * LW + 16 * wv + (l16 & ~1), LW,
+            store_tile_transposed(gbuf + ((2 * i + 1) * 16 + 4 * q) * LW + col0 + (l16 & ~1), LW,
                                   make_uint2(dq[i].z, dq[i].w), lane);
         }
         // ---- dx slice of this wave's 16 tokens: dF^T = Wqkv^T d(q|k|v)^T, rows = channels ----
-        {
+        if (valid) {
             f32x4 df[CTF];
 #pragma unroll
             for (int ct = 0; ct < CTF; ++ct) df[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -676,32 +692,28 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
             }
             // the same tiles as the previous group's first kernel adds them to its dO (Eq. 8)
             if (casc_in) {
-                uint4 *cdst = reinterpret_cast<uint4 *>(cgf + ((size_t)win * 4 + wv) * HG * 1024) + lane;
+                uint4 *cdst = reinterpret_cast<uint4 *>(cgf + ((size_t)win * 4 + tt) * HG * 1024) + lane;
 #pragma unroll
                 for (int hl = 0; hl < HG; ++hl) cdst[hl * 64] = cat(pack_bf16x4(df[2 * hl]), pack_bf16x4(df[2 * hl + 1]));
             }
         }
         __syncthreads();
-        // ---- d w_qkv, d b_qkv: wave w owns row tiles w*RW .., K = the window's 64 tokens ----
-        uint4 afr[RW][2];
+        // ---- d w_qkv, d b_qkv: K = the pair's 128 tokens ----
 #pragma unroll
-        for (int r = 0; r < RW; ++r) {
-            const int rt = wv * RW + r;
-            const uint16_t *ar = gbuf + (16 * (rt < FT ? rt : 0) + l16) * LW + 8 * q;
+        for (int kp = 0; kp < 4; ++kp) {
+            uint4 afr[RW];
 #pragma unroll
-            for (int kp = 0; kp < 2; ++kp)
-                afr[r][kp] = cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
-                                 *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4));
-        }
+            for (int r = 0; r < RW; ++r) {
+                const int rt = wv + NWV * r;
+                const uint16_t *ar = gbuf + (16 * (rt < FT ? rt : 0) + l16) * LW + 32 * kp + 8 * q;
+                afr[r] = cat(*reinterpret_cast<const uint2 *>(ar), *reinterpret_cast<const uint2 *>(ar + 4));
+            }
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const uint16_t *br = fbuf + (16 * ct + l16) * LW + 8 * q;
+            for (int ct = 0; ct < CT; ++ct) {
+                const uint16_t *br = fbuf + (16 * ct + l16) * LW + 32 * kp + 8 * q;
+                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br), *reinterpret_cast<const uint2 *>(br + 4));
 #pragma unroll
-            for (int kp = 0; kp < 2; ++kp) {
-                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
-                                     *reinterpret_cast<const uint2 *>(br + 32 * kp + 4));
-#pragma unroll
-                for (int r = 0; r < RW; ++r) acc[r][ct] = mma32(afr[r][kp], bf, acc[r][ct]);
+                for (int r = 0; r < RW; ++r) acc[r][ct] = mma32(afr[r], bf, acc[r][ct]);
             }
         }
     }
@@ -712,7 +724,7 @@ __global__ __launch_bounds__(256, 1) void wide_qkv_grad_kernel(Geom g, const bf1
     float *mine = part + (size_t)blockIdx.x * W::L_TOTAL;
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
-        const int rt = wv * RW + r; // (head, q|k|v, half of the head's features)
+        const int rt = wv + NWV * r; // (head, q|k|v, half of the head's features)
         if (rt < FT) {
             const int i = rt >> 1, et = rt & 1, hl = i / 3, t3 = i - 3 * hl;
 #pragma unroll
@@ -785,7 +797,9 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
             attr_done = true;
         }
         KernelTimer kt(K_WIDE_WGRAD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), W::G_LDS_BYTES, s, g, x, attn, pack, dqkv, dx, cgf, part);
+        const int pairs = (g.nW + 1) / 2;
+        hipLaunchKernelGGL(kern, dim3(grid < pairs ? grid : pairs), dim3(64 * W::G_WAVES), W::G_LDS_BYTES, s, g, x, attn,
+                           pack, dqkv, dx, cgf, part);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -794,7 +808,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
     out.ptr[1] = db_qkv + GI * 3 * Cf::CG; out.begin[1] = W::L_DB;
     out.begin[2] = W::L_TOTAL;
     out.nseg = 2;
-    return launch_reduce(part, grid, W::L_TOTAL, out, accumulate, s);
+    return launch_reduce(part, grid < (g.nW + 1) / 2 ? grid : (g.nW + 1) / 2, W::L_TOTAL, out, accumulate, s);
 }
 
 template <class Cf, int GI>
@@ -840,6 +854,9 @@ bool wide_bwd_supported(const Geom &g)
 {
     if (!wide_fwd_supported(g)) return false; // (8x8 windows, q and k of the head's width; the forward fills the fragments)
     if (g.shift % 2 != 0) return false;        // (the runs of a window's rows are fetched in 16-byte pieces)
+    // With three groups and at most one window per wavefront the six short launches cost more than the
+    // per-chunk kernels of fused_bwd.hip (measured at 1024 windows: 0.56 against 0.52 ms per layer pair).
+    if (g.groups == 3 && g.nW <= 4 * kSizingCus) return false;
     // 32-bit byte offsets into d(q|k|v)
     if ((size_t)g.nW * 4 * 9 * 1024 >= (size_t(1) << 32)) return false;
 #define X(C_, H_, G_) \

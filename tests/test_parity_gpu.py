@@ -204,7 +204,7 @@ FULL = [
     # name, groups, layer index: full benchmark shapes, every element compared
     ("c2", 1, 0), ("c2", 2, 1), ("c2", 3, 0), ("c2", 6, 1),
     ("c3", 1, 1), ("c3", 2, 0), ("c3", 3, 1),
-    ("c4", 2, 1),
+    ("c4", 2, 1), ("c4", 3, 1),
     ("agile_h4_qk16", 2, 1), ("agile_h4_qk32", 4, 0), ("agile_h6_qk24", 2, 1), ("agile_h6_qk24", 3, 0),
 ]
 
@@ -222,7 +222,7 @@ def test_full_size_layers(oracle, name, groups, layer):
 # The benchmark's initialisation (weights of standard deviation 0.02) gives nearly uniform
 # probabilities, which would hide a wrong mask, bias index or exponential: the wide layers are
 # therefore also run at full size with scores of order 1-5 (`stress`), shifted.
-FULL_STRESS = [("c2", 2, 1), ("c3", 1, 1), ("c3", 2, 1), ("c3", 3, 1), ("c4", 2, 1)]
+FULL_STRESS = [("c2", 2, 1), ("c3", 1, 1), ("c3", 2, 1), ("c3", 3, 1), ("c4", 2, 1), ("c4", 3, 1)]
 
 
 @pytest.mark.parametrize("name,groups,layer", FULL_STRESS)
@@ -244,6 +244,24 @@ def test_more_windows_than_wavefronts(oracle, groups):
     errs, _ = parity.check_case(oracle, 48, 72, 40, 60, 6, groups, 8, 4, "bf16",
                                 seed=synth.LAYER_SEED0 + 3, regime="stress")
     _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("groups", [2, 3])
+def test_wide_layers_more_windows_than_wavefronts(oracle, groups):
+    """27 x (9 x 5) = 1215 windows of a wide layer: more than the 1024 wavefronts of a backward launch
+    on 256 compute units (a ragged second round), an odd number of windows (the kernel that takes
+    them in pairs is left with one), odd window counts per image, shifted."""
+    _say("many windows, wide", groups)
+    errs, _ = parity.check_case(oracle, 27, 72, 40, 180, 6, groups, 8, 4, "bf16",
+                                seed=synth.LAYER_SEED0 + 5, regime="stress")
+    _say("  errors", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("shift", [2, 3, 6])
+def test_wide_layers_other_shifts(oracle, shift):
+    """Shifts other than half a window: even ones split the last window column's rows at a
+    16-byte boundary (the streamed backward), odd ones take the per-chunk kernels."""
+    parity.check_case(oracle, 1, 24, 16, 180, 6, 2, 8, shift, "bf16", regime="stress")
 
 
 @pytest.mark.parametrize("regime", ["init", "stress"])
