@@ -115,12 +115,13 @@ __device__ __forceinline__ void bstore64(buf_t b, uint32_t voff, uint32_t soff, 
 // the wave-uniform LDS address `dst` + 16 l.  Asynchronous: the data is in LDS once the wave's
 // vector-memory counter has drained (s_waitcnt vmcnt(0)), which the caller does before the barrier
 // that hands the data to its readers; the compiler is not told that LDS changes, so it adds no wait
-// of its own to later LDS reads (they must not touch the destination before that barrier).
+// of its own to later LDS reads (they must not touch the destination before that barrier).  M0 is
+// written here; the compiler reserves it and sets it itself before each of its own uses.
 __device__ __forceinline__ void lds_dma16(const void *src, void *dst)
 {
     const uint32_t ldsaddr =
         __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(ldsaddr), "v"(src) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(ldsaddr), "v"(src) : "memory");
 }
 
 __device__ __forceinline__ uint4 cat(uint2 a, uint2 b) { return make_uint4(a.x, a.y, b.x, b.y); }

@@ -20,6 +20,7 @@
 // Notation (T-form, N-form, head-padded order): fused_bwd.hip, wide_fwd.hip.
 #include "fused.h"
 #include "mfma.h"
+#include "wide_rows.h"
 
 namespace gswa {
 
@@ -47,14 +48,10 @@ template <class Cf> struct WideBwdCfg {
     // per wave: the dy rows of its window as they lie in memory (64 tokens x C channels, image row after
     // image row), fetched ahead by direct-to-LDS loads; a few bytes of slack behind the last row, where the
     // operand reads of the zero-padded last K step reach
-    static constexpr int DY_CHUNKS = 64 * 2 * Cf::C / 16;          // 16-byte pieces of a window
-    static constexpr int DY_ROW_CHUNKS = 8 * 2 * Cf::C / 16;       // of one image row of the window (8 tokens)
-    static constexpr int DY_INSTR = (DY_CHUNKS + 63) / 64;
-    static constexpr size_t STAGE_BYTES = (size_t)DY_CHUNKS * 16 + 64;
+    static constexpr size_t STAGE_BYTES = WindowRows<Cf::C>::BYTES;
     static constexpr size_t OFF_STAGE = OFF_W + 2 * UNIT_BYTES;
     static constexpr size_t LDS_BYTES = OFF_STAGE + NWAVES * STAGE_BYTES;
     static_assert(OFF_W % 16 == 0 && OFF_STAGE % 16 == 0 && STAGE_BYTES % 16 == 0, "16-byte pieces");
-    static_assert((8 * 2 * Cf::C) % 16 == 0, "an image row of a window is whole 16-byte pieces");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(Cf::ET == 2 && Cf::D + 1 <= 32 && Cf::CG % Cf::D == 0, "heads of 17..31 channels");
     // d(q|k|v) in scratch: fragment ((window * 4 + token tile) * HG + head of the group) * 3 + (q|k|v)
@@ -140,35 +137,9 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         }
     };
 
-    // dy rows of a window -> this wave's staging buffer, in memory order: 8 image rows of 8 tokens, each one
-    // contiguous run of 16 C bytes (two runs in the last window column of a shifted layer, split at token
-    // M - s: a whole number of 16-byte pieces because s is even).  Piece 64 k + lane is moved by instruction k.
+    // dy rows of a window -> this wave's staging buffer, in memory order (wide_rows.h)
     uint8_t *stage = lds + W::OFF_STAGE + (size_t)wv * W::STAGE_BYTES;
-    auto fetch_dy = [&](int win_) {
-        const int b = win_ / per_img;
-        const int wr = win_ - b * per_img;
-        const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
-        const bool wrap = s > 0 && wj == g.nwj - 1;
-        const uint32_t col_a = (uint32_t)(wj * M + s) * (2u * C);              // first run: from this column
-        const uint32_t split = wrap ? (uint32_t)(M - s) * (2u * C) : 0xffffffffu; // second run (from column 0) starts here
-        const int si0 = wi * M + s;
-        int cc = lane, r = 0; // piece within the image row, image row
-#pragma unroll
-        for (int k = 0; k < W::DY_INSTR; ++k) {
-            if (cc >= W::DY_ROW_CHUNKS) {
-                cc -= W::DY_ROW_CHUNKS;
-                ++r;
-            }
-            if (64 * k + lane < W::DY_CHUNKS) {
-                int si = si0 + r;
-                if (si >= g.H) si -= g.H;
-                const uint32_t br = 16u * cc;
-                const uint32_t off = (uint32_t)((b * g.H + si) * g.W) * (2u * C) + (br < split ? col_a + br : br - split);
-                lds_dma16(reinterpret_cast<const uint8_t *>(dy) + off, stage + k * 1024);
-            }
-            cc += 64;
-        }
-    };
+    auto fetch_dy = [&](int win_) { fetch_window_rows<C>(g, dy, win_, lane, stage); };
     // F = x slice (+ previous group's output, Eq. 8) as operands, channels in their own order: K = 32 steps,
     // lane group q holds channels 32 ks + 8 q .. + 7 (one 16-byte piece of the row)
     uint4 xh[KS][4];
