@@ -86,7 +86,8 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                                                                const bf16_t *__restrict__ attn,
                                                                const uint8_t *__restrict__ pack,
                                                                const uint8_t *__restrict__ cgf,
-                                                               uint8_t *__restrict__ dqkv, float *__restrict__ tpart)
+                                                               uint8_t *__restrict__ dqkv, uint8_t *__restrict__ ffr,
+                                                               float *__restrict__ tpart)
 {
     using W = WideBwdCfg<Cf>;
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, G = Cf::G;
@@ -312,7 +313,15 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                 if (hl == 0) {
                     // the staging buffer is free (the dO units are done): dy of this wave's next window
                     if (more && win + stride < g.nW) fetch_dy(win + stride);
-                    if (active) add_cascade();
+                    if (active) {
+                        add_cascade();
+                        // F as the second kernel's operand of the weight gradient: the same fragments
+                        uint4 *fdst = reinterpret_cast<uint4 *>(ffr + (size_t)win * 4 * KS * 1024) + lane;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) fdst[(t * KS + ks) * 64] = xh[ks][t];
+                    }
                 }
                 if (active) {
                     // ---- Q^T, K^T, V^T exactly as the forward computes them (rows = head features) ----
@@ -537,8 +546,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
 // at a time: wave w = token tile w % 4 of window w / 4 (the tokens whose fragments the first kernel stored
 // as that tile), so a SIMD holds two waves and the weight-gradient products run over 128 tokens.
 template <class Cf, int GI>
-__global__ __launch_bounds__(512, 1) void wide_qkv_grad_kernel(Geom g, const bf16_t *__restrict__ x,
-                                                               const bf16_t *__restrict__ attn,
+__global__ __launch_bounds__(512, 1) void wide_qkv_grad_kernel(Geom g, const uint8_t *__restrict__ ffr,
                                                                const uint8_t *__restrict__ pack,
                                                                const uint8_t *__restrict__ dqkv,
                                                                bf16_t *__restrict__ dx, uint8_t *__restrict__ cgf,
@@ -563,7 +571,7 @@ __global__ __launch_bounds__(512, 1) void wide_qkv_grad_kernel(Geom g, const bf1
     const int per_img = g.nwi * g.nwj;
     const int rn = 2 * tt + (l16 >> 3), cn = l16 & 7;
     const uint32_t tbytes = (uint32_t)g.T * (2u * C);
-    const buf_t xbuf = make_buf(x, tbytes), abuf = make_buf(attn, tbytes), dxbuf = make_buf(dx, tbytes);
+    const buf_t dxbuf = make_buf(dx, tbytes);
     const bool casc_in = GI > 0 && g.cascade;
     const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
 
@@ -599,26 +607,10 @@ __global__ __launch_bounds__(512, 1) void wide_qkv_grad_kernel(Geom g, const bf1
             const uint4 *dsrc = reinterpret_cast<const uint4 *>(dqkv + ((size_t)win * 4 + tt) * W::FR_TILE * 1024) + lane;
 #pragma unroll
             for (int i = 0; i < HG * 3; ++i) dq[i] = dsrc[i * 64];
+            // F of these tokens as the first kernel used it (x slice + previous group's output, Eq. 8)
+            const uint4 *fsrc = reinterpret_cast<const uint4 *>(ffr + ((size_t)win * 4 + tt) * KS * 1024) + lane;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const uint32_t off = tok + 2u * (GI * CG) + 64u * ks + 16u * q;
-                uint4 v = bload128(xbuf, off, 0u);
-                if (casc_in) {
-                    const uint4 a = bload128(abuf, tok + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
-                    v.x = add_bf16x2(v.x, a.x);
-                    v.y = add_bf16x2(v.y, a.y);
-                    v.z = add_bf16x2(v.z, a.z);
-                    v.w = add_bf16x2(v.w, a.w);
-                }
-                const int c0 = 32 * ks + 8 * q;
-                if (32 * ks + 32 > CG) {
-                    v.x = c0 < CG ? v.x : 0u;
-                    v.y = c0 + 2 < CG ? v.y : 0u;
-                    v.z = c0 + 4 < CG ? v.z : 0u;
-                    v.w = c0 + 6 < CG ? v.w : 0u;
-                }
-                xf[ks] = v;
-            }
+            for (int ks = 0; ks < KS; ++ks) xf[ks] = fsrc[ks * 64];
         } else { // the odd window out: its columns of the row buffers are zero
 #pragma unroll
             for (int i = 0; i < HG * 3; ++i) dq[i] = make_uint4(0u, 0u, 0u, 0u);
@@ -723,7 +715,7 @@ int attn_grid(const Geom &g, int cus)
 }
 
 // scratch: [ d(q|k|v) of one group | d w_qkv partials of one group | table partials | a group's dF as the
-// previous group's dO tiles ]; the projection's weight
+// previous group's dO tiles | a group's input F as operand fragments ]; the projection's weight
 // gradient, which runs after this pass, puts its partial vectors over the same memory
 template <class Cf> struct WideBwdWs {
     using W = WideBwdCfg<Cf>;
@@ -735,13 +727,14 @@ template <class Cf> struct WideBwdWs {
         return up((size_t)attn_grid(g, kSizingCus) * W::NWAVES * Cf::HEADS * W::NTBL * 4);
     }
     static size_t cg_bytes(const Geom &g) { return up((size_t)g.nW * 4 * Cf::HG * 1024); }
+    static size_t f_bytes(const Geom &g) { return up((size_t)g.nW * 4 * W::KS * 1024); }
     static size_t wproj_bytes(const Geom &g) { return up((size_t)attn_grid(g, kSizingCus) * (Cf::C * Cf::C + Cf::C) * 4); }
 };
 
 template <class Cf, int GI>
 hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const uint8_t *pack,
                      bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv, float *part, float *tpart,
-                     uint8_t *cgf, hipStream_t s)
+                     uint8_t *cgf, uint8_t *ffr, hipStream_t s)
 {
     using W = WideBwdCfg<Cf>;
     {
@@ -754,7 +747,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
             attr_done = true;
         }
         KernelTimer kt(K_WIDE_ATTN_BWD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, dy, attn, pack, cgf, dqkv, tpart);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, dy, attn, pack, cgf, dqkv, ffr, tpart);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -769,8 +762,8 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
         }
         KernelTimer kt(K_WIDE_WGRAD, s);
         const int pairs = (g.nW + 1) / 2;
-        hipLaunchKernelGGL(kern, dim3(grid < pairs ? grid : pairs), dim3(64 * W::G_WAVES), W::G_LDS_BYTES, s, g, x, attn,
-                           pack, dqkv, dx, cgf, part);
+        hipLaunchKernelGGL(kern, dim3(grid < pairs ? grid : pairs), dim3(64 * W::G_WAVES), W::G_LDS_BYTES, s, g, ffr, pack,
+                           dqkv, dx, cgf, part);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -785,12 +778,12 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
 template <class Cf, int GI>
 hipError_t run_groups(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                       const uint8_t *pack, bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv,
-                      float *part, float *tpart, uint8_t *cgf, hipStream_t s)
+                      float *part, float *tpart, uint8_t *cgf, uint8_t *ffr, hipStream_t s)
 {
-    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, s);
+    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, ffr, s);
     if (e != hipSuccess) return e;
     if constexpr (GI > 0)
-        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, s);
+        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, ffr, s);
     return hipSuccess;
 }
 
@@ -805,9 +798,10 @@ hipError_t run_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const 
     float *part = reinterpret_cast<float *>(base + Ws::dqkv_bytes(g));
     float *tpart = reinterpret_cast<float *>(base + Ws::dqkv_bytes(g) + Ws::part_bytes(g));
     uint8_t *cgf = base + Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g);
+    uint8_t *ffr = cgf + Ws::cg_bytes(g);
     const int grid = attn_grid(g, device_cu_count());
     hipError_t e = run_groups<Cf, Cf::G - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part,
-                                             tpart, cgf, s);
+                                             tpart, cgf, ffr, s);
     if (e != hipSuccess) return e;
     ReduceOut out{};
     out.ptr[0] = dtable; out.begin[0] = 0;
@@ -842,7 +836,7 @@ size_t wide_bwd_ws_bytes(const Geom &g)
 #define X(C_, H_, G_)                                                                       \
     if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                     \
         using Ws = WideBwdWs<FusedCfg<C_, H_, G_>>;                                         \
-        const size_t own = Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g) + Ws::cg_bytes(g); \
+        const size_t own = Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g) + Ws::cg_bytes(g) + Ws::f_bytes(g); \
         return own > Ws::wproj_bytes(g) ? own : Ws::wproj_bytes(g);                         \
     }
     GSWA_WIDE_BWD_SHAPES(X)
