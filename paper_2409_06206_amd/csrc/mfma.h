@@ -126,6 +126,20 @@ __device__ __forceinline__ void lds_dma16(const void *src, void *dst)
 
 __device__ __forceinline__ uint4 cat(uint2 a, uint2 b) { return make_uint4(a.x, a.y, b.x, b.y); }
 
+// Two packed result tiles that are neighbours along their rows (lane group q of `a` holds rows 4q..4q+3
+// of a 16-row run, of `b` the same rows of the next run) -> lane group q holds rows 8q..8q+7 of the
+// 32-row run [a | b]: 16 contiguous bytes per lane, so that a column leaves in two stores of 32 bytes
+// per lane pair instead of four of 8.  v_permlane32_swap(d, s): d' = {d.lower half, s.lower half},
+// s' = {d.upper, s.upper}; v_permlane16_swap(d, s): d' = rows (d0, s0, d2, s2), s' = rows (d1, s1, d3, s3).
+__device__ __forceinline__ uint4 pair_rows(uint2 a, uint2 b)
+{
+    const u32x2 r0 = __builtin_amdgcn_permlane32_swap(a.x, b.x, false, false);
+    const u32x2 r1 = __builtin_amdgcn_permlane32_swap(a.y, b.y, false, false);
+    const u32x2 s0 = __builtin_amdgcn_permlane16_swap(r0[0], r0[1], false, false);
+    const u32x2 s1 = __builtin_amdgcn_permlane16_swap(r1[0], r1[1], false, false);
+    return make_uint4(s0[0], s1[0], s0[1], s1[1]);
+}
+
 // Transposed store of a packed result tile (this lane: rows 4q..4q+3 of column l16) into
 // row-major LDS rows.  Neighbouring lanes l16, l16^1 swap halves through DPP so that every lane
 // writes whole dwords: even lanes rows 4q and 4q+2, odd lanes rows 4q+1 and 4q+3, each holding

@@ -436,11 +436,16 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
                         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
                             for (int h2 = gi * HG; h2 <= hd; ++h2) {
-                                const uint32_t off = tok[nt] + c8 + 2u * (h2 * D);
-                                const uint4 o = Ob[h2][nt];
-                                bstore64(abuf, off, 0u, make_uint2(o.x, o.y));
-                                if (m_hy) bstore64(abuf, off + 32u, 0u, make_uint2(o.z, o.w));
-                                else if (m_hx) bstore32(abuf, off + 32u, 0u, o.z);
+                                // lane group q: features 8q .. 8q+7 of the head (16 contiguous bytes)
+                                const uint32_t off = tok[nt] + 16u * q + 2u * (h2 * D);
+                                const uint4 o = pair_rows(make_uint2(Ob[h2][nt].x, Ob[h2][nt].y),
+                                                          make_uint2(Ob[h2][nt].z, Ob[h2][nt].w));
+                                if (8 * q + 8 <= D) {
+                                    bstore128(abuf, off, 0u, o);
+                                } else {
+                                    if (8 * q + 4 <= D) bstore64(abuf, off, 0u, make_uint2(o.x, o.y));
+                                    if (8 * q + 6 <= D) bstore32(abuf, off + 8u, 0u, o.z);
+                                }
                             }
                     }
                 }
@@ -449,10 +454,9 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
                 // ---- Y^T = Wproj A^T + b for OT_UNIT output tiles: rows = output channels, column = token ----
                 constexpr int pu = u - W::NHU;
                 if (active) {
-#pragma unroll
-                    for (int oi = 0; oi < OT_UNIT; ++oi) {
-                        const int ot = pu * OT_UNIT + oi;
-                        f32x4 acc[4];
+                    // two output tiles at a time: their packed results are regrouped so that a lane holds 16
+                    // contiguous bytes of its token's row (a tile left over at the end goes out in 8-byte pieces)
+                    auto project = [&](int ot, f32x4(&acc)[4]) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const int o = 16 * ot + 4 * q + j;
@@ -462,10 +466,31 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
                         }
 #pragma unroll
                         for (int hd = 0; hd < HEADS; ++hd) {
-                            const uint4 wf = wu[(oi * HEADS + hd) * 64 + lane];
+                            const uint4 wf = wu[((ot - pu * OT_UNIT) * HEADS + hd) * 64 + lane];
 #pragma unroll
                             for (int t = 0; t < 4; ++t) acc[t] = mma32(wf, Ob[hd][t], acc[t]);
                         }
+                    };
+#pragma unroll
+                    for (int oi = 0; oi + 1 < OT_UNIT; oi += 2) {
+                        const int ot = pu * OT_UNIT + oi;
+                        f32x4 acc0[4], acc1[4];
+                        project(ot, acc0);
+                        project(ot + 1, acc1);
+                        const int o0 = 16 * ot + 8 * q; // first channel of this lane's eight
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const uint4 v = pair_rows(pack_bf16x4(acc0[t]), pack_bf16x4(acc1[t]));
+                            const uint32_t off = tok[t] + 2u * o0;
+                            if (o0 + 8 <= C) bstore128(ybuf, off, 0u, v);
+                            else if (o0 + 4 <= C) bstore64(ybuf, off, 0u, make_uint2(v.x, v.y));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (OT_UNIT % 2 == 1) {
+                        const int ot = pu * OT_UNIT + OT_UNIT - 1;
+                        f32x4 acc[4];
+                        project(ot, acc);
                         const int o0 = 16 * ot + 4 * q;
 #pragma unroll
                         for (int t = 0; t < 4; ++t)
