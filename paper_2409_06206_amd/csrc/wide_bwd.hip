@@ -105,11 +105,15 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     const buf_t xbuf = make_buf(x, tbytes), abuf = make_buf(attn, tbytes);
     const bool casc_in = GI > 0 && g.cascade, casc_out = GI < G - 1 && g.cascade;
 
+    // The lane index as the address arithmetic of a round sees it: opaque, re-made every round, so that
+    // the per-lane addresses of a round's loads are computed where they are used and not kept (and
+    // spilled) across the whole kernel.
+    int lane_r = lane;
     // ---- weight stream (see wide_fwd.hip): loads that write LDS directly, one fragment per instruction ----
     auto stream_unit = [&](int u, int slot) {
         const size_t from = u < W::NAU ? Cf::P_WPT + ((size_t)GI * HG * Cf::ET * KSC + (size_t)u * W::FR_UNIT) * 1024
                                        : Cf::P_WQN + ((size_t)GI * HG + (u - W::NAU)) * W::UNIT_BYTES;
-        const uint8_t *src = pack + from + 16 * lane;
+        const uint8_t *src = pack + from + 16 * lane_r;
         uint8_t *dst = lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES;
 #pragma unroll
         for (int k = 0; k < W::FPW; ++k) {
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
 
     // dy rows of a window -> this wave's staging buffer, in memory order (wide_rows.h)
     uint8_t *stage = lds + W::OFF_STAGE + (size_t)wv * W::STAGE_BYTES;
-    auto fetch_dy = [&](int win_) { fetch_window_rows<C>(g, dy, win_, lane, stage); };
+    auto fetch_dy = [&](int win_) { fetch_window_rows<C>(g, dy, win_, lane_r, stage); };
     // F = x slice (+ previous group's output, Eq. 8) as operands, channels in their own order: K = 32 steps,
     // lane group q holds channels 32 ks + 8 q .. + 7 (one 16-byte piece of the row)
     uint4 xh[KS][4];
@@ -235,10 +239,12 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
 
         uint32_t lds0 = 0;
         asm volatile("" : "+v"(lds0)); // keeps the LDS reads of a round inside the round
+        lane_r = lane;
+        asm volatile("" : "+v"(lane_r));
         const float *bqkv = reinterpret_cast<const float *>(lds + lds0 + W::OFF_BIAS);
         const float *tbl = reinterpret_cast<const float *>(lds + lds0 + W::OFF_TBL);
-        uint8_t *dq_win = dqkv + (size_t)win * 4 * W::FR_TILE * 1024 + 16 * lane;
-        const uint8_t *cg_win = cgf + (size_t)win * 4 * HG * 1024 + 16 * lane;
+        uint8_t *dq_win = dqkv + (size_t)win * 4 * W::FR_TILE * 1024 + 16 * lane_r;
+        const uint8_t *cg_win = cgf + (size_t)win * 4 * HG * 1024 + 16 * lane_r;
 
         static_for<NU>([&](auto u_) {
             constexpr int u = decltype(u_)::value;
@@ -316,7 +322,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                     if (active) {
                         add_cascade();
                         // F as the second kernel's operand of the weight gradient: the same fragments
-                        uint4 *fdst = reinterpret_cast<uint4 *>(ffr + (size_t)win * 4 * KS * 1024) + lane;
+                        uint4 *fdst = reinterpret_cast<uint4 *>(ffr + (size_t)win * 4 * KS * 1024) + lane_r;
 #pragma unroll
                         for (int t = 0; t < 4; ++t)
 #pragma unroll

@@ -185,6 +185,9 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
     // then projection fragments of OT_UNIT output tiles.  A thread stages its 16-byte pieces of the
     // next unit in registers while the current unit is computed with, and writes them to the other
     // LDS buffer afterwards; one barrier per unit. ----
+    // (the lane index as a round's address arithmetic sees it: opaque, re-made every round, so that per-lane
+    // addresses are computed where they are used instead of being kept, and spilled, across the kernel)
+    int lane_r = lane;
     auto unit_src = [&](int u) {
         return pack + (u < W::NHU ? Cf::P_WQW + (size_t)u * W::UNIT_BYTES
                                   : Cf::P_WPW + (size_t)(u - W::NHU) * W::UNIT_BYTES);
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
     // Loads that write LDS directly: one instruction moves one fragment (64 lanes x 16 bytes land at
     // the wave-uniform LDS address + 16 * lane).  Wave w moves fragments w, w + 4, ... of the unit.
     auto stream_unit = [&](int u, int slot) {
-        const uint8_t *src = unit_src(u) + 16 * lane;
+        const uint8_t *src = unit_src(u) + 16 * lane_r;
         uint8_t *dst = lds + W::OFF_W + (size_t)slot * W::UNIT_BYTES;
 #pragma unroll
         for (int k = 0; k < FPW; ++k) {
@@ -280,6 +283,8 @@ __global__ __launch_bounds__(256, 1) void wide_fwd_kernel(Geom g, const bf16_t *
 
         uint32_t lds0 = 0;
         asm volatile("" : "+v"(lds0)); // keeps the LDS reads of a round inside the round
+        lane_r = lane;
+        asm volatile("" : "+v"(lane_r));
         const float *bqkv = reinterpret_cast<const float *>(lds + lds0 + W::OFF_BIAS);
         const float *bproj = bqkv + 3 * C;
         const float *tbl = reinterpret_cast<const float *>(lds + lds0 + W::OFF_TBL);
