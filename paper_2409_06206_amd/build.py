@@ -17,13 +17,22 @@ HIPCC_FLAGS = [
 ]
 
 
+# Kernels that run one wavefront per SIMD (512 registers) keep their matrix-core results in the
+# architectural registers, where the vector ALU reads them, instead of the accumulation registers
+# (one copy instruction per value and use otherwise).
+FILE_FLAGS = {
+    "wide_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "wide_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(_HERE, "csrc", "*.hip")))
 
 
 def _compile(hipcc, src, verbose):
     obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
-    cmd = [hipcc, *HIPCC_FLAGS, "-c", "-o", obj, src]
+    cmd = [hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), "-c", "-o", obj, src]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
