@@ -13,17 +13,12 @@ HIPCC_FLAGS = [
     "-munsafe-fp-atomics",
     # packed fp32 instructions are kept off
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-core results stay in the architectural registers, where the vector ALU reads them, instead
+    # of the accumulation registers (otherwise one copy instruction per value and use in every kernel
+    # that may occupy a SIMD alone)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
-
-
-# Kernels that run one wavefront per SIMD (512 registers) keep their matrix-core results in the
-# architectural registers, where the vector ALU reads them, instead of the accumulation registers
-# (one copy instruction per value and use otherwise).
-FILE_FLAGS = {
-    "wide_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    "wide_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-}
 
 
 def sources():
@@ -32,7 +27,7 @@ def sources():
 
 def _compile(hipcc, src, verbose):
     obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
-    cmd = [hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), "-c", "-o", obj, src]
+    cmd = [hipcc, *HIPCC_FLAGS, "-c", "-o", obj, src]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

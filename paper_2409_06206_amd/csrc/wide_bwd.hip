@@ -825,9 +825,6 @@ bool wide_bwd_supported(const Geom &g)
 {
     if (!wide_fwd_supported(g)) return false; // (8x8 windows, q and k of the head's width; the forward fills the fragments)
     if (g.shift % 2 != 0) return false;        // (the runs of a window's rows are fetched in 16-byte pieces)
-    // With three groups and at most one window per wavefront the six short launches cost more than the
-    // per-chunk kernels of fused_bwd.hip (measured at 1024 windows: 0.56 against 0.52 ms per layer pair).
-    if (g.groups == 3 && g.nW <= 4 * kSizingCus) return false;
     // 32-bit byte offsets into d(q|k|v)
     if ((size_t)g.nW * 4 * 9 * 1024 >= (size_t(1) << 32)) return false;
 #define X(C_, H_, G_) \
