@@ -395,11 +395,12 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                                          transpose_tile(dOb[hl][et][2 * p2 + 1], ident));
                         }
                         uint2 Pq[4][2], dSq[4][2]; // P and dS with rows = queries, column = key
+                        // ---- S^T, P^T, dP^T, dS^T of the pair's two query tiles (rows = keys 16kt+4q+j, column =
+                        // query), every stage for both tiles: two independent chains to overlap ----
+                        f32x4 st[2][4], dp[2][4];
 #pragma unroll
                         for (int ni = 0; ni < 2; ++ni) {
                             const int nt = 2 * p2 + ni;
-                            // ---- S^T, P^T, dP^T, dS^T of one query tile: rows = keys 16kt+4q+j, column = query ----
-                            f32x4 st[4], dp[4];
                             const uint4 qop = cat(Qb[0][nt], Qb[1][nt]);
                             const uint4 oop = cat(dOb[hl][0][nt], dOb[hl][1][nt]);
 #pragma unroll
@@ -407,67 +408,95 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                                 f32x4 bt;
 #pragma unroll
                                 for (int j = 0; j < 4; ++j) bt[j] = tbl[hl * TP + tb0 + 30 * (nt - kt) - j];
-                                st[kt] = mma32(cat(Kb[0][kt], Kb[1][kt]), qop, bt);
-                                dp[kt] = mma32(cat(Vb[0][kt], Vb[1][kt]), oop, zero4);
+                                st[ni][kt] = mma32(cat(Kb[0][kt], Kb[1][kt]), qop, bt);
+                                dp[ni][kt] = mma32(cat(Vb[0][kt], Vb[1][kt]), oop, zero4);
                             }
-                            if (lastrow || lastcol) {
+                        }
+                        if (lastrow || lastcol) {
+#pragma unroll
+                            for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
                                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                                     for (int j = 0; j < 4; ++j)
-                                        if ((lastrow && qr_w[nt] != kr_w[kt]) || (lastcol && qc_w != kc_w[j]))
-                                            st[kt][j] += kMaskLog2;
-                            }
-                            float mx = fmaxf(fmaxf(st[0][0], st[0][1]), fmaxf(st[0][2], st[0][3]));
+                                        if ((lastrow && qr_w[2 * p2 + ni] != kr_w[kt]) || (lastcol && qc_w != kc_w[j]))
+                                            st[ni][kt][j] += kMaskLog2;
+                        }
+                        float mx[2], sum[2], dlt[2];
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            float m0 = fmaxf(fmaxf(st[ni][0][0], st[ni][0][1]), fmaxf(st[ni][0][2], st[ni][0][3]));
 #pragma unroll
                             for (int kt = 1; kt < 4; ++kt)
 #pragma unroll
-                                for (int j = 0; j < 4; j += 2) mx = fmaxf(fmaxf(mx, st[kt][j]), st[kt][j + 1]);
-                            mx = qgroup_max(mx);
-                            float sum = 0.f, dlt = 0.f;
+                                for (int j = 0; j < 4; j += 2) m0 = fmaxf(fmaxf(m0, st[ni][kt][j]), st[ni][kt][j + 1]);
+                            mx[ni] = m0;
+                        }
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) mx[ni] = qgroup_max(mx[ni]);
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            float a = 0.f, b = 0.f;
 #pragma unroll
                             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                                 for (int j = 0; j < 4; ++j) {
-                                    const float p = __builtin_amdgcn_exp2f(st[kt][j] - mx);
-                                    st[kt][j] = p;
-                                    sum += p;
-                                    dlt = fmaf(p, dp[kt][j], dlt);
+                                    const float p = __builtin_amdgcn_exp2f(st[ni][kt][j] - mx[ni]);
+                                    st[ni][kt][j] = p;
+                                    a += p;
+                                    b = fmaf(p, dp[ni][kt][j], b);
                                 }
-                            sum = qgroup_sum(sum);
-                            dlt = qgroup_sum(dlt);
-                            const float inv = __builtin_amdgcn_rcpf(sum);
-                            const float delta = dlt * inv; // sum over keys of P dP
-                            uint2 Pb[4], dSb[4];
+                            sum[ni] = a;
+                            dlt[ni] = b;
+                        }
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            sum[ni] = qgroup_sum(sum[ni]);
+                            dlt[ni] = qgroup_sum(dlt[ni]);
+                        }
+                        uint2 Pb[2][4], dSb[2][4];
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            const int nt = 2 * p2 + ni;
+                            const float inv = __builtin_amdgcn_rcpf(sum[ni]);
+                            const float delta = dlt[ni] * inv; // sum over keys of P dP
 #pragma unroll
                             for (int kt = 0; kt < 4; ++kt) {
 #pragma unroll
                                 for (int j = 0; j < 4; ++j) {
-                                    const float p = st[kt][j] * inv;
-                                    st[kt][j] = p;
-                                    dp[kt][j] = p * (dp[kt][j] - delta);
+                                    const float p = st[ni][kt][j] * inv;
+                                    st[ni][kt][j] = p;
+                                    dp[ni][kt][j] = p * (dp[ni][kt][j] - delta);
                                 }
-                                Pb[kt] = pack_bf16x4(st[kt]);
-                                dSb[kt] = pack_bf16x4(dp[kt]);
-                                fold4[(nt - kt + 3) * 64 + lane] += dp[kt];
+                                Pb[ni][kt] = pack_bf16x4(st[ni][kt]);
+                                dSb[ni][kt] = pack_bf16x4(dp[ni][kt]);
+                                fold4[(nt - kt + 3) * 64 + lane] += dp[ni][kt];
                             }
-                            // dQ^T = K^T dS^T (gradient of q / sqrt(d)): rows = head features, column = query
-                            f32x4 d0 = zero4, d1 = zero4;
+                        }
+                        // dQ^T = K^T dS^T (gradient of q / sqrt(d)): rows = head features, column = query
+                        f32x4 d0[2], d1[2];
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            d0[ni] = d1[ni] = zero4;
 #pragma unroll
                             for (int kp = 0; kp < 2; ++kp) {
-                                const uint4 sop = cat(dSb[2 * kp], dSb[2 * kp + 1]);
-                                d0 = mma32(cat(KN[0][2 * kp], KN[0][2 * kp + 1]), sop, d0);
-                                d1 = mma32(cat(KN[1][2 * kp], KN[1][2 * kp + 1]), sop, d1);
+                                const uint4 sop = cat(dSb[ni][2 * kp], dSb[ni][2 * kp + 1]);
+                                d0[ni] = mma32(cat(KN[0][2 * kp], KN[0][2 * kp + 1]), sop, d0[ni]);
+                                d1[ni] = mma32(cat(KN[1][2 * kp], KN[1][2 * kp + 1]), sop, d1[ni]);
                             }
+                        }
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
                             for (int kt = 0; kt < 4; ++kt) {
-                                Pq[kt][ni] = transpose_tile(Pb[kt], ident);
-                                dSq[kt][ni] = transpose_tile(dSb[kt], ident);
+                                Pq[kt][ni] = transpose_tile(Pb[ni][kt], ident);
+                                dSq[kt][ni] = transpose_tile(dSb[ni][kt], ident);
                             }
-                            *reinterpret_cast<uint4 *>(dq_win + (size_t)((nt * HG + hl) * 3 + 0) * 1024) =
-                                cat(pack_bf16x4(d0), pack_bf16x4(d1));
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni)
+                            *reinterpret_cast<uint4 *>(dq_win + (size_t)(((2 * p2 + ni) * HG + hl) * 3 + 0) * 1024) =
+                                cat(pack_bf16x4(d0[ni]), pack_bf16x4(d1[ni]));
+                        __builtin_amdgcn_sched_barrier(0);
                         // dK^T += Q^T dS, dV^T += dO^T P over the 32 queries of the pair
 #pragma unroll
                         for (int et = 0; et < 2; ++et)
