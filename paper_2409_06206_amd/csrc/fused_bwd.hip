@@ -281,6 +281,11 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
     const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
 
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+        // (the lane index as this window's address arithmetic sees it: opaque, so that the many per-lane LDS and
+        // memory addresses below are computed where they are used instead of being kept, and spilled, across windows)
+        int lane_w = threadIdx.x & 63;
+        asm volatile("" : "+v"(lane_w));
+        const int lane = lane_w, l16 = lane & 15, q = lane >> 4;
         if (!PIPE) load_rows(win);
         // Eq. 8: the input of a group with a cascade term is F = x slice + previous group's output,
         // rounded to bf16 exactly as the forward kernels round it (it is the operand of their QKV
