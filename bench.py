@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the launch kinds of that kernel), valid only for the kernel source they were taken on:
 # {(workload, groups, kernel): (source file, sha256 of it, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c4", 2, "fused_bwd"): ("fused_bwd.hip", "0f5966a802b405a14bc28e2c8ef915c2c013d667d38ef649b5e90da11ad862a5", 187015665),
-    ("c3", 2, "fused_bwd"): ("fused_bwd.hip", "0f5966a802b405a14bc28e2c8ef915c2c013d667d38ef649b5e90da11ad862a5", 103379503),
-    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "0f5966a802b405a14bc28e2c8ef915c2c013d667d38ef649b5e90da11ad862a5", 83589576),
-    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "7feb3b126cf1049bfdf47aa8df6ae3a87c8e3bbc8d61c77ff37fcce7af9c863d", 274594216),
-    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "87766f7201ea41409439c8069d667625587b2b4454e3b3928cb56883acdb02ec", 428977916),
+    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "64bf95df4fab49c696a035603c4fd21f81087a4655f4886f8f20ba8decc6f62c", 231784604),
+    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "64bf95df4fab49c696a035603c4fd21f81087a4655f4886f8f20ba8decc6f62c", 117428160),
+    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "8536961e0fd9be33e7b8ff4afb144d53fa42c502fdc99f2cd7835dea6df02a29", 74173832),
+    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "40b706f5360b5b1b725536557eb972afb71807e67636e134b0e8a6a11509e669", 224617040),
+    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "87766f7201ea41409439c8069d667625587b2b4454e3b3928cb56883acdb02ec", 427825204),
 }
 
 
