@@ -105,7 +105,12 @@ typedef struct gswa_desc {
  *                  64- or 144-token windows, one bias-table gradient per window.
  *                  Fused path: one partial parameter-gradient vector per workgroup of ONE head-group
  *                  launch (each launch is followed by the fixed-order sum of its partials, and the next
- *                  reuses the buffer), so this size does not grow with the group count.
+ *                  reuses the buffer), so this size does not grow with the group count.  Layers of
+ *                  180 channels with two or three groups and 8x8 windows additionally pass ONE
+ *                  group's intermediate gradients (d(q|k|v), the group's input and its gradient, as
+ *                  matrix-core operand fragments) from the attention kernel to the kernel that forms
+ *                  dx and the weight gradients: about 7.6 Cg bytes per token, falling with the group
+ *                  count.
  * Which path serves a layer, and every size, depends only on desc (shape, dtype, flags), not on the
  * device.
  * Any output pointer may be NULL.  All sizes are multiples of 256.
