@@ -528,6 +528,11 @@ __global__ __launch_bounds__(4 * M * M, M == 8 ? 2 : 1) void fused_attn_fwd_kern
     const bool casc = GI > 0 && g.cascade;
 
     for (int win = blockIdx.x; win < g.nW; win += gridDim.x) {
+        // (the lane index as this window's address arithmetic sees it: opaque, so that per-lane LDS and memory
+        // addresses are computed where they are used instead of being kept, and spilled, across windows)
+        int lane_w = threadIdx.x & 63;
+        asm volatile("" : "+v"(lane_w));
+        const int lane = lane_w, l16 = lane & 15, q = lane >> 4;
         const int b = win / per_img;
         const int wr = win - b * per_img;
         const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
@@ -539,7 +544,7 @@ __global__ __launch_bounds__(4 * M * M, M == 8 ? 2 : 1) void fused_attn_fwd_kern
 
         const uint32_t *xrow = reinterpret_cast<const uint32_t *>(x + tok * C + GI * CG);
         const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + tok * C + (GI > 0 ? GI - 1 : 0) * CG);
-        uint4 xf[KS], af[KS];
+        uint4 xf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             uint32_t xv[4], av[4];
@@ -549,11 +554,13 @@ __global__ __launch_bounds__(4 * M * M, M == 8 ? 2 : 1) void fused_attn_fwd_kern
                 xv[dw] = c < CG ? xrow[c >> 1] : 0u;
                 av[dw] = (casc && c < CG) ? arow[c >> 1] : 0u;
             }
-            xf[ks] = make_uint4(xv[0], xv[1], xv[2], xv[3]);
-            af[ks] = make_uint4(av[0], av[1], av[2], av[3]);
+            // Eq. 8: F = x slice + previous group's output, rounded to bf16 once (the operand of the products below)
+            xf[ks] = casc ? make_uint4(add_bf16x2(xv[0], av[0]), add_bf16x2(xv[1], av[1]), add_bf16x2(xv[2], av[2]),
+                                       add_bf16x2(xv[3], av[3]))
+                          : make_uint4(xv[0], xv[1], xv[2], xv[3]);
         }
 
-#pragma unroll
+#pragma unroll 1
         for (int hx = 0; hx < NH; ++hx) {
             const int hd = HB + hx, hl = hd % HG;
             f32x4 qT[ET], kT[ET], vv[ET];
@@ -576,11 +583,6 @@ __global__ __launch_bounds__(4 * M * M, M == 8 ? 2 : 1) void fused_attn_fwd_kern
                     qT[et] = mma32(fq_, xf[ks], qT[et]);
                     kT[et] = mma32(fk_, xf[ks], kT[et]);
                     vv[et] = mma32(xf[ks], fv_, vv[et]);
-                    if (casc) {
-                        qT[et] = mma32(fq_, af[ks], qT[et]);
-                        kT[et] = mma32(fk_, af[ks], kT[et]);
-                        vv[et] = mma32(af[ks], fv_, vv[et]);
-                    }
                 }
             }
             uint2 Qb[ET];
