@@ -1014,7 +1014,7 @@ hipError_t run_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const bf16_
     float *part = static_cast<float *>(ws);
     const int grid = bwd_grid(g, device_cu_count());
     if constexpr (Cf::SPLIT) {
-        if (wide_bwd_supported(g) && (reinterpret_cast<uintptr_t>(dy) & 15) == 0) { // (the projection's gradient reuses the scratch afterwards)
+        if (wide_bwd_supported(g)) { // (16-byte aligned tensors: the entry points check; the projection's gradient reuses the scratch afterwards)
             hipError_t e = launch_wide_bwd(g, x, dy, attn, pack_, dx, dw_qkv, db_qkv, dtable, accumulate, ws, s);
             if (e != hipSuccess) return e;
             return run_wproj_grad<Cf>(g, grid, dy, attn, part, dw_proj, db_proj, accumulate, s);

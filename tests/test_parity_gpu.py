@@ -59,9 +59,31 @@ def test_forced_staged_path_wide_layer(oracle):
                       extra_flags=gswa.GSWA_FORCE_STAGED)
 
 
-def test_no_cascade_flag_wide_layer(oracle):
-    """Split fused path (C=180) with Eq. 8 switched off."""
-    parity.check_case(oracle, 1, 16, 16, 180, 6, 2, 8, 4, "bf16", regime="stress", cascade=False)
+@pytest.mark.parametrize("groups", [2, 3])
+def test_no_cascade_flag_wide_layer(oracle, groups):
+    """Wide fused path (C=180) with Eq. 8 switched off: no cascade input, no cascade gradient."""
+    parity.check_case(oracle, 1, 16, 16, 180, 6, groups, 8, 4, "bf16", regime="stress", cascade=False)
+
+
+@pytest.mark.parametrize("groups", [2, 3])
+def test_accumulate_flag_on_wide_fused_path(oracle, groups):
+    """Every partial-sum launch of the wide backward (per group, table, projection) adds into its output."""
+    import torch
+    from paper_2409_06206_amd import gswa, runner
+    x, dy, p = parity.make_inputs(2, 16, 24, 180, 6, groups, 8, "bf16", synth.LAYER_SEED0 + 1, "stress")
+    layer = runner.DeviceLayer(2, 16, 24, 180, 6, groups, 8, 4, "bf16", gswa.GSWA_ACCUM_WGRAD)
+    layer.set_params(p)
+    layer.set_inputs(x, dy)
+    for g in layer.grads.values():
+        g.fill_(0.5)
+    layer.forward()
+    layer.backward()
+    layer.backward()
+    torch.cuda.synchronize()
+    got = layer.results()
+    want = parity.oracle_results(oracle, x, dy, p, 6, groups, 8, 4)
+    for k in parity.GRAD_NAMES[1:]:
+        assert parity.rel_err(got[k] - 0.5, 2.0 * want[k]) <= parity.TOL["bf16"], k
 
 
 def test_kernel_timing_aid_reports_the_launched_kernels():
