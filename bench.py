@@ -51,6 +51,7 @@ def measured_traffic(workload, groups, kernel):
 FLAGS = 0  # extra descriptor flags for every layer (--force-staged)
 BATCH = 0  # batch size override (--batch); 0 = the workload's own
 CHECKPOINT_EVERY = 0  # layers per recomputed block of a stack workload (--checkpoint-every)
+BAND_WINDOWS = 0      # window rows per band of a forward-only stack workload (--band-windows)
 
 
 def build_case(name, groups):
@@ -65,7 +66,8 @@ def build_case(name, groups):
         # one call runs the whole sequence of layers (alternating shift) in each direction
         S = runner.DeviceStack(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups, cfg["window"],
                                cfg["stack_shift"], cfg["dtype"], cfg["hidden"], cfg["stack"], CHECKPOINT_EVERY,
-                               flags=FLAGS, dqk=cfg.get("dqk", 0))
+                               flags=FLAGS, dqk=cfg.get("dqk", 0), band_windows=BAND_WINDOWS,
+                               inference_only=bool(cfg.get("forward_only")))
         S.set_params([synth.astl_params(cfg["C"], cfg["heads"], groups, cfg["window"], cfg["hidden"],
                                         synth.LAYER_SEED0 + li, dqk=cfg.get("dqk", 0)) for li in range(cfg["stack"])])
         S.set_inputs(x, dy)
@@ -293,7 +295,8 @@ def is_forward_only(name):
 def workload_text(name, cfg, groups, n_layers, backward):
     return (f"{name}: {n_layers} {'whole (LN, GSWA, MLP, skips)' if cfg.get('block') else 'GSWA'} layer(s), "
             f"shifts {list(cfg['layers'])[:4]}{'...' if n_layers > 4 else ''}"
-            f"{' one stack call per pass, shifts 0/%d alternating, checkpoint_every=%d' % (cfg['stack_shift'], CHECKPOINT_EVERY) if cfg.get('stack') else ''}, "
+            f"{' one stack call per pass, shifts 0/%d alternating, checkpoint_every=%d' % (cfg['stack_shift'], CHECKPOINT_EVERY) if cfg.get('stack') else ''}"
+            f"{' in bands of %d window rows' % BAND_WINDOWS if cfg.get('stack') and BAND_WINDOWS else ''}, "
             f"{'fwd+bwd' if backward else 'forward only'}, "
             f"B={cfg['B']} {cfg['H']}x{cfg['W']} C={cfg['C']} heads={cfg['heads']} "
             f"window={cfg['window']} groups={groups}"
@@ -381,7 +384,7 @@ def main():
     ap.add_argument("--groups", type=int, default=2)
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5_m8", "c5_m16", "agile_h4_qk16", "agile_h4_qk32", "agile_h6_qk24", "agile_infer",
                                                               "astl_c2", "astl_agile", "astl_c3", "astl_infer", "astl_stack36",
-                                                              "astl_agile_stack36"],
+                                                              "astl_agile_stack36", "astl_infer_stack6", "astl_infer_stack6_2k"],
                     help="c4 (the 36-layer stack, the largest benchmark configuration) is the headline; a default "
                          "run also carries c2, c3 and c5_* in by_workload (c5_*: forward only)")
     ap.add_argument("--batch", type=int, default=0,
@@ -394,6 +397,9 @@ def main():
     ap.add_argument("--checkpoint-every", type=int, default=0,
                     help="stack workloads: keep only every k-th layer input and recompute blocks of k layers "
                          "in the backward pass (0 = keep everything)")
+    ap.add_argument("--band-windows", type=int, default=0,
+                    help="forward-only stack workloads: inference band by band, this many window rows per band "
+                         "(0 = the whole map per layer call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-sweep", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true",
@@ -408,8 +414,9 @@ def main():
     import torch
     from paper_2409_06206_amd import gswa
     gswa.lib()
-    global FLAGS, BATCH, CHECKPOINT_EVERY
+    global FLAGS, BATCH, CHECKPOINT_EVERY, BAND_WINDOWS
     CHECKPOINT_EVERY = max(0, args.checkpoint_every)
+    BAND_WINDOWS = max(0, args.band_windows)
     if args.force_staged:
         FLAGS = gswa.GSWA_FORCE_STAGED
     BATCH = max(0, args.batch)

@@ -121,6 +121,26 @@ int astl_stack_query_bytes(const astl_stack_desc *desc, size_t *saved_bytes, siz
 int astl_stack_forward(const astl_stack_desc *desc, const void *x, const astl_params *params, void *y,
                        void *saved, void *ws, void *hip_stream);
 
+/*
+ * Inference of a stack on a map of any height with scratch that does not grow with the map (Sec. "Agile
+ * Swin Transformer Block"; large inputs at test time).  Every step of Eq. 4-5 acts within one window, so
+ * the map goes through each layer in bands of `band_windows` rows of windows of that layer's (shifted)
+ * window grid, one image at a time.  A band of a shifted layer that does not reach the map's last window
+ * row is a contiguous run of image rows and needs only the column part of the shift mask; the band that
+ * ends the map also takes the map's first `shift` rows.  The result is the one astl_stack_forward gives
+ * for inference, bit for bit.
+ *
+ * x [B,H,W,C] is read only; y [B,H,W,C] receives layer 0's output and is then updated in place by the
+ * later layers; x and y must not overlap.  ws: *ws_bytes of astl_stack_tiled_query_bytes, 256-byte
+ * aligned: two bands of activations and one layer's scratch for a band ((band_windows + 1) * window
+ * rows of one image).  band_windows >= the map's window rows means one band per image.  desc->
+ * checkpoint_every is ignored.  Errors as for astl_stack_forward; band_windows <= 0 is GSWA_EINVAL.
+ * Work per shifted layer grows by one row of windows per band (computed and dropped).
+ */
+int astl_stack_tiled_query_bytes(const astl_stack_desc *desc, int32_t band_windows, size_t *ws_bytes);
+int astl_stack_forward_tiled(const astl_stack_desc *desc, const void *x, const astl_params *params, void *y,
+                             int32_t band_windows, void *ws, void *hip_stream);
+
 /* Gradients through the whole stack: dx, and grads[l] for the parameters of layer l. */
 int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *dy,
                         const astl_params *params, const void *saved, void *dx, const astl_grads *grads,

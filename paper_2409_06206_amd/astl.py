@@ -9,7 +9,8 @@ from . import gswa
 from .gswa import _check, _ptr, _stream
 
 EXPORTS = ("astl_query_bytes", "astl_forward", "astl_backward",
-           "astl_stack_query_bytes", "astl_stack_forward", "astl_stack_backward")
+           "astl_stack_query_bytes", "astl_stack_forward", "astl_stack_backward",
+           "astl_stack_tiled_query_bytes", "astl_stack_forward_tiled")
 PARAM_FIELDS = ("ln1_w", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "bias_table",
                 "ln2_w", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -55,6 +56,10 @@ def lib():
         L.astl_stack_backward.argtypes = [sd, vp, vp, ctypes.POINTER(astl_params), vp, vp,
                                           ctypes.POINTER(astl_grads), vp, vp]
         L.astl_stack_backward.restype = ctypes.c_int
+        L.astl_stack_tiled_query_bytes.argtypes = [sd, ctypes.c_int32, sp]
+        L.astl_stack_tiled_query_bytes.restype = ctypes.c_int
+        L.astl_stack_forward_tiled.argtypes = [sd, vp, ctypes.POINTER(astl_params), vp, ctypes.c_int32, vp, vp]
+        L.astl_stack_forward_tiled.restype = ctypes.c_int
         _ready = True
     return L
 
@@ -120,3 +125,15 @@ def astl_stack_backward(desc, x, dy, params, saved, dx, grads, ws, stream=None):
     p, g = _fill_array(astl_params, params), _fill_array(astl_grads, grads)
     _check(lib().astl_stack_backward(ctypes.byref(desc), _ptr(x), _ptr(dy), p, _ptr(saved), _ptr(dx), g,
                                      _ptr(ws), _stream(stream)))
+
+
+def astl_stack_tiled_query_bytes(desc, band_windows):
+    a = ctypes.c_size_t()
+    _check(lib().astl_stack_tiled_query_bytes(ctypes.byref(desc), band_windows, ctypes.byref(a)))
+    return a.value
+
+
+def astl_stack_forward_tiled(desc, x, params, y, band_windows, ws, stream=None):
+    p = _fill_array(astl_params, params)
+    _check(lib().astl_stack_forward_tiled(ctypes.byref(desc), _ptr(x), p, _ptr(y), band_windows, _ptr(ws),
+                                          _stream(stream)))

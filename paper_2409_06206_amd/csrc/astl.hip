@@ -762,6 +762,129 @@ int astl_stack_forward(const astl_stack_desc *desc, const void *x, const astl_pa
     return GSWA_OK;
 }
 
+} // extern "C"
+
+namespace {
+
+// Inference of a stack band by band (Sec. "Agile Swin Transformer Block"; every step of Eq. 4-5 stays
+// inside a window, so a band of window rows of the shifted frame goes through a whole layer on its own).
+struct TiledPlan {
+    StackPlan sp;
+    int nb;          // window rows per band
+    int M, nwi;
+    size_t band_act; // bytes of the largest band, [rows, W, C] (256-aligned)
+    size_t layer_ws; // scratch of one layer call on the largest band (inference form)
+    size_t ws;
+};
+
+int make_tiled_plan(const astl_stack_desc *d, int band_windows, TiledPlan *tp)
+{
+    int rc = make_stack_plan(d, &tp->sp);
+    if (rc != GSWA_OK) return rc;
+    if (band_windows <= 0) return GSWA_EINVAL;
+    tp->M = d->layer.attn.window;
+    tp->nwi = d->layer.attn.H / tp->M;
+    tp->nb = band_windows < tp->nwi ? band_windows : tp->nwi;
+    // window rows of the sub-problems that occur: whole bands (unshifted layers), whole bands plus the
+    // row of windows that is computed and dropped (shifted layers), and the band that ends the map
+    const int rem = tp->nwi % tp->nb;
+    const int kinds[3] = {tp->nb, tp->nb < tp->nwi ? tp->nb + 1 : tp->nb, rem ? rem : tp->nb};
+    tp->band_act = tp->layer_ws = 0;
+    for (int k = 0; k < 3; ++k)
+        for (int odd = 0; odd < 2; ++odd) {
+            astl_desc sd = odd ? tp->sp.odd : tp->sp.even;
+            sd.attn.B = 1;
+            sd.attn.H = kinds[k] * tp->M;
+            Plan pl;
+            rc = make_plan(&sd, &pl);
+            if (rc != GSWA_OK) return rc;
+            if (pl.act > tp->band_act) tp->band_act = pl.act;
+            if (pl.fwd_ws + pl.saved > tp->layer_ws) tp->layer_ws = pl.fwd_ws + pl.saved;
+        }
+    tp->ws = 2 * tp->band_act + tp->layer_ws;
+    return GSWA_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int astl_stack_tiled_query_bytes(const astl_stack_desc *desc, int32_t band_windows, size_t *ws_bytes)
+{
+    TiledPlan tp;
+    int rc = make_tiled_plan(desc, band_windows, &tp);
+    if (rc != GSWA_OK) return rc;
+    if (ws_bytes) *ws_bytes = tp.ws;
+    return GSWA_OK;
+}
+
+int astl_stack_forward_tiled(const astl_stack_desc *desc, const void *x, const astl_params *params, void *y,
+                             int32_t band_windows, void *ws, void *hip_stream)
+{
+    TiledPlan tp;
+    int rc = make_tiled_plan(desc, band_windows, &tp);
+    if (rc != GSWA_OK) return rc;
+    if (!x || !params || !y || !ws || x == y) return GSWA_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) || !aligned16(x, y)) return GSWA_EINVAL;
+    for (int l = 0; l < tp.sp.L; ++l)
+        if (!params_ok(params + l)) return GSWA_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const gswa_desc &at = desc->layer.attn;
+    const int M = tp.M, nwi = tp.nwi, nb = tp.nb, H = at.H;
+    const size_t row = (size_t)at.W * at.C * (at.dtype == GSWA_F32 ? 4 : 2); // bytes of one image row
+    const size_t img = (size_t)H * row;
+    char *xb = static_cast<char *>(ws), *yb = xb + tp.band_act, *layer_ws = yb + tp.band_act;
+    auto copy_rows = [&](char *dst, const char *src, int rows) -> hipError_t {
+        return rows > 0 ? hipMemcpyAsync(dst, src, (size_t)rows * row, hipMemcpyDeviceToDevice, st) : hipSuccess;
+    };
+    // Layer 0 reads x and writes y; every later layer works on y in place: a band's result goes to yb first
+    // and over the band's own rows afterwards, which no later band of the layer reads (see below).
+    const char *cur = static_cast<const char *>(x);
+    char *out = static_cast<char *>(y);
+    for (int l = 0; l < tp.sp.L; ++l) {
+        const astl_desc *ld = (l & 1) ? &tp.sp.odd : &tp.sp.even;
+        const int s = ld->attn.shift;
+        for (int b = 0; b < at.B; ++b) {
+            const char *ib = cur + (size_t)b * img;
+            char *ob = out + (size_t)b * img;
+            for (int a = 0; a < nwi; a += nb) {
+                const int e = a + nb < nwi ? a + nb : nwi; // window rows [a, e) of the shifted frame
+                astl_desc sd = *ld;
+                sd.attn.B = 1;
+                const char *src;
+                if (s == 0 || e < nwi) {
+                    // Image rows [aM + s, eM + s), contiguous.  As a problem of its own with the same shift,
+                    // starting at image row aM: its window rows 0 .. e-a-1 are exactly these windows (no
+                    // row of theirs is beyond the last M - s rows, so only the column mask applies, as in
+                    // the map); one more row of windows, which wraps within the band, is computed on
+                    // whatever lies there and dropped.
+                    const int wr = e - a + (s ? 1 : 0);
+                    sd.attn.H = wr * M;
+                    src = ib + (size_t)a * M * row;
+                    if (!aligned16(src)) {
+                        ASTL_HIP(copy_rows(xb, src, wr * M));
+                        src = xb;
+                    }
+                    ASTL_RC(forward_checked(&sd, src, params + l, yb, nullptr, layer_ws, hip_stream, nullptr));
+                    ASTL_HIP(copy_rows(ob + ((size_t)a * M + s) * row, yb + (size_t)s * row, (e - a) * M));
+                } else {
+                    // The band that ends the map wraps to the map's first s rows: [rows 0 .. s | rows
+                    // aM + s .. H) is an ordinary shifted problem (its last window row is the map's).
+                    const int rows = (e - a) * M;
+                    sd.attn.H = rows;
+                    ASTL_HIP(copy_rows(xb, ib, s));
+                    ASTL_HIP(copy_rows(xb + (size_t)s * row, ib + ((size_t)a * M + s) * row, rows - s));
+                    ASTL_RC(forward_checked(&sd, xb, params + l, yb, nullptr, layer_ws, hip_stream, nullptr));
+                    ASTL_HIP(copy_rows(ob, yb, s));
+                    ASTL_HIP(copy_rows(ob + ((size_t)a * M + s) * row, yb + (size_t)s * row, rows - s));
+                }
+            }
+        }
+        cur = out;
+    }
+    return GSWA_OK;
+}
+
 int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *dy, const astl_params *params,
                         const void *saved, void *dx, const astl_grads *grads, void *ws, void *hip_stream)
 {

@@ -115,7 +115,10 @@ class DeviceStack:
     """Buffers of a sequence of whole layers (alternating shift) behind the stack entry points."""
 
     def __init__(self, B, H, W, C, heads, groups, window, shift, dtype, hidden, n_layers, checkpoint_every=0,
-                 eps=1e-5, flags=0, device="cuda:0", dqk=0):
+                 eps=1e-5, flags=0, device="cuda:0", dqk=0, band_windows=0, inference_only=False):
+        """band_windows > 0: inference runs band by band (forward(keep=False)), with that many window rows
+        per band.  inference_only: no buffers for the backward pass."""
+        self.band_windows = band_windows
         self.desc = astl.make_stack_desc(B, H, W, C, heads, groups, window, shift, dtype, hidden, n_layers,
                                          checkpoint_every, eps, flags, dqk)
         self.dtype, self.device, self.n_layers = dtype, device, n_layers
@@ -123,12 +126,19 @@ class DeviceStack:
         tdt = torch.float32 if dtype == "f32" else torch.bfloat16
         self.saved_bytes, self.fwd_ws_bytes, self.bwd_ws_bytes = astl.astl_stack_query_bytes(self.desc)
         self.y = torch.empty(self.shape, dtype=tdt, device=device)
-        self.dx = torch.empty(self.shape, dtype=tdt, device=device)
-        self.saved = torch.empty(self.saved_bytes, dtype=torch.uint8, device=device)
+        if band_windows:
+            self.fwd_ws_bytes = astl.astl_stack_tiled_query_bytes(self.desc, band_windows)
+        if inference_only:
+            self.saved_bytes = self.bwd_ws_bytes = 0
+            self.dx = self.saved = None
+            self.grads = []
+        else:
+            self.dx = torch.empty(self.shape, dtype=tdt, device=device)
+            self.saved = torch.empty(self.saved_bytes, dtype=torch.uint8, device=device)
+            shp = synth.astl_param_shapes(C, heads, groups, window, hidden, dqk)
+            self.grads = [{k: torch.empty(s, dtype=torch.float32, device=device) for k, s in shp.items()}
+                          for _ in range(n_layers)]
         self.ws = torch.empty(max(self.fwd_ws_bytes, self.bwd_ws_bytes), dtype=torch.uint8, device=device)
-        shp = synth.astl_param_shapes(C, heads, groups, window, hidden, dqk)
-        self.grads = [{k: torch.empty(s, dtype=torch.float32, device=device) for k, s in shp.items()}
-                      for _ in range(n_layers)]
         self.params = None
         self.x = self.dy = None
 
@@ -140,8 +150,20 @@ class DeviceStack:
         self.dy = None if dy is None else to_device(dy, self.dtype, self.device)
 
     def forward(self, keep=True, stream=None):
+        if self.band_windows and not keep:
+            astl.astl_stack_forward_tiled(self.desc, self.x, [DeviceBlock._fields(p) for p in self.params], self.y,
+                                          self.band_windows, self.ws, stream)
+            return
         astl.astl_stack_forward(self.desc, self.x, [DeviceBlock._fields(p) for p in self.params], self.y,
                                 self.saved if keep else None, self.ws, stream)
+
+    def forward_tiled(self, band_windows, stream=None):
+        """Inference band by band; the scratch is allocated here, at the size the library asks for."""
+        need = astl.astl_stack_tiled_query_bytes(self.desc, band_windows)
+        ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        astl.astl_stack_forward_tiled(self.desc, self.x, [DeviceBlock._fields(p) for p in self.params], self.y,
+                                      band_windows, ws, stream)
+        return need
 
     def backward(self, stream=None):
         astl.astl_stack_backward(self.desc, self.x, self.dy, [DeviceBlock._fields(p) for p in self.params],

@@ -164,6 +164,10 @@ CONFIGS.update({
     # the deep feature extractor's depth: 36 layers (6 blocks of 6), shifts 0, 4, 0, 4, ...
     "astl_stack36": dict(CONFIGS["c2"], block=True, hidden=120, stack=36, stack_shift=4, groups=(1, 2, 3, 6)),
     "astl_agile_stack36": dict(CONFIGS["agile_h4_qk16"], block=True, hidden=120, stack=36, stack_shift=6),
+    # inference of one block of six whole layers on large maps (forward only)
+    "astl_infer_stack6": dict(CONFIGS["c5_m8"], block=True, hidden=360, stack=6, stack_shift=4, forward_only=True),
+    "astl_infer_stack6_2k": dict(CONFIGS["c5_m8"], H=2048, W=2048, block=True, hidden=360, stack=6, stack_shift=4,
+                                 forward_only=True),
 })
 ACT_SEED = 0
 LAYER_SEED0 = 100

@@ -267,6 +267,64 @@ def test_stack_matches_oracle_with_and_without_checkpointing(case, every):
     assert torch.equal(st.y, y_train)
 
 
+TILED = [
+    # (case, band sizes in window rows): bands that divide the map and bands that do not, one band per
+    # image, one window row per band; shift 0 in every layer; odd shift; three images
+    (dict(B=1, H=48, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=120, n_layers=4),
+     (1, 2, 4, 5, 6, 9)),
+    (dict(B=3, H=32, W=24, C=60, heads=6, groups=3, window=8, shift=3, dtype="bf16", hidden=120, n_layers=3),
+     (1, 3)),
+    (dict(B=2, H=40, W=16, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360, n_layers=3),
+     (2, 3)),
+    (dict(B=1, H=24, W=8, C=60, heads=6, groups=2, window=8, shift=0, dtype="bf16", hidden=120, n_layers=2),
+     (1, 2)),
+    (dict(B=2, H=20, W=12, C=12, heads=2, groups=1, window=4, shift=1, dtype="f32", hidden=20, n_layers=3),
+     (1, 2, 4)),
+    (dict(B=1, H=48, W=24, C=60, heads=4, groups=2, window=12, shift=6, dtype="bf16", hidden=120, n_layers=2,
+          dqk=4), (1, 3)),
+]
+
+
+@pytest.mark.parametrize("case,bands", TILED, ids=lambda v: _id(v) if isinstance(v, dict) else str(v))
+def test_band_by_band_inference_is_the_whole_map_inference(case, bands):
+    """Bands of window rows through every layer: the oracle's output within tolerance, and the very bits of
+    the call that takes each image as one band (a window's arithmetic does not depend on the band it is in)."""
+    import torch
+    from paper_2409_06206_amd import runner
+    c = dict(case)
+    print("case", c, flush=True)
+    dtype, L, dqk = c["dtype"], c["n_layers"], c.get("dqk", 0)
+    ps = [synth.astl_params(c["C"], c["heads"], c["groups"], c["window"], c["hidden"], 500 + l, "stress", dqk)
+          for l in range(L)]
+    ps = [{k: synth.quantize(v, dtype) for k, v in p.items()} for p in ps]
+    x = synth.quantize(synth.activations(c["B"], c["H"], c["W"], c["C"], 1)[0], dtype)
+    kw = dict(heads=c["heads"], groups=c["groups"], window=c["window"], shift=c["shift"], dqk=dqk,
+              store=None if dtype == "f32" else (lambda a: synth.quantize(a, dtype)))
+    want = astl_oracle.stack_forward(x, ps, **kw)
+    st = runner.DeviceStack(c["B"], c["H"], c["W"], c["C"], c["heads"], c["groups"], c["window"], c["shift"], dtype,
+                            c["hidden"], L, 0, dqk=dqk)
+    st.set_params(ps)
+    st.set_inputs(x)
+    x_before = st.x.clone()
+    # one band per image: every layer is one plain call of the whole-layer forward per image
+    st.forward_tiled(c["H"])
+    torch.cuda.synchronize()
+    whole = st.y.clone()
+    assert parity.rel_err(runner.to_host(whole), want) <= parity.TOL[dtype]
+    for nb in bands:
+        print("band_windows", nb, flush=True)
+        st.y.fill_(float("nan"))
+        st.forward_tiled(nb)
+        torch.cuda.synchronize()
+        assert torch.equal(st.y, whole), nb
+        assert torch.equal(st.x, x_before)
+    # the whole-map call hands LayerNorm_1 from layer to layer inside its MLP kernel where it can, which
+    # sums a row in another order: equal up to the rounding of the stored activations
+    st.forward(keep=False)
+    torch.cuda.synchronize()
+    assert parity.rel_err(runner.to_host(st.y), runner.to_host(whole)) <= (1e-6 if dtype == "f32" else 2e-2)
+
+
 def _random_layers(n, seed):
     """Seeded random whole-layer shapes that satisfy the divisibility rules: any window, head count,
     head width, hidden width, narrow or plain queries and keys."""
