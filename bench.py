@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the launch kinds of that kernel), valid only for the kernel source they were taken on:
 # {(workload, groups, kernel): (source file, sha256 of it, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "64bf95df4fab49c696a035603c4fd21f81087a4655f4886f8f20ba8decc6f62c", 231784604),
-    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "64bf95df4fab49c696a035603c4fd21f81087a4655f4886f8f20ba8decc6f62c", 117428160),
-    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "8536961e0fd9be33e7b8ff4afb144d53fa42c502fdc99f2cd7835dea6df02a29", 74173832),
-    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "40b706f5360b5b1b725536557eb972afb71807e67636e134b0e8a6a11509e669", 224617040),
-    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "87766f7201ea41409439c8069d667625587b2b4454e3b3928cb56883acdb02ec", 427825204),
+    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "40053e9f6cd31015a4a90b218c07532b1187e800995a519484405cb1a27b82cb", 231635806),
+    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "40053e9f6cd31015a4a90b218c07532b1187e800995a519484405cb1a27b82cb", 118014728),
+    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "bfb37c2def83c8e913ef3dbd1c3c8324163695feddfbb762db7a3f56c2e2ded4", 74174188),
+    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "40b706f5360b5b1b725536557eb972afb71807e67636e134b0e8a6a11509e669", 224548480),
+    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "c24e6214397b7c3373e4c3371eb01d1d402509c96a7fa2c96ed8408b7fd0bbc6", 181162956),
 }
 
 

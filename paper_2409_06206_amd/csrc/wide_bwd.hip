@@ -126,19 +126,21 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     const int rounds = (g.nW + stride - 1) / stride;
     uint32_t tok[4];
     bool lastrow = false, lastcol = false;
-    auto window_tokens = [&](int win) {
+    auto window_tokens = [&](int win, uint32_t (&tk)[4], bool edges) {
         const int b = win / per_img;
         const int wr = win - b * per_img;
         const int wi = wr / g.nwj, wj = wr - wi * g.nwj;
-        lastrow = s > 0 && wi == g.nwi - 1;
-        lastcol = s > 0 && wj == g.nwj - 1;
+        if (edges) {
+            lastrow = s > 0 && wi == g.nwi - 1;
+            lastcol = s > 0 && wj == g.nwj - 1;
+        }
         int sj = wj * M + cn + s;
         if (sj >= g.W) sj -= g.W;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             int si = wi * M + 2 * t + rsub + s;
             if (si >= g.H) si -= g.H;
-            tok[t] = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
+            tk[t] = (uint32_t)((((b * g.H + si) * g.W) + sj) * C) * 2u;
         }
     };
 
@@ -149,13 +151,14 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     // lane group q holds channels 32 ks + 8 q .. + 7 (one 16-byte piece of the row)
     uint4 xh[KS][4];
     uint4 ah[KS][4]; // the previous group's output, added when the loads have landed
-    auto load_x = [&]() {
+    uint4 xnx[KS][4], anx[KS][4]; // the same of this wave's next window, fetched under the last head
+    auto load_x = [&](const uint32_t (&tk)[4], uint4 (&xd)[KS][4], uint4 (&ad)[KS][4]) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                xh[ks][t] = bload128(xbuf, tok[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
-                if (casc_in) ah[ks][t] = bload128(abuf, tok[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
+                xd[ks][t] = bload128(xbuf, tk[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
+                if (casc_in) ad[ks][t] = bload128(abuf, tk[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
             }
     };
     auto add_cascade = [&]() { // and the channels past the group's width, which belong to the next slice, cleared
@@ -232,8 +235,17 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     for (int round = 0; round < rounds; ++round) {
         const bool more = round + 1 < rounds;
         if (active) {
-            window_tokens(win);
-            load_x(); // lands under the dO products
+            window_tokens(win, tok, true);
+            if (round == 0) load_x(tok, xh, ah); // lands under the dO products
+            else {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        xh[ks][t] = xnx[ks][t];
+                        if (casc_in) ah[ks][t] = anx[ks][t];
+                    }
+            }
         }
         uint2 dOb[HG][2][4]; // dO^T of the group's heads, packed T-form tiles
 
@@ -328,6 +340,12 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
 #pragma unroll
                             for (int ks = 0; ks < KS; ++ks) fdst[(t * KS + ks) * 64] = xh[ks][t];
                     }
+                }
+                if (hl == HG - 1 && more && win + stride < g.nW) {
+                    // x and the saved slice of this wave's next window: a head's time to land
+                    uint32_t tkn[4];
+                    window_tokens(win + stride, tkn, false);
+                    load_x(tkn, xnx, anx);
                 }
                 if (active) {
                     // ---- Q^T, K^T, V^T exactly as the forward computes them (rows = head features) ----
