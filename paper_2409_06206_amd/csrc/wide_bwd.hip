@@ -151,15 +151,24 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     // lane group q holds channels 32 ks + 8 q .. + 7 (one 16-byte piece of the row)
     uint4 xh[KS][4];
     uint4 ah[KS][4]; // the previous group's output, added when the loads have landed
-    uint4 xnx[KS][4], anx[KS][4]; // the same of this wave's next window, fetched under the last head
-    auto load_x = [&](const uint32_t (&tk)[4], uint4 (&xd)[KS][4], uint4 (&ad)[KS][4]) {
+    // the x slice of this wave's next window, fetched under the last head where the registers that live
+    // across a window (x, the cascade input, dO, the table-gradient sums and this) leave room for it
+    constexpr bool PREFETCH = KS * 16 * (GI > 0 ? 3 : 2) + HG * (28 + 16) <= 240;
+    uint4 xnx[PREFETCH ? KS : 1][4];
+    auto load_x = [&](const uint32_t (&tk)[4], auto &xd) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                xd[ks][t] = bload128(xbuf, tk[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
-                if (casc_in) ad[ks][t] = bload128(abuf, tk[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
-            }
+            for (int t = 0; t < 4; ++t) xd[ks][t] = bload128(xbuf, tk[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
+    };
+    auto load_a = [&]() {
+        if (casc_in) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    ah[ks][t] = bload128(abuf, tok[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
+        }
     };
     auto add_cascade = [&]() { // and the channels past the group's width, which belong to the next slice, cleared
 #pragma unroll
@@ -225,27 +234,25 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     // receives, from the lanes with 2 (dl - 3) + rsub - q/2 = dr, the slots with cn - 4 (q%2) - j = dc.
     float *fold = reinterpret_cast<float *>(lds + W::OFF_FOLD + (size_t)wv * W::FOLD_BYTES);
     f32x4 *fold4 = reinterpret_cast<f32x4 *>(fold);
-    float tgrad[HG][4];
+    f32x4 facc[HG][7];
 #pragma unroll
     for (int hl = 0; hl < HG; ++hl)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) tgrad[hl][i] = 0.f;
+        for (int dl = 0; dl < 7; ++dl) facc[hl][dl] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     int par = 0; // LDS buffer of the first unit of this round
     for (int round = 0; round < rounds; ++round) {
         const bool more = round + 1 < rounds;
         if (active) {
             window_tokens(win, tok, true);
-            if (round == 0) load_x(tok, xh, ah); // lands under the dO products
-            else {
+            if (!PREFETCH || round == 0) load_x(tok, xh); // lands under the dO products
+            else if constexpr (PREFETCH) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        xh[ks][t] = xnx[ks][t];
-                        if (casc_in) ah[ks][t] = anx[ks][t];
-                    }
+                    for (int t = 0; t < 4; ++t) xh[ks][t] = xnx[ks][t];
             }
+            load_a();
         }
         uint2 dOb[HG][2][4]; // dO^T of the group's heads, packed T-form tiles
 
@@ -341,11 +348,11 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                             for (int ks = 0; ks < KS; ++ks) fdst[(t * KS + ks) * 64] = xh[ks][t];
                     }
                 }
-                if (hl == HG - 1 && more && win + stride < g.nW) {
-                    // x and the saved slice of this wave's next window: a head's time to land
+                if (PREFETCH && hl == HG - 1 && more && win + stride < g.nW) {
+                    // the x slice of this wave's next window: a head's time to land
                     uint32_t tkn[4];
                     window_tokens(win + stride, tkn, false);
-                    load_x(tkn, xnx, anx);
+                    if constexpr (PREFETCH) load_x(tkn, xnx);
                 }
                 if (active) {
                     // ---- Q^T, K^T, V^T exactly as the forward computes them (rows = head features) ----
@@ -397,11 +404,6 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                     for (int et = 0; et < 2; ++et)
 #pragma unroll
                         for (int t = 0; t < 4; ++t) dkT[et][t] = dvT[et][t] = zero4;
-                    // sums of dS over the score tiles with the same offset nt - kt, in this wave's piece of LDS:
-                    // [offset][lane] x 4 key rows
-#pragma unroll
-                    for (int dl = 0; dl < 7; ++dl) fold4[dl * 64 + lane] = zero4;
-
 #pragma unroll
                     for (int p2 = 0; p2 < 2; ++p2) {
                         // N-forms of Q and dO of this pair of query tiles, for dK and dV
@@ -488,7 +490,7 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                                 }
                                 Pb[ni][kt] = pack_bf16x4(st[ni][kt]);
                                 dSb[ni][kt] = pack_bf16x4(dp[ni][kt]);
-                                fold4[(nt - kt + 3) * 64 + lane] += dp[ni][kt];
+                                facc[hl][nt - kt + 3] += dp[ni][kt];
                             }
                         }
                         // dQ^T = K^T dS^T (gradient of q / sqrt(d)): rows = head features, column = query
@@ -532,47 +534,6 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                         *reinterpret_cast<uint4 *>(dq_win + (size_t)((kt * HG + hl) * 3 + 2) * 1024) =
                             cat(pack_bf16x4(dvT[0][kt]), pack_bf16x4(dvT[1][kt]));
                     }
-                    // ---- bias-table gradient of this head and window: fold to the offsets ----
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    int lane_here = lane; // (opaque: the 64 addresses below are recomputed here, not kept in registers)
-                    asm volatile("" : "+v"(lane_here));
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int e = lane_here + 64 * i;
-                        const int R = e / 15, dc = e - 15 * R - 7, dr = R - 7;
-                        // the 16 reads of an entry are issued together, then summed
-                        float v[16];
-                        bool ok[16];
-#pragma unroll
-                        for (int c = 0; c < 2; ++c) {
-                            // lanes (rsub, q/2) = (c, c) for even dr, (c, 1 - c) for odd dr
-                            const int odd = dr & 1;
-                            const int rs = c, qh = odd ? 1 - c : c;
-                            const int num = dr - rs + qh; // = 2 (dl - 3)
-                            const int dl = (num >> 1) + 3;
-                            const bool rok = e < NTBL && dl >= 0 && dl <= 6;
-                            const int base = dl * 256 + 128 * qh + 32 * rs + 4 * dc;
-#pragma unroll
-                            for (int ql = 0; ql < 2; ++ql)
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) {
-                                    const int kc = dc + 4 * ql + j; // the contributing lane's query column
-                                    const int k = (c * 2 + ql) * 4 + j;
-                                    ok[k] = rok && kc >= 0 && kc < M;
-                                    v[k] = fold[ok[k] ? base + 80 * ql + 5 * j : 0];
-                                }
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        float acc = 0.f;
-#pragma unroll
-                        for (int k = 0; k < 16; ++k) acc += ok[k] ? v[k] : 0.f;
-                        tgrad[hl][i] += acc;
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
                 }
             }
             // the next unit has landed in LDS before any wave reads it
@@ -584,15 +545,45 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         active = win < g.nW;
     }
 
-    // this wave's partial sums of the bias-table gradient (heads of this group; every wave writes)
+    // this wave's partial sums of the bias-table gradient (heads of this group; every wave writes): per head the
+    // 28 sums of every lane go through the wave's piece of LDS, and lane l collects entries l, l + 64, ...
     float *mine = tpart + ((size_t)blockIdx.x * W::NWAVES + wv) * (HEADS * NTBL);
 #pragma unroll
-    for (int hl = 0; hl < HG; ++hl)
+    for (int hl = 0; hl < HG; ++hl) {
+#pragma unroll
+        for (int dl = 0; dl < 7; ++dl) fold4[dl * 64 + lane] = facc[hl][dl];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int e = lane + 64 * i;
-            if (e < NTBL) mine[(GI * HG + hl) * NTBL + e] = tgrad[hl][i];
+            const int R = e / 15, dc = e - 15 * R - 7, dr = R - 7;
+            float acc = 0.f;
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                // lanes (rsub, q/2) = (c, c) for even dr, (c, 1 - c) for odd dr
+                const int odd = dr & 1;
+                const int rs = c, qh = odd ? 1 - c : c;
+                const int num = dr - rs + qh; // = 2 (dl - 3)
+                const int dl = (num >> 1) + 3;
+                const bool rok = e < NTBL && dl >= 0 && dl <= 6;
+                const int base = dl * 256 + 128 * qh + 32 * rs + 4 * dc;
+#pragma unroll
+                for (int ql = 0; ql < 2; ++ql)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int kc = dc + 4 * ql + j; // the contributing lane's query column
+                        const bool ok = rok && kc >= 0 && kc < M;
+                        const float v = fold[ok ? base + 80 * ql + 5 * j : 0];
+                        acc += ok ? v : 0.f;
+                    }
+            }
+            if (e < NTBL) mine[(GI * HG + hl) * NTBL + e] = acc;
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // The group's dx slice and weight gradients from d(q|k|v).  A workgroup of eight waves takes two windows
