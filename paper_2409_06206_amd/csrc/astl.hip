@@ -318,13 +318,7 @@ template <typename T> hipError_t launch_ln_bwd(const LnBwdArgs &a, hipStream_t s
     return (a.C % 4 == 0) ? launch_ln_bwd_v<T, 4>(a, s) : launch_ln_bwd_v<T, 1>(a, s);
 }
 
-// GELU in its Gaussian-CDF form and its derivative Phi(t) + t phi(t)
-__device__ __forceinline__ float gelu_f(float t) { return 0.5f * t * (1.f + erff(t * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_df(float t)
-{
-    return 0.5f * (1.f + erff(t * 0.70710678118654752f)) + t * 0.39894228040143268f * __expf(-0.5f * t * t);
-}
-
+// (GELU and its derivative: staged_kernels.h)
 // h = GELU(pre);  with dh: dh <- dh * GELU'(pre) in place (h not written)
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_kernel(const T *pre, T *h, T *dh, long n)
@@ -458,8 +452,14 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
     LinearArgs f1{};
     f1.a1 = xn; f1.lda1 = C; f1.w = p->w_fc1; f1.w_sn = C; f1.w_sk = 1; f1.bias = p->b_fc1;
     f1.out = pre; f1.ldout = Hd; f1.rows = rows; f1.N = Hd; f1.K = C; f1.prof_id = K_FC1_LINEAR;
-    ASTL_HIP(launch_linear<T>(f1, st));
-    ASTL_HIP(launch_gelu<T>(pre, h, nullptr, rows * Hd, st));
+    if (sizeof(T) == 2 && linear_act_supported(f1)) {
+        // the hidden layer straight from the product (the pre-activation is never read in this pass)
+        f1.act = kActGelu; f1.out = h;
+        ASTL_HIP(launch_linear<T>(f1, st));
+    } else {
+        ASTL_HIP(launch_linear<T>(f1, st));
+        ASTL_HIP(launch_gelu<T>(pre, h, nullptr, rows * Hd, st));
+    }
     LinearArgs f2{};
     f2.a1 = h; f2.lda1 = Hd; f2.w = p->w_fc2; f2.w_sn = Hd; f2.w_sk = 1; f2.bias = p->b_fc2;
     f2.add = x1; f2.ldadd = C;
@@ -514,12 +514,19 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         LinearArgs f1{};
         f1.a1 = xn; f1.lda1 = C; f1.w = p->w_fc1; f1.w_sn = C; f1.w_sk = 1; f1.bias = p->b_fc1;
         f1.out = pre; f1.ldout = Hd; f1.rows = rows; f1.N = Hd; f1.K = C; f1.prof_id = K_FC1_LINEAR;
-        ASTL_HIP(launch_linear<T>(f1, st));
-        ASTL_HIP(launch_gelu<T>(pre, h, nullptr, rows * Hd, st));
-        // dh = dy Wfc2;  d Wfc2 = dy^T h
+        if (sizeof(T) == 2 && linear_act_supported(f1)) {
+            f1.act = kActGelu; f1.out = h; f1.pre_out = pre;
+            ASTL_HIP(launch_linear<T>(f1, st));
+        } else {
+            ASTL_HIP(launch_linear<T>(f1, st));
+            ASTL_HIP(launch_gelu<T>(pre, h, nullptr, rows * Hd, st));
+        }
+        // dh = dy Wfc2 (through the GELU in the same launch where the kernel can);  d Wfc2 = dy^T h
         LinearArgs b2{};
         b2.a1 = dy; b2.lda1 = C; b2.w = p->w_fc2; b2.w_sn = 1; b2.w_sk = Hd;
         b2.out = dh; b2.ldout = Hd; b2.rows = rows; b2.N = Hd; b2.K = C; b2.prof_id = K_FC_DLINEAR;
+        const bool gelu_in_b2 = sizeof(T) == 2 && linear_act_supported(b2);
+        if (gelu_in_b2) { b2.act = kActGeluGrad; b2.aux = pre; b2.ldaux = Hd; }
         ASTL_HIP(launch_linear<T>(b2, st));
         WgradArgs w2{};
         w2.dout = dy; w2.lddout = C; w2.a1 = h; w2.lda1 = Hd;
@@ -527,7 +534,7 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
         ASTL_HIP(launch_wgrad<T>(w2, st));
         // through the GELU, then d Wfc1 = dpre^T LN_2(x1) and d LN_2(x1) = dpre Wfc1
-        ASTL_HIP(launch_gelu<T>(pre, nullptr, dh, rows * Hd, st));
+        if (!gelu_in_b2) ASTL_HIP(launch_gelu<T>(pre, nullptr, dh, rows * Hd, st));
         WgradArgs w1{};
         w1.dout = dh; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
         w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;

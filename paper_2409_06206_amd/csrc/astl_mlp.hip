@@ -16,6 +16,7 @@
 // first product takes the plain normalised row.
 #include "astl_mlp.h"
 #include "mfma.h"
+#include "staged_kernels.h"
 #include "profile.h"
 
 namespace gswa {
@@ -27,20 +28,7 @@ constexpr int kMlpWaves = kMlpThreads / 64;
 constexpr int kFwdThreads = 512; // the forward needs few registers: eight wavefronts share one copy of the weights
 constexpr int kFwdWaves = kFwdThreads / 64;
 
-// Gaussian CDF Phi(t) and density phi(t): erf by the rational-times-exponential approximation
-// 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7); exp(-t^2/2) serves both.
-__device__ __forceinline__ void gauss(float t, float &Phi, float &phi)
-{
-    // exp(-t^2/2) as a power of two; with x = |t|/sqrt(2) the formula's 1/(1 + 0.3275911 x) is
-    // 1/(1 + 0.2316419 |t|), and its five coefficients are halved here: w = (1 - erf x)/2
-    const float e = __builtin_amdgcn_exp2f(t * t * -0.72134752044448170f);
-    const float k = __builtin_amdgcn_rcpf(fmaf(fabsf(t), 0.23164190f, 1.f));
-    const float poly = ((((0.5307027145f * k - 0.7265760135f) * k + 0.7107068705f) * k - 0.142248368f) * k + 0.127414796f) * k;
-    const float w = poly * e;
-    Phi = t >= 0.f ? 1.f - w : w;
-    phi = 0.39894228040143268f * e;
-}
-
+// (Gaussian CDF and density `gauss`: staged_kernels.h)
 __device__ __forceinline__ float bf(const bf16_t *p, long i) { return __uint_as_float((uint32_t)p[i].bits << 16); }
 
 // channel (or hidden feature) a lane's k-slot j of step s stands for

@@ -18,7 +18,38 @@ struct LinearArgs {
     void *out; long ldout;
     long rows; int N, K;
     int prof_id; // KernelId this launch is accounted under
+    // Activation folded into the store (only where linear_act_supported() says so; 0 = none):
+    //   kActGelu:     v' = the result rounded to the element type; out = GELU(v'), pre_out (may be null) = v'
+    //   kActGeluGrad: out = v' * GELU'(aux[t, n])
+    // i.e. a pass over the stored result folded into the store (GELU through `gauss` below).
+    int act;
+    void *pre_out;           // [rows, N], pitch ldout
+    const void *aux; long ldaux;
 };
+constexpr int kActGelu = 1, kActGeluGrad = 2;
+// true when launch_linear<bf16_t> runs this call on the kernel that implements `act`
+bool linear_act_supported(const LinearArgs &a);
+
+// Gaussian CDF Phi(t) and density phi(t): erf by the rational-times-exponential approximation
+// 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7); exp(-t^2/2) serves both.
+__device__ __forceinline__ void gauss(float t, float &Phi, float &phi)
+{
+    // exp(-t^2/2) as a power of two; with x = |t|/sqrt(2) the formula's 1/(1 + 0.3275911 x) is
+    // 1/(1 + 0.2316419 |t|), and its five coefficients are halved here: w = (1 - erf x)/2
+    const float e = __builtin_amdgcn_exp2f(t * t * -0.72134752044448170f);
+    const float k = __builtin_amdgcn_rcpf(fmaf(fabsf(t), 0.23164190f, 1.f));
+    const float poly = ((((0.5307027145f * k - 0.7265760135f) * k + 0.7107068705f) * k - 0.142248368f) * k + 0.127414796f) * k;
+    const float w = poly * e;
+    Phi = t >= 0.f ? 1.f - w : w;
+    phi = 0.39894228040143268f * e;
+}
+
+// GELU in its Gaussian-CDF form and its derivative Phi(t) + t phi(t)
+__device__ __forceinline__ float gelu_f(float t) { return 0.5f * t * (1.f + erff(t * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float t)
+{
+    return 0.5f * (1.f + erff(t * 0.70710678118654752f)) + t * 0.39894228040143268f * __expf(-0.5f * t * t);
+}
 
 // Atomic adds of many workgroups to one address serialise (tens of ns each), so the staged
 // backward accumulates every parameter gradient in kGradReplicas copies (a workgroup adds into

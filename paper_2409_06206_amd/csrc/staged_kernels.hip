@@ -254,7 +254,9 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
     const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
     const uint16_t *add = static_cast<const uint16_t *>(p.add);
     uint16_t *out = static_cast<uint16_t *>(p.out);
-    const bool out_even = !(reinterpret_cast<uintptr_t>(p.out) & 3);
+    uint16_t *pre_out = static_cast<uint16_t *>(p.pre_out);
+    const uint16_t *aux = static_cast<const uint16_t *>(p.aux);
+    const bool out_even = !(reinterpret_cast<uintptr_t>(p.out) & 3) && !(reinterpret_cast<uintptr_t>(p.pre_out) & 3);
     const long ntile = (p.rows + 15) / 16;
     for (long tile = (long)blockIdx.x * nwaves + wave; tile < ntile; tile += (long)gridDim.x * nwaves) {
         const long row = 16 * tile + l16;
@@ -321,7 +323,52 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
                     }
                 }
                 uint16_t *dst = out + row * p.ldout + n0;
-                if (n0 + 4 <= p.N && out_even && !((row * p.ldout + n0) & 1)) {
+                const bool pair_ok = n0 + 4 <= p.N && out_even && !((row * p.ldout + n0) & 1);
+                if (p.act) {
+                    // the activation of the value as a separate pass would read it back: rounded to bf16
+                    float r[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) r[r4] = __uint_as_float((uint32_t)f32_to_bf16_bits(v[r4]) << 16);
+                    if (p.act == kActGelu) {
+                        if (pre_out) {
+                            uint16_t *pd = pre_out + row * p.ldout + n0;
+                            if (pair_ok) {
+                                reinterpret_cast<uint32_t *>(pd)[0] = pack_bf16x2(r[0], r[1]);
+                                reinterpret_cast<uint32_t *>(pd)[1] = pack_bf16x2(r[2], r[3]);
+                            } else {
+#pragma unroll
+                                for (int r4 = 0; r4 < 4; ++r4)
+                                    if (n0 + r4 < p.N) pd[r4] = f32_to_bf16_bits(r[r4]);
+                            }
+                        }
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            float Phi, phi;
+                            gauss(r[r4], Phi, phi);
+                            v[r4] = r[r4] * Phi;
+                        }
+                    } else {
+                        float tv[4];
+                        const uint16_t *ap = aux + row * p.ldaux + n0;
+                        if (n0 + 4 <= p.N && !(reinterpret_cast<uintptr_t>(ap) & 3)) { // the four as two dwords
+                            const uint32_t a01 = reinterpret_cast<const uint32_t *>(ap)[0];
+                            const uint32_t a23 = reinterpret_cast<const uint32_t *>(ap)[1];
+                            tv[0] = bf16_lo(a01); tv[1] = bf16_hi(a01); tv[2] = bf16_lo(a23); tv[3] = bf16_hi(a23);
+                        } else {
+#pragma unroll
+                            for (int r4 = 0; r4 < 4; ++r4)
+                                tv[r4] = n0 + r4 < p.N ? __uint_as_float((uint32_t)ap[r4] << 16) : 0.f;
+                        }
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const float t = tv[r4];
+                            float Phi, phi;
+                            gauss(t, Phi, phi);
+                            v[r4] = r[r4] * fmaf(t, phi, Phi);
+                        }
+                    }
+                }
+                if (pair_ok) {
                     uint32_t *d32 = reinterpret_cast<uint32_t *>(dst);
                     d32[0] = pack_bf16x2(v[0], v[1]);
                     d32[1] = pack_bf16x2(v[2], v[3]);
@@ -412,14 +459,18 @@ static hipError_t launch_linear_mfma(const LinearArgs &a, const LinearArgs *b, i
     return launch_linear_mfma_t<18, 4>(a, b, prof_id, zero, nzero, s);
 }
 
+bool linear_act_supported(const LinearArgs &a) { return a.rows > 0 && a.N > 0 && linear_mfma_ok(a) && linear_wide_ok(a); }
+
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0) return hipSuccess;
     if constexpr (sizeof(T) == 2) {
         if (linear_mfma_ok(a) && linear_wide_ok(a))
             return (a.K + 31) / 32 <= 6 ? launch_linear_wide_t<6, 1024>(a, s) : launch_linear_wide_t<12, 512>(a, s);
+        if (a.act) return hipErrorInvalidValue; // (callers ask linear_act_supported first)
         if (linear_mfma_ok(a)) return launch_linear_mfma(a, nullptr, a.prof_id, nullptr, 0, s);
     }
+    if (a.act) return hipErrorInvalidValue;
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
     KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(linear_kernel<T>, grid, dim3(kThreads), 0, s, a);

@@ -151,24 +151,14 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     // lane group q holds channels 32 ks + 8 q .. + 7 (one 16-byte piece of the row)
     uint4 xh[KS][4];
     uint4 ah[KS][4]; // the previous group's output, added when the loads have landed
-    // the x slice of this wave's next window, fetched under the last head where the registers that live
-    // across a window (x, the cascade input, dO, the table-gradient sums and this) leave room for it
-    constexpr bool PREFETCH = KS * 16 * (GI > 0 ? 3 : 2) + HG * (28 + 16) <= 240;
-    uint4 xnx[PREFETCH ? KS : 1][4];
-    auto load_x = [&](const uint32_t (&tk)[4], auto &xd) {
+    auto load_x = [&](const uint32_t (&tk)[4]) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) xd[ks][t] = bload128(xbuf, tk[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
-    };
-    auto load_a = [&]() {
-        if (casc_in) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    ah[ks][t] = bload128(abuf, tok[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
-        }
+            for (int t = 0; t < 4; ++t) {
+                xh[ks][t] = bload128(xbuf, tk[t] + 2u * (GI * CG) + 64u * ks + 16u * q, 0u);
+                if (casc_in) ah[ks][t] = bload128(abuf, tk[t] + 2u * ((GI > 0 ? GI - 1 : 0) * CG) + 64u * ks + 16u * q, 0u);
+            }
     };
     auto add_cascade = [&]() { // and the channels past the group's width, which belong to the next slice, cleared
 #pragma unroll
@@ -245,14 +235,8 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
         const bool more = round + 1 < rounds;
         if (active) {
             window_tokens(win, tok, true);
-            if (!PREFETCH || round == 0) load_x(tok, xh); // lands under the dO products
-            else if constexpr (PREFETCH) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) xh[ks][t] = xnx[ks][t];
-            }
-            load_a();
+            // (the rows of a later window are on their way since the last head of the window before)
+            if (round == 0) load_x(tok); // lands under the dO products
         }
         uint2 dOb[HG][2][4]; // dO^T of the group's heads, packed T-form tiles
 
@@ -348,12 +332,6 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                             for (int ks = 0; ks < KS; ++ks) fdst[(t * KS + ks) * 64] = xh[ks][t];
                     }
                 }
-                if (PREFETCH && hl == HG - 1 && more && win + stride < g.nW) {
-                    // the x slice of this wave's next window: a head's time to land
-                    uint32_t tkn[4];
-                    window_tokens(win + stride, tkn, false);
-                    if constexpr (PREFETCH) load_x(tkn, xnx);
-                }
                 if (active) {
                     // ---- Q^T, K^T, V^T exactly as the forward computes them (rows = head features) ----
                     uint2 Qb[2][4], Kb[2][4], Vb[2][4];
@@ -392,6 +370,13 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                                 else Vb[et][t] = pk;
                             }
                         __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (hl == HG - 1 && more && win + stride < g.nW) {
+                        // F has served its last product of this window: the x slice and the cascade input of this
+                        // wave's next window go into the same registers, with the rest of the head to land
+                        uint32_t tkn[4];
+                        window_tokens(win + stride, tkn, false);
+                        load_x(tkn);
                     }
                     // N-form (rows = tokens, column = feature) of K for dQ
                     uint2 KN[2][4];
