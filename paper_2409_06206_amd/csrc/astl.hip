@@ -532,6 +532,8 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w2.dout = dy; w2.lddout = C; w2.a1 = h; w2.lda1 = Hd;
         w2.dw = rep + o_w2; w2.db = rep + o_b2; w2.rep_stride = P; w2.reps = kGradReplicas;
         w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
+        // (dn and dx1 are not written before the last weight gradient is done: their slots serve as scratch)
+        w2.scratch = ws + pl.act; w2.scratch_bytes = 2 * pl.act;
         ASTL_HIP(launch_wgrad<T>(w2, st));
         // through the GELU, then d Wfc1 = dpre^T LN_2(x1) and d LN_2(x1) = dpre Wfc1
         if (!gelu_in_b2) ASTL_HIP(launch_gelu<T>(pre, nullptr, dh, rows * Hd, st));
@@ -539,6 +541,7 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w1.dout = dh; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
         w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
         w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
+        w1.scratch = ws + pl.act; w1.scratch_bytes = 2 * pl.act;
         ASTL_HIP(launch_wgrad<T>(w1, st));
         LinearArgs b1{};
         b1.a1 = dh; b1.lda1 = Hd; b1.w = p->w_fc1; b1.w_sn = 1; b1.w_sk = C;

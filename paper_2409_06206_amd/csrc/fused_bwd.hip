@@ -713,32 +713,41 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 }
 
 // (segment table: ReduceOut, fused.h)
+// A block sums 32 * V consecutive entries over all partial vectors: thread (column group, slice) adds the
+// partials slice, slice + 32, ... (V entries each, one load of 4 V bytes: with V = 2 a wave half reads 256
+// contiguous bytes of a partial vector), the 32 slices meet in LDS in a fixed order.
+template <int V>
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
                                                                int n, ReduceOut out, int accumulate)
 {
     constexpr int SL = 32; // slices of the partials, one per wave half: few additions per thread, all loads in flight
-    __shared__ float red[SL][33];
+    typedef float vec_t __attribute__((ext_vector_type(V)));
+    __shared__ float red[SL][32 * V + 1];
     const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
-    const int i = blockIdx.x * 32 + col;
-    float acc = 0.f;
-    if (i < n) {
-        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int i0 = (blockIdx.x * 32 + col) * V;
+    vec_t acc = 0.f;
+    if (i0 < n) {
+        vec_t a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = 0.f;
         int w = slice;
         for (; w + 7 * SL < nparts; w += 8 * SL) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(w + SL * u) * n + i];
+            for (int u = 0; u < 8; ++u) a[u] += *reinterpret_cast<const vec_t *>(part + (size_t)(w + SL * u) * n + i0);
         }
-        for (; w < nparts; w += SL) a[0] += part[(size_t)w * n + i];
+        for (; w < nparts; w += SL) a[0] += *reinterpret_cast<const vec_t *>(part + (size_t)w * n + i0);
         acc = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     }
-    red[slice][col] = acc;
+#pragma unroll
+    for (int v = 0; v < V; ++v) red[slice][col * V + v] = acc[v];
     __syncthreads();
-    if (slice == 0 && i < n) {
+    const int c = threadIdx.x, i = blockIdx.x * 32 * V + c;
+    if (c < 32 * V && i < n) {
         float t[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            t[u] = (red[4 * u][col] + red[4 * u + 1][col]) + (red[4 * u + 2][col] + red[4 * u + 3][col]);
-        acc = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+            t[u] = (red[4 * u][c] + red[4 * u + 1][c]) + (red[4 * u + 2][c] + red[4 * u + 3][c]);
+        const float sum = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
         int seg = 0;
         while (seg < out.nseg - 1 && i >= out.begin[seg + 1]) ++seg;
         const int k = i - out.begin[seg];
@@ -747,53 +756,73 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
             const int hd = k / out.tbl_entries, e = k - hd * out.tbl_entries;
             dst = out.ptr[seg] + e * out.tbl_stride + out.tbl_head0 + hd;
         }
-        *dst = accumulate ? *dst + acc : acc;
+        *dst = accumulate ? *dst + sum : sum;
     }
 }
 
-// d w_proj, d b_proj of wide layers: dY^T [A | 1] over plain token rows, 64 tokens per pass.
-// Both operands are moved into [channel][token] LDS rows by selector MFMAs; wave w owns output
-// row tiles w*RW .. w*RW+RW-1 and all column tiles; the spare column C carries the bias sums.
+// d w_proj, d b_proj of wide layers: dY^T [A | 1] over plain token rows, 128 tokens per pass of a workgroup
+// of eight waves.  Both operands are moved into [channel][token] LDS rows by selector MFMAs; wave w owns
+// the output row tiles (w % 4) * RW .. + RW - 1 and half of the column tiles; the spare column C carries the
+// bias sums.  The next pass's rows are fetched under the products of the pass in hand.
+template <class Cf> struct WprojGradCfg {
+    static constexpr int C = Cf::C, KSC = Cf::KSC;
+    static constexpr int OTP = (C + 15) / 16, CTP = C / 16 + 1;
+    static constexpr int NWV = 8, TOK = 16 * NWV;
+    static constexpr int RW = (OTP + 3) / 4;       // row tiles per wave (four row groups)
+    static constexpr int CW = (CTP + 1) / 2;       // column tiles per wave (two column halves)
+    static constexpr int LW = TOK + 8;             // pitch (bf16) of the [channel][128 tokens] rows
+    static constexpr size_t LDS_BYTES = (size_t)16 * (OTP + CTP) * LW * 2;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
 template <class Cf>
-__global__ __launch_bounds__(256, 2) void wproj_grad_kernel(long T, const bf16_t *__restrict__ dy,
+__global__ __launch_bounds__(512, 1) void wproj_grad_kernel(long T, const bf16_t *__restrict__ dy,
                                                             const bf16_t *__restrict__ attn,
                                                             float *__restrict__ part)
 {
-    using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
-    constexpr int C = Cf::C, KSC = Cf::KSC, OTP = B::OTP, CTP = B::CTP, LW = B::LW;
-    constexpr int RW = (OTP + 3) / 4;
+    using P = WprojGradCfg<Cf>;
+    constexpr int C = Cf::C, KSC = Cf::KSC, OTP = P::OTP, CTP = P::CTP, LW = P::LW, RW = P::RW, CW = P::CW;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint16_t *dybuf = reinterpret_cast<uint16_t *>(lds);
     uint16_t *abuf = dybuf + 16 * OTP * LW;
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rg = wv & 3, ch = wv >> 2;
     const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
 
-    f32x4 acc[RW][CTP];
+    f32x4 acc[RW][CW];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
 #pragma unroll
-        for (int ct = 0; ct < CTP; ++ct) acc[r][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < CW; ++c) acc[r][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const long ntile = T / 64;
-    for (long tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
-        const long tok = tile * 64 + 16 * wv + l16;
-        const uint32_t *dyrow = reinterpret_cast<const uint32_t *>(dy + tok * C);
-        const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + tok * C);
-        uint4 dyf[KSC], af[KSC];
+    // this lane's token of a pass as operands: channels 32 ks + 8 q .. + 7 of dy and of the saved outputs
+    auto load_rows = [&](long tile, uint4 (&dyf)[KSC], uint4 (&af)[KSC]) {
+        const long tok = tile * P::TOK + 16 * wv + l16;
+        const bool ok = tok < T;
+        const uint32_t *dyrow = reinterpret_cast<const uint32_t *>(dy + (ok ? tok : 0) * C);
+        const uint32_t *arow = reinterpret_cast<const uint32_t *>(attn + (ok ? tok : 0) * C);
 #pragma unroll
         for (int ks = 0; ks < KSC; ++ks) {
             uint32_t dv[4], av[4];
 #pragma unroll
             for (int dw = 0; dw < 4; ++dw) {
                 const int c = 32 * ks + 8 * q + 2 * dw;
-                dv[dw] = c < C ? dyrow[c >> 1] : 0u;
+                dv[dw] = c < C ? dyrow[c >> 1] : 0u; // (unconditional loads of a valid row: they merge into 16-byte ones)
                 av[dw] = c < C ? arow[c >> 1] : 0u;
             }
-            dyf[ks] = make_uint4(dv[0], dv[1], dv[2], dv[3]);
-            af[ks] = make_uint4(av[0], av[1], av[2], av[3]);
+            dyf[ks] = ok ? make_uint4(dv[0], dv[1], dv[2], dv[3]) : make_uint4(0u, 0u, 0u, 0u);
+            af[ks] = ok ? make_uint4(av[0], av[1], av[2], av[3]) : make_uint4(0u, 0u, 0u, 0u);
         }
-        __syncthreads(); // the previous tile's rows are consumed
+    };
+
+    const long ntile = (T + P::TOK - 1) / P::TOK;
+    uint4 dyf[KSC], af[KSC], dyn[KSC], an[KSC];
+    if ((long)blockIdx.x < ntile) load_rows(blockIdx.x, dyf, af);
+    for (long tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        const bool more = tile + (long)gridDim.x < ntile;
+        if (more) load_rows(tile + gridDim.x, dyn, an);
+        __syncthreads(); // the previous pass's rows are consumed
 #pragma unroll
         for (int ot = 0; ot < OTP; ++ot) {
             const f32x4 tN = mma32(dyf[ot >> 1], select_slot(16 * ot + l16, 32 * (ot >> 1) + 8 * q),
@@ -806,46 +835,53 @@ __global__ __launch_bounds__(256, 2) void wproj_grad_kernel(long T, const bf16_t
             if ((ct >> 1) < KSC)
                 tN = mma32(af[(ct >> 1) < KSC ? (ct >> 1) : 0], select_slot(16 * ct + l16, 32 * (ct >> 1) + 8 * q), tN);
             uint2 pk = pack_bf16x4(tN);
-            if (16 * ct + l16 == C) pk = ones2;
+            if (16 * ct + l16 == C) pk = ones2; // (tokens past the end have dy = 0)
             *reinterpret_cast<uint2 *>(abuf + (16 * ct + l16) * LW + 16 * wv + 4 * q) = pk;
         }
         __syncthreads();
-        uint4 afr[RW][2];
 #pragma unroll
-        for (int r = 0; r < RW; ++r) {
-            const int ot = wv * RW + r;
-            const uint16_t *ar = dybuf + (16 * (ot < OTP ? ot : 0) + l16) * LW + 8 * q;
+        for (int kp = 0; kp < P::TOK / 32; ++kp) {
+            uint4 afr[RW];
 #pragma unroll
-            for (int kp = 0; kp < 2; ++kp)
-                afr[r][kp] = cat(*reinterpret_cast<const uint2 *>(ar + 32 * kp),
-                                 *reinterpret_cast<const uint2 *>(ar + 32 * kp + 4));
+            for (int r = 0; r < RW; ++r) {
+                const int ot = rg * RW + r;
+                const uint16_t *ar = dybuf + (16 * (ot < OTP ? ot : 0) + l16) * LW + 32 * kp + 8 * q;
+                afr[r] = cat(*reinterpret_cast<const uint2 *>(ar), *reinterpret_cast<const uint2 *>(ar + 4));
+            }
+#pragma unroll
+            for (int c = 0; c < CW; ++c) {
+                const int ct = ch * CW + c;
+                const uint16_t *br = abuf + (16 * (ct < CTP ? ct : 0) + l16) * LW + 32 * kp + 8 * q;
+                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br), *reinterpret_cast<const uint2 *>(br + 4));
+#pragma unroll
+                for (int r = 0; r < RW; ++r) acc[r][c] = mma32(afr[r], bf, acc[r][c]);
+            }
         }
+        if (more) {
 #pragma unroll
-        for (int ct = 0; ct < CTP; ++ct) {
-            const uint16_t *br = abuf + (16 * ct + l16) * LW + 8 * q;
-#pragma unroll
-            for (int kp = 0; kp < 2; ++kp) {
-                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br + 32 * kp),
-                                     *reinterpret_cast<const uint2 *>(br + 32 * kp + 4));
-#pragma unroll
-                for (int r = 0; r < RW; ++r) acc[r][ct] = mma32(afr[r][kp], bf, acc[r][ct]);
+            for (int ks = 0; ks < KSC; ++ks) {
+                dyf[ks] = dyn[ks];
+                af[ks] = an[ks];
             }
         }
     }
     float *mine = part + (size_t)blockIdx.x * (C * C + C); // [d w_proj | d b_proj]
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
-        const int ot = wv * RW + r;
+        const int ot = rg * RW + r;
         if (ot < OTP) {
 #pragma unroll
-            for (int ct = 0; ct < CTP; ++ct) {
-                const int c = 16 * ct + l16;
+            for (int c = 0; c < CW; ++c) {
+                const int ct = ch * CW + c;
+                const int col = 16 * ct + l16;
+                if (ct < CTP) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int o = 16 * ot + 4 * q + j;
-                    if (o < C) {
-                        if (c < C) mine[o * C + c] = acc[r][ct][j];
-                        else if (c == C) mine[C * C + o] = acc[r][ct][j];
+                    for (int j = 0; j < 4; ++j) {
+                        const int o = 16 * ot + 4 * q + j;
+                        if (o < C) {
+                            if (col < C) mine[o * C + col] = acc[r][c][j];
+                            else if (col == C) mine[C * C + o] = acc[r][c][j];
+                        }
                     }
                 }
             }
@@ -893,7 +929,11 @@ struct GradOut {
 hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s)
 {
     KernelTimer kt(K_REDUCE, s);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);
+    // (pairs of entries where every partial vector starts on an 8-byte boundary)
+    if (n % 2 == 0 && reinterpret_cast<uintptr_t>(part) % 8 == 0)
+        hipLaunchKernelGGL(reduce_partials_kernel<2>, dim3((n + 63) / 64), dim3(1024), 0, s, part, nparts, n, out, accumulate);
+    else
+        hipLaunchKernelGGL(reduce_partials_kernel<1>, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);
     return hipGetLastError();
 }
 
@@ -981,8 +1021,8 @@ template <class Cf>
 hipError_t run_wproj_grad(const Geom &g, int grid, const bf16_t *dy, const bf16_t *attn, float *part, float *dw_proj,
                           float *db_proj, int accumulate, hipStream_t s)
 {
-    using B = BwdCfg<Cf, 0, Cf::HEADS, false>;
-    constexpr size_t lds = (size_t)16 * (B::OTP + B::CTP) * B::LW * 2;
+    using P = WprojGradCfg<Cf>;
+    constexpr size_t lds = P::LDS_BYTES;
     auto kern = wproj_grad_kernel<Cf>;
     static bool attr_done = false;
     if (!attr_done && lds > 64 * 1024) {
@@ -993,7 +1033,7 @@ hipError_t run_wproj_grad(const Geom &g, int grid, const bf16_t *dy, const bf16_
     }
     {
         KernelTimer kt(K_WPROJ_GRAD, s);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g.T, dy, attn, part);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * P::NWV), lds, s, g.T, dy, attn, part);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -71,6 +71,8 @@ struct WgradArgs {
     int prof_id;
     int exclusive; // nonzero: at most `reps` splits of the token range, so that every copy receives exactly
                    // one addition per entry (onto zero) and the sum over the copies has a fixed order
+    void *scratch; size_t scratch_bytes; // optional (may be null): device memory free for the duration of the call;
+                                         // wide layers then take the streaming kernel, which needs no atomics
 };
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);

@@ -3,6 +3,7 @@
 // write token-major buffers in the tokens' own (unshifted) order; the cyclic shift and the
 // window partition exist only as the index map window_token().
 #include "staged_kernels.h"
+#include "fused.h"
 #include "mfma.h"
 #include <cmath>
 
@@ -796,11 +797,203 @@ static hipError_t launch_wgrad_mfma(const WgradArgs &a, const WgradArgs *b, cons
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Weight gradients of wide fully connected layers (Eq. 5 at C = 180, hidden 360): the 64 x 64 tiling
+// above reads every row once per tile row and tile column and pays N*K memory-side atomic adds per
+// split.  Here the gradient [N][K | bias] is cut into blocks of NB x KB entries (two for these layers)
+// and a workgroup of eight waves owns a whole block for a share of the rows, which it streams once, 128
+// tokens per pass: both operands are moved into [channel][token] LDS rows by selector MFMAs, wave w
+// accumulates the row tiles of row group w % 4 against one half of the column tiles in registers over
+// all its passes.  The workgroups of a share store into one partial array [N*K | N]; the library's
+// fixed-order sum adds the arrays onto copy 0 of the gradient (no atomics: run-to-run identical).
+// ---------------------------------------------------------------------------------------
+template <int NB, int KB> struct WgradStreamCfg {
+    static constexpr int NT = (NB + 15) / 16, KT = KB / 16 + 1;     // 16-row tiles of dout^T; of [a | 1]^T (column KB: ones)
+    static constexpr int KSN = (NB + 31) / 32, KSK = (KB + 31) / 32; // K=32 operand steps along a row of dout, of a
+    static constexpr int NWV = 8, TOK = 16 * NWV;
+    static constexpr int RW = (NT + 3) / 4, CW = (KT + 1) / 2;
+    static constexpr int LW = TOK + 8;                               // pitch (bf16) of the [channel][128 tokens] rows
+    static constexpr size_t LDS_BYTES = (size_t)16 * (NT + KT) * LW * 2;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(NB % 2 == 0 && KB % 2 == 0, "dword-granular row reads");
+};
+
+// block (n0, k0) of the gradient: dout and a point at the block's first column; `bias`: this block also
+// carries the bias sums (column KB of [a | 1])
+template <int NB, int KB>
+__global__ __launch_bounds__(512, 1) void wgrad_stream_kernel(long rows, const bf16_t *__restrict__ dout, long lddout,
+                                                              const bf16_t *__restrict__ a, long lda,
+                                                              float *__restrict__ part, int N, int K)
+{
+    using P = WgradStreamCfg<NB, KB>;
+    constexpr int NT = P::NT, KT = P::KT, KSN = P::KSN, KSK = P::KSK, LW = P::LW, RW = P::RW, CW = P::CW;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint16_t *gbuf = reinterpret_cast<uint16_t *>(lds);  // dout^T rows [feature n][token]
+    uint16_t *abuf = gbuf + 16 * NT * LW;                 // [a | 1]^T rows [channel k][token]
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rg = wv & 3, ch = wv >> 2;
+    const int nkb = K / KB;                                // blocks along K; block index = nb * nkb + kb
+    const int n0 = ((int)blockIdx.y / nkb) * NB, k0 = ((int)blockIdx.y % nkb) * KB;
+    const bool bias = k0 == 0;
+    dout += n0;
+    a += k0;
+    const uint2 ones2 = make_uint2(0x3f803f80u, 0x3f803f80u);
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    f32x4 acc[RW][CW];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int c = 0; c < CW; ++c) acc[r][c] = zero4;
+
+    const long ntile = (rows + P::TOK - 1) / P::TOK;
+    for (long tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        // this lane's token of the pass as operands: features 32 ks + 8 q .. + 7 of its row (a valid row is
+        // read unconditionally so that the dwords merge into wide loads; rows past the end count as zero)
+        const long tok = tile * P::TOK + 16 * wv + l16;
+        const bool ok = tok < rows;
+        const uint32_t *grow = reinterpret_cast<const uint32_t *>(dout + (ok ? tok : 0) * lddout);
+        const uint32_t *arow = reinterpret_cast<const uint32_t *>(a + (ok ? tok : 0) * lda);
+        uint4 gf[KSN], af[KSK];
+#pragma unroll
+        for (int ks = 0; ks < KSN; ++ks) {
+            uint32_t v[4];
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int c = 32 * ks + 8 * q + 2 * dw;
+                v[dw] = c < NB ? grow[c >> 1] : 0u;
+            }
+            gf[ks] = ok ? make_uint4(v[0], v[1], v[2], v[3]) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KSK; ++ks) {
+            uint32_t v[4];
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int c = 32 * ks + 8 * q + 2 * dw;
+                v[dw] = c < KB ? arow[c >> 1] : 0u;
+            }
+            af[ks] = ok ? make_uint4(v[0], v[1], v[2], v[3]) : make_uint4(0u, 0u, 0u, 0u);
+        }
+        __syncthreads(); // the previous pass's rows are consumed
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const f32x4 tN = mma32(gf[nt >> 1], select_slot(16 * nt + l16, 32 * (nt >> 1) + 8 * q), zero4);
+            *reinterpret_cast<uint2 *>(gbuf + (16 * nt + l16) * LW + 16 * wv + 4 * q) = pack_bf16x4(tN);
+        }
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            f32x4 tN = zero4;
+            if ((kt >> 1) < KSK) tN = mma32(af[(kt >> 1) < KSK ? (kt >> 1) : 0], select_slot(16 * kt + l16, 32 * (kt >> 1) + 8 * q), zero4);
+            uint2 pk = pack_bf16x4(tN);
+            if (16 * kt + l16 == KB) pk = bias ? ones2 : make_uint2(0u, 0u); // (rows past the end have dout = 0)
+            *reinterpret_cast<uint2 *>(abuf + (16 * kt + l16) * LW + 16 * wv + 4 * q) = pk;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kp = 0; kp < P::TOK / 32; ++kp) {
+            uint4 afr[RW];
+#pragma unroll
+            for (int r = 0; r < RW; ++r) {
+                const int nt = rg * RW + r;
+                const uint16_t *ar = gbuf + (16 * (nt < NT ? nt : 0) + l16) * LW + 32 * kp + 8 * q;
+                afr[r] = cat(*reinterpret_cast<const uint2 *>(ar), *reinterpret_cast<const uint2 *>(ar + 4));
+            }
+#pragma unroll
+            for (int c = 0; c < CW; ++c) {
+                const int kt = ch * CW + c;
+                const uint16_t *br = abuf + (16 * (kt < KT ? kt : 0) + l16) * LW + 32 * kp + 8 * q;
+                const uint4 bf = cat(*reinterpret_cast<const uint2 *>(br), *reinterpret_cast<const uint2 *>(br + 4));
+#pragma unroll
+                for (int r = 0; r < RW; ++r) acc[r][c] = mma32(afr[r], bf, acc[r][c]);
+            }
+        }
+    }
+    float *mine = part + (size_t)blockIdx.x * ((size_t)N * K + N); // the share's partial array [d w | d b]
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const int nt = rg * RW + r;
+        if (nt < NT) {
+#pragma unroll
+            for (int c = 0; c < CW; ++c) {
+                const int kt = ch * CW + c;
+                const int col = 16 * kt + l16;
+                if (kt < KT) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int n = 16 * nt + 4 * q + j;
+                        if (n < NB) {
+                            if (col < KB) mine[(size_t)(n0 + n) * K + k0 + col] = acc[r][c][j];
+                            else if (col == KB && bias) mine[(size_t)N * K + n0 + n] = acc[r][c][j];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+constexpr int kWgradStreamBlock = 180; // block side of the streaming kernel's one instance
+
+// Shares of the rows (one workgroup per share and block) for these arguments, 0 where the streaming kernel
+// does not apply: N or K not whole blocks, a second addend, rows that are not dword-aligned, or a scratch
+// too small for a useful share of the chip.
+static int wgrad_stream_shares(const WgradArgs &a)
+{
+    constexpr int B = kWgradStreamBlock;
+    if (!a.scratch || a.a2 || a.rows < 4096) return 0;
+    if (a.N % B || a.K % B || (long)a.N * a.K < 2L * B * B) return 0;
+    if (a.lddout % 2 || a.lda1 % 2 || (reinterpret_cast<uintptr_t>(a.dout) | reinterpret_cast<uintptr_t>(a.a1)) % 4) return 0;
+    if (reinterpret_cast<uintptr_t>(a.scratch) % 8) return 0;
+    const size_t per = ((size_t)a.N * a.K + a.N) * 4;
+    const int blocks = (a.N / B) * (a.K / B);
+    long shares = (long)(a.scratch_bytes / per);
+    const long passes = (a.rows + 127) / 128;
+    const long want = device_cu_count() / blocks; // one workgroup per compute unit
+    if (shares > want) shares = want;
+    if (shares > passes) shares = passes;
+    return shares >= 16 ? (int)shares : 0;
+}
+
+static hipError_t run_wgrad_stream(const WgradArgs &a, int shares, hipStream_t s)
+{
+    constexpr int B = kWgradStreamBlock;
+    using P = WgradStreamCfg<B, B>;
+    auto kern = wgrad_stream_kernel<B, B>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)P::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    float *part = static_cast<float *>(a.scratch);
+    {
+        KernelTimer kt(a.prof_id, s);
+        hipLaunchKernelGGL(kern, dim3(shares, (a.N / B) * (a.K / B)), dim3(64 * P::NWV), P::LDS_BYTES, s, a.rows,
+                           static_cast<const bf16_t *>(a.dout), a.lddout, static_cast<const bf16_t *>(a.a1), a.lda1, part,
+                           a.N, a.K);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int total = a.N * a.K + a.N;
+    ReduceOut out{};
+    out.ptr[0] = a.dw; out.begin[0] = 0;
+    out.ptr[1] = a.db; out.begin[1] = a.N * a.K;
+    out.begin[2] = total;
+    out.nseg = 2;
+    return launch_reduce(part, shares, total, out, 1, s); // onto copy 0 of the gradient
+}
+
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
     if (a.reps < 1) return hipErrorInvalidValue;
-    if constexpr (sizeof(T) == 2) return launch_wgrad_mfma(a, nullptr, nullptr, s);
+    if constexpr (sizeof(T) == 2) {
+        if (const int shares = wgrad_stream_shares(a)) return run_wgrad_stream(a, shares, s);
+        return launch_wgrad_mfma(a, nullptr, nullptr, s);
+    }
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
     long splits = 2048 / (long)(tn * tk);
     const long max_splits = (a.rows + 255) / 256;

@@ -13,6 +13,7 @@ template <int C> struct WindowRows {
     // a few bytes of slack behind the last row, where operand reads of a zero-padded last K step reach
     static constexpr size_t BYTES = (size_t)CHUNKS * 16 + 64;
     static_assert((8 * 2 * C) % 16 == 0, "an image row of a window is whole 16-byte pieces");
+    static_assert(ROW_CHUNKS >= 64, "fetch_window_rows advances at most one image row per instruction");
 };
 
 // The rows [64 tokens][C] (bf16) of window `win` of tensor `base` -> `stage`, in memory order: 8 image

@@ -95,6 +95,18 @@ def test_benchmark_shape_pair_against_the_oracle(name):
         parity.check_block(astl_oracle, seed=synth.LAYER_SEED0 + li, **case)
 
 
+@pytest.mark.parametrize("case", [
+    dict(B=2, H=64, W=32, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
+    # 4800 tokens: 37 passes of 128 and a ragged one
+    dict(B=3, H=40, W=40, C=180, heads=6, groups=3, window=8, shift=0, dtype="bf16", hidden=360),
+], ids=_id)
+def test_wide_layer_with_enough_tokens_for_the_streaming_weight_gradients(case):
+    """C = 180, hidden 360 from 4096 tokens on: the MLP's weight gradients come from the kernel that streams
+    the rows once and sums per-workgroup partial arrays in a fixed order."""
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, **case)
+
+
 @pytest.mark.parametrize("case", [SMALL[0], SMALL[8]], ids=_id)
 def test_groups_without_the_cascade(case):
     print("case", case, flush=True)
