@@ -282,6 +282,9 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         wq.db = rep + o_bq + (size_t)grp * Rg;
         wq.rep_stride = P; wq.reps = nreps; wq.exclusive = det;
         wq.rows = g.T; wq.N = Rg; wq.K = Cg; wq.prof_id = K_QKV_WGRAD;
+        // (q|k|v of the group has served its last read: its buffer is scratch for the weight gradients)
+        wq.scratch = qkv; wq.scratch_bytes = sz.qkv;
+        wp.scratch = qkv; wp.scratch_bytes = sz.qkv;
         GSWA_HIP(launch_wgrad_group<T>(wq, grp == G - 1 ? &wp : nullptr, lx, st));
     }
     ReplicaSum rs{};

@@ -943,7 +943,7 @@ static int wgrad_stream_shares(const WgradArgs &a)
 {
     constexpr int B = kWgradStreamBlock;
     if (!a.scratch || a.a2 || a.rows < 4096) return 0;
-    if (a.N % B || a.K % B || (long)a.N * a.K < 2L * B * B) return 0;
+    if (a.N % B || a.K % B) return 0;
     if (a.lddout % 2 || a.lda1 % 2 || (reinterpret_cast<uintptr_t>(a.dout) | reinterpret_cast<uintptr_t>(a.a1)) % 4) return 0;
     if (reinterpret_cast<uintptr_t>(a.scratch) % 8) return 0;
     const size_t per = ((size_t)a.N * a.K + a.N) * 4;
@@ -1015,6 +1015,15 @@ template <typename T>
 hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const LinearArgs &lin, hipStream_t s)
 {
     if constexpr (sizeof(T) == 2) {
+        if (const int shares = wgrad_stream_shares(a)) {
+            // wide layers: the linear map on its own, the reductions from the streaming kernel (they use the
+            // same scratch one after the other)
+            hipError_t e = launch_linear<T>(lin, s);
+            if (e != hipSuccess) return e;
+            e = run_wgrad_stream(a, shares, s);
+            if (e != hipSuccess || !b) return e;
+            return launch_wgrad<T>(*b, s);
+        }
         const bool wg_ok = a.rows > 0 && a.N > 0 && a.K > 0 && a.reps >= 1 &&
                            (!b || (b->rows > 0 && b->N > 0 && b->K > 0 && b->reps >= 1));
         const bool lin_ok = lin.rows > 0 && lin.N > 0 && lin.N <= 64 && lin.K <= 64 && linear_mfma_ok(lin);
