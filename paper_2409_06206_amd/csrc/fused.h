@@ -133,7 +133,7 @@ hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &
 // Wide layers (C = 180, two or three groups, 8x8 windows), backward of the attention and of the QKV
 // projection, group by group in reverse order (wide_bwd.hip): one launch with one wavefront per
 // window recomputes the group's q, k, v and probabilities and leaves d(q|k|v) in scratch and the
-// bias-table gradient as per-wavefront partial sums; a second launch turns d(q|k|v) into the
+// bias-table gradient as per-workgroup partial sums; a second launch turns d(q|k|v) into the
 // group's dx slice (the cascade gradient of the group before, Eq. 8) and its weight gradients.
 // d w_proj / d b_proj are not produced here.
 bool wide_bwd_supported(const Geom &g);

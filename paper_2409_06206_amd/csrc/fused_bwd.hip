@@ -929,8 +929,10 @@ struct GradOut {
 hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s)
 {
     KernelTimer kt(K_REDUCE, s);
-    // (pairs of entries where every partial vector starts on an 8-byte boundary)
-    if (n % 2 == 0 && reinterpret_cast<uintptr_t>(part) % 8 == 0)
+    // (two or four entries per load where every partial vector starts on such a boundary)
+    if (n % 4 == 0 && reinterpret_cast<uintptr_t>(part) % 16 == 0)
+        hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((n + 127) / 128), dim3(1024), 0, s, part, nparts, n, out, accumulate);
+    else if (n % 2 == 0 && reinterpret_cast<uintptr_t>(part) % 8 == 0)
         hipLaunchKernelGGL(reduce_partials_kernel<2>, dim3((n + 63) / 64), dim3(1024), 0, s, part, nparts, n, out, accumulate);
     else
         hipLaunchKernelGGL(reduce_partials_kernel<1>, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);

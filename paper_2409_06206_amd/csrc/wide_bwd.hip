@@ -54,6 +54,7 @@ template <class Cf> struct WideBwdCfg {
     static_assert(OFF_W % 16 == 0 && OFF_STAGE % 16 == 0 && STAGE_BYTES % 16 == 0, "16-byte pieces");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(Cf::ET == 2 && Cf::D + 1 <= 32 && Cf::CG % Cf::D == 0, "heads of 17..31 channels");
+    static_assert(NWAVES == 4, "the table sums of four waves are added pairwise");
     // d(q|k|v) in scratch: fragment ((window * 4 + token tile) * HG + head of the group) * 3 + (q|k|v)
     static constexpr int FR_TILE = Cf::HG * 3;
     // second kernel
@@ -531,8 +532,11 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
     }
 
     // this wave's partial sums of the bias-table gradient (heads of this group; every wave writes): per head the
-    // 28 sums of every lane go through the wave's piece of LDS, and lane l collects entries l, l + 64, ...
-    float *mine = tpart + ((size_t)blockIdx.x * W::NWAVES + wv) * (HEADS * NTBL);
+    // 28 sums of every lane go through the wave's piece of LDS, and lane l collects entries l, l + 64, ...;
+    // the four waves' sums meet in LDS (the weight stream's buffers are free) and leave as one vector
+    float *tmeet = reinterpret_cast<float *>(lds + W::OFF_W);
+    float *mine = tmeet + (size_t)wv * (HG * NTBL);
+    static_assert((size_t)W::NWAVES * HG * NTBL * 4 <= 2 * W::UNIT_BYTES, "the waves' table sums fit the stream buffers");
 #pragma unroll
     for (int hl = 0; hl < HG; ++hl) {
 #pragma unroll
@@ -564,11 +568,15 @@ __global__ __launch_bounds__(256, 1) void wide_attn_bwd_kernel(Geom g, const bf1
                         acc += ok ? v : 0.f;
                     }
             }
-            if (e < NTBL) mine[(GI * HG + hl) * NTBL + e] = acc;
+            if (e < NTBL) mine[hl * NTBL + e] = acc;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
+    __syncthreads();
+    float *out = tpart + (size_t)blockIdx.x * (HEADS * NTBL) + GI * HG * NTBL;
+    for (int i = tid; i < HG * NTBL; i += W::NTHREADS)
+        out[i] = (tmeet[i] + tmeet[HG * NTBL + i]) + (tmeet[2 * HG * NTBL + i] + tmeet[3 * HG * NTBL + i]);
 }
 
 // The group's dx slice and weight gradients from d(q|k|v).  A workgroup of eight waves takes two windows
@@ -753,7 +761,7 @@ template <class Cf> struct WideBwdWs {
     static size_t part_bytes(const Geom &g) { return up((size_t)attn_grid(g, kSizingCus) * W::L_TOTAL * 4); }
     static size_t tbl_bytes(const Geom &g)
     {
-        return up((size_t)attn_grid(g, kSizingCus) * W::NWAVES * Cf::HEADS * W::NTBL * 4);
+        return up((size_t)attn_grid(g, kSizingCus) * Cf::HEADS * W::NTBL * 4);
     }
     static size_t cg_bytes(const Geom &g) { return up((size_t)g.nW * 4 * Cf::HG * 1024); }
     static size_t f_bytes(const Geom &g) { return up((size_t)g.nW * 4 * W::KS * 1024); }
@@ -837,7 +845,7 @@ hipError_t run_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const 
     out.begin[1] = Cf::HEADS * W::NTBL;
     out.nseg = 1;
     out.tbl_heads = Cf::HEADS; out.tbl_entries = W::NTBL; out.tbl_stride = Cf::HEADS; out.tbl_head0 = 0;
-    return launch_reduce(tpart, grid * W::NWAVES, Cf::HEADS * W::NTBL, out, accumulate, s);
+    return launch_reduce(tpart, grid, Cf::HEADS * W::NTBL, out, accumulate, s);
 }
 
 #define GSWA_WIDE_BWD_SHAPES(X) X(180, 6, 2) X(180, 6, 3)
