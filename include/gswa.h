@@ -119,6 +119,21 @@ int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_
                      size_t *bwd_ws_bytes);
 
 /*
+ * Which organisation of kernels serves the layer (a function of desc alone, like the sizes): for callers
+ * that want to know before they commit to a shape, since the organisations differ several-fold in speed.
+ *   *forward_path, *backward_path  receive one of the values below; either pointer may be NULL.
+ * Returns GSWA_OK, or the error gswa_query_bytes would return for desc.
+ */
+enum {
+    GSWA_PATH_STAGED = 0,     /* one kernel per step of Eq. 6-8 and head group (every shape, both types) */
+    GSWA_PATH_FUSED = 1,      /* the whole pass in one kernel, or one per head chunk (bf16, 8x8 or 16x16
+                                 windows, six heads, C = 60 or 180; backward: 8x8 windows only)          */
+    GSWA_PATH_WINDOW_FWD = 2  /* forward in one launch per layer, one workgroup per window (bf16 layers
+                                 with narrow q/k or 12x12 windows); their backward is GSWA_PATH_STAGED   */
+};
+int gswa_query_path(const gswa_desc *desc, int *forward_path, int *backward_path);
+
+/*
  * y = GSWA(x)  (Eq. 6-8 with shift, partition, bias and mask as above).
  *   saved  NULL for inference; otherwise receives what gswa_backward needs and must be left
  *          untouched until that call has run.

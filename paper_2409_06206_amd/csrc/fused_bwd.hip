@@ -87,7 +87,8 @@ template <class Cf, int HB_, int HE_, bool WPROJ_ = (HE_ == Cf::HEADS)> struct B
     static constexpr int L_DWP = L_DBQ + NG * 3 * RG;
     static constexpr int L_DBP = L_DWP + (WPROJ ? C * C : 0);
     static constexpr int L_TBL = L_DBP + (WPROJ ? C : 0);
-    static constexpr int L_TOTAL = L_TBL + NH * NTBL;
+    static constexpr int L_END = L_TBL + NH * NTBL;
+    static constexpr int L_TOTAL = (L_END + 3) & ~3; // stride of the vectors: whole 16-byte pieces (the sum reads four entries per load)
     static_assert(!WPROJ || (OTP <= 2 * KSC && SZ_SQ >= (size_t)16 * OTP * LW * 2 &&
                              SZ_SQ >= (size_t)16 * CTP * LW * 2),
                   "dY^T / A^T rows alias the P / dS squares");
@@ -742,7 +743,7 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
     for (int v = 0; v < V; ++v) red[slice][col * V + v] = acc[v];
     __syncthreads();
     const int c = threadIdx.x, i = blockIdx.x * 32 * V + c;
-    if (c < 32 * V && i < n) {
+    if (c < 32 * V && i < n && i < out.begin[out.nseg]) { // (entries behind the last segment pad the vectors' stride)
         float t[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -929,10 +930,12 @@ struct GradOut {
 hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s)
 {
     KernelTimer kt(K_REDUCE, s);
-    // (two or four entries per load where every partial vector starts on such a boundary)
-    if (n % 4 == 0 && reinterpret_cast<uintptr_t>(part) % 16 == 0)
+    // (two or four entries per load where every partial vector starts on such a boundary and enough
+    // workgroups remain to fill the chip)
+    const uintptr_t at = reinterpret_cast<uintptr_t>(part);
+    if (n % 4 == 0 && at % 16 == 0 && n >= 200 * 128)
         hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((n + 127) / 128), dim3(1024), 0, s, part, nparts, n, out, accumulate);
-    else if (n % 2 == 0 && reinterpret_cast<uintptr_t>(part) % 8 == 0)
+    else if (n % 2 == 0 && at % 8 == 0 && n >= 200 * 64)
         hipLaunchKernelGGL(reduce_partials_kernel<2>, dim3((n + 63) / 64), dim3(1024), 0, s, part, nparts, n, out, accumulate);
     else
         hipLaunchKernelGGL(reduce_partials_kernel<1>, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);
@@ -984,7 +987,7 @@ hipError_t launch_chunk(const Geom &g, int grid, const bf16_t *x, const bf16_t *
         out.ptr[k] = go.db_proj; out.begin[k++] = B::L_DBP;
     }
     out.ptr[k] = go.dtable; out.begin[k++] = B::L_TBL;
-    out.begin[k] = B::L_TOTAL;
+    out.begin[k] = B::L_END;
     out.nseg = k;
     out.tbl_heads = B::NH; out.tbl_entries = B::NTBL; out.tbl_stride = Cf::HEADS; out.tbl_head0 = HB;
     return launch_reduce(part, grid, B::L_TOTAL, out, go.accumulate, s);

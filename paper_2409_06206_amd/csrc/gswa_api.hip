@@ -332,6 +332,20 @@ int gswa_query_bytes(const gswa_desc *desc, size_t *saved_bytes, size_t *fwd_ws_
     return GSWA_OK;
 }
 
+int gswa_query_path(const gswa_desc *desc, int *forward_path, int *backward_path)
+{
+    Geom g;
+    int rc = make_geom(desc, &g);
+    if (rc != GSWA_OK) return rc;
+    const Sizes s = make_sizes(desc, g); // (the same decisions gswa_forward and gswa_backward take)
+    int fwd = GSWA_PATH_STAGED;
+    if (s.fused_fwd) fwd = GSWA_PATH_FUSED;
+    else if (desc->dtype == GSWA_BF16 && !(desc->flags & GSWA_FORCE_STAGED) && window_fwd_supported(g)) fwd = GSWA_PATH_WINDOW_FWD;
+    if (forward_path) *forward_path = fwd;
+    if (backward_path) *backward_path = s.fused_bwd ? GSWA_PATH_FUSED : GSWA_PATH_STAGED;
+    return GSWA_OK;
+}
+
 int gswa_forward(const gswa_desc *desc, const void *x, const void *w_qkv, const void *b_qkv,
                  const void *w_proj, const void *b_proj, const void *bias_table, void *y,
                  void *saved, void *ws, void *hip_stream)

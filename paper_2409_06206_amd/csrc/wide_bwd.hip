@@ -71,7 +71,8 @@ template <class Cf> struct WideBwdCfg {
     static constexpr size_t G_OFF_F = G_OFF_G + (size_t)FT * 16 * G_LW * 2;
     static constexpr size_t G_LDS_BYTES = G_OFF_F + (size_t)CT * 16 * G_LW * 2;
     static_assert(G_LDS_BYTES <= 160 * 1024, "LDS budget");
-    static constexpr int L_DW = 0, L_DB = 3 * Cf::CG * Cf::CG, L_TOTAL = L_DB + 3 * Cf::CG;
+    static constexpr int L_DW = 0, L_DB = 3 * Cf::CG * Cf::CG, L_END = L_DB + 3 * Cf::CG;
+    static constexpr int L_TOTAL = (L_END + 3) & ~3; // stride of the partial vectors: whole 16-byte pieces
 };
 
 // transposes a packed 16x16 tile on the matrix cores: the tile as the A operand (row l16, k-slots
@@ -807,7 +808,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
     ReduceOut out{};
     out.ptr[0] = dw_qkv + (size_t)GI * 3 * Cf::CG * Cf::CG; out.begin[0] = W::L_DW;
     out.ptr[1] = db_qkv + GI * 3 * Cf::CG; out.begin[1] = W::L_DB;
-    out.begin[2] = W::L_TOTAL;
+    out.begin[2] = W::L_END;
     out.nseg = 2;
     return launch_reduce(part, grid < (g.nW + 1) / 2 ? grid : (g.nW + 1) / 2, W::L_TOTAL, out, accumulate, s);
 }

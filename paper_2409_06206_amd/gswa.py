@@ -14,8 +14,9 @@ GSWA_OK, GSWA_EINVAL, GSWA_EUNSUPPORTED, GSWA_EHIP, GSWA_ETOOBIG = 0, -1, -2, -3
 GSWA_STATIC_SCRATCH_BYTES = 96 * 1024 * 1024
 GSWA_F32, GSWA_BF16 = 0, 1
 GSWA_NO_CASCADE, GSWA_ACCUM_WGRAD, GSWA_FORCE_STAGED, GSWA_DETERMINISTIC = 1, 2, 4, 8
+GSWA_PATH_STAGED, GSWA_PATH_FUSED, GSWA_PATH_WINDOW_FWD = 0, 1, 2
 
-EXPORTS = ("gswa_query_bytes", "gswa_forward", "gswa_backward", "gswa_backward_static", "gswa_strerror",
+EXPORTS = ("gswa_query_bytes", "gswa_query_path", "gswa_forward", "gswa_backward", "gswa_backward_static", "gswa_strerror",
            "gswa_last_hip_error", "gswa_version", "gswa_profile_enable",
            "gswa_profile_kernel_count", "gswa_profile_kernel_name", "gswa_profile_collect")
 
@@ -52,6 +53,8 @@ def lib():
         dp = ctypes.POINTER(gswa_desc)
         L.gswa_query_bytes.argtypes = [dp, sp, sp, sp]
         L.gswa_query_bytes.restype = ctypes.c_int
+        L.gswa_query_path.argtypes = [dp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.gswa_query_path.restype = ctypes.c_int
         L.gswa_forward.argtypes = [dp] + [vp] * 10
         L.gswa_forward.restype = ctypes.c_int
         L.gswa_backward.argtypes = [dp] + [vp] * 16
@@ -120,6 +123,13 @@ def gswa_query_bytes(desc):
     _check(lib().gswa_query_bytes(ctypes.byref(desc), ctypes.byref(a), ctypes.byref(b),
                                   ctypes.byref(c)))
     return a.value, b.value, c.value
+
+
+def gswa_query_path(desc):
+    """(forward_path, backward_path): which organisation of kernels serves the layer (GSWA_PATH_*)."""
+    f, b = ctypes.c_int(), ctypes.c_int()
+    _check(lib().gswa_query_path(ctypes.byref(desc), ctypes.byref(f), ctypes.byref(b)))
+    return f.value, b.value
 
 
 def gswa_forward(desc, x, w_qkv, b_qkv, w_proj, b_proj, bias_table, y, saved, ws, stream=None):

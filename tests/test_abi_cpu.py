@@ -109,6 +109,22 @@ def test_fused_path_sizes():
         assert bwd > 0 and bwd % 256 == 0
 
 
+def test_query_path_names_the_organisation_that_serves_a_layer():
+    """gswa_query_path: the benchmark shapes take the fused kernels, fp32 and forced layers the per-step
+    path, narrow q/k and 12 x 12 windows the one-launch forward with a per-step backward."""
+    F, S, WF = gswa.GSWA_PATH_FUSED, gswa.GSWA_PATH_STAGED, gswa.GSWA_PATH_WINDOW_FWD
+    assert gswa.gswa_query_path(gswa.make_desc(**GOOD)) == (F, F)
+    assert gswa.gswa_query_path(gswa.make_desc(**{**GOOD, "C": 180})) == (F, F)
+    assert gswa.gswa_query_path(gswa.make_desc(**{**GOOD, "dtype": "f32"})) == (S, S)
+    assert gswa.gswa_query_path(gswa.make_desc(**{**GOOD, "flags": gswa.GSWA_FORCE_STAGED})) == (S, S)
+    assert gswa.gswa_query_path(gswa.make_desc(**{**GOOD, "C": 180, "H": 32, "W": 32, "window": 16, "shift": 8})) == (F, S)
+    assert gswa.gswa_query_path(gswa.make_desc(**{**GOOD, "dqk": 4})) == (WF, S)
+    assert gswa.gswa_query_path(gswa.make_desc(B=1, H=24, W=24, C=60, heads=6, groups=2, window=12, shift=6,
+                                               dtype="bf16")) == (WF, S)
+    with pytest.raises(gswa.GswaError):
+        gswa.gswa_query_path(gswa.make_desc(**{**GOOD, "groups": 4}))
+
+
 def test_whole_layer_entry_points_are_exported():
     from paper_2409_06206_amd import astl
     names = declared_functions("astl.h", "astl")
