@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the launch kinds of that kernel), valid only for the kernel source they were taken on:
 # {(workload, groups, kernel): (source file, sha256 of it, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "d12953291e4acbd6ec6511a3e6a196a8cfadf50e69a842c5e0fa7dfda218beba", 231624025),
-    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "d12953291e4acbd6ec6511a3e6a196a8cfadf50e69a842c5e0fa7dfda218beba", 117387192),
-    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "bfb37c2def83c8e913ef3dbd1c3c8324163695feddfbb762db7a3f56c2e2ded4", 74174188),
-    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "40b706f5360b5b1b725536557eb972afb71807e67636e134b0e8a6a11509e669", 224548480),
-    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "c24e6214397b7c3373e4c3371eb01d1d402509c96a7fa2c96ed8408b7fd0bbc6", 181162956),
+    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "9ac4c21a780e8451684fa022c213914257db80afe5ee2b75151ff7ed6344a395", 229609792),
+    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "9ac4c21a780e8451684fa022c213914257db80afe5ee2b75151ff7ed6344a395", 115242464),
+    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "92589044b3bf2ea2d7ca5b00695a8ac15517743b5a7660400c266f182455d4e1", 74167912),
+    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "40b706f5360b5b1b725536557eb972afb71807e67636e134b0e8a6a11509e669", 224898104),
+    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "c24e6214397b7c3373e4c3371eb01d1d402509c96a7fa2c96ed8408b7fd0bbc6", 181316592),
 }
 
 
