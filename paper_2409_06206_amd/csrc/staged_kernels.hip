@@ -248,16 +248,25 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
             wl[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
         }
     }
+    // the linear bias as fp32 behind the fragments
+    float *bias_l = reinterpret_cast<float *>(lsm + (size_t)NT * KS * 1024);
+    const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
+    for (int n = tid; n < 16 * NT; n += nthreads) bias_l[n] = (bias && n < p.N) ? __uint_as_float((uint32_t)bias[n] << 16) : 0.f;
     __syncthreads();
 
     const uint32_t *a1 = static_cast<const uint32_t *>(p.a1);
     const uint32_t *a2 = static_cast<const uint32_t *>(p.a2);
-    const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
     const uint16_t *add = static_cast<const uint16_t *>(p.add);
     uint16_t *out = static_cast<uint16_t *>(p.out);
     uint16_t *pre_out = static_cast<uint16_t *>(p.pre_out);
     const uint16_t *aux = static_cast<const uint16_t *>(p.aux);
     const bool out_even = !(reinterpret_cast<uintptr_t>(p.out) & 3) && !(reinterpret_cast<uintptr_t>(p.pre_out) & 3);
+    // What the stores add (the skip tensor) or take the GELU's derivative of: four features of a row as two dword
+    // reads where its pitch is even and its base dword-aligned.
+    const bool ep_add = add != nullptr;
+    const uint16_t *ep_src = ep_add ? add : (p.act == kActGeluGrad ? aux : nullptr);
+    const long ep_ld = ep_add ? p.ldadd : p.ldaux;
+    if (ep_src && ((ep_ld & 1) || (reinterpret_cast<uintptr_t>(ep_src) & 3))) ep_src = nullptr;
     const long ntile = (p.rows + 15) / 16;
     for (long tile = (long)blockIdx.x * nwaves + wave; tile < ntile; tile += (long)gridDim.x * nwaves) {
         const long row = 16 * tile + l16;
@@ -296,31 +305,51 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
         }
         int opq = lane; // (opaque, so that the fragment reads are not hoisted out of the tile loop)
         asm volatile("" : "+v"(opq));
-        for (int nt0 = 0; nt0 < NT; nt0 += 4) {
-            f32x4 acc[4];
+        // (output tiles per group: four, or two where 16 waves share the registers)
+        constexpr int GRP = NTHREADS >= 1024 ? 2 : 4;
+        for (int nt0 = 0; nt0 < NT; nt0 += GRP) {
+            // What the stores of this group of tiles add or multiply by (the skip tensor, the GELU's argument): four
+            // consecutive features of this lane's row per tile, fetched as two dwords each BEFORE the products, so
+            // that their latency passes under the matrix-core work instead of in front of every store.
+            uint32_t epv[GRP][2]; // (one of the two: a map with both takes the two-byte reads below for the second)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int j = 0; j < GRP; ++j) {
+                const int n0 = 16 * (nt0 + j) + 4 * q;
+                epv[j][0] = epv[j][1] = 0u;
+                if (ep_src && row < p.rows && nt0 + j < NT && n0 + 4 <= p.N) {
+                    const uint32_t *ap = reinterpret_cast<const uint32_t *>(ep_src + row * ep_ld + n0);
+                    epv[j][0] = ap[0];
+                    epv[j][1] = ap[1];
+                }
+            }
+            f32x4 acc[GRP];
+#pragma unroll
+            for (int j = 0; j < GRP; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks)
                 if (ks < KS) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)   // weights as the A operand: the transposed product
+                    for (int j = 0; j < GRP; ++j)   // weights as the A operand: the transposed product
                         if (nt0 + j < NT) acc[j] = mma32(wl[((nt0 + j) * KS + ks) * 64 + opq], af[ks], acc[j]);
                 }
             // result: column l16 = row of the tile, rows 4q + r4 = four consecutive output features
             if (row >= p.rows) continue;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < GRP; ++j) {
                 const int n0 = 16 * (nt0 + j) + 4 * q;
                 if (nt0 + j >= NT || n0 >= p.N) continue;
+                const bool whole = ep_src && n0 + 4 <= p.N;
                 float v[4];
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int n = n0 + r4;
                     v[r4] = acc[j][r4];
                     if (n < p.N) {
-                        if (bias) v[r4] += __uint_as_float((uint32_t)bias[n] << 16);
-                        if (add) v[r4] += __uint_as_float((uint32_t)add[row * p.ldadd + n] << 16);
+                        if (bias) v[r4] += bias_l[n];
+                        if (add) {
+                            if (whole && ep_add) v[r4] += (r4 & 1) ? bf16_hi(epv[j][r4 >> 1]) : bf16_lo(epv[j][r4 >> 1]);
+                            else v[r4] += __uint_as_float((uint32_t)add[row * p.ldadd + n] << 16);
+                        }
                     }
                 }
                 uint16_t *dst = out + row * p.ldout + n0;
@@ -350,12 +379,11 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
                         }
                     } else {
                         float tv[4];
-                        const uint16_t *ap = aux + row * p.ldaux + n0;
-                        if (n0 + 4 <= p.N && !(reinterpret_cast<uintptr_t>(ap) & 3)) { // the four as two dwords
-                            const uint32_t a01 = reinterpret_cast<const uint32_t *>(ap)[0];
-                            const uint32_t a23 = reinterpret_cast<const uint32_t *>(ap)[1];
-                            tv[0] = bf16_lo(a01); tv[1] = bf16_hi(a01); tv[2] = bf16_lo(a23); tv[3] = bf16_hi(a23);
+                        if (whole && !ep_add) {
+                            tv[0] = bf16_lo(epv[j][0]); tv[1] = bf16_hi(epv[j][0]);
+                            tv[2] = bf16_lo(epv[j][1]); tv[3] = bf16_hi(epv[j][1]);
                         } else {
+                            const uint16_t *ap = aux + row * p.ldaux + n0;
 #pragma unroll
                             for (int r4 = 0; r4 < 4; ++r4)
                                 tv[r4] = n0 + r4 < p.N ? __uint_as_float((uint32_t)ap[r4] << 16) : 0.f;
@@ -393,10 +421,10 @@ static bool linear_wide_ok(const LinearArgs &a)
 template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const LinearArgs &a, hipStream_t s)
 {
     const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
-    const size_t lds = (size_t)nt * ks * 1024;
+    const size_t lds = (size_t)nt * ks * 1024 + (size_t)nt * 16 * sizeof(float); // fragments | fp32 bias
     auto kern = linear_mfma_wide_kernel<KSM, NTHREADS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       152 * 1024);
+                                       156 * 1024);
     if (e != hipSuccess) return e;
     const long ntile = (a.rows + 15) / 16;
     long blocks = (ntile + NTHREADS / 64 - 1) / (NTHREADS / 64);
