@@ -468,9 +468,17 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
     return GSWA_OK;
 }
 
+// What a sequence of layers hands from one backward call to the next (the layer BEFORE it in the network):
+// the sum of the copies of LayerNorm-1's gradients is the last, tiny launch of a layer; where the next call
+// starts with the fused MLP backward, that kernel's first workgroup takes the sum over on its way.
+struct BackLink {
+    MlpPending pending; // in: sums the previous call left (w == null: none);  out: sums this call leaves
+    bool may_defer;     // in: another call of the same sequence follows and will take this call's sums
+};
+
 template <typename T>
 int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, const astl_params *p,
-               const char *saved, T *dx, const astl_grads *g, char *ws, hipStream_t st)
+               const char *saved, T *dx, const astl_grads *g, char *ws, hipStream_t st, BackLink *link)
 {
     const long rows = pl.T;
     const int C = pl.C, Hd = pl.Hd;
@@ -489,6 +497,20 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     const long o_g1 = own ? 0 : o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
     const int accumulate = (d->attn.flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
 
+    MlpPending pend{};
+    if (link) {
+        pend = link->pending;
+        link->pending = MlpPending{};
+    }
+    if (pend.w && !own) { // (no kernel of this call takes the pending sums over: a launch of their own)
+        ReplicaSum ps{};
+        ps.rep = const_cast<float *>(pend.src); ps.stride = pend.stride; ps.reps = pend.reps;
+        ps.out[0] = pend.w; ps.off[0] = 0; ps.n[0] = pend.n;
+        ps.out[1] = pend.b; ps.off[1] = pend.n; ps.n[1] = pend.n;
+        ps.count = 2;
+        ps.accumulate = pend.accumulate;
+        ASTL_HIP(launch_reduce_replicas(ps, st));
+    }
     if (!own) {
         ZeroList z{};
         z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P; z.count = 1;
@@ -503,7 +525,7 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
                                      (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                      (const bf16_t *)p->w_fc2, (bf16_t *)dx1, g->w_fc1, g->b_fc1, g->w_fc2,
                                      g->b_fc2, g->ln2_w, g->ln2_b, accumulate, rep, (long)kGradReplicas * P,
-                                     saved + pl.saved - pl.pack, rest, &mlp_sum, st));
+                                     saved + pl.saved - pl.pack, rest, &mlp_sum, pend.w ? &pend : nullptr, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);
@@ -568,6 +590,13 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     n1.rows = rows; n1.C = C; n1.eps = d->eps;
     ASTL_HIP(launch_ln_bwd<T>(n1, st));
 
+    if (own && link && link->may_defer) {
+        // LayerNorm-1's gradient copies stay where they are: the next call of the sequence sums them
+        link->pending.src = rep + o_g1; link->pending.w = g->ln1_w; link->pending.b = g->ln1_b;
+        link->pending.n = C; link->pending.reps = kGradReplicas; link->pending.stride = P;
+        link->pending.accumulate = accumulate;
+        return GSWA_OK;
+    }
     ReplicaSum rs{};
     rs.rep = rep; rs.stride = P; rs.reps = kGradReplicas;
     if (own) {
@@ -608,6 +637,8 @@ bool grads_ok(const astl_grads *g)
 
 int forward_checked(const astl_desc *desc, const void *x, const astl_params *p, void *y, void *saved, void *ws,
                     void *hip_stream, LayerLink *link);
+int backward_checked(const astl_desc *desc, const void *x, const void *dy, const astl_params *p, const void *saved,
+                     void *dx, const astl_grads *g, void *ws, void *hip_stream, BackLink *link);
 
 } // namespace
 
@@ -662,6 +693,17 @@ extern "C" {
 int astl_backward(const astl_desc *desc, const void *x, const void *dy, const astl_params *p, const void *saved,
                   void *dx, const astl_grads *g, void *ws, void *hip_stream)
 {
+    return backward_checked(desc, x, dy, p, saved, dx, g, ws, hip_stream, nullptr);
+}
+
+} // extern "C"
+
+namespace gswa {
+namespace {
+
+int backward_checked(const astl_desc *desc, const void *x, const void *dy, const astl_params *p, const void *saved,
+                     void *dx, const astl_grads *g, void *ws, void *hip_stream, BackLink *link)
+{
     Plan pl;
     int rc = make_plan(desc, &pl);
     if (rc != GSWA_OK) return rc;
@@ -671,12 +713,13 @@ int astl_backward(const astl_desc *desc, const void *x, const void *dy, const as
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (desc->attn.dtype == GSWA_F32)
         return backward_t<float>(desc, pl, (const float *)x, (const float *)dy, p, (const char *)saved, (float *)dx,
-                                 g, (char *)ws, st);
+                                 g, (char *)ws, st, link);
     return backward_t<bf16_t>(desc, pl, (const bf16_t *)x, (const bf16_t *)dy, p, (const char *)saved, (bf16_t *)dx,
-                              g, (char *)ws, st);
+                              g, (char *)ws, st, link);
 }
 
-} // extern "C"
+} // namespace
+} // namespace gswa
 
 namespace {
 
@@ -915,11 +958,13 @@ int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *
     if (sp.k == 0) {
         char *gbuf[2] = {w, w + sp.A};
         char *layer_ws = w + 2 * sp.A;
+        BackLink link{};
         for (int l = sp.L - 1; l >= 0; --l) {
             const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
             const void *xin = l == 0 ? x : sv + (size_t)(l - 1) * slot + sp.S;
-            rc = astl_backward(ld, xin, grad_in(l, gbuf), params + l, sv + (size_t)l * slot, grad_out(l, gbuf),
-                               grads + l, layer_ws, hip_stream);
+            link.may_defer = l > 0; // (layer l - 1 runs next on the same scratch, before anything else touches it)
+            rc = backward_checked(ld, xin, grad_in(l, gbuf), params + l, sv + (size_t)l * slot, grad_out(l, gbuf),
+                                  grads + l, layer_ws, hip_stream, &link);
             if (rc != GSWA_OK) return rc;
         }
         return GSWA_OK;
@@ -942,11 +987,13 @@ int astl_stack_backward(const astl_stack_desc *desc, const void *x, const void *
             if (rc != GSWA_OK) return rc;
             in = st + sp.S;
         }
+        BackLink blink{};
         for (int l = l1 - 1; l >= l0; --l) {
             const astl_desc *ld = (l & 1) ? &sp.odd : &sp.even;
             const void *xin = l == l0 ? block_in : region + (size_t)(l - l0 - 1) * slot + sp.S;
-            rc = astl_backward(ld, xin, grad_in(l, gbuf), params + l, region + (size_t)(l - l0) * slot,
-                               grad_out(l, gbuf), grads + l, layer_ws, hip_stream);
+            blink.may_defer = l > l0; // (not across blocks: the forward pass of the next block uses the scratch)
+            rc = backward_checked(ld, xin, grad_in(l, gbuf), params + l, region + (size_t)(l - l0) * slot,
+                                  grad_out(l, gbuf), grads + l, layer_ws, hip_stream, &blink);
             if (rc != GSWA_OK) return rc;
         }
     }

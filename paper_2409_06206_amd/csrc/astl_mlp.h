@@ -92,13 +92,23 @@ __device__ __forceinline__ void astl_mlp_reduce_block(const MlpReduceArgs &a, in
 // layers, gamma and beta of LN_2) are written to their final places, or added there when
 // `accumulate` is set.  `zero` (may be null) is an fp32 array of nzero entries the first kernel
 // clears on the way, for a later launch of the caller's.  `pack` is what the forward call of the
-// same layer wrote; `ws` holds astl_mlp_bwd_ws_bytes().  With `deferred` non-null the final sum over the
+// same layer wrote; `ws` holds astl_mlp_bwd_ws_bytes().  `pending` (may be null): see MlpPending.  With `deferred` non-null the final sum over the
 // workgroups' partial results is not launched: its arguments are returned there and the caller runs
 // astl_mlp_reduce_block for astl_mlp_reduce_blocks() blocks of 256 threads in a launch of its own.
+// Sums the call before left for this one (a sequence of layers, backward): `reps` copies, `stride` floats apart,
+// of [w: n | b: n] at `src`; the kernel adds them up into w and b before it clears `zero` (often the same array).
+struct MlpPending {
+    const float *src;
+    float *w, *b;
+    int n, reps, accumulate;
+    long stride;
+};
+
 hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
                                float *db_fc2, float *dln_w, float *dln_b, int accumulate, float *zero, long nzero,
-                               const void *pack, void *ws, MlpReduceArgs *deferred, hipStream_t s);
+                               const void *pack, void *ws, MlpReduceArgs *deferred, const MlpPending *pending,
+                               hipStream_t s);
 
 } // namespace gswa

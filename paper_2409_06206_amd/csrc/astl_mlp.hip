@@ -59,6 +59,13 @@ struct MlpArgs {
     bf16_t *xn_out;            // ... and where its output goes (null: not wanted)
     float *zero;               // backward: fp32 array the kernel clears for a later launch of the caller's
     long nzero;
+    // backward, optional: pend_src holds `pend_reps` copies, `pend_stride` floats apart, of two vectors
+    // [pend_n | pend_n] that the call before this one left unsummed (LayerNorm-1 gradients of the layer after
+    // this one in a sequence); they are summed to pend_w / pend_b before `zero` (often the same array) is cleared
+    const float *pend_src;
+    float *pend_w, *pend_b;
+    int pend_n, pend_reps, pend_accumulate;
+    long pend_stride;
     void *pack;                // weights in fragment order, written by the pack kernel
     float *part;               // backward: one pair of partial weight-gradient matrices per workgroup
 };
@@ -366,8 +373,22 @@ __global__ __launch_bounds__(kBwdThreads) void astl_mlp_bwd_kernel(MlpArgs a)
         stage(w2t, pk + L::w2t, 2 * L::frag);                        // w2t and w1t lie back to back
         stage(reinterpret_cast<uint4 *>(b1s), pk + L::floats_at, FT * 16 / 4);
     }
-    for (long i = (long)blockIdx.x * kBwdThreads + threadIdx.x; i < a.nzero; i += (long)gridDim.x * kBwdThreads)
-        a.zero[i] = 0.f;
+    if (a.pend_w) {
+        // the first workgroup sums the pending copies in a fixed order, then clears the array
+        if (blockIdx.x == 0) {
+            for (int e = threadIdx.x; e < 2 * a.pend_n; e += kBwdThreads) {
+                float sum = 0.f;
+                for (int r = 0; r < a.pend_reps; ++r) sum += a.pend_src[(long)r * a.pend_stride + e];
+                float *dst = e < a.pend_n ? a.pend_w + e : a.pend_b + (e - a.pend_n);
+                *dst = a.pend_accumulate ? *dst + sum : sum;
+            }
+            __syncthreads();
+            for (long i = threadIdx.x; i < a.nzero; i += kBwdThreads) a.zero[i] = 0.f;
+        }
+    } else {
+        for (long i = (long)blockIdx.x * kBwdThreads + threadIdx.x; i < a.nzero; i += (long)gridDim.x * kBwdThreads)
+            a.zero[i] = 0.f;
+    }
     __syncthreads();
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tok = lane & 15, q = lane >> 4;
@@ -645,7 +666,8 @@ hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf
                                const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                const bf16_t *w_fc2, bf16_t *dx1, float *dw_fc1, float *db_fc1, float *dw_fc2,
                                float *db_fc2, float *dln_w, float *dln_b, int accumulate, float *zero, long nzero,
-                               const void *pack, void *ws, MlpReduceArgs *deferred, hipStream_t s)
+                               const void *pack, void *ws, MlpReduceArgs *deferred, const MlpPending *pending,
+                               hipStream_t s)
 {
     if (!astl_mlp_bwd_supported(C, hidden)) return hipErrorInvalidValue;
     MlpArgs m{};
@@ -653,6 +675,10 @@ hipError_t launch_astl_mlp_bwd(long rows, int C, int hidden, float eps, const bf
     m.x = x1; m.a = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
     m.y = dx1;
     m.zero = zero; m.nzero = zero ? nzero : 0;
+    if (pending && pending->w) {
+        m.pend_src = pending->src; m.pend_w = pending->w; m.pend_b = pending->b; m.pend_n = pending->n; m.pend_reps = pending->reps;
+        m.pend_stride = pending->stride; m.pend_accumulate = pending->accumulate;
+    }
     m.pack = const_cast<void *>(pack);
     m.part = static_cast<float *>(ws);
     hipError_t e;
