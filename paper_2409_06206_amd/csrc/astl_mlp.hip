@@ -599,12 +599,7 @@ template <int KSC, int KSF> hipError_t launch_fwd_t(const MlpArgs &a, hipStream_
     }
     auto kern = astl_mlp_fwd_kernel<KSC, KSF>;
     const size_t lds = fwd_lds<KSC, KSF>();
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_MLP_FWD, s);
     hipLaunchKernelGGL(kern, dim3(fwd_blocks(a.rows)), dim3(kFwdThreads), lds, s, a);
     return hipGetLastError();
@@ -614,12 +609,7 @@ template <int KSC, int KSF> hipError_t launch_bwd_t(const MlpArgs &a, hipStream_
 {
     auto kern = astl_mlp_bwd_kernel<KSC, KSF>;
     const size_t lds = BwdLds<KSC, KSF>::bytes;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_MLP_BWD, s);
     hipLaunchKernelGGL(kern, dim3(bwd_blocks(a.rows)), dim3(kBwdThreads), lds, s, a);
     return hipGetLastError();

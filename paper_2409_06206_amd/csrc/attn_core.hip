@@ -457,13 +457,7 @@ hipError_t launch_fwd(const Geom &g, int grp, const bf16_t *qkv, const bf16_t *t
     using Cf = CoreCfg<NT, ET, KQ>;
     const size_t lds = fwd_lds_bytes<Cf>(g.M);
     auto kern = attn_core_fwd_kernel<NT, ET, KQ>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_ATTN_CORE_FWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(Cf::NTHREADS), lds, s, g, grp, qkv, table, attn_out);
     return hipGetLastError();
@@ -476,13 +470,7 @@ hipError_t launch_bwd(const Geom &g, int grp, const bf16_t *qkv, bf16_t *dqkv, c
     using Cf = CoreCfg<NT, ET, KQ>;
     const size_t lds = bwd_lds_bytes<Cf>(g.M);
     auto kern = attn_core_bwd_kernel<NT, ET, KQ>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_ATTN_CORE_BWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(Cf::NTHREADS), lds, s, g, grp, qkv, dqkv, table, tpart);
     return hipGetLastError();

@@ -70,6 +70,10 @@ __device__ __forceinline__ long window_token(const Geom &g, int w, int n, int &r
 // Records the text of a failed HIP call for gswa_last_hip_error() and returns GSWA_EHIP.
 int report_hip_error(hipError_t e);
 
+// Raises a kernel's limit of dynamic LDS to at least `bytes` on the current device (nothing to do up to the
+// 64 KB every kernel may use).  Remembered per kernel and device, safe to call from several host threads.
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);
+
 // Compute units of the current device, for sizing launch grids (looked up once per process, in a
 // thread-safe way; 256 if the runtime cannot tell).  Buffer sizes never depend on it.
 inline int device_cu_count()

@@ -955,13 +955,7 @@ hipError_t launch_chunk(const Geom &g, int grid, const bf16_t *x, const bf16_t *
     using B = BwdCfg<Cf, HB, HE, WPROJ>;
     static_assert(B::LDS_BYTES <= 160 * 1024, "LDS budget");
     auto kern = fused_bwd_kernel<Cf, HB, HE, WPROJ>;
-    static bool attr_done = false;
-    if (!attr_done && B::LDS_BYTES > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)B::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), B::LDS_BYTES); ea != hipSuccess) return ea;
     {
         KernelTimer kt(K_FUSED_BWD, s);
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), B::LDS_BYTES, s, g, x, dy, attn, pack, table, dx, part);
@@ -1029,13 +1023,7 @@ hipError_t run_wproj_grad(const Geom &g, int grid, const bf16_t *dy, const bf16_
     using P = WprojGradCfg<Cf>;
     constexpr size_t lds = P::LDS_BYTES;
     auto kern = wproj_grad_kernel<Cf>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     {
         KernelTimer kt(K_WPROJ_GRAD, s);
         hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * P::NWV), lds, s, g.T, dy, attn, part);

@@ -724,13 +724,7 @@ hipError_t launch_attn_chunks(const Geom &g, const bf16_t *x, const uint8_t *pac
         using A = AttnChunkCfg<Cf, Plan::B[I], Plan::E[I], M>;
         static_assert(A::LDS_BYTES <= 160 * 1024, "LDS budget");
         auto kern = fused_attn_fwd_kernel<Cf, Plan::B[I], Plan::E[I], M>;
-        static bool attr_done = false;
-        if (!attr_done && A::LDS_BYTES > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)A::LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), A::LDS_BYTES); ea != hipSuccess) return ea;
         int grid = ((M == 8 && A::LDS_BYTES <= 80 * 1024) ? 2 : 1) * device_cu_count();
         if (grid > g.nW) grid = g.nW;
         {
@@ -771,13 +765,7 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
         if (e != hipSuccess) return e;
         constexpr size_t lds = (size_t)Cf::N_WPK * 1024 + 4 * Cf::C;
         auto kern = proj_gemm_kernel<Cf>;
-        static bool attr_done = false;
-        if (!attr_done && lds > 64 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
         long ntile = (g.T + 63) / 64;
         int grid = 2 * device_cu_count();
         if (grid > ntile) grid = (int)ntile;
@@ -788,13 +776,7 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
         using W = WaveFwdCfg<Cf>;
         static_assert(W::LDS_BYTES <= 160 * 1024, "LDS budget");
         auto kern = wave_fwd_kernel<Cf>;
-        static bool attr_done = false;
-        if (!attr_done && W::LDS_BYTES > 64 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)W::LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), W::LDS_BYTES); ea != hipSuccess) return ea;
         // one window per wave: spread the windows over the compute units before filling a workgroup
         int grid = device_cu_count();
         if (grid > g.nW) grid = g.nW;

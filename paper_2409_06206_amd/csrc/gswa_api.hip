@@ -5,12 +5,30 @@
 #include "staged_kernels.h"
 #include "fused.h"
 
+#include <map>
 #include <mutex>
 #include <string>
+#include <utility>
 #include <type_traits>
 
 namespace {
 thread_local std::string g_hip_error;
+}
+
+hipError_t gswa::allow_dynamic_lds(const void *kernel, size_t bytes)
+{
+    if (bytes <= 64 * 1024) return hipSuccess;
+    static std::mutex mu;
+    static std::map<std::pair<const void *, int>, size_t> allowed; // (kernel, device) -> limit set so far
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lk(mu);
+    size_t &cur = allowed[std::make_pair(kernel, dev)];
+    if (cur >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) cur = bytes;
+    return e;
 }
 
 int gswa::report_hip_error(hipError_t e)

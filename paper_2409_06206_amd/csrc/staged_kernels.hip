@@ -423,9 +423,7 @@ template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const Li
     const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
     const size_t lds = (size_t)nt * ks * 1024 + (size_t)nt * 16 * sizeof(float); // fragments | fp32 bias
     auto kern = linear_mfma_wide_kernel<KSM, NTHREADS>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       156 * 1024);
-    if (e != hipSuccess) return e;
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     const long ntile = (a.rows + 15) / 16;
     long blocks = (ntile + NTHREADS / 64 - 1) / (NTHREADS / 64);
     if (blocks > device_cu_count()) blocks = device_cu_count();
@@ -453,13 +451,7 @@ static hipError_t launch_linear_mfma_t(const LinearArgs &a, const LinearArgs *b,
     const unsigned chunks_a = (unsigned)((nta + NTC - 1) / NTC), chunks = chunks_a + (unsigned)((ntb + NTC - 1) / NTC);
     const size_t lds = (size_t)NTC * (ksa > ksb ? ksa : ksb) * 1024;
     auto kern = linear_mfma_kernel<KSM, NTC>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, NTC * KSM * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     const long rows = b && b->rows > a.rows ? b->rows : a.rows;
     const long ntile = (rows + 15) / 16;
     // every workgroup builds its chunk's weight fragments first: with several chunks the rows are
@@ -989,13 +981,7 @@ static hipError_t run_wgrad_stream(const WgradArgs &a, int shares, hipStream_t s
     constexpr int B = kWgradStreamBlock;
     using P = WgradStreamCfg<B, B>;
     auto kern = wgrad_stream_kernel<B, B>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)P::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), P::LDS_BYTES); ea != hipSuccess) return ea;
     float *part = static_cast<float *>(a.scratch);
     {
         KernelTimer kt(a.prof_id, s);
@@ -1217,11 +1203,7 @@ hipError_t launch_attn_fwd(const Geom &g, int grp, const T *qkv, const T *table,
     const size_t lds = attn_fwd_lds_bytes(g, &rs);
     if (rs == 0) return hipErrorInvalidValue;
     auto kern = attn_fwd_kernel<T>;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_ATTN_FWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, table, attn_out, rs);
     return hipGetLastError();
@@ -1385,11 +1367,7 @@ hipError_t launch_attn_bwd(const Geom &g, int grp, const T *qkv, T *dqkv, const 
     const size_t lds = attn_bwd_lds_bytes(g, &rs);
     if (rs == 0) return hipErrorInvalidValue;
     auto kern = attn_bwd_kernel<T>;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_ATTN_BWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW, g.hg), dim3(kThreads), lds, s, g, grp, qkv, dqkv, table, dtable, rep_stride, reps, rs);
     return hipGetLastError();

@@ -777,13 +777,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
     using W = WideBwdCfg<Cf>;
     {
         auto kern = wide_attn_bwd_kernel<Cf, GI>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)W::LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), W::LDS_BYTES); ea != hipSuccess) return ea;
         KernelTimer kt(K_WIDE_ATTN_BWD, s);
         hipLaunchKernelGGL(kern, dim3(grid), dim3(W::NTHREADS), W::LDS_BYTES, s, g, x, dy, attn, pack, cgf, dqkv, ffr, tpart);
     }
@@ -791,13 +785,7 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
     if (e != hipSuccess) return e;
     {
         auto kern = wide_qkv_grad_kernel<Cf, GI>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)W::G_LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), W::G_LDS_BYTES); ea != hipSuccess) return ea;
         KernelTimer kt(K_WIDE_WGRAD, s);
         const int pairs = (g.nW + 1) / 2;
         hipLaunchKernelGGL(kern, dim3(grid < pairs ? grid : pairs), dim3(64 * W::G_WAVES), W::G_LDS_BYTES, s, g, ffr, pack,

@@ -521,13 +521,7 @@ hipError_t run_wide_fwd(const Geom &g, const bf16_t *x, const uint8_t *pack, bf1
 {
     using W = WideFwdCfg<Cf>;
     auto kern = wide_fwd_kernel<Cf>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)W::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), W::LDS_BYTES); ea != hipSuccess) return ea;
     // one window per wave: spread the windows over the compute units before filling a workgroup
     int grid = device_cu_count();
     if (grid > g.nW) grid = g.nW;

@@ -338,13 +338,7 @@ hipError_t launch_window_fwd_t(const Geom &g, const bf16_t *x, const bf16_t *w_q
 {
     const size_t lds = win_layout(g).bytes;
     auto kern = window_fwd_kernel<NT, QTN, VTN>;
-    static bool attr_done = false;
-    if (!attr_done && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     KernelTimer kt(K_WINDOW_FWD, s);
     hipLaunchKernelGGL(kern, dim3(g.nW), dim3(64 * NT), lds, s, g, x, w_qkv, b_qkv, w_proj, b_proj, table, y, attn_out);
     return hipGetLastError();
