@@ -444,14 +444,23 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
         return GSWA_OK;
     }
     // Eq. 5: y = MLP(LN_2(x1)) + x1
-    LnArgs l2{};
-    l2.u = x; l2.add = a; l2.gamma = p->ln2_w; l2.beta = p->ln2_b; l2.sum_out = x1; l2.out = xn;
-    l2.rows = rows; l2.C = C; l2.eps = d->eps;
-    ASTL_HIP(launch_ln_fwd<T>(l2, st));
     T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
     LinearArgs f1{};
     f1.a1 = xn; f1.lda1 = C; f1.w = p->w_fc1; f1.w_sn = C; f1.w_sk = 1; f1.bias = p->b_fc1;
     f1.out = pre; f1.ldout = Hd; f1.rows = rows; f1.N = Hd; f1.K = C; f1.prof_id = K_FC1_LINEAR;
+    // Eq. 4's skip and LN_2 in the operand read of the first map where its kernel has them: x1 is
+    // written from there and LN_2(x1) never leaves the registers
+    LinearArgs f1n = f1;
+    f1n.a1 = x; f1n.a2 = a; f1n.lda2 = C; f1n.sum_out = x1;
+    f1n.ln_gamma = p->ln2_w; f1n.ln_beta = p->ln2_b; f1n.ln_eps = d->eps;
+    if (sizeof(T) == 2 && linear_ln_supported(f1n)) {
+        f1 = f1n;
+    } else {
+        LnArgs l2{};
+        l2.u = x; l2.add = a; l2.gamma = p->ln2_w; l2.beta = p->ln2_b; l2.sum_out = x1; l2.out = xn;
+        l2.rows = rows; l2.C = C; l2.eps = d->eps;
+        ASTL_HIP(launch_ln_fwd<T>(l2, st));
+    }
     if (sizeof(T) == 2 && linear_act_supported(f1)) {
         // the hidden layer straight from the product (the pre-activation is never read in this pass)
         f1.act = kActGelu; f1.out = h;
@@ -530,12 +539,20 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);
         // recompute LN_2(x1), the pre-activation and the hidden layer
-        LnArgs l2{};
-        l2.u = x1; l2.gamma = p->ln2_w; l2.beta = p->ln2_b; l2.out = xn; l2.rows = rows; l2.C = C; l2.eps = d->eps;
-        ASTL_HIP(launch_ln_fwd<T>(l2, st));
         LinearArgs f1{};
         f1.a1 = xn; f1.lda1 = C; f1.w = p->w_fc1; f1.w_sn = C; f1.w_sk = 1; f1.bias = p->b_fc1;
         f1.out = pre; f1.ldout = Hd; f1.rows = rows; f1.N = Hd; f1.K = C; f1.prof_id = K_FC1_LINEAR;
+        // (LN_2 in the operand read of the first map where its kernel has it; the weight gradient below
+        // still wants LN_2(x1) in memory)
+        LinearArgs f1n = f1;
+        f1n.a1 = x1; f1n.ln_out = xn; f1n.ln_gamma = p->ln2_w; f1n.ln_beta = p->ln2_b; f1n.ln_eps = d->eps;
+        if (sizeof(T) == 2 && linear_ln_supported(f1n)) {
+            f1 = f1n;
+        } else {
+            LnArgs l2{};
+            l2.u = x1; l2.gamma = p->ln2_w; l2.beta = p->ln2_b; l2.out = xn; l2.rows = rows; l2.C = C; l2.eps = d->eps;
+            ASTL_HIP(launch_ln_fwd<T>(l2, st));
+        }
         if (sizeof(T) == 2 && linear_act_supported(f1)) {
             f1.act = kActGelu; f1.out = h; f1.pre_out = pre;
             ASTL_HIP(launch_linear<T>(f1, st));

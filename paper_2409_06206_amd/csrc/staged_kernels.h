@@ -25,10 +25,19 @@ struct LinearArgs {
     int act;
     void *pre_out;           // [rows, N], pitch ldout
     const void *aux; long ldaux;
+    // LayerNorm folded into the operand read (only where linear_ln_supported() says so; ln_gamma null = none):
+    // u = a1 + a2 rounded to the element type goes to sum_out (may be null), LN(u) = (u - mean) rstd gamma + beta
+    // rounded to the element type is what the map multiplies, and goes to ln_out (may be null).  Both outputs
+    // are [rows, K] of pitch lda1.
+    const void *ln_gamma, *ln_beta;
+    float ln_eps;
+    void *sum_out, *ln_out;
 };
 constexpr int kActGelu = 1, kActGeluGrad = 2;
 // true when launch_linear<bf16_t> runs this call on the kernel that implements `act`
 bool linear_act_supported(const LinearArgs &a);
+// true when launch_linear<bf16_t> runs this call on the kernel that implements the LayerNorm of the operand
+bool linear_ln_supported(const LinearArgs &a);
 
 // Gaussian CDF Phi(t) and density phi(t): erf by the rational-times-exponential approximation
 // 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7); exp(-t^2/2) serves both.

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_kernel(LinearArgs pa, Li
 // registers) builds all of them once, and a wave reads the rows
 // of its 16-row tile ONCE for all output columns (the chunked kernel above reads them once per 64
 // columns and rebuilds fragments per workgroup and chunk).
-template <int KSM, int NTHREADS>
+template <int KSM, int NTHREADS, bool LN>
 __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p, int KS, int NT)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lsm[];
@@ -252,6 +252,14 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
     float *bias_l = reinterpret_cast<float *>(lsm + (size_t)NT * KS * 1024);
     const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
     for (int n = tid; n < 16 * NT; n += nthreads) bias_l[n] = (bias && n < p.N) ? __uint_as_float((uint32_t)bias[n] << 16) : 0.f;
+    // scale and shift of the LayerNorm of the operand, as (gamma, beta) pairs per channel, zero beyond K
+    float2 *ln_gb = reinterpret_cast<float2 *>(bias_l + 16 * NT);
+    if (LN) {
+        const uint16_t *lg = static_cast<const uint16_t *>(p.ln_gamma), *lb = static_cast<const uint16_t *>(p.ln_beta);
+        for (int k = tid; k < 32 * KS; k += nthreads)
+            ln_gb[k] = k < p.K ? make_float2(__uint_as_float((uint32_t)lg[k] << 16), __uint_as_float((uint32_t)lb[k] << 16))
+                               : make_float2(0.f, 0.f);
+    }
     __syncthreads();
 
     const uint32_t *a1 = static_cast<const uint32_t *>(p.a1);
@@ -270,10 +278,11 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
     const long ntile = (p.rows + 15) / 16;
     for (long tile = (long)blockIdx.x * nwaves + wave; tile < ntile; tile += (long)gridDim.x * nwaves) {
         const long row = 16 * tile + l16;
-        uint4 af[KSM];
+        uint32_t af[KSM][4];
 #pragma unroll
         for (int ks = 0; ks < KSM; ++ks) {
-            uint32_t v[4] = {0u, 0u, 0u, 0u};
+            uint32_t (&v)[4] = af[ks];
+            v[0] = v[1] = v[2] = v[3] = 0u;
             const int k0 = 32 * ks + 8 * q;
             if (ks < KS && row < p.rows) {
                 if (k0 + 8 <= p.K) { // the lane's 8 channels as one 16-byte read (dword aligned)
@@ -301,7 +310,74 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
                     }
                 }
             }
-            af[ks] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+        if (LN) {
+            // LayerNorm of the row just read (Eq. 4-5): the row is spread over the four lanes that share l16;
+            // mean, then the sum of squared distances from it, as the separate LayerNorm kernel computes them
+            float sum = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) sum += bf16_lo(af[ks][dw]) + bf16_hi(af[ks][dw]); // (zero beyond K)
+            const float mean = qgroup_sum(sum) / (float)p.K;
+            // (each pass unpacks the row again: the unpacked values of a whole row would take twice its registers)
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) asm volatile("" : "+v"(af[ks][dw]));
+            float dev = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw)
+                    if (ks < KS && 32 * ks + 8 * q + 2 * dw < p.K) {
+                        const float d0 = bf16_lo(af[ks][dw]) - mean, d1 = bf16_hi(af[ks][dw]) - mean;
+                        dev += d0 * d0 + d1 * d1;
+                    }
+            const float rstd = rsqrtf(qgroup_sum(dev) / (float)p.K + p.ln_eps);
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) asm volatile("" : "+v"(af[ks][dw]));
+            uint32_t *so = static_cast<uint32_t *>(p.sum_out), *lo = static_cast<uint32_t *>(p.ln_out);
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+                if (ks < KS) {
+                    const int k0 = 32 * ks + 8 * q;
+                    const long at = (row * p.lda1 + k0) >> 1;
+                    const bool live = row < p.rows;
+                    if (so && live) {
+                        if (k0 + 8 <= p.K) {
+                            dwords4 u;
+#pragma unroll
+                            for (int dw = 0; dw < 4; ++dw) u.v[dw] = af[ks][dw];
+                            *reinterpret_cast<dwords4 *>(so + at) = u;
+                        } else {
+#pragma unroll
+                            for (int dw = 0; dw < 4; ++dw)
+                                if (k0 + 2 * dw < p.K) so[at + dw] = af[ks][dw];
+                        }
+                    }
+#pragma unroll
+                    for (int dw = 0; dw < 4; ++dw) {
+                        const float2 g0 = ln_gb[k0 + 2 * dw], g1 = ln_gb[k0 + 2 * dw + 1];
+                        af[ks][dw] = pack_bf16x2((bf16_lo(af[ks][dw]) - mean) * rstd * g0.x + g0.y,
+                                                 (bf16_hi(af[ks][dw]) - mean) * rstd * g1.x + g1.y);
+                    }
+                    if (lo && live) {
+                        if (k0 + 8 <= p.K) {
+                            dwords4 u;
+#pragma unroll
+                            for (int dw = 0; dw < 4; ++dw) u.v[dw] = af[ks][dw];
+                            *reinterpret_cast<dwords4 *>(lo + at) = u;
+                        } else {
+#pragma unroll
+                            for (int dw = 0; dw < 4; ++dw)
+                                if (k0 + 2 * dw < p.K) lo[at + dw] = af[ks][dw];
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0); // (one slice's scale and shift in registers at a time)
+                }
         }
         int opq = lane; // (opaque, so that the fragment reads are not hoisted out of the tile loop)
         asm volatile("" : "+v"(opq));
@@ -330,7 +406,8 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
                 if (ks < KS) {
 #pragma unroll
                     for (int j = 0; j < GRP; ++j)   // weights as the A operand: the transposed product
-                        if (nt0 + j < NT) acc[j] = mma32(wl[((nt0 + j) * KS + ks) * 64 + opq], af[ks], acc[j]);
+                        if (nt0 + j < NT) acc[j] = mma32(wl[((nt0 + j) * KS + ks) * 64 + opq],
+                                                      make_uint4(af[ks][0], af[ks][1], af[ks][2], af[ks][3]), acc[j]);
                 }
             // result: column l16 = row of the tile, rows 4q + r4 = four consecutive output features
             if (row >= p.rows) continue;
@@ -415,14 +492,17 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
 static bool linear_wide_ok(const LinearArgs &a)
 {
     const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
-    return a.N > 64 && ks <= 12 && (long)nt * ks <= 152 && a.rows >= 4096;
+    // (fragments, the fp32 bias and the LayerNorm's pairs within the 160 KB of a compute unit)
+    const long lds = (long)nt * ks * 1024 + (long)nt * 64 + (long)ks * 256;
+    return a.N > 64 && ks <= 12 && (long)nt * ks <= 152 && lds <= 160 * 1024 && a.rows >= 4096;
 }
 
-template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const LinearArgs &a, hipStream_t s)
+template <int KSM, int NTHREADS, bool LN> static hipError_t launch_linear_wide_ln(const LinearArgs &a, hipStream_t s)
 {
     const int nt = (a.N + 15) / 16, ks = (a.K + 31) / 32;
-    const size_t lds = (size_t)nt * ks * 1024 + (size_t)nt * 16 * sizeof(float); // fragments | fp32 bias
-    auto kern = linear_mfma_wide_kernel<KSM, NTHREADS>;
+    // fragments | fp32 bias | (gamma, beta) of the operand's LayerNorm
+    const size_t lds = (size_t)nt * ks * 1024 + (size_t)nt * 16 * sizeof(float) + (a.ln_gamma ? (size_t)ks * 32 * sizeof(float2) : 0);
+    auto kern = linear_mfma_wide_kernel<KSM, NTHREADS, LN>;
     if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds); ea != hipSuccess) return ea;
     const long ntile = (a.rows + 15) / 16;
     long blocks = (ntile + NTHREADS / 64 - 1) / (NTHREADS / 64);
@@ -430,6 +510,11 @@ template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const Li
     KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), lds, s, a, ks, nt);
     return hipGetLastError();
+}
+
+template <int KSM, int NTHREADS> static hipError_t launch_linear_wide_t(const LinearArgs &a, hipStream_t s)
+{
+    return a.ln_gamma ? launch_linear_wide_ln<KSM, NTHREADS, true>(a, s) : launch_linear_wide_ln<KSM, NTHREADS, false>(a, s);
 }
 
 // true when the matrix-core kernel can serve the call (the dword reads need even offsets)
@@ -481,6 +566,11 @@ static hipError_t launch_linear_mfma(const LinearArgs &a, const LinearArgs *b, i
 }
 
 bool linear_act_supported(const LinearArgs &a) { return a.rows > 0 && a.N > 0 && linear_mfma_ok(a) && linear_wide_ok(a); }
+// (the LayerNorm's outputs are written as dwords at the operand's own offsets)
+bool linear_ln_supported(const LinearArgs &a)
+{
+    return linear_act_supported(a) && !(reinterpret_cast<uintptr_t>(a.sum_out) & 3) && !(reinterpret_cast<uintptr_t>(a.ln_out) & 3);
+}
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s)
 {
@@ -488,10 +578,10 @@ template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t 
     if constexpr (sizeof(T) == 2) {
         if (linear_mfma_ok(a) && linear_wide_ok(a))
             return (a.K + 31) / 32 <= 6 ? launch_linear_wide_t<6, 1024>(a, s) : launch_linear_wide_t<12, 512>(a, s);
-        if (a.act) return hipErrorInvalidValue; // (callers ask linear_act_supported first)
+        if (a.act || a.ln_gamma) return hipErrorInvalidValue; // (callers ask linear_act_supported first)
         if (linear_mfma_ok(a)) return launch_linear_mfma(a, nullptr, a.prof_id, nullptr, 0, s);
     }
-    if (a.act) return hipErrorInvalidValue;
+    if (a.act || a.ln_gamma) return hipErrorInvalidValue;
     dim3 grid((unsigned)((a.rows + 63) / 64), (unsigned)((a.N + 63) / 64));
     KernelTimer kt(a.prof_id, s);
     hipLaunchKernelGGL(linear_kernel<T>, grid, dim3(kThreads), 0, s, a);
