@@ -354,6 +354,7 @@ struct Plan {
     size_t reps;                  // bytes of the kGradReplicas copies
     size_t pack;                  // bytes of the MLP's repacked weights at the end of `saved` (fused MLP)
     bool fused_mlp, fused_mlp_bwd;
+    bool wide_mlp;                // forward of the MLP half by the streaming kernel for wide layers
 };
 
 int make_plan(const astl_desc *d, Plan *p)
@@ -372,13 +373,15 @@ int make_plan(const astl_desc *d, Plan *p)
     p->fused_mlp = d->attn.dtype == GSWA_BF16 && !(d->attn.flags & GSWA_FORCE_STAGED) &&
                    astl_mlp_supported(p->C, p->Hd);
     p->fused_mlp_bwd = p->fused_mlp && astl_mlp_bwd_supported(p->C, p->Hd);
+    p->wide_mlp = !p->fused_mlp && d->attn.dtype == GSWA_BF16 && !(d->attn.flags & GSWA_FORCE_STAGED) &&
+                  astl_mlp_wide_supported(p->C, p->Hd);
     // (with the fused MLP backward only LN_1's two vectors go through the gradient copies)
     p->params = p->fused_mlp_bwd ? 2 * (size_t)p->C : 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
     p->reps = align256(kGradReplicas * p->params * sizeof(float));
-    p->pack = p->fused_mlp ? astl_mlp_pack_bytes() : 0;
+    p->pack = p->fused_mlp ? astl_mlp_pack_bytes() : p->wide_mlp ? astl_mlp_wide_pack_bytes() : 0;
     p->saved = p->act + p->at_saved + p->pack;
     // forward: xn | a | max(attention scratch (+ its saved state at inference), pre | h)
-    const size_t hid_f = p->fused_mlp ? 0 : 2 * p->hid;
+    const size_t hid_f = p->fused_mlp || p->wide_mlp ? 0 : 2 * p->hid;
     p->fwd_ws = 2 * p->act + (p->at_fws > hid_f ? p->at_fws : hid_f);
     // backward: xn | dn | dx1 | max(pre | h | dh, attention scratch) | copies of the gradients
     const size_t hid_b = p->fused_mlp_bwd ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd) : 3 * p->hid;
@@ -440,6 +443,20 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
                                      (const bf16_t *)p->w_fc2, (const bf16_t *)p->b_fc2,
                                      (bf16_t *)x1, (bf16_t *)y, pack, nx ? (const bf16_t *)nx->ln1_w : nullptr,
                                      nx ? (const bf16_t *)nx->ln1_b : nullptr, nx ? (bf16_t *)xn : nullptr, st));
+        if (link && nx) link->emitted = true;
+        return GSWA_OK;
+    }
+    if (pl.wide_mlp) {
+        // the same for wide layers, the weights streamed through LDS; x1 is stored only where the backward
+        // pass will read it
+        const astl_params *nx = link ? link->next : nullptr;
+        ASTL_HIP(launch_astl_mlp_wide_fwd(rows, C, Hd, d->eps, (const bf16_t *)x, (const bf16_t *)a,
+                                          (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
+                                          (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
+                                          (const bf16_t *)p->w_fc2, (const bf16_t *)p->b_fc2,
+                                          saved ? (bf16_t *)x1 : nullptr, (bf16_t *)y, pack,
+                                          nx ? (const bf16_t *)nx->ln1_w : nullptr,
+                                          nx ? (const bf16_t *)nx->ln1_b : nullptr, nx ? (bf16_t *)xn : nullptr, st));
         if (link && nx) link->emitted = true;
         return GSWA_OK;
     }

@@ -1,0 +1,403 @@
+// Fused forward of the MLP half of a layer (Sec. "Agile Swin Transformer Block", Eq. 5, with the skip
+// connection of Eq. 4 in the prologue) for WIDE bf16 layers: the two weight matrices together (282 KB as
+// matrix-core fragments at C = 180, hidden = 360) do not fit LDS, so they are streamed through it in units
+// of 96 hidden features (three steps of 32), double buffered, by loads that write LDS directly, one barrier
+// per unit.
+//
+// A wavefront owns 16 tokens from the first load to the last store; the hidden layer never leaves its
+// registers.  Lane (tok = lane & 15, q = lane >> 4) holds, of its token, the channels 32 p + 8 q + 0..7
+// (p < KSC): one 16-byte access per p.  Both products are taken transposed (features x tokens), weights as
+// the A operand from the fragments of the unit in LDS, activations as the B operand from registers:
+//   pre^T = W1 LN_2(x1)^T  reduces over channels: k-slot j of lane q in step p is channel 32 p + 8 q + j,
+//                          the order the row was loaded in;
+//   y^T  += W2 h^T         reduces over the unit's 32 hidden features: h^T comes out of the first product
+//                          with features 16 ft + 4 q + i of token tok in the lane, and the two tiles of
+//                          the unit pack into one B operand (k-slot j = feature 16 (j >> 2) + 4 q + (j & 3));
+//                          the ROWS of the W2 fragments are ordered so that a lane's results of channel
+//                          tiles 2p and 2p + 1 are again the channels 32 p + 8 q + 0..7: the skip of Eq. 5
+//                          adds the lane's own x1 registers and y leaves in 16-byte pieces.
+// Arithmetic follows the one-kernel-per-step path value by value (x1 and LN_2(x1) rounded to bf16, the
+// pre-activation rounded before the GELU), so the backward pass recomputes exactly this hidden layer.
+#include "astl_mlp.h"
+#include "mfma.h"
+#include "staged_kernels.h"
+#include "profile.h"
+
+namespace gswa {
+
+namespace {
+
+constexpr int kWideThreads = 512;
+constexpr int kWideWaves = kWideThreads / 64;
+
+struct __attribute__((aligned(4))) row16 {
+    uint32_t v[4];
+};
+
+struct WideMlpArgs {
+    long rows;
+    int C, Hd;
+    float eps;
+    const bf16_t *x, *a;       // x1 = x + a
+    const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+    bf16_t *x1, *y;
+    const bf16_t *nxt_w, *nxt_b; // optional: gamma, beta of the LayerNorm that reads y next ...
+    bf16_t *xn_out;              // ... and where its output goes (null: not wanted)
+    void *pack;
+};
+
+// KSC k-steps of 32 channels, KSF steps of 32 hidden features, HU of them per stream unit.
+template <int KSC, int KSF> struct WideMlp {
+    static constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    static constexpr int HU = 3;
+    static_assert(KSF % HU == 0, "whole units");
+    static constexpr int FR_STEP = 2 * KSC + CT;        // W1: 2 feature tiles x KSC steps | W2: CT channel tiles x 1 step
+    static constexpr int FR_UNIT = HU * FR_STEP;
+    static constexpr int UNIT_BYTES = FR_UNIT * 1024;
+    static constexpr int FPW = (FR_UNIT + kWideWaves - 1) / kWideWaves; // fragments a wave moves per unit
+    // tables behind the fragments, in the pack and in LDS alike (floats):
+    //   b1 [FT * 16] | b2 [CT * 16] | (gamma, beta) of LN_2 [32 KSC][2] | (gamma, beta) of the next LN [32 KSC][2]
+    static constexpr int T_B1 = 0, T_B2 = FT * 16, T_GB = T_B2 + CT * 16, T_NGB = T_GB + 64 * KSC;
+    static constexpr int T_FLOATS = T_NGB + 64 * KSC;
+    static constexpr size_t P_TABLES = (size_t)(KSF / HU) * UNIT_BYTES;
+    static constexpr size_t P_BYTES = P_TABLES + (size_t)T_FLOATS * 4;
+    static constexpr int OFF_TABLES = 2 * UNIT_BYTES;
+    static constexpr size_t LDS_BYTES = (size_t)OFF_TABLES + (size_t)T_FLOATS * 4;
+    static_assert(T_FLOATS % 4 == 0, "tables are copied in 16-byte pieces");
+};
+
+__device__ __forceinline__ float bfv(const bf16_t *p, long i) { return __uint_as_float((uint32_t)p[i].bits << 16); }
+
+// Once per forward call: the weights in the order the units are streamed in, zero outside the matrices.
+template <int KSC, int KSF>
+__global__ __launch_bounds__(256) void astl_mlp_wide_pack_kernel(WideMlpArgs a, int nu)
+{
+    using L = WideMlp<KSC, KSF>;
+    const int C = a.C, Hd = a.Hd;
+    uint16_t *d16 = static_cast<uint16_t *>(a.pack);
+    const int total = nu * L::FR_UNIT * 512; // (nu units: steps of hidden features beyond the matrix are zero)
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+        const int j = e & 7, l = (e >> 3) & 63, fr = e >> 9;
+        const int u = fr / L::FR_STEP, f = fr - u * L::FR_STEP; // u: step of 32 hidden features
+        const int m = l & 15, lq = l >> 4;
+        float v = 0.f;
+        if (f < 2 * KSC) {
+            const int jt = f / KSC, s = f - jt * KSC;
+            const int hid = 16 * (2 * u + jt) + m, ch = 32 * s + 8 * lq + j;
+            if (hid < Hd && ch < C) v = bfv(a.w_fc1, (long)hid * C + ch);
+        } else {
+            const int ct = f - 2 * KSC;
+            const int ch = 32 * (ct >> 1) + 8 * (m >> 2) + 4 * (ct & 1) + (m & 3);
+            const int hid = 16 * (2 * u + (j >> 2)) + 4 * lq + (j & 3);
+            if (hid < Hd && ch < C) v = bfv(a.w_fc2, (long)ch * Hd + hid);
+        }
+        d16[e] = f32_to_bf16_bits(v);
+    }
+    float *tb = reinterpret_cast<float *>(static_cast<uint8_t *>(a.pack) + L::P_TABLES);
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < L::T_FLOATS; i += gridDim.x * 256) {
+        float v = 0.f;
+        if (i < L::T_B2) {
+            if (i < Hd) v = bfv(a.b_fc1, i);
+        } else if (i < L::T_GB) {
+            if (i - L::T_B2 < C) v = bfv(a.b_fc2, i - L::T_B2);
+        } else if (i < L::T_NGB) {
+            const int c = (i - L::T_GB) >> 1;
+            if (c < C) v = bfv((i & 1) ? a.ln_b : a.ln_w, c);
+        } else if (a.nxt_w) {
+            const int c = (i - L::T_NGB) >> 1;
+            if (c < C) v = bfv((i & 1) ? a.nxt_b : a.nxt_w, c);
+        }
+        tb[i] = v;
+    }
+}
+
+// LayerNorm of a row held as packed bf16 in the lane pattern of this file (zero beyond C): the row is
+// spread over the four lanes that share tok.  Mean first, then the squared distances from it, as the
+// LayerNorm kernel of the one-kernel-per-step path computes them; result rounded to bf16, zero beyond C.
+template <int KSC>
+__device__ __forceinline__ void layer_norm_rows(uint32_t (&r)[KSC][4], int C, int q, float eps, const float2 *gb)
+{
+    asm volatile("" : "+v"(q)); // (as in load_rows)
+    float sum = 0.f;
+#pragma unroll
+    for (int p = 0; p < KSC; ++p)
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw) sum += bf16_lo(r[p][dw]) + bf16_hi(r[p][dw]);
+    const float mean = qgroup_sum(sum) / (float)C;
+    // (each pass unpacks the row again: the unpacked values of a whole row would take twice its registers)
+#pragma unroll
+    for (int p = 0; p < KSC; ++p)
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw) asm volatile("" : "+v"(r[p][dw]));
+    float dev = 0.f;
+#pragma unroll
+    for (int p = 0; p < KSC; ++p)
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw)
+            if (32 * p + 8 * q + 2 * dw < C) {
+                const float d0 = bf16_lo(r[p][dw]) - mean, d1 = bf16_hi(r[p][dw]) - mean;
+                dev += d0 * d0 + d1 * d1;
+            }
+    const float rstd = rsqrtf(qgroup_sum(dev) / (float)C + eps);
+#pragma unroll
+    for (int p = 0; p < KSC; ++p)
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw) asm volatile("" : "+v"(r[p][dw]));
+#pragma unroll
+    for (int p = 0; p < KSC; ++p) {
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw) {
+            const int c = 32 * p + 8 * q + 2 * dw;
+            const float4 g = *reinterpret_cast<const float4 *>(gb + c); // (gamma, beta) of c and c + 1; zero beyond C
+            r[p][dw] = pack_bf16x2((bf16_lo(r[p][dw]) - mean) * rstd * g.x + g.y,
+                                   (bf16_hi(r[p][dw]) - mean) * rstd * g.z + g.w);
+        }
+        __builtin_amdgcn_sched_barrier(0); // (one step's scale and shift in registers at a time)
+    }
+}
+
+// the lane's pieces of row t: channels 32 p + 8 q + 0..7 (zero beyond C or the rows).  Steps that lie inside
+// the row for every lane (a wave-uniform test) are read from a clamped row without a condition on the load.
+template <int KSC>
+__device__ __forceinline__ void load_rows(const bf16_t *base, long t, bool ok, long rows, int C, int q,
+                                          uint32_t (&r)[KSC][4])
+{
+    const uint32_t *b32 = reinterpret_cast<const uint32_t *>(base);
+    const long tc = t < rows ? t : rows - 1;
+    asm volatile("" : "+v"(q)); // (offsets and masks are made per call: kept, they would take dozens of registers)
+#pragma unroll
+    for (int p = 0; p < KSC; ++p) {
+        const int c0 = 32 * p + 8 * q;
+        if (p < KSC - 2 || 32 * p + 32 <= C) { // (C > 32 (KSC - 2): only the last two steps can be ragged)
+            const row16 u = *reinterpret_cast<const row16 *>(b32 + ((tc * C + c0) >> 1));
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) r[p][dw] = ok ? u.v[dw] : 0u;
+        } else {
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int c = c0 + 2 * dw;
+                const uint32_t v = b32[(tc * C + (c < C ? c : 0)) >> 1];
+                r[p][dw] = ok && c < C ? v : 0u;
+            }
+        }
+    }
+}
+
+template <int KSC>
+__device__ __forceinline__ void store_rows(bf16_t *base, long t, bool ok, int C, int q, const uint32_t (&r)[KSC][4])
+{
+    uint32_t *b32 = reinterpret_cast<uint32_t *>(base);
+    asm volatile("" : "+v"(q)); // (as in load_rows)
+#pragma unroll
+    for (int p = 0; p < KSC; ++p) {
+        const int c0 = 32 * p + 8 * q;
+        if (p < KSC - 2 || 32 * p + 32 <= C) { // (C > 32 (KSC - 2): only the last two steps can be ragged)
+            if (ok) {
+                row16 u;
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) u.v[dw] = r[p][dw];
+                *reinterpret_cast<row16 *>(b32 + ((t * C + c0) >> 1)) = u;
+            }
+        } else {
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw)
+                if (ok && c0 + 2 * dw < C) b32[(t * C + c0 + 2 * dw) >> 1] = r[p][dw];
+        }
+    }
+}
+
+template <int KSC, int KSF>
+__global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_fwd_kernel(WideMlpArgs a, int nu)
+{
+    using L = WideMlp<KSC, KSF>;
+    constexpr int CT = L::CT;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint8_t *pack = static_cast<const uint8_t *>(a.pack);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, tok = lane & 15, q = lane >> 4;
+    const int C = a.C;
+    int lane_r = lane;
+
+    // One load instruction moves one fragment (64 lanes x 16 bytes land at the wave-uniform LDS address
+    // + 16 lane); wave w moves fragments w, w + 8, ... of the unit.
+    auto stream_unit = [&](int u, int slot) {
+        int ln = lane_r;
+        asm volatile("" : "+v"(ln)); // (the per-fragment addresses are made here, not kept over the unit loop)
+        const uint8_t *src = pack + (size_t)u * L::UNIT_BYTES + 16 * ln;
+        uint8_t *dst = lds + (size_t)slot * L::UNIT_BYTES;
+#pragma unroll 1
+        for (int k = 0; k < L::FPW; ++k) { // (not unrolled: one address in registers at a time)
+            const int f = k * kWideWaves + wv;
+            if (f < L::FR_UNIT) lds_dma16(src + (size_t)f * 1024, dst + (size_t)f * 1024);
+        }
+    };
+
+    const long ntiles = (a.rows + 15) / 16;
+    const long stride = (long)gridDim.x * kWideWaves;
+    const int rounds = (int)((ntiles + stride - 1) / stride);
+    long tile = (long)blockIdx.x * kWideWaves + wv;
+
+    uint32_t rx[KSC][4], ra[KSC][4];
+    load_rows<KSC>(a.x, tile * 16 + tok, tile * 16 + tok < a.rows, a.rows, C, q, rx);
+    load_rows<KSC>(a.a, tile * 16 + tok, tile * 16 + tok < a.rows, a.rows, C, q, ra);
+
+    stream_unit(0, 0);
+    for (int i = tid; i < L::T_FLOATS / 4; i += kWideThreads)
+        reinterpret_cast<uint4 *>(lds + L::OFF_TABLES)[i] = reinterpret_cast<const uint4 *>(pack + L::P_TABLES)[i];
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    int slot = 0; // buffer the unit about to be used lies in
+    for (int round = 0; round < rounds; ++round, tile += stride) {
+        const bool more = round + 1 < rounds;
+        const long t = tile * 16 + tok;
+        const bool ok = t < a.rows;
+        uint32_t lds0 = 0;
+        asm volatile("" : "+v"(lds0)); // keeps the LDS reads of a round inside the round
+        lane_r = lane;
+        asm volatile("" : "+v"(lane_r));
+        const float *tb = reinterpret_cast<const float *>(lds + lds0 + L::OFF_TABLES);
+
+        // Eq. 4's skip; the stored (rounded) sum is what LN_2 sees here and in the backward pass
+        uint32_t x1[KSC][4];
+#pragma unroll
+        for (int p = 0; p < KSC; ++p)
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw)
+                x1[p][dw] = pack_bf16x2(bf16_lo(rx[p][dw]) + bf16_lo(ra[p][dw]), bf16_hi(rx[p][dw]) + bf16_hi(ra[p][dw]));
+        {   // the next round's rows are on their way while this one is computed
+            const long tn = t + stride * 16;
+            load_rows<KSC>(a.x, tn, more && tn < a.rows, a.rows, C, q, rx);
+            load_rows<KSC>(a.a, tn, more && tn < a.rows, a.rows, C, q, ra);
+        }
+        if (a.x1) store_rows<KSC>(a.x1, t, ok, C, q, x1);
+        uint32_t bx[KSC][4];
+#pragma unroll
+        for (int p = 0; p < KSC; ++p)
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) bx[p][dw] = x1[p][dw];
+        layer_norm_rows<KSC>(bx, C, q, a.eps, reinterpret_cast<const float2 *>(tb + L::T_GB));
+
+        f32x4 yacc[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) yacc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // one loop over the steps of 32 hidden features; every HU-th step starts a unit (the next one is sent
+        // on its way) and every unit ends with the barrier that hands the next one over
+        int hs = 0, unit = 0;
+        for (int st = 0; st < L::HU * nu; ++st) {
+            if (hs == 0) {
+                // into the other buffer (the first unit of the next round after the last): every wave has
+                // passed the previous barrier, i.e. finished reading that buffer
+                if (unit + 1 < nu) stream_unit(unit + 1, slot ^ 1);
+                else if (more) stream_unit(0, slot ^ 1);
+            }
+            const uint4 *ws = reinterpret_cast<const uint4 *>(lds + lds0 + (size_t)slot * L::UNIT_BYTES) + hs * L::FR_STEP * 64;
+            const int f0 = 32 * st; // hidden features f0 + 16 jt + 4 q + i of token tok
+            f32x4 h0 = f32x4{0.f, 0.f, 0.f, 0.f}, h1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSC; ++s) {
+                const uint4 b = make_uint4(bx[s][0], bx[s][1], bx[s][2], bx[s][3]);
+                h0 = mma32(ws[s * 64 + lane_r], b, h0);
+                h1 = mma32(ws[(KSC + s) * 64 + lane_r], b, h1);
+                if (s % 3 == 2) __builtin_amdgcn_sched_barrier(0); // (at most six fragments on their way at a time)
+            }
+            const float4 b10 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 4 * q);
+            const float4 b11 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 16 + 4 * q);
+            // the pre-activation as the one-kernel-per-step path stores it (rounded), then the GELU
+            const uint32_t pp[4] = {pack_bf16x2(h0[0] + b10.x, h0[1] + b10.y), pack_bf16x2(h0[2] + b10.z, h0[3] + b10.w),
+                                    pack_bf16x2(h1[0] + b11.x, h1[1] + b11.y), pack_bf16x2(h1[2] + b11.z, h1[3] + b11.w)};
+            uint32_t hp[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float r0 = bf16_lo(pp[i]), r1 = bf16_hi(pp[i]);
+                float Phi0, Phi1, phi;
+                gauss(r0, Phi0, phi);
+                gauss(r1, Phi1, phi);
+                hp[i] = pack_bf16x2(r0 * Phi0, r1 * Phi1);
+            }
+            const uint4 hb = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                yacc[ct] = mma32(ws[(2 * KSC + ct) * 64 + lane_r], hb, yacc[ct]);
+                if (ct % 4 == 3) __builtin_amdgcn_sched_barrier(0); // (at most four)
+            }
+
+            if (++hs == L::HU) {
+                // the next unit has landed in LDS before any wave reads it
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+                slot ^= 1;
+                hs = 0;
+                ++unit;
+            }
+        }
+
+        // bias and the skip of Eq. 5; tiles 2p and 2p + 1 hold the lane's channels 32 p + 8 q + 0..3 and + 4..7
+        uint32_t yo[KSC][4];
+#pragma unroll
+        for (int p = 0; p < KSC; ++p) {
+            const float4 b2a = *reinterpret_cast<const float4 *>(tb + L::T_B2 + 32 * p + 8 * q);
+            const float4 b2b = *reinterpret_cast<const float4 *>(tb + L::T_B2 + 32 * p + 8 * q + 4);
+            const f32x4 lo = yacc[2 * p], hi = yacc[2 * p + 1];
+            yo[p][0] = pack_bf16x2(lo[0] + b2a.x + bf16_lo(x1[p][0]), lo[1] + b2a.y + bf16_hi(x1[p][0]));
+            yo[p][1] = pack_bf16x2(lo[2] + b2a.z + bf16_lo(x1[p][1]), lo[3] + b2a.w + bf16_hi(x1[p][1]));
+            yo[p][2] = pack_bf16x2(hi[0] + b2b.x + bf16_lo(x1[p][2]), hi[1] + b2b.y + bf16_hi(x1[p][2]));
+            yo[p][3] = pack_bf16x2(hi[2] + b2b.z + bf16_lo(x1[p][3]), hi[3] + b2b.w + bf16_hi(x1[p][3]));
+        }
+        store_rows<KSC>(a.y, t, ok, C, q, yo);
+        if (a.xn_out) {
+            // the LayerNorm of the layer that follows, taken of y as stored (the padding channels of the lane
+            // hold b2 = 0 plus x1 = 0 plus products with zero weight rows: zero)
+            layer_norm_rows<KSC>(yo, C, q, a.eps, reinterpret_cast<const float2 *>(tb + L::T_NGB));
+            store_rows<KSC>(a.xn_out, t, ok, C, q, yo);
+        }
+    }
+}
+
+template <int KSC, int KSF> hipError_t launch_wide_t(const WideMlpArgs &a, hipStream_t s)
+{
+    using L = WideMlp<KSC, KSF>;
+    const int nu = ((a.Hd + 31) / 32 + L::HU - 1) / L::HU; // stream units
+    {
+        KernelTimer kt(K_MLP_PACK, s);
+        hipLaunchKernelGGL((astl_mlp_wide_pack_kernel<KSC, KSF>), dim3(64), dim3(256), 0, s, a, nu);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    auto kern = astl_mlp_wide_fwd_kernel<KSC, KSF>;
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), L::LDS_BYTES); ea != hipSuccess) return ea;
+    const long tiles = (a.rows + 15) / 16;
+    long blocks = (tiles + kWideWaves - 1) / kWideWaves;
+    if (blocks > device_cu_count()) blocks = device_cu_count(); // (one workgroup of eight waves per compute unit)
+    KernelTimer kt(K_MLP_FWD, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(blocks < 1 ? 1 : blocks)), dim3(kWideThreads), L::LDS_BYTES, s, a, nu);
+    return hipGetLastError();
+}
+
+} // namespace
+
+bool astl_mlp_wide_supported(int C, int hidden)
+{
+    return C > 64 && C <= 192 && C % 4 == 0 && hidden >= 32 && hidden <= 384 && hidden % 4 == 0;
+}
+
+size_t astl_mlp_wide_pack_bytes() { return (WideMlp<6, 12>::P_BYTES + 255) & ~size_t(255); }
+
+hipError_t launch_astl_mlp_wide_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
+                                    const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
+                                    const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
+                                    const bf16_t *next_ln_w, const bf16_t *next_ln_b, bf16_t *next_ln_out, hipStream_t s)
+{
+    if (!astl_mlp_wide_supported(C, hidden) || rows <= 0) return hipErrorInvalidValue;
+    WideMlpArgs m{};
+    m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
+    m.x = x; m.a = a; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2; m.b_fc2 = b_fc2;
+    m.x1 = x1; m.y = y; m.pack = pack;
+    if (next_ln_out && next_ln_w && next_ln_b) {
+        m.nxt_w = next_ln_w; m.nxt_b = next_ln_b; m.xn_out = next_ln_out;
+    }
+    if (C <= 128) return launch_wide_t<4, 12>(m, s);
+    return launch_wide_t<6, 12>(m, s);
+}
+
+} // namespace gswa
