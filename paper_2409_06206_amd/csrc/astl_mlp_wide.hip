@@ -30,6 +30,15 @@ namespace {
 constexpr int kWideThreads = 512;
 constexpr int kWideWaves = kWideThreads / 64;
 
+// s_waitcnt immediate: vector-memory counter down to 2 KSC, the other counters not waited for
+// (vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+template <int KSC> constexpr int kWaitAllBut2Ksc = ((2 * KSC) & 15) | (((2 * KSC) >> 4) << 14) | (7 << 4) | (15 << 8);
+
+// a lane's 16-byte piece of a row as ONE four-register value (kept whole from the load to its use: loose
+// dwords carried around the round loop get copied right behind the load, which waits for it)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+
 struct __attribute__((aligned(4))) row16 {
     uint32_t v[4];
 };
@@ -156,29 +165,42 @@ __device__ __forceinline__ void layer_norm_rows(uint32_t (&r)[KSC][4], int C, in
     }
 }
 
-// the lane's pieces of row t: channels 32 p + 8 q + 0..7 (zero beyond C or the rows).  Steps that lie inside
-// the row for every lane (a wave-uniform test) are read from a clamped row without a condition on the load.
+// The lane's pieces of row t: channels 32 p + 8 q + 0..7, as one 16-byte load per step that nothing here
+// computes with, so that the loads can stay in flight until their registers are used; tidy_rows() then puts
+// the ragged end of the row right.  A piece that would reach beyond the row is read 8 channels before the
+// row's end instead (C is a multiple of 4, so a piece is whole, the row's last 4 channels, or nothing).  Rows
+// beyond the last one read the last one (their results are never stored, and a token's values stay in its
+// own column of every product).
 template <int KSC>
-__device__ __forceinline__ void load_rows(const bf16_t *base, long t, bool ok, long rows, int C, int q,
-                                          uint32_t (&r)[KSC][4])
+__device__ __forceinline__ void load_rows(const bf16_t *base, long t, long rows, int C, int q, u32x4 (&r)[KSC])
 {
     const uint32_t *b32 = reinterpret_cast<const uint32_t *>(base);
     const long tc = t < rows ? t : rows - 1;
     asm volatile("" : "+v"(q)); // (offsets and masks are made per call: kept, they would take dozens of registers)
 #pragma unroll
     for (int p = 0; p < KSC; ++p) {
-        const int c0 = 32 * p + 8 * q;
-        if (p < KSC - 2 || 32 * p + 32 <= C) { // (C > 32 (KSC - 2): only the last two steps can be ragged)
-            const row16 u = *reinterpret_cast<const row16 *>(b32 + ((tc * C + c0) >> 1));
+        int c0 = 32 * p + 8 * q;
+        if (p >= KSC - 2 && c0 + 8 > C) c0 = C - 8; // (C > 32 (KSC - 2): only the last two steps can be ragged)
+        r[p] = *reinterpret_cast<const u32x4_a4 *>(b32 + ((tc * C + c0) >> 1));
+    }
+}
+
+// after load_rows, once the values are wanted: zero beyond C, the row's last 4 channels moved into place
+template <int KSC>
+__device__ __forceinline__ void tidy_rows(int C, int q, const u32x4 (&r)[KSC], uint32_t (&o)[KSC][4])
+{
+    asm volatile("" : "+v"(q));
 #pragma unroll
-            for (int dw = 0; dw < 4; ++dw) r[p][dw] = ok ? u.v[dw] : 0u;
+    for (int p = 0; p < KSC; ++p) {
+        if (p < KSC - 2) {
+            o[p][0] = r[p].x; o[p][1] = r[p].y; o[p][2] = r[p].z; o[p][3] = r[p].w;
         } else {
-#pragma unroll
-            for (int dw = 0; dw < 4; ++dw) {
-                const int c = c0 + 2 * dw;
-                const uint32_t v = b32[(tc * C + (c < C ? c : 0)) >> 1];
-                r[p][dw] = ok && c < C ? v : 0u;
-            }
+            const int c0 = 32 * p + 8 * q;
+            const bool whole = c0 + 8 <= C, half = c0 + 4 == C;
+            o[p][0] = whole ? r[p].x : half ? r[p].z : 0u;
+            o[p][1] = whole ? r[p].y : half ? r[p].w : 0u;
+            o[p][2] = whole ? r[p].z : 0u;
+            o[p][3] = whole ? r[p].w : 0u;
         }
     }
 }
@@ -236,9 +258,9 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_fwd_kernel(WideMlp
     const int rounds = (int)((ntiles + stride - 1) / stride);
     long tile = (long)blockIdx.x * kWideWaves + wv;
 
-    uint32_t rx[KSC][4], ra[KSC][4];
-    load_rows<KSC>(a.x, tile * 16 + tok, tile * 16 + tok < a.rows, a.rows, C, q, rx);
-    load_rows<KSC>(a.a, tile * 16 + tok, tile * 16 + tok < a.rows, a.rows, C, q, ra);
+    u32x4 rx[KSC], ra[KSC];
+    load_rows<KSC>(a.x, tile * 16 + tok, a.rows, C, q, rx);
+    load_rows<KSC>(a.a, tile * 16 + tok, a.rows, C, q, ra);
 
     stream_unit(0, 0);
     for (int i = tid; i < L::T_FLOATS / 4; i += kWideThreads)
@@ -259,15 +281,15 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_fwd_kernel(WideMlp
 
         // Eq. 4's skip; the stored (rounded) sum is what LN_2 sees here and in the backward pass
         uint32_t x1[KSC][4];
+        {
+            uint32_t xv[KSC][4], av[KSC][4];
+            tidy_rows<KSC>(C, q, rx, xv);
+            tidy_rows<KSC>(C, q, ra, av);
 #pragma unroll
-        for (int p = 0; p < KSC; ++p)
+            for (int p = 0; p < KSC; ++p)
 #pragma unroll
-            for (int dw = 0; dw < 4; ++dw)
-                x1[p][dw] = pack_bf16x2(bf16_lo(rx[p][dw]) + bf16_lo(ra[p][dw]), bf16_hi(rx[p][dw]) + bf16_hi(ra[p][dw]));
-        {   // the next round's rows are on their way while this one is computed
-            const long tn = t + stride * 16;
-            load_rows<KSC>(a.x, tn, more && tn < a.rows, a.rows, C, q, rx);
-            load_rows<KSC>(a.a, tn, more && tn < a.rows, a.rows, C, q, ra);
+                for (int dw = 0; dw < 4; ++dw)
+                    x1[p][dw] = pack_bf16x2(bf16_lo(xv[p][dw]) + bf16_lo(av[p][dw]), bf16_hi(xv[p][dw]) + bf16_hi(av[p][dw]));
         }
         if (a.x1) store_rows<KSC>(a.x1, t, ok, C, q, x1);
         uint32_t bx[KSC][4];
@@ -281,55 +303,68 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_fwd_kernel(WideMlp
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) yacc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        // one loop over the steps of 32 hidden features; every HU-th step starts a unit (the next one is sent
-        // on its way) and every unit ends with the barrier that hands the next one over
-        int hs = 0, unit = 0;
-        for (int st = 0; st < L::HU * nu; ++st) {
-            if (hs == 0) {
-                // into the other buffer (the first unit of the next round after the last): every wave has
-                // passed the previous barrier, i.e. finished reading that buffer
-                if (unit + 1 < nu) stream_unit(unit + 1, slot ^ 1);
-                else if (more) stream_unit(0, slot ^ 1);
-            }
-            const uint4 *ws = reinterpret_cast<const uint4 *>(lds + lds0 + (size_t)slot * L::UNIT_BYTES) + hs * L::FR_STEP * 64;
-            const int f0 = 32 * st; // hidden features f0 + 16 jt + 4 q + i of token tok
-            f32x4 h0 = f32x4{0.f, 0.f, 0.f, 0.f}, h1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        // The steps of a unit, written out one after the other (the products of one step can run under the
+        // GELU of the step before).
+        auto unit_steps = [&](int unit) {
+            const uint4 *wu = reinterpret_cast<const uint4 *>(lds + lds0 + (size_t)slot * L::UNIT_BYTES);
 #pragma unroll
-            for (int s = 0; s < KSC; ++s) {
-                const uint4 b = make_uint4(bx[s][0], bx[s][1], bx[s][2], bx[s][3]);
-                h0 = mma32(ws[s * 64 + lane_r], b, h0);
-                h1 = mma32(ws[(KSC + s) * 64 + lane_r], b, h1);
-                if (s % 3 == 2) __builtin_amdgcn_sched_barrier(0); // (at most six fragments on their way at a time)
-            }
-            const float4 b10 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 4 * q);
-            const float4 b11 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 16 + 4 * q);
-            // the pre-activation as the one-kernel-per-step path stores it (rounded), then the GELU
-            const uint32_t pp[4] = {pack_bf16x2(h0[0] + b10.x, h0[1] + b10.y), pack_bf16x2(h0[2] + b10.z, h0[3] + b10.w),
-                                    pack_bf16x2(h1[0] + b11.x, h1[1] + b11.y), pack_bf16x2(h1[2] + b11.z, h1[3] + b11.w)};
-            uint32_t hp[4];
+            for (int hs = 0; hs < L::HU; ++hs) {
+                const uint4 *ws = wu + hs * L::FR_STEP * 64;
+                const int f0 = 32 * (L::HU * unit + hs); // hidden features f0 + 16 jt + 4 q + i of token tok
+                f32x4 h0 = f32x4{0.f, 0.f, 0.f, 0.f}, h1 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float r0 = bf16_lo(pp[i]), r1 = bf16_hi(pp[i]);
-                float Phi0, Phi1, phi;
-                gauss(r0, Phi0, phi);
-                gauss(r1, Phi1, phi);
-                hp[i] = pack_bf16x2(r0 * Phi0, r1 * Phi1);
-            }
-            const uint4 hb = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+                for (int s = 0; s < KSC; ++s) {
+                    const uint4 b = make_uint4(bx[s][0], bx[s][1], bx[s][2], bx[s][3]);
+                    h0 = mma32(ws[s * 64 + lane_r], b, h0);
+                    h1 = mma32(ws[(KSC + s) * 64 + lane_r], b, h1);
+                }
+                const float4 b10 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 4 * q);
+                const float4 b11 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 16 + 4 * q);
+                // the pre-activation as the one-kernel-per-step path stores it (rounded), then the GELU
+                const uint32_t pp[4] = {pack_bf16x2(h0[0] + b10.x, h0[1] + b10.y), pack_bf16x2(h0[2] + b10.z, h0[3] + b10.w),
+                                        pack_bf16x2(h1[0] + b11.x, h1[1] + b11.y), pack_bf16x2(h1[2] + b11.z, h1[3] + b11.w)};
+                uint32_t hp[4];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                yacc[ct] = mma32(ws[(2 * KSC + ct) * 64 + lane_r], hb, yacc[ct]);
-                if (ct % 4 == 3) __builtin_amdgcn_sched_barrier(0); // (at most four)
+                for (int i = 0; i < 4; ++i) {
+                    const float r0 = bf16_lo(pp[i]), r1 = bf16_hi(pp[i]);
+                    float Phi0, Phi1, phi;
+                    gauss(r0, Phi0, phi);
+                    gauss(r1, Phi1, phi);
+                    hp[i] = pack_bf16x2(r0 * Phi0, r1 * Phi1);
+                }
+                const uint4 hb = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) yacc[ct] = mma32(ws[(2 * KSC + ct) * 64 + lane_r], hb, yacc[ct]);
             }
+        };
 
-            if (++hs == L::HU) {
-                // the next unit has landed in LDS before any wave reads it
-                __builtin_amdgcn_s_waitcnt(0);
-                __syncthreads();
-                slot ^= 1;
-                hs = 0;
-                ++unit;
-            }
+        // First unit of the round (written apart from the loop over the others, so that the compiler sees that
+        // the row loads below are not in flight when it runs): the second unit is sent on its way into the
+        // other buffer (every wave has passed the previous barrier, i.e. finished reading that buffer), and
+        // BEHIND its loads the next round's rows, which have until the end of the round.
+        if (nu > 1) stream_unit(1, slot ^ 1);
+        else if (more) stream_unit(0, slot ^ 1);
+        if (more) {
+            const long tn = t + stride * 16;
+            load_rows<KSC>(a.x, tn, a.rows, C, q, rx);
+            load_rows<KSC>(a.a, tn, a.rows, C, q, ra);
+        }
+        unit_steps(0);
+        // The next unit has landed in LDS before any wave reads it.  Vector-memory operations complete in the
+        // order they were issued, so "at most n outstanding" covers everything older than the n youngest: here
+        // those are the row loads (each of the KSC steps of the two tensors is one load instruction), which
+        // stay in flight.
+        if (more) __builtin_amdgcn_s_waitcnt(kWaitAllBut2Ksc<KSC>);
+        else __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        slot ^= 1;
+        for (int unit = 1; unit < nu; ++unit) {
+            if (unit + 1 < nu) stream_unit(unit + 1, slot ^ 1);
+            else if (more) stream_unit(0, slot ^ 1); // (the first unit of the next round)
+            unit_steps(unit);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            slot ^= 1;
         }
 
         // bias and the skip of Eq. 5; tiles 2p and 2p + 1 hold the lane's channels 32 p + 8 q + 0..3 and + 4..7
