@@ -162,6 +162,40 @@ def test_extreme_widths(case):
     parity.check_block(astl_oracle, **case)
 
 
+@pytest.mark.parametrize("C,hidden,tokens", [
+    (180, 360, (1, 8, 12)),    # the benchmark's widths, 96 tokens: fewer tiles than waves of a workgroup
+    (192, 384, (1, 8, 8)),     # every tile of both instantiation's largest shape full
+    (132, 100, (2, 8, 12)),    # narrowest of the six-step kernel: two ragged channel steps; hidden not a multiple of 32
+    (128, 256, (1, 12, 8)),    # widest of the four-step kernel, whole steps only
+    (68, 32, (3, 4, 4)),       # narrowest wide layer, one stream unit, one of its three hidden steps in use
+    (100, 196, (1, 20, 4)),    # the row's last four channels alone in a piece (C % 8 == 4), ragged hidden step
+    (96, 384, (5, 4, 4)),
+])
+def test_shape_edges_of_the_streaming_mlp_forward_of_wide_layers(C, hidden, tokens):
+    """Layers wider than 64 channels (up to 192, hidden up to 384) take the forward kernel that streams the
+    MLP's weights through LDS: channel counts around its 32-channel steps, hidden widths around its 32-feature
+    steps and 96-feature units, token counts that are not a multiple of the 16-token tiles."""
+    import torch
+    B, H, W = tokens
+    case = dict(B=B, H=H, W=W, C=C, heads=4, groups=2, window=4, shift=1, dtype="bf16", hidden=hidden)
+    print("case", case, flush=True)
+    gswa.gswa_profile_enable(True)
+    gswa.gswa_profile_collect()
+    parity.check_block(astl_oracle, **case)
+    torch.cuda.synchronize()
+    names, dropped = gswa.gswa_profile_collect()
+    gswa.gswa_profile_enable(False)
+    assert dropped == 0
+    assert "mlp_fwd" in names and "fc2_linear" not in names, names
+
+
+def test_many_rounds_of_the_streaming_mlp_forward():
+    """More 16-token tiles than the launch has waves (several rounds per wave, a ragged last round)."""
+    case = dict(B=9, H=64, W=64, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360)
+    print("case", case, flush=True)
+    parity.check_block(astl_oracle, backward=False, **case)
+
+
 def test_ragged_token_count_in_the_fused_mlp_kernels():
     """Token counts that are not a multiple of the 16-token tiles or of the 128-token rounds."""
     for B, H, W in ((1, 4, 12), (3, 4, 4), (7, 8, 4)):
