@@ -384,7 +384,11 @@ int make_plan(const astl_desc *d, Plan *p)
     const size_t hid_f = p->fused_mlp || p->wide_mlp ? 0 : 2 * p->hid;
     p->fwd_ws = 2 * p->act + (p->at_fws > hid_f ? p->at_fws : hid_f);
     // backward: xn | dn | dx1 | max(pre | h | dh, attention scratch) | copies of the gradients
-    const size_t hid_b = p->fused_mlp_bwd ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd) : 3 * p->hid;
+    // (wide layers: h | dpre | the backward's repacked weights, then scratch of the weight gradients)
+    const size_t wpack = align256(astl_mlp_wide_bwd_pack_bytes());
+    const size_t hid_b = p->fused_mlp_bwd ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd)
+                         : p->wide_mlp    ? 2 * p->hid + (p->hid > wpack ? p->hid : wpack)
+                                          : 3 * p->hid;
     p->bwd_ws = 3 * p->act + (p->at_bws > hid_b ? p->at_bws : hid_b) + p->reps;
     return GSWA_OK;
 }
@@ -552,6 +556,36 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
                                      (const bf16_t *)p->w_fc2, (bf16_t *)dx1, g->w_fc1, g->b_fc1, g->w_fc2,
                                      g->b_fc2, g->ln2_w, g->ln2_b, accumulate, rep, (long)kGradReplicas * P,
                                      saved + pl.saved - pl.pack, rest, &mlp_sum, pend.w ? &pend : nullptr, st));
+    } else if (pl.wide_mlp) {
+        // one launch from x1 and dy to dn; LN_2(x1), h and dpre are written for the weight gradients
+        T *h = reinterpret_cast<T *>(rest), *dpre = reinterpret_cast<T *>(rest + pl.hid);
+        char *third = rest + 2 * pl.hid;
+        const size_t wpack = align256(astl_mlp_wide_bwd_pack_bytes());
+        const size_t third_bytes = pl.hid > wpack ? pl.hid : wpack;
+        ASTL_HIP(launch_astl_mlp_wide_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
+                                          (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
+                                          (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
+                                          (const bf16_t *)p->w_fc2, (bf16_t *)xn, (bf16_t *)h, (bf16_t *)dpre,
+                                          (bf16_t *)dn, third, st));
+        // d Wfc2 = dy^T h,  d Wfc1 = dpre^T LN_2(x1)  (their scratch: what the third slot has behind the pack)
+        WgradArgs w2{};
+        w2.dout = dy; w2.lddout = C; w2.a1 = h; w2.lda1 = Hd;
+        w2.dw = rep + o_w2; w2.db = rep + o_b2; w2.rep_stride = P; w2.reps = kGradReplicas;
+        w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
+        w2.scratch = third + wpack; w2.scratch_bytes = third_bytes - wpack;
+        ASTL_HIP(launch_wgrad<T>(w2, st));
+        WgradArgs w1{};
+        w1.dout = dpre; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
+        w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
+        w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
+        w1.scratch = third + wpack; w1.scratch_bytes = third_bytes - wpack;
+        ASTL_HIP(launch_wgrad<T>(w1, st));
+        // through LN_2, plus the skip of Eq. 5: dx1
+        LnBwdArgs n2{};
+        n2.u = x1; n2.dout = dn; n2.res = dy; n2.gamma = p->ln2_w; n2.du = dx1;
+        n2.dgamma = rep + o_g2; n2.dbeta = rep + o_be2; n2.rep_stride = P; n2.reps = kGradReplicas;
+        n2.rows = rows; n2.C = C; n2.eps = d->eps;
+        ASTL_HIP(launch_ln_bwd<T>(n2, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);

@@ -409,6 +409,261 @@ template <int KSC, int KSF> hipError_t launch_wide_t(const WideMlpArgs &a, hipSt
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Backward pass, the part between the two LayerNorm adjoints: one launch recomputes LN_2(x1), the
+// pre-activation and the hidden layer as the forward does and takes the gradient back to LN_2's output,
+//   dh = dy W2,   dpre = dh o GELU'(pre),   dn = dpre W1,
+// with the hidden-sized intermediates that nobody else reads (pre, dh) never leaving the registers.  What
+// the weight gradients need is written on the way: LN_2(x1), h and dpre; dn goes to LayerNorm's adjoint.
+// Same organisation as the forward kernel: 16 tokens per wave, stream units of 64 hidden features holding,
+// per step of 32, the fragments of W1 (pre), of W2^T (dh; both with their rows ordered so that a lane's
+// results of the step's two tiles are the 8 consecutive features 32 u + 8 q + 0..7: one 16-byte store per
+// tensor, and the B operand of the third product as it stands) and of W1^T (dn, rows ordered as W2's in
+// the forward).  Values are rounded where the one-kernel-per-step path stores them (pre, dh, h, dpre, dn).
+// ---------------------------------------------------------------------------------------------------------
+struct WideMlpBwdArgs {
+    long rows;
+    int C, Hd;
+    float eps;
+    const bf16_t *x1, *dy;
+    const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2;
+    bf16_t *xn, *h, *dpre, *dn; // LN_2(x1) [rows, C]; h, dpre [rows, Hd]; dn [rows, C]
+    void *pack;
+};
+
+template <int KSC, int KSF> struct WideMlpBwd {
+    static constexpr int CT = 2 * KSC, FT = 2 * KSF;
+    static constexpr int HU = 2;
+    static_assert(KSF % HU == 0, "whole units");
+    static constexpr int FR_STEP = 4 * KSC + CT; // W1: 2 tiles x KSC steps | W2^T: the same | W1^T: CT tiles x 1 step
+    static constexpr int FR_UNIT = HU * FR_STEP;
+    static constexpr int UNIT_BYTES = FR_UNIT * 1024;
+    static constexpr int FPW = (FR_UNIT + kWideWaves - 1) / kWideWaves;
+    // tables (floats): b1 [FT * 16] | (gamma, beta) of LN_2 [32 KSC][2]
+    static constexpr int T_B1 = 0, T_GB = FT * 16, T_FLOATS = T_GB + 64 * KSC;
+    static constexpr size_t P_TABLES = (size_t)(KSF / HU) * UNIT_BYTES;
+    static constexpr size_t P_BYTES = P_TABLES + (size_t)T_FLOATS * 4;
+    static constexpr int OFF_TABLES = 2 * UNIT_BYTES;
+    static constexpr size_t LDS_BYTES = (size_t)OFF_TABLES + (size_t)T_FLOATS * 4;
+    static_assert(T_FLOATS % 4 == 0, "tables are copied in 16-byte pieces");
+};
+
+template <int KSC, int KSF>
+__global__ __launch_bounds__(256) void astl_mlp_wide_bwd_pack_kernel(WideMlpBwdArgs a, int nu)
+{
+    using L = WideMlpBwd<KSC, KSF>;
+    const int C = a.C, Hd = a.Hd;
+    uint16_t *d16 = static_cast<uint16_t *>(a.pack);
+    const int total = nu * L::FR_UNIT * 512; // (nu units: steps of hidden features beyond the matrix are zero)
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+        const int j = e & 7, l = (e >> 3) & 63, fr = e >> 9;
+        const int u = fr / L::FR_STEP, f = fr - u * L::FR_STEP; // u: step of 32 hidden features
+        const int m = l & 15, lq = l >> 4;
+        float v = 0.f;
+        if (f < 4 * KSC) {
+            const int g = f < 2 * KSC ? f : f - 2 * KSC;
+            const int jt = g / KSC, s = g - jt * KSC;
+            const int hid = 32 * u + 8 * (m >> 2) + 4 * jt + (m & 3), ch = 32 * s + 8 * lq + j;
+            if (hid < Hd && ch < C) v = f < 2 * KSC ? bfv(a.w_fc1, (long)hid * C + ch) : bfv(a.w_fc2, (long)ch * Hd + hid);
+        } else {
+            const int ct = f - 4 * KSC;
+            const int ch = 32 * (ct >> 1) + 8 * (m >> 2) + 4 * (ct & 1) + (m & 3);
+            const int hid = 32 * u + 8 * lq + j;
+            if (hid < Hd && ch < C) v = bfv(a.w_fc1, (long)hid * C + ch);
+        }
+        d16[e] = f32_to_bf16_bits(v);
+    }
+    float *tb = reinterpret_cast<float *>(static_cast<uint8_t *>(a.pack) + L::P_TABLES);
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < L::T_FLOATS; i += gridDim.x * 256) {
+        float v = 0.f;
+        if (i < L::T_GB) {
+            if (i < Hd) v = bfv(a.b_fc1, i);
+        } else {
+            const int c = (i - L::T_GB) >> 1;
+            if (c < C) v = bfv((i & 1) ? a.ln_b : a.ln_w, c);
+        }
+        tb[i] = v;
+    }
+}
+
+// a lane's 8 consecutive hidden features f .. f + 7 of row t (Hd is a multiple of 4: a piece is whole, its
+// first half, or nothing)
+__device__ __forceinline__ void store_hidden(bf16_t *base, long t, bool ok, int Hd, int f, uint4 v)
+{
+    uint32_t *b32 = reinterpret_cast<uint32_t *>(base) + ((t * Hd + f) >> 1);
+    if (ok && f + 8 <= Hd) {
+        row16 u;
+        u.v[0] = v.x; u.v[1] = v.y; u.v[2] = v.z; u.v[3] = v.w;
+        *reinterpret_cast<row16 *>(b32) = u;
+    } else if (ok && f + 4 <= Hd) {
+        b32[0] = v.x;
+        b32[1] = v.y;
+    }
+}
+
+template <int KSC, int KSF>
+__global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlpBwdArgs a, int nu)
+{
+    using L = WideMlpBwd<KSC, KSF>;
+    constexpr int CT = L::CT;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint8_t *pack = static_cast<const uint8_t *>(a.pack);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, tok = lane & 15, q = lane >> 4;
+    const int C = a.C, Hd = a.Hd;
+    int lane_r = lane;
+
+    auto stream_unit = [&](int u, int slot) {
+        int ln = lane_r;
+        asm volatile("" : "+v"(ln)); // (the per-fragment addresses are made here, not kept over the unit loop)
+        const uint8_t *src = pack + (size_t)u * L::UNIT_BYTES + 16 * ln;
+        uint8_t *dst = lds + (size_t)slot * L::UNIT_BYTES;
+#pragma unroll 1
+        for (int k = 0; k < L::FPW; ++k) { // (not unrolled: one address in registers at a time)
+            const int f = k * kWideWaves + wv;
+            if (f < L::FR_UNIT) lds_dma16(src + (size_t)f * 1024, dst + (size_t)f * 1024);
+        }
+    };
+
+    const long ntiles = (a.rows + 15) / 16;
+    const long stride = (long)gridDim.x * kWideWaves;
+    const int rounds = (int)((ntiles + stride - 1) / stride);
+    long tile = (long)blockIdx.x * kWideWaves + wv;
+
+    u32x4 rx[KSC], rd[KSC];
+    load_rows<KSC>(a.x1, tile * 16 + tok, a.rows, C, q, rx);
+    load_rows<KSC>(a.dy, tile * 16 + tok, a.rows, C, q, rd);
+
+    stream_unit(0, 0);
+    for (int i = tid; i < L::T_FLOATS / 4; i += kWideThreads)
+        reinterpret_cast<uint4 *>(lds + L::OFF_TABLES)[i] = reinterpret_cast<const uint4 *>(pack + L::P_TABLES)[i];
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    int slot = 0; // buffer the unit about to be used lies in
+    for (int round = 0; round < rounds; ++round, tile += stride) {
+        const bool more = round + 1 < rounds;
+        const long t = tile * 16 + tok;
+        const bool ok = t < a.rows;
+        uint32_t lds0 = 0;
+        asm volatile("" : "+v"(lds0)); // keeps the LDS reads of a round inside the round
+        lane_r = lane;
+        asm volatile("" : "+v"(lane_r));
+        const float *tb = reinterpret_cast<const float *>(lds + lds0 + L::OFF_TABLES);
+
+        // operands of the round: LN_2(x1) (also written out for the weight gradient of the first map) and dy
+        uint32_t bx[KSC][4], bd[KSC][4];
+        tidy_rows<KSC>(C, q, rx, bx);
+        tidy_rows<KSC>(C, q, rd, bd);
+        layer_norm_rows<KSC>(bx, C, q, a.eps, reinterpret_cast<const float2 *>(tb + L::T_GB));
+        store_rows<KSC>(a.xn, t, ok, C, q, bx);
+
+        f32x4 dnacc[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) dnacc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        auto unit_steps = [&](int unit) {
+            const uint4 *wu = reinterpret_cast<const uint4 *>(lds + lds0 + (size_t)slot * L::UNIT_BYTES);
+#pragma unroll
+            for (int hs = 0; hs < L::HU; ++hs) {
+                const uint4 *ws = wu + hs * L::FR_STEP * 64;
+                const int f0 = 32 * (L::HU * unit + hs) + 8 * q; // the lane's hidden features f0 + 0..7 of token tok
+                f32x4 p0 = f32x4{0.f, 0.f, 0.f, 0.f}, p1 = p0, d0 = p0, d1 = p0;
+#pragma unroll
+                for (int s = 0; s < KSC; ++s) {
+                    const uint4 b = make_uint4(bx[s][0], bx[s][1], bx[s][2], bx[s][3]);
+                    p0 = mma32(ws[s * 64 + lane_r], b, p0);
+                    p1 = mma32(ws[(KSC + s) * 64 + lane_r], b, p1);
+                }
+#pragma unroll
+                for (int s = 0; s < KSC; ++s) {
+                    const uint4 b = make_uint4(bd[s][0], bd[s][1], bd[s][2], bd[s][3]);
+                    d0 = mma32(ws[(2 * KSC + s) * 64 + lane_r], b, d0);
+                    d1 = mma32(ws[(3 * KSC + s) * 64 + lane_r], b, d1);
+                }
+                const float4 b10 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0);
+                const float4 b11 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 4);
+                // pre and dh as the one-kernel-per-step path stores them (rounded)
+                const uint32_t pp[4] = {pack_bf16x2(p0[0] + b10.x, p0[1] + b10.y), pack_bf16x2(p0[2] + b10.z, p0[3] + b10.w),
+                                        pack_bf16x2(p1[0] + b11.x, p1[1] + b11.y), pack_bf16x2(p1[2] + b11.z, p1[3] + b11.w)};
+                const uint32_t dd[4] = {pack_bf16x2(d0[0], d0[1]), pack_bf16x2(d0[2], d0[3]),
+                                        pack_bf16x2(d1[0], d1[1]), pack_bf16x2(d1[2], d1[3])};
+                uint32_t hp[4], gp[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float t0 = bf16_lo(pp[i]), t1 = bf16_hi(pp[i]);
+                    float Phi0, phi0, Phi1, phi1;
+                    gauss(t0, Phi0, phi0);
+                    gauss(t1, Phi1, phi1);
+                    hp[i] = pack_bf16x2(t0 * Phi0, t1 * Phi1);
+                    gp[i] = pack_bf16x2(bf16_lo(dd[i]) * fmaf(t0, phi0, Phi0), bf16_hi(dd[i]) * fmaf(t1, phi1, Phi1));
+                }
+                const uint4 hq = make_uint4(hp[0], hp[1], hp[2], hp[3]), gq = make_uint4(gp[0], gp[1], gp[2], gp[3]);
+                store_hidden(a.h, t, ok, Hd, f0, hq);
+                store_hidden(a.dpre, t, ok, Hd, f0, gq);
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) dnacc[ct] = mma32(ws[(4 * KSC + ct) * 64 + lane_r], gq, dnacc[ct]);
+            }
+        };
+
+        // first unit of the round: see the forward kernel (the stores of the unit's own steps are younger than
+        // the row loads; leaving 2 KSC operations in flight then waits for as many of the row loads as there
+        // were stores, whichever way loads and stores are ordered among each other)
+        if (nu > 1) stream_unit(1, slot ^ 1);
+        else if (more) stream_unit(0, slot ^ 1);
+        if (more) {
+            const long tn = t + stride * 16;
+            load_rows<KSC>(a.x1, tn, a.rows, C, q, rx);
+            load_rows<KSC>(a.dy, tn, a.rows, C, q, rd);
+        }
+        unit_steps(0);
+        if (more) __builtin_amdgcn_s_waitcnt(kWaitAllBut2Ksc<KSC>);
+        else __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        slot ^= 1;
+        for (int unit = 1; unit < nu; ++unit) {
+            if (unit + 1 < nu) stream_unit(unit + 1, slot ^ 1);
+            else if (more) stream_unit(0, slot ^ 1); // (the first unit of the next round)
+            unit_steps(unit);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            slot ^= 1;
+        }
+
+        // dn as stored: tiles 2p and 2p + 1 hold the lane's channels 32 p + 8 q + 0..3 and + 4..7
+        uint32_t dno[KSC][4];
+#pragma unroll
+        for (int p = 0; p < KSC; ++p) {
+            const f32x4 lo = dnacc[2 * p], hi = dnacc[2 * p + 1];
+            dno[p][0] = pack_bf16x2(lo[0], lo[1]);
+            dno[p][1] = pack_bf16x2(lo[2], lo[3]);
+            dno[p][2] = pack_bf16x2(hi[0], hi[1]);
+            dno[p][3] = pack_bf16x2(hi[2], hi[3]);
+        }
+        store_rows<KSC>(a.dn, t, ok, C, q, dno);
+    }
+}
+
+template <int KSC, int KSF> hipError_t launch_wide_bwd_t(const WideMlpBwdArgs &a, hipStream_t s)
+{
+    using L = WideMlpBwd<KSC, KSF>;
+    const int nu = ((a.Hd + 31) / 32 + L::HU - 1) / L::HU; // stream units
+    {
+        KernelTimer kt(K_MLP_PACK, s);
+        hipLaunchKernelGGL((astl_mlp_wide_bwd_pack_kernel<KSC, KSF>), dim3(64), dim3(256), 0, s, a, nu);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    auto kern = astl_mlp_wide_bwd_kernel<KSC, KSF>;
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), L::LDS_BYTES); ea != hipSuccess) return ea;
+    const long tiles = (a.rows + 15) / 16;
+    long blocks = (tiles + kWideWaves - 1) / kWideWaves;
+    if (blocks > device_cu_count()) blocks = device_cu_count();
+    KernelTimer kt(K_MLP_BWD, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(blocks < 1 ? 1 : blocks)), dim3(kWideThreads), L::LDS_BYTES, s, a, nu);
+    return hipGetLastError();
+}
+
 } // namespace
 
 bool astl_mlp_wide_supported(int C, int hidden)
@@ -433,6 +688,22 @@ hipError_t launch_astl_mlp_wide_fwd(long rows, int C, int hidden, float eps, con
     }
     if (C <= 128) return launch_wide_t<4, 12>(m, s);
     return launch_wide_t<6, 12>(m, s);
+}
+
+size_t astl_mlp_wide_bwd_pack_bytes() { return (WideMlpBwd<6, 12>::P_BYTES + 255) & ~size_t(255); }
+
+hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
+                                    const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
+                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn, void *pack,
+                                    hipStream_t s)
+{
+    if (!astl_mlp_wide_supported(C, hidden) || rows <= 0) return hipErrorInvalidValue;
+    WideMlpBwdArgs m{};
+    m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
+    m.x1 = x1; m.dy = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
+    m.xn = xn; m.h = h; m.dpre = dpre; m.dn = dn; m.pack = pack;
+    if (C <= 128) return launch_wide_bwd_t<4, 12>(m, s);
+    return launch_wide_bwd_t<6, 12>(m, s);
 }
 
 } // namespace gswa
