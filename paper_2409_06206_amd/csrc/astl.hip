@@ -378,17 +378,15 @@ int make_plan(const astl_desc *d, Plan *p)
     // (with the fused MLP backward only LN_1's two vectors go through the gradient copies)
     p->params = p->fused_mlp_bwd ? 2 * (size_t)p->C : 2 * (size_t)p->C * p->Hd + p->Hd + 5 * (size_t)p->C;
     p->reps = align256(kGradReplicas * p->params * sizeof(float));
-    p->pack = p->fused_mlp ? astl_mlp_pack_bytes() : p->wide_mlp ? astl_mlp_wide_pack_bytes() : 0;
+    // (wide layers: the forward kernel's order of the MLP weights, then the backward kernel's)
+    p->pack = p->fused_mlp ? astl_mlp_pack_bytes()
+              : p->wide_mlp ? astl_mlp_wide_pack_bytes() + astl_mlp_wide_bwd_pack_bytes() : 0;
     p->saved = p->act + p->at_saved + p->pack;
     // forward: xn | a | max(attention scratch (+ its saved state at inference), pre | h)
     const size_t hid_f = p->fused_mlp || p->wide_mlp ? 0 : 2 * p->hid;
     p->fwd_ws = 2 * p->act + (p->at_fws > hid_f ? p->at_fws : hid_f);
     // backward: xn | dn | dx1 | max(pre | h | dh, attention scratch) | copies of the gradients
-    // (wide layers: h | dpre | the backward's repacked weights, then scratch of the weight gradients)
-    const size_t wpack = align256(astl_mlp_wide_bwd_pack_bytes());
-    const size_t hid_b = p->fused_mlp_bwd ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd)
-                         : p->wide_mlp    ? 2 * p->hid + (p->hid > wpack ? p->hid : wpack)
-                                          : 3 * p->hid;
+    const size_t hid_b = p->fused_mlp_bwd ? astl_mlp_bwd_ws_bytes(p->T, p->C, p->Hd) : 3 * p->hid;
     p->bwd_ws = 3 * p->act + (p->at_bws > hid_b ? p->at_bws : hid_b) + p->reps;
     return GSWA_OK;
 }
@@ -459,6 +457,7 @@ int forward_t(const astl_desc *d, const Plan &pl, const T *x, const astl_params 
                                           (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                           (const bf16_t *)p->w_fc2, (const bf16_t *)p->b_fc2,
                                           saved ? (bf16_t *)x1 : nullptr, (bf16_t *)y, pack,
+                                          saved ? static_cast<char *>(pack) + astl_mlp_wide_pack_bytes() : nullptr,
                                           nx ? (const bf16_t *)nx->ln1_w : nullptr,
                                           nx ? (const bf16_t *)nx->ln1_b : nullptr, nx ? (bf16_t *)xn : nullptr, st));
         if (link && nx) link->emitted = true;
@@ -559,26 +558,25 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     } else if (pl.wide_mlp) {
         // one launch from x1 and dy to dn; LN_2(x1), h and dpre are written for the weight gradients
         T *h = reinterpret_cast<T *>(rest), *dpre = reinterpret_cast<T *>(rest + pl.hid);
-        char *third = rest + 2 * pl.hid;
-        const size_t wpack = align256(astl_mlp_wide_bwd_pack_bytes());
-        const size_t third_bytes = pl.hid > wpack ? pl.hid : wpack;
+        char *third = rest + 2 * pl.hid; // (scratch of the weight gradients)
         ASTL_HIP(launch_astl_mlp_wide_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
                                           (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                           (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                           (const bf16_t *)p->w_fc2, (bf16_t *)xn, (bf16_t *)h, (bf16_t *)dpre,
-                                          (bf16_t *)dn, third, st));
-        // d Wfc2 = dy^T h,  d Wfc1 = dpre^T LN_2(x1)  (their scratch: what the third slot has behind the pack)
+                                          (bf16_t *)dn,
+                                          saved + pl.saved - pl.pack + astl_mlp_wide_pack_bytes(), st));
+        // d Wfc2 = dy^T h,  d Wfc1 = dpre^T LN_2(x1)
         WgradArgs w2{};
         w2.dout = dy; w2.lddout = C; w2.a1 = h; w2.lda1 = Hd;
         w2.dw = rep + o_w2; w2.db = rep + o_b2; w2.rep_stride = P; w2.reps = kGradReplicas;
         w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
-        w2.scratch = third + wpack; w2.scratch_bytes = third_bytes - wpack;
+        w2.scratch = third; w2.scratch_bytes = pl.hid;
         ASTL_HIP(launch_wgrad<T>(w2, st));
         WgradArgs w1{};
         w1.dout = dpre; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
         w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
         w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
-        w1.scratch = third + wpack; w1.scratch_bytes = third_bytes - wpack;
+        w1.scratch = third; w1.scratch_bytes = pl.hid;
         ASTL_HIP(launch_wgrad<T>(w1, st));
         // through LN_2, plus the skip of Eq. 5: dx1
         LnBwdArgs n2{};

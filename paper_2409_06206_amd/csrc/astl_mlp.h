@@ -21,23 +21,25 @@ hipError_t launch_astl_mlp_fwd(long rows, int C, int hidden, float eps, const bf
                                const bf16_t *next_ln_w, const bf16_t *next_ln_b, bf16_t *next_ln_out, hipStream_t s);
 
 // The same forward for wide layers (64 < C <= 192, hidden <= 384): the weights are streamed through LDS in
-// units of 32 hidden features.  Arguments as above (astl_mlp_wide_pack_bytes() bytes at `pack`); x1 may be
-// null where nobody reads it afterwards (inference).
+// units of 96 hidden features.  Arguments as above (astl_mlp_wide_pack_bytes() bytes at `pack`); x1 may be
+// null where nobody reads it afterwards (inference).  With bwd_pack non-null (astl_mlp_wide_bwd_pack_bytes()
+// bytes) the same pack launch also writes the weights in the backward kernel's order.
 bool astl_mlp_wide_supported(int C, int hidden);
 size_t astl_mlp_wide_pack_bytes();
 hipError_t launch_astl_mlp_wide_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                     const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
-                                    const bf16_t *next_ln_w, const bf16_t *next_ln_b, bf16_t *next_ln_out, hipStream_t s);
+                                    void *bwd_pack, const bf16_t *next_ln_w, const bf16_t *next_ln_b,
+                                    bf16_t *next_ln_out, hipStream_t s);
 
 // Backward of the same layers between the two LayerNorm adjoints, one launch: from x1 and dy it writes
 // LN_2(x1) (xn), the hidden layer h and dpre = (dy W2) o GELU'(pre) for the weight gradients, and
-// dn = dpre W1 for LayerNorm's adjoint.  `pack` receives astl_mlp_wide_bwd_pack_bytes() bytes.
+// dn = dpre W1 for LayerNorm's adjoint.  `pack` is what the forward call wrote at its bwd_pack.
 size_t astl_mlp_wide_bwd_pack_bytes();
 hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
-                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn, void *pack,
-                                    hipStream_t s);
+                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn,
+                                    const void *pack, hipStream_t s);
 
 // The backward kernel covers the same shapes.
 bool astl_mlp_bwd_supported(int C, int hidden);

@@ -53,6 +53,7 @@ struct WideMlpArgs {
     const bf16_t *nxt_w, *nxt_b; // optional: gamma, beta of the LayerNorm that reads y next ...
     bf16_t *xn_out;              // ... and where its output goes (null: not wanted)
     void *pack;
+    void *bwd_pack;              // optional: the backward kernel's order of the same weights, written by the same launch
 };
 
 // KSC k-steps of 32 channels, KSF steps of 32 hidden features, HU of them per stream unit.
@@ -79,7 +80,7 @@ __device__ __forceinline__ float bfv(const bf16_t *p, long i) { return __uint_as
 
 // Once per forward call: the weights in the order the units are streamed in, zero outside the matrices.
 template <int KSC, int KSF>
-__global__ __launch_bounds__(256) void astl_mlp_wide_pack_kernel(WideMlpArgs a, int nu)
+__device__ __forceinline__ void wide_fwd_pack_body(const WideMlpArgs &a, int nu)
 {
     using L = WideMlp<KSC, KSF>;
     const int C = a.C, Hd = a.Hd;
@@ -389,27 +390,6 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_fwd_kernel(WideMlp
     }
 }
 
-template <int KSC, int KSF> hipError_t launch_wide_t(const WideMlpArgs &a, hipStream_t s)
-{
-    using L = WideMlp<KSC, KSF>;
-    const int nu = ((a.Hd + 31) / 32 + L::HU - 1) / L::HU; // stream units
-    {
-        KernelTimer kt(K_MLP_PACK, s);
-        hipLaunchKernelGGL((astl_mlp_wide_pack_kernel<KSC, KSF>), dim3(64), dim3(256), 0, s, a, nu);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    auto kern = astl_mlp_wide_fwd_kernel<KSC, KSF>;
-    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), L::LDS_BYTES); ea != hipSuccess) return ea;
-    const long tiles = (a.rows + 15) / 16;
-    long blocks = (tiles + kWideWaves - 1) / kWideWaves;
-    if (blocks > device_cu_count()) blocks = device_cu_count(); // (one workgroup of eight waves per compute unit)
-    KernelTimer kt(K_MLP_FWD, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(blocks < 1 ? 1 : blocks)), dim3(kWideThreads), L::LDS_BYTES, s, a, nu);
-    return hipGetLastError();
-}
-
-
 // ---------------------------------------------------------------------------------------------------------
 // Backward pass, the part between the two LayerNorm adjoints: one launch recomputes LN_2(x1), the
 // pre-activation and the hidden layer as the forward does and takes the gradient back to LN_2's output,
@@ -449,8 +429,9 @@ template <int KSC, int KSF> struct WideMlpBwd {
     static_assert(T_FLOATS % 4 == 0, "tables are copied in 16-byte pieces");
 };
 
+// (runs in the forward call's pack launch: the forward keeps both orders with its saved state)
 template <int KSC, int KSF>
-__global__ __launch_bounds__(256) void astl_mlp_wide_bwd_pack_kernel(WideMlpBwdArgs a, int nu)
+__device__ __forceinline__ void wide_bwd_pack_body(const WideMlpBwdArgs &a, int nu)
 {
     using L = WideMlpBwd<KSC, KSF>;
     const int C = a.C, Hd = a.Hd;
@@ -644,16 +625,43 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
     }
 }
 
+template <int KSC, int KSF>
+__global__ __launch_bounds__(256) void astl_mlp_wide_pack_kernel(WideMlpArgs a, int nu, WideMlpBwdArgs b, int nub)
+{
+    wide_fwd_pack_body<KSC, KSF>(a, nu);
+    if (b.pack) wide_bwd_pack_body<KSC, KSF>(b, nub);
+}
+
+template <int KSC, int KSF> hipError_t launch_wide_t(const WideMlpArgs &a, hipStream_t s)
+{
+    using L = WideMlp<KSC, KSF>;
+    const int nu = ((a.Hd + 31) / 32 + L::HU - 1) / L::HU; // stream units
+    {
+        KernelTimer kt(K_MLP_PACK, s);
+        WideMlpBwdArgs b{};
+        b.C = a.C; b.Hd = a.Hd; b.ln_w = a.ln_w; b.ln_b = a.ln_b; b.w_fc1 = a.w_fc1; b.b_fc1 = a.b_fc1; b.w_fc2 = a.w_fc2;
+        b.pack = a.bwd_pack;
+        using LB = WideMlpBwd<KSC, KSF>;
+        const int nub = ((a.Hd + 31) / 32 + LB::HU - 1) / LB::HU;
+        hipLaunchKernelGGL((astl_mlp_wide_pack_kernel<KSC, KSF>), dim3(256), dim3(256), 0, s, a, nu, b, nub);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    auto kern = astl_mlp_wide_fwd_kernel<KSC, KSF>;
+    if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), L::LDS_BYTES); ea != hipSuccess) return ea;
+    const long tiles = (a.rows + 15) / 16;
+    long blocks = (tiles + kWideWaves - 1) / kWideWaves;
+    if (blocks > device_cu_count()) blocks = device_cu_count(); // (one workgroup of eight waves per compute unit)
+    KernelTimer kt(K_MLP_FWD, s);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(blocks < 1 ? 1 : blocks)), dim3(kWideThreads), L::LDS_BYTES, s, a, nu);
+    return hipGetLastError();
+}
+
+
 template <int KSC, int KSF> hipError_t launch_wide_bwd_t(const WideMlpBwdArgs &a, hipStream_t s)
 {
     using L = WideMlpBwd<KSC, KSF>;
     const int nu = ((a.Hd + 31) / 32 + L::HU - 1) / L::HU; // stream units
-    {
-        KernelTimer kt(K_MLP_PACK, s);
-        hipLaunchKernelGGL((astl_mlp_wide_bwd_pack_kernel<KSC, KSF>), dim3(64), dim3(256), 0, s, a, nu);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
     auto kern = astl_mlp_wide_bwd_kernel<KSC, KSF>;
     if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), L::LDS_BYTES); ea != hipSuccess) return ea;
     const long tiles = (a.rows + 15) / 16;
@@ -676,10 +684,12 @@ size_t astl_mlp_wide_pack_bytes() { return (WideMlp<6, 12>::P_BYTES + 255) & ~si
 hipError_t launch_astl_mlp_wide_fwd(long rows, int C, int hidden, float eps, const bf16_t *x, const bf16_t *a,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
                                     const bf16_t *w_fc2, const bf16_t *b_fc2, bf16_t *x1, bf16_t *y, void *pack,
-                                    const bf16_t *next_ln_w, const bf16_t *next_ln_b, bf16_t *next_ln_out, hipStream_t s)
+                                    void *bwd_pack, const bf16_t *next_ln_w, const bf16_t *next_ln_b,
+                                    bf16_t *next_ln_out, hipStream_t s)
 {
     if (!astl_mlp_wide_supported(C, hidden) || rows <= 0) return hipErrorInvalidValue;
     WideMlpArgs m{};
+    m.bwd_pack = bwd_pack;
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x = x; m.a = a; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2; m.b_fc2 = b_fc2;
     m.x1 = x1; m.y = y; m.pack = pack;
@@ -694,14 +704,14 @@ size_t astl_mlp_wide_bwd_pack_bytes() { return (WideMlpBwd<6, 12>::P_BYTES + 255
 
 hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
-                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn, void *pack,
-                                    hipStream_t s)
+                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn,
+                                    const void *pack, hipStream_t s)
 {
     if (!astl_mlp_wide_supported(C, hidden) || rows <= 0) return hipErrorInvalidValue;
     WideMlpBwdArgs m{};
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x1 = x1; m.dy = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
-    m.xn = xn; m.h = h; m.dpre = dpre; m.dn = dn; m.pack = pack;
+    m.xn = xn; m.h = h; m.dpre = dpre; m.dn = dn; m.pack = const_cast<void *>(pack);
     if (C <= 128) return launch_wide_bwd_t<4, 12>(m, s);
     return launch_wide_bwd_t<6, 12>(m, s);
 }
