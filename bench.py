@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the launch kinds of that kernel), valid only for the kernel source they were taken on:
 # {(workload, groups, kernel): (source file, sha256 of it, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "9ac4c21a780e8451684fa022c213914257db80afe5ee2b75151ff7ed6344a395", 229609792),
-    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "9ac4c21a780e8451684fa022c213914257db80afe5ee2b75151ff7ed6344a395", 115242464),
-    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "92589044b3bf2ea2d7ca5b00695a8ac15517743b5a7660400c266f182455d4e1", 74167912),
-    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "40b706f5360b5b1b725536557eb972afb71807e67636e134b0e8a6a11509e669", 224898104),
-    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "c24e6214397b7c3373e4c3371eb01d1d402509c96a7fa2c96ed8408b7fd0bbc6", 181316592),
+    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "158602457b041f4c94dfbe9b8edc07ca0c5d835d27a840c8c3296a24d2d24f0f", 229427494),
+    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "158602457b041f4c94dfbe9b8edc07ca0c5d835d27a840c8c3296a24d2d24f0f", 115486216),
+    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "3a98c5eb92f557edc56922db2302d3f0dc3401adb35a911fdcea18938f683891", 74168036),
+    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "27b4b2d84686b97a0a880931895a9931791951e845e149e305ce746d9e6a0d71", 225349760),
+    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "343bdeb326f796c0b47b8287a0447dd307db4cbace850e7a7844ecfae1c72ece", 180698384),
 }
 
 
