@@ -107,6 +107,31 @@ def test_wide_layer_with_enough_tokens_for_the_streaming_weight_gradients(case):
     parity.check_block(astl_oracle, **case)
 
 
+@pytest.mark.parametrize("case,kernels", [
+    # hidden 400 > 384: the first map (180 -> 400) keeps its whole weight matrix in LDS and takes Eq. 4's skip and
+    # LN_2 in its operand read and the GELU in its stores; the second (K = 400) runs on the chunked kernel
+    (dict(B=1, H=64, W=64, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=400), ("fc1_linear", "fc2_linear")),
+    # 256 channels > 192: both maps on the whole-matrix kernel with 512 threads (K = 256 and 288: more than six
+    # steps of 32), LN_2 in the operand read of the first; ragged last 16-row tile (4160 tokens)
+    (dict(B=1, H=80, W=52, C=256, heads=4, groups=2, window=4, shift=2, dtype="bf16", hidden=288), ("fc1_linear", "fc2_linear")),
+], ids=lambda v: _id(v) if isinstance(v, dict) else "")
+def test_wide_layers_beyond_the_streaming_mlp_kernels(case, kernels):
+    """Wide bf16 layers that the streaming MLP kernels do not take (hidden > 384 or C > 192), with enough
+    tokens (>= 4096) for the linear-map kernel that holds a whole weight matrix in LDS."""
+    import torch
+    print("case", case, flush=True)
+    gswa.gswa_profile_enable(True)
+    gswa.gswa_profile_collect()
+    parity.check_block(astl_oracle, **case)
+    torch.cuda.synchronize()
+    names, dropped = gswa.gswa_profile_collect()
+    gswa.gswa_profile_enable(False)
+    assert dropped == 0
+    assert all(k in names for k in kernels) and "mlp_fwd" not in names, names
+    # LN_2 of the forward and of the backward's recomputation ride in the first map: only LN_1 is launched (twice)
+    assert names["ln_fwd"][1] == 2, names
+
+
 @pytest.mark.parametrize("case", [SMALL[0], SMALL[8]], ids=_id)
 def test_groups_without_the_cascade(case):
     print("case", case, flush=True)
