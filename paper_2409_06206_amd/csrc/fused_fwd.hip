@@ -27,8 +27,15 @@ __global__ __launch_bounds__(256) void pack_params_kernel(const bf16_t *__restri
                                                           const bf16_t *__restrict__ w_proj,
                                                           const bf16_t *__restrict__ b_proj,
                                                           const bf16_t *__restrict__ table,
-                                                          uint8_t *__restrict__ pack)
+                                                          uint8_t *__restrict__ pack, int wide_first)
 {
+    // blocks from wide_first on (if not negative): the layouts of the wide one-launch kernels, same launch
+    if constexpr (Cf::SPLIT) {
+        if (wide_first >= 0 && (int)blockIdx.x >= wide_first) {
+            wide_pack_entry<Cf>(((int)blockIdx.x - wide_first) * 256 + (int)threadIdx.x, w_qkv, w_proj, table, pack);
+            return;
+        }
+    }
     constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET;
     constexpr int KS = Cf::KS, KSC = Cf::KSC;
     constexpr int E_WQH = Cf::N_WQH * 64, E_WP2 = Cf::N_WP2 * 64, E_BF = Cf::N_BF * 64, E_WQ = Cf::N_WQ * 64,
@@ -747,16 +754,17 @@ hipError_t run_fwd(const Geom &g, const bf16_t *x, const bf16_t *w_qkv, const bf
     {
         constexpr int entries =
             (Cf::N_WQH + Cf::N_WP2 + Cf::N_BF + Cf::N_WQ + Cf::N_WPT + Cf::N_WQT + Cf::N_WPK) * 64 + 4 * Cf::C;
+        constexpr int wide_entries = (Cf::N_WQW + Cf::N_WPW + Cf::N_WQX + Cf::N_WQN) * 64 + Cf::HEADS * Cf::TBW_PITCH;
+        const int blocks = (entries + 255) / 256;
+        const bool wide = Cf::SPLIT && wide_fwd_supported(g);
         KernelTimer kt(K_PACK_FWD, s);
-        hipLaunchKernelGGL(pack_params_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, b_qkv,
-                           w_proj, b_proj, table, pack);
+        hipLaunchKernelGGL(pack_params_kernel<Cf>, dim3(blocks + (wide ? (wide_entries + 255) / 256 : 0)), dim3(256), 0, s,
+                           w_qkv, b_qkv, w_proj, b_proj, table, pack, wide ? blocks : -1);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if constexpr (Cf::SPLIT) {
         if (wide_fwd_supported(g)) { // 8x8 windows: the whole layer in one launch
-            e = launch_wide_pack(g, w_qkv, w_proj, table, pack, s);
-            if (e != hipSuccess) return e;
             return launch_wide_fwd(g, x, pack, y, attn, training, s);
         }
         if (!attn) return hipErrorInvalidValue;

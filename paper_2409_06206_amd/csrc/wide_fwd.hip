@@ -27,101 +27,6 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMaskLog2 = -100.0f * kLog2e; // the additive -100 of the shift mask, in base-2 units
 
-// ---------------------------------------------------------------------------------------
-// Parameter packing for this kernel (layout: FusedCfg, WQW / WPW / TBW)
-// ---------------------------------------------------------------------------------------
-template <class Cf>
-__global__ __launch_bounds__(256) void wide_pack_kernel(const bf16_t *__restrict__ w_qkv,
-                                                        const bf16_t *__restrict__ w_proj,
-                                                        const bf16_t *__restrict__ table,
-                                                        uint8_t *__restrict__ pack)
-{
-    constexpr int C = Cf::C, D = Cf::D, CG = Cf::CG, HG = Cf::HG, HEADS = Cf::HEADS, ET = Cf::ET, KSX = Cf::KSX;
-    constexpr int E_WQW = Cf::N_WQW * 64, E_WPW = Cf::N_WPW * 64, E_TBW = HEADS * Cf::TBW_PITCH, E_WQX = Cf::N_WQX * 64;
-    const float qscale = kLog2e / sqrtf((float)D);
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const int l16 = i & 15, q = (i >> 4) & 3;
-    // feature of a head held in k-slot s of lane group q
-    auto slot_feature = [&](int s) { return s < 4 ? 4 * q + s : 16 + 4 * q + (s - 4); };
-    if (i < E_WQW) {
-        int f = i >> 6;
-        const int ks = f % KSX; f /= KSX;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3;
-        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int e = 16 * et + l16;
-        uint32_t v[8];
-        for (int s = 0; s < 8; ++s) {
-            const int fe = slot_feature(s);
-            float w = 0.f;
-            if (e < D && fe < D)
-                w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + ks * D + fe]) * (t == 0 ? qscale : 1.0f);
-            v[s] = f32_to_bf16_bits(w);
-        }
-        reinterpret_cast<uint4 *>(pack + Cf::P_WQW)[i] =
-            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
-        return;
-    }
-    i -= E_WQW;
-    if (i < E_WPW) {
-        const int f = i >> 6;
-        const int hd = f % HEADS, ot = f / HEADS;
-        const int o = 16 * ot + l16;
-        uint32_t v[8];
-        for (int s = 0; s < 8; ++s) {
-            const int fe = slot_feature(s);
-            v[s] = (o < C && fe < D) ? (uint32_t)w_proj[(size_t)o * C + hd * D + fe].bits : 0u;
-        }
-        reinterpret_cast<uint4 *>(pack + Cf::P_WPW)[i] =
-            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
-        return;
-    }
-    i -= E_WPW;
-    if (i < E_TBW) {
-        const int hd = i / Cf::TBW_PITCH, e = i % Cf::TBW_PITCH;
-        reinterpret_cast<float *>(pack + Cf::P_TBW)[i] = e < 225 ? to_f32(table[e * HEADS + hd]) * kLog2e : 0.f;
-        return;
-    }
-    i -= E_TBW;
-    if (i < E_WQX) { // Wqkv^T for the backward: row l16 -> input channel (per head of the group), k-slots -> features of (hd, t)
-        int f = i >> 6;
-        const int ct = f % Cf::CTF; f /= Cf::CTF;
-        const int t = f % 3;
-        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int cl = 16 * (ct % ET) + (i & 15), c = (ct / ET) * D + cl; // channel inside its head, inside the group
-        const int qq = (i >> 4) & 3;
-        const float sc = t == 0 ? 1.0f / sqrtf((float)D) : 1.0f;
-        uint32_t v[8];
-        for (int s = 0; s < 8; ++s) {
-            const int fe = s < 4 ? 4 * qq + s : 16 + 4 * qq + (s - 4);
-            float w = 0.f;
-            if (cl < D && fe < D) w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + fe) * CG + c]) * sc;
-            v[s] = f32_to_bf16_bits(w);
-        }
-        reinterpret_cast<uint4 *>(pack + Cf::P_WQX)[i] =
-            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
-        return;
-    }
-    i -= E_WQX;
-    if (i < Cf::N_WQN * 64) { // (hd, t, et, ks): row l16 -> feature 16 et + l16, k-slots -> channels 32 ks + 8 q ..
-        int f = i >> 6;
-        const int ks = f % Cf::KS; f /= Cf::KS;
-        const int et = f % ET; f /= ET;
-        const int t = f % 3;
-        const int hd = f / 3, gi = hd / HG, hl = hd % HG;
-        const int e = 16 * et + (i & 15);
-        const int c0 = 32 * ks + 8 * ((i >> 4) & 3);
-        uint32_t v[8];
-        for (int s = 0; s < 8; ++s) {
-            float w = 0.f;
-            if (e < D && c0 + s < CG)
-                w = to_f32(w_qkv[((size_t)gi * 3 * CG + t * CG + hl * D + e) * CG + c0 + s]) * (t == 0 ? qscale : 1.0f);
-            v[s] = f32_to_bf16_bits(w);
-        }
-        reinterpret_cast<uint4 *>(pack + Cf::P_WQN)[i] =
-            make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
-    }
-}
 
 template <class Cf> struct WideFwdCfg {
     // one wave per SIMD: a wave then has the whole register file of its SIMD (512 registers), which
@@ -540,23 +445,6 @@ bool wide_fwd_supported(const Geom &g)
     GSWA_WIDE_SHAPES(X)
 #undef X
     return false;
-}
-
-hipError_t launch_wide_pack(const Geom &g, const bf16_t *w_qkv, const bf16_t *w_proj, const bf16_t *table,
-                            void *pack, hipStream_t s)
-{
-#define X(C_, H_, G_)                                                                                    \
-    if (g.C == C_ && g.heads == H_ && g.groups == G_) {                                                  \
-        using Cf = FusedCfg<C_, H_, G_>;                                                                 \
-        constexpr int entries = (Cf::N_WQW + Cf::N_WPW + Cf::N_WQX + Cf::N_WQN) * 64 + Cf::HEADS * Cf::TBW_PITCH;                \
-        KernelTimer kt(K_PACK_FWD, s);                                                                   \
-        hipLaunchKernelGGL(wide_pack_kernel<Cf>, dim3((entries + 255) / 256), dim3(256), 0, s, w_qkv, w_proj, \
-                           table, static_cast<uint8_t *>(pack));                                        \
-        return hipGetLastError();                                                                        \
-    }
-    GSWA_WIDE_SHAPES(X)
-#undef X
-    return hipErrorInvalidValue;
 }
 
 hipError_t launch_wide_fwd(const Geom &g, const bf16_t *x, const void *pack, bf16_t *y, bf16_t *attn, int training,
