@@ -224,6 +224,14 @@ struct ReduceOut {
     int tbl_heads, tbl_entries, tbl_stride, tbl_head0;
 };
 hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s);
+// two such sums in one launch (the second with short vectors, e.g. a bias-table gradient)
+struct ReduceJob {
+    const float *part;
+    int nparts, n;
+    ReduceOut out;
+    int accumulate;
+};
+hipError_t launch_reduce_pair(const ReduceJob &a, const ReduceJob &b, hipStream_t s);
 
 // Wide layers (C = 180, two or three groups, 8x8 windows), backward of the attention and of the QKV
 // projection, group by group in reverse order (wide_bwd.hip): one launch with one wavefront per

@@ -718,14 +718,14 @@ void fused_bwd_kernel(Geom g, const bf16_t *__restrict__ x,
 // partials slice, slice + 32, ... (V entries each, one load of 4 V bytes: with V = 2 a wave half reads 256
 // contiguous bytes of a partial vector), the 32 slices meet in LDS in a fixed order.
 template <int V>
-__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
-                                                               int n, ReduceOut out, int accumulate)
+__device__ __forceinline__ void reduce_partials_block(const float *__restrict__ part, int nparts, int n,
+                                                      const ReduceOut &out, int accumulate, int block, float *red)
 {
     constexpr int SL = 32; // slices of the partials, one per wave half: few additions per thread, all loads in flight
+    constexpr int RP = 32 * V + 1; // pitch of red[SL][RP]
     typedef float vec_t __attribute__((ext_vector_type(V)));
-    __shared__ float red[SL][32 * V + 1];
     const int col = threadIdx.x & 31, slice = threadIdx.x >> 5;
-    const int i0 = (blockIdx.x * 32 + col) * V;
+    const int i0 = (block * 32 + col) * V;
     vec_t acc = 0.f;
     if (i0 < n) {
         vec_t a[8];
@@ -740,14 +740,14 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
         acc = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     }
 #pragma unroll
-    for (int v = 0; v < V; ++v) red[slice][col * V + v] = acc[v];
+    for (int v = 0; v < V; ++v) red[slice * RP + col * V + v] = acc[v];
     __syncthreads();
-    const int c = threadIdx.x, i = blockIdx.x * 32 * V + c;
+    const int c = threadIdx.x, i = block * 32 * V + c;
     if (c < 32 * V && i < n && i < out.begin[out.nseg]) { // (entries behind the last segment pad the vectors' stride)
         float t[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            t[u] = (red[4 * u][c] + red[4 * u + 1][c]) + (red[4 * u + 2][c] + red[4 * u + 3][c]);
+            t[u] = (red[(4 * u) * RP + c] + red[(4 * u + 1) * RP + c]) + (red[(4 * u + 2) * RP + c] + red[(4 * u + 3) * RP + c]);
         const float sum = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
         int seg = 0;
         while (seg < out.nseg - 1 && i >= out.begin[seg + 1]) ++seg;
@@ -759,6 +759,26 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
         }
         *dst = accumulate ? *dst + sum : sum;
     }
+}
+
+template <int V>
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nparts,
+                                                               int n, ReduceOut out, int accumulate)
+{
+    __shared__ float red[32 * (32 * V + 1)];
+    reduce_partials_block<V>(part, nparts, n, out, accumulate, (int)blockIdx.x, red);
+}
+
+// Two sums in one launch: blocks [0, blocks0) take the first (V entries per load), the others the second
+// (one entry per load: the short vectors of a bias-table gradient).
+template <int V>
+__global__ __launch_bounds__(1024) void reduce_partials_pair_kernel(ReduceJob j0, int blocks0, ReduceJob j1)
+{
+    __shared__ float red[32 * (32 * V + 1)];
+    if ((int)blockIdx.x < blocks0)
+        reduce_partials_block<V>(j0.part, j0.nparts, j0.n, j0.out, j0.accumulate, (int)blockIdx.x, red);
+    else
+        reduce_partials_block<1>(j1.part, j1.nparts, j1.n, j1.out, j1.accumulate, (int)blockIdx.x - blocks0, red);
 }
 
 // d w_proj, d b_proj of wide layers: dY^T [A | 1] over plain token rows, 128 tokens per pass of a workgroup
@@ -927,18 +947,38 @@ struct GradOut {
 
 } // namespace
 
+// entries per load: two or four where every partial vector starts on such a boundary and enough workgroups
+// remain to fill the chip
+static int reduce_width(const float *part, int n)
+{
+    const uintptr_t at = reinterpret_cast<uintptr_t>(part);
+    if (n % 4 == 0 && at % 16 == 0 && n >= 200 * 128) return 4;
+    if (n % 2 == 0 && at % 8 == 0 && n >= 200 * 64) return 2;
+    return 1;
+}
+
 hipError_t launch_reduce(const float *part, int nparts, int n, const ReduceOut &out, int accumulate, hipStream_t s)
 {
     KernelTimer kt(K_REDUCE, s);
-    // (two or four entries per load where every partial vector starts on such a boundary and enough
-    // workgroups remain to fill the chip)
-    const uintptr_t at = reinterpret_cast<uintptr_t>(part);
-    if (n % 4 == 0 && at % 16 == 0 && n >= 200 * 128)
-        hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((n + 127) / 128), dim3(1024), 0, s, part, nparts, n, out, accumulate);
-    else if (n % 2 == 0 && at % 8 == 0 && n >= 200 * 64)
-        hipLaunchKernelGGL(reduce_partials_kernel<2>, dim3((n + 63) / 64), dim3(1024), 0, s, part, nparts, n, out, accumulate);
-    else
-        hipLaunchKernelGGL(reduce_partials_kernel<1>, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate);
+    switch (reduce_width(part, n)) {
+    case 4: hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((n + 127) / 128), dim3(1024), 0, s, part, nparts, n, out, accumulate); break;
+    case 2: hipLaunchKernelGGL(reduce_partials_kernel<2>, dim3((n + 63) / 64), dim3(1024), 0, s, part, nparts, n, out, accumulate); break;
+    default: hipLaunchKernelGGL(reduce_partials_kernel<1>, dim3((n + 31) / 32), dim3(1024), 0, s, part, nparts, n, out, accumulate); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_pair(const ReduceJob &a, const ReduceJob &b, hipStream_t s)
+{
+    KernelTimer kt(K_REDUCE, s);
+    const int v = reduce_width(a.part, a.n);
+    const int blocks0 = (a.n + 32 * v - 1) / (32 * v), blocks1 = (b.n + 31) / 32;
+    const dim3 grid(blocks0 + blocks1);
+    switch (v) {
+    case 4: hipLaunchKernelGGL(reduce_partials_pair_kernel<4>, grid, dim3(1024), 0, s, a, blocks0, b); break;
+    case 2: hipLaunchKernelGGL(reduce_partials_pair_kernel<2>, grid, dim3(1024), 0, s, a, blocks0, b); break;
+    default: hipLaunchKernelGGL(reduce_partials_pair_kernel<1>, grid, dim3(1024), 0, s, a, blocks0, b); break;
+    }
     return hipGetLastError();
 }
 

@@ -772,7 +772,7 @@ template <class Cf> struct WideBwdWs {
 template <class Cf, int GI>
 hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn, const uint8_t *pack,
                      bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv, float *part, float *tpart,
-                     uint8_t *cgf, uint8_t *ffr, hipStream_t s)
+                     uint8_t *cgf, uint8_t *ffr, ReduceJob *last, hipStream_t s)
 {
     using W = WideBwdCfg<Cf>;
     {
@@ -798,18 +798,23 @@ hipError_t run_group(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy,
     out.ptr[1] = db_qkv + GI * 3 * Cf::CG; out.begin[1] = W::L_DB;
     out.begin[2] = W::L_END;
     out.nseg = 2;
-    return launch_reduce(part, grid < (g.nW + 1) / 2 ? grid : (g.nW + 1) / 2, W::L_TOTAL, out, accumulate, s);
+    const int nparts = grid < (g.nW + 1) / 2 ? grid : (g.nW + 1) / 2;
+    if (GI == 0 && last) { // (the last group's sum shares a launch with the bias table's)
+        last->part = part; last->nparts = nparts; last->n = W::L_TOTAL; last->out = out; last->accumulate = accumulate;
+        return hipSuccess;
+    }
+    return launch_reduce(part, nparts, W::L_TOTAL, out, accumulate, s);
 }
 
 template <class Cf, int GI>
 hipError_t run_groups(const Geom &g, int grid, const bf16_t *x, const bf16_t *dy, const bf16_t *attn,
                       const uint8_t *pack, bf16_t *dx, float *dw_qkv, float *db_qkv, int accumulate, uint8_t *dqkv,
-                      float *part, float *tpart, uint8_t *cgf, uint8_t *ffr, hipStream_t s)
+                      float *part, float *tpart, uint8_t *cgf, uint8_t *ffr, ReduceJob *last, hipStream_t s)
 {
-    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, ffr, s);
+    hipError_t e = run_group<Cf, GI>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, ffr, last, s);
     if (e != hipSuccess) return e;
     if constexpr (GI > 0)
-        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, ffr, s);
+        return run_groups<Cf, GI - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part, tpart, cgf, ffr, last, s);
     return hipSuccess;
 }
 
@@ -826,15 +831,18 @@ hipError_t run_wide_bwd(const Geom &g, const bf16_t *x, const bf16_t *dy, const 
     uint8_t *cgf = base + Ws::dqkv_bytes(g) + Ws::part_bytes(g) + Ws::tbl_bytes(g);
     uint8_t *ffr = cgf + Ws::cg_bytes(g);
     const int grid = attn_grid(g, device_cu_count());
+    ReduceJob last{};
     hipError_t e = run_groups<Cf, Cf::G - 1>(g, grid, x, dy, attn, pack, dx, dw_qkv, db_qkv, accumulate, dqkv, part,
-                                             tpart, cgf, ffr, s);
+                                             tpart, cgf, ffr, &last, s);
     if (e != hipSuccess) return e;
     ReduceOut out{};
     out.ptr[0] = dtable; out.begin[0] = 0;
     out.begin[1] = Cf::HEADS * W::NTBL;
     out.nseg = 1;
     out.tbl_heads = Cf::HEADS; out.tbl_entries = W::NTBL; out.tbl_stride = Cf::HEADS; out.tbl_head0 = 0;
-    return launch_reduce(tpart, grid, Cf::HEADS * W::NTBL, out, accumulate, s);
+    ReduceJob tbl{};
+    tbl.part = tpart; tbl.nparts = grid; tbl.n = Cf::HEADS * W::NTBL; tbl.out = out; tbl.accumulate = accumulate;
+    return launch_reduce_pair(last, tbl, s);
 }
 
 #define GSWA_WIDE_BWD_SHAPES(X) X(180, 6, 2) X(180, 6, 3)
