@@ -27,11 +27,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the launch kinds of that kernel), valid only for the kernel source they were taken on:
 # {(workload, groups, kernel): (source file, sha256 of it, bytes per launch)}
 MEASURED_TRAFFIC = {
-    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "158602457b041f4c94dfbe9b8edc07ca0c5d835d27a840c8c3296a24d2d24f0f", 229427494),
-    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "158602457b041f4c94dfbe9b8edc07ca0c5d835d27a840c8c3296a24d2d24f0f", 115486216),
-    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "3a98c5eb92f557edc56922db2302d3f0dc3401adb35a911fdcea18938f683891", 74168036),
-    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "27b4b2d84686b97a0a880931895a9931791951e845e149e305ce746d9e6a0d71", 225349760),
-    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "343bdeb326f796c0b47b8287a0447dd307db4cbace850e7a7844ecfae1c72ece", 180698384),
+    ("c4", 2, "wide_attn_bwd"): ("wide_bwd.hip", "9049b09287411286713757e150239f25eb4b0fc83b84015ac04c6c9f78170307", 229576312),
+    ("c3", 2, "wide_attn_bwd"): ("wide_bwd.hip", "9049b09287411286713757e150239f25eb4b0fc83b84015ac04c6c9f78170307", 116065640),
+    ("c2", 2, "fused_bwd"): ("fused_bwd.hip", "8aefb5890a71d6f6e8172a7992c221f0116de8d79eace3ae9662cfa534bd9b74", 74163908),
+    ("c5_m8", 2, "fused_fwd"): ("wide_fwd.hip", "2741dc20c76eea55b1b9254b569d5d7423fdfab82ee26444cc861f11740d1a99", 225001912),
+    ("c5_m16", 2, "fused_attn_fwd"): ("fused_fwd.hip", "fb20eb1f46acd89fc3898bd81bb6dcaaef9a8566d74eb9b3c773e5ab64968f98", 181130520),
 }
 
 
