@@ -291,6 +291,19 @@ template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, const M
 
 template <typename T> hipError_t launch_ln_fwd(const LnArgs &a, hipStream_t s, const MlpReduceArgs *r = nullptr)
 {
+    if constexpr (sizeof(T) == 2) {
+        // bf16 rows of up to 192 channels: the kernel with four lanes per row and whole tiles of loads in flight
+        // (whatever the number of rows: a band of a map must get the arithmetic the whole map gets)
+        if (!r && ln_rows_supported(a.C)) {
+            LnRowsArgs n{};
+            n.u = static_cast<const bf16_t *>(a.u); n.add = static_cast<const bf16_t *>(a.add);
+            n.gamma = static_cast<const bf16_t *>(a.gamma); n.beta = static_cast<const bf16_t *>(a.beta);
+            n.sum_out = static_cast<bf16_t *>(a.sum_out); n.out = static_cast<bf16_t *>(a.out);
+            n.rows = a.rows; n.C = a.C; n.eps = a.eps;
+            KernelTimer kt(K_LN_FWD, s);
+            return launch_ln_rows_fwd(n, s);
+        }
+    }
     return (a.C % 4 == 0) ? launch_ln_fwd_v<T, 4>(a, r, s) : launch_ln_fwd_v<T, 1>(a, r, s);
 }
 

@@ -41,6 +41,18 @@ hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, con
                                     const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn,
                                     const void *pack, hipStream_t s);
 
+// LayerNorm of bf16 rows (Eq. 4-5) for C <= 192, C a multiple of 4: out = LN(u + add) with gamma, beta; `add`
+// may be null; with it, the rounded sum goes to sum_out (may be null) and is what gets normalised.
+struct LnRowsArgs {
+    const bf16_t *u, *add, *gamma, *beta;
+    bf16_t *sum_out, *out;
+    long rows;
+    int C;
+    float eps;
+};
+bool ln_rows_supported(int C);
+hipError_t launch_ln_rows_fwd(const LnRowsArgs &a, hipStream_t s);
+
 // The backward kernel covers the same shapes.
 bool astl_mlp_bwd_supported(int C, int hidden);
 

@@ -672,6 +672,56 @@ template <int KSC, int KSF> hipError_t launch_wide_bwd_t(const WideMlpBwdArgs &a
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// LayerNorm of bf16 rows in the lane pattern of this file: four lanes per row, 16 rows per wave, every load a
+// 16-byte piece that nothing touches until the whole tile of the NEXT iteration is on its way (2 KSC, or with
+// a second input 4 KSC, loads in flight per lane: what a streaming kernel needs to reach the memory's rate).
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kLnRowsThreads = 256;
+
+template <int KSC>
+__global__ __launch_bounds__(kLnRowsThreads) void ln_rows_fwd_kernel(LnRowsArgs a)
+{
+    __shared__ float2 gb[32 * KSC];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, tok = lane & 15, q = lane >> 4;
+    const int C = a.C;
+    for (int c = tid; c < 32 * KSC; c += kLnRowsThreads)
+        gb[c] = c < C ? make_float2(bfv(a.gamma, c), bfv(a.beta, c)) : make_float2(0.f, 0.f);
+    const long ntiles = (a.rows + 15) / 16;
+    const long stride = (long)gridDim.x * (kLnRowsThreads / 64);
+    long tile = (long)blockIdx.x * (kLnRowsThreads / 64) + wv;
+    u32x4 ru[KSC], rv[KSC];
+    if (tile < ntiles) {
+        load_rows<KSC>(a.u, tile * 16 + tok, a.rows, C, q, ru);
+        if (a.add) load_rows<KSC>(a.add, tile * 16 + tok, a.rows, C, q, rv);
+    }
+    __syncthreads();
+    for (; tile < ntiles; tile += stride) {
+        const long t = tile * 16 + tok;
+        const bool ok = t < a.rows;
+        uint32_t x[KSC][4];
+        tidy_rows<KSC>(C, q, ru, x);
+        if (a.add) {
+            // the stored (rounded) sum is what gets normalised
+            uint32_t v[KSC][4];
+            tidy_rows<KSC>(C, q, rv, v);
+#pragma unroll
+            for (int p = 0; p < KSC; ++p)
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw)
+                    x[p][dw] = pack_bf16x2(bf16_lo(x[p][dw]) + bf16_lo(v[p][dw]), bf16_hi(x[p][dw]) + bf16_hi(v[p][dw]));
+        }
+        if (tile + stride < ntiles) { // the next tile's rows are on their way while this one is computed
+            load_rows<KSC>(a.u, t + stride * 16, a.rows, C, q, ru);
+            if (a.add) load_rows<KSC>(a.add, t + stride * 16, a.rows, C, q, rv);
+        }
+        if (a.add && a.sum_out) store_rows<KSC>(a.sum_out, t, ok, C, q, x);
+        layer_norm_rows<KSC>(x, C, q, a.eps, gb);
+        store_rows<KSC>(a.out, t, ok, C, q, x);
+    }
+}
+
 } // namespace
 
 bool astl_mlp_wide_supported(int C, int hidden)
@@ -714,6 +764,22 @@ hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, con
     m.xn = xn; m.h = h; m.dpre = dpre; m.dn = dn; m.pack = const_cast<void *>(pack);
     if (C <= 128) return launch_wide_bwd_t<4, 12>(m, s);
     return launch_wide_bwd_t<6, 12>(m, s);
+}
+
+bool ln_rows_supported(int C) { return C >= 8 && C <= 192 && C % 4 == 0; }
+
+hipError_t launch_ln_rows_fwd(const LnRowsArgs &a, hipStream_t s)
+{
+    if (!ln_rows_supported(a.C) || a.rows <= 0) return hipErrorInvalidValue;
+    const long tiles = (a.rows + 15) / 16;
+    long blocks = (tiles + kLnRowsThreads / 64 - 1) / (kLnRowsThreads / 64);
+    const long cap = 8L * device_cu_count(); // (eight workgroups of four waves per compute unit: one pass at 131072 rows)
+    if (blocks > cap) blocks = cap;
+    const dim3 grid((unsigned)blocks), block(kLnRowsThreads);
+    if (a.C <= 64) hipLaunchKernelGGL(ln_rows_fwd_kernel<2>, grid, block, 0, s, a);
+    else if (a.C <= 128) hipLaunchKernelGGL(ln_rows_fwd_kernel<4>, grid, block, 0, s, a);
+    else hipLaunchKernelGGL(ln_rows_fwd_kernel<6>, grid, block, 0, s, a);
+    return hipGetLastError();
 }
 
 } // namespace gswa
