@@ -83,7 +83,7 @@ def test_accumulate_flag_adds_into_every_parameter_gradient(case):
         assert err <= 1e-3, (k, err)
 
 
-@pytest.mark.parametrize("name", ["astl_c2", "astl_agile"])
+@pytest.mark.parametrize("name", ["astl_c2", "astl_agile", "astl_c3"])
 def test_benchmark_shape_pair_against_the_oracle(name):
     """The two layers of a whole-layer workload at its full size, every output element."""
     cfg = synth.CONFIGS[name]
@@ -394,6 +394,38 @@ def test_band_by_band_inference_is_the_whole_map_inference(case, bands):
     st.forward(keep=False)
     torch.cuda.synchronize()
     assert parity.rel_err(runner.to_host(st.y), runner.to_host(whole)) <= (1e-6 if dtype == "f32" else 2e-2)
+
+
+def test_inference_sequence_at_the_benchmark_size():
+    """astl_infer_stack6 as bench.py runs it (six whole layers, one 512x512 map, C = 180, hidden 360, in one
+    call): every output element against the oracle's loop over the layers, and the band-by-band form on the
+    same map against both."""
+    import torch
+    from paper_2409_06206_amd import runner
+    cfg = synth.CONFIGS["astl_infer_stack6"]
+    L, groups, dtype = cfg["stack"], cfg["groups"][0], cfg["dtype"]
+    print("case", cfg, flush=True)
+    ps = [synth.astl_params(cfg["C"], cfg["heads"], groups, cfg["window"], cfg["hidden"], 700 + l, "stress")
+          for l in range(L)]
+    ps = [{k: synth.quantize(v, dtype) for k, v in p.items()} for p in ps]
+    x, _ = synth.activations(cfg["B"], cfg["H"], cfg["W"], cfg["C"], synth.ACT_SEED + 9)
+    x = synth.quantize(x, dtype)
+    want = astl_oracle.stack_forward(x, ps, heads=cfg["heads"], groups=groups, window=cfg["window"],
+                                     shift=cfg["stack_shift"], store=lambda a: synth.quantize(a, dtype))
+    st = runner.DeviceStack(cfg["B"], cfg["H"], cfg["W"], cfg["C"], cfg["heads"], groups, cfg["window"],
+                            cfg["stack_shift"], dtype, cfg["hidden"], L, 0, inference_only=True)
+    st.set_params(ps)
+    st.set_inputs(x)
+    st.forward(keep=False)
+    torch.cuda.synchronize()
+    whole = runner.to_host(st.y)
+    assert parity.rel_err(whole, want) <= parity.TOL[dtype]
+    st.y.fill_(float("nan"))
+    st.forward_tiled(16)
+    torch.cuda.synchronize()
+    banded = runner.to_host(st.y)
+    assert parity.rel_err(banded, want) <= parity.TOL[dtype]
+    assert parity.rel_err(banded, whole) <= parity.TOL[dtype]
 
 
 def _random_layers(n, seed):
