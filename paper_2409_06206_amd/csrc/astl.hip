@@ -569,14 +569,15 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
                                      g->b_fc2, g->ln2_w, g->ln2_b, accumulate, rep, (long)kGradReplicas * P,
                                      saved + pl.saved - pl.pack, rest, &mlp_sum, pend.w ? &pend : nullptr, st));
     } else if (pl.wide_mlp) {
-        // one launch from x1 and dy to dn; LN_2(x1), h and dpre are written for the weight gradients
+        // one launch from x1 and dy to dx1 (through LN_2's adjoint and the skip of Eq. 5; its gamma / beta sums
+        // go into the gradient copies); LN_2(x1), h and dpre are written for the weight gradients
         T *h = reinterpret_cast<T *>(rest), *dpre = reinterpret_cast<T *>(rest + pl.hid);
         char *third = rest + 2 * pl.hid; // (scratch of the weight gradients)
         ASTL_HIP(launch_astl_mlp_wide_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
                                           (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                           (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                           (const bf16_t *)p->w_fc2, (bf16_t *)xn, (bf16_t *)h, (bf16_t *)dpre,
-                                          (bf16_t *)dn,
+                                          nullptr, (bf16_t *)dx1, rep + o_g2, rep + o_be2, P, kGradReplicas,
                                           saved + pl.saved - pl.pack + astl_mlp_wide_pack_bytes(), st));
         // d Wfc2 = dy^T h,  d Wfc1 = dpre^T LN_2(x1)
         WgradArgs w2{};
@@ -591,12 +592,6 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
         w1.scratch = third; w1.scratch_bytes = pl.hid;
         ASTL_HIP(launch_wgrad<T>(w1, st));
-        // through LN_2, plus the skip of Eq. 5: dx1
-        LnBwdArgs n2{};
-        n2.u = x1; n2.dout = dn; n2.res = dy; n2.gamma = p->ln2_w; n2.du = dx1;
-        n2.dgamma = rep + o_g2; n2.dbeta = rep + o_be2; n2.rep_stride = P; n2.reps = kGradReplicas;
-        n2.rows = rows; n2.C = C; n2.eps = d->eps;
-        ASTL_HIP(launch_ln_bwd<T>(n2, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);

@@ -34,12 +34,16 @@ hipError_t launch_astl_mlp_wide_fwd(long rows, int C, int hidden, float eps, con
 
 // Backward of the same layers between the two LayerNorm adjoints, one launch: from x1 and dy it writes
 // LN_2(x1) (xn), the hidden layer h and dpre = (dy W2) o GELU'(pre) for the weight gradients, and
-// dn = dpre W1 for LayerNorm's adjoint.  `pack` is what the forward call wrote at its bwd_pack.
+// dn = dpre W1 for LayerNorm's adjoint (dn may be null if dx1 is not).  With dx1 non-null the kernel goes on
+// through that adjoint and the skip of Eq. 5: dx1 = dy + LN_2's adjoint of dn at x1, and LN_2's d gamma, d beta
+// are added into copy (workgroup mod reps) of `reps` copies rep_stride floats apart at dln_w / dln_b (fp32
+// atomics, one per channel and workgroup).  `pack` is what the forward call wrote at its bwd_pack.
 size_t astl_mlp_wide_bwd_pack_bytes();
 hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
-                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn,
-                                    const void *pack, hipStream_t s);
+                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn, bf16_t *dx1,
+                                    float *dln_w, float *dln_b, long rep_stride, int reps, const void *pack,
+                                    hipStream_t s);
 
 // LayerNorm of bf16 rows (Eq. 4-5) for C <= 192, C a multiple of 4: out = LN(u + add) with gamma, beta; `add`
 // may be null; with it, the rounded sum goes to sum_out (may be null) and is what gets normalised.

@@ -124,8 +124,9 @@ __device__ __forceinline__ void wide_fwd_pack_body(const WideMlpArgs &a, int nu)
 // LayerNorm of a row held as packed bf16 in the lane pattern of this file (zero beyond C): the row is
 // spread over the four lanes that share tok.  Mean first, then the squared distances from it, as the
 // LayerNorm kernel of the one-kernel-per-step path computes them; result rounded to bf16, zero beyond C.
+// Returns (mean, 1/sqrt(var + eps)) of the row.
 template <int KSC>
-__device__ __forceinline__ void layer_norm_rows(uint32_t (&r)[KSC][4], int C, int q, float eps, const float2 *gb)
+__device__ __forceinline__ float2 layer_norm_rows(uint32_t (&r)[KSC][4], int C, int q, float eps, const float2 *gb)
 {
     asm volatile("" : "+v"(q)); // (as in load_rows)
     float sum = 0.f;
@@ -164,6 +165,18 @@ __device__ __forceinline__ void layer_norm_rows(uint32_t (&r)[KSC][4], int C, in
         }
         __builtin_amdgcn_sched_barrier(0); // (one step's scale and shift in registers at a time)
     }
+    return make_float2(mean, rstd);
+}
+
+// sum over the 16 lanes of a row (lanes that share q), valid in the row's last lane: a prefix sum by row shifts
+// on the vector ALU's data path (lanes shifted in from outside the row read zero)
+__device__ __forceinline__ float row_sum_in_last_lane(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true)); // row_shr:1
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true)); // row_shr:2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true)); // row_shr:4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true)); // row_shr:8
+    return v;
 }
 
 // The lane's pieces of row t: channels 32 p + 8 q + 0..7, as one 16-byte load per step that nothing here
@@ -226,6 +239,26 @@ __device__ __forceinline__ void store_rows(bf16_t *base, long t, bool ok, int C,
             for (int dw = 0; dw < 4; ++dw)
                 if (ok && c0 + 2 * dw < C) b32[(t * C + c0 + 2 * dw) >> 1] = r[p][dw];
         }
+    }
+}
+
+// one step of store_rows: the lane's piece of channels 32 p + 8 q + 0..7 of row t
+template <int KSC>
+__device__ __forceinline__ void store_piece(bf16_t *base, long t, bool ok, int C, int q, int p, const uint32_t (&v)[4])
+{
+    uint32_t *b32 = reinterpret_cast<uint32_t *>(base);
+    const int c0 = 32 * p + 8 * q;
+    if (p < KSC - 2 || 32 * p + 32 <= C) {
+        if (ok) {
+            row16 u;
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) u.v[dw] = v[dw];
+            *reinterpret_cast<row16 *>(b32 + ((t * C + c0) >> 1)) = u;
+        }
+    } else {
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw)
+            if (ok && c0 + 2 * dw < C) b32[(t * C + c0 + 2 * dw) >> 1] = v[dw];
     }
 }
 
@@ -408,7 +441,14 @@ struct WideMlpBwdArgs {
     float eps;
     const bf16_t *x1, *dy;
     const bf16_t *ln_w, *ln_b, *w_fc1, *b_fc1, *w_fc2;
-    bf16_t *xn, *h, *dpre, *dn; // LN_2(x1) [rows, C]; h, dpre [rows, Hd]; dn [rows, C]
+    bf16_t *xn, *h, *dpre, *dn; // LN_2(x1) [rows, C]; h, dpre [rows, Hd]; dn [rows, C] (may be null with dx1)
+    // With dx1 non-null the kernel goes on through LayerNorm's adjoint and the skip of Eq. 5:
+    //   dx1 = dy + adjoint of LN_2 at x1 applied to dn;  d gamma, d beta of LN_2 are added (atomically, once per
+    //   workgroup and channel) into copy (workgroup index mod reps) of `reps` copies rep_stride floats apart.
+    bf16_t *dx1;
+    float *dgamma, *dbeta;
+    long rep_stride;
+    int reps;
     void *pack;
 };
 
@@ -425,7 +465,11 @@ template <int KSC, int KSF> struct WideMlpBwd {
     static constexpr size_t P_TABLES = (size_t)(KSF / HU) * UNIT_BYTES;
     static constexpr size_t P_BYTES = P_TABLES + (size_t)T_FLOATS * 4;
     static constexpr int OFF_TABLES = 2 * UNIT_BYTES;
-    static constexpr size_t LDS_BYTES = (size_t)OFF_TABLES + (size_t)T_FLOATS * 4;
+    // sums of LN_2's gamma / beta gradients over the rows a wave has seen: [wave][q][gamma | beta][8 KSC] floats
+    static constexpr int OFF_GSUM = OFF_TABLES + T_FLOATS * 4;
+    static constexpr int GSUM_FLOATS = kWideWaves * 4 * 2 * 8 * KSC;
+    static constexpr size_t LDS_BYTES = (size_t)OFF_GSUM + (size_t)GSUM_FLOATS * 4;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(T_FLOATS % 4 == 0, "tables are copied in 16-byte pieces");
 };
 
@@ -518,6 +562,7 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
     stream_unit(0, 0);
     for (int i = tid; i < L::T_FLOATS / 4; i += kWideThreads)
         reinterpret_cast<uint4 *>(lds + L::OFF_TABLES)[i] = reinterpret_cast<const uint4 *>(pack + L::P_TABLES)[i];
+    for (int i = tid; i < L::GSUM_FLOATS; i += kWideThreads) reinterpret_cast<float *>(lds + L::OFF_GSUM)[i] = 0.f;
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -536,7 +581,7 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
         uint32_t bx[KSC][4], bd[KSC][4];
         tidy_rows<KSC>(C, q, rx, bx);
         tidy_rows<KSC>(C, q, rd, bd);
-        layer_norm_rows<KSC>(bx, C, q, a.eps, reinterpret_cast<const float2 *>(tb + L::T_GB));
+        const float2 stats = layer_norm_rows<KSC>(bx, C, q, a.eps, reinterpret_cast<const float2 *>(tb + L::T_GB));
         store_rows<KSC>(a.xn, t, ok, C, q, bx);
 
         f32x4 dnacc[CT];
@@ -556,17 +601,18 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
                     p0 = mma32(ws[s * 64 + lane_r], b, p0);
                     p1 = mma32(ws[(KSC + s) * 64 + lane_r], b, p1);
                 }
+                const float4 b10 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0);
+                const float4 b11 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 4);
+                // pre and dh as the one-kernel-per-step path stores them (rounded)
+                const uint32_t pp[4] = {pack_bf16x2(p0[0] + b10.x, p0[1] + b10.y), pack_bf16x2(p0[2] + b10.z, p0[3] + b10.w),
+                                        pack_bf16x2(p1[0] + b11.x, p1[1] + b11.y), pack_bf16x2(p1[2] + b11.z, p1[3] + b11.w)};
+                __builtin_amdgcn_sched_barrier(0); // (the first product's accumulators are packed before the second's are live)
 #pragma unroll
                 for (int s = 0; s < KSC; ++s) {
                     const uint4 b = make_uint4(bd[s][0], bd[s][1], bd[s][2], bd[s][3]);
                     d0 = mma32(ws[(2 * KSC + s) * 64 + lane_r], b, d0);
                     d1 = mma32(ws[(3 * KSC + s) * 64 + lane_r], b, d1);
                 }
-                const float4 b10 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0);
-                const float4 b11 = *reinterpret_cast<const float4 *>(tb + L::T_B1 + f0 + 4);
-                // pre and dh as the one-kernel-per-step path stores them (rounded)
-                const uint32_t pp[4] = {pack_bf16x2(p0[0] + b10.x, p0[1] + b10.y), pack_bf16x2(p0[2] + b10.z, p0[3] + b10.w),
-                                        pack_bf16x2(p1[0] + b11.x, p1[1] + b11.y), pack_bf16x2(p1[2] + b11.z, p1[3] + b11.w)};
                 const uint32_t dd[4] = {pack_bf16x2(d0[0], d0[1]), pack_bf16x2(d0[2], d0[3]),
                                         pack_bf16x2(d1[0], d1[1]), pack_bf16x2(d1[2], d1[3])};
                 uint32_t hp[4], gp[4];
@@ -621,7 +667,86 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
             dno[p][2] = pack_bf16x2(hi[0], hi[1]);
             dno[p][3] = pack_bf16x2(hi[2], hi[3]);
         }
-        store_rows<KSC>(a.dn, t, ok, C, q, dno);
+        if (a.dn) store_rows<KSC>(a.dn, t, ok, C, q, dno);
+        if (a.dx1) {
+            // LayerNorm's adjoint at x1 (re-read: the operand registers held its normalised form) with the skip
+            // of Eq. 5:  xh = (x1 - mean) rstd,  g = dn gamma,  dx1 = rstd (g - mean(g) - xh mean(g xh)) + dy;
+            // d gamma += dn xh, d beta += dn over the rows (dn as stored: rounded)
+            u32x4 rx1[KSC];
+            load_rows<KSC>(a.x1, t, a.rows, C, q, rx1);
+            uint32_t xr[KSC][4];
+            tidy_rows<KSC>(C, q, rx1, xr);
+            const float2 *gb = reinterpret_cast<const float2 *>(tb + L::T_GB);
+            const float mean = stats.x, rstd = stats.y;
+            int qq = q;
+            asm volatile("" : "+v"(qq));
+            float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+            for (int p = 0; p < KSC; ++p)
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) {
+                    const int c = 32 * p + 8 * qq + 2 * dw;
+                    const bool in = c < C;
+                    const float4 g = *reinterpret_cast<const float4 *>(gb + c);
+                    const float g0 = bf16_lo(dno[p][dw]) * g.x, g1 = bf16_hi(dno[p][dw]) * g.z;
+                    const float h0 = in ? (bf16_lo(xr[p][dw]) - mean) * rstd : 0.f;
+                    const float h1 = in ? (bf16_hi(xr[p][dw]) - mean) * rstd : 0.f;
+                    s1 += g0 + g1;
+                    s2 += g0 * h0 + g1 * h1;
+                }
+            s1 = qgroup_sum(s1) / (float)C;
+            s2 = qgroup_sum(s2) / (float)C;
+            float *gsum = reinterpret_cast<float *>(lds + lds0 + L::OFF_GSUM) + (wv * 4 + q) * (2 * 8 * KSC);
+#pragma unroll
+            for (int p = 0; p < KSC; ++p) {
+                float pg[8], pb[8];
+                uint32_t dxo[4];
+#pragma unroll
+                for (int dw = 0; dw < 4; ++dw) {
+                    const int c = 32 * p + 8 * qq + 2 * dw;
+                    const bool in = c < C;
+                    const float4 g = *reinterpret_cast<const float4 *>(gb + c);
+                    const float d0 = bf16_lo(dno[p][dw]), d1 = bf16_hi(dno[p][dw]);
+                    const float h0 = in ? (bf16_lo(xr[p][dw]) - mean) * rstd : 0.f;
+                    const float h1 = in ? (bf16_hi(xr[p][dw]) - mean) * rstd : 0.f;
+                    dxo[dw] = pack_bf16x2(rstd * (d0 * g.x - s1 - h0 * s2) + bf16_lo(bd[p][dw]),
+                                             rstd * (d1 * g.z - s1 - h1 * s2) + bf16_hi(bd[p][dw]));
+                    // (rows beyond the last one repeat the last one: they must not be counted)
+                    pg[2 * dw] = ok ? d0 * h0 : 0.f; pg[2 * dw + 1] = ok ? d1 * h1 : 0.f;
+                    pb[2 * dw] = ok ? d0 : 0.f; pb[2 * dw + 1] = ok ? d1 : 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    pg[j] = row_sum_in_last_lane(pg[j]);
+                    pb[j] = row_sum_in_last_lane(pb[j]);
+                }
+                // (in the padding channels dn, gamma, xh and dy are zero: dx1 is -rstd s1 there, not stored)
+                store_piece<KSC>(a.dx1, t, ok, C, qq, p, dxo);
+                if (tok == 15) { // the row's last lane adds the 16 rows' sums to the wave's own
+                    float4 *ag = reinterpret_cast<float4 *>(gsum + 8 * p), *ab = reinterpret_cast<float4 *>(gsum + 8 * KSC + 8 * p);
+                    const float4 a0 = ag[0], a1 = ag[1], b0 = ab[0], b1 = ab[1];
+                    ag[0] = make_float4(a0.x + pg[0], a0.y + pg[1], a0.z + pg[2], a0.w + pg[3]);
+                    ag[1] = make_float4(a1.x + pg[4], a1.y + pg[5], a1.z + pg[6], a1.w + pg[7]);
+                    ab[0] = make_float4(b0.x + pb[0], b0.y + pb[1], b0.z + pb[2], b0.w + pb[3]);
+                    ab[1] = make_float4(b1.x + pb[4], b1.y + pb[5], b1.z + pb[6], b1.w + pb[7]);
+                }
+            }
+        }
+    }
+    if (a.dx1) {
+        // the waves' sums meet: one atomic add per channel and workgroup into one of the copies
+        __syncthreads();
+        const float *gs = reinterpret_cast<const float *>(lds + L::OFF_GSUM);
+        const long rep = (long)(blockIdx.x % a.reps) * a.rep_stride;
+        for (int i = tid; i < 2 * 32 * KSC; i += kWideThreads) {
+            const int which = i / (32 * KSC), c = i - which * (32 * KSC);
+            if (c >= C) continue;
+            const int p = c >> 5, cq = (c >> 3) & 3, j = c & 7;
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWideWaves; ++w) sum += gs[(w * 4 + cq) * (2 * 8 * KSC) + which * 8 * KSC + 8 * p + j];
+            atomicAdd((which ? a.dbeta : a.dgamma) + rep + c, sum);
+        }
     }
 }
 
@@ -754,14 +879,17 @@ size_t astl_mlp_wide_bwd_pack_bytes() { return (WideMlpBwd<6, 12>::P_BYTES + 255
 
 hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
-                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn,
-                                    const void *pack, hipStream_t s)
+                                    const bf16_t *w_fc2, bf16_t *xn, bf16_t *h, bf16_t *dpre, bf16_t *dn, bf16_t *dx1,
+                                    float *dln_w, float *dln_b, long rep_stride, int reps, const void *pack,
+                                    hipStream_t s)
 {
     if (!astl_mlp_wide_supported(C, hidden) || rows <= 0) return hipErrorInvalidValue;
     WideMlpBwdArgs m{};
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x1 = x1; m.dy = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
     m.xn = xn; m.h = h; m.dpre = dpre; m.dn = dn; m.pack = const_cast<void *>(pack);
+    if ((!dn && !dx1) || (dx1 && (!dln_w || !dln_b || reps < 1))) return hipErrorInvalidValue;
+    m.dx1 = dx1; m.dgamma = dln_w; m.dbeta = dln_b; m.rep_stride = rep_stride; m.reps = reps;
     if (C <= 128) return launch_wide_bwd_t<4, 12>(m, s);
     return launch_wide_bwd_t<6, 12>(m, s);
 }
