@@ -585,13 +585,12 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w2.dw = rep + o_w2; w2.db = rep + o_b2; w2.rep_stride = P; w2.reps = kGradReplicas;
         w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
         w2.scratch = third; w2.scratch_bytes = pl.hid;
-        ASTL_HIP(launch_wgrad<T>(w2, st));
         WgradArgs w1{};
         w1.dout = dpre; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
         w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
         w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
         w1.scratch = third; w1.scratch_bytes = pl.hid;
-        ASTL_HIP(launch_wgrad<T>(w1, st));
+        ASTL_HIP(launch_wgrad_pair<T>(w2, w1, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
         T *dh = reinterpret_cast<T *>(rest + 2 * pl.hid);

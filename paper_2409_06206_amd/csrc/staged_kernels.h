@@ -93,6 +93,8 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 // The tail of a group's backward: the weight-gradient reduction `a`, optionally a second independent
 // one (`b`, may be null) and the linear map `lin` (dF of the group), which all read the same
 // d(q|k|v): one launch where the kernels allow it.
+// two weight gradients over the same rows and scratch: one launch and one sum where the streaming kernel takes both
+template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s);
 template <typename T>
 hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const LinearArgs &lin, hipStream_t s);
 

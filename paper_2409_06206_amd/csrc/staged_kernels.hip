@@ -930,11 +930,27 @@ template <int NB, int KB> struct WgradStreamCfg {
 
 // block (n0, k0) of the gradient: dout and a point at the block's first column; `bias`: this block also
 // carries the bias sums (column KB of [a | 1])
+// One of the (one or two) gradients of a launch: its operands, its shape and where its [d w | d b] lies inside a
+// share's partial array.
+struct WgradStreamJob {
+    const bf16_t *dout; long lddout;
+    const bf16_t *a; long lda;
+    int N, K;
+    long part_off;
+};
+
+// blockIdx.y < blocks0: a block of the first gradient, otherwise of the second (both over the same rows);
+// `per` = floats of a share's partial array (both gradients).
 template <int NB, int KB>
-__global__ __launch_bounds__(512, 1) void wgrad_stream_kernel(long rows, const bf16_t *__restrict__ dout, long lddout,
-                                                              const bf16_t *__restrict__ a, long lda,
-                                                              float *__restrict__ part, int N, int K)
+__global__ __launch_bounds__(512, 1) void wgrad_stream_kernel(long rows, WgradStreamJob j0, int blocks0, WgradStreamJob j1,
+                                                              float *__restrict__ part, long per)
 {
+    const bool second = (int)blockIdx.y >= blocks0;
+    const bf16_t *__restrict__ dout = second ? j1.dout : j0.dout;
+    const bf16_t *__restrict__ a = second ? j1.a : j0.a;
+    const long lddout = second ? j1.lddout : j0.lddout, lda = second ? j1.lda : j0.lda;
+    const int N = second ? j1.N : j0.N, K = second ? j1.K : j0.K;
+    const int by = (int)blockIdx.y - (second ? blocks0 : 0);
     using P = WgradStreamCfg<NB, KB>;
     constexpr int NT = P::NT, KT = P::KT, KSN = P::KSN, KSK = P::KSK, LW = P::LW, RW = P::RW, CW = P::CW;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -944,7 +960,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_stream_kernel(long rows, const b
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rg = wv & 3, ch = wv >> 2;
     const int nkb = K / KB;                                // blocks along K; block index = nb * nkb + kb
-    const int n0 = ((int)blockIdx.y / nkb) * NB, k0 = ((int)blockIdx.y % nkb) * KB;
+    const int n0 = (by / nkb) * NB, k0 = (by % nkb) * KB;
     const bool bias = k0 == 0;
     dout += n0;
     a += k0;
@@ -1020,7 +1036,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_stream_kernel(long rows, const b
             }
         }
     }
-    float *mine = part + (size_t)blockIdx.x * ((size_t)N * K + N); // the share's partial array [d w | d b]
+    float *mine = part + (size_t)blockIdx.x * per + (second ? j1.part_off : j0.part_off); // the share's [d w | d b]
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         const int nt = rg * RW + r;
@@ -1066,28 +1082,45 @@ static int wgrad_stream_shares(const WgradArgs &a)
     return shares >= 16 ? (int)shares : 0;
 }
 
-static hipError_t run_wgrad_stream(const WgradArgs &a, int shares, hipStream_t s)
+static WgradStreamJob stream_job(const WgradArgs &a, long part_off)
+{
+    WgradStreamJob j{};
+    j.dout = static_cast<const bf16_t *>(a.dout); j.lddout = a.lddout;
+    j.a = static_cast<const bf16_t *>(a.a1); j.lda = a.lda1;
+    j.N = a.N; j.K = a.K; j.part_off = part_off;
+    return j;
+}
+
+// `b` may be null: one gradient.  Two gradients share the rows, the scratch and the number of shares.
+static hipError_t run_wgrad_stream(const WgradArgs &a, const WgradArgs *b, int shares, hipStream_t s)
 {
     constexpr int B = kWgradStreamBlock;
     using P = WgradStreamCfg<B, B>;
     auto kern = wgrad_stream_kernel<B, B>;
     if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), P::LDS_BYTES); ea != hipSuccess) return ea;
     float *part = static_cast<float *>(a.scratch);
+    const int total0 = a.N * a.K + a.N, total1 = b ? b->N * b->K + b->N : 0;
+    const int blocks0 = (a.N / B) * (a.K / B), blocks1 = b ? (b->N / B) * (b->K / B) : 0;
     {
         KernelTimer kt(a.prof_id, s);
-        hipLaunchKernelGGL(kern, dim3(shares, (a.N / B) * (a.K / B)), dim3(64 * P::NWV), P::LDS_BYTES, s, a.rows,
-                           static_cast<const bf16_t *>(a.dout), a.lddout, static_cast<const bf16_t *>(a.a1), a.lda1, part,
-                           a.N, a.K);
+        hipLaunchKernelGGL(kern, dim3(shares, blocks0 + blocks1), dim3(64 * P::NWV), P::LDS_BYTES, s, a.rows,
+                           stream_job(a, 0), blocks0, b ? stream_job(*b, total0) : stream_job(a, 0), part,
+                           (long)total0 + total1);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int total = a.N * a.K + a.N;
     ReduceOut out{};
     out.ptr[0] = a.dw; out.begin[0] = 0;
     out.ptr[1] = a.db; out.begin[1] = a.N * a.K;
-    out.begin[2] = total;
+    out.begin[2] = total0;
     out.nseg = 2;
-    return launch_reduce(part, shares, total, out, 1, s); // onto copy 0 of the gradient
+    if (b) {
+        out.ptr[2] = b->dw; out.begin[2] = total0;
+        out.ptr[3] = b->db; out.begin[3] = total0 + b->N * b->K;
+        out.begin[4] = total0 + total1;
+        out.nseg = 4;
+    }
+    return launch_reduce(part, shares, total0 + total1, out, 1, s); // onto copy 0 of the gradients
 }
 
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
@@ -1095,7 +1128,7 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
     if (a.rows <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
     if (a.reps < 1) return hipErrorInvalidValue;
     if constexpr (sizeof(T) == 2) {
-        if (const int shares = wgrad_stream_shares(a)) return run_wgrad_stream(a, shares, s);
+        if (const int shares = wgrad_stream_shares(a)) return run_wgrad_stream(a, nullptr, shares, s);
         return launch_wgrad_mfma(a, nullptr, nullptr, s);
     }
     const unsigned tn = (a.N + 63) / 64, tk = (a.K + 63) / 64;
@@ -1115,6 +1148,30 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 template hipError_t launch_wgrad<float>(const WgradArgs &, hipStream_t);
 template hipError_t launch_wgrad<bf16_t>(const WgradArgs &, hipStream_t);
 
+// Two weight gradients over the same rows (and the same scratch) in one launch and one sum where the streaming
+// kernel takes both; otherwise one after the other.
+template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s)
+{
+    if constexpr (sizeof(T) == 2) {
+        if (a.rows == b.rows && a.scratch == b.scratch && a.scratch_bytes == b.scratch_bytes && a.reps >= 1 && b.reps >= 1 &&
+            wgrad_stream_shares(a) && wgrad_stream_shares(b)) {
+            constexpr int B = kWgradStreamBlock;
+            const size_t per = ((size_t)a.N * a.K + a.N + (size_t)b.N * b.K + b.N) * 4;
+            const int blocks = (a.N / B) * (a.K / B) + (b.N / B) * (b.K / B);
+            long shares = (long)(a.scratch_bytes / per);
+            const long passes = (a.rows + 127) / 128, want = device_cu_count() / blocks;
+            if (shares > want) shares = want;
+            if (shares > passes) shares = passes;
+            // (the second gradient's part of a share's array must start on the boundary the sum's wide loads need)
+            if (shares >= 16 && ((size_t)a.N * a.K + a.N) % 4 == 0) return run_wgrad_stream(a, &b, (int)shares, s);
+        }
+    }
+    hipError_t e = launch_wgrad<T>(a, s);
+    return e != hipSuccess ? e : launch_wgrad<T>(b, s);
+}
+template hipError_t launch_wgrad_pair<float>(const WgradArgs &, const WgradArgs &, hipStream_t);
+template hipError_t launch_wgrad_pair<bf16_t>(const WgradArgs &, const WgradArgs &, hipStream_t);
+
 template <typename T>
 hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const LinearArgs &lin, hipStream_t s)
 {
@@ -1124,7 +1181,7 @@ hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const Line
             // same scratch one after the other)
             hipError_t e = launch_linear<T>(lin, s);
             if (e != hipSuccess) return e;
-            e = run_wgrad_stream(a, shares, s);
+            e = run_wgrad_stream(a, nullptr, shares, s);
             if (e != hipSuccess || !b) return e;
             return launch_wgrad<T>(*b, s);
         }
