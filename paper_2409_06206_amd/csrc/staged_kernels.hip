@@ -1181,9 +1181,8 @@ hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const Line
             // same scratch one after the other)
             hipError_t e = launch_linear<T>(lin, s);
             if (e != hipSuccess) return e;
-            e = run_wgrad_stream(a, nullptr, shares, s);
-            if (e != hipSuccess || !b) return e;
-            return launch_wgrad<T>(*b, s);
+            if (b) return launch_wgrad_pair<T>(a, *b, s); // (one launch for both where the kernel takes both)
+            return run_wgrad_stream(a, nullptr, shares, s);
         }
         const bool wg_ok = a.rows > 0 && a.N > 0 && a.K > 0 && a.reps >= 1 &&
                            (!b || (b->rows > 0 && b->N > 0 && b->K > 0 && b->reps >= 1));
