@@ -533,10 +533,20 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     float *rep = reinterpret_cast<float *>(ws + pl.bwd_ws - pl.reps);
     // one copy of the gradients: dw_fc1 | db_fc1 | dw_fc2 | db_fc2 | dln1_w | dln1_b | dln2_w | dln2_b;
     // with the fused MLP backward, which writes its six gradients itself: dln1_w | dln1_b only
-    const long P = (long)pl.params;
     const bool own = pl.fused_mlp_bwd;
+    // Wide layers whose four MLP weight gradients come from the streaming kernel (its own partial arrays and a
+    // fixed-order sum straight into the gradients): the copies then hold the LayerNorm sums only
+    bool mlp_direct = false;
+    if (pl.wide_mlp) {
+        WgradArgs t2{}, t1{};
+        t2.dout = dy; t2.lddout = C; t2.a1 = ws; t2.lda1 = Hd; t2.rows = rows; t2.N = C; t2.K = Hd; t2.reps = 1;
+        t1.dout = ws; t1.lddout = Hd; t1.a1 = ws; t1.lda1 = C; t1.rows = rows; t1.N = Hd; t1.K = C; t1.reps = 1;
+        t2.scratch = t1.scratch = ws + 3 * pl.act + 2 * pl.hid; t2.scratch_bytes = t1.scratch_bytes = pl.hid;
+        mlp_direct = wgrad_pair_streams(t2, t1);
+    }
+    const long P = own ? (long)pl.params : mlp_direct ? 4L * C : (long)pl.params;
     const long o_w1 = 0, o_b1 = o_w1 + (long)Hd * C, o_w2 = o_b1 + Hd, o_b2 = o_w2 + (long)C * Hd;
-    const long o_g1 = own ? 0 : o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
+    const long o_g1 = own || mlp_direct ? 0 : o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
     const int accumulate = (d->attn.flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
 
     MlpPending pend{};
@@ -590,6 +600,10 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
         w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
         w1.scratch = third; w1.scratch_bytes = pl.hid;
+        if (mlp_direct) { // (no copies: the kernel's sum writes, or adds to, the gradients themselves)
+            w2.dw = g->w_fc2; w2.db = g->b_fc2; w1.dw = g->w_fc1; w1.db = g->b_fc1;
+            w2.direct = w1.direct = 1; w2.accumulate = w1.accumulate = accumulate;
+        }
         ASTL_HIP(launch_wgrad_pair<T>(w2, w1, st));
     } else {
         T *pre = reinterpret_cast<T *>(rest), *h = reinterpret_cast<T *>(rest + pl.hid);
@@ -676,6 +690,12 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         rs.out[0] = g->ln1_w; rs.off[0] = o_g1; rs.n[0] = C;
         rs.out[1] = g->ln1_b; rs.off[1] = o_be1; rs.n[1] = C;
         rs.count = 2;
+    } else if (mlp_direct) {
+        rs.out[0] = g->ln1_w; rs.off[0] = o_g1; rs.n[0] = C;
+        rs.out[1] = g->ln1_b; rs.off[1] = o_be1; rs.n[1] = C;
+        rs.out[2] = g->ln2_w; rs.off[2] = o_g2; rs.n[2] = C;
+        rs.out[3] = g->ln2_b; rs.off[3] = o_be2; rs.n[3] = C;
+        rs.count = 4;
     } else {
         rs.out[0] = g->w_fc1; rs.off[0] = o_w1; rs.n[0] = (long)Hd * C;
         rs.out[1] = g->b_fc1; rs.off[1] = o_b1; rs.n[1] = Hd;

@@ -82,6 +82,9 @@ struct WgradArgs {
                    // one addition per entry (onto zero) and the sum over the copies has a fixed order
     void *scratch; size_t scratch_bytes; // optional (may be null): device memory free for the duration of the call;
                                          // wide layers then take the streaming kernel, which needs no atomics
+    // Where the caller knows that the streaming kernel will run (wgrad_pair_streams), dw / db may be the final
+    // gradient arrays instead of a zeroed copy: `direct` nonzero, and the sum then writes (accumulate 0) or adds.
+    int direct, accumulate;
 };
 
 template <typename T> hipError_t launch_linear(const LinearArgs &a, hipStream_t s);
@@ -95,6 +98,8 @@ template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
 // d(q|k|v): one launch where the kernels allow it.
 // two weight gradients over the same rows and scratch: one launch and one sum where the streaming kernel takes both
 template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s);
+// true when launch_wgrad_pair<bf16_t> runs both on the streaming kernel (no copies, no atomics)
+bool wgrad_pair_streams(const WgradArgs &a, const WgradArgs &b);
 template <typename T>
 hipError_t launch_wgrad_group(const WgradArgs &a, const WgradArgs *b, const LinearArgs &lin, hipStream_t s);
 

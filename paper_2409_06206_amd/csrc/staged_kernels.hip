@@ -1120,7 +1120,8 @@ static hipError_t run_wgrad_stream(const WgradArgs &a, const WgradArgs *b, int s
         out.begin[4] = total0 + total1;
         out.nseg = 4;
     }
-    return launch_reduce(part, shares, total0 + total1, out, 1, s); // onto copy 0 of the gradients
+    // onto copy 0 of the gradients, or into the gradients themselves
+    return launch_reduce(part, shares, total0 + total1, out, a.direct ? a.accumulate : 1, s);
 }
 
 template <typename T> hipError_t launch_wgrad(const WgradArgs &a, hipStream_t s)
@@ -1150,22 +1151,31 @@ template hipError_t launch_wgrad<bf16_t>(const WgradArgs &, hipStream_t);
 
 // Two weight gradients over the same rows (and the same scratch) in one launch and one sum where the streaming
 // kernel takes both; otherwise one after the other.
+// shares of the rows for both gradients in one launch of the streaming kernel; 0: not both there
+static int wgrad_pair_shares(const WgradArgs &a, const WgradArgs &b)
+{
+    if (!(a.rows == b.rows && a.scratch == b.scratch && a.scratch_bytes == b.scratch_bytes && a.reps >= 1 && b.reps >= 1 &&
+          a.direct == b.direct && a.accumulate == b.accumulate && wgrad_stream_shares(a) && wgrad_stream_shares(b)))
+        return 0;
+    constexpr int B = kWgradStreamBlock;
+    const size_t per = ((size_t)a.N * a.K + a.N + (size_t)b.N * b.K + b.N) * 4;
+    const int blocks = (a.N / B) * (a.K / B) + (b.N / B) * (b.K / B);
+    long shares = (long)(a.scratch_bytes / per);
+    const long passes = (a.rows + 127) / 128, want = device_cu_count() / blocks;
+    if (shares > want) shares = want;
+    if (shares > passes) shares = passes;
+    // (the second gradient's part of a share's array must start on the boundary the sum's wide loads need)
+    return shares >= 16 && ((size_t)a.N * a.K + a.N) % 4 == 0 ? (int)shares : 0;
+}
+
+bool wgrad_pair_streams(const WgradArgs &a, const WgradArgs &b) { return wgrad_pair_shares(a, b) > 0; }
+
 template <typename T> hipError_t launch_wgrad_pair(const WgradArgs &a, const WgradArgs &b, hipStream_t s)
 {
     if constexpr (sizeof(T) == 2) {
-        if (a.rows == b.rows && a.scratch == b.scratch && a.scratch_bytes == b.scratch_bytes && a.reps >= 1 && b.reps >= 1 &&
-            wgrad_stream_shares(a) && wgrad_stream_shares(b)) {
-            constexpr int B = kWgradStreamBlock;
-            const size_t per = ((size_t)a.N * a.K + a.N + (size_t)b.N * b.K + b.N) * 4;
-            const int blocks = (a.N / B) * (a.K / B) + (b.N / B) * (b.K / B);
-            long shares = (long)(a.scratch_bytes / per);
-            const long passes = (a.rows + 127) / 128, want = device_cu_count() / blocks;
-            if (shares > want) shares = want;
-            if (shares > passes) shares = passes;
-            // (the second gradient's part of a share's array must start on the boundary the sum's wide loads need)
-            if (shares >= 16 && ((size_t)a.N * a.K + a.N) % 4 == 0) return run_wgrad_stream(a, &b, (int)shares, s);
-        }
+        if (const int shares = wgrad_pair_shares(a, b)) return run_wgrad_stream(a, &b, shares, s);
     }
+    if (a.direct || b.direct) return hipErrorInvalidValue; // (callers ask wgrad_pair_streams first)
     hipError_t e = launch_wgrad<T>(a, s);
     return e != hipSuccess ? e : launch_wgrad<T>(b, s);
 }

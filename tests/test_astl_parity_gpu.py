@@ -65,7 +65,12 @@ def test_inference_call_gives_the_training_output(case):
     assert torch.equal(y_inf, blk.y)
 
 
-@pytest.mark.parametrize("case", [SMALL[0], SMALL[7]], ids=_id)
+@pytest.mark.parametrize("case", [
+    SMALL[0], SMALL[7],
+    # a wide layer with enough tokens for the streaming weight-gradient kernel, whose sum then writes or adds
+    # straight into the gradients of the two MLP maps
+    dict(B=2, H=64, W=32, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
+], ids=_id)
 def test_accumulate_flag_adds_into_every_parameter_gradient(case):
     print("case", case, flush=True)
     import torch
