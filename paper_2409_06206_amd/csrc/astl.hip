@@ -7,6 +7,7 @@
 #include "common.h"
 #include "staged_kernels.h"
 #include "astl_mlp.h"
+#include "fused.h"
 
 namespace gswa {
 
@@ -535,7 +536,7 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     // with the fused MLP backward, which writes its six gradients itself: dln1_w | dln1_b only
     const bool own = pl.fused_mlp_bwd;
     // Wide layers whose four MLP weight gradients come from the streaming kernel (its own partial arrays and a
-    // fixed-order sum straight into the gradients): the copies then hold the LayerNorm sums only
+    // fixed-order sum straight into the gradients): no gradient copies, no atomics anywhere in this file's part
     bool mlp_direct = false;
     if (pl.wide_mlp) {
         WgradArgs t2{}, t1{};
@@ -544,9 +545,9 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         t2.scratch = t1.scratch = ws + 3 * pl.act + 2 * pl.hid; t2.scratch_bytes = t1.scratch_bytes = pl.hid;
         mlp_direct = wgrad_pair_streams(t2, t1);
     }
-    const long P = own ? (long)pl.params : mlp_direct ? 4L * C : (long)pl.params;
+    const long P = (long)pl.params;
     const long o_w1 = 0, o_b1 = o_w1 + (long)Hd * C, o_w2 = o_b1 + Hd, o_b2 = o_w2 + (long)C * Hd;
-    const long o_g1 = own || mlp_direct ? 0 : o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
+    const long o_g1 = own ? 0 : o_b2 + C, o_be1 = o_g1 + C, o_g2 = o_be1 + C, o_be2 = o_g2 + C;
     const int accumulate = (d->attn.flags & GSWA_ACCUM_WGRAD) ? 1 : 0;
 
     MlpPending pend{};
@@ -563,7 +564,14 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         ps.accumulate = pend.accumulate;
         ASTL_HIP(launch_reduce_replicas(ps, st));
     }
-    if (!own) {
+    // (mlp_direct: nothing is added into copies at all.  The two LayerNorms' gamma / beta sums leave their kernels
+    // as one vector per workgroup, in the copies' memory, and one launch sums both sets in a fixed order.)
+    float *lnpart2 = rep;
+    const int nparts2 = mlp_direct ? astl_mlp_wide_bwd_blocks(rows) : 0;
+    float *lnpart1 = rep + (size_t)nparts2 * 2 * C;
+    const int nparts1 = mlp_direct ? ln_rows_bwd_blocks(rows) : 0;
+    if (mlp_direct && (size_t)(nparts1 + nparts2) * 2 * C * sizeof(float) > pl.reps) return GSWA_EINVAL;
+    if (!own && !mlp_direct) {
         ZeroList z{};
         z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P; z.count = 1;
         ASTL_HIP(launch_fill_zero(z, st));
@@ -587,7 +595,8 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
                                           (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                           (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
                                           (const bf16_t *)p->w_fc2, (bf16_t *)xn, (bf16_t *)h, (bf16_t *)dpre,
-                                          nullptr, (bf16_t *)dx1, rep + o_g2, rep + o_be2, P, kGradReplicas,
+                                          nullptr, (bf16_t *)dx1, mlp_direct ? lnpart2 : rep + o_g2,
+                                          mlp_direct ? nullptr : rep + o_be2, P, mlp_direct ? 0 : kGradReplicas,
                                           saved + pl.saved - pl.pack + astl_mlp_wide_pack_bytes(), st));
         // d Wfc2 = dy^T h,  d Wfc1 = dpre^T LN_2(x1)
         WgradArgs w2{};
@@ -671,6 +680,24 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     ASTL_HIP(launch_ln_fwd<T>(l1, st, pl.fused_mlp_bwd ? &mlp_sum : nullptr));
     ASTL_RC(gswa_backward(&d->attn, xn, dx1, p->w_qkv, p->b_qkv, p->w_proj, p->b_proj, p->bias_table, at_saved,
                           dn, g->w_qkv, g->b_qkv, g->w_proj, g->b_proj, g->bias_table, rest, st));
+    if (mlp_direct) {
+        LnRowsBwdArgs n1{};
+        n1.u = (const bf16_t *)x; n1.dout = (const bf16_t *)dn; n1.res = (const bf16_t *)dx1;
+        n1.gamma = (const bf16_t *)p->ln1_w; n1.du = (bf16_t *)dx; n1.part = lnpart1;
+        n1.rows = rows; n1.C = C; n1.eps = d->eps;
+        {
+            KernelTimer kt(K_LN_BWD, st);
+            ASTL_HIP(launch_ln_rows_bwd(n1, st));
+        }
+        ReduceJob j1{}, j2{};
+        j1.part = lnpart1; j1.nparts = nparts1; j1.n = 2 * C; j1.accumulate = accumulate;
+        j1.out.ptr[0] = g->ln1_w; j1.out.begin[0] = 0; j1.out.ptr[1] = g->ln1_b; j1.out.begin[1] = C;
+        j1.out.begin[2] = 2 * C; j1.out.nseg = 2;
+        j2 = j1;
+        j2.part = lnpart2; j2.nparts = nparts2; j2.out.ptr[0] = g->ln2_w; j2.out.ptr[1] = g->ln2_b;
+        ASTL_HIP(launch_reduce_pair(j1, j2, st));
+        return GSWA_OK;
+    }
     LnBwdArgs n1{};
     n1.u = x; n1.dout = dn; n1.res = dx1; n1.gamma = p->ln1_w; n1.du = dx;
     n1.dgamma = rep + o_g1; n1.dbeta = rep + o_be1; n1.rep_stride = P; n1.reps = kGradReplicas;
@@ -690,12 +717,6 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         rs.out[0] = g->ln1_w; rs.off[0] = o_g1; rs.n[0] = C;
         rs.out[1] = g->ln1_b; rs.off[1] = o_be1; rs.n[1] = C;
         rs.count = 2;
-    } else if (mlp_direct) {
-        rs.out[0] = g->ln1_w; rs.off[0] = o_g1; rs.n[0] = C;
-        rs.out[1] = g->ln1_b; rs.off[1] = o_be1; rs.n[1] = C;
-        rs.out[2] = g->ln2_w; rs.off[2] = o_g2; rs.n[2] = C;
-        rs.out[3] = g->ln2_b; rs.off[3] = o_be2; rs.n[3] = C;
-        rs.count = 4;
     } else {
         rs.out[0] = g->w_fc1; rs.off[0] = o_w1; rs.n[0] = (long)Hd * C;
         rs.out[1] = g->b_fc1; rs.off[1] = o_b1; rs.n[1] = Hd;

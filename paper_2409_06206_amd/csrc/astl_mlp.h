@@ -37,7 +37,8 @@ hipError_t launch_astl_mlp_wide_fwd(long rows, int C, int hidden, float eps, con
 // dn = dpre W1 for LayerNorm's adjoint (dn may be null if dx1 is not).  With dx1 non-null the kernel goes on
 // through that adjoint and the skip of Eq. 5: dx1 = dy + LN_2's adjoint of dn at x1, and LN_2's d gamma, d beta
 // are added into copy (workgroup mod reps) of `reps` copies rep_stride floats apart at dln_w / dln_b (fp32
-// atomics, one per channel and workgroup).  `pack` is what the forward call wrote at its bwd_pack.
+// atomics, one per channel and workgroup), or with reps == 0 written as one vector [d gamma | d beta] per
+// workgroup at dln_w (astl_mlp_wide_bwd_blocks(rows) vectors of 2 C floats; no atomics).  `pack` is what the forward call wrote at its bwd_pack.
 size_t astl_mlp_wide_bwd_pack_bytes();
 hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, const bf16_t *x1, const bf16_t *dy,
                                     const bf16_t *ln_w, const bf16_t *ln_b, const bf16_t *w_fc1, const bf16_t *b_fc1,
@@ -56,6 +57,21 @@ struct LnRowsArgs {
 };
 bool ln_rows_supported(int C);
 hipError_t launch_ln_rows_fwd(const LnRowsArgs &a, hipStream_t s);
+// The adjoint for the same rows: du = LN's adjoint of dout at u (+ res, may be null).  The gamma / beta sums leave as
+// one vector [d gamma: C | d beta: C] per workgroup at `part` (ln_rows_bwd_blocks(rows) of them), to be summed by
+// the caller in a fixed order: no atomics.
+struct LnRowsBwdArgs {
+    const bf16_t *u, *dout, *res, *gamma;
+    bf16_t *du;
+    float *part;
+    long rows;
+    int C;
+    float eps;
+};
+int ln_rows_bwd_blocks(long rows);
+hipError_t launch_ln_rows_bwd(const LnRowsBwdArgs &a, hipStream_t s);
+// workgroups of launch_astl_mlp_wide_bwd for `rows` rows (= partial vectors it writes with reps == 0)
+int astl_mlp_wide_bwd_blocks(long rows);
 
 // The backward kernel covers the same shapes.
 bool astl_mlp_bwd_supported(int C, int hidden);

@@ -444,7 +444,9 @@ struct WideMlpBwdArgs {
     bf16_t *xn, *h, *dpre, *dn; // LN_2(x1) [rows, C]; h, dpre [rows, Hd]; dn [rows, C] (may be null with dx1)
     // With dx1 non-null the kernel goes on through LayerNorm's adjoint and the skip of Eq. 5:
     //   dx1 = dy + adjoint of LN_2 at x1 applied to dn;  d gamma, d beta of LN_2 are added (atomically, once per
-    //   workgroup and channel) into copy (workgroup index mod reps) of `reps` copies rep_stride floats apart.
+    //   workgroup and channel) into copy (workgroup index mod reps) of `reps` copies rep_stride floats apart, or,
+    //   with reps == 0, written as one vector [d gamma: C | d beta: C] per workgroup at dgamma (no atomics; the
+    //   caller sums astl_mlp_wide_bwd_blocks() of them).
     bf16_t *dx1;
     float *dgamma, *dbeta;
     long rep_stride;
@@ -737,7 +739,7 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
         // the waves' sums meet: one atomic add per channel and workgroup into one of the copies
         __syncthreads();
         const float *gs = reinterpret_cast<const float *>(lds + L::OFF_GSUM);
-        const long rep = (long)(blockIdx.x % a.reps) * a.rep_stride;
+        const long rep = a.reps > 0 ? (long)(blockIdx.x % a.reps) * a.rep_stride : 0;
         for (int i = tid; i < 2 * 32 * KSC; i += kWideThreads) {
             const int which = i / (32 * KSC), c = i - which * (32 * KSC);
             if (c >= C) continue;
@@ -745,7 +747,8 @@ __global__ __launch_bounds__(kWideThreads) void astl_mlp_wide_bwd_kernel(WideMlp
             float sum = 0.f;
 #pragma unroll
             for (int w = 0; w < kWideWaves; ++w) sum += gs[(w * 4 + cq) * (2 * 8 * KSC) + which * 8 * KSC + 8 * p + j];
-            atomicAdd((which ? a.dbeta : a.dgamma) + rep + c, sum);
+            if (a.reps > 0) atomicAdd((which ? a.dbeta : a.dgamma) + rep + c, sum);
+            else a.dgamma[(size_t)blockIdx.x * 2 * C + which * C + c] = sum; // the workgroup's own vector [d gamma | d beta]
         }
     }
 }
@@ -789,11 +792,8 @@ template <int KSC, int KSF> hipError_t launch_wide_bwd_t(const WideMlpBwdArgs &a
     const int nu = ((a.Hd + 31) / 32 + L::HU - 1) / L::HU; // stream units
     auto kern = astl_mlp_wide_bwd_kernel<KSC, KSF>;
     if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(kern), L::LDS_BYTES); ea != hipSuccess) return ea;
-    const long tiles = (a.rows + 15) / 16;
-    long blocks = (tiles + kWideWaves - 1) / kWideWaves;
-    if (blocks > device_cu_count()) blocks = device_cu_count();
     KernelTimer kt(K_MLP_BWD, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(blocks < 1 ? 1 : blocks)), dim3(kWideThreads), L::LDS_BYTES, s, a, nu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)astl_mlp_wide_bwd_blocks(a.rows)), dim3(kWideThreads), L::LDS_BYTES, s, a, nu);
     return hipGetLastError();
 }
 
@@ -847,6 +847,118 @@ __global__ __launch_bounds__(kLnRowsThreads) void ln_rows_fwd_kernel(LnRowsArgs 
     }
 }
 
+
+// LayerNorm's adjoint of the same rows, same lane pattern: with xh = (u - mean) rstd and g = dout gamma,
+//   du = rstd (g - mean(g) - xh mean(g xh)) (+ res);   d gamma = sum_t dout xh;   d beta = sum_t dout.
+// The sums over rows as in the MLP backward kernel above (row shifts, per-wave sums in LDS); every workgroup
+// writes ONE vector [d gamma: C | d beta: C] of its own, which the caller sums in a fixed order: no atomics.
+template <int KSC>
+__global__ __launch_bounds__(kLnRowsThreads) void ln_rows_bwd_kernel(LnRowsBwdArgs a)
+{
+    constexpr int NW = kLnRowsThreads / 64;
+    __shared__ float gam[32 * KSC];
+    __shared__ __attribute__((aligned(16))) float gsum_all[NW * 4 * 2 * 8 * KSC];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, tok = lane & 15, q = lane >> 4;
+    const int C = a.C;
+    for (int c = tid; c < 32 * KSC; c += kLnRowsThreads) gam[c] = c < C ? bfv(a.gamma, c) : 0.f;
+    for (int i = tid; i < NW * 4 * 2 * 8 * KSC; i += kLnRowsThreads) gsum_all[i] = 0.f;
+    __syncthreads();
+    float *gsum = gsum_all + (wv * 4 + q) * (2 * 8 * KSC);
+    const long ntiles = (a.rows + 15) / 16;
+    const long stride = (long)gridDim.x * NW;
+    for (long tile = (long)blockIdx.x * NW + wv; tile < ntiles; tile += stride) {
+        const long t = tile * 16 + tok;
+        const bool ok = t < a.rows;
+        u32x4 ru[KSC], rd[KSC], rr[KSC];
+        load_rows<KSC>(a.u, t, a.rows, C, q, ru);
+        load_rows<KSC>(a.dout, t, a.rows, C, q, rd);
+        if (a.res) load_rows<KSC>(a.res, t, a.rows, C, q, rr);
+        uint32_t xu[KSC][4], xd[KSC][4];
+        tidy_rows<KSC>(C, q, ru, xu);
+        tidy_rows<KSC>(C, q, rd, xd);
+        int qq = q;
+        asm volatile("" : "+v"(qq));
+        // mean and 1 / sqrt(var + eps) as the forward kernels take them
+        float sum = 0.f;
+#pragma unroll
+        for (int p = 0; p < KSC; ++p)
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) sum += bf16_lo(xu[p][dw]) + bf16_hi(xu[p][dw]);
+        const float mean = qgroup_sum(sum) / (float)C;
+        float dev = 0.f, s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int p = 0; p < KSC; ++p)
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw)
+                if (32 * p + 8 * qq + 2 * dw < C) {
+                    const float d0 = bf16_lo(xu[p][dw]) - mean, d1 = bf16_hi(xu[p][dw]) - mean;
+                    dev += d0 * d0 + d1 * d1;
+                }
+        const float rstd = rsqrtf(qgroup_sum(dev) / (float)C + a.eps);
+#pragma unroll
+        for (int p = 0; p < KSC; ++p)
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int c = 32 * p + 8 * qq + 2 * dw;
+                const bool in = c < C;
+                const float2 gm = *reinterpret_cast<const float2 *>(gam + c);
+                const float g0 = bf16_lo(xd[p][dw]) * gm.x, g1 = bf16_hi(xd[p][dw]) * gm.y;
+                const float h0 = in ? (bf16_lo(xu[p][dw]) - mean) * rstd : 0.f;
+                const float h1 = in ? (bf16_hi(xu[p][dw]) - mean) * rstd : 0.f;
+                s1 += g0 + g1;
+                s2 += g0 * h0 + g1 * h1;
+            }
+        s1 = qgroup_sum(s1) / (float)C;
+        s2 = qgroup_sum(s2) / (float)C;
+        uint32_t xr[KSC][4];
+        if (a.res) tidy_rows<KSC>(C, q, rr, xr);
+#pragma unroll
+        for (int p = 0; p < KSC; ++p) {
+            float pg[8], pb[8];
+            uint32_t duo[4];
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int c = 32 * p + 8 * qq + 2 * dw;
+                const bool in = c < C;
+                const float2 gm = *reinterpret_cast<const float2 *>(gam + c);
+                const float d0 = bf16_lo(xd[p][dw]), d1 = bf16_hi(xd[p][dw]);
+                const float h0 = in ? (bf16_lo(xu[p][dw]) - mean) * rstd : 0.f;
+                const float h1 = in ? (bf16_hi(xu[p][dw]) - mean) * rstd : 0.f;
+                float o0 = rstd * (d0 * gm.x - s1 - h0 * s2), o1 = rstd * (d1 * gm.y - s1 - h1 * s2);
+                if (a.res) { o0 += bf16_lo(xr[p][dw]); o1 += bf16_hi(xr[p][dw]); }
+                duo[dw] = pack_bf16x2(o0, o1);
+                // (rows beyond the last one repeat the last one: they must not be counted)
+                pg[2 * dw] = ok ? d0 * h0 : 0.f; pg[2 * dw + 1] = ok ? d1 * h1 : 0.f;
+                pb[2 * dw] = ok ? d0 : 0.f; pb[2 * dw + 1] = ok ? d1 : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                pg[j] = row_sum_in_last_lane(pg[j]);
+                pb[j] = row_sum_in_last_lane(pb[j]);
+            }
+            store_piece<KSC>(a.du, t, ok, C, qq, p, duo);
+            if (tok == 15) { // the row's last lane adds the 16 rows' sums to the wave's own
+                float4 *ag = reinterpret_cast<float4 *>(gsum + 8 * p), *ab = reinterpret_cast<float4 *>(gsum + 8 * KSC + 8 * p);
+                const float4 a0 = ag[0], a1 = ag[1], b0 = ab[0], b1 = ab[1];
+                ag[0] = make_float4(a0.x + pg[0], a0.y + pg[1], a0.z + pg[2], a0.w + pg[3]);
+                ag[1] = make_float4(a1.x + pg[4], a1.y + pg[5], a1.z + pg[6], a1.w + pg[7]);
+                ab[0] = make_float4(b0.x + pb[0], b0.y + pb[1], b0.z + pb[2], b0.w + pb[3]);
+                ab[1] = make_float4(b1.x + pb[4], b1.y + pb[5], b1.z + pb[6], b1.w + pb[7]);
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < 2 * 32 * KSC; i += kLnRowsThreads) {
+        const int which = i / (32 * KSC), c = i - which * (32 * KSC);
+        if (c >= C) continue;
+        const int p = c >> 5, cq = (c >> 3) & 3, j = c & 7;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += gsum_all[(w * 4 + cq) * (2 * 8 * KSC) + which * 8 * KSC + 8 * p + j];
+        a.part[(size_t)blockIdx.x * 2 * C + which * C + c] = sum;
+    }
+}
+
 } // namespace
 
 bool astl_mlp_wide_supported(int C, int hidden)
@@ -888,13 +1000,40 @@ hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, con
     m.rows = rows; m.C = C; m.Hd = hidden; m.eps = eps;
     m.x1 = x1; m.dy = dy; m.ln_w = ln_w; m.ln_b = ln_b; m.w_fc1 = w_fc1; m.b_fc1 = b_fc1; m.w_fc2 = w_fc2;
     m.xn = xn; m.h = h; m.dpre = dpre; m.dn = dn; m.pack = const_cast<void *>(pack);
-    if ((!dn && !dx1) || (dx1 && (!dln_w || !dln_b || reps < 1))) return hipErrorInvalidValue;
+    if ((!dn && !dx1) || (dx1 && (!dln_w || reps < 0 || (reps > 0 && !dln_b)))) return hipErrorInvalidValue;
     m.dx1 = dx1; m.dgamma = dln_w; m.dbeta = dln_b; m.rep_stride = rep_stride; m.reps = reps;
     if (C <= 128) return launch_wide_bwd_t<4, 12>(m, s);
     return launch_wide_bwd_t<6, 12>(m, s);
 }
 
 bool ln_rows_supported(int C) { return C >= 8 && C <= 192 && C % 4 == 0; }
+
+int astl_mlp_wide_bwd_blocks(long rows)
+{
+    const long tiles = (rows + 15) / 16;
+    long blocks = (tiles + kWideWaves - 1) / kWideWaves;
+    if (blocks > device_cu_count()) blocks = device_cu_count();
+    return (int)(blocks < 1 ? 1 : blocks);
+}
+
+int ln_rows_bwd_blocks(long rows)
+{
+    const long tiles = (rows + 15) / 16;
+    long blocks = (tiles + kLnRowsThreads / 64 - 1) / (kLnRowsThreads / 64);
+    const long cap = 4L * device_cu_count();
+    if (blocks > cap) blocks = cap;
+    return (int)(blocks < 1 ? 1 : blocks);
+}
+
+hipError_t launch_ln_rows_bwd(const LnRowsBwdArgs &a, hipStream_t s)
+{
+    if (!ln_rows_supported(a.C) || a.rows <= 0 || !a.part) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)ln_rows_bwd_blocks(a.rows)), block(kLnRowsThreads);
+    if (a.C <= 64) hipLaunchKernelGGL(ln_rows_bwd_kernel<2>, grid, block, 0, s, a);
+    else if (a.C <= 128) hipLaunchKernelGGL(ln_rows_bwd_kernel<4>, grid, block, 0, s, a);
+    else hipLaunchKernelGGL(ln_rows_bwd_kernel<6>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_ln_rows_fwd(const LnRowsArgs &a, hipStream_t s)
 {
