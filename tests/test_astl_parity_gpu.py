@@ -69,7 +69,7 @@ def test_inference_call_gives_the_training_output(case):
     SMALL[0], SMALL[7],
     # a wide layer with enough tokens for the streaming weight-gradient kernel, whose sum then writes or adds
     # straight into the gradients of the two MLP maps
-    dict(B=2, H=64, W=32, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
+    dict(B=4, H=64, W=64, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
 ], ids=_id)
 def test_accumulate_flag_adds_into_every_parameter_gradient(case):
     print("case", case, flush=True)
@@ -101,15 +101,40 @@ def test_benchmark_shape_pair_against_the_oracle(name):
 
 
 @pytest.mark.parametrize("case", [
-    dict(B=2, H=64, W=32, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
-    # 4800 tokens: 37 passes of 128 and a ragged one
-    dict(B=3, H=40, W=40, C=180, heads=6, groups=3, window=8, shift=0, dtype="bf16", hidden=360),
+    dict(B=4, H=64, W=64, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360),
+    # 15552 tokens: 121 passes of 128 and a ragged one
+    dict(B=3, H=72, W=72, C=180, heads=6, groups=3, window=8, shift=0, dtype="bf16", hidden=360),
 ], ids=_id)
 def test_wide_layer_with_enough_tokens_for_the_streaming_weight_gradients(case):
-    """C = 180, hidden 360 from 4096 tokens on: the MLP's weight gradients come from the kernel that streams
-    the rows once and sums per-workgroup partial arrays in a fixed order."""
+    """C = 180, hidden 360 with enough tokens for 16 shares of the rows (the scratch is one hidden-sized tensor):
+    the MLP's four weight gradients come from ONE launch of the kernel that streams the rows once and sums
+    per-workgroup partial arrays in a fixed order, straight into the gradients."""
+    import torch
     print("case", case, flush=True)
+    gswa.gswa_profile_enable(True)
+    gswa.gswa_profile_collect()
     parity.check_block(astl_oracle, **case)
+    torch.cuda.synchronize()
+    names, dropped = gswa.gswa_profile_collect()
+    gswa.gswa_profile_enable(False)
+    assert dropped == 0
+    assert names["fc_wgrad"][1] == 1 and "fill_zero" not in names, names
+
+
+def test_wide_layer_with_few_tokens_keeps_the_gradient_copies():
+    """4096 tokens: too few rows for the streaming weight-gradient kernel; the layer takes the kernels that add
+    into 16 gradient copies (and still the streaming MLP kernels)."""
+    import torch
+    case = dict(B=2, H=64, W=32, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360)
+    print("case", case, flush=True)
+    gswa.gswa_profile_enable(True)
+    gswa.gswa_profile_collect()
+    parity.check_block(astl_oracle, **case)
+    torch.cuda.synchronize()
+    names, dropped = gswa.gswa_profile_collect()
+    gswa.gswa_profile_enable(False)
+    assert dropped == 0
+    assert names["fc_wgrad"][1] == 2 and "fill_zero" in names and "mlp_bwd" in names, names
 
 
 @pytest.mark.parametrize("case,kernels", [
@@ -135,6 +160,24 @@ def test_wide_layers_beyond_the_streaming_mlp_kernels(case, kernels):
     assert all(k in names for k in kernels) and "mlp_fwd" not in names, names
     # LN_2 of the forward and of the backward's recomputation ride in the first map: only LN_1 is launched (twice)
     assert names["ln_fwd"][1] == 2, names
+
+
+def test_wide_layer_backward_is_run_to_run_identical():
+    """A wide bf16 layer with enough tokens for the streaming weight-gradient kernel sums every parameter
+    gradient in a fixed order (partial vectors per workgroup, no atomics, no flag needed): two backward passes
+    give the same bits."""
+    import torch
+    case = dict(B=4, H=64, W=64, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360)
+    print("case", case, flush=True)
+    _, blk = parity.check_block(astl_oracle, **case)
+    first = {k: v.clone() for k, v in blk.grads.items()}
+    dx = blk.dx.clone()
+    for _ in range(2):
+        blk.backward()
+        torch.cuda.synchronize()
+        assert torch.equal(blk.dx, dx)
+        for k, v in blk.grads.items():
+            assert torch.equal(v, first[k]), k
 
 
 @pytest.mark.parametrize("case", [SMALL[0], SMALL[8]], ids=_id)
