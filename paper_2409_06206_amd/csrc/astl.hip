@@ -537,13 +537,22 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     const bool own = pl.fused_mlp_bwd;
     // Wide layers whose four MLP weight gradients come from the streaming kernel (its own partial arrays and a
     // fixed-order sum straight into the gradients): no gradient copies, no atomics anywhere in this file's part
+    // (Then the copies' memory is free too: the kernel's scratch runs from behind h | dpre to the end of the
+    // workspace, less the LayerNorms' partial vectors, which close it.)
     bool mlp_direct = false;
-    if (pl.wide_mlp) {
+    const int nparts2 = pl.wide_mlp ? astl_mlp_wide_bwd_blocks(rows) : 0;
+    const int nparts1 = pl.wide_mlp ? ln_rows_bwd_blocks(rows) : 0;
+    const size_t ln_bytes = align256((size_t)(nparts1 + nparts2) * 2 * C * sizeof(float));
+    char *wg_scratch = ws + 3 * pl.act + 2 * pl.hid;
+    size_t wg_scratch_bytes = pl.hid;
+    if (pl.wide_mlp && ln_bytes <= pl.reps) {
+        const size_t all = (size_t)((ws + pl.bwd_ws) - wg_scratch) - ln_bytes;
         WgradArgs t2{}, t1{};
         t2.dout = dy; t2.lddout = C; t2.a1 = ws; t2.lda1 = Hd; t2.rows = rows; t2.N = C; t2.K = Hd; t2.reps = 1;
         t1.dout = ws; t1.lddout = Hd; t1.a1 = ws; t1.lda1 = C; t1.rows = rows; t1.N = Hd; t1.K = C; t1.reps = 1;
-        t2.scratch = t1.scratch = ws + 3 * pl.act + 2 * pl.hid; t2.scratch_bytes = t1.scratch_bytes = pl.hid;
+        t2.scratch = t1.scratch = wg_scratch; t2.scratch_bytes = t1.scratch_bytes = all;
         mlp_direct = wgrad_pair_streams(t2, t1);
+        if (mlp_direct) wg_scratch_bytes = all;
     }
     const long P = (long)pl.params;
     const long o_w1 = 0, o_b1 = o_w1 + (long)Hd * C, o_w2 = o_b1 + Hd, o_b2 = o_w2 + (long)C * Hd;
@@ -566,11 +575,8 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
     }
     // (mlp_direct: nothing is added into copies at all.  The two LayerNorms' gamma / beta sums leave their kernels
     // as one vector per workgroup, in the copies' memory, and one launch sums both sets in a fixed order.)
-    float *lnpart2 = rep;
-    const int nparts2 = mlp_direct ? astl_mlp_wide_bwd_blocks(rows) : 0;
-    float *lnpart1 = rep + (size_t)nparts2 * 2 * C;
-    const int nparts1 = mlp_direct ? ln_rows_bwd_blocks(rows) : 0;
-    if (mlp_direct && (size_t)(nparts1 + nparts2) * 2 * C * sizeof(float) > pl.reps) return GSWA_EINVAL;
+    float *lnpart2 = reinterpret_cast<float *>(ws + pl.bwd_ws - ln_bytes);
+    float *lnpart1 = lnpart2 + (size_t)nparts2 * 2 * C;
     if (!own && !mlp_direct) {
         ZeroList z{};
         z.p[0] = rep; z.n[0] = (size_t)kGradReplicas * P; z.count = 1;
@@ -590,7 +596,6 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         // one launch from x1 and dy to dx1 (through LN_2's adjoint and the skip of Eq. 5; its gamma / beta sums
         // go into the gradient copies); LN_2(x1), h and dpre are written for the weight gradients
         T *h = reinterpret_cast<T *>(rest), *dpre = reinterpret_cast<T *>(rest + pl.hid);
-        char *third = rest + 2 * pl.hid; // (scratch of the weight gradients)
         ASTL_HIP(launch_astl_mlp_wide_bwd(rows, C, Hd, d->eps, (const bf16_t *)x1, (const bf16_t *)dy,
                                           (const bf16_t *)p->ln2_w, (const bf16_t *)p->ln2_b,
                                           (const bf16_t *)p->w_fc1, (const bf16_t *)p->b_fc1,
@@ -603,12 +608,12 @@ int backward_t(const astl_desc *d, const Plan &pl, const T *x, const T *dy, cons
         w2.dout = dy; w2.lddout = C; w2.a1 = h; w2.lda1 = Hd;
         w2.dw = rep + o_w2; w2.db = rep + o_b2; w2.rep_stride = P; w2.reps = kGradReplicas;
         w2.rows = rows; w2.N = C; w2.K = Hd; w2.prof_id = K_FC_WGRAD;
-        w2.scratch = third; w2.scratch_bytes = pl.hid;
+        w2.scratch = wg_scratch; w2.scratch_bytes = wg_scratch_bytes;
         WgradArgs w1{};
         w1.dout = dpre; w1.lddout = Hd; w1.a1 = xn; w1.lda1 = C;
         w1.dw = rep + o_w1; w1.db = rep + o_b1; w1.rep_stride = P; w1.reps = kGradReplicas;
         w1.rows = rows; w1.N = Hd; w1.K = C; w1.prof_id = K_FC_WGRAD;
-        w1.scratch = third; w1.scratch_bytes = pl.hid;
+        w1.scratch = wg_scratch; w1.scratch_bytes = wg_scratch_bytes;
         if (mlp_direct) { // (no copies: the kernel's sum writes, or adds to, the gradients themselves)
             w2.dw = g->w_fc2; w2.db = g->b_fc2; w1.dw = g->w_fc1; w1.db = g->b_fc1;
             w2.direct = w1.direct = 1; w2.accumulate = w1.accumulate = accumulate;
