@@ -342,6 +342,8 @@ STACKS = [
     dict(B=1, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="f32", hidden=120, n_layers=3),
     dict(B=2, H=16, W=16, C=60, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=120, n_layers=5),
     dict(B=1, H=24, W=24, C=60, heads=4, groups=2, window=12, shift=6, dtype="bf16", hidden=120, n_layers=4, dqk=4),
+    # wide layers: the streaming MLP kernels (the forward one hands LN_1 to the next layer), 4096 tokens
+    dict(B=1, H=64, W=64, C=180, heads=6, groups=2, window=8, shift=4, dtype="bf16", hidden=360, n_layers=3),
 ]
 
 
