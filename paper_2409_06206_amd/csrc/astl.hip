@@ -293,7 +293,7 @@ template <typename T, int V> hipError_t launch_ln_fwd_v(const LnArgs &a, const M
 template <typename T> hipError_t launch_ln_fwd(const LnArgs &a, hipStream_t s, const MlpReduceArgs *r = nullptr)
 {
     if constexpr (sizeof(T) == 2) {
-        // bf16 rows of up to 192 channels: the kernel with four lanes per row and whole tiles of loads in flight
+        // bf16 rows of 65 to 192 channels: the kernel with four lanes per row and whole tiles of loads in flight
         // (whatever the number of rows: a band of a map must get the arithmetic the whole map gets)
         if (!r && ln_rows_supported(a.C)) {
             LnRowsArgs n{};

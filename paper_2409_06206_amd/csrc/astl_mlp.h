@@ -46,7 +46,7 @@ hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, con
                                     float *dln_w, float *dln_b, long rep_stride, int reps, const void *pack,
                                     hipStream_t s);
 
-// LayerNorm of bf16 rows (Eq. 4-5) for C <= 192, C a multiple of 4: out = LN(u + add) with gamma, beta; `add`
+// LayerNorm of bf16 rows (Eq. 4-5) for 64 < C <= 192, C a multiple of 4: out = LN(u + add) with gamma, beta; `add`
 // may be null; with it, the rounded sum goes to sum_out (may be null) and is what gets normalised.
 struct LnRowsArgs {
     const bf16_t *u, *add, *gamma, *beta;

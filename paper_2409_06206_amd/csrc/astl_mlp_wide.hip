@@ -1006,7 +1006,10 @@ hipError_t launch_astl_mlp_wide_bwd(long rows, int C, int hidden, float eps, con
     return launch_wide_bwd_t<6, 12>(m, s);
 }
 
-bool ln_rows_supported(int C) { return C >= 8 && C <= 192 && C % 4 == 0; }
+// (narrow layers keep the 16-lanes-per-row kernel in both passes: at 60 channels this one is no faster, and the
+// backward's recomputation of LN_1, which shares a launch with the fused MLP's final sum there, must round as
+// the forward did)
+bool ln_rows_supported(int C) { return C > 64 && C <= 192 && C % 4 == 0; }
 
 int astl_mlp_wide_bwd_blocks(long rows)
 {
@@ -1029,8 +1032,7 @@ hipError_t launch_ln_rows_bwd(const LnRowsBwdArgs &a, hipStream_t s)
 {
     if (!ln_rows_supported(a.C) || a.rows <= 0 || !a.part) return hipErrorInvalidValue;
     const dim3 grid((unsigned)ln_rows_bwd_blocks(a.rows)), block(kLnRowsThreads);
-    if (a.C <= 64) hipLaunchKernelGGL(ln_rows_bwd_kernel<2>, grid, block, 0, s, a);
-    else if (a.C <= 128) hipLaunchKernelGGL(ln_rows_bwd_kernel<4>, grid, block, 0, s, a);
+    if (a.C <= 128) hipLaunchKernelGGL(ln_rows_bwd_kernel<4>, grid, block, 0, s, a);
     else hipLaunchKernelGGL(ln_rows_bwd_kernel<6>, grid, block, 0, s, a);
     return hipGetLastError();
 }
@@ -1043,8 +1045,7 @@ hipError_t launch_ln_rows_fwd(const LnRowsArgs &a, hipStream_t s)
     const long cap = 8L * device_cu_count(); // (eight workgroups of four waves per compute unit: one pass at 131072 rows)
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned)blocks), block(kLnRowsThreads);
-    if (a.C <= 64) hipLaunchKernelGGL(ln_rows_fwd_kernel<2>, grid, block, 0, s, a);
-    else if (a.C <= 128) hipLaunchKernelGGL(ln_rows_fwd_kernel<4>, grid, block, 0, s, a);
+    if (a.C <= 128) hipLaunchKernelGGL(ln_rows_fwd_kernel<4>, grid, block, 0, s, a);
     else hipLaunchKernelGGL(ln_rows_fwd_kernel<6>, grid, block, 0, s, a);
     return hipGetLastError();
 }
