@@ -292,6 +292,7 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         lx.w = wg; lx.w_sn = 1; lx.w_sk = Cg;
         lx.out = dx + grp * Cg; lx.ldout = C;
         lx.rows = g.T; lx.N = Cg; lx.K = Rg; lx.prof_id = K_DX_LINEAR;
+        lx.scratch = qkv; lx.scratch_bytes = sz.qkv; // (q|k|v of the group has had its last read)
         WgradArgs wq{};
         wq.dout = dqkv; wq.lddout = Rg;
         wq.a1 = x + grp * Cg; wq.lda1 = C;

@@ -32,6 +32,10 @@ struct LinearArgs {
     const void *ln_gamma, *ln_beta;
     float ln_eps;
     void *sum_out, *ln_out;
+    // optional (may be null): device memory free for the duration of the call; maps with few output columns and a
+    // long reduction (N <= 192, K > 384: the input gradient of a wide one-group q|k|v projection) then run on the
+    // kernel that streams the repacked weights through LDS and reads every row once
+    void *scratch; size_t scratch_bytes;
 };
 constexpr int kActGelu = 1, kActGeluGrad = 2;
 // true when launch_linear<bf16_t> runs this call on the kernel that implements `act`
