@@ -262,6 +262,9 @@ int backward_staged(const Geom &g, const Sizes &sz, uint32_t flags, const T *x, 
         la.bias = b_qkv + (size_t)grp * Rg;
         la.out = qkv; la.ldout = Rg;
         la.rows = g.T; la.N = Rg; la.K = Cg; la.prof_id = K_QKV_LINEAR;
+        // (the per-window table gradients are written from this group's attention adjoint on: until then, in the
+        // first group processed, their memory is free)
+        if (grp == G - 1 && sz.tpart) { la.scratch = tpart; la.scratch_bytes = sz.tpart; }
         // dO_g = dy Wproj[:, slice g] (+ dF_{g+1}, which is dx[:, slice g+1]) into the v part of dqkv
         LinearArgs lo{};
         lo.a1 = dy; lo.lda1 = C;

@@ -32,9 +32,9 @@ struct LinearArgs {
     const void *ln_gamma, *ln_beta;
     float ln_eps;
     void *sum_out, *ln_out;
-    // optional (may be null): device memory free for the duration of the call; maps with few output columns and a
-    // long reduction (N <= 192, K > 384: the input gradient of a wide one-group q|k|v projection) then run on the
-    // kernel that streams the repacked weights through LDS and reads every row once
+    // optional (may be null): device memory free for the duration of the call; maps whose weight matrix does not
+    // fit LDS (up to 576 output columns with K > 384 or more than 192 columns: a wide one-group q|k|v projection
+    // and its input gradient) then run on the kernel that streams the repacked weights through LDS
     void *scratch; size_t scratch_bytes;
 };
 constexpr int kActGelu = 1, kActGeluGrad = 2;

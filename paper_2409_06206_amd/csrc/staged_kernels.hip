@@ -489,44 +489,50 @@ __global__ __launch_bounds__(NTHREADS) void linear_mfma_wide_kernel(LinearArgs p
 }
 
 // ---------------------------------------------------------------------------------------
-// out[t, n] = sum_k a1[t, k] w(n, k) (+ bias[n]) (+ add[t, n]) for maps with few output columns and a long
-// reduction (N <= 192, any K): the weights, repacked by a launch of their own into matrix-core fragments in the
-// order they are used, are streamed through LDS in units of four K = 32 steps (double buffered, loads that write
-// LDS directly, one barrier per unit); a wave owns 16 rows, reads each of them once, 16 bytes per lane and step,
-// one unit ahead, and keeps all output tiles in registers.  The rows of the fragments are ordered so that a
-// lane's results of tiles 2p and 2p + 1 are the 8 consecutive columns 32 p + 8 q + 0..7: 16-byte stores.
+// out[t, n] = sum_k a1[t, k] w(n, k) (+ bias[n]) (+ add[t, n]) for maps whose weight matrix does not fit LDS
+// (up to 576 output columns, any K): the weights, repacked by a launch of their own into matrix-core fragments
+// in the order they are used, are streamed through LDS in units of four K = 32 steps (double buffered, loads
+// that write LDS directly, one barrier per unit); a wave owns 16 rows, reads them 16 bytes per lane and step,
+// one unit ahead, and keeps the output tiles of a block of 192 columns in registers.  With more columns the
+// blocks follow one another (the rows are read once per block: from L2 after the first).  The rows of the
+// fragments are ordered so that a lane's results of tiles 2p and 2p + 1 are the 8 consecutive columns
+// 32 p + 8 q + 0..7 of the block: 16-byte stores.
 // ---------------------------------------------------------------------------------------
 struct LinStream {
     static constexpr int NT = 12, HU = 4, NWV = 16;
+    static constexpr int NMAX = 3 * 16 * NT; // up to three blocks of 192 output columns, one after the other
     static constexpr int FR_UNIT = NT * HU, UNIT_BYTES = FR_UNIT * 1024;
     static constexpr int FPW = (FR_UNIT + NWV - 1) / NWV;
-    static constexpr size_t LDS_BYTES = 2 * (size_t)UNIT_BYTES + NT * 16 * sizeof(float);
+    static constexpr size_t LDS_BYTES = 2 * (size_t)UNIT_BYTES + NMAX * sizeof(float);
     static int units(int K) { return ((K + 31) / 32 + HU - 1) / HU; }
-    static size_t pack_bytes(int K) { return (size_t)units(K) * UNIT_BYTES + NT * 16 * sizeof(float); }
+    static int blocks(int N) { return (N + 16 * NT - 1) / (16 * NT); }
+    static size_t pack_bytes(int N, int K) { return (size_t)blocks(N) * units(K) * UNIT_BYTES + NMAX * sizeof(float); }
 };
 
-__global__ __launch_bounds__(256) void linear_stream_pack_kernel(LinearArgs p, int nu)
+// pack: [column block][unit][step of the unit][tile] fragments, then the bias as fp32 (zero beyond N)
+__global__ __launch_bounds__(256) void linear_stream_pack_kernel(LinearArgs p, int nu, int nb)
 {
     using L = LinStream;
     const uint16_t *w = static_cast<const uint16_t *>(p.w);
     uint16_t *d16 = static_cast<uint16_t *>(p.scratch);
-    const int total = nu * L::FR_UNIT * 512;
+    const int total = nb * nu * L::FR_UNIT * 512;
     for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
         const int j = e & 7, l = (e >> 3) & 63, fr = e >> 9;
-        const int u = fr / L::FR_UNIT, f = fr - u * L::FR_UNIT;
+        const int gu = fr / L::FR_UNIT, f = fr - gu * L::FR_UNIT;
+        const int blk = gu / nu, u = gu - blk * nu;
         const int hs = f / L::NT, ct = f - hs * L::NT;
         const int m = l & 15, lq = l >> 4;
-        const int n = 32 * (ct >> 1) + 8 * (m >> 2) + 4 * (ct & 1) + (m & 3);
+        const int n = 16 * L::NT * blk + 32 * (ct >> 1) + 8 * (m >> 2) + 4 * (ct & 1) + (m & 3);
         const int k = 32 * (L::HU * u + hs) + 8 * lq + j;
         d16[e] = (n < p.N && k < p.K) ? w[(long)n * p.w_sn + (long)k * p.w_sk] : (uint16_t)0;
     }
-    float *bl = reinterpret_cast<float *>(static_cast<uint8_t *>(p.scratch) + (size_t)nu * L::UNIT_BYTES);
+    float *bl = reinterpret_cast<float *>(static_cast<uint8_t *>(p.scratch) + (size_t)nb * nu * L::UNIT_BYTES);
     const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
-    for (int n = blockIdx.x * 256 + threadIdx.x; n < L::NT * 16; n += gridDim.x * 256)
+    for (int n = blockIdx.x * 256 + threadIdx.x; n < L::NMAX; n += gridDim.x * 256)
         bl[n] = (bias && n < p.N) ? __uint_as_float((uint32_t)bias[n] << 16) : 0.f;
 }
 
-__global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(LinearArgs p, int nu)
+__global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(LinearArgs p, int nu, int nb)
 {
     using L = LinStream;
     constexpr int NT = L::NT, HU = L::HU;
@@ -536,11 +542,12 @@ __global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(Line
     const uint8_t *pack = static_cast<const uint8_t *>(p.scratch);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, tok = lane & 15, q = lane >> 4;
     const uint32_t *a32 = static_cast<const uint32_t *>(p.a1);
+    const int tu = nu * nb; // units of a round: every column block takes all K
     int lane_r = lane;
-    auto stream_unit = [&](int u, int slot) {
+    auto stream_unit = [&](int gu, int slot) {
         int ln = lane_r;
         asm volatile("" : "+v"(ln));
-        const uint8_t *src = pack + (size_t)u * L::UNIT_BYTES + 16 * ln;
+        const uint8_t *src = pack + (size_t)gu * L::UNIT_BYTES + 16 * ln;
         uint8_t *dst = lds + (size_t)slot * L::UNIT_BYTES;
 #pragma unroll 1
         for (int k = 0; k < L::FPW; ++k) {
@@ -548,7 +555,7 @@ __global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(Line
             if (f < L::FR_UNIT) lds_dma16(src + (size_t)f * 1024, dst + (size_t)f * 1024);
         }
     };
-    // the lane's pieces of the unit's four steps: columns 32 s + 8 q + 0..7 of its row (a piece that would reach
+    // the lane's pieces of a unit's four steps: columns 32 s + 8 q + 0..7 of its row (a piece that would reach
     // beyond the row is read 8 columns before the row's end instead and put right by tidy(); K is a multiple of 4)
     auto load_unit = [&](long row, int u, u32q (&b)[HU]) {
         int qq = q;
@@ -572,8 +579,8 @@ __global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(Line
 
     stream_unit(0, 0);
     float *bias_l = reinterpret_cast<float *>(lds + 2 * L::UNIT_BYTES);
-    for (int i = tid; i < NT * 16; i += 64 * L::NWV)
-        bias_l[i] = reinterpret_cast<const float *>(pack + (size_t)nu * L::UNIT_BYTES)[i];
+    for (int i = tid; i < L::NMAX; i += 64 * L::NWV)
+        bias_l[i] = reinterpret_cast<const float *>(pack + (size_t)tu * L::UNIT_BYTES)[i];
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -590,14 +597,19 @@ __global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(Line
         lane_r = lane;
         asm volatile("" : "+v"(lane_r));
         f32x4 acc[NT];
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
         u32q b[HU], bn[HU];
         load_unit(tc, 0, b);
-        for (int u = 0; u < nu; ++u) {
-            if (u + 1 < nu) stream_unit(u + 1, slot ^ 1);
+        int u = 0, blk = 0;
+        for (int gu = 0; gu < tu; ++gu) {
+            if (gu + 1 < tu) stream_unit(gu + 1, slot ^ 1);
             else if (more) stream_unit(0, slot ^ 1);
-            if (u + 1 < nu) load_unit(tc, u + 1, bn);
+            // the pieces of the next unit: of the same rows again when the next column block begins
+            const int un = u + 1 < nu ? u + 1 : 0;
+            if (gu + 1 < tu) load_unit(tc, un, bn);
+            if (u == 0) {
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
             const uint4 *wu = reinterpret_cast<const uint4 *>(lds + lds0 + (size_t)slot * L::UNIT_BYTES);
             int qq = q;
             asm volatile("" : "+v"(qq));
@@ -607,63 +619,66 @@ __global__ __launch_bounds__(64 * LinStream::NWV) void linear_stream_kernel(Line
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct) acc[ct] = mma32(wu[(hs * NT + ct) * 64 + lane_r], bb, acc[ct]);
             }
+            if (u == nu - 1) {
+                // the block's columns: tiles 2p and 2p + 1 hold the lane's columns 32 p + 8 q + 0..3 and + 4..7
+#pragma unroll
+                for (int pz = 0; pz < NT / 2; ++pz) {
+                    const int n0 = 16 * NT * blk + 32 * pz + 8 * qq;
+                    if (!ok || n0 >= p.N) continue;
+                    const f32x4 lo = acc[2 * pz], hi = acc[2 * pz + 1];
+                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        v[i] += bias_l[n0 + i];
+                        if (add && n0 + i < p.N) v[i] += __uint_as_float((uint32_t)add[t * p.ldadd + n0 + i] << 16);
+                    }
+                    uint16_t *dst = out + t * p.ldout + n0;
+                    const bool even = !((t * p.ldout + n0) & 1) && !(reinterpret_cast<uintptr_t>(out) & 3);
+                    if (n0 + 8 <= p.N && even) {
+                        u32q o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+                        *reinterpret_cast<u32q_a4 *>(dst) = o;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (n0 + i < p.N) dst[i] = f32_to_bf16_bits(v[i]);
+                    }
+                }
+            }
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
             slot ^= 1;
 #pragma unroll
             for (int hs = 0; hs < HU; ++hs) b[hs] = bn[hs];
-        }
-        // tiles 2p and 2p + 1 hold the lane's columns 32 p + 8 q + 0..3 and + 4..7
-        int qq = q;
-        asm volatile("" : "+v"(qq));
-#pragma unroll
-        for (int pz = 0; pz < NT / 2; ++pz) {
-            const int n0 = 32 * pz + 8 * qq;
-            if (!ok || n0 >= p.N) continue;
-            const f32x4 lo = acc[2 * pz], hi = acc[2 * pz + 1];
-            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                v[i] += bias_l[n0 + i];
-                if (add && n0 + i < p.N) v[i] += __uint_as_float((uint32_t)add[t * p.ldadd + n0 + i] << 16);
-            }
-            uint16_t *dst = out + t * p.ldout + n0;
-            const bool even = !((t * p.ldout + n0) & 1) && !(reinterpret_cast<uintptr_t>(out) & 3);
-            if (n0 + 8 <= p.N && even) {
-                u32q o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
-                *reinterpret_cast<u32q_a4 *>(dst) = o;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (n0 + i < p.N) dst[i] = f32_to_bf16_bits(v[i]);
-            }
+            if (++u == nu) { u = 0; ++blk; }
         }
     }
 }
 
-// maps the streaming kernel takes: bf16 (checked by the caller), no second addend, activation or LayerNorm, few
-// output columns, a reduction too long for the whole matrix to sit in LDS, dword-aligned rows, scratch for the pack
+// Maps the streaming kernel takes: bf16 (checked by the caller), no second addend, activation or LayerNorm, at most
+// 576 output columns, dword-aligned rows, scratch for the pack - and a shape the kernel that keeps a whole weight
+// matrix in LDS does not take (a reduction longer than 384, or more than 192 columns).
 static bool linear_stream_ok(const LinearArgs &a)
 {
     if (!a.scratch || a.a2 || a.act || a.ln_gamma) return false;
-    if (a.N > 16 * LinStream::NT || a.N < 64 || a.K <= 384 || a.K % 4 || a.rows < 4096) return false;
+    if (a.N > LinStream::NMAX || a.N < 64 || a.K < 32 || a.K % 4 || a.rows < 4096) return false;
+    if (a.K <= 384 && a.N <= 16 * LinStream::NT) return false;
     if ((a.lda1 & 1) || (reinterpret_cast<uintptr_t>(a.a1) & 3) || (reinterpret_cast<uintptr_t>(a.scratch) & 15)) return false;
-    return a.scratch_bytes >= LinStream::pack_bytes(a.K);
+    return a.scratch_bytes >= LinStream::pack_bytes(a.N, a.K);
 }
 
 static hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t s)
 {
     using L = LinStream;
-    const int nu = L::units(a.K);
+    const int nu = L::units(a.K), nb = L::blocks(a.N);
     KernelTimer kt(a.prof_id, s);
-    hipLaunchKernelGGL(linear_stream_pack_kernel, dim3(128), dim3(256), 0, s, a, nu);
+    hipLaunchKernelGGL(linear_stream_pack_kernel, dim3(128), dim3(256), 0, s, a, nu, nb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(linear_stream_kernel), L::LDS_BYTES); ea != hipSuccess) return ea;
     const long tiles = (a.rows + 15) / 16;
     long blocks = (tiles + L::NWV - 1) / L::NWV;
     if (blocks > device_cu_count()) blocks = device_cu_count();
-    hipLaunchKernelGGL(linear_stream_kernel, dim3((unsigned)blocks), dim3(64 * L::NWV), L::LDS_BYTES, s, a, nu);
+    hipLaunchKernelGGL(linear_stream_kernel, dim3((unsigned)blocks), dim3(64 * L::NWV), L::LDS_BYTES, s, a, nu, nb);
     return hipGetLastError();
 }
 
@@ -774,8 +789,13 @@ template <typename T>
 hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, float *zero, size_t nzero, hipStream_t s)
 {
     if constexpr (sizeof(T) == 2) {
-        if (a.rows > 0 && a.N > 0 && b.rows > 0 && b.N > 0 && linear_mfma_ok(a) && linear_mfma_ok(b))
+        if (a.rows > 0 && a.N > 0 && b.rows > 0 && b.N > 0 && linear_mfma_ok(a) && linear_mfma_ok(b)) {
+            if (linear_stream_ok(a)) { // (the first map on the streaming kernel, the second with the fill)
+                hipError_t e = launch_linear_stream(a, s);
+                return e != hipSuccess ? e : launch_linear_mfma(b, nullptr, K_LINEAR_PAIR, zero, (long)nzero, s);
+            }
             return launch_linear_mfma(a, &b, K_LINEAR_PAIR, zero, (long)nzero, s);
+        }
     }
     hipError_t e = hipSuccess;
     if (zero && nzero > 0) {

@@ -59,6 +59,16 @@ def test_forced_staged_path_wide_layer(oracle):
                       extra_flags=gswa.GSWA_FORCE_STAGED)
 
 
+@pytest.mark.parametrize("C,heads", [(96, 6), (140, 5), (180, 6), (192, 6)])
+def test_forced_staged_path_one_group_many_tokens(oracle, C, heads):
+    """One group and at least 4096 tokens: the backward recomputes q|k|v (3C output columns: two or three column
+    blocks of the kernel that streams the weights through LDS, the last one ragged or full) and, from 132 channels
+    on, takes the input gradient on the same kernel."""
+    from paper_2409_06206_amd import gswa
+    parity.check_case(oracle, 1, 64, 72, C, heads, 1, 8, 4, "bf16", regime="stress",
+                      extra_flags=gswa.GSWA_FORCE_STAGED)
+
+
 @pytest.mark.parametrize("groups", [2, 3])
 def test_no_cascade_flag_wide_layer(oracle, groups):
     """Wide fused path (C=180) with Eq. 8 switched off: no cascade input, no cascade gradient."""
