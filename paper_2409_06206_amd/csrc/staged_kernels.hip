@@ -790,9 +790,19 @@ hipError_t launch_linear_pair(const LinearArgs &a, const LinearArgs &b, float *z
 {
     if constexpr (sizeof(T) == 2) {
         if (a.rows > 0 && a.N > 0 && b.rows > 0 && b.N > 0 && linear_mfma_ok(a) && linear_mfma_ok(b)) {
-            if (linear_stream_ok(a)) { // (the first map on the streaming kernel, the second with the fill)
+            if (linear_stream_ok(a)) {
+                // the first map on the streaming kernel; the second on the kernel that keeps its whole weight
+                // matrix in LDS and reads every row once where that one takes it, else with the fill
                 hipError_t e = launch_linear_stream(a, s);
-                return e != hipSuccess ? e : launch_linear_mfma(b, nullptr, K_LINEAR_PAIR, zero, (long)nzero, s);
+                if (e != hipSuccess) return e;
+                if (!(linear_wide_ok(b) && !b.act && !b.ln_gamma))
+                    return launch_linear_mfma(b, nullptr, K_LINEAR_PAIR, zero, (long)nzero, s);
+                if (zero && nzero > 0) {
+                    ZeroList z{};
+                    z.p[0] = zero; z.n[0] = nzero; z.count = 1;
+                    if (e = launch_fill_zero(z, s); e != hipSuccess) return e;
+                }
+                return launch_linear<T>(b, s);
             }
             return launch_linear_mfma(a, &b, K_LINEAR_PAIR, zero, (long)nzero, s);
         }
